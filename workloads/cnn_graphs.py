@@ -1,0 +1,312 @@
+"""Seeded synthetic CNN compute graphs (shapes and value distributions only).
+
+This module is the one thing the fp64 CPU oracle and the HIP path share: it
+describes a CNN as a topologically ordered list of operator records with
+seeded fp32 parameters, in the vocabulary of the paper's operator library
+(Table 3: conv, bn/bias/relu which fuse to CBR, max/avg/global pooling, add,
+concat, matmul/FC).  It contains none of the method's arithmetic: no
+convolution, folding, linking or tiling happens here.
+
+Tensor ids: 0 is the graph input, i + 1 is the output of ops[i].
+
+The five workloads stand in for the model families the paper evaluates
+(Section 7.1: MobileNet, ResNet18, SqueezeNet, ...) with the public
+architectures' shapes and random values; no trained weights or dataset images
+are involved (inference time does not depend on values).
+
+Value recipe (He-normal = N(0, std = sqrt(2 / fan_in)), fan_in = C/groups*R*S):
+  input  ~ U[-1, 1];  conv / fc weight ~ He-normal;  bias = 0 unless asked;
+  BN: gamma ~ U[0.5, 1.5], beta ~ N(0, 0.1), mean ~ N(0, 0.1), var ~ U[0.5, 1.5],
+  eps = 1e-5.
+Draw order from one numpy PCG64 stream: input, then per operator in
+topological order: weight, bias (only if non-zero biases are requested),
+gamma, beta, mean, var.  Seed = 230200282 + 1000 * config + batch.
+"""
+from __future__ import annotations
+
+import math
+from dataclasses import dataclass, field
+from typing import Dict, List, Optional, Tuple
+
+import numpy as np
+
+BASE_SEED = 230200282
+
+
+def seed_for(config: int, batch: int) -> int:
+    return BASE_SEED + 1000 * int(config) + int(batch)
+
+
+@dataclass
+class Op:
+    kind: str                      # conv bias bn relu maxpool avgpool gap add concat fc
+    inputs: List[int]
+    attrs: Dict[str, float] = field(default_factory=dict)
+    params: Dict[str, np.ndarray] = field(default_factory=dict)
+    name: str = ""
+
+
+@dataclass
+class Graph:
+    name: str
+    input_shape: Tuple[int, int, int, int]        # N, C, H, W
+    ops: List[Op]
+    output: int                                   # tensor id of the graph output
+    x: Optional[np.ndarray] = None                # seeded input, fp32 NCHW
+
+    def shapes(self) -> List[Tuple[int, int, int, int]]:
+        """Shape (N, C, H, W) of every tensor id; pure integer bookkeeping."""
+        out = [tuple(self.input_shape)]
+        for op in self.ops:
+            out.append(_infer(op, [out[i] for i in op.inputs]))
+        return out
+
+
+def _pool_out(n: int, k: int, s: int, p: int, ceil_mode: int) -> int:
+    if ceil_mode:
+        o = -(-(n + 2 * p - k) // s) + 1
+        if (o - 1) * s >= n + p:      # last window must start inside the input or left padding
+            o -= 1
+        return o
+    return (n + 2 * p - k) // s + 1
+
+
+def _infer(op: Op, ins):
+    a = op.attrs
+    n, c, h, w = ins[0]
+    if op.kind == "conv":
+        oh = (h + 2 * a["pad"] - a["kh"]) // a["stride"] + 1
+        ow = (w + 2 * a["pad"] - a["kw"]) // a["stride"] + 1
+        return (n, a["out_c"], oh, ow)
+    if op.kind in ("bias", "bn", "relu"):
+        return (n, c, h, w)
+    if op.kind in ("maxpool", "avgpool"):
+        return (n, c, _pool_out(h, a["k"], a["stride"], a["pad"], a.get("ceil", 0)),
+                _pool_out(w, a["k"], a["stride"], a["pad"], a.get("ceil", 0)))
+    if op.kind == "gap":
+        return (n, c, 1, 1)
+    if op.kind == "add":
+        assert ins[0] == ins[1], (ins, op.name)
+        return ins[0]
+    if op.kind == "concat":
+        assert all(i[0] == n and i[2:] == (h, w) for i in ins)
+        return (n, sum(i[1] for i in ins), h, w)
+    if op.kind == "fc":
+        return (n, a["out_c"], 1, 1)
+    raise ValueError(op.kind)
+
+
+class _Builder:
+    """Appends operators and draws their parameters in the documented order."""
+
+    def __init__(self, name, input_shape, seed, nonzero_bias=False, draw=True):
+        self.rng = np.random.default_rng(seed)
+        self.g = Graph(name, tuple(input_shape), [], 0)
+        self.draw = draw
+        self.nonzero_bias = nonzero_bias
+        self.g.x = self._uniform(input_shape, -1.0, 1.0)
+        self._shapes = [tuple(input_shape)]
+
+    # -- random draws (all fp32) ------------------------------------------
+    def _normal(self, shape, std):
+        if not self.draw:
+            return np.zeros(shape, np.float32)
+        return (self.rng.standard_normal(shape, dtype=np.float32) * np.float32(std)).astype(np.float32)
+
+    def _uniform(self, shape, lo, hi):
+        if not self.draw:
+            return np.zeros(shape, np.float32)
+        return (self.rng.random(shape, dtype=np.float32) * np.float32(hi - lo) + np.float32(lo)).astype(np.float32)
+
+    # -- operators ----------------------------------------------------------
+    def _push(self, op: Op) -> int:
+        self.g.ops.append(op)
+        self._shapes.append(_infer(op, [self._shapes[i] for i in op.inputs]))
+        return len(self.g.ops)
+
+    def shape(self, t):
+        return self._shapes[t]
+
+    def conv(self, x, out_c, k, stride=1, pad=0, groups=1, name="", bias=None):
+        c = self._shapes[x][1]
+        fan_in = (c // groups) * k * k
+        p = {"weight": self._normal((out_c, c // groups, k, k), math.sqrt(2.0 / fan_in))}
+        want_bias = self.nonzero_bias if bias is None else bias
+        if want_bias:
+            p["bias"] = self._normal((out_c,), 0.1)
+        return self._push(Op("conv", [x], dict(out_c=out_c, kh=k, kw=k, stride=stride, pad=pad,
+                                                groups=groups), p, name))
+
+    def bias(self, x, name=""):
+        c = self._shapes[x][1]
+        return self._push(Op("bias", [x], {}, {"bias": self._normal((c,), 0.1)}, name))
+
+    def bn(self, x, name=""):
+        c = self._shapes[x][1]
+        p = {"gamma": self._uniform((c,), 0.5, 1.5), "beta": self._normal((c,), 0.1),
+             "mean": self._normal((c,), 0.1), "var": self._uniform((c,), 0.5, 1.5)}
+        return self._push(Op("bn", [x], {"eps": 1e-5}, p, name))
+
+    def relu(self, x, name=""):
+        return self._push(Op("relu", [x], {}, {}, name))
+
+    def maxpool(self, x, k, stride, pad=0, ceil=0, name=""):
+        return self._push(Op("maxpool", [x], dict(k=k, stride=stride, pad=pad, ceil=ceil), {}, name))
+
+    def avgpool(self, x, k, stride, pad=0, ceil=0, count_include_pad=0, name=""):
+        return self._push(Op("avgpool", [x], dict(k=k, stride=stride, pad=pad, ceil=ceil,
+                                                   count_include_pad=count_include_pad), {}, name))
+
+    def gap(self, x, name=""):
+        return self._push(Op("gap", [x], {}, {}, name))
+
+    def add(self, a, b, name=""):
+        return self._push(Op("add", [a, b], {}, {}, name))
+
+    def concat(self, xs, name=""):
+        return self._push(Op("concat", list(xs), {}, {}, name))
+
+    def fc(self, x, out_c, name="", bias=None):
+        n, c, h, w = self._shapes[x]
+        fan_in = c * h * w
+        p = {"weight": self._normal((out_c, fan_in), math.sqrt(2.0 / fan_in))}
+        want_bias = self.nonzero_bias if bias is None else bias
+        if want_bias:
+            p["bias"] = self._normal((out_c,), 0.1)
+        return self._push(Op("fc", [x], dict(out_c=out_c), p, name))
+
+    def cbr(self, x, out_c, k, stride=1, pad=0, groups=1, name="", bn=True, relu=True):
+        t = self.conv(x, out_c, k, stride, pad, groups, name)
+        if bn:
+            t = self.bn(t, name + ".bn")
+        if relu:
+            t = self.relu(t, name + ".relu")
+        return t
+
+    def finish(self, out) -> Graph:
+        self.g.output = out
+        return self.g
+
+
+# ---------------------------------------------------------------------------
+# The five workloads
+# ---------------------------------------------------------------------------
+
+def single_chain(batch=1, seed=None, hw=32, in_c=3, out_c=16, nonzero_bias=False, draw=True) -> Graph:
+    """Config 0: Conv3x3 s1 p1 -> BN -> ReLU -> MaxPool2x2 s2 (the paper's CBRM, Table 3)."""
+    b = _Builder("single_chain", (batch, in_c, hw, hw), seed_for(0, batch) if seed is None else seed,
+                 nonzero_bias, draw)
+    t = b.cbr(0, out_c, 3, 1, 1, name="c0")
+    t = b.maxpool(t, 2, 2, name="pool")
+    return b.finish(t)
+
+
+MOBILENET_BLOCKS = [(64, 1), (128, 2), (128, 1), (256, 2), (256, 1), (512, 2),
+                    (512, 1), (512, 1), (512, 1), (512, 1), (512, 1), (1024, 2), (1024, 1)]
+
+
+def mobilenet_v1(batch=1, seed=None, hw=224, width=1.0, classes=1000, nonzero_bias=False, draw=True) -> Graph:
+    """Config 1: depthwise-separable stack (the paper's Section 2.2 / Figure 5 example family)."""
+    b = _Builder("mobilenet_v1", (batch, 3, hw, hw), seed_for(1, batch) if seed is None else seed,
+                 nonzero_bias, draw)
+    ch = lambda c: max(8, int(c * width))
+    t = b.cbr(0, ch(32), 3, 2, 1, name="conv0")
+    for i, (oc, s) in enumerate(MOBILENET_BLOCKS, 1):
+        c = b.shape(t)[1]
+        t = b.cbr(t, c, 3, s, 1, groups=c, name=f"dw{i}")
+        t = b.cbr(t, ch(oc), 1, 1, 0, name=f"pw{i}")
+    t = b.gap(t, "gap")
+    t = b.fc(t, classes, "fc")
+    return b.finish(t)
+
+
+def resnet18(batch=1, seed=None, hw=224, width=1.0, classes=1000, nonzero_bias=False, draw=True) -> Graph:
+    """Config 2: BasicBlock backbone; exercises the shortcut-connection linking pattern (Table 1)."""
+    b = _Builder("resnet18", (batch, 3, hw, hw), seed_for(2, batch) if seed is None else seed,
+                 nonzero_bias, draw)
+    ch = lambda c: max(8, int(c * width))
+    t = b.cbr(0, ch(64), 7, 2, 3, name="conv1")
+    t = b.maxpool(t, 3, 2, 1, name="pool1")
+    for si, c in enumerate((64, 128, 256, 512), 1):
+        for bi in range(2):
+            stride = 2 if (si > 1 and bi == 0) else 1
+            name = f"s{si}b{bi}"
+            skip = t
+            u = b.cbr(t, ch(c), 3, stride, 1, name=name + ".c1")
+            u = b.cbr(u, ch(c), 3, 1, 1, name=name + ".c2", relu=False)
+            if stride != 1 or b.shape(skip)[1] != ch(c):
+                skip = b.cbr(skip, ch(c), 1, stride, 0, name=name + ".proj", relu=False)
+            u = b.add(u, skip, name + ".add")
+            t = b.relu(u, name + ".out")
+    t = b.gap(t, "gap")
+    t = b.fc(t, classes, "fc")
+    return b.finish(t)
+
+
+VGG_GROUPS = [(64, 2), (128, 2), (256, 3), (512, 3), (512, 3)]
+
+
+def vgg16(batch=32, seed=None, hw=224, width=1.0, fc_dim=4096, classes=1000, nonzero_bias=False,
+          draw=True) -> Graph:
+    """Config 3: plain Conv3x3+ReLU stack, MaxPool2x2 ending each group, three FC layers."""
+    b = _Builder("vgg16", (batch, 3, hw, hw), seed_for(3, batch) if seed is None else seed,
+                 nonzero_bias, draw)
+    ch = lambda c: max(8, int(c * width))
+    t = 0
+    for gi, (c, n) in enumerate(VGG_GROUPS, 1):
+        for ci in range(1, n + 1):
+            t = b.cbr(t, ch(c), 3, 1, 1, name=f"g{gi}c{ci}", bn=False)
+        t = b.maxpool(t, 2, 2, name=f"pool{gi}")
+    t = b.fc(t, fc_dim, "fc6")
+    t = b.relu(t, "fc6.relu")
+    t = b.fc(t, fc_dim, "fc7")
+    t = b.relu(t, "fc7.relu")
+    t = b.fc(t, classes, "fc8")
+    return b.finish(t)
+
+
+SQUEEZE = [16, 16, 32, 32, 48, 48, 64, 64]
+
+
+def squeezenet11(batch=1, seed=None, hw=224, classes=1000, nonzero_bias=False, draw=True) -> Graph:
+    """Config 4: Fire modules; exercises linking across concat and fan-out of a shared producer."""
+    b = _Builder("squeezenet11", (batch, 3, hw, hw), seed_for(4, batch) if seed is None else seed,
+                 nonzero_bias, draw)
+    t = b.cbr(0, 64, 3, 2, 0, name="conv1", bn=False)
+    t = b.maxpool(t, 3, 2, 0, ceil=1, name="pool1")
+    for i, s in enumerate(SQUEEZE, 1):
+        q = b.cbr(t, s, 1, name=f"f{i}.sq", bn=False)
+        e1 = b.cbr(q, 4 * s, 1, name=f"f{i}.e1", bn=False)
+        e3 = b.cbr(q, 4 * s, 3, 1, 1, name=f"f{i}.e3", bn=False)
+        t = b.concat([e1, e3], f"f{i}.cat")
+        if i in (2, 4):
+            t = b.maxpool(t, 3, 2, 0, ceil=1, name=f"pool_f{i}")
+    t = b.cbr(t, classes, 1, name="conv10", bn=False)
+    t = b.gap(t, "gap")
+    return b.finish(t)
+
+
+CONFIGS = {0: single_chain, 1: mobilenet_v1, 2: resnet18, 3: vgg16, 4: squeezenet11}
+
+
+def build(config: int, batch: int, **kw) -> Graph:
+    return CONFIGS[config](batch=batch, **kw)
+
+
+# ---------------------------------------------------------------------------
+# Shape-only bookkeeping used by the bench report (no arithmetic on values)
+# ---------------------------------------------------------------------------
+
+def conv_fc_flops(g: Graph) -> int:
+    """2 * MACs of the conv and fc operators (the paper's operators x.conv / x.matmul)."""
+    shp = g.shapes()
+    total = 0
+    for i, op in enumerate(g.ops):
+        n, k, oh, ow = shp[i + 1]
+        if op.kind == "conv":
+            c = shp[op.inputs[0]][1] // op.attrs["groups"]
+            total += 2 * n * k * oh * ow * c * op.attrs["kh"] * op.attrs["kw"]
+        elif op.kind == "fc":
+            _, c, h, w = shp[op.inputs[0]]
+            total += 2 * n * k * c * h * w
+    return total
