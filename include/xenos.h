@@ -1,0 +1,160 @@
+/*
+ * xenos.h -- C ABI of the MI355X (gfx950) linked-operator-chain CNN inference library.
+ *
+ * The interface follows the paper's problem statement (Section 6): the user hands over a
+ * computation graph plus the hardware description (memory hierarchy, number of compute
+ * units); an automatic optimiser (Sections 4.1-4.4) links adjacent operators and splits
+ * them across the units; a runtime then executes the optimised model on input data
+ * (Section 3).  Operator vocabulary: Table 3.
+ *
+ * Conventions
+ *  - Opaque handles; every entry point returns a status and never throws.  On failure
+ *    nothing is written through output pointers and xenos_last_error() holds a message.
+ *  - HOST pointers: descriptors, operator parameters (fp32), hw info, options, JSON buffer.
+ *    They are borrowed only for the duration of the call (parameters are copied).
+ *  - DEVICE pointers: d_weights, d_workspace, d_input, d_output.  All device memory is owned
+ *    by the caller (e.g. PyTorch tensors); the library never allocates device memory and
+ *    never synchronises in xenos_run.
+ *  - hip_stream is a hipStream_t passed as void* (NULL = the default stream).
+ *  - One GPU; a plan may be run on one stream at a time.
+ */
+#ifndef XENOS_H
+#define XENOS_H
+
+#include <stddef.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  XENOS_OK = 0,
+  XENOS_EINVAL = 1,        /* NULL / out-of-range argument                     */
+  XENOS_ESHAPE = 2,        /* operator shapes do not fit together              */
+  XENOS_EUNSUPPORTED = 3,  /* valid graph, but outside what the kernels cover  */
+  XENOS_ENOMEM = 4,        /* host allocation failed                           */
+  XENOS_EDEVICE = 5        /* a HIP call failed                                */
+} xenos_status;
+
+typedef enum { XENOS_F32 = 0, XENOS_BF16 = 1 } xenos_dtype;
+typedef enum { XENOS_NCHW = 0, XENOS_NHWC = 1 } xenos_layout;   /* graph I/O only */
+
+/* Operator kinds: the members of the paper's operator library (Table 3) that a CNN graph
+ * is built from before fusion.  Conv+Bn+Bias+Relu are fused to CBR by the optimiser
+ * (Section 4.3); CBR followed by pooling is linked to CBRM / CBRA (Table 3). */
+typedef enum {
+  XENOS_OP_CONV = 0,            /* x.conv: cross-correlation, zero padding, floor output size, groups */
+  XENOS_OP_BIAS = 1,            /* per-channel add                                                   */
+  XENOS_OP_BN = 2,              /* inference batch-norm: gamma*(x-mean)/sqrt(var+eps)+beta            */
+  XENOS_OP_RELU = 3,
+  XENOS_OP_MAXPOOL = 4,         /* x.gampool                                                         */
+  XENOS_OP_AVGPOOL = 5,
+  XENOS_OP_GLOBAL_AVGPOOL = 6,
+  XENOS_OP_ADD = 7,             /* x.add, two inputs of equal shape                                  */
+  XENOS_OP_CONCAT = 8,          /* x.concat along channels, 2..4 inputs                              */
+  XENOS_OP_FC = 9               /* x.matmul as FullyConnected over the NCHW flattening of its input  */
+} xenos_op_kind;
+
+typedef struct {
+  int n, c, h, w;
+  xenos_dtype dtype;            /* element type of the caller's buffer (graph input / output) */
+  xenos_layout layout;
+} xenos_tensor_desc;
+
+/* One operator.  Tensor ids: 0 is the graph input, i + 1 is the output of ops[i]; ops must be
+ * in topological order.  Parameter arrays are HOST fp32 and may be NULL where optional. */
+typedef struct {
+  xenos_op_kind kind;
+  int n_inputs;
+  int inputs[4];
+  int out_c;                    /* conv, fc                                        */
+  int kh, kw;                   /* conv, pool                                      */
+  int stride_h, stride_w;       /* conv, pool (must be equal)                      */
+  int pad_h, pad_w;             /* conv, pool (must be equal)                      */
+  int groups;                   /* conv: 1 (dense) or == channels (depthwise)      */
+  int ceil_mode;                /* pool                                            */
+  int count_include_pad;        /* avgpool                                         */
+  float eps;                    /* bn                                              */
+  const float* weight;          /* conv: [out_c][c/groups][kh][kw]; fc: [out_c][c*h*w] */
+  const float* bias;            /* conv, fc (optional); bias op (required): [c]    */
+  const float* gamma;           /* bn: [c] each                                    */
+  const float* beta;
+  const float* mean;
+  const float* var;
+} xenos_op_desc;
+
+/* Hardware description (Section 6: "memory hierarchy, number of DSP units").  The planner
+ * sizes tiles from these numbers; nothing about the chip is hard-coded in the planner. */
+typedef struct {
+  int num_cu;                   /* compute units that share the work (MI355X: 256)          */
+  size_t lds_bytes_per_cu;      /* private memory per unit (MI355X: 160 KiB LDS)            */
+  size_t l2_bytes;              /* shared cache per XCD (MI355X: 4 MiB)                     */
+  size_t llc_bytes;             /* memory-side cache (MI355X: 256 MiB)                      */
+  size_t hbm_bytes;             /* device memory                                           */
+} xenos_hw_info;
+
+/* link:  0 = operator by operator (the paper's Vanilla dataflow: every operator is one pass)
+ *        1 = fused CBR only; pooling / add / concat stay separate passes (the "HO baseline")
+ *        2 = operator linking on (Section 4.1): CBR + pool, shortcut add, concat-by-offset
+ *        3 = 2 plus depthwise -> pointwise chains kept on chip (Section 2.2 example)
+ * split: 0 = every chain runs on ONE compute unit (no operator split; for tests)
+ *        1 = DSP-aware operator split (Section 4.2): output channels first, then H/W
+ * compute: element type of activations and weights in HBM; accumulation is always fp32.
+ * tile: 0 = planner's choice, otherwise forces tile configuration tile-1 (tests, tuning). */
+typedef struct {
+  int link;
+  int split;
+  xenos_dtype compute;
+  int tile;
+} xenos_plan_opts;
+
+typedef struct xenos_graph xenos_graph;
+typedef struct xenos_plan xenos_plan;
+
+/* Section 6, "users need to provide a computation graph": validates the operator list, infers
+ * every tensor shape and copies descriptors and parameters.  output_tensor_id names the graph
+ * output; output gives the dtype/layout the caller wants it in (n,c,h,w are checked if non-zero). */
+xenos_status xenos_graph_create(const xenos_tensor_desc* input, const xenos_op_desc* ops, int n_ops,
+                                int output_tensor_id, const xenos_tensor_desc* output,
+                                xenos_graph** out);
+
+/* Sections 4.1-4.4, the automatic optimiser: fusion pre-pass (Conv/Bn/Bias/Relu -> CBR), operator
+ * linking (pattern table, Table 1) with per-edge layout assignment, then DSP-aware operator split
+ * (feature-map partition over outC then H/W; parameter split K first, C/R/S as in-kernel reduction).
+ * Host only; does not touch the device. */
+xenos_status xenos_plan_link_split(const xenos_graph* graph, const xenos_hw_info* hw,
+                                   const xenos_plan_opts* opts, xenos_plan** out);
+
+/* Plan metadata (Section 4.1 "metadata"): sizes the caller must allocate, the output descriptor and
+ * a JSON description of chains, tiles, layouts and algorithmic HBM bytes.  Any pointer may be NULL.
+ * json_cap is the capacity of json in bytes; the text is truncated (and NUL-terminated) if larger;
+ * *json_len receives the full length needed, NUL included. */
+xenos_status xenos_plan_query(const xenos_plan* plan, size_t* weight_bytes, size_t* workspace_bytes,
+                              xenos_tensor_desc* out_desc, char* json, size_t json_cap, size_t* json_len);
+
+/* Packs the parameters in operand order (K-tile major, (r,s,c) contiguous; Section 4.2.2) into the
+ * caller's device buffer d_weights (>= weight_bytes) and records d_workspace (>= workspace_bytes).
+ * Both must be 256-byte aligned.  Synchronises hip_stream before returning. */
+xenos_status xenos_plan_bind(xenos_plan* plan, void* d_weights, void* d_workspace, void* hip_stream);
+
+/* Section 3, the runtime: enqueues the planned kernel sequence on hip_stream.  d_input / d_output
+ * are device buffers in the dtype / layout of the graph's input / output descriptors.
+ * Asynchronous; allocates nothing; returns XENOS_EDEVICE if a launch fails. */
+xenos_status xenos_run(xenos_plan* plan, const void* d_input, void* d_output, void* hip_stream);
+
+/* Runs only chain `chain` of a bound plan (0 <= chain < number of chains in the JSON), reading and
+ * writing the same buffers xenos_run would; used for per-chain timing. */
+xenos_status xenos_run_chain(xenos_plan* plan, int chain, const void* d_input, void* d_output,
+                             void* hip_stream);
+
+/* Releases a graph or a plan (either handle type; NULL is ignored).  A plan holds a reference to
+ * nothing of the graph after xenos_plan_link_split returns. */
+void xenos_destroy(void* graph_or_plan);
+
+/* Thread-local message of the last failing call on this thread ("" if none). */
+const char* xenos_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* XENOS_H */

@@ -1,0 +1,104 @@
+// Launch descriptors shared by the host planner/runtime and the gfx950 kernels.
+// Everything here is plain data: the planner fills these at plan time, the runtime patches
+// the external input/output pointers and launches.
+#pragma once
+#include <stddef.h>
+#include <stdint.h>
+
+namespace xenos {
+
+enum { DT_F32 = 0, DT_BF16 = 1 };
+
+// How the rows (m) of an implicit-GEMM tile enumerate conv-output pixels.  The enumeration IS the
+// linked dataflow of Section 4.1 / Figure 4: the producer walks pixels in the order its linked
+// consumer (the pooling) reads them.
+enum {
+  M_FLAT = 0,     // m = (n*OH + oh)*OW + ow: no pooling, output written pixel-major
+  M_ZIGZAG = 1,   // m = 4*window + (dy*2+dx): 2x2/s2 pooling windows are 4 consecutive rows (Figure 4 zig-zag)
+  M_PATCH = 2,    // tile = spatial patch of one image, staged on chip, then pooled (any k/s/pad/ceil)
+  M_GAP = 3       // tile = (image, channel tile); loops over the whole map, global average in registers
+};
+
+enum { POOL_NONE = 0, POOL_MAX = 1, POOL_AVG = 2, POOL_GAP = 3 };
+
+// Tile configurations of the dense-conv kernel (block = 256 threads = 4 wavefronts).
+struct TileCfg { int bm, bn, wm, wn; };
+static const TileCfg kTileCfgs[] = {
+  {128, 128, 64, 64},
+  {128, 64, 64, 32},
+  {64, 64, 32, 32},
+  {32, 128, 32, 32},
+};
+static const int kNumTileCfgs = 4;
+
+struct ConvArgs {
+  const void* in;        // activations: NHWC in the compute type (vector loader), or any strided fp32/T tensor (scalar loader)
+  const void* w;         // packed weights [Kout_pad][Kred_pad] in the compute type, reduction index = (r*S+s)*C + c
+  const float* scale;    // folded per-channel scale [Kout_pad] (1 where no BN)
+  const float* shift;    // folded per-channel shift [Kout_pad]
+  const void* res;       // residual (NHWC view, compute type) or nullptr
+  void* out;
+  const int32_t* ktab;   // scalar loader only: per reduction index {offset, (r<<16)|s}
+  int N, C, H, W;
+  long long in_sN, in_sH, in_sW;   // element strides of the input view (channel stride is 1 for the vector loader)
+  int in_f32;            // scalar loader: input elements are fp32 (graph input) instead of the compute type
+  int K, R, S, stride, pad, OH, OW;
+  int Kred, Kred_pad;    // R*S*C and its padding to the reduction step
+  int mode;              // M_*
+  int relu, has_res;
+  long long res_sN, res_sP;        // residual strides (image, pixel); channel stride 1
+  int pool, pk, ps, pp, PH, PW, cip;   // linked pooling (POOL_*), window, stride, pad, pooled size, count_include_pad
+  int patch_h, patch_w, pph, ppw, patches_y, patches_x;   // M_PATCH geometry (conv-output patch, pooled patch)
+  long long out_sN, out_sP, out_sK;    // output strides (image, pixel, channel) in elements
+  int out_f32;           // store fp32 instead of the compute type (graph output)
+  int M_total;           // rows enumerated over the whole problem (FLAT, ZIGZAG); per-image rows for GAP
+  int tiles_m, tiles_n, ntiles;
+  int grid;              // workgroups launched (>= 1); tiles are visited with a stride of `grid`
+};
+
+struct DwArgs {
+  const void* in; const void* w;     // w: [R*S][C] in the compute type
+  const float* scale; const float* shift;
+  void* out;
+  int N, C, H, W, R, S, stride, pad, OH, OW;
+  long long in_sN, in_sP;            // NHWC view strides (image, pixel)
+  long long out_sN, out_sP;
+  int relu;
+  long long total_vec;               // N*OH*OW*(C/vec)
+};
+
+// Stand-alone passes of the un-linked baselines (and of whatever the link pass could not absorb).
+enum { ELT_AFFINE = 0, ELT_RELU = 1, ELT_ADD = 2, ELT_COPY = 3 };
+struct EltArgs {
+  const void* a; const void* b; void* out;
+  const float* scale; const float* shift;
+  int op, relu;                      // relu applied after op when set
+  int C;                             // channels of the view
+  long long pixels;                  // N*H*W
+  long long a_sP, b_sP, out_sP;      // pixel strides of the NHWC views
+};
+
+struct PoolArgs {
+  const void* in; void* out;
+  int N, C, H, W, OH, OW, k, s, p, kind, cip;   // kind: POOL_MAX / POOL_AVG / POOL_GAP
+  long long in_sN, in_sP, out_sN, out_sP;
+};
+
+// Layout / type conversion at the graph boundary (the transpose operator of Table 3).
+struct CvtArgs {
+  const void* in; void* out;
+  int N, C, H, W;
+  long long in_sN, in_sC, in_sP;     // element strides: image, channel, pixel (pixel index = h*W + w)
+  long long out_sN, out_sC, out_sP;
+  int in_f32, out_f32;
+};
+
+// Launchers (defined in xenos_kernels.hip).  dtype = DT_*.  Return a hipError_t value as int.
+int launch_conv(const ConvArgs& a, int dtype, int cfg, int scalar_loader, void* stream);
+int launch_dw(const DwArgs& a, int dtype, void* stream);
+int launch_elt(const EltArgs& a, int dtype, void* stream);
+int launch_pool(const PoolArgs& a, int dtype, void* stream);
+int launch_cvt(const CvtArgs& a, int dtype, void* stream);
+size_t conv_lds_bytes(int cfg, int mode);
+
+}  // namespace xenos

@@ -1,0 +1,649 @@
+// gfx950 (CDNA4) kernels of the linked-operator-chain path.
+//
+//  conv_kernel   implicit-GEMM dense convolution on MFMA (bf16 32x32x16 / fp32 32x32x2, fp32
+//                accumulate) with the whole linked chain in its epilogue: folded BN/bias scale+shift,
+//                shortcut add, ReLU, max/avg/global pooling, and a store at a channel offset of the
+//                consumer's buffer (CBR / CBRM / CBRA of Table 3; shortcut and concat rows of Table 1).
+//  dw_kernel     depthwise convolution chain (Section 2.2), channel-vectorised NHWC.
+//  elt/pool/cvt  stand-alone passes used by the un-linked baselines and at the graph boundary.
+//
+// Rows of a GEMM tile are conv-output pixels, columns are output channels, the reduction runs over
+// (r, s, c) with c fastest, which is contiguous in NHWC.  Output-channel tiles are the paper's
+// outC-first partition, pixel tiles its inH/inW partition (Section 4.2.1); the (c, r, s) loop is the
+// in-unit parameter split (Section 4.2.2) and never crosses workgroups.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include "kernels.h"
+
+namespace xenos {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
+typedef __attribute__((ext_vector_type(16))) float f32x16_t;
+typedef __attribute__((ext_vector_type(4))) float f32x4_t;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;
+
+struct bf16_t { uint16_t v; };
+
+__device__ __forceinline__ float bf2f(uint16_t v) { return __uint_as_float(((uint32_t)v) << 16); }
+// round-to-nearest-even; inputs are finite by contract
+__device__ __forceinline__ uint16_t f2bf(float f) {
+  uint32_t u = __float_as_uint(f);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+
+template <typename T> struct Tr;
+template <> struct Tr<float> {
+  static constexpr int CE = 4;     // elements per 16-byte chunk
+  static constexpr int BKE = 16;   // reduction elements per step (64 bytes per tile row)
+  __device__ static __forceinline__ float ld(const void* p, long long i) { return ((const float*)p)[i]; }
+  __device__ static __forceinline__ void st(void* p, long long i, float v) { ((float*)p)[i] = v; }
+  __device__ static __forceinline__ void unpack(const u32x4_t& v, float* f) {
+#pragma unroll
+    for (int e = 0; e < 4; ++e) f[e] = __uint_as_float(v[e]);
+  }
+  __device__ static __forceinline__ u32x4_t pack(const float* f) {
+    u32x4_t v;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) v[e] = __float_as_uint(f[e]);
+    return v;
+  }
+};
+template <> struct Tr<bf16_t> {
+  static constexpr int CE = 8;
+  static constexpr int BKE = 32;
+  __device__ static __forceinline__ float ld(const void* p, long long i) { return bf2f(((const uint16_t*)p)[i]); }
+  __device__ static __forceinline__ void st(void* p, long long i, float v) { ((uint16_t*)p)[i] = f2bf(v); }
+  __device__ static __forceinline__ void unpack(const u32x4_t& v, float* f) {
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      f[2 * e] = __uint_as_float(v[e] << 16);
+      f[2 * e + 1] = __uint_as_float(v[e] & 0xffff0000u);
+    }
+  }
+  __device__ static __forceinline__ u32x4_t pack(const float* f) {
+    u32x4_t v;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) v[e] = (uint32_t)f2bf(f[2 * e]) | ((uint32_t)f2bf(f[2 * e + 1]) << 16);
+    return v;
+  }
+};
+
+constexpr int NT = 256;          // threads per workgroup (4 wavefronts of 64)
+constexpr int ROWB = 64;         // data bytes per tile row per reduction step
+constexpr int LDS_ROW = 80;      // row pitch in LDS: 64 + 16 bytes, so 16 consecutive rows hit distinct 16-byte slots
+constexpr int NUM_XCD = 8;
+
+__host__ __device__ constexpr int cmax(int a, int b) { return a > b ? a : b; }
+
+template <int BM, int BN>
+__host__ __device__ constexpr int lds_main_bytes() { return 2 * (BM + BN) * LDS_ROW; }
+template <int BM, int BN>
+__host__ __device__ constexpr int lds_patch_bytes() { return BM * (BN + 1) * 4; }
+
+// ---------------------------------------------------------------------------------------------
+// Dense convolution chain
+// ---------------------------------------------------------------------------------------------
+template <typename T, int BM, int BN, int WM, int WN, bool SCALAR>
+__global__ __launch_bounds__(NT) void conv_kernel(const ConvArgs a) {
+  using tr = Tr<T>;
+  constexpr int CE = tr::CE, BKE = tr::BKE;
+  constexpr int WAVES_N = BN / WN;
+  constexpr int TM = WM / 32, TN = WN / 32;
+  constexpr int A_CH = BM * 4, B_CH = BN * 4;                      // 16-byte chunks per step
+  constexpr int A_IT = (A_CH + NT - 1) / NT, B_IT = (B_CH + NT - 1) / NT;
+  static_assert((BM / WM) * WAVES_N == 4, "four wavefronts per workgroup");
+
+  extern __shared__ __align__(16) unsigned char smem[];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wave_m = wave / WAVES_N, wave_n = wave % WAVES_N;
+  const int l31 = lane & 31, lhalf = lane >> 5;
+
+  const int nsteps = a.Kred_pad / BKE;
+  const int OHW = a.OH * a.OW;
+  const int chunk = (a.ntiles + NUM_XCD - 1) / NUM_XCD;
+  const int slots = chunk * NUM_XCD;
+
+  for (int t = blockIdx.x; t < slots; t += gridDim.x) {
+    // Workgroups are dealt round-robin to the 8 XCDs; give each XCD a contiguous run of tiles so that
+    // tiles sharing an input halo or a weight slice meet in the same L2.
+    const int L = (t % NUM_XCD) * chunk + t / NUM_XCD;
+    if (L >= a.ntiles) continue;                                   // uniform per workgroup
+    const int tile_m = L / a.tiles_n, tile_n = L % a.tiles_n;
+
+    // patch / gap geometry of this tile
+    int img = 0, oy0 = 0, ox0 = 0, py = 0, px = 0;
+    if (a.mode == M_PATCH) {
+      const int pper = a.patches_y * a.patches_x;
+      img = tile_m / pper;
+      const int pr = tile_m % pper;
+      py = pr / a.patches_x; px = pr % a.patches_x;
+      oy0 = py * a.pph * a.ps - a.pp;
+      ox0 = px * a.ppw * a.ps - a.pp;
+    } else if (a.mode == M_GAP) {
+      img = tile_m;
+    }
+    const int nchunks = (a.mode == M_GAP) ? (OHW + BM - 1) / BM : 1;
+    float colsum[TN];
+#pragma unroll
+    for (int j = 0; j < TN; ++j) colsum[j] = 0.f;
+
+    for (int mc = 0; mc < nchunks; ++mc) {
+      // ---- decode the rows this thread loads ---------------------------------------------------
+      int ih0[A_IT], iw0[A_IT];
+      long long nbase[A_IT];
+      const int ch = tid & 3;
+#pragma unroll
+      for (int it = 0; it < A_IT; ++it) {
+        const int row = (tid + it * NT) >> 2;
+        int n = 0, oh = 0, ow = 0;
+        bool ok = row < BM;
+        if (a.mode == M_FLAT) {
+          const int m = tile_m * BM + row;
+          ok = ok && m < a.M_total;
+          n = m / OHW; const int p = m - n * OHW; oh = p / a.OW; ow = p - oh * a.OW;
+        } else if (a.mode == M_ZIGZAG) {
+          const int m = tile_m * BM + row;
+          ok = ok && m < a.M_total;
+          const int wdx = m >> 2, j = m & 3, pw_ = a.PH * a.PW;
+          n = wdx / pw_; const int q = wdx - n * pw_; const int ph = q / a.PW;
+          oh = 2 * ph + (j >> 1); ow = 2 * (q - ph * a.PW) + (j & 1);
+        } else if (a.mode == M_PATCH) {
+          const int cy = row / a.patch_w, cx = row - cy * a.patch_w;
+          n = img; oh = oy0 + cy; ow = ox0 + cx;
+          ok = ok && cy < a.patch_h && oh >= 0 && oh < a.OH && ow >= 0 && ow < a.OW;
+        } else {
+          const int p = mc * BM + row;
+          ok = ok && p < OHW;
+          n = img; oh = p / a.OW; ow = p - oh * a.OW;
+        }
+        ih0[it] = ok ? oh * a.stride - a.pad : -(1 << 28);
+        iw0[it] = ow * a.stride - a.pad;
+        nbase[it] = (long long)n * a.in_sN;
+      }
+      // reduction position (r, s, c) of this thread's 16-byte chunk
+      int kc, kr, ks;
+      {
+        const int kk = ch * CE;
+        kc = kk % a.C; const int rs = kk / a.C; ks = rs % a.S; kr = rs / a.S;
+      }
+      const unsigned char* wrow[B_IT];
+#pragma unroll
+      for (int it = 0; it < B_IT; ++it) {
+        const int row = (tid + it * NT) >> 2;
+        wrow[it] = (const unsigned char*)a.w +
+                   ((long long)(tile_n * BN + (row < BN ? row : 0)) * a.Kred_pad + ch * CE) * (long long)sizeof(T);
+      }
+
+      f32x16_t acc[TM][TN];
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+          for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+      u32x4_t ra[A_IT], rb[B_IT];
+
+      auto load_global = [&](int step) {
+        if constexpr (!SCALAR) {
+          const bool kok = kr < a.R;
+#pragma unroll
+          for (int it = 0; it < A_IT; ++it) {
+            const int ih = ih0[it] + kr, iw = iw0[it] + ks;
+            const bool ok = kok && (unsigned)ih < (unsigned)a.H && (unsigned)iw < (unsigned)a.W;
+            u32x4_t v = {0u, 0u, 0u, 0u};
+            if (ok) {
+              const T* p = (const T*)a.in + nbase[it] + (long long)ih * a.in_sH + (long long)iw * a.in_sW + kc;
+              v = *(const u32x4_t*)p;
+            }
+            ra[it] = v;
+          }
+          kc += BKE;
+          while (kc >= a.C) { kc -= a.C; if (++ks == a.S) { ks = 0; ++kr; } }
+        } else {
+          float f[A_IT][CE];
+#pragma unroll
+          for (int e = 0; e < CE; ++e) {
+            const int kk = step * BKE + ch * CE + e;
+            const int off = a.ktab[2 * kk], rs = a.ktab[2 * kk + 1];
+            const int r = rs >> 16, s = rs & 0xffff;
+#pragma unroll
+            for (int it = 0; it < A_IT; ++it) {
+              const int ih = ih0[it] + r, iw = iw0[it] + s;
+              const bool ok = (unsigned)ih < (unsigned)a.H && (unsigned)iw < (unsigned)a.W;
+              float v = 0.f;
+              if (ok) {
+                const long long idx = nbase[it] + (long long)ih0[it] * a.in_sH + (long long)iw0[it] * a.in_sW + off;
+                v = a.in_f32 ? ((const float*)a.in)[idx] : tr::ld(a.in, idx);
+              }
+              f[it][e] = v;
+            }
+          }
+#pragma unroll
+          for (int it = 0; it < A_IT; ++it) ra[it] = tr::pack(f[it]);
+        }
+#pragma unroll
+        for (int it = 0; it < B_IT; ++it) rb[it] = *(const u32x4_t*)(wrow[it] + (long long)step * ROWB);
+      };
+      auto store_lds = [&](int stage) {
+        unsigned char* sa = smem + stage * (BM + BN) * LDS_ROW;
+        unsigned char* sb = sa + BM * LDS_ROW;
+#pragma unroll
+        for (int it = 0; it < A_IT; ++it) {
+          const int idx = tid + it * NT;
+          if (A_CH % NT == 0 || idx < A_CH) *(u32x4_t*)(sa + (idx >> 2) * LDS_ROW + (idx & 3) * 16) = ra[it];
+        }
+#pragma unroll
+        for (int it = 0; it < B_IT; ++it) {
+          const int idx = tid + it * NT;
+          if (B_CH % NT == 0 || idx < B_CH) *(u32x4_t*)(sb + (idx >> 2) * LDS_ROW + (idx & 3) * 16) = rb[it];
+        }
+      };
+
+      load_global(0);
+      store_lds(0);
+      __syncthreads();
+      for (int step = 0; step < nsteps; ++step) {
+        const bool more = step + 1 < nsteps;
+        if (more) load_global(step + 1);
+        const unsigned char* sa = smem + (step & 1) * (BM + BN) * LDS_ROW;
+        const unsigned char* sb = sa + BM * LDS_ROW;
+#pragma unroll
+        for (int kg = 0; kg < 2; ++kg) {
+          u32x4_t fa[TM], fb[TN];
+#pragma unroll
+          for (int i = 0; i < TM; ++i)
+            fa[i] = *(const u32x4_t*)(sa + (wave_m * WM + i * 32 + l31) * LDS_ROW + kg * 32 + lhalf * 16);
+#pragma unroll
+          for (int j = 0; j < TN; ++j)
+            fb[j] = *(const u32x4_t*)(sb + (wave_n * WN + j * 32 + l31) * LDS_ROW + kg * 32 + lhalf * 16);
+#pragma unroll
+          for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+              if constexpr (sizeof(T) == 2) {
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, fa[i]),
+                                                                    __builtin_bit_cast(bf16x8_t, fb[j]), acc[i][j], 0, 0, 0);
+              } else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                  acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(fa[i][e]), __uint_as_float(fb[j][e]),
+                                                                   acc[i][j], 0, 0, 0);
+              }
+            }
+        }
+        if (more) store_lds((step + 1) & 1);
+        __syncthreads();
+      }
+
+      // ---- epilogue: the rest of the linked chain ------------------------------------------------
+      // Accumulator element e of lane l in a 32x32 tile: row = (e/4)*8 + (l/32)*4 + e%4, column = l%32.
+      if (a.mode == M_FLAT) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+          for (int e = 0; e < 16; ++e) {
+            const int m = tile_m * BM + wave_m * WM + i * 32 + (e >> 2) * 8 + lhalf * 4 + (e & 3);
+            if (m >= a.M_total) continue;
+            const int n = m / OHW, p = m - n * OHW;
+            const long long obase = (long long)n * a.out_sN + (long long)p * a.out_sP;
+            const long long rbase = (long long)n * a.res_sN + (long long)p * a.res_sP;
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+              const int k = tile_n * BN + wave_n * WN + j * 32 + l31;
+              if (k >= a.K) continue;
+              float v = acc[i][j][e] * a.scale[k] + a.shift[k];
+              if (a.has_res) v += tr::ld(a.res, rbase + k);
+              if (a.relu) v = fmaxf(v, 0.f);
+              const long long o = obase + (long long)k * a.out_sK;
+              if (a.out_f32) ((float*)a.out)[o] = v; else tr::st(a.out, o, v);
+            }
+          }
+      } else if (a.mode == M_ZIGZAG) {
+        const int PHW = a.PH * a.PW, nwin = a.M_total >> 2;
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+          for (int g = 0; g < 4; ++g) {
+            const int wdx = ((tile_m * BM + wave_m * WM + i * 32) >> 2) + g * 2 + lhalf;
+            if (wdx >= nwin) continue;
+            const int n = wdx / PHW, q = wdx - n * PHW;
+            const long long obase = (long long)n * a.out_sN + (long long)q * a.out_sP;
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+              const int k = tile_n * BN + wave_n * WN + j * 32 + l31;
+              if (k >= a.K) continue;
+              const float sc = a.scale[k], sh = a.shift[k];
+              float r = 0.f;
+#pragma unroll
+              for (int e = 0; e < 4; ++e) {
+                float v = acc[i][j][g * 4 + e] * sc + sh;
+                if (a.relu) v = fmaxf(v, 0.f);
+                if (a.pool == POOL_MAX) r = (e == 0) ? v : fmaxf(r, v); else r += v;
+              }
+              if (a.pool == POOL_AVG) r *= 0.25f;
+              const long long o = obase + (long long)k * a.out_sK;
+              if (a.out_f32) ((float*)a.out)[o] = r; else tr::st(a.out, o, r);
+            }
+          }
+      } else if (a.mode == M_PATCH) {
+        float* stg = (float*)smem;                                 // [BM][BN+1], aliases the operand stages
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+          for (int j = 0; j < TN; ++j) {
+            const int col = wave_n * WN + j * 32 + l31;
+            const int k = tile_n * BN + col;
+            const float sc = a.scale[k], sh = a.shift[k];           // arrays are padded to the tile
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+              const int row = wave_m * WM + i * 32 + (e >> 2) * 8 + lhalf * 4 + (e & 3);
+              float v = acc[i][j][e] * sc + sh;
+              if (a.relu) v = fmaxf(v, 0.f);
+              stg[row * (BN + 1) + col] = v;
+            }
+          }
+        __syncthreads();
+        const int nq = a.pph * a.ppw;
+        for (int idx = tid; idx < nq * BN; idx += NT) {
+          const int col = idx % BN, q = idx / BN;
+          const int k = tile_n * BN + col;
+          const int qy = q / a.ppw, qx = q - qy * a.ppw;
+          const int gy = py * a.pph + qy, gx = px * a.ppw + qx;
+          if (k >= a.K || gy >= a.PH || gx >= a.PW) continue;
+          float mx = -INFINITY, sum = 0.f;
+          int cnt = 0, cntp = 0;
+          for (int r = 0; r < a.pk; ++r)
+            for (int s = 0; s < a.pk; ++s) {
+              const int cy = qy * a.ps + r, cx = qx * a.ps + s;
+              const int oh = oy0 + cy, ow = ox0 + cx;
+              if (oh < a.OH + a.pp && ow < a.OW + a.pp) ++cntp;
+              if (oh < 0 || oh >= a.OH || ow < 0 || ow >= a.OW) continue;
+              const float v = stg[(cy * a.patch_w + cx) * (BN + 1) + col];
+              mx = fmaxf(mx, v); sum += v; ++cnt;
+            }
+          const float r = (a.pool == POOL_MAX) ? mx : sum / (float)(a.cip ? cntp : cnt);
+          const long long o = (long long)img * a.out_sN + (long long)(gy * a.PW + gx) * a.out_sP + (long long)k * a.out_sK;
+          if (a.out_f32) ((float*)a.out)[o] = r; else tr::st(a.out, o, r);
+        }
+        __syncthreads();
+      } else {  // M_GAP: accumulate the column sums of this chunk
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+          const int k = tile_n * BN + wave_n * WN + j * 32 + l31;
+          const float sc = a.scale[k], sh = a.shift[k];
+#pragma unroll
+          for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+              const int p = mc * BM + wave_m * WM + i * 32 + (e >> 2) * 8 + lhalf * 4 + (e & 3);
+              float v = acc[i][j][e] * sc + sh;
+              if (a.relu) v = fmaxf(v, 0.f);
+              if (p < OHW) colsum[j] += v;
+            }
+        }
+      }
+    }  // chunks
+
+    if (a.mode == M_GAP) {
+      // fixed-order reduction: lane pair, then wavefronts along m through LDS
+      float* red = (float*)smem;                                   // [BM/WM][BN]
+#pragma unroll
+      for (int j = 0; j < TN; ++j) {
+        const float other = __shfl_xor(colsum[j], 32);
+        const float s = lhalf ? other + colsum[j] : colsum[j] + other;   // same operand order on both lanes
+        if (lhalf == 0) red[wave_m * BN + wave_n * WN + j * 32 + l31] = s;
+      }
+      __syncthreads();
+      for (int col = tid; col < BN; col += NT) {
+        const int k = tile_n * BN + col;
+        if (k >= a.K) continue;
+        float s = 0.f;
+        for (int wm = 0; wm < BM / WM; ++wm) s += red[wm * BN + col];
+        s /= (float)OHW;
+        const long long o = (long long)img * a.out_sN + (long long)k * a.out_sK;
+        if (a.out_f32) ((float*)a.out)[o] = s; else tr::st(a.out, o, s);
+      }
+      __syncthreads();
+    }
+  }
+}
+
+template <typename T, int BM, int BN, int WM, int WN>
+static int launch_conv_cfg(const ConvArgs& a, int scalar, hipStream_t st) {
+  const int lds = (a.mode == M_PATCH) ? cmax(lds_main_bytes<BM, BN>(), lds_patch_bytes<BM, BN>()) : lds_main_bytes<BM, BN>();
+  constexpr int lds_max = cmax(lds_main_bytes<BM, BN>(), lds_patch_bytes<BM, BN>());
+  if (lds_max > 64 * 1024) {   // more than the default dynamic-LDS limit: raise it once per instantiation
+    static bool raised[2] = {false, false};
+    if (!raised[scalar ? 1 : 0]) {
+      hipError_t e = scalar ? hipFuncSetAttribute((const void*)conv_kernel<T, BM, BN, WM, WN, true>,
+                                                  hipFuncAttributeMaxDynamicSharedMemorySize, lds_max)
+                            : hipFuncSetAttribute((const void*)conv_kernel<T, BM, BN, WM, WN, false>,
+                                                  hipFuncAttributeMaxDynamicSharedMemorySize, lds_max);
+      if (e != hipSuccess) return (int)e;
+      raised[scalar ? 1 : 0] = true;
+    }
+  }
+  if (scalar)
+    hipLaunchKernelGGL((conv_kernel<T, BM, BN, WM, WN, true>), dim3(a.grid), dim3(NT), lds, st, a);
+  else
+    hipLaunchKernelGGL((conv_kernel<T, BM, BN, WM, WN, false>), dim3(a.grid), dim3(NT), lds, st, a);
+  return (int)hipGetLastError();
+}
+
+template <typename T>
+static int launch_conv_t(const ConvArgs& a, int cfg, int scalar, hipStream_t st) {
+  switch (cfg) {
+    case 0: return launch_conv_cfg<T, 128, 128, 64, 64>(a, scalar, st);
+    case 1: return launch_conv_cfg<T, 128, 64, 64, 32>(a, scalar, st);
+    case 2: return launch_conv_cfg<T, 64, 64, 32, 32>(a, scalar, st);
+    case 3: return launch_conv_cfg<T, 32, 128, 32, 32>(a, scalar, st);
+  }
+  return (int)hipErrorInvalidValue;
+}
+
+int launch_conv(const ConvArgs& a, int dtype, int cfg, int scalar_loader, void* stream) {
+  hipStream_t st = (hipStream_t)stream;
+  return dtype == DT_BF16 ? launch_conv_t<bf16_t>(a, cfg, scalar_loader, st) : launch_conv_t<float>(a, cfg, scalar_loader, st);
+}
+
+size_t conv_lds_bytes(int cfg, int mode) {
+  const TileCfg& c = kTileCfgs[cfg];
+  size_t main_b = (size_t)2 * (c.bm + c.bn) * LDS_ROW;
+  size_t patch_b = (size_t)c.bm * (c.bn + 1) * 4;
+  return (mode == M_PATCH && patch_b > main_b) ? patch_b : main_b;
+}
+
+// ---------------------------------------------------------------------------------------------
+// Depthwise convolution chain: one thread = one 16-byte channel vector of one output pixel.
+// ---------------------------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(NT) void dw_kernel(const DwArgs a) {
+  using tr = Tr<T>;
+  constexpr int CE = tr::CE;
+  const int cv = a.C / CE;
+  for (long long idx = (long long)blockIdx.x * NT + threadIdx.x; idx < a.total_vec; idx += (long long)gridDim.x * NT) {
+    const int c0 = (int)(idx % cv) * CE;
+    long long pix = idx / cv;
+    const int ow = (int)(pix % a.OW); pix /= a.OW;
+    const int oh = (int)(pix % a.OH);
+    const int n = (int)(pix / a.OH);
+    float acc[CE];
+#pragma unroll
+    for (int e = 0; e < CE; ++e) acc[e] = 0.f;
+    for (int r = 0; r < a.R; ++r) {
+      const int ih = oh * a.stride - a.pad + r;
+      if ((unsigned)ih >= (unsigned)a.H) continue;
+      for (int s = 0; s < a.S; ++s) {
+        const int iw = ow * a.stride - a.pad + s;
+        if ((unsigned)iw >= (unsigned)a.W) continue;
+        const T* p = (const T*)a.in + (long long)n * a.in_sN + ((long long)ih * a.W + iw) * a.in_sP + c0;
+        const T* q = (const T*)a.w + (long long)(r * a.S + s) * a.C + c0;
+        float x[CE], w[CE];
+        tr::unpack(*(const u32x4_t*)p, x);
+        tr::unpack(*(const u32x4_t*)q, w);
+#pragma unroll
+        for (int e = 0; e < CE; ++e) acc[e] = fmaf(x[e], w[e], acc[e]);
+      }
+    }
+#pragma unroll
+    for (int e = 0; e < CE; ++e) {
+      float v = acc[e] * a.scale[c0 + e] + a.shift[c0 + e];
+      acc[e] = a.relu ? fmaxf(v, 0.f) : v;
+    }
+    T* o = (T*)a.out + (long long)n * a.out_sN + ((long long)oh * a.OW + ow) * a.out_sP + c0;
+    *(u32x4_t*)o = tr::pack(acc);
+  }
+}
+
+static int grid_for(long long work_items, int per_block) {
+  long long b = (work_items + per_block - 1) / per_block;
+  if (b < 1) b = 1;
+  if (b > 256 * 32) b = 256 * 32;
+  return (int)b;
+}
+
+int launch_dw(const DwArgs& a, int dtype, void* stream) {
+  hipStream_t st = (hipStream_t)stream;
+  const int grid = grid_for(a.total_vec, NT);
+  if (dtype == DT_BF16) hipLaunchKernelGGL(dw_kernel<bf16_t>, dim3(grid), dim3(NT), 0, st, a);
+  else hipLaunchKernelGGL(dw_kernel<float>, dim3(grid), dim3(NT), 0, st, a);
+  return (int)hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------------
+// Stand-alone element-wise pass (bias / BN as scale+shift, ReLU, add, concat copy) on NHWC views.
+// ---------------------------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(NT) void elt_kernel(const EltArgs a) {
+  using tr = Tr<T>;
+  const long long total = a.pixels * a.C;
+  for (long long idx = (long long)blockIdx.x * NT + threadIdx.x; idx < total; idx += (long long)gridDim.x * NT) {
+    const int c = (int)(idx % a.C);
+    const long long p = idx / a.C;
+    float v = tr::ld(a.a, p * a.a_sP + c);
+    if (a.op == ELT_AFFINE) v = v * a.scale[c] + a.shift[c];
+    else if (a.op == ELT_ADD) v += tr::ld(a.b, p * a.b_sP + c);
+    if (a.relu || a.op == ELT_RELU) v = fmaxf(v, 0.f);
+    tr::st(a.out, p * a.out_sP + c, v);
+  }
+}
+
+template <typename T>
+__global__ __launch_bounds__(NT) void elt_vec_kernel(const EltArgs a) {
+  using tr = Tr<T>;
+  constexpr int CE = tr::CE;
+  const int cv = a.C / CE;
+  const long long total = a.pixels * cv;
+  for (long long idx = (long long)blockIdx.x * NT + threadIdx.x; idx < total; idx += (long long)gridDim.x * NT) {
+    const int c = (int)(idx % cv) * CE;
+    const long long p = idx / cv;
+    float v[CE];
+    tr::unpack(*(const u32x4_t*)((const T*)a.a + p * a.a_sP + c), v);
+    if (a.op == ELT_AFFINE) {
+#pragma unroll
+      for (int e = 0; e < CE; ++e) v[e] = v[e] * a.scale[c + e] + a.shift[c + e];
+    } else if (a.op == ELT_ADD) {
+      float w[CE];
+      tr::unpack(*(const u32x4_t*)((const T*)a.b + p * a.b_sP + c), w);
+#pragma unroll
+      for (int e = 0; e < CE; ++e) v[e] += w[e];
+    }
+    if (a.relu || a.op == ELT_RELU) {
+#pragma unroll
+      for (int e = 0; e < CE; ++e) v[e] = fmaxf(v[e], 0.f);
+    }
+    *(u32x4_t*)((T*)a.out + p * a.out_sP + c) = tr::pack(v);
+  }
+}
+
+int launch_elt(const EltArgs& a, int dtype, void* stream) {
+  hipStream_t st = (hipStream_t)stream;
+  const int ce = dtype == DT_BF16 ? 8 : 4;
+  const bool vec = a.C % ce == 0 && a.a_sP % ce == 0 && a.out_sP % ce == 0 && (a.op != ELT_ADD || a.b_sP % ce == 0) &&
+                   ((uintptr_t)a.a % 16 == 0) && ((uintptr_t)a.out % 16 == 0) && (a.op != ELT_ADD || (uintptr_t)a.b % 16 == 0);
+  if (vec) {
+    const int grid = grid_for(a.pixels * (a.C / ce), NT);
+    if (dtype == DT_BF16) hipLaunchKernelGGL(elt_vec_kernel<bf16_t>, dim3(grid), dim3(NT), 0, st, a);
+    else hipLaunchKernelGGL(elt_vec_kernel<float>, dim3(grid), dim3(NT), 0, st, a);
+  } else {
+    const int grid = grid_for(a.pixels * a.C, NT);
+    if (dtype == DT_BF16) hipLaunchKernelGGL(elt_kernel<bf16_t>, dim3(grid), dim3(NT), 0, st, a);
+    else hipLaunchKernelGGL(elt_kernel<float>, dim3(grid), dim3(NT), 0, st, a);
+  }
+  return (int)hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------------
+// Stand-alone pooling pass (max / average / global average) on NHWC views; one thread per output element.
+// ---------------------------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(NT) void pool_kernel(const PoolArgs a) {
+  using tr = Tr<T>;
+  const long long total = (long long)a.N * a.OH * a.OW * a.C;
+  for (long long idx = (long long)blockIdx.x * NT + threadIdx.x; idx < total; idx += (long long)gridDim.x * NT) {
+    const int c = (int)(idx % a.C);
+    long long q = idx / a.C;
+    const int ow = (int)(q % a.OW); q /= a.OW;
+    const int oh = (int)(q % a.OH);
+    const int n = (int)(q / a.OH);
+    const long long ib = (long long)n * a.in_sN + c;
+    float r;
+    if (a.kind == POOL_GAP) {
+      float s = 0.f;
+      for (int p = 0; p < a.H * a.W; ++p) s += tr::ld(a.in, ib + (long long)p * a.in_sP);
+      r = s / (float)(a.H * a.W);
+    } else {
+      float mx = -INFINITY, sum = 0.f;
+      int cnt = 0, cntp = 0;
+      for (int i = 0; i < a.k; ++i)
+        for (int j = 0; j < a.k; ++j) {
+          const int ih = oh * a.s - a.p + i, iw = ow * a.s - a.p + j;
+          if (ih < a.H + a.p && iw < a.W + a.p) ++cntp;
+          if (ih < 0 || ih >= a.H || iw < 0 || iw >= a.W) continue;
+          const float v = tr::ld(a.in, ib + ((long long)ih * a.W + iw) * a.in_sP);
+          mx = fmaxf(mx, v); sum += v; ++cnt;
+        }
+      r = a.kind == POOL_MAX ? mx : sum / (float)(a.cip ? cntp : cnt);
+    }
+    tr::st(a.out, (long long)n * a.out_sN + ((long long)oh * a.OW + ow) * a.out_sP + c, r);
+  }
+}
+
+int launch_pool(const PoolArgs& a, int dtype, void* stream) {
+  hipStream_t st = (hipStream_t)stream;
+  const int grid = grid_for((long long)a.N * a.OH * a.OW * a.C, NT);
+  if (dtype == DT_BF16) hipLaunchKernelGGL(pool_kernel<bf16_t>, dim3(grid), dim3(NT), 0, st, a);
+  else hipLaunchKernelGGL(pool_kernel<float>, dim3(grid), dim3(NT), 0, st, a);
+  return (int)hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------------
+// Graph-boundary layout / type conversion (strided gather, channel-fastest writes).
+// ---------------------------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(NT) void cvt_kernel(const CvtArgs a) {
+  using tr = Tr<T>;
+  const long long HW = (long long)a.H * a.W, total = (long long)a.N * HW * a.C;
+  for (long long idx = (long long)blockIdx.x * NT + threadIdx.x; idx < total; idx += (long long)gridDim.x * NT) {
+    const int c = (int)(idx % a.C);
+    long long q = idx / a.C;
+    const long long p = q % HW;
+    const long long n = q / HW;
+    const long long i = n * a.in_sN + c * a.in_sC + p * a.in_sP;
+    const long long o = n * a.out_sN + c * a.out_sC + p * a.out_sP;
+    const float v = a.in_f32 ? ((const float*)a.in)[i] : tr::ld(a.in, i);
+    if (a.out_f32) ((float*)a.out)[o] = v; else tr::st(a.out, o, v);
+  }
+}
+
+int launch_cvt(const CvtArgs& a, int dtype, void* stream) {
+  hipStream_t st = (hipStream_t)stream;
+  const int grid = grid_for((long long)a.N * a.H * a.W * a.C, NT);
+  if (dtype == DT_BF16) hipLaunchKernelGGL(cvt_kernel<bf16_t>, dim3(grid), dim3(NT), 0, st, a);
+  else hipLaunchKernelGGL(cvt_kernel<float>, dim3(grid), dim3(NT), 0, st, a);
+  return (int)hipGetLastError();
+}
+
+}  // namespace xenos

@@ -1,0 +1,1121 @@
+// Host side of the library: graph ingest, the automatic optimiser (fusion pre-pass, operator
+// linking, DSP-aware operator split; Sections 4.1-4.4 of the paper) and the runtime that enqueues
+// the planned kernel sequence (Section 3).  Pure C++ plus the HIP runtime API; all arithmetic on
+// tensor data happens in the gfx950 kernels.
+#include <hip/hip_runtime_api.h>
+#include <math.h>
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <algorithm>
+#include <map>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "../../include/xenos.h"
+#include "kernels.h"
+
+using namespace xenos;
+
+namespace {
+
+thread_local std::string g_err;
+
+xenos_status fail(xenos_status st, const char* fmt, ...) {
+  char buf[512];
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(buf, sizeof buf, fmt, ap);
+  va_end(ap);
+  g_err = buf;
+  return st;
+}
+
+constexpr uint32_t MAGIC_GRAPH = 0x58474631u, MAGIC_PLAN = 0x58504c31u;
+
+struct Shape { int n = 0, c = 0, h = 0, w = 0; };
+
+struct GOp {
+  xenos_op_desc d;
+  std::vector<float> weight, bias, gamma, beta, mean, var;
+};
+
+int pool_out(int n, int k, int s, int p, int ceil_mode) {
+  if (ceil_mode) {
+    int o = (n + 2 * p - k + s - 1) / s + 1;
+    if ((o - 1) * s >= n + p) --o;
+    return o;
+  }
+  return (n + 2 * p - k) / s + 1;
+}
+
+}  // namespace
+
+struct xenos_graph {
+  uint32_t magic = MAGIC_GRAPH;
+  xenos_tensor_desc in{}, out{};
+  std::vector<GOp> ops;
+  std::vector<Shape> shapes;   // by tensor id
+  int output_id = 0;
+};
+
+// ---------------------------------------------------------------------------------------------
+// Plan structures
+// ---------------------------------------------------------------------------------------------
+namespace {
+
+enum StepKind { S_CONV = 0, S_DW = 1, S_ELT = 2, S_POOL = 3, S_CVT = 4 };
+const char* kStepNames[] = {"conv", "dwconv", "elt", "pool", "cvt"};
+const char* kModeNames[] = {"flat", "zigzag", "patch", "gap"};
+
+struct Buffer {
+  long long bytes = 0;
+  int ext = 0;                 // 0 workspace, 1 graph input, 2 graph output
+  size_t offset = 0;
+  int first = 1 << 30, last = -1;
+};
+
+// A logical tensor as laid out in memory: element strides for image, pixel (h*W+w) and channel.
+struct View {
+  int buf = -1;
+  long long off = 0;           // element offset into the buffer (channel offset of a concat slice)
+  long long sN = 0, sP = 0, sK = 1;
+  int f32 = 0;                 // elements are fp32 (only possible for graph input / output)
+  int esz = 4;
+  Shape s;
+  bool internal_nhwc() const { return sK == 1; }
+};
+
+struct Step {
+  int kind = S_CONV;
+  std::string name;
+  std::vector<int> ops;        // graph operator ids executed by this step
+  ConvArgs conv{};
+  DwArgs dw{};
+  EltArgs elt{};
+  PoolArgs pool{};
+  CvtArgs cvt{};
+  int cfg = 0, scalar = 0;
+  int v_in = -1, v_in2 = -1, v_out = -1;
+  long long w_off = -1, scale_off = -1, shift_off = -1, ktab_off = -1;   // byte offsets into the weight image
+  double flops = 0;
+  long long bytes_in = 0, bytes_w = 0, bytes_out = 0, bytes_res = 0;
+  size_t lds = 0;
+};
+
+// Internal node list (a rewritten copy of the graph: pooling hoisted above concat when linking).
+struct Node {
+  int kind = 0;
+  std::vector<int> in;
+  int src = -1;                // graph op that supplies attributes / parameters
+  Shape out;
+};
+
+}  // namespace
+
+struct xenos_plan {
+  uint32_t magic = MAGIC_PLAN;
+  xenos_plan_opts opts{};
+  xenos_hw_info hw{};
+  xenos_tensor_desc in{}, out{};
+  int dt = DT_F32, esz = 4, ce = 4;
+  std::vector<Buffer> bufs;
+  std::vector<View> views;
+  std::vector<Step> steps;
+  std::vector<unsigned char> wimage;   // exact image of the device weight buffer
+  size_t workspace_bytes = 0;
+  std::string json;
+  void* d_weights = nullptr;
+  void* d_workspace = nullptr;
+  bool bound = false;
+};
+
+namespace {
+
+size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+uint16_t f2bf_host(float f) {
+  uint32_t u;
+  memcpy(&u, &f, 4);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Planner
+// ---------------------------------------------------------------------------------------------
+struct Planner {
+  const xenos_graph& g;
+  xenos_plan& p;
+  std::vector<Node> nodes;
+  std::vector<Shape> tshape;                 // by tensor id (node list numbering)
+  std::vector<std::vector<int>> consumers;   // tensor id -> node indices
+  int out_tid = 0;
+  std::vector<int> tview;                    // tensor id -> view index (-1 = not materialised)
+  std::vector<int> node_step;                // node -> step index (-1 = not yet planned)
+  std::vector<int> node_final;               // node -> 1 if its output is its step's output
+  struct Place { int cat_tid; int c_off; };
+  std::map<int, Place> placed;               // tensor id -> slice of a concat output
+  std::vector<char> free_concat;             // node -> concat realised by offset writes
+
+  Planner(const xenos_graph& g_, xenos_plan& p_) : g(g_), p(p_) {}
+
+  const xenos_op_desc& desc(const Node& n) const { return g.ops[n.src].d; }
+
+  size_t wpush(const void* data, size_t bytes) {
+    size_t off = align_up(p.wimage.size(), 256);
+    p.wimage.resize(off + bytes);
+    if (data) memcpy(p.wimage.data() + off, data, bytes);
+    return off;
+  }
+
+  // ---- node list -----------------------------------------------------------------------------
+  void build_nodes() {
+    const int n_ops = (int)g.ops.size();
+    std::vector<std::vector<int>> cons(n_ops + 1);
+    for (int i = 0; i < n_ops; ++i)
+      for (int j = 0; j < g.ops[i].d.n_inputs; ++j) cons[g.ops[i].d.inputs[j]].push_back(i);
+    auto is_pool = [&](int k) { return k == XENOS_OP_MAXPOOL || k == XENOS_OP_AVGPOOL || k == XENOS_OP_GLOBAL_AVGPOOL; };
+    // concat -> pool hoisting (pooling is per channel, so it commutes with a channel concat); lets the
+    // pooling link into each producer of the concat
+    std::vector<int> hoist_pool(n_ops, -1);   // concat op -> pool op
+    std::vector<char> skip(n_ops, 0);
+    if (p.opts.link >= 2)
+      for (int i = 0; i < n_ops; ++i) {
+        if (g.ops[i].d.kind != XENOS_OP_CONCAT || g.output_id == i + 1) continue;
+        if (cons[i + 1].size() == 1 && is_pool(g.ops[cons[i + 1][0]].d.kind)) {
+          hoist_pool[i] = cons[i + 1][0];
+          skip[cons[i + 1][0]] = 1;
+        }
+      }
+    std::vector<int> remap(n_ops + 1, -1);
+    remap[0] = 0;
+    tshape.clear();
+    tshape.push_back(g.shapes[0]);
+    auto push = [&](Node nd) {
+      nodes.push_back(nd);
+      tshape.push_back(nd.out);
+      return (int)nodes.size();
+    };
+    for (int i = 0; i < n_ops; ++i) {
+      if (skip[i]) continue;   // remap set when its concat was emitted
+      const xenos_op_desc& d = g.ops[i].d;
+      if (hoist_pool[i] >= 0) {
+        const int po = hoist_pool[i];
+        Node cat;
+        cat.kind = XENOS_OP_CONCAT; cat.src = i; cat.out = g.shapes[po + 1];
+        for (int j = 0; j < d.n_inputs; ++j) {
+          Node pl;
+          pl.kind = g.ops[po].d.kind; pl.src = po;
+          pl.in = {remap[d.inputs[j]]};
+          pl.out = g.shapes[po + 1];
+          pl.out.c = g.shapes[d.inputs[j]].c;
+          cat.in.push_back(push(pl));
+        }
+        const int t = push(cat);
+        remap[i + 1] = t;
+        remap[po + 1] = t;
+        continue;
+      }
+      Node nd;
+      nd.kind = d.kind; nd.src = i; nd.out = g.shapes[i + 1];
+      for (int j = 0; j < d.n_inputs; ++j) nd.in.push_back(remap[d.inputs[j]]);
+      remap[i + 1] = push(nd);
+    }
+    out_tid = remap[g.output_id];
+    consumers.assign(nodes.size() + 1, {});
+    for (int i = 0; i < (int)nodes.size(); ++i)
+      for (int t : nodes[i].in) consumers[t].push_back(i);
+  }
+
+  // ---- views / buffers -----------------------------------------------------------------------
+  int new_buffer(long long bytes, int ext) {
+    Buffer b;
+    b.bytes = bytes; b.ext = ext;
+    p.bufs.push_back(b);
+    return (int)p.bufs.size() - 1;
+  }
+
+  int ext_view(const xenos_tensor_desc& d, int ext) {
+    View v;
+    v.s = Shape{d.n, d.c, d.h, d.w};
+    v.f32 = d.dtype == XENOS_F32 ? 1 : 0;
+    v.esz = d.dtype == XENOS_F32 ? 4 : 2;
+    if (d.layout == XENOS_NHWC) { v.sK = 1; v.sP = d.c; v.sN = (long long)d.h * d.w * d.c; }
+    else { v.sK = (long long)d.h * d.w; v.sP = 1; v.sN = (long long)d.c * d.h * d.w; }
+    v.buf = new_buffer((long long)d.n * d.c * d.h * d.w * v.esz, ext);
+    p.views.push_back(v);
+    return (int)p.views.size() - 1;
+  }
+  // is the external tensor directly usable as an internal NHWC tensor of the compute type?
+  bool ext_is_internal(const xenos_tensor_desc& d) const {
+    const bool dt_ok = (d.dtype == XENOS_F32 && p.dt == DT_F32) || (d.dtype == XENOS_BF16 && p.dt == DT_BF16);
+    const bool lay_ok = d.layout == XENOS_NHWC || (d.h == 1 && d.w == 1);
+    return dt_ok && lay_ok;
+  }
+  int internal_view(const Shape& s, int buf = -1, int ctot = 0, int c_off = 0) {
+    View v;
+    v.s = s; v.esz = p.esz; v.f32 = 0;
+    if (ctot == 0) ctot = s.c;
+    v.sK = 1; v.sP = ctot; v.sN = (long long)s.h * s.w * ctot; v.off = c_off;
+    v.buf = buf >= 0 ? buf : new_buffer((long long)s.n * s.h * s.w * ctot * p.esz, 0);
+    p.views.push_back(v);
+    return (int)p.views.size() - 1;
+  }
+  // Fix up an external view so that steps treating it as "internal" see NHWC strides (1x1 maps in NCHW).
+  void normalise_1x1(View& v) {
+    if (v.s.h == 1 && v.s.w == 1) { v.sK = 1; v.sP = v.s.c; v.sN = v.s.c; }
+  }
+
+  // View a step should write tensor `tid` to.  Creates it on first request.
+  int out_view_for(int tid, bool producer_is_conv) {
+    if (tview[tid] >= 0) return tview[tid];
+    const Shape s = tshape[tid];
+    int v;
+    auto it = placed.find(tid);
+    if (it != placed.end()) {
+      const int cat = it->second.cat_tid;
+      const int cv = out_view_for(cat, false);
+      const View& c = p.views[cv];
+      View sl = c;
+      sl.s = s; sl.off = c.off + it->second.c_off;
+      p.views.push_back(sl);
+      v = (int)p.views.size() - 1;
+    } else if (tid == out_tid) {
+      if (producer_is_conv || ext_is_internal(p.out)) {
+        v = ext_view(p.out, 2);
+        if (ext_is_internal(p.out)) { normalise_1x1(p.views[v]); p.views[v].f32 = 0; }
+      } else {
+        v = internal_view(s);
+        need_export = true;
+      }
+    } else {
+      v = internal_view(s);
+    }
+    tview[tid] = v;
+    return v;
+  }
+  bool need_export = false;
+
+  void touch(int view, int step) {
+    Buffer& b = p.bufs[p.views[view].buf];
+    b.first = std::min(b.first, step);
+    b.last = std::max(b.last, step);
+  }
+
+  long long view_bytes(int v) const {
+    const View& vw = p.views[v];
+    return (long long)vw.s.n * vw.s.c * vw.s.h * vw.s.w * vw.esz;
+  }
+
+  // ---- the fusion pre-pass: fold Bias / Bn into one per-channel scale and shift (fp64) --------
+  struct Affine { std::vector<double> scale, shift; };
+  static void fold_bias(Affine& a, const std::vector<float>& b) {
+    for (size_t k = 0; k < a.shift.size(); ++k) a.shift[k] += (double)b[k];
+  }
+  static void fold_bn(Affine& a, const GOp& o) {
+    for (size_t k = 0; k < a.shift.size(); ++k) {
+      const double s = (double)o.gamma[k] / sqrt((double)o.var[k] + (double)o.d.eps);
+      a.scale[k] *= s;
+      a.shift[k] = (a.shift[k] - (double)o.mean[k]) * s + (double)o.beta[k];
+    }
+  }
+  void push_affine(const Affine& a, int padded, long long* scale_off, long long* shift_off) {
+    std::vector<float> sc(padded, 1.f), sh(padded, 0.f);
+    for (size_t k = 0; k < a.scale.size(); ++k) { sc[k] = (float)a.scale[k]; sh[k] = (float)a.shift[k]; }
+    *scale_off = (long long)wpush(sc.data(), sc.size() * 4);
+    *shift_off = (long long)wpush(sh.data(), sh.size() * 4);
+  }
+
+  // ---- operator split for one dense-conv chain ------------------------------------------------
+  bool choose_patch(int bm, int pk, int ps, int PH, int PW, int* pph, int* ppw) {
+    int best = 0;
+    for (int a = 1; a <= PH; ++a)
+      for (int b = 1; b <= PW; ++b) {
+        const int hh = (a - 1) * ps + pk, ww = (b - 1) * ps + pk;
+        if (hh * ww > bm) continue;
+        const int score = a * b * 64 - abs(a - b);
+        if (score > best) { best = score; *pph = a; *ppw = b; }
+      }
+    return best > 0;
+  }
+
+  xenos_status split_conv(Step& st) {
+    ConvArgs& c = st.conv;
+    const int num_cu = std::max(1, p.hw.num_cu);
+    static const double eff[kNumTileCfgs] = {1.0, 0.85, 0.6, 0.55};
+    double best_cost = 1e300;
+    int best = -1;
+    ConvArgs best_args{};
+    for (int cfg = 0; cfg < kNumTileCfgs; ++cfg) {
+      if (p.opts.tile > 0 && cfg != p.opts.tile - 1) continue;
+      const TileCfg& tc = kTileCfgs[cfg];
+      if (conv_lds_bytes(cfg, c.mode) > p.hw.lds_bytes_per_cu) continue;   // parameter split must fit private memory
+      ConvArgs t = c;
+      if (c.mode == M_FLAT || c.mode == M_ZIGZAG) {
+        t.tiles_m = (c.M_total + tc.bm - 1) / tc.bm;
+      } else if (c.mode == M_PATCH) {
+        if (!choose_patch(tc.bm, c.pk, c.ps, c.PH, c.PW, &t.pph, &t.ppw)) continue;
+        t.patch_h = (t.pph - 1) * c.ps + c.pk;
+        t.patch_w = (t.ppw - 1) * c.ps + c.pk;
+        t.patches_y = (c.PH + t.pph - 1) / t.pph;
+        t.patches_x = (c.PW + t.ppw - 1) / t.ppw;
+        t.tiles_m = c.N * t.patches_y * t.patches_x;
+      } else {
+        t.tiles_m = c.N;
+      }
+      t.tiles_n = (c.K + tc.bn - 1) / tc.bn;
+      t.ntiles = t.tiles_m * t.tiles_n;
+      double per_tile = (double)tc.bm * tc.bn / eff[cfg];
+      if (c.mode == M_GAP) per_tile *= (double)((c.OH * c.OW + tc.bm - 1) / tc.bm);
+      // two workgroups fit on a compute unit; below that, a smaller tile only shortens the critical path
+      const double cost = std::max((double)t.ntiles / (2.0 * num_cu), 1.0) * per_tile;
+      if (cost < best_cost) { best_cost = cost; best = cfg; best_args = t; }
+    }
+    if (best < 0) return fail(XENOS_EUNSUPPORTED, "%s: no tile configuration fits %zu bytes of LDS", st.name.c_str(), p.hw.lds_bytes_per_cu);
+    c = best_args;
+    st.cfg = best;
+    const int slots = (c.ntiles + 7) / 8 * 8;
+    c.grid = p.opts.split ? slots : 1;
+    st.lds = conv_lds_bytes(best, c.mode);
+    return XENOS_OK;
+  }
+
+  // ---- pack weights of a dense conv / fc in operand order -------------------------------------
+  void pack_dense(Step& st, const GOp& o, int C, int R, int S, int K) {
+    const int bke = p.dt == DT_BF16 ? 32 : 16;
+    const int kred = R * S * C, kred_pad = (kred + bke - 1) / bke * bke;
+    const int kout_pad = (K + 127) / 128 * 128;
+    st.conv.Kred = kred; st.conv.Kred_pad = kred_pad;
+    const size_t bytes = (size_t)kout_pad * kred_pad * p.esz;
+    st.w_off = (long long)wpush(nullptr, bytes);
+    unsigned char* base = p.wimage.data() + st.w_off;
+    memset(base, 0, bytes);
+    // source [K][C][R][S] -> destination [K][(r*S+s)*C + c]
+    for (int k = 0; k < K; ++k) {
+      const float* src = o.weight.data() + (size_t)k * C * R * S;
+      if (p.dt == DT_BF16) {
+        uint16_t* dst = (uint16_t*)base + (size_t)k * kred_pad;
+        for (int c = 0; c < C; ++c)
+          for (int rs = 0; rs < R * S; ++rs) dst[(size_t)rs * C + c] = f2bf_host(src[(size_t)c * R * S + rs]);
+      } else {
+        float* dst = (float*)base + (size_t)k * kred_pad;
+        for (int c = 0; c < C; ++c)
+          for (int rs = 0; rs < R * S; ++rs) dst[(size_t)rs * C + c] = src[(size_t)c * R * S + rs];
+      }
+    }
+    st.bytes_w = (long long)K * kred * p.esz;
+  }
+
+  // ---- main pass --------------------------------------------------------------------------------
+  xenos_status run() {
+    p.dt = p.opts.compute == XENOS_BF16 ? DT_BF16 : DT_F32;
+    p.esz = p.dt == DT_BF16 ? 2 : 4;
+    p.ce = 16 / p.esz;
+    build_nodes();
+    const int nn = (int)nodes.size();
+    tview.assign(nn + 1, -1);
+    node_step.assign(nn, -1);
+    node_final.assign(nn, 0);
+    free_concat.assign(nn, 0);
+
+    // concat realised as channel-offset stores of its producers (Eq. 1: split halves join without a
+    // layout transformation)
+    if (p.opts.link >= 2)
+      for (int i = 0; i < nn; ++i) {
+        if (nodes[i].kind != XENOS_OP_CONCAT) continue;
+        const int ctot = nodes[i].out.c;
+        bool ok = ctot % p.ce == 0;
+        int off = 0;
+        for (int t : nodes[i].in) {
+          if (t == 0 || t == out_tid || placed.count(t) || off % p.ce != 0) ok = false;
+          else if (nodes[t - 1].kind == XENOS_OP_CONCAT) ok = false;
+          off += tshape[t].c;
+        }
+        for (size_t a = 0; a < nodes[i].in.size(); ++a)
+          for (size_t b = a + 1; b < nodes[i].in.size(); ++b)
+            if (nodes[i].in[a] == nodes[i].in[b]) ok = false;
+        if (!ok) continue;
+        free_concat[i] = 1;
+        off = 0;
+        for (int t : nodes[i].in) { placed[t] = Place{i + 1, off}; off += tshape[t].c; }
+      }
+
+    // graph input
+    {
+      bool direct = ext_is_internal(p.in) && p.in.c % p.ce == 0;
+      bool scalar_ok = !consumers[0].empty() && p.in.c <= 8;
+      for (int ci : consumers[0]) {
+        const Node& nd = nodes[ci];
+        const bool dense = (nd.kind == XENOS_OP_CONV && desc(nd).groups == 1);
+        if (!dense) scalar_ok = false;
+      }
+      const int ev = ext_view(p.in, 1);
+      if (direct) {
+        normalise_1x1(p.views[ev]);
+        p.views[ev].f32 = 0;
+        tview[0] = ev;
+      } else if (scalar_ok) {
+        tview[0] = ev;
+      } else {
+        // import: convert to the internal NHWC layout of the compute type
+        const int iv = internal_view(tshape[0]);
+        Step st;
+        st.kind = S_CVT; st.name = "import";
+        st.v_in = ev; st.v_out = iv;
+        fill_cvt(st);
+        add_step(st);
+        tview[0] = iv;
+      }
+    }
+
+    for (int i = 0; i < nn; ++i) {
+      if (node_step[i] >= 0) continue;
+      xenos_status rc = plan_node(i);
+      if (rc != XENOS_OK) return rc;
+    }
+
+    if (need_export) {
+      Step st;
+      st.kind = S_CVT; st.name = "export";
+      st.v_in = tview[out_tid];
+      st.v_out = ext_view(p.out, 2);
+      fill_cvt(st);
+      add_step(st);
+    }
+    if (out_tid == 0) return fail(XENOS_EUNSUPPORTED, "graph output is the graph input");
+    allocate();
+    write_json();
+    return XENOS_OK;
+  }
+
+  void fill_cvt(Step& st) {
+    const View& a = p.views[st.v_in];
+    const View& b = p.views[st.v_out];
+    CvtArgs& c = st.cvt;
+    c.N = a.s.n; c.C = a.s.c; c.H = a.s.h; c.W = a.s.w;
+    c.in_sN = a.sN; c.in_sC = a.sK; c.in_sP = a.sP; c.in_f32 = a.f32;
+    c.out_sN = b.sN; c.out_sC = b.sK; c.out_sP = b.sP; c.out_f32 = b.f32;
+    st.bytes_in = view_bytes(st.v_in);
+    st.bytes_out = view_bytes(st.v_out);
+  }
+
+  void add_step(Step& st) {
+    const int idx = (int)p.steps.size();
+    if (st.v_in >= 0) touch(st.v_in, idx);
+    if (st.v_in2 >= 0) touch(st.v_in2, idx);
+    if (st.v_out >= 0) touch(st.v_out, idx);
+    p.steps.push_back(st);
+  }
+
+  bool available(int tid) const {
+    if (tid == 0) return true;
+    return node_step[tid - 1] >= 0 && node_final[tid - 1] && tview[tid] >= 0;
+  }
+
+  int single_consumer(int tid) const {
+    if (tid == out_tid || consumers[tid].size() != 1) return -1;
+    return consumers[tid][0];
+  }
+
+  xenos_status need_internal_input(int tid, const char* who, int* view) {
+    const int v = tview[tid];
+    if (v < 0) return fail(XENOS_EINVAL, "%s: input tensor %d is not materialised", who, tid);
+    const View& vw = p.views[v];
+    if (!vw.internal_nhwc() || vw.f32 != 0 || vw.esz != p.esz) {
+      // the graph input reaches an operator that needs the internal layout: import once
+      if (tid != 0) return fail(XENOS_EUNSUPPORTED, "%s: tensor %d has no internal layout", who, tid);
+      const int iv = internal_view(tshape[0]);
+      Step st;
+      st.kind = S_CVT; st.name = "import";
+      st.v_in = v; st.v_out = iv;
+      fill_cvt(st);
+      add_step(st);
+      tview[0] = iv;
+      *view = iv;
+      return XENOS_OK;
+    }
+    *view = v;
+    return XENOS_OK;
+  }
+
+  xenos_status plan_node(int i) {
+    const Node& nd = nodes[i];
+    const xenos_op_desc& d = desc(nd);
+    const GOp& go = g.ops[nd.src];
+    const int link = p.opts.link;
+    const Shape is = tshape[nd.in[0]];
+    Step st;
+    st.name = std::string("op") + std::to_string(nd.src);
+    st.ops.push_back(nd.src);
+    auto finish = [&](int, int out_tensor, bool is_conv) { st.v_out = out_view_for(out_tensor, is_conv); };
+
+    if (nd.kind == XENOS_OP_CONV || nd.kind == XENOS_OP_FC) {
+      const bool is_fc = nd.kind == XENOS_OP_FC;
+      const bool dw = !is_fc && d.groups != 1;
+      const int K = d.out_c;
+      if (dw && (d.groups != is.c || K != is.c)) return fail(XENOS_EUNSUPPORTED, "%s: only groups == 1 or depthwise (groups == C == out_c)", st.name.c_str());
+      if (dw && is.c % p.ce != 0) return fail(XENOS_EUNSUPPORTED, "%s: depthwise channels must be a multiple of %d", st.name.c_str(), p.ce);
+      Affine af;
+      af.scale.assign(K, 1.0);
+      af.shift.assign(K, 0.0);
+      if (!go.bias.empty()) fold_bias(af, go.bias);
+      bool relu = false, has_res = false;
+      int res_tid = -1, pool_node = -1;
+      int cur = i + 1, stage = 0, last = i;
+      std::vector<int> absorbed;
+      while (link >= 1) {
+        const int nx = single_consumer(cur);
+        if (nx < 0 || placed.count(cur)) break;
+        const Node& nn_ = nodes[nx];
+        const GOp& ng = g.ops[nn_.src];
+        if ((nn_.kind == XENOS_OP_BIAS || nn_.kind == XENOS_OP_BN) && stage == 0) {
+          if (nn_.kind == XENOS_OP_BIAS) fold_bias(af, ng.bias); else fold_bn(af, ng);
+        } else if (nn_.kind == XENOS_OP_ADD && link >= 2 && !dw && stage <= 1) {
+          const int other = nn_.in[0] == cur ? nn_.in[1] : nn_.in[0];
+          if (other == cur || !available(other) || other == 0) break;
+          const View& ov = p.views[tview[other]];
+          if (!ov.internal_nhwc() || ov.f32) break;
+          has_res = true; res_tid = other; stage = 2;
+        } else if (nn_.kind == XENOS_OP_RELU && stage <= 2) {
+          relu = true; stage = 3;
+        } else if ((nn_.kind == XENOS_OP_MAXPOOL || nn_.kind == XENOS_OP_AVGPOOL || nn_.kind == XENOS_OP_GLOBAL_AVGPOOL) &&
+                   link >= 2 && !dw && !has_res && stage <= 3) {
+          pool_node = nx; stage = 4;
+        } else {
+          break;
+        }
+        absorbed.push_back(nx);
+        cur = nx + 1; last = nx;
+        if (stage == 4) break;
+      }
+      for (int a : absorbed) st.ops.push_back(nodes[a].src);
+
+      if (dw) {
+        int vin;
+        xenos_status rc = need_internal_input(nd.in[0], st.name.c_str(), &vin);
+        if (rc != XENOS_OK) return rc;
+        st.kind = S_DW;
+        st.v_in = vin;
+        finish(last, cur, false);
+        const View& iv = p.views[st.v_in];
+        const View& ov = p.views[st.v_out];
+        if (!ov.internal_nhwc() || ov.f32) return fail(XENOS_EUNSUPPORTED, "%s: depthwise output must be internal", st.name.c_str());
+        DwArgs& a = st.dw;
+        const Shape os = tshape[i + 1];
+        a.N = is.n; a.C = is.c; a.H = is.h; a.W = is.w; a.R = d.kh; a.S = d.kw; a.stride = d.stride_h; a.pad = d.pad_h;
+        a.OH = os.h; a.OW = os.w; a.in_sN = iv.sN; a.in_sP = iv.sP; a.out_sN = ov.sN; a.out_sP = ov.sP; a.relu = relu;
+        a.total_vec = (long long)a.N * a.OH * a.OW * (a.C / p.ce);
+        // weights [R*S][C]
+        const int taps = d.kh * d.kw;
+        const size_t bytes = (size_t)taps * is.c * p.esz;
+        st.w_off = (long long)wpush(nullptr, bytes);
+        unsigned char* base = p.wimage.data() + st.w_off;
+        for (int c = 0; c < is.c; ++c)
+          for (int t = 0; t < taps; ++t) {
+            const float v = go.weight[(size_t)c * taps + t];
+            if (p.dt == DT_BF16) ((uint16_t*)base)[(size_t)t * is.c + c] = f2bf_host(v);
+            else ((float*)base)[(size_t)t * is.c + c] = v;
+          }
+        push_affine(af, is.c, &st.scale_off, &st.shift_off);
+        st.flops = 2.0 * a.N * a.OH * a.OW * a.C * taps;
+        st.bytes_in = view_bytes(st.v_in); st.bytes_w = (long long)bytes; st.bytes_out = view_bytes(st.v_out);
+      } else {
+        st.kind = S_CONV;
+        const int vin = tview[nd.in[0]];
+        if (vin < 0) return fail(XENOS_EINVAL, "%s: input not materialised", st.name.c_str());
+        st.v_in = vin;
+        const View& iv = p.views[vin];
+        ConvArgs& a = st.conv;
+        a.N = is.n; a.C = is.c; a.H = is.h; a.W = is.w;
+        a.K = K;
+        if (is_fc) { a.R = is.h; a.S = is.w; a.stride = 1; a.pad = 0; a.OH = 1; a.OW = 1; }
+        else { a.R = d.kh; a.S = d.kw; a.stride = d.stride_h; a.pad = d.pad_h; a.OH = tshape[i + 1].h; a.OW = tshape[i + 1].w; }
+        st.scalar = !(iv.internal_nhwc() && !iv.f32 && iv.esz == p.esz && is.c % p.ce == 0 && iv.off % p.ce == 0 && iv.sP % p.ce == 0);
+        a.in_sN = iv.sN; a.in_sH = iv.sP * is.w; a.in_sW = iv.sP; a.in_f32 = iv.f32;
+        a.relu = relu; a.has_res = has_res;
+        if (has_res) {
+          st.v_in2 = tview[res_tid];
+          a.res_sN = p.views[st.v_in2].sN; a.res_sP = p.views[st.v_in2].sP;
+        }
+        a.pool = POOL_NONE; a.mode = M_FLAT;
+        a.PH = a.OH; a.PW = a.OW;
+        if (pool_node >= 0) {
+          const xenos_op_desc& pd = desc(nodes[pool_node]);
+          const Shape ps = tshape[pool_node + 1];
+          a.PH = ps.h; a.PW = ps.w;
+          if (pd.kind == XENOS_OP_GLOBAL_AVGPOOL) { a.pool = POOL_GAP; a.mode = M_GAP; }
+          else {
+            a.pool = pd.kind == XENOS_OP_MAXPOOL ? POOL_MAX : POOL_AVG;
+            a.pk = pd.kh; a.ps = pd.stride_h; a.pp = pd.pad_h; a.cip = pd.count_include_pad;
+            a.mode = (a.pk == 2 && a.ps == 2 && a.pp == 0 && 2 * a.PH <= a.OH && 2 * a.PW <= a.OW) ? M_ZIGZAG : M_PATCH;
+          }
+        }
+        a.M_total = a.mode == M_FLAT ? a.N * a.OH * a.OW : a.mode == M_ZIGZAG ? a.N * a.PH * a.PW * 4 : a.OH * a.OW;
+        pack_dense(st, go, a.C, a.R, a.S, K);
+        push_affine(af, (K + 127) / 128 * 128, &st.scale_off, &st.shift_off);
+        if (st.scalar) {
+          std::vector<int32_t> tab((size_t)2 * a.Kred_pad);
+          for (int kk = 0; kk < a.Kred_pad; ++kk) {
+            if (kk < a.Kred) {
+              const int c = kk % a.C, rs = kk / a.C, s = rs % a.S, r = rs / a.S;
+              tab[2 * kk] = (int32_t)(r * a.in_sH + s * a.in_sW + c * iv.sK);
+              tab[2 * kk + 1] = (r << 16) | s;
+            } else {
+              tab[2 * kk] = 0;
+              tab[2 * kk + 1] = (0x4000 << 16);   // row far outside any map: contributes zero
+            }
+          }
+          st.ktab_off = (long long)wpush(tab.data(), tab.size() * 4);
+        }
+        xenos_status rc = split_conv(st);
+        if (rc != XENOS_OK) return rc;
+        finish(last, cur, true);
+        const View& ov = p.views[st.v_out];
+        a.out_sN = ov.sN; a.out_sP = ov.sP; a.out_sK = ov.sK; a.out_f32 = ov.f32;
+        st.flops = 2.0 * a.N * a.OH * a.OW * (double)K * a.Kred;
+        st.bytes_in = view_bytes(st.v_in); st.bytes_out = view_bytes(st.v_out);
+        if (has_res) st.bytes_res = view_bytes(st.v_in2);
+      }
+      const int sidx = (int)p.steps.size();
+      node_step[i] = sidx;
+      for (int a : absorbed) node_step[a] = sidx;
+      node_final[last] = 1;
+      add_step(st);
+      return XENOS_OK;
+    }
+
+    // ---- stand-alone operators ---------------------------------------------------------------
+    if (nd.kind == XENOS_OP_CONCAT && free_concat[i]) {
+      out_view_for(i + 1, false);          // the buffer exists; producers write their slices into it
+      node_step[i] = std::max(0, (int)p.steps.size() - 1);
+      node_final[i] = 1;
+      return XENOS_OK;
+    }
+    if (nd.kind == XENOS_OP_CONCAT) {
+      const int ov = out_view_for(i + 1, false);
+      if (!p.views[ov].internal_nhwc() || p.views[ov].f32) return fail(XENOS_EUNSUPPORTED, "concat output must be internal");
+      int off = 0;
+      for (size_t j = 0; j < nd.in.size(); ++j) {
+        Step cs;
+        cs.kind = S_ELT; cs.name = st.name + ".part" + std::to_string(j);
+        cs.ops.push_back(nd.src);
+        xenos_status rc = need_internal_input(nd.in[j], cs.name.c_str(), &cs.v_in);
+        if (rc != XENOS_OK) return rc;
+        View sl = p.views[ov];
+        sl.s = tshape[nd.in[j]]; sl.off += off;
+        p.views.push_back(sl);
+        cs.v_out = (int)p.views.size() - 1;
+        fill_elt(cs, ELT_COPY, 0);
+        add_step(cs);
+        off += tshape[nd.in[j]].c;
+      }
+      node_step[i] = (int)p.steps.size() - 1;
+      node_final[i] = 1;
+      return XENOS_OK;
+    }
+
+    xenos_status rc = need_internal_input(nd.in[0], st.name.c_str(), &st.v_in);
+    if (rc != XENOS_OK) return rc;
+    if (nd.kind == XENOS_OP_ADD) {
+      rc = need_internal_input(nd.in[1], st.name.c_str(), &st.v_in2);
+      if (rc != XENOS_OK) return rc;
+    }
+    st.v_out = out_view_for(i + 1, false);
+    if (!p.views[st.v_out].internal_nhwc() || p.views[st.v_out].f32)
+      return fail(XENOS_EUNSUPPORTED, "%s: output must be internal", st.name.c_str());
+    switch (nd.kind) {
+      case XENOS_OP_BIAS:
+      case XENOS_OP_BN: {
+        Affine af;
+        af.scale.assign(is.c, 1.0);
+        af.shift.assign(is.c, 0.0);
+        if (nd.kind == XENOS_OP_BIAS) fold_bias(af, go.bias); else fold_bn(af, go);
+        st.kind = S_ELT;
+        push_affine(af, is.c, &st.scale_off, &st.shift_off);
+        fill_elt(st, ELT_AFFINE, 0);
+        break;
+      }
+      case XENOS_OP_RELU: st.kind = S_ELT; fill_elt(st, ELT_RELU, 0); break;
+      case XENOS_OP_ADD: st.kind = S_ELT; fill_elt(st, ELT_ADD, 0); break;
+      case XENOS_OP_MAXPOOL:
+      case XENOS_OP_AVGPOOL:
+      case XENOS_OP_GLOBAL_AVGPOOL: {
+        st.kind = S_POOL;
+        PoolArgs& a = st.pool;
+        const View& iv = p.views[st.v_in];
+        const View& ov = p.views[st.v_out];
+        const Shape os = tshape[i + 1];
+        a.N = is.n; a.C = is.c; a.H = is.h; a.W = is.w; a.OH = os.h; a.OW = os.w;
+        a.k = d.kh; a.s = d.stride_h; a.p = d.pad_h; a.cip = d.count_include_pad;
+        a.kind = nd.kind == XENOS_OP_MAXPOOL ? POOL_MAX : nd.kind == XENOS_OP_AVGPOOL ? POOL_AVG : POOL_GAP;
+        a.in_sN = iv.sN; a.in_sP = iv.sP; a.out_sN = ov.sN; a.out_sP = ov.sP;
+        st.bytes_in = view_bytes(st.v_in); st.bytes_out = view_bytes(st.v_out);
+        break;
+      }
+      default: return fail(XENOS_EUNSUPPORTED, "operator kind %d", nd.kind);
+    }
+    node_step[i] = (int)p.steps.size();
+    node_final[i] = 1;
+    add_step(st);
+    return XENOS_OK;
+  }
+
+  void fill_elt(Step& st, int op, int relu) {
+    EltArgs& e = st.elt;
+    const View& a = p.views[st.v_in];
+    const View& o = p.views[st.v_out];
+    e.op = op; e.relu = relu; e.C = a.s.c;
+    e.pixels = (long long)a.s.n * a.s.h * a.s.w;
+    e.a_sP = a.sP; e.out_sP = o.sP;
+    if (st.v_in2 >= 0) e.b_sP = p.views[st.v_in2].sP;
+    st.bytes_in = view_bytes(st.v_in) + (st.v_in2 >= 0 ? view_bytes(st.v_in2) : 0);
+    st.bytes_out = view_bytes(st.v_out);
+  }
+
+  // ---- workspace allocation with liveness (first fit) -------------------------------------------
+  void allocate() {
+    struct Blk { size_t off, size; };
+    std::vector<Blk> free_list;
+    size_t top = 0;
+    const int ns = (int)p.steps.size();
+    std::vector<std::vector<int>> born(ns + 1), dies(ns + 1);
+    for (int b = 0; b < (int)p.bufs.size(); ++b) {
+      Buffer& bf = p.bufs[b];
+      if (bf.ext || bf.last < 0) continue;
+      born[bf.first].push_back(b);
+      dies[bf.last].push_back(b);
+    }
+    for (int s = 0; s < ns; ++s) {
+      for (int b : born[s]) {
+        const size_t need = align_up((size_t)p.bufs[b].bytes + 64, 256);   // slack: vector loads never cross the end
+        size_t got = (size_t)-1;
+        for (size_t k = 0; k < free_list.size(); ++k)
+          if (free_list[k].size >= need) {
+            got = free_list[k].off;
+            free_list[k].off += need; free_list[k].size -= need;
+            if (free_list[k].size == 0) free_list.erase(free_list.begin() + k);
+            break;
+          }
+        if (got == (size_t)-1) { got = top; top += need; }
+        p.bufs[b].offset = got;
+        p.bufs[b].bytes = (long long)need;
+      }
+      for (int b : dies[s]) {
+        Blk nb{p.bufs[b].offset, (size_t)p.bufs[b].bytes};
+        free_list.push_back(nb);
+        // coalesce
+        std::sort(free_list.begin(), free_list.end(), [](const Blk& x, const Blk& y) { return x.off < y.off; });
+        for (size_t k = 0; k + 1 < free_list.size();)
+          if (free_list[k].off + free_list[k].size == free_list[k + 1].off) {
+            free_list[k].size += free_list[k + 1].size;
+            free_list.erase(free_list.begin() + k + 1);
+          } else ++k;
+      }
+    }
+    p.workspace_bytes = std::max<size_t>(top, 256);
+  }
+
+  void write_json() {
+    std::string& j = p.json;
+    char buf[1024];
+    double tf = 0; long long tb = 0;
+    for (const Step& s : p.steps) { tf += s.flops; tb += s.bytes_in + s.bytes_w + s.bytes_out + s.bytes_res; }
+    snprintf(buf, sizeof buf, "{\"link\":%d,\"split\":%d,\"compute\":\"%s\",\"num_cu\":%d,\"n_chains\":%d,\"flops\":%.0f,\"hbm_bytes\":%lld,"
+             "\"weight_bytes\":%zu,\"workspace_bytes\":%zu,\"chains\":[",
+             p.opts.link, p.opts.split, p.dt == DT_BF16 ? "bf16" : "f32", p.hw.num_cu, (int)p.steps.size(), tf, tb,
+             p.wimage.size(), p.workspace_bytes);
+    j = buf;
+    for (size_t i = 0; i < p.steps.size(); ++i) {
+      const Step& s = p.steps[i];
+      std::string ops;
+      for (size_t k = 0; k < s.ops.size(); ++k) ops += (k ? "," : "") + std::to_string(s.ops[k]);
+      snprintf(buf, sizeof buf, "%s{\"i\":%d,\"name\":\"%s\",\"kind\":\"%s\",\"ops\":[%s],\"flops\":%.0f,\"bytes_in\":%lld,\"bytes_w\":%lld,"
+               "\"bytes_out\":%lld,\"bytes_res\":%lld",
+               i ? "," : "", (int)i, s.name.c_str(), kStepNames[s.kind], ops.c_str(), s.flops, s.bytes_in, s.bytes_w, s.bytes_out, s.bytes_res);
+      j += buf;
+      if (s.kind == S_CONV) {
+        const ConvArgs& c = s.conv;
+        const TileCfg& tc = kTileCfgs[s.cfg];
+        snprintf(buf, sizeof buf, ",\"mode\":\"%s\",\"loader\":\"%s\",\"N\":%d,\"C\":%d,\"H\":%d,\"W\":%d,\"K\":%d,\"R\":%d,\"S\":%d,\"stride\":%d,"
+                 "\"pad\":%d,\"OH\":%d,\"OW\":%d,\"PH\":%d,\"PW\":%d,\"pool\":%d,\"relu\":%d,\"res\":%d,\"bm\":%d,\"bn\":%d,\"tiles_m\":%d,"
+                 "\"tiles_n\":%d,\"grid\":%d,\"lds\":%zu,\"pph\":%d,\"ppw\":%d,\"patch_h\":%d,\"patch_w\":%d,\"out_c_off\":%lld,\"out_sP\":%lld",
+                 kModeNames[c.mode], s.scalar ? "scalar" : "vector", c.N, c.C, c.H, c.W, c.K, c.R, c.S, c.stride, c.pad, c.OH, c.OW,
+                 c.PH, c.PW, c.pool, c.relu, c.has_res, tc.bm, tc.bn, c.tiles_m, c.tiles_n, c.grid, s.lds, c.pph, c.ppw, c.patch_h,
+                 c.patch_w, p.views[s.v_out].off, c.out_sP);
+        j += buf;
+      }
+      j += "}";
+    }
+    j += "]}";
+  }
+};
+
+// ---------------------------------------------------------------------------------------------
+// Runtime
+// ---------------------------------------------------------------------------------------------
+const unsigned char* view_ptr(const xenos_plan& p, int v, const void* d_in, void* d_out) {
+  const View& vw = p.views[v];
+  const Buffer& b = p.bufs[vw.buf];
+  const unsigned char* base = b.ext == 1 ? (const unsigned char*)d_in
+                              : b.ext == 2 ? (const unsigned char*)d_out
+                                           : (const unsigned char*)p.d_workspace + b.offset;
+  return base + vw.off * vw.esz;
+}
+
+xenos_status launch_step(xenos_plan& p, const Step& s, const void* d_in, void* d_out, void* stream) {
+  const unsigned char* wb = (const unsigned char*)p.d_weights;
+  int rc = 0;
+  switch (s.kind) {
+    case S_CONV: {
+      ConvArgs a = s.conv;
+      a.in = view_ptr(p, s.v_in, d_in, d_out);
+      a.out = (void*)view_ptr(p, s.v_out, d_in, d_out);
+      a.res = s.v_in2 >= 0 ? view_ptr(p, s.v_in2, d_in, d_out) : nullptr;
+      a.w = wb + s.w_off;
+      a.scale = (const float*)(wb + s.scale_off);
+      a.shift = (const float*)(wb + s.shift_off);
+      a.ktab = s.ktab_off >= 0 ? (const int32_t*)(wb + s.ktab_off) : nullptr;
+      rc = launch_conv(a, p.dt, s.cfg, s.scalar, stream);
+      break;
+    }
+    case S_DW: {
+      DwArgs a = s.dw;
+      a.in = view_ptr(p, s.v_in, d_in, d_out);
+      a.out = (void*)view_ptr(p, s.v_out, d_in, d_out);
+      a.w = wb + s.w_off;
+      a.scale = (const float*)(wb + s.scale_off);
+      a.shift = (const float*)(wb + s.shift_off);
+      rc = launch_dw(a, p.dt, stream);
+      break;
+    }
+    case S_ELT: {
+      EltArgs a = s.elt;
+      a.a = view_ptr(p, s.v_in, d_in, d_out);
+      a.b = s.v_in2 >= 0 ? view_ptr(p, s.v_in2, d_in, d_out) : nullptr;
+      a.out = (void*)view_ptr(p, s.v_out, d_in, d_out);
+      a.scale = s.scale_off >= 0 ? (const float*)(wb + s.scale_off) : nullptr;
+      a.shift = s.shift_off >= 0 ? (const float*)(wb + s.shift_off) : nullptr;
+      rc = launch_elt(a, p.dt, stream);
+      break;
+    }
+    case S_POOL: {
+      PoolArgs a = s.pool;
+      a.in = view_ptr(p, s.v_in, d_in, d_out);
+      a.out = (void*)view_ptr(p, s.v_out, d_in, d_out);
+      rc = launch_pool(a, p.dt, stream);
+      break;
+    }
+    case S_CVT: {
+      CvtArgs a = s.cvt;
+      a.in = view_ptr(p, s.v_in, d_in, d_out);
+      a.out = (void*)view_ptr(p, s.v_out, d_in, d_out);
+      rc = launch_cvt(a, p.dt, stream);
+      break;
+    }
+  }
+  if (rc != 0) return fail(XENOS_EDEVICE, "launch of chain %s failed: %s", s.name.c_str(), hipGetErrorString((hipError_t)rc));
+  return XENOS_OK;
+}
+
+}  // namespace
+
+// ---------------------------------------------------------------------------------------------
+// C ABI
+// ---------------------------------------------------------------------------------------------
+extern "C" {
+
+const char* xenos_last_error(void) { return g_err.c_str(); }
+
+xenos_status xenos_graph_create(const xenos_tensor_desc* input, const xenos_op_desc* ops, int n_ops,
+                                int output_tensor_id, const xenos_tensor_desc* output, xenos_graph** out) {
+  if (!input || !ops || !out || n_ops <= 0) return fail(XENOS_EINVAL, "xenos_graph_create: NULL argument or no operators");
+  if (input->n <= 0 || input->c <= 0 || input->h <= 0 || input->w <= 0) return fail(XENOS_ESHAPE, "input shape must be positive");
+  if (output_tensor_id <= 0 || output_tensor_id > n_ops) return fail(XENOS_EINVAL, "output tensor id %d out of range", output_tensor_id);
+  xenos_graph* g = new (std::nothrow) xenos_graph;
+  if (!g) return fail(XENOS_ENOMEM, "out of host memory");
+  g->in = *input;
+  g->shapes.push_back(Shape{input->n, input->c, input->h, input->w});
+  g->output_id = output_tensor_id;
+  xenos_status rc = XENOS_OK;
+  try {
+    for (int i = 0; i < n_ops && rc == XENOS_OK; ++i) {
+      const xenos_op_desc& d = ops[i];
+      GOp o;
+      o.d = d;
+      o.d.weight = o.d.bias = o.d.gamma = o.d.beta = o.d.mean = o.d.var = nullptr;
+      const int want_in = d.kind == XENOS_OP_ADD ? 2 : d.kind == XENOS_OP_CONCAT ? d.n_inputs : 1;
+      if (d.n_inputs != want_in || d.n_inputs < 1 || d.n_inputs > 4 || (d.kind == XENOS_OP_CONCAT && d.n_inputs < 2)) {
+        rc = fail(XENOS_EINVAL, "op %d: wrong number of inputs (%d)", i, d.n_inputs);
+        break;
+      }
+      for (int j = 0; j < d.n_inputs; ++j)
+        if (d.inputs[j] < 0 || d.inputs[j] > i) { rc = fail(XENOS_EINVAL, "op %d: input %d is not an earlier tensor", i, d.inputs[j]); break; }
+      if (rc != XENOS_OK) break;
+      const Shape s = g->shapes[d.inputs[0]];
+      Shape os = s;
+      auto need = [&](const float* ptr, size_t n, std::vector<float>& dst, const char* what, bool required) {
+        if (!ptr) {
+          if (required) rc = fail(XENOS_EINVAL, "op %d: missing %s", i, what);
+          return;
+        }
+        dst.assign(ptr, ptr + n);
+      };
+      switch (d.kind) {
+        case XENOS_OP_CONV: {
+          if (d.kh <= 0 || d.kw <= 0 || d.stride_h <= 0 || d.out_c <= 0 || d.groups <= 0 || d.pad_h < 0)
+            { rc = fail(XENOS_EINVAL, "op %d: bad conv attributes", i); break; }
+          if (d.stride_h != d.stride_w || d.pad_h != d.pad_w) { rc = fail(XENOS_EUNSUPPORTED, "op %d: stride/pad must be equal in h and w", i); break; }
+          if (s.c % d.groups || d.out_c % d.groups) { rc = fail(XENOS_ESHAPE, "op %d: channels not divisible by groups", i); break; }
+          if (s.h + 2 * d.pad_h < d.kh || s.w + 2 * d.pad_w < d.kw) { rc = fail(XENOS_ESHAPE, "op %d: kernel larger than padded map", i); break; }
+          if (d.kh >= 0x4000 || d.kw >= 0x4000) { rc = fail(XENOS_EUNSUPPORTED, "op %d: kernel too large", i); break; }
+          os = Shape{s.n, d.out_c, (s.h + 2 * d.pad_h - d.kh) / d.stride_h + 1, (s.w + 2 * d.pad_w - d.kw) / d.stride_w + 1};
+          need(d.weight, (size_t)d.out_c * (s.c / d.groups) * d.kh * d.kw, o.weight, "weight", true);
+          need(d.bias, d.out_c, o.bias, "bias", false);
+          break;
+        }
+        case XENOS_OP_FC:
+          if (d.out_c <= 0) { rc = fail(XENOS_EINVAL, "op %d: bad fc attributes", i); break; }
+          os = Shape{s.n, d.out_c, 1, 1};
+          need(d.weight, (size_t)d.out_c * s.c * s.h * s.w, o.weight, "weight", true);
+          need(d.bias, d.out_c, o.bias, "bias", false);
+          break;
+        case XENOS_OP_BIAS: need(d.bias, s.c, o.bias, "bias", true); break;
+        case XENOS_OP_BN:
+          need(d.gamma, s.c, o.gamma, "gamma", true);
+          need(d.beta, s.c, o.beta, "beta", true);
+          need(d.mean, s.c, o.mean, "mean", true);
+          need(d.var, s.c, o.var, "var", true);
+          if (rc == XENOS_OK)
+            for (int k = 0; k < s.c; ++k)
+              if (!(o.var[k] + d.eps > 0.f)) { rc = fail(XENOS_EINVAL, "op %d: var + eps must be positive", i); break; }
+          break;
+        case XENOS_OP_RELU: break;
+        case XENOS_OP_MAXPOOL:
+        case XENOS_OP_AVGPOOL:
+          if (d.kh <= 0 || d.kh != d.kw || d.stride_h <= 0 || d.stride_h != d.stride_w || d.pad_h != d.pad_w || d.pad_h < 0 || 2 * d.pad_h > d.kh)
+            { rc = fail(XENOS_EUNSUPPORTED, "op %d: pooling needs a square window, equal strides and pad <= k/2", i); break; }
+          if (s.h + 2 * d.pad_h < d.kh || s.w + 2 * d.pad_w < d.kw) { rc = fail(XENOS_ESHAPE, "op %d: pooling window larger than map", i); break; }
+          os = Shape{s.n, s.c, pool_out(s.h, d.kh, d.stride_h, d.pad_h, d.ceil_mode), pool_out(s.w, d.kw, d.stride_w, d.pad_w, d.ceil_mode)};
+          break;
+        case XENOS_OP_GLOBAL_AVGPOOL: os = Shape{s.n, s.c, 1, 1}; break;
+        case XENOS_OP_ADD: {
+          const Shape b = g->shapes[d.inputs[1]];
+          if (b.n != s.n || b.c != s.c || b.h != s.h || b.w != s.w) rc = fail(XENOS_ESHAPE, "op %d: add operands differ in shape", i);
+          break;
+        }
+        case XENOS_OP_CONCAT: {
+          int ct = 0;
+          for (int j = 0; j < d.n_inputs; ++j) {
+            const Shape b = g->shapes[d.inputs[j]];
+            if (b.n != s.n || b.h != s.h || b.w != s.w) rc = fail(XENOS_ESHAPE, "op %d: concat operands differ in N/H/W", i);
+            ct += b.c;
+          }
+          os.c = ct;
+          break;
+        }
+        default: rc = fail(XENOS_EINVAL, "op %d: unknown kind %d", i, (int)d.kind);
+      }
+      if (rc != XENOS_OK) break;
+      if (os.h <= 0 || os.w <= 0) { rc = fail(XENOS_ESHAPE, "op %d: empty output", i); break; }
+      g->shapes.push_back(os);
+      g->ops.push_back(std::move(o));
+    }
+  } catch (const std::bad_alloc&) {
+    rc = fail(XENOS_ENOMEM, "out of host memory");
+  }
+  if (rc != XENOS_OK) { delete g; return rc; }
+  const Shape os = g->shapes[output_tensor_id];
+  xenos_tensor_desc od{os.n, os.c, os.h, os.w, XENOS_F32, XENOS_NCHW};
+  if (output) {
+    if ((output->n && output->n != os.n) || (output->c && output->c != os.c) || (output->h && output->h != os.h) || (output->w && output->w != os.w)) {
+      delete g;
+      return fail(XENOS_ESHAPE, "output descriptor %dx%dx%dx%d does not match inferred %dx%dx%dx%d", output->n, output->c, output->h, output->w, os.n, os.c, os.h, os.w);
+    }
+    od.dtype = output->dtype; od.layout = output->layout;
+  }
+  g->out = od;
+  *out = g;
+  return XENOS_OK;
+}
+
+xenos_status xenos_plan_link_split(const xenos_graph* graph, const xenos_hw_info* hw, const xenos_plan_opts* opts, xenos_plan** out) {
+  if (!graph || !hw || !opts || !out || graph->magic != MAGIC_GRAPH) return fail(XENOS_EINVAL, "xenos_plan_link_split: bad argument");
+  if (opts->link < 0 || opts->link > 3 || opts->tile < 0 || opts->tile > kNumTileCfgs || (opts->compute != XENOS_F32 && opts->compute != XENOS_BF16))
+    return fail(XENOS_EINVAL, "xenos_plan_link_split: option out of range");
+  if (hw->num_cu <= 0 || hw->lds_bytes_per_cu == 0) return fail(XENOS_EINVAL, "xenos_plan_link_split: hardware description is empty");
+  if ((graph->in.dtype == XENOS_BF16 || graph->out.dtype == XENOS_BF16) && opts->compute != XENOS_BF16)
+    return fail(XENOS_EUNSUPPORTED, "bf16 graph input/output needs the bf16 compute type");
+  xenos_plan* p = new (std::nothrow) xenos_plan;
+  if (!p) return fail(XENOS_ENOMEM, "out of host memory");
+  p->opts = *opts; p->hw = *hw; p->in = graph->in; p->out = graph->out;
+  xenos_status rc;
+  try {
+    Planner pl(*graph, *p);
+    rc = pl.run();
+  } catch (const std::bad_alloc&) {
+    rc = fail(XENOS_ENOMEM, "out of host memory");
+  }
+  if (rc != XENOS_OK) { delete p; return rc; }
+  *out = p;
+  return XENOS_OK;
+}
+
+xenos_status xenos_plan_query(const xenos_plan* plan, size_t* weight_bytes, size_t* workspace_bytes, xenos_tensor_desc* out_desc,
+                              char* json, size_t json_cap, size_t* json_len) {
+  if (!plan || plan->magic != MAGIC_PLAN) return fail(XENOS_EINVAL, "xenos_plan_query: bad plan");
+  if (weight_bytes) *weight_bytes = std::max<size_t>(plan->wimage.size(), 256);
+  if (workspace_bytes) *workspace_bytes = plan->workspace_bytes;
+  if (out_desc) *out_desc = plan->out;
+  if (json_len) *json_len = plan->json.size() + 1;
+  if (json && json_cap) {
+    const size_t n = std::min(json_cap - 1, plan->json.size());
+    memcpy(json, plan->json.data(), n);
+    json[n] = 0;
+  }
+  return XENOS_OK;
+}
+
+xenos_status xenos_plan_bind(xenos_plan* plan, void* d_weights, void* d_workspace, void* hip_stream) {
+  if (!plan || plan->magic != MAGIC_PLAN || !d_weights || !d_workspace) return fail(XENOS_EINVAL, "xenos_plan_bind: bad argument");
+  if (((uintptr_t)d_weights | (uintptr_t)d_workspace) & 255) return fail(XENOS_EINVAL, "xenos_plan_bind: buffers must be 256-byte aligned");
+  hipStream_t st = (hipStream_t)hip_stream;
+  if (!plan->wimage.empty()) {
+    hipError_t e = hipMemcpyAsync(d_weights, plan->wimage.data(), plan->wimage.size(), hipMemcpyHostToDevice, st);
+    if (e != hipSuccess) return fail(XENOS_EDEVICE, "weight upload failed: %s", hipGetErrorString(e));
+  }
+  hipError_t e = hipStreamSynchronize(st);
+  if (e != hipSuccess) return fail(XENOS_EDEVICE, "stream synchronise failed: %s", hipGetErrorString(e));
+  plan->d_weights = d_weights;
+  plan->d_workspace = d_workspace;
+  plan->bound = true;
+  return XENOS_OK;
+}
+
+xenos_status xenos_run(xenos_plan* plan, const void* d_input, void* d_output, void* hip_stream) {
+  if (!plan || plan->magic != MAGIC_PLAN || !d_input || !d_output) return fail(XENOS_EINVAL, "xenos_run: bad argument");
+  if (!plan->bound) return fail(XENOS_EINVAL, "xenos_run: plan is not bound (call xenos_plan_bind)");
+  for (const Step& s : plan->steps) {
+    xenos_status rc = launch_step(*plan, s, d_input, d_output, hip_stream);
+    if (rc != XENOS_OK) return rc;
+  }
+  return XENOS_OK;
+}
+
+xenos_status xenos_run_chain(xenos_plan* plan, int chain, const void* d_input, void* d_output, void* hip_stream) {
+  if (!plan || plan->magic != MAGIC_PLAN || !d_input || !d_output) return fail(XENOS_EINVAL, "xenos_run_chain: bad argument");
+  if (!plan->bound) return fail(XENOS_EINVAL, "xenos_run_chain: plan is not bound");
+  if (chain < 0 || chain >= (int)plan->steps.size()) return fail(XENOS_EINVAL, "xenos_run_chain: chain %d out of range", chain);
+  return launch_step(*plan, plan->steps[chain], d_input, d_output, hip_stream);
+}
+
+void xenos_destroy(void* h) {
+  if (!h) return;
+  const uint32_t magic = *(const uint32_t*)h;
+  if (magic == MAGIC_GRAPH) { ((xenos_graph*)h)->magic = 0; delete (xenos_graph*)h; }
+  else if (magic == MAGIC_PLAN) { ((xenos_plan*)h)->magic = 0; delete (xenos_plan*)h; }
+}
+
+}  // extern "C"

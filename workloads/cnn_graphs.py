@@ -310,3 +310,8 @@ def conv_fc_flops(g: Graph) -> int:
             _, c, h, w = shp[op.inputs[0]]
             total += 2 * n * k * c * h * w
     return total
+
+
+def builder(name: str, input_shape, seed: int, nonzero_bias: bool = False) -> _Builder:
+    """A builder for ad-hoc graphs (unit chains in the tests); same draw rules as the five workloads."""
+    return _Builder(name, input_shape, seed, nonzero_bias)
