@@ -1,0 +1,191 @@
+#!/usr/bin/env python3
+"""Benchmark of the linked-operator-chain CNN path on one MI355X.
+
+One "step" = one forward pass of the whole planned chain sequence over one batch of synthetic input
+that is already resident in HBM.  Prints ONE JSON line.  The headline workload is config 3
+(VGG-16-style, batch 32, bf16 MFMA / fp32 accumulate, linked + split): the largest single-GPU
+configuration and the compute-bound regime in which the MFMA roofline is meaningful.  The same line
+carries the linked / U1 / U0 comparison for that workload and, unless --quick, images/s for the other
+configurations (batch 1 and 32).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+WORKLOADS = {
+    # name: (config, batch, compute)
+    "vgg16_n32_bf16": (3, 32, 1),
+    "resnet18_n32_bf16": (2, 32, 1),
+    "resnet18_n1_bf16": (2, 1, 1),
+    "mobilenet_n1_bf16": (1, 1, 1),
+    "mobilenet_n1_f32": (1, 1, 0),
+    "squeezenet_n1_bf16": (4, 1, 1),
+    "squeezenet_n1_f32": (4, 1, 0),
+    "squeezenet_n32_bf16": (4, 32, 1),
+    "squeezenet_n32_f32": (4, 32, 0),
+    "single_chain_n1_f32": (0, 1, 0),
+}
+PEAK = {1: 2500.0, 0: 157.3}          # dense MFMA TFLOP/s: bf16, fp32
+HBM_PEAK = 8000.0                     # GB/s
+LINK_NAMES = {2: "linked", 1: "U1", 0: "U0"}
+
+
+def time_steps(sess, torch, steps, warmup):
+    for _ in range(warmup):
+        sess.run()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    for _ in range(steps):
+        sess.run()
+    e1.record()
+    torch.cuda.synchronize()
+    wall = (time.perf_counter() - t0) * 1e3 / steps
+    return e0.elapsed_time(e1) / steps, wall
+
+
+def time_chains(sess, torch, steps):
+    """Per-chain launch durations (ms), HIP events around every launch on the launch stream."""
+    n = sess.info["n_chains"]
+    tot = np.zeros(n)
+    for _ in range(steps):
+        evs = [torch.cuda.Event(enable_timing=True) for _ in range(n + 1)]
+        evs[0].record()
+        for i in range(n):
+            sess.run_chain(i)
+            evs[i + 1].record()
+        torch.cuda.synchronize()
+        tot += np.array([evs[i].elapsed_time(evs[i + 1]) for i in range(n)])
+    return tot / steps
+
+
+def run_workload(name, steps, warmup, links=(2,), chains=False, wg=None, X=None, torch=None, graph=None):
+    cfg, batch, compute = WORKLOADS[name]
+    g = graph if graph is not None else wg.build(cfg, batch)
+    out = {"workload": name, "config": cfg, "batch": batch, "dtype": "bf16" if compute else "f32",
+           "gflop": wg.conv_fc_flops(g) / 1e9}
+    for link in links:
+        s = X.Session(g, link=link, split=1, compute=compute)
+        s.set_input(g.x)
+        ms, wall = time_steps(s, torch, steps, warmup)
+        rec = {"ms_per_step": ms, "wall_ms_per_step": wall, "images_per_s": batch / ms * 1e3,
+               "tflops": out["gflop"] / ms, "n_chains": s.info["n_chains"],
+               "algorithmic_hbm_mb": s.info["hbm_bytes"] / 1e6,
+               "algorithmic_gb_per_s": s.info["hbm_bytes"] / ms / 1e6}
+        if chains and link == 2:
+            cms = time_chains(s, torch, max(3, steps // 2))
+            rec["chains"] = [dict(i=c["i"], name=c["name"], kind=c["kind"], ms=float(cms[c["i"]]), gflop=c["flops"] / 1e9,
+                                  mb=(c["bytes_in"] + c["bytes_w"] + c["bytes_out"] + c["bytes_res"]) / 1e6,
+                                  mode=c.get("mode"), tile=[c.get("bm"), c.get("bn")] if c["kind"] == "conv" else None,
+                                  loader=c.get("loader"))
+                             for c in s.info["chains"]]
+        out[LINK_NAMES[link]] = rec
+        s.close()
+        del s
+        torch.cuda.empty_cache()
+    return out, g
+
+
+def cpu_baseline(g, images):
+    """The fp64 oracle as it stands, on `images` images of the same workload, host cores of this machine."""
+    from oracle import xenos_oracle as xo
+    x = g.x[:images]
+    t0 = time.perf_counter()
+    xo.forward(g, x)
+    dt = time.perf_counter() - t0
+    return {"value": images / dt, "unit": "images/s", "cores": xo.threads(), "kind": "oracle",
+            "sample": f"{images} of the {g.input_shape[0]} images of the headline batch, full network, fp64, {dt:.1f} s"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="vgg16_n32_bf16", choices=sorted(WORKLOADS))
+    ap.add_argument("--quick", action="store_true", help="headline workload, linked mode only, no CPU baseline")
+    ap.add_argument("--cpu-images", type=int, default=2)
+    ap.add_argument("--detail", default="", help="write the full per-chain report (JSON) to this file")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (no collectives, no sharding); --gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2302_00282_amd import xenos as X
+    from workloads import cnn_graphs as wg
+    X.lib()     # fails loudly if the HIP library has not been built
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    torch.cuda.set_device(0)
+
+    name = args.workload
+    cfg, batch, compute = WORKLOADS[name]
+    links = (2,) if args.quick else (2, 1, 0)
+    head, g = run_workload(name, args.steps, args.warmup, links, chains=True, wg=wg, X=X, torch=torch)
+    lk = head["linked"]
+
+    # roofline of the dominant kernel: all launches of the dense-conv MFMA kernel in one step
+    conv = [c for c in lk["chains"] if c["kind"] == "conv"]
+    conv_ms = sum(c["ms"] for c in conv)
+    conv_gflop = sum(c["gflop"] for c in conv)
+    compute_bound = [c for c in conv if c["gflop"] / max(c["mb"], 1e-9) * 1e3 > PEAK[compute] * 1e3 / HBM_PEAK]
+    roof = {"bound": "mfma", "kernel": "conv_kernel (implicit-GEMM MFMA, all %d launches of one step)" % len(conv),
+            "achieved": conv_gflop / conv_ms, "peak": PEAK[compute], "unit": "TFLOP/s",
+            "frac": conv_gflop / conv_ms / PEAK[compute], "traffic": None,
+            "avg_launch_ms": conv_ms / len(conv), "flops_per_launch": conv_gflop * 1e9 / len(conv),
+            "share_of_step": conv_ms / sum(c["ms"] for c in lk["chains"])}
+    if compute_bound:
+        cb_ms = sum(c["ms"] for c in compute_bound)
+        cb_gf = sum(c["gflop"] for c in compute_bound)
+        roof["compute_bound_layers"] = {"n": len(compute_bound), "achieved": cb_gf / cb_ms, "frac": cb_gf / cb_ms / PEAK[compute]}
+
+    line = {
+        "metric": "images/sec + % MFMA/HBM roofline, linked vs unlinked, batch 1 and 32",
+        "value": lk["images_per_s"], "unit": "images/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": lk["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": head["dtype"], "data": "synthetic",
+        "config": {"workload": f"config {cfg}: {g.name}-style, batch {batch}, {head['dtype']}, linked+split, "
+                               f"synthetic seeded weights and input", "batch": batch, "mode": "linked+split",
+                   "gflop_per_step": head["gflop"]},
+        "tflops": lk["tflops"],
+        "roofline": roof,
+        "linked_vs_unlinked": {k: {"images_per_s": head[k]["images_per_s"], "ms_per_step": head[k]["ms_per_step"],
+                                   "n_chains": head[k]["n_chains"], "algorithmic_hbm_mb": head[k]["algorithmic_hbm_mb"]}
+                               for k in ("linked", "U1", "U0") if k in head},
+    }
+    detail = {"headline": head}
+    if not args.quick:
+        line["cpu_baseline"] = cpu_baseline(g, min(args.cpu_images, batch))
+        del g
+        others = []
+        for other in WORKLOADS:
+            if other == name:
+                continue
+            r, _ = run_workload(other, args.steps, args.warmup, (2, 1, 0), chains=True, wg=wg, X=X, torch=torch)
+            detail[other] = r
+            others.append({"workload": other, "gflop": r["gflop"],
+                           **{k: round(r[k]["images_per_s"], 1) for k in ("linked", "U1", "U0")},
+                           "linked_tflops": round(r["linked"]["tflops"], 2),
+                           "linked_algorithmic_gb_per_s": round(r["linked"]["algorithmic_gb_per_s"], 1)})
+        line["other_workloads_images_per_s"] = others
+    if args.detail:
+        os.makedirs(os.path.dirname(os.path.abspath(args.detail)), exist_ok=True)
+        with open(args.detail, "w") as f:
+            json.dump(detail, f, indent=1)
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

@@ -51,6 +51,7 @@ struct ConvArgs {
   int patch_h, patch_w, pph, ppw, patches_y, patches_x;   // M_PATCH geometry (conv-output patch, pooled patch)
   long long out_sN, out_sP, out_sK;    // output strides (image, pixel, channel) in elements
   int out_f32;           // store fp32 instead of the compute type (graph output)
+  int vec_out, vec_res;  // 16-byte channel-group stores / shortcut loads are legal (alignment, unit channel stride, K % group == 0)
   int M_total;           // rows enumerated over the whole problem (FLAT, ZIGZAG); per-image rows for GAP
   int tiles_m, tiles_n, ntiles;
   int grid;              // workgroups launched (>= 1); tiles are visited with a stride of `grid`
@@ -100,5 +101,6 @@ int launch_elt(const EltArgs& a, int dtype, void* stream);
 int launch_pool(const PoolArgs& a, int dtype, void* stream);
 int launch_cvt(const CvtArgs& a, int dtype, void* stream);
 size_t conv_lds_bytes(int cfg, int mode);
+bool conv_cfg_has_scalar_loader(int cfg);
 
 }  // namespace xenos

@@ -76,22 +76,25 @@ constexpr int NUM_XCD = 8;
 
 __host__ __device__ constexpr int cmax(int a, int b) { return a > b ? a : b; }
 
-template <int BM, int BN>
-__host__ __device__ constexpr int lds_main_bytes() { return 2 * (BM + BN) * LDS_ROW; }
-template <int BM, int BN>
-__host__ __device__ constexpr int lds_patch_bytes() { return BM * (BN + 1) * 4; }
 
 // ---------------------------------------------------------------------------------------------
 // Dense convolution chain
 // ---------------------------------------------------------------------------------------------
-template <typename T, int BM, int BN, int WM, int WN, bool SCALAR>
-__global__ __launch_bounds__(NT) void conv_kernel(const ConvArgs a) {
+constexpr int STG_PAD = 4;       // staging row pitch = BN + 4 floats (keeps 16-byte alignment of channel groups)
+
+template <int BM, int BN>
+__host__ __device__ constexpr int lds_conv_bytes() { return cmax(2 * (BM + BN) * LDS_ROW, BM * (BN + STG_PAD) * 4); }
+
+template <typename T, int BM, int BN, int WM, int WN, bool SCALAR, int MODE>
+__global__ __launch_bounds__(NT, 2) void conv_kernel(const ConvArgs a) {
   using tr = Tr<T>;
   constexpr int CE = tr::CE, BKE = tr::BKE;
   constexpr int WAVES_N = BN / WN;
   constexpr int TM = WM / 32, TN = WN / 32;
   constexpr int A_CH = BM * 4, B_CH = BN * 4;                      // 16-byte chunks per step
   constexpr int A_IT = (A_CH + NT - 1) / NT, B_IT = (B_CH + NT - 1) / NT;
+  constexpr int SP = BN + STG_PAD;                                 // staging pitch in floats
+  constexpr int CG = BN / CE;                                      // channel groups (16-byte stores) per row
   static_assert((BM / WM) * WAVES_N == 4, "four wavefronts per workgroup");
 
   extern __shared__ __align__(16) unsigned char smem[];
@@ -113,42 +116,40 @@ __global__ __launch_bounds__(NT) void conv_kernel(const ConvArgs a) {
 
     // patch / gap geometry of this tile
     int img = 0, oy0 = 0, ox0 = 0, py = 0, px = 0;
-    if (a.mode == M_PATCH) {
+    if (MODE == M_PATCH) {
       const int pper = a.patches_y * a.patches_x;
       img = tile_m / pper;
       const int pr = tile_m % pper;
       py = pr / a.patches_x; px = pr % a.patches_x;
       oy0 = py * a.pph * a.ps - a.pp;
       ox0 = px * a.ppw * a.ps - a.pp;
-    } else if (a.mode == M_GAP) {
+    } else if (MODE == M_GAP) {
       img = tile_m;
     }
-    const int nchunks = (a.mode == M_GAP) ? (OHW + BM - 1) / BM : 1;
-    float colsum[TN];
-#pragma unroll
-    for (int j = 0; j < TN; ++j) colsum[j] = 0.f;
+    const int nchunks = (MODE == M_GAP) ? (OHW + BM - 1) / BM : 1;
+    float gsum = 0.f;                                              // M_GAP: this thread's column partial sum
 
     for (int mc = 0; mc < nchunks; ++mc) {
       // ---- decode the rows this thread loads ---------------------------------------------------
       int ih0[A_IT], iw0[A_IT];
-      long long nbase[A_IT];
+      long long rbase[A_IT];
       const int ch = tid & 3;
 #pragma unroll
       for (int it = 0; it < A_IT; ++it) {
         const int row = (tid + it * NT) >> 2;
         int n = 0, oh = 0, ow = 0;
         bool ok = row < BM;
-        if (a.mode == M_FLAT) {
+        if (MODE == M_FLAT) {
           const int m = tile_m * BM + row;
           ok = ok && m < a.M_total;
           n = m / OHW; const int p = m - n * OHW; oh = p / a.OW; ow = p - oh * a.OW;
-        } else if (a.mode == M_ZIGZAG) {
+        } else if (MODE == M_ZIGZAG) {
           const int m = tile_m * BM + row;
           ok = ok && m < a.M_total;
           const int wdx = m >> 2, j = m & 3, pw_ = a.PH * a.PW;
           n = wdx / pw_; const int q = wdx - n * pw_; const int ph = q / a.PW;
           oh = 2 * ph + (j >> 1); ow = 2 * (q - ph * a.PW) + (j & 1);
-        } else if (a.mode == M_PATCH) {
+        } else if (MODE == M_PATCH) {
           const int cy = row / a.patch_w, cx = row - cy * a.patch_w;
           n = img; oh = oy0 + cy; ow = ox0 + cx;
           ok = ok && cy < a.patch_h && oh >= 0 && oh < a.OH && ow >= 0 && ow < a.OW;
@@ -159,7 +160,8 @@ __global__ __launch_bounds__(NT) void conv_kernel(const ConvArgs a) {
         }
         ih0[it] = ok ? oh * a.stride - a.pad : -(1 << 28);
         iw0[it] = ow * a.stride - a.pad;
-        nbase[it] = (long long)n * a.in_sN;
+        // element offset of input pixel (ih0, iw0); only ever dereferenced together with an in-range tap
+        rbase[it] = ok ? (long long)n * a.in_sN + (long long)ih0[it] * a.in_sH + (long long)iw0[it] * a.in_sW : 0;
       }
       // reduction position (r, s, c) of this thread's 16-byte chunk
       int kc, kr, ks;
@@ -183,20 +185,20 @@ __global__ __launch_bounds__(NT) void conv_kernel(const ConvArgs a) {
 #pragma unroll
           for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-      u32x4_t ra[A_IT], rb[B_IT];
+      // Two register sets: the loads of step i+2 are issued while step i computes and are written to LDS
+      // at the end of step i+1, so a global access has two steps of MFMA work to hide behind.
+      u32x4_t ra0[A_IT], rb0[B_IT], ra1[A_IT], rb1[B_IT];
 
-      auto load_global = [&](int step) {
+      auto load_global = [&](int step, u32x4_t* ra, u32x4_t* rb) {
         if constexpr (!SCALAR) {
           const bool kok = kr < a.R;
+          const long long koff = (long long)kr * a.in_sH + (long long)ks * a.in_sW + kc;
 #pragma unroll
           for (int it = 0; it < A_IT; ++it) {
             const int ih = ih0[it] + kr, iw = iw0[it] + ks;
             const bool ok = kok && (unsigned)ih < (unsigned)a.H && (unsigned)iw < (unsigned)a.W;
             u32x4_t v = {0u, 0u, 0u, 0u};
-            if (ok) {
-              const T* p = (const T*)a.in + nbase[it] + (long long)ih * a.in_sH + (long long)iw * a.in_sW + kc;
-              v = *(const u32x4_t*)p;
-            }
+            if (ok) v = *(const u32x4_t*)((const T*)a.in + rbase[it] + koff);
             ra[it] = v;
           }
           kc += BKE;
@@ -213,10 +215,7 @@ __global__ __launch_bounds__(NT) void conv_kernel(const ConvArgs a) {
               const int ih = ih0[it] + r, iw = iw0[it] + s;
               const bool ok = (unsigned)ih < (unsigned)a.H && (unsigned)iw < (unsigned)a.W;
               float v = 0.f;
-              if (ok) {
-                const long long idx = nbase[it] + (long long)ih0[it] * a.in_sH + (long long)iw0[it] * a.in_sW + off;
-                v = a.in_f32 ? ((const float*)a.in)[idx] : tr::ld(a.in, idx);
-              }
+              if (ok) v = a.in_f32 ? ((const float*)a.in)[rbase[it] + off] : tr::ld(a.in, rbase[it] + off);
               f[it][e] = v;
             }
           }
@@ -226,7 +225,7 @@ __global__ __launch_bounds__(NT) void conv_kernel(const ConvArgs a) {
 #pragma unroll
         for (int it = 0; it < B_IT; ++it) rb[it] = *(const u32x4_t*)(wrow[it] + (long long)step * ROWB);
       };
-      auto store_lds = [&](int stage) {
+      auto store_lds = [&](int stage, const u32x4_t* ra, const u32x4_t* rb) {
         unsigned char* sa = smem + stage * (BM + BN) * LDS_ROW;
         unsigned char* sb = sa + BM * LDS_ROW;
 #pragma unroll
@@ -240,14 +239,8 @@ __global__ __launch_bounds__(NT) void conv_kernel(const ConvArgs a) {
           if (B_CH % NT == 0 || idx < B_CH) *(u32x4_t*)(sb + (idx >> 2) * LDS_ROW + (idx & 3) * 16) = rb[it];
         }
       };
-
-      load_global(0);
-      store_lds(0);
-      __syncthreads();
-      for (int step = 0; step < nsteps; ++step) {
-        const bool more = step + 1 < nsteps;
-        if (more) load_global(step + 1);
-        const unsigned char* sa = smem + (step & 1) * (BM + BN) * LDS_ROW;
+      auto compute = [&](int stage) {
+        const unsigned char* sa = smem + stage * (BM + BN) * LDS_ROW;
         const unsigned char* sb = sa + BM * LDS_ROW;
 #pragma unroll
         for (int kg = 0; kg < 2; ++kg) {
@@ -273,172 +266,226 @@ __global__ __launch_bounds__(NT) void conv_kernel(const ConvArgs a) {
               }
             }
         }
-        if (more) store_lds((step + 1) & 1);
+      };
+
+      load_global(0, ra0, rb0);
+      store_lds(0, ra0, rb0);
+      if (nsteps > 1) load_global(1, ra1, rb1);
+      __syncthreads();
+      for (int step = 0; step < nsteps; step += 2) {
+        // even step: compute stage 0, prefetch step+2 into set 0, publish set 1 (step+1) to stage 1
+        if (step + 2 < nsteps) load_global(step + 2, ra0, rb0);
+        compute(0);
+        if (step + 1 < nsteps) store_lds(1, ra1, rb1);
+        __syncthreads();
+        if (step + 1 >= nsteps) break;
+        // odd step
+        if (step + 3 < nsteps) load_global(step + 3, ra1, rb1);
+        compute(1);
+        if (step + 2 < nsteps) store_lds(0, ra0, rb0);
         __syncthreads();
       }
 
       // ---- epilogue: the rest of the linked chain ------------------------------------------------
+      // Phase 1: raw accumulators to LDS (aliases the operand stages; the loop above ended with a barrier).
       // Accumulator element e of lane l in a 32x32 tile: row = (e/4)*8 + (l/32)*4 + e%4, column = l%32.
-      if (a.mode == M_FLAT) {
+      float* stg = (float*)smem;
 #pragma unroll
-        for (int i = 0; i < TM; ++i)
-#pragma unroll
-          for (int e = 0; e < 16; ++e) {
-            const int m = tile_m * BM + wave_m * WM + i * 32 + (e >> 2) * 8 + lhalf * 4 + (e & 3);
-            if (m >= a.M_total) continue;
-            const int n = m / OHW, p = m - n * OHW;
-            const long long obase = (long long)n * a.out_sN + (long long)p * a.out_sP;
-            const long long rbase = (long long)n * a.res_sN + (long long)p * a.res_sP;
-#pragma unroll
-            for (int j = 0; j < TN; ++j) {
-              const int k = tile_n * BN + wave_n * WN + j * 32 + l31;
-              if (k >= a.K) continue;
-              float v = acc[i][j][e] * a.scale[k] + a.shift[k];
-              if (a.has_res) v += tr::ld(a.res, rbase + k);
-              if (a.relu) v = fmaxf(v, 0.f);
-              const long long o = obase + (long long)k * a.out_sK;
-              if (a.out_f32) ((float*)a.out)[o] = v; else tr::st(a.out, o, v);
-            }
-          }
-      } else if (a.mode == M_ZIGZAG) {
-        const int PHW = a.PH * a.PW, nwin = a.M_total >> 2;
-#pragma unroll
-        for (int i = 0; i < TM; ++i)
-#pragma unroll
-          for (int g = 0; g < 4; ++g) {
-            const int wdx = ((tile_m * BM + wave_m * WM + i * 32) >> 2) + g * 2 + lhalf;
-            if (wdx >= nwin) continue;
-            const int n = wdx / PHW, q = wdx - n * PHW;
-            const long long obase = (long long)n * a.out_sN + (long long)q * a.out_sP;
-#pragma unroll
-            for (int j = 0; j < TN; ++j) {
-              const int k = tile_n * BN + wave_n * WN + j * 32 + l31;
-              if (k >= a.K) continue;
-              const float sc = a.scale[k], sh = a.shift[k];
-              float r = 0.f;
-#pragma unroll
-              for (int e = 0; e < 4; ++e) {
-                float v = acc[i][j][g * 4 + e] * sc + sh;
-                if (a.relu) v = fmaxf(v, 0.f);
-                if (a.pool == POOL_MAX) r = (e == 0) ? v : fmaxf(r, v); else r += v;
-              }
-              if (a.pool == POOL_AVG) r *= 0.25f;
-              const long long o = obase + (long long)k * a.out_sK;
-              if (a.out_f32) ((float*)a.out)[o] = r; else tr::st(a.out, o, r);
-            }
-          }
-      } else if (a.mode == M_PATCH) {
-        float* stg = (float*)smem;                                 // [BM][BN+1], aliases the operand stages
-#pragma unroll
-        for (int i = 0; i < TM; ++i)
-#pragma unroll
-          for (int j = 0; j < TN; ++j) {
-            const int col = wave_n * WN + j * 32 + l31;
-            const int k = tile_n * BN + col;
-            const float sc = a.scale[k], sh = a.shift[k];           // arrays are padded to the tile
-#pragma unroll
-            for (int e = 0; e < 16; ++e) {
-              const int row = wave_m * WM + i * 32 + (e >> 2) * 8 + lhalf * 4 + (e & 3);
-              float v = acc[i][j][e] * sc + sh;
-              if (a.relu) v = fmaxf(v, 0.f);
-              stg[row * (BN + 1) + col] = v;
-            }
-          }
-        __syncthreads();
-        const int nq = a.pph * a.ppw;
-        for (int idx = tid; idx < nq * BN; idx += NT) {
-          const int col = idx % BN, q = idx / BN;
-          const int k = tile_n * BN + col;
-          const int qy = q / a.ppw, qx = q - qy * a.ppw;
-          const int gy = py * a.pph + qy, gx = px * a.ppw + qx;
-          if (k >= a.K || gy >= a.PH || gx >= a.PW) continue;
-          float mx = -INFINITY, sum = 0.f;
-          int cnt = 0, cntp = 0;
-          for (int r = 0; r < a.pk; ++r)
-            for (int s = 0; s < a.pk; ++s) {
-              const int cy = qy * a.ps + r, cx = qx * a.ps + s;
-              const int oh = oy0 + cy, ow = ox0 + cx;
-              if (oh < a.OH + a.pp && ow < a.OW + a.pp) ++cntp;
-              if (oh < 0 || oh >= a.OH || ow < 0 || ow >= a.OW) continue;
-              const float v = stg[(cy * a.patch_w + cx) * (BN + 1) + col];
-              mx = fmaxf(mx, v); sum += v; ++cnt;
-            }
-          const float r = (a.pool == POOL_MAX) ? mx : sum / (float)(a.cip ? cntp : cnt);
-          const long long o = (long long)img * a.out_sN + (long long)(gy * a.PW + gx) * a.out_sP + (long long)k * a.out_sK;
-          if (a.out_f32) ((float*)a.out)[o] = r; else tr::st(a.out, o, r);
-        }
-        __syncthreads();
-      } else {  // M_GAP: accumulate the column sums of this chunk
+      for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
-          const int k = tile_n * BN + wave_n * WN + j * 32 + l31;
-          const float sc = a.scale[k], sh = a.shift[k];
+          const int col = wave_n * WN + j * 32 + l31;
 #pragma unroll
-          for (int i = 0; i < TM; ++i)
+          for (int e = 0; e < 16; ++e) {
+            const int row = wave_m * WM + i * 32 + (e >> 2) * 8 + lhalf * 4 + (e & 3);
+            stg[row * SP + col] = acc[i][j][e];
+          }
+        }
+      __syncthreads();
+
+      // Phase 2: each thread finishes CE consecutive channels of one output element: scale/shift, shortcut,
+      // ReLU, pooling over the rows of its window, then one 16-byte store into the consumer's buffer.
+      if (MODE != M_GAP) {
+        const int nq = MODE == M_FLAT ? BM : MODE == M_ZIGZAG ? BM / 4 : a.pph * a.ppw;
+        for (int idx = tid; idx < nq * CG; idx += NT) {
+          const int cg = idx % CG, q = idx / CG;
+          const int col0 = cg * CE, k0 = tile_n * BN + col0;
+          if (k0 >= a.K) continue;
+          long long obase, rb_ = 0;
+          float v[CE];
+          float sc[CE], sh[CE];
+          *(f32x4_t*)&sc[0] = *(const f32x4_t*)(a.scale + k0);
+          *(f32x4_t*)&sh[0] = *(const f32x4_t*)(a.shift + k0);
+          if (CE == 8) {
+            *(f32x4_t*)&sc[4] = *(const f32x4_t*)(a.scale + k0 + 4);
+            *(f32x4_t*)&sh[4] = *(const f32x4_t*)(a.shift + k0 + 4);
+          }
+          if (MODE == M_FLAT) {
+            const int m = tile_m * BM + q;
+            if (m >= a.M_total) continue;
+            const int n = m / OHW, p = m - n * OHW;
+            obase = (long long)n * a.out_sN + (long long)p * a.out_sP;
+            rb_ = (long long)n * a.res_sN + (long long)p * a.res_sP;
+            const float* sp = stg + q * SP + col0;
 #pragma unroll
-            for (int e = 0; e < 16; ++e) {
-              const int p = mc * BM + wave_m * WM + i * 32 + (e >> 2) * 8 + lhalf * 4 + (e & 3);
-              float v = acc[i][j][e] * sc + sh;
-              if (a.relu) v = fmaxf(v, 0.f);
-              if (p < OHW) colsum[j] += v;
+            for (int e = 0; e < CE; e += 4) *(f32x4_t*)&v[e] = *(const f32x4_t*)(sp + e);
+#pragma unroll
+            for (int e = 0; e < CE; ++e) v[e] = v[e] * sc[e] + sh[e];
+            if (a.has_res) {
+              if (a.vec_res) {
+                float r[CE];
+                tr::unpack(*(const u32x4_t*)((const T*)a.res + rb_ + k0), r);
+#pragma unroll
+                for (int e = 0; e < CE; ++e) v[e] += r[e];
+              } else {
+#pragma unroll
+                for (int e = 0; e < CE; ++e) if (k0 + e < a.K) v[e] += tr::ld(a.res, rb_ + k0 + e);
+              }
             }
+            if (a.relu) {
+#pragma unroll
+              for (int e = 0; e < CE; ++e) v[e] = fmaxf(v[e], 0.f);
+            }
+          } else if (MODE == M_ZIGZAG) {
+            const int wdx = ((tile_m * BM) >> 2) + q;
+            if (wdx >= (a.M_total >> 2)) continue;
+            const int PHW = a.PH * a.PW;
+            const int n = wdx / PHW, pq = wdx - n * PHW;
+            obase = (long long)n * a.out_sN + (long long)pq * a.out_sP;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+              float u[CE];
+              const float* sp = stg + (4 * q + j) * SP + col0;
+#pragma unroll
+              for (int e = 0; e < CE; e += 4) *(f32x4_t*)&u[e] = *(const f32x4_t*)(sp + e);
+#pragma unroll
+              for (int e = 0; e < CE; ++e) {
+                float x = u[e] * sc[e] + sh[e];
+                if (a.relu) x = fmaxf(x, 0.f);
+                v[e] = j == 0 ? x : (a.pool == POOL_MAX ? fmaxf(v[e], x) : v[e] + x);
+              }
+            }
+            if (a.pool == POOL_AVG) {
+#pragma unroll
+              for (int e = 0; e < CE; ++e) v[e] *= 0.25f;
+            }
+          } else {  // M_PATCH
+            const int qy = q / a.ppw, qx = q - qy * a.ppw;
+            const int gy = py * a.pph + qy, gx = px * a.ppw + qx;
+            if (gy >= a.PH || gx >= a.PW) continue;
+            obase = (long long)img * a.out_sN + (long long)(gy * a.PW + gx) * a.out_sP;
+            float mx[CE], sum[CE];
+#pragma unroll
+            for (int e = 0; e < CE; ++e) { mx[e] = -INFINITY; sum[e] = 0.f; }
+            int cnt = 0, cntp = 0;
+            for (int r = 0; r < a.pk; ++r)
+              for (int s = 0; s < a.pk; ++s) {
+                const int cy = qy * a.ps + r, cx = qx * a.ps + s;
+                const int oh = oy0 + cy, ow = ox0 + cx;
+                if (oh < a.OH + a.pp && ow < a.OW + a.pp) ++cntp;
+                if (oh < 0 || oh >= a.OH || ow < 0 || ow >= a.OW) continue;
+                float u[CE];
+                const float* sp = stg + (cy * a.patch_w + cx) * SP + col0;
+#pragma unroll
+                for (int e = 0; e < CE; e += 4) *(f32x4_t*)&u[e] = *(const f32x4_t*)(sp + e);
+#pragma unroll
+                for (int e = 0; e < CE; ++e) {
+                  float x = u[e] * sc[e] + sh[e];
+                  if (a.relu) x = fmaxf(x, 0.f);
+                  mx[e] = fmaxf(mx[e], x); sum[e] += x;
+                }
+                ++cnt;
+              }
+            const float inv = 1.f / (float)(a.cip ? cntp : cnt);
+#pragma unroll
+            for (int e = 0; e < CE; ++e) v[e] = a.pool == POOL_MAX ? mx[e] : sum[e] * inv;
+          }
+          if (a.vec_out) {
+            *(u32x4_t*)((T*)a.out + obase + k0) = tr::pack(v);
+          } else {
+#pragma unroll
+            for (int e = 0; e < CE; ++e) {
+              if (k0 + e >= a.K) continue;
+              const long long o = obase + (long long)(k0 + e) * a.out_sK;
+              if (a.out_f32) ((float*)a.out)[o] = v[e]; else tr::st(a.out, o, v[e]);
+            }
+          }
+        }
+      } else {
+        // global average: thread (part, col) adds the rows part, part + NT/BN, ... of its column, in row order
+        const int col = tid % BN, part = tid / BN;
+        const int k = tile_n * BN + col;
+        const float sc = a.scale[k], sh = a.shift[k];
+        for (int row = part; row < BM; row += NT / BN) {
+          if (mc * BM + row >= OHW) break;
+          float x = stg[row * SP + col] * sc + sh;
+          if (a.relu) x = fmaxf(x, 0.f);
+          gsum += x;
         }
       }
+      __syncthreads();                                             // staging is reused as operand stage 0
     }  // chunks
 
-    if (a.mode == M_GAP) {
-      // fixed-order reduction: lane pair, then wavefronts along m through LDS
-      float* red = (float*)smem;                                   // [BM/WM][BN]
-#pragma unroll
-      for (int j = 0; j < TN; ++j) {
-        const float other = __shfl_xor(colsum[j], 32);
-        const float s = lhalf ? other + colsum[j] : colsum[j] + other;   // same operand order on both lanes
-        if (lhalf == 0) red[wave_m * BN + wave_n * WN + j * 32 + l31] = s;
-      }
+    if (MODE == M_GAP) {
+      float* red = (float*)smem;                                   // [NT/BN][BN], fixed-order final sum
+      red[tid] = gsum;                                             // tid == part * BN + col
       __syncthreads();
-      for (int col = tid; col < BN; col += NT) {
-        const int k = tile_n * BN + col;
-        if (k >= a.K) continue;
-        float s = 0.f;
-        for (int wm = 0; wm < BM / WM; ++wm) s += red[wm * BN + col];
-        s /= (float)OHW;
-        const long long o = (long long)img * a.out_sN + (long long)k * a.out_sK;
-        if (a.out_f32) ((float*)a.out)[o] = s; else tr::st(a.out, o, s);
+      if (tid < BN) {
+        const int k = tile_n * BN + tid;
+        if (k < a.K) {
+          float s = 0.f;
+          for (int part = 0; part < NT / BN; ++part) s += red[part * BN + tid];
+          s /= (float)OHW;
+          const long long o = (long long)img * a.out_sN + (long long)k * a.out_sK;
+          if (a.out_f32) ((float*)a.out)[o] = s; else tr::st(a.out, o, s);
+        }
       }
       __syncthreads();
     }
   }
 }
 
-template <typename T, int BM, int BN, int WM, int WN>
-static int launch_conv_cfg(const ConvArgs& a, int scalar, hipStream_t st) {
-  const int lds = (a.mode == M_PATCH) ? cmax(lds_main_bytes<BM, BN>(), lds_patch_bytes<BM, BN>()) : lds_main_bytes<BM, BN>();
-  constexpr int lds_max = cmax(lds_main_bytes<BM, BN>(), lds_patch_bytes<BM, BN>());
-  if (lds_max > 64 * 1024) {   // more than the default dynamic-LDS limit: raise it once per instantiation
-    static bool raised[2] = {false, false};
-    if (!raised[scalar ? 1 : 0]) {
-      hipError_t e = scalar ? hipFuncSetAttribute((const void*)conv_kernel<T, BM, BN, WM, WN, true>,
-                                                  hipFuncAttributeMaxDynamicSharedMemorySize, lds_max)
-                            : hipFuncSetAttribute((const void*)conv_kernel<T, BM, BN, WM, WN, false>,
-                                                  hipFuncAttributeMaxDynamicSharedMemorySize, lds_max);
+template <typename T, int BM, int BN, int WM, int WN, bool SCALAR, int MODE>
+static int launch_conv_inst(const ConvArgs& a, hipStream_t st) {
+  constexpr int lds = lds_conv_bytes<BM, BN>();
+  if (lds > 64 * 1024) {   // more than the default dynamic-LDS limit: raise it once per instantiation
+    static bool raised = false;
+    if (!raised) {
+      hipError_t e = hipFuncSetAttribute((const void*)conv_kernel<T, BM, BN, WM, WN, SCALAR, MODE>,
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, lds);
       if (e != hipSuccess) return (int)e;
-      raised[scalar ? 1 : 0] = true;
+      raised = true;
     }
   }
-  if (scalar)
-    hipLaunchKernelGGL((conv_kernel<T, BM, BN, WM, WN, true>), dim3(a.grid), dim3(NT), lds, st, a);
-  else
-    hipLaunchKernelGGL((conv_kernel<T, BM, BN, WM, WN, false>), dim3(a.grid), dim3(NT), lds, st, a);
+  hipLaunchKernelGGL((conv_kernel<T, BM, BN, WM, WN, SCALAR, MODE>), dim3(a.grid), dim3(NT), lds, st, a);
   return (int)hipGetLastError();
+}
+
+template <typename T, int BM, int BN, int WM, int WN, bool SCALAR>
+static int launch_conv_mode(const ConvArgs& a, hipStream_t st) {
+  switch (a.mode) {
+    case M_FLAT: return launch_conv_inst<T, BM, BN, WM, WN, SCALAR, M_FLAT>(a, st);
+    case M_ZIGZAG: return launch_conv_inst<T, BM, BN, WM, WN, SCALAR, M_ZIGZAG>(a, st);
+    case M_PATCH: return launch_conv_inst<T, BM, BN, WM, WN, SCALAR, M_PATCH>(a, st);
+    case M_GAP: return launch_conv_inst<T, BM, BN, WM, WN, SCALAR, M_GAP>(a, st);
+  }
+  return (int)hipErrorInvalidValue;
 }
 
 template <typename T>
 static int launch_conv_t(const ConvArgs& a, int cfg, int scalar, hipStream_t st) {
+  if (scalar) {   // the element-wise gather loader (first layers) exists for the two mid-size tiles only
+    switch (cfg) {
+      case 1: return launch_conv_mode<T, 128, 64, 64, 32, true>(a, st);
+      case 2: return launch_conv_mode<T, 64, 64, 32, 32, true>(a, st);
+    }
+    return (int)hipErrorInvalidValue;
+  }
   switch (cfg) {
-    case 0: return launch_conv_cfg<T, 128, 128, 64, 64>(a, scalar, st);
-    case 1: return launch_conv_cfg<T, 128, 64, 64, 32>(a, scalar, st);
-    case 2: return launch_conv_cfg<T, 64, 64, 32, 32>(a, scalar, st);
-    case 3: return launch_conv_cfg<T, 32, 128, 32, 32>(a, scalar, st);
+    case 0: return launch_conv_mode<T, 128, 128, 64, 64, false>(a, st);
+    case 1: return launch_conv_mode<T, 128, 64, 64, 32, false>(a, st);
+    case 2: return launch_conv_mode<T, 64, 64, 32, 32, false>(a, st);
+    case 3: return launch_conv_mode<T, 32, 128, 32, 32, false>(a, st);
   }
   return (int)hipErrorInvalidValue;
 }
@@ -448,12 +495,14 @@ int launch_conv(const ConvArgs& a, int dtype, int cfg, int scalar_loader, void* 
   return dtype == DT_BF16 ? launch_conv_t<bf16_t>(a, cfg, scalar_loader, st) : launch_conv_t<float>(a, cfg, scalar_loader, st);
 }
 
-size_t conv_lds_bytes(int cfg, int mode) {
+size_t conv_lds_bytes(int cfg, int /*mode*/) {
   const TileCfg& c = kTileCfgs[cfg];
-  size_t main_b = (size_t)2 * (c.bm + c.bn) * LDS_ROW;
-  size_t patch_b = (size_t)c.bm * (c.bn + 1) * 4;
-  return (mode == M_PATCH && patch_b > main_b) ? patch_b : main_b;
+  const size_t main_b = (size_t)2 * (c.bm + c.bn) * LDS_ROW;
+  const size_t stg_b = (size_t)c.bm * (c.bn + STG_PAD) * 4;
+  return stg_b > main_b ? stg_b : main_b;
 }
+
+bool conv_cfg_has_scalar_loader(int cfg) { return cfg == 1 || cfg == 2; }
 
 // ---------------------------------------------------------------------------------------------
 // Depthwise convolution chain: one thread = one 16-byte channel vector of one output pixel.

@@ -353,6 +353,7 @@ struct Planner {
       if (p.opts.tile > 0 && cfg != p.opts.tile - 1) continue;
       const TileCfg& tc = kTileCfgs[cfg];
       if (conv_lds_bytes(cfg, c.mode) > p.hw.lds_bytes_per_cu) continue;   // parameter split must fit private memory
+      if (st.scalar && !conv_cfg_has_scalar_loader(cfg)) continue;
       ConvArgs t = c;
       if (c.mode == M_FLAT || c.mode == M_ZIGZAG) {
         t.tiles_m = (c.M_total + tc.bm - 1) / tc.bm;
@@ -675,6 +676,13 @@ struct Planner {
         finish(last, cur, true);
         const View& ov = p.views[st.v_out];
         a.out_sN = ov.sN; a.out_sP = ov.sP; a.out_sK = ov.sK; a.out_f32 = ov.f32;
+        // 16-byte channel-group accesses need unit channel stride, the compute type and aligned slices
+        a.vec_out = ov.sK == 1 && (!ov.f32 || p.dt == DT_F32) && ov.esz == p.esz && K % p.ce == 0 && ov.off % p.ce == 0 &&
+                    ov.sP % p.ce == 0 && ov.sN % p.ce == 0;
+        if (has_res) {
+          const View& rv = p.views[st.v_in2];
+          a.vec_res = K % p.ce == 0 && rv.off % p.ce == 0 && rv.sP % p.ce == 0 && rv.sN % p.ce == 0;
+        }
         st.flops = 2.0 * a.N * a.OH * a.OW * (double)K * a.Kred;
         st.bytes_in = view_bytes(st.v_in); st.bytes_out = view_bytes(st.v_out);
         if (has_res) st.bytes_res = view_bytes(st.v_in2);

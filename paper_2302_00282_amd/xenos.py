@@ -69,6 +69,9 @@ def lib():
         if not os.path.exists(LIB_PATH):
             raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2302_00282_amd.build` "
                               "(hipcc, gfx950); there is no CPU fallback")
+        # PyTorch provides the device memory and streams, so the library must share the HIP runtime that
+        # torch loads (both have the same soname; the first one loaded serves the whole process).
+        import torch  # noqa: F401
         L = C.CDLL(LIB_PATH)
         vp = C.c_void_p
         L.xenos_graph_create.argtypes = [C.POINTER(TensorDesc), C.POINTER(OpDesc), C.c_int, C.c_int,
