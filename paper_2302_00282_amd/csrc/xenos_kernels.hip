@@ -186,34 +186,40 @@ __global__ __launch_bounds__(NT, 2) void conv_kernel(const ConvArgs a) {
           for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
       // Two register sets: the loads of step i+2 are issued while step i computes and are written to LDS
-      // at the end of step i+1, so a global access has two steps of MFMA work to hide behind.
+      // at the end of step i+1, so a global access has two steps of MFMA work to hide behind.  The vector
+      // loader is branch-free (out-of-range taps load a dummy address and are zeroed when published), so
+      // the number of loads in flight is known statically and only the older set is waited for.
       u32x4_t ra0[A_IT], rb0[B_IT], ra1[A_IT], rb1[B_IT];
+      unsigned ok0 = 0, ok1 = 0;
 
-      auto load_global = [&](int step, u32x4_t* ra, u32x4_t* rb) {
+      auto load_global = [&](int step, u32x4_t* ra, u32x4_t* rb, unsigned& okm) {
+        const int bstep = step < nsteps ? step : nsteps - 1;      // steps past the end re-read valid weights
         if constexpr (!SCALAR) {
-          const bool kok = kr < a.R;
+          const bool kok = kr < a.R;                              // false for every step past the end
           const long long koff = (long long)kr * a.in_sH + (long long)ks * a.in_sW + kc;
+          okm = 0;
 #pragma unroll
           for (int it = 0; it < A_IT; ++it) {
             const int ih = ih0[it] + kr, iw = iw0[it] + ks;
             const bool ok = kok && (unsigned)ih < (unsigned)a.H && (unsigned)iw < (unsigned)a.W;
-            u32x4_t v = {0u, 0u, 0u, 0u};
-            if (ok) v = *(const u32x4_t*)((const T*)a.in + rbase[it] + koff);
-            ra[it] = v;
+            const long long off = ok ? rbase[it] + koff : 0;
+            ra[it] = *(const u32x4_t*)((const T*)a.in + off);
+            okm |= (ok ? 1u : 0u) << it;
           }
           kc += BKE;
           while (kc >= a.C) { kc -= a.C; if (++ks == a.S) { ks = 0; ++kr; } }
         } else {
+          okm = ~0u;
           float f[A_IT][CE];
 #pragma unroll
           for (int e = 0; e < CE; ++e) {
-            const int kk = step * BKE + ch * CE + e;
+            const int kk = bstep * BKE + ch * CE + e;
             const int off = a.ktab[2 * kk], rs = a.ktab[2 * kk + 1];
             const int r = rs >> 16, s = rs & 0xffff;
 #pragma unroll
             for (int it = 0; it < A_IT; ++it) {
               const int ih = ih0[it] + r, iw = iw0[it] + s;
-              const bool ok = (unsigned)ih < (unsigned)a.H && (unsigned)iw < (unsigned)a.W;
+              const bool ok = step < nsteps && (unsigned)ih < (unsigned)a.H && (unsigned)iw < (unsigned)a.W;
               float v = 0.f;
               if (ok) v = a.in_f32 ? ((const float*)a.in)[rbase[it] + off] : tr::ld(a.in, rbase[it] + off);
               f[it][e] = v;
@@ -223,15 +229,17 @@ __global__ __launch_bounds__(NT, 2) void conv_kernel(const ConvArgs a) {
           for (int it = 0; it < A_IT; ++it) ra[it] = tr::pack(f[it]);
         }
 #pragma unroll
-        for (int it = 0; it < B_IT; ++it) rb[it] = *(const u32x4_t*)(wrow[it] + (long long)step * ROWB);
+        for (int it = 0; it < B_IT; ++it) rb[it] = *(const u32x4_t*)(wrow[it] + (long long)bstep * ROWB);
       };
-      auto store_lds = [&](int stage, const u32x4_t* ra, const u32x4_t* rb) {
+      auto store_lds = [&](int stage, const u32x4_t* ra, const u32x4_t* rb, unsigned okm) {
         unsigned char* sa = smem + stage * (BM + BN) * LDS_ROW;
         unsigned char* sb = sa + BM * LDS_ROW;
 #pragma unroll
         for (int it = 0; it < A_IT; ++it) {
           const int idx = tid + it * NT;
-          if (A_CH % NT == 0 || idx < A_CH) *(u32x4_t*)(sa + (idx >> 2) * LDS_ROW + (idx & 3) * 16) = ra[it];
+          const u32x4_t z = {0u, 0u, 0u, 0u};
+          if (A_CH % NT == 0 || idx < A_CH)
+            *(u32x4_t*)(sa + (idx >> 2) * LDS_ROW + (idx & 3) * 16) = ((okm >> it) & 1u) ? ra[it] : z;
         }
 #pragma unroll
         for (int it = 0; it < B_IT; ++it) {
@@ -268,21 +276,20 @@ __global__ __launch_bounds__(NT, 2) void conv_kernel(const ConvArgs a) {
         }
       };
 
-      load_global(0, ra0, rb0);
-      store_lds(0, ra0, rb0);
-      if (nsteps > 1) load_global(1, ra1, rb1);
+      load_global(0, ra0, rb0, ok0);
+      store_lds(0, ra0, rb0, ok0);
+      load_global(1, ra1, rb1, ok1);
       __syncthreads();
+      // Steady state without branches; when the step count is odd the last half-iteration multiplies an
+      // all-zero A stage (every tap past the end is out of range), which leaves the accumulators unchanged.
       for (int step = 0; step < nsteps; step += 2) {
-        // even step: compute stage 0, prefetch step+2 into set 0, publish set 1 (step+1) to stage 1
-        if (step + 2 < nsteps) load_global(step + 2, ra0, rb0);
+        load_global(step + 2, ra0, rb0, ok0);     // prefetch step+2 into set 0
         compute(0);
-        if (step + 1 < nsteps) store_lds(1, ra1, rb1);
+        store_lds(1, ra1, rb1, ok1);              // publish step+1
         __syncthreads();
-        if (step + 1 >= nsteps) break;
-        // odd step
-        if (step + 3 < nsteps) load_global(step + 3, ra1, rb1);
+        load_global(step + 3, ra1, rb1, ok1);
         compute(1);
-        if (step + 2 < nsteps) store_lds(0, ra0, rb0);
+        store_lds(0, ra0, rb0, ok0);
         __syncthreads();
       }
 
