@@ -9,6 +9,10 @@ namespace xenos {
 
 enum { DT_F32 = 0, DT_BF16 = 1 };
 
+// Bytes of one tile row consumed per reduction step of the dense-conv kernel (64 bf16 / 32 fp32 elements).
+// The packed weight layout depends on it, so host and kernels share the constant.
+constexpr int kRowBytes = 128;
+
 // How the rows (m) of an implicit-GEMM tile enumerate conv-output pixels.  The enumeration IS the
 // linked dataflow of Section 4.1 / Figure 4: the producer walks pixels in the order its linked
 // consumer (the pooling) reads them.
@@ -44,6 +48,7 @@ struct ConvArgs {
   int in_f32;            // scalar loader: input elements are fp32 (graph input) instead of the compute type
   int K, R, S, stride, pad, OH, OW;
   int Kred, Kred_pad;    // R*S*C and its padding to the reduction step
+  int kchunk;            // reduction order: 1 = (channel chunk, r, s, channel in chunk), needs C % step == 0; 0 = (r, s, c)
   int mode;              // M_*
   int relu, has_res;
   long long res_sN, res_sP;        // residual strides (image, pixel); channel stride 1
@@ -89,6 +94,7 @@ struct PoolArgs {
 struct CvtArgs {
   const void* in; void* out;
   int N, C, H, W;
+  int Cout;                          // channels written per pixel (>= C; channels C..Cout-1 are zero-filled)
   long long in_sN, in_sC, in_sP;     // element strides: image, channel, pixel (pixel index = h*W + w)
   long long out_sN, out_sC, out_sP;
   int in_f32, out_f32;

@@ -35,7 +35,7 @@ __device__ __forceinline__ uint16_t f2bf(float f) {
 template <typename T> struct Tr;
 template <> struct Tr<float> {
   static constexpr int CE = 4;     // elements per 16-byte chunk
-  static constexpr int BKE = 16;   // reduction elements per step (64 bytes per tile row)
+  static constexpr int BKE = kRowBytes / 4;   // reduction elements per step
   __device__ static __forceinline__ float ld(const void* p, long long i) { return ((const float*)p)[i]; }
   __device__ static __forceinline__ void st(void* p, long long i, float v) { ((float*)p)[i] = v; }
   __device__ static __forceinline__ void unpack(const u32x4_t& v, float* f) {
@@ -51,7 +51,7 @@ template <> struct Tr<float> {
 };
 template <> struct Tr<bf16_t> {
   static constexpr int CE = 8;
-  static constexpr int BKE = 32;
+  static constexpr int BKE = kRowBytes / 2;
   __device__ static __forceinline__ float ld(const void* p, long long i) { return bf2f(((const uint16_t*)p)[i]); }
   __device__ static __forceinline__ void st(void* p, long long i, float v) { ((uint16_t*)p)[i] = f2bf(v); }
   __device__ static __forceinline__ void unpack(const u32x4_t& v, float* f) {
@@ -70,8 +70,10 @@ template <> struct Tr<bf16_t> {
 };
 
 constexpr int NT = 256;          // threads per workgroup (4 wavefronts of 64)
-constexpr int ROWB = 64;         // data bytes per tile row per reduction step
-constexpr int LDS_ROW = 80;      // row pitch in LDS: 64 + 16 bytes, so 16 consecutive rows hit distinct 16-byte slots
+constexpr int ROWB = kRowBytes;  // data bytes per tile row per reduction step
+constexpr int CPR = ROWB / 16;   // 16-byte chunks per tile row
+constexpr int KG = ROWB / 32;    // k-groups (one MFMA fragment pair each) per step
+constexpr int LDS_ROW = ROWB + 16;   // row pitch in LDS: an odd number of 16-byte slots, so consecutive rows hit distinct slots
 constexpr int NUM_XCD = 8;
 
 __host__ __device__ constexpr int cmax(int a, int b) { return a > b ? a : b; }
@@ -91,7 +93,7 @@ __global__ __launch_bounds__(NT, 2) void conv_kernel(const ConvArgs a) {
   constexpr int CE = tr::CE, BKE = tr::BKE;
   constexpr int WAVES_N = BN / WN;
   constexpr int TM = WM / 32, TN = WN / 32;
-  constexpr int A_CH = BM * 4, B_CH = BN * 4;                      // 16-byte chunks per step
+  constexpr int A_CH = BM * CPR, B_CH = BN * CPR;                      // 16-byte chunks per step
   constexpr int A_IT = (A_CH + NT - 1) / NT, B_IT = (B_CH + NT - 1) / NT;
   constexpr int SP = BN + STG_PAD;                                 // staging pitch in floats
   constexpr int CG = BN / CE;                                      // channel groups (16-byte stores) per row
@@ -104,15 +106,17 @@ __global__ __launch_bounds__(NT, 2) void conv_kernel(const ConvArgs a) {
 
   const int nsteps = a.Kred_pad / BKE;
   const int OHW = a.OH * a.OW;
-  const int chunk = (a.ntiles + NUM_XCD - 1) / NUM_XCD;
-  const int slots = chunk * NUM_XCD;
+  const int mchunk = (a.tiles_m + NUM_XCD - 1) / NUM_XCD;
+  const int slots = mchunk * NUM_XCD * a.tiles_n;
 
   for (int t = blockIdx.x; t < slots; t += gridDim.x) {
-    // Workgroups are dealt round-robin to the 8 XCDs; give each XCD a contiguous run of tiles so that
-    // tiles sharing an input halo or a weight slice meet in the same L2.
-    const int L = (t % NUM_XCD) * chunk + t / NUM_XCD;
-    if (L >= a.ntiles) continue;                                   // uniform per workgroup
-    const int tile_m = L / a.tiles_n, tile_n = L % a.tiles_n;
+    // Workgroups are dealt round-robin to the 8 XCDs.  Each XCD owns a contiguous range of pixel tiles and
+    // walks it once per output-channel tile, so at any time the workgroups of one XCD share one weight
+    // slice in their L2 and neighbouring pixel tiles share their input halo.
+    const int local = t / NUM_XCD;
+    const int tile_n = local / mchunk;
+    const int tile_m = (t % NUM_XCD) * mchunk + local % mchunk;
+    if (tile_m >= a.tiles_m) continue;                             // uniform per workgroup
 
     // patch / gap geometry of this tile
     int img = 0, oy0 = 0, ox0 = 0, py = 0, px = 0;
@@ -133,10 +137,10 @@ __global__ __launch_bounds__(NT, 2) void conv_kernel(const ConvArgs a) {
       // ---- decode the rows this thread loads ---------------------------------------------------
       int ih0[A_IT], iw0[A_IT];
       long long rbase[A_IT];
-      const int ch = tid & 3;
+      const int ch = tid % CPR;
 #pragma unroll
       for (int it = 0; it < A_IT; ++it) {
-        const int row = (tid + it * NT) >> 2;
+        const int row = (tid + it * NT) / CPR;
         int n = 0, oh = 0, ow = 0;
         bool ok = row < BM;
         if (MODE == M_FLAT) {
@@ -167,12 +171,13 @@ __global__ __launch_bounds__(NT, 2) void conv_kernel(const ConvArgs a) {
       int kc, kr, ks;
       {
         const int kk = ch * CE;
-        kc = kk % a.C; const int rs = kk / a.C; ks = rs % a.S; kr = rs / a.S;
+        if (a.kchunk) { kc = kk; ks = 0; kr = 0; }
+        else { kc = kk % a.C; const int rs = kk / a.C; ks = rs % a.S; kr = rs / a.S; }
       }
       const unsigned char* wrow[B_IT];
 #pragma unroll
       for (int it = 0; it < B_IT; ++it) {
-        const int row = (tid + it * NT) >> 2;
+        const int row = (tid + it * NT) / CPR;
         wrow[it] = (const unsigned char*)a.w +
                    ((long long)(tile_n * BN + (row < BN ? row : 0)) * a.Kred_pad + ch * CE) * (long long)sizeof(T);
       }
@@ -195,7 +200,7 @@ __global__ __launch_bounds__(NT, 2) void conv_kernel(const ConvArgs a) {
       auto load_global = [&](int step, u32x4_t* ra, u32x4_t* rb, unsigned& okm) {
         const int bstep = step < nsteps ? step : nsteps - 1;      // steps past the end re-read valid weights
         if constexpr (!SCALAR) {
-          const bool kok = kr < a.R;                              // false for every step past the end
+          const bool kok = kr < a.R && kc < a.C;                  // false for every step past the end
           const long long koff = (long long)kr * a.in_sH + (long long)ks * a.in_sW + kc;
           okm = 0;
 #pragma unroll
@@ -206,8 +211,12 @@ __global__ __launch_bounds__(NT, 2) void conv_kernel(const ConvArgs a) {
             ra[it] = *(const u32x4_t*)((const T*)a.in + off);
             okm |= (ok ? 1u : 0u) << it;
           }
-          kc += BKE;
-          while (kc >= a.C) { kc -= a.C; if (++ks == a.S) { ks = 0; ++kr; } }
+          if (a.kchunk) {   // channel-chunk major: all taps of one chunk in consecutive steps (halo reuse in cache)
+            if (++ks == a.S) { ks = 0; if (++kr == a.R) { kr = 0; kc += BKE; } }
+          } else {          // tap major: (r, s) outer, channels inner
+            kc += BKE;
+            while (kc >= a.C) { kc -= a.C; if (++ks == a.S) { ks = 0; ++kr; } }
+          }
         } else {
           okm = ~0u;
           float f[A_IT][CE];
@@ -239,19 +248,19 @@ __global__ __launch_bounds__(NT, 2) void conv_kernel(const ConvArgs a) {
           const int idx = tid + it * NT;
           const u32x4_t z = {0u, 0u, 0u, 0u};
           if (A_CH % NT == 0 || idx < A_CH)
-            *(u32x4_t*)(sa + (idx >> 2) * LDS_ROW + (idx & 3) * 16) = ((okm >> it) & 1u) ? ra[it] : z;
+            *(u32x4_t*)(sa + (idx / CPR) * LDS_ROW + (idx % CPR) * 16) = ((okm >> it) & 1u) ? ra[it] : z;
         }
 #pragma unroll
         for (int it = 0; it < B_IT; ++it) {
           const int idx = tid + it * NT;
-          if (B_CH % NT == 0 || idx < B_CH) *(u32x4_t*)(sb + (idx >> 2) * LDS_ROW + (idx & 3) * 16) = rb[it];
+          if (B_CH % NT == 0 || idx < B_CH) *(u32x4_t*)(sb + (idx / CPR) * LDS_ROW + (idx % CPR) * 16) = rb[it];
         }
       };
       auto compute = [&](int stage) {
         const unsigned char* sa = smem + stage * (BM + BN) * LDS_ROW;
         const unsigned char* sb = sa + BM * LDS_ROW;
 #pragma unroll
-        for (int kg = 0; kg < 2; ++kg) {
+        for (int kg = 0; kg < KG; ++kg) {
           u32x4_t fa[TM], fb[TN];
 #pragma unroll
           for (int i = 0; i < TM; ++i)
@@ -481,11 +490,8 @@ static int launch_conv_mode(const ConvArgs& a, hipStream_t st) {
 
 template <typename T>
 static int launch_conv_t(const ConvArgs& a, int cfg, int scalar, hipStream_t st) {
-  if (scalar) {   // the element-wise gather loader (first layers) exists for the two mid-size tiles only
-    switch (cfg) {
-      case 1: return launch_conv_mode<T, 128, 64, 64, 32, true>(a, st);
-      case 2: return launch_conv_mode<T, 64, 64, 32, 32, true>(a, st);
-    }
+  if (scalar) {   // the element-wise gather loader (odd channel counts, strided graph input) exists for the 64x64 tile only
+    if (cfg == 2) return launch_conv_mode<T, 64, 64, 32, 32, true>(a, st);
     return (int)hipErrorInvalidValue;
   }
   switch (cfg) {
@@ -509,7 +515,7 @@ size_t conv_lds_bytes(int cfg, int /*mode*/) {
   return stg_b > main_b ? stg_b : main_b;
 }
 
-bool conv_cfg_has_scalar_loader(int cfg) { return cfg == 1 || cfg == 2; }
+bool conv_cfg_has_scalar_loader(int cfg) { return cfg == 2; }
 
 // ---------------------------------------------------------------------------------------------
 // Depthwise convolution chain: one thread = one 16-byte channel vector of one output pixel.
@@ -681,22 +687,25 @@ int launch_pool(const PoolArgs& a, int dtype, void* stream) {
 template <typename T>
 __global__ __launch_bounds__(NT) void cvt_kernel(const CvtArgs a) {
   using tr = Tr<T>;
-  const long long HW = (long long)a.H * a.W, total = (long long)a.N * HW * a.C;
+  const long long HW = (long long)a.H * a.W, total = (long long)a.N * HW * a.Cout;
   for (long long idx = (long long)blockIdx.x * NT + threadIdx.x; idx < total; idx += (long long)gridDim.x * NT) {
-    const int c = (int)(idx % a.C);
-    long long q = idx / a.C;
+    const int c = (int)(idx % a.Cout);
+    long long q = idx / a.Cout;
     const long long p = q % HW;
     const long long n = q / HW;
-    const long long i = n * a.in_sN + c * a.in_sC + p * a.in_sP;
     const long long o = n * a.out_sN + c * a.out_sC + p * a.out_sP;
-    const float v = a.in_f32 ? ((const float*)a.in)[i] : tr::ld(a.in, i);
+    float v = 0.f;                                                 // padding channel
+    if (c < a.C) {
+      const long long i = n * a.in_sN + c * a.in_sC + p * a.in_sP;
+      v = a.in_f32 ? ((const float*)a.in)[i] : tr::ld(a.in, i);
+    }
     if (a.out_f32) ((float*)a.out)[o] = v; else tr::st(a.out, o, v);
   }
 }
 
 int launch_cvt(const CvtArgs& a, int dtype, void* stream) {
   hipStream_t st = (hipStream_t)stream;
-  const int grid = grid_for((long long)a.N * a.H * a.W * a.C, NT);
+  const int grid = grid_for((long long)a.N * a.H * a.W * a.Cout, NT);
   if (dtype == DT_BF16) hipLaunchKernelGGL(cvt_kernel<bf16_t>, dim3(grid), dim3(NT), 0, st, a);
   else hipLaunchKernelGGL(cvt_kernel<float>, dim3(grid), dim3(NT), 0, st, a);
   return (int)hipGetLastError();

@@ -85,6 +85,7 @@ struct View {
   int f32 = 0;                 // elements are fp32 (only possible for graph input / output)
   int esz = 4;
   Shape s;
+  int cphys = 0;               // channels physically present per pixel (> s.c: zero-filled padding channels follow)
   bool internal_nhwc() const { return sK == 1; }
 };
 
@@ -378,15 +379,16 @@ struct Planner {
     if (best < 0) return fail(XENOS_EUNSUPPORTED, "%s: no tile configuration fits %zu bytes of LDS", st.name.c_str(), p.hw.lds_bytes_per_cu);
     c = best_args;
     st.cfg = best;
-    const int slots = (c.ntiles + 7) / 8 * 8;
+    const int slots = (c.tiles_m + 7) / 8 * 8 * c.tiles_n;      // 8 XCDs x (pixel tiles per XCD) x channel tiles
     c.grid = p.opts.split ? slots : 1;
     st.lds = conv_lds_bytes(best, c.mode);
     return XENOS_OK;
   }
 
   // ---- pack weights of a dense conv / fc in operand order -------------------------------------
-  void pack_dense(Step& st, const GOp& o, int C, int R, int S, int K) {
-    const int bke = p.dt == DT_BF16 ? 32 : 16;
+  // Csrc = channels of the operator's weights, C = channels the kernel reduces over (>= Csrc, extra ones zero)
+  void pack_dense(Step& st, const GOp& o, int Csrc, int C, int R, int S, int K) {
+    const int bke = kRowBytes / p.esz;
     const int kred = R * S * C, kred_pad = (kred + bke - 1) / bke * bke;
     const int kout_pad = (K + 127) / 128 * 128;
     st.conv.Kred = kred; st.conv.Kred_pad = kred_pad;
@@ -394,20 +396,27 @@ struct Planner {
     st.w_off = (long long)wpush(nullptr, bytes);
     unsigned char* base = p.wimage.data() + st.w_off;
     memset(base, 0, bytes);
-    // source [K][C][R][S] -> destination [K][(r*S+s)*C + c]
+    // source [K][C][R][S] -> destination [K][reduction index]; the reduction index is (r*S+s)*C + c, or, when
+    // the channels divide into whole steps, ((c/step)*R*S + r*S + s)*step + c%step so that the R*S taps of
+    // one channel chunk are consecutive steps and re-read the same input pixels while they are still cached
+    const bool kchunk = C % bke == 0 && R * S > 1 && !st.scalar;
+    st.conv.kchunk = kchunk ? 1 : 0;
+    auto kidx = [&](int c, int rs) -> size_t {
+      return kchunk ? ((size_t)(c / bke) * R * S + rs) * bke + c % bke : (size_t)rs * C + c;
+    };
     for (int k = 0; k < K; ++k) {
-      const float* src = o.weight.data() + (size_t)k * C * R * S;
+      const float* src = o.weight.data() + (size_t)k * Csrc * R * S;
       if (p.dt == DT_BF16) {
         uint16_t* dst = (uint16_t*)base + (size_t)k * kred_pad;
-        for (int c = 0; c < C; ++c)
-          for (int rs = 0; rs < R * S; ++rs) dst[(size_t)rs * C + c] = f2bf_host(src[(size_t)c * R * S + rs]);
+        for (int c = 0; c < Csrc; ++c)
+          for (int rs = 0; rs < R * S; ++rs) dst[kidx(c, rs)] = f2bf_host(src[(size_t)c * R * S + rs]);
       } else {
         float* dst = (float*)base + (size_t)k * kred_pad;
-        for (int c = 0; c < C; ++c)
-          for (int rs = 0; rs < R * S; ++rs) dst[(size_t)rs * C + c] = src[(size_t)c * R * S + rs];
+        for (int c = 0; c < Csrc; ++c)
+          for (int rs = 0; rs < R * S; ++rs) dst[kidx(c, rs)] = src[(size_t)c * R * S + rs];
       }
     }
-    st.bytes_w = (long long)K * kred * p.esz;
+    st.bytes_w = (long long)K * R * S * Csrc * p.esz;
   }
 
   // ---- main pass --------------------------------------------------------------------------------
@@ -447,26 +456,28 @@ struct Planner {
     // graph input
     {
       bool direct = ext_is_internal(p.in) && p.in.c % p.ce == 0;
-      bool scalar_ok = !consumers[0].empty() && p.in.c <= 8;
+      bool all_dense = !consumers[0].empty();
       for (int ci : consumers[0]) {
         const Node& nd = nodes[ci];
-        const bool dense = (nd.kind == XENOS_OP_CONV && desc(nd).groups == 1);
-        if (!dense) scalar_ok = false;
+        if (!(nd.kind == XENOS_OP_CONV && desc(nd).groups == 1)) all_dense = false;
       }
       const int ev = ext_view(p.in, 1);
       if (direct) {
         normalise_1x1(p.views[ev]);
         p.views[ev].f32 = 0;
         tview[0] = ev;
-      } else if (scalar_ok) {
-        tview[0] = ev;
       } else {
-        // import: convert to the internal NHWC layout of the compute type
-        const int iv = internal_view(tshape[0]);
+        // import: convert to the internal NHWC layout of the compute type.  When only dense convolutions read
+        // the input (the usual 3-channel image), the channels are zero-padded to a whole 16-byte group so that
+        // the first layer runs on the vector loader like every other layer (its padded weights are zero).
+        const int cpad = all_dense ? (p.in.c + p.ce - 1) / p.ce * p.ce : p.in.c;
+        const int iv = internal_view(tshape[0], -1, cpad);
+        p.views[iv].cphys = cpad;
         Step st;
         st.kind = S_CVT; st.name = "import";
         st.v_in = ev; st.v_out = iv;
         fill_cvt(st);
+        st.cvt.Cout = cpad;
         add_step(st);
         tview[0] = iv;
       }
@@ -496,7 +507,7 @@ struct Planner {
     const View& a = p.views[st.v_in];
     const View& b = p.views[st.v_out];
     CvtArgs& c = st.cvt;
-    c.N = a.s.n; c.C = a.s.c; c.H = a.s.h; c.W = a.s.w;
+    c.N = a.s.n; c.C = a.s.c; c.Cout = a.s.c; c.H = a.s.h; c.W = a.s.w;
     c.in_sN = a.sN; c.in_sC = a.sK; c.in_sP = a.sP; c.in_f32 = a.f32;
     c.out_sN = b.sN; c.out_sC = b.sK; c.out_sP = b.sP; c.out_f32 = b.f32;
     st.bytes_in = view_bytes(st.v_in);
@@ -630,11 +641,11 @@ struct Planner {
         st.v_in = vin;
         const View& iv = p.views[vin];
         ConvArgs& a = st.conv;
-        a.N = is.n; a.C = is.c; a.H = is.h; a.W = is.w;
+        a.N = is.n; a.C = std::max(is.c, iv.cphys); a.H = is.h; a.W = is.w;   // padding channels multiply zero weights
         a.K = K;
         if (is_fc) { a.R = is.h; a.S = is.w; a.stride = 1; a.pad = 0; a.OH = 1; a.OW = 1; }
         else { a.R = d.kh; a.S = d.kw; a.stride = d.stride_h; a.pad = d.pad_h; a.OH = tshape[i + 1].h; a.OW = tshape[i + 1].w; }
-        st.scalar = !(iv.internal_nhwc() && !iv.f32 && iv.esz == p.esz && is.c % p.ce == 0 && iv.off % p.ce == 0 && iv.sP % p.ce == 0);
+        st.scalar = !(iv.internal_nhwc() && !iv.f32 && iv.esz == p.esz && a.C % p.ce == 0 && iv.off % p.ce == 0 && iv.sP % p.ce == 0);
         a.in_sN = iv.sN; a.in_sH = iv.sP * is.w; a.in_sW = iv.sP; a.in_f32 = iv.f32;
         a.relu = relu; a.has_res = has_res;
         if (has_res) {
@@ -655,7 +666,7 @@ struct Planner {
           }
         }
         a.M_total = a.mode == M_FLAT ? a.N * a.OH * a.OW : a.mode == M_ZIGZAG ? a.N * a.PH * a.PW * 4 : a.OH * a.OW;
-        pack_dense(st, go, a.C, a.R, a.S, K);
+        pack_dense(st, go, is_fc ? is.c : is.c, a.C, a.R, a.S, K);
         push_affine(af, (K + 127) / 128 * 128, &st.scale_off, &st.shift_off);
         if (st.scalar) {
           std::vector<int32_t> tab((size_t)2 * a.Kred_pad);
@@ -683,7 +694,7 @@ struct Planner {
           const View& rv = p.views[st.v_in2];
           a.vec_res = K % p.ce == 0 && rv.off % p.ce == 0 && rv.sP % p.ce == 0 && rv.sN % p.ce == 0;
         }
-        st.flops = 2.0 * a.N * a.OH * a.OW * (double)K * a.Kred;
+        st.flops = 2.0 * a.N * a.OH * a.OW * (double)K * a.R * a.S * is.c;
         st.bytes_in = view_bytes(st.v_in); st.bytes_out = view_bytes(st.v_out);
         if (has_res) st.bytes_res = view_bytes(st.v_in2);
       }
