@@ -435,6 +435,7 @@ __global__ __launch_bounds__(NT, 2) void conv_kernel(const ConvArgs a) {
         for (int row = part; row < BM; row += NT / BN) {
           if (mc * BM + row >= OHW) break;
           float x = stg[row * SP + col] * sc + sh;
+          if (a.has_res && k < a.K) x += tr::ld(a.res, (long long)img * a.res_sN + (long long)(mc * BM + row) * a.res_sP + k);
           if (a.relu) x = fmaxf(x, 0.f);
           gsum += x;
         }

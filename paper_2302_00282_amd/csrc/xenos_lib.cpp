@@ -462,9 +462,14 @@ struct Planner {
         if (!(nd.kind == XENOS_OP_CONV && desc(nd).groups == 1)) all_dense = false;
       }
       const int ev = ext_view(p.in, 1);
+      // small inputs: the first convolution gathers straight from the caller's tensor (one pass fewer);
+      // large inputs: a conversion pass pays for itself because the first layer then runs on the vector loader
+      const bool gather_direct = all_dense && p.in.c <= 8 && (long long)p.in.n * p.in.h * p.in.w < 100000;
       if (direct) {
         normalise_1x1(p.views[ev]);
         p.views[ev].f32 = 0;
+        tview[0] = ev;
+      } else if (gather_direct) {
         tview[0] = ev;
       } else {
         // import: convert to the internal NHWC layout of the compute type.  When only dense convolutions read
@@ -594,7 +599,7 @@ struct Planner {
         } else if (nn_.kind == XENOS_OP_RELU && stage <= 2) {
           relu = true; stage = 3;
         } else if ((nn_.kind == XENOS_OP_MAXPOOL || nn_.kind == XENOS_OP_AVGPOOL || nn_.kind == XENOS_OP_GLOBAL_AVGPOOL) &&
-                   link >= 2 && !dw && !has_res && stage <= 3) {
+                   link >= 2 && !dw && (!has_res || nn_.kind == XENOS_OP_GLOBAL_AVGPOOL) && stage <= 3) {
           pool_node = nx; stage = 4;
         } else {
           break;

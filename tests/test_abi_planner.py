@@ -1,0 +1,175 @@
+"""CPU-side checks (no GPU): the C-ABI library loads and exports every symbol the header declares,
+graph ingest validates and infers shapes, and the optimiser (fusion pre-pass, operator linking,
+operator split) produces plans that are structurally sound.  No kernel is launched here."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2302_00282_amd import xenos as X
+from workloads import cnn_graphs as wg
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def plan_json(g, **kw):
+    G = X.graph_from_workload(g)
+    try:
+        P = X.xenos_plan_link_split(G, **kw)
+        try:
+            return X.xenos_plan_query(P)
+        finally:
+            X.xenos_destroy(P)
+    finally:
+        X.xenos_destroy(G)
+
+
+def test_library_exports_every_declared_symbol():
+    hdr = open(os.path.join(ROOT, "include", "xenos.h")).read()
+    names = set(re.findall(r"\b(xenos_[a-z_]+)\s*\(", hdr))
+    assert {"xenos_graph_create", "xenos_plan_link_split", "xenos_run", "xenos_destroy"} <= names
+    lib = ctypes.CDLL(X.LIB_PATH)
+    for n in sorted(names):
+        assert hasattr(lib, n), n
+
+
+def test_missing_library_fails_loudly(monkeypatch):
+    monkeypatch.setattr(X, "_lib", None)
+    monkeypatch.setattr(X, "LIB_PATH", "/nonexistent/libxenos.so")
+    with pytest.raises(ImportError):
+        X.lib()
+
+
+def test_graph_validation_errors():
+    g = wg.single_chain(batch=1)
+    keep = []
+    ops = X.op_descs(g, keep)
+    ind = X.TensorDesc(1, 3, 32, 32, X.XENOS_F32, X.XENOS_NCHW)
+    with pytest.raises(X.XenosError) as e:
+        X.xenos_graph_create(ind, ops, 9)                      # output id out of range
+    assert e.value.status == X.XENOS_EINVAL
+    bad = X.op_descs(g, keep)
+    bad[0].weight = ctypes.cast(None, ctypes.POINTER(ctypes.c_float))
+    with pytest.raises(X.XenosError) as e:
+        X.xenos_graph_create(ind, bad, 4)
+    assert e.value.status == X.XENOS_EINVAL and "weight" in str(e.value)
+    bad = X.op_descs(g, keep)
+    bad[0].kh = bad[0].kw = 40                                 # kernel larger than the padded map
+    with pytest.raises(X.XenosError) as e:
+        X.xenos_graph_create(ind, bad, 4)
+    assert e.value.status == X.XENOS_ESHAPE
+    with pytest.raises(X.XenosError) as e:                     # wrong output descriptor
+        X.xenos_graph_create(ind, ops, 4, X.TensorDesc(1, 16, 8, 8, X.XENOS_F32, X.XENOS_NCHW))
+    assert e.value.status == X.XENOS_ESHAPE
+    b = wg.builder("bad_add", (1, 8, 8, 8), 1)
+    t1 = b.conv(0, 8, 3, 1, 1)
+    t2 = b.conv(0, 8, 3, 2, 1)
+    b.g.ops.append(wg.Op("add", [t1, t2]))
+    with pytest.raises(X.XenosError) as e:
+        X.xenos_graph_create(X.TensorDesc(1, 8, 8, 8, 0, 0), X.op_descs(b.g, keep), 3)
+    assert e.value.status == X.XENOS_ESHAPE
+    assert X.xenos_destroy(None) is None
+
+
+def test_plan_option_errors():
+    G = X.graph_from_workload(wg.single_chain(batch=1))
+    try:
+        with pytest.raises(X.XenosError):
+            X.xenos_plan_link_split(G, link=7)
+        with pytest.raises(X.XenosError):
+            X.xenos_plan_link_split(G, hw=dict(num_cu=0, lds_bytes_per_cu=0, l2_bytes=0, llc_bytes=0, hbm_bytes=0))
+        with pytest.raises(X.XenosError) as e:                 # private memory too small for any parameter split
+            X.xenos_plan_link_split(G, hw=dict(num_cu=8, lds_bytes_per_cu=4096, l2_bytes=0, llc_bytes=0, hbm_bytes=0))
+        assert e.value.status == X.XENOS_EUNSUPPORTED
+    finally:
+        X.xenos_destroy(G)
+
+
+def test_cfg0_links_to_one_chain_and_unlinked_levels():
+    g = wg.build(0, 1)
+    q2 = plan_json(g, link=2)["plan"]
+    q1 = plan_json(g, link=1)["plan"]
+    q0 = plan_json(g, link=0)["plan"]
+    assert q2["n_chains"] == 1 and q2["chains"][0]["ops"] == [0, 1, 2, 3]       # CBR + MaxPool = one pass (CBRM)
+    assert q2["chains"][0]["mode"] == "zigzag"
+    assert [c["ops"] for c in q1["chains"] if c["kind"] == "conv"] == [[0, 1, 2]]   # fused CBR, pool separate
+    assert sum(1 for c in q0["chains"] if c["ops"]) == 4                            # operator by operator
+    assert q0["hbm_bytes"] > q1["hbm_bytes"] > q2["hbm_bytes"]
+
+
+@pytest.mark.parametrize("cfg,batch", [(1, 1), (2, 1), (2, 32), (4, 1), (4, 32)])
+def test_every_operator_runs_exactly_once(cfg, batch):
+    g = wg.build(cfg, batch, draw=False)
+    for link in (0, 1, 2):
+        q = plan_json(g, link=link, compute=X.XENOS_BF16)["plan"]
+        seen = [o for c in q["chains"] for o in c["ops"]]
+        # a hoisted pooling operator appears once per concat producer; a copied concat once per input
+        assert set(seen) == set(range(len(g.ops))) - ({i for i, o in enumerate(g.ops) if o.kind == "concat"} if link >= 2 else set())
+        if link < 2:
+            non_cat = [o for o in seen if g.ops[o].kind != "concat"]
+            assert len(non_cat) == len(set(non_cat))
+
+
+def test_linking_patterns_of_the_workloads():
+    res = plan_json(wg.build(2, 1, draw=False), link=2, compute=X.XENOS_BF16)["plan"]
+    convs = [c for c in res["chains"] if c["kind"] == "conv"]
+    assert sum(c["res"] for c in convs) == 8                   # every shortcut add runs in a conv epilogue
+    assert convs[0]["mode"] == "patch" and convs[0]["pool"] == 1      # stem conv + 3x3/2 max-pool
+    assert convs[-2]["mode"] == "gap"                          # last block + global average (CBRA)
+    sq = plan_json(wg.build(4, 1, draw=False), link=2, compute=X.XENOS_BF16)["plan"]
+    assert all(c["kind"] == "conv" for c in sq["chains"] if c["name"] != "import")   # concat and pools cost no pass
+    offs = sorted({(c["out_c_off"], c["out_sP"]) for c in sq["chains"] if c["kind"] == "conv" and c["out_c_off"]})
+    assert (64, 128) in offs and (256, 512) in offs            # expand3x3 halves land at their channel offset
+    vgg = plan_json(wg.build(3, 2, draw=False), link=2, compute=X.XENOS_BF16)["plan"]
+    assert [c["mode"] for c in vgg["chains"] if c["kind"] == "conv"].count("zigzag") == 5
+
+
+@pytest.mark.parametrize("cfg,batch,compute", [(1, 1, 0), (2, 32, 1), (3, 32, 1), (4, 32, 0)])
+def test_split_covers_the_output_and_fits_private_memory(cfg, batch, compute):
+    g = wg.build(cfg, batch, draw=False)
+    q = plan_json(g, link=2, compute=compute)
+    for c in q["plan"]["chains"]:
+        if c["kind"] != "conv":
+            continue
+        assert c["lds"] <= X.MI355X["lds_bytes_per_cu"]
+        assert c["tiles_n"] * c["bn"] >= c["K"] > (c["tiles_n"] - 1) * c["bn"]      # outC partition, no gap, no overlap
+        if c["mode"] == "flat":
+            m = c["N"] * c["OH"] * c["OW"]
+            assert c["tiles_m"] * c["bm"] >= m > (c["tiles_m"] - 1) * c["bm"]
+        elif c["mode"] == "zigzag":
+            m = c["N"] * c["PH"] * c["PW"] * 4
+            assert c["tiles_m"] * c["bm"] >= m > (c["tiles_m"] - 1) * c["bm"]
+        elif c["mode"] == "patch":
+            assert c["patch_h"] * c["patch_w"] <= c["bm"]
+            py, px = -(-c["PH"] // c["pph"]), -(-c["PW"] // c["ppw"])
+            assert c["tiles_m"] == c["N"] * py * px
+        assert c["grid"] >= c["tiles_m"] * c["tiles_n"]
+    assert q["workspace_bytes"] > 0 and q["weight_bytes"] > 0
+
+
+def test_unsplit_plan_uses_one_workgroup():
+    q = plan_json(wg.build(0, 1), link=2, split=0)["plan"]
+    assert all(c["grid"] == 1 for c in q["chains"] if c["kind"] == "conv")
+
+
+def test_hardware_description_drives_the_split():
+    g = wg.build(2, 32, draw=False)
+    big = plan_json(g, compute=1)["plan"]
+    small = plan_json(g, compute=1, hw=dict(num_cu=8, lds_bytes_per_cu=160 * 1024, l2_bytes=1 << 20, llc_bytes=0, hbm_bytes=1 << 30))["plan"]
+    tb = sum(c["tiles_m"] * c["tiles_n"] for c in big["chains"] if c["kind"] == "conv")
+    ts = sum(c["tiles_m"] * c["tiles_n"] for c in small["chains"] if c["kind"] == "conv")
+    assert ts <= tb            # fewer units -> never a finer split
+
+
+def test_planning_time_is_reported_scale():
+    import time
+    g = wg.build(1, 1)
+    G = X.graph_from_workload(g)
+    t0 = time.perf_counter()
+    P = X.xenos_plan_link_split(G, compute=X.XENOS_BF16)
+    dt = time.perf_counter() - t0
+    X.xenos_destroy(P)
+    X.xenos_destroy(G)
+    assert dt < 5.0            # the paper reports 0.11 s for MobileNet (Table 2); same order of magnitude

@@ -79,6 +79,10 @@ def chain_graph(kind, seed=3, n=2, c=16, hw=13, k=24, bias=True):
         v = b.cbr(v, k, 3, 1, 1, name="c2", relu=False)
         p = b.cbr(u, k, 1, 2, 0, name="proj", relu=False)
         t = b.relu(b.add(v, p))
+    elif kind == "shortcut_gap":             # last residual block linked with the global average (CBRA after a shortcut)
+        u = b.cbr(0, c, 3, 1, 1, name="c1")
+        v = b.cbr(u, c, 3, 1, 1, name="c2", relu=False)
+        t = b.gap(b.relu(b.add(v, u)))
     elif kind == "fire":                     # one producer, two consumers, concat by offset, pool hoisted over concat
         q = b.cbr(0, 16, 1, name="sq", bn=False)
         e1 = b.cbr(q, 32, 1, name="e1", bn=False)
@@ -98,7 +102,7 @@ def chain_graph(kind, seed=3, n=2, c=16, hw=13, k=24, bias=True):
 
 
 KINDS = ["conv3", "conv3s2", "conv1", "conv7s2", "cbrm2", "cbra2", "cbrm3", "cbrm3ceil", "cbra3", "cbra3cip",
-         "cbrgap", "bias_after_bn", "shortcut", "shortcut_proj", "fire", "dw", "dws2pw", "fc"]
+         "cbrgap", "bias_after_bn", "shortcut", "shortcut_proj", "shortcut_gap", "fire", "dw", "dws2pw", "fc"]
 
 
 @pytest.mark.parametrize("compute", [0, 1])
