@@ -34,6 +34,11 @@ static const TileCfg kTileCfgs[] = {
   {32, 128, 32, 32},
 };
 static const int kNumTileCfgs = 4;
+// Configuration index of the halo-staged 3x3 kernel: 256 pixels x 128 channels, 512 threads, TH x TW spatial tile.
+static const int kHaloCfg = 4;
+static const int kHaloRows = 256, kHaloCols = 128, kHaloPatchMax = 384;
+// the staged patch has one of two fixed row pitches (pixels): tiles up to 16 or up to 32 pixels wide
+static const int kHaloPitchNarrow = 18, kHaloPitchWide = 34;
 
 struct ConvArgs {
   const void* in;        // activations: NHWC in the compute type (vector loader), or any strided fp32/T tensor (scalar loader)
@@ -57,6 +62,7 @@ struct ConvArgs {
   long long out_sN, out_sP, out_sK;    // output strides (image, pixel, channel) in elements
   int out_f32;           // store fp32 instead of the compute type (graph output)
   int vec_out, vec_res;  // 16-byte channel-group stores / shortcut loads are legal (alignment, unit channel stride, K % group == 0)
+  int th, tw, tiles_y, tiles_x;   // halo kernel: spatial tile and tile grid over the stacked padded rows n*(H+2)+oh
   int M_total;           // rows enumerated over the whole problem (FLAT, ZIGZAG); per-image rows for GAP
   int tiles_m, tiles_n, ntiles;
   int grid;              // workgroups launched (>= 1); tiles are visited with a stride of `grid`

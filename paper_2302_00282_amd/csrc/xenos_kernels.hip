@@ -13,6 +13,7 @@
 // in-unit parameter split (Section 4.2.2) and never crosses workgroups.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <type_traits>
 #include "kernels.h"
 
 namespace xenos {
@@ -293,11 +294,15 @@ __global__ __launch_bounds__(NT, 2) void conv_kernel(const ConvArgs a) {
       // all-zero A stage (every tap past the end is out of range), which leaves the accumulators unchanged.
       for (int step = 0; step < nsteps; step += 2) {
         load_global(step + 2, ra0, rb0, ok0);     // prefetch step+2 into set 0
+        __builtin_amdgcn_sched_barrier(0);        // keep the prefetch loads ahead of the MFMA block
         compute(0);
+        __builtin_amdgcn_sched_barrier(0);
         store_lds(1, ra1, rb1, ok1);              // publish step+1
         __syncthreads();
         load_global(step + 3, ra1, rb1, ok1);
+        __builtin_amdgcn_sched_barrier(0);
         compute(1);
+        __builtin_amdgcn_sched_barrier(0);
         store_lds(0, ra0, rb0, ok0);
         __syncthreads();
       }
@@ -462,6 +467,329 @@ __global__ __launch_bounds__(NT, 2) void conv_kernel(const ConvArgs a) {
   }
 }
 
+// ---------------------------------------------------------------------------------------------
+// Dense 3x3 / stride 1 / pad 1 convolution chain with the input halo staged on chip
+// ---------------------------------------------------------------------------------------------
+// The im2col gather of conv_kernel re-reads every input pixel nine times through L2 and re-writes it nine
+// times into LDS; LDS writes (~75 B/clk/CU) and L2->CU traffic (~45 B/clk/CU) then cost as much as the MFMA
+// work.  Here a workgroup owns a TH x TW block of output pixels (256 GEMM rows) x 128 output channels, loads the
+// (TH+2) x (TW+2) input patch of one 64-element channel chunk ONCE, and runs the nine taps out of that patch
+// (the fragment address of a row only shifts by the tap offset).  This is the GPU form of the paper's halo
+// replication (Section 4.1, last paragraph): neighbouring tiles hold their own copy of the boundary rows and
+// columns instead of looking back.  Images are stacked with their padding rows (row q = n*(H+2) + oh), so a
+// tile may span two images and small maps still fill the 256 rows; rows with oh >= H are dummies.
+constexpr int V2_BM = 256, V2_BN = 128, V2_NT = 512, V2_PPMAX = 384;
+constexpr int V2_ABYTES = V2_PPMAX * LDS_ROW, V2_BBYTES = V2_BN * LDS_ROW;
+constexpr int V2_LDS = 2 * V2_ABYTES + 2 * V2_BBYTES;
+static_assert(V2_LDS >= V2_BM * (V2_BN + STG_PAD) * 4, "epilogue staging must fit in the operand buffers");
+
+// PWID = row pitch of the staged patch in pixels (compile time, so that every tap is an immediate LDS offset)
+template <typename T, int MODE, int PWID>
+__global__ __launch_bounds__(V2_NT) void conv3x3_kernel(const ConvArgs a) {
+  using tr = Tr<T>;
+  constexpr int CE = tr::CE, BKE = tr::BKE;
+  constexpr int BM = V2_BM, BN = V2_BN, NTH = V2_NT;
+  constexpr int A_IT = V2_PPMAX * CPR / NTH;                       // 6 patch chunks per thread
+  constexpr int B_IT = BN * CPR / NTH;                             // 2 weight chunks per thread
+  constexpr int SP = BN + STG_PAD, CG = BN / CE;
+  static_assert(MODE == M_FLAT || MODE == M_ZIGZAG, "row enumerations of the halo kernel");
+
+  extern __shared__ __align__(16) unsigned char smem[];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wave_m = wave >> 1, wave_n = wave & 1;                 // 4 x 2 wavefronts of 64 x 64
+  const int l31 = lane & 31, lhalf = lane >> 5;
+
+  const int PP = (a.th + 2) * PWID, Hp = a.H + 2;               // a.tw + 2 <= PWID
+  const int nchunks = a.C / BKE, nsteps = nchunks * 9;
+  const int mchunk = (a.tiles_m + NUM_XCD - 1) / NUM_XCD;
+  const int slots = mchunk * NUM_XCD * a.tiles_n;
+
+  for (int t = blockIdx.x; t < slots; t += gridDim.x) {
+    const int local = t / NUM_XCD;
+    const int tile_n = local / mchunk;
+    const int tile_m = (t % NUM_XCD) * mchunk + local % mchunk;
+    if (tile_m >= a.tiles_m) continue;                             // uniform per workgroup
+    const int tyi = tile_m / a.tiles_x;
+    const int q0 = tyi * a.th, x0 = (tile_m - tyi * a.tiles_x) * a.tw;
+
+    // ---- what this thread loads: 6 chunks of the input patch, 2 chunks of the weight tile ----------
+    int aoff[A_IT];
+    unsigned aok = 0;
+#pragma unroll
+    for (int it = 0; it < A_IT; ++it) {
+      const int idx = tid + it * NTH;
+      const int pp = idx / CPR, c8 = idx % CPR;
+      const int pr = pp / PWID, pc = pp - pr * PWID;
+      const int P = q0 + pr, n = P / Hp, ih = P - n * Hp - 1, iw = x0 - 1 + pc;
+      const bool ok = pp < PP && n < a.N && (unsigned)ih < (unsigned)a.H && (unsigned)iw < (unsigned)a.W;
+      aoff[it] = ok ? (int)((long long)n * a.in_sN + (long long)ih * a.in_sH + (long long)iw * a.in_sW) + c8 * CE : c8 * CE;
+      aok |= (ok ? 1u : 0u) << it;
+    }
+    const unsigned char* wrow[B_IT];
+#pragma unroll
+    for (int it = 0; it < B_IT; ++it) {
+      const int idx = tid + it * NTH;
+      wrow[it] = (const unsigned char*)a.w +
+                 ((long long)(tile_n * BN + idx / CPR) * a.Kred_pad + (idx % CPR) * CE) * (long long)sizeof(T);
+    }
+    // ---- fragment addresses of this lane's rows (pixels of the tile) -------------------------------
+    int abase[2], bbase[2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const int m = wave_m * 64 + i * 32 + l31;
+      int ty, tx;
+      bool ok;
+      if (MODE == M_FLAT) { ty = m / a.tw; tx = m - ty * a.tw; ok = ty < a.th; }
+      else {
+        const int w = m >> 2, j = m & 3, hw = a.tw >> 1;
+        const int wy = w / hw, wx = w - wy * hw;
+        ty = 2 * wy + (j >> 1); tx = 2 * wx + (j & 1); ok = ty < a.th;
+      }
+      abase[i] = (ok ? ty * PWID + tx : 0) * LDS_ROW + lhalf * 16;
+      bbase[i] = (wave_n * 64 + i * 32 + l31) * LDS_ROW + lhalf * 16;
+    }
+
+    f32x16_t acc[2][2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+    constexpr int A_HALF = A_IT / 2;
+    u32x4_t pa[A_HALF], rb0[B_IT], rb1[B_IT];
+
+    // the patch of a channel chunk travels in two halves of 3 chunks per thread (12 staging registers)
+    auto load_patch = [&](int cc, int half) {
+      const int c = (cc < nchunks ? cc : nchunks - 1) * BKE;
+#pragma unroll
+      for (int it = 0; it < A_HALF; ++it) pa[it] = *(const u32x4_t*)((const T*)a.in + aoff[half * A_HALF + it] + c);
+    };
+    auto store_patch = [&](int buf, int half) {
+      unsigned char* sa = smem + buf * V2_ABYTES;
+      const u32x4_t z = {0u, 0u, 0u, 0u};
+#pragma unroll
+      for (int it = 0; it < A_HALF; ++it) {
+        const int idx = tid + (half * A_HALF + it) * NTH;
+        *(u32x4_t*)(sa + (idx / CPR) * LDS_ROW + (idx % CPR) * 16) = ((aok >> (half * A_HALF + it)) & 1u) ? pa[it] : z;
+      }
+    };
+    auto load_w = [&](int step, u32x4_t* rb) {
+      const int bstep = step < nsteps ? step : nsteps - 1;
+#pragma unroll
+      for (int it = 0; it < B_IT; ++it) rb[it] = *(const u32x4_t*)(wrow[it] + (long long)bstep * ROWB);
+    };
+    auto store_w = [&](int stage, const u32x4_t* rb) {
+      unsigned char* sb = smem + 2 * V2_ABYTES + stage * V2_BBYTES;
+#pragma unroll
+      for (int it = 0; it < B_IT; ++it) {
+        const int idx = tid + it * NTH;
+        *(u32x4_t*)(sb + (idx / CPR) * LDS_ROW + (idx % CPR) * 16) = rb[it];
+      }
+    };
+    // one tap of one channel chunk: 4 k-groups, fragments of k-group g+1 are fetched before the MFMAs of g
+    auto compute = [&](int abuf, int bstage, int tapoff) {
+      const unsigned char* sa = smem + abuf * V2_ABYTES + tapoff;
+      const unsigned char* sb = smem + 2 * V2_ABYTES + bstage * V2_BBYTES;
+      u32x4_t fa[2][2], fb[2][2];
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        fa[0][i] = *(const u32x4_t*)(sa + abase[i]);
+        fb[0][i] = *(const u32x4_t*)(sb + bbase[i]);
+      }
+#pragma unroll
+      for (int kg = 0; kg < KG; ++kg) {
+        const int cur = kg & 1, nxt = cur ^ 1;
+        if (kg + 1 < KG) {
+#pragma unroll
+          for (int i = 0; i < 2; ++i) {
+            fa[nxt][i] = *(const u32x4_t*)(sa + abase[i] + (kg + 1) * 32);
+            fb[nxt][i] = *(const u32x4_t*)(sb + bbase[i] + (kg + 1) * 32);
+          }
+        }
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+          for (int j = 0; j < 2; ++j) {
+            if constexpr (sizeof(T) == 2) {
+              acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, fa[cur][i]),
+                                                                  __builtin_bit_cast(bf16x8_t, fb[cur][j]), acc[i][j], 0, 0, 0);
+            } else {
+#pragma unroll
+              for (int e = 0; e < 4; ++e)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(fa[cur][i][e]), __uint_as_float(fb[cur][j][e]),
+                                                                 acc[i][j], 0, 0, 0);
+            }
+          }
+      }
+      // the schedule wanted: fragments of k-group g+1 are in flight while the MFMAs of k-group g issue
+      // (0x100 = LDS read, 0x008 = MFMA); without it the scheduler serialises read -> wait -> MFMA
+      __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
+#pragma unroll
+      for (int kg = 0; kg < KG; ++kg) {
+        if (kg + 1 < KG) __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, sizeof(T) == 2 ? 4 : 16, 0);
+      }
+    };
+    // nine statically unrolled taps of channel chunk cc; PAR = parity of the first step of the chunk
+    auto chunk_body = [&](int cc, auto par) {
+      constexpr int PAR = decltype(par)::value;
+      const int step0 = cc * 9;
+#pragma unroll
+      for (int tap = 0; tap < 9; ++tap) {
+        constexpr int dummy = 0; (void)dummy;
+        const int sp = (PAR + tap) & 1;                            // weight stage / register set of this step
+        if (sp == 0) load_w(step0 + tap + 2, rb0); else load_w(step0 + tap + 2, rb1);
+        if (tap == 0) load_patch(cc + 1, 0);                       // next chunk's patch: half 0 in flight over taps 0-3,
+        if (tap == 4) load_patch(cc + 1, 1);                       // half 1 over taps 4-8
+        __builtin_amdgcn_sched_barrier(0);                         // keep the prefetch loads ahead of the MFMA block
+        compute(cc & 1, sp, ((tap / 3) * PWID + tap % 3) * LDS_ROW);
+        __builtin_amdgcn_sched_barrier(0);
+        if (sp == 0) store_w(1, rb1); else store_w(0, rb0);       // publish step + 1
+        if (tap == 3) store_patch((cc + 1) & 1, 0);
+        if (tap == 8) store_patch((cc + 1) & 1, 1);
+        __syncthreads();
+      }
+    };
+
+    load_patch(0, 0);
+    load_w(0, rb0);
+    store_patch(0, 0);
+    load_patch(0, 1);
+    store_w(0, rb0);
+    store_patch(0, 1);
+    load_w(1, rb1);
+    __syncthreads();
+    for (int cc = 0; cc < nchunks; cc += 2) {
+      chunk_body(cc, std::integral_constant<int, 0>{});
+      if (cc + 1 >= nchunks) break;
+      chunk_body(cc + 1, std::integral_constant<int, 1>{});
+    }
+
+    // ---- epilogue ---------------------------------------------------------------------------------
+    float* stg = (float*)smem;
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        const int col = wave_n * 64 + j * 32 + l31;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          const int row = wave_m * 64 + i * 32 + (e >> 2) * 8 + lhalf * 4 + (e & 3);
+          stg[row * SP + col] = acc[i][j][e];
+        }
+      }
+    __syncthreads();
+    const int nq = MODE == M_FLAT ? a.th * a.tw : (a.th >> 1) * (a.tw >> 1);
+    for (int idx = tid; idx < nq * CG; idx += NTH) {
+      const int cg = idx % CG, q = idx / CG;
+      const int col0 = cg * CE, k0 = tile_n * BN + col0;
+      if (k0 >= a.K) continue;
+      float sc[CE], sh[CE], v[CE];
+      *(f32x4_t*)&sc[0] = *(const f32x4_t*)(a.scale + k0);
+      *(f32x4_t*)&sh[0] = *(const f32x4_t*)(a.shift + k0);
+      if (CE == 8) {
+        *(f32x4_t*)&sc[4] = *(const f32x4_t*)(a.scale + k0 + 4);
+        *(f32x4_t*)&sh[4] = *(const f32x4_t*)(a.shift + k0 + 4);
+      }
+      long long obase;
+      if (MODE == M_FLAT) {
+        const int ty = q / a.tw, tx = q - ty * a.tw;
+        const int qq = q0 + ty, n = qq / Hp, oh = qq - n * Hp, ow = x0 + tx;
+        if (n >= a.N || oh >= a.H || ow >= a.W) continue;
+        obase = (long long)n * a.out_sN + (long long)(oh * a.OW + ow) * a.out_sP;
+        const float* sp = stg + q * SP + col0;
+#pragma unroll
+        for (int e = 0; e < CE; e += 4) *(f32x4_t*)&v[e] = *(const f32x4_t*)(sp + e);
+#pragma unroll
+        for (int e = 0; e < CE; ++e) v[e] = v[e] * sc[e] + sh[e];
+        if (a.has_res) {
+          const long long rb_ = (long long)n * a.res_sN + (long long)(oh * a.OW + ow) * a.res_sP;
+          if (a.vec_res) {
+            float r[CE];
+            tr::unpack(*(const u32x4_t*)((const T*)a.res + rb_ + k0), r);
+#pragma unroll
+            for (int e = 0; e < CE; ++e) v[e] += r[e];
+          } else {
+#pragma unroll
+            for (int e = 0; e < CE; ++e) if (k0 + e < a.K) v[e] += tr::ld(a.res, rb_ + k0 + e);
+          }
+        }
+        if (a.relu) {
+#pragma unroll
+          for (int e = 0; e < CE; ++e) v[e] = fmaxf(v[e], 0.f);
+        }
+      } else {
+        const int hw = a.tw >> 1;
+        const int wy = q / hw, wx = q - wy * hw;
+        const int qq = q0 + 2 * wy, n = qq / Hp, oh = qq - n * Hp, ow = x0 + 2 * wx;
+        if (n >= a.N || oh >= a.H || ow >= a.W) continue;
+        obase = (long long)n * a.out_sN + (long long)((oh >> 1) * a.PW + (ow >> 1)) * a.out_sP;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          float u[CE];
+          const float* sp = stg + (4 * q + j) * SP + col0;
+#pragma unroll
+          for (int e = 0; e < CE; e += 4) *(f32x4_t*)&u[e] = *(const f32x4_t*)(sp + e);
+#pragma unroll
+          for (int e = 0; e < CE; ++e) {
+            float x = u[e] * sc[e] + sh[e];
+            if (a.relu) x = fmaxf(x, 0.f);
+            v[e] = j == 0 ? x : (a.pool == POOL_MAX ? fmaxf(v[e], x) : v[e] + x);
+          }
+        }
+        if (a.pool == POOL_AVG) {
+#pragma unroll
+          for (int e = 0; e < CE; ++e) v[e] *= 0.25f;
+        }
+      }
+      if (a.vec_out) {
+        *(u32x4_t*)((T*)a.out + obase + k0) = tr::pack(v);
+      } else {
+#pragma unroll
+        for (int e = 0; e < CE; ++e) {
+          if (k0 + e >= a.K) continue;
+          const long long o = obase + (long long)(k0 + e) * a.out_sK;
+          if (a.out_f32) ((float*)a.out)[o] = v[e]; else tr::st(a.out, o, v[e]);
+        }
+      }
+    }
+    __syncthreads();
+  }
+}
+
+template <typename T, int MODE, int PWID>
+static int launch_conv3x3_pw(const ConvArgs& a, hipStream_t st) {
+  static bool raised = false;
+  if (!raised) {
+    hipError_t e = hipFuncSetAttribute((const void*)conv3x3_kernel<T, MODE, PWID>, hipFuncAttributeMaxDynamicSharedMemorySize, V2_LDS);
+    if (e != hipSuccess) return (int)e;
+    raised = true;
+  }
+  hipLaunchKernelGGL((conv3x3_kernel<T, MODE, PWID>), dim3(a.grid), dim3(V2_NT), V2_LDS, st, a);
+  return (int)hipGetLastError();
+}
+
+template <typename T, int MODE>
+static int launch_conv3x3_inst(const ConvArgs& a, hipStream_t st) {
+  if (a.tw + 2 <= kHaloPitchNarrow && (a.th + 2) * kHaloPitchNarrow <= V2_PPMAX) return launch_conv3x3_pw<T, MODE, kHaloPitchNarrow>(a, st);
+  if (a.tw + 2 <= kHaloPitchWide && (a.th + 2) * kHaloPitchWide <= V2_PPMAX) return launch_conv3x3_pw<T, MODE, kHaloPitchWide>(a, st);
+  return (int)hipErrorInvalidValue;
+}
+
+template <typename T>
+static int launch_conv3x3_t(const ConvArgs& a, hipStream_t st) {
+  // the host checks the preconditions again: a wrong shape here would index outside the patch buffers
+  if (a.R != 3 || a.S != 3 || a.stride != 1 || a.pad != 1 || !a.kchunk || a.C % Tr<T>::BKE != 0 || a.th < 1 || a.tw < 1 ||
+      a.th * a.tw > V2_BM || a.tiles_m != a.tiles_y * a.tiles_x ||
+      (a.mode == M_ZIGZAG && ((a.th | a.tw | a.H | a.W) & 1)))
+    return (int)hipErrorInvalidValue;
+  if (a.mode == M_FLAT) return launch_conv3x3_inst<T, M_FLAT>(a, st);
+  if (a.mode == M_ZIGZAG) return launch_conv3x3_inst<T, M_ZIGZAG>(a, st);
+  return (int)hipErrorInvalidValue;
+}
+
 template <typename T, int BM, int BN, int WM, int WN, bool SCALAR, int MODE>
 static int launch_conv_inst(const ConvArgs& a, hipStream_t st) {
   constexpr int lds = lds_conv_bytes<BM, BN>();
@@ -506,10 +834,15 @@ static int launch_conv_t(const ConvArgs& a, int cfg, int scalar, hipStream_t st)
 
 int launch_conv(const ConvArgs& a, int dtype, int cfg, int scalar_loader, void* stream) {
   hipStream_t st = (hipStream_t)stream;
+  if (cfg == kHaloCfg) {
+    if (scalar_loader) return (int)hipErrorInvalidValue;
+    return dtype == DT_BF16 ? launch_conv3x3_t<bf16_t>(a, st) : launch_conv3x3_t<float>(a, st);
+  }
   return dtype == DT_BF16 ? launch_conv_t<bf16_t>(a, cfg, scalar_loader, st) : launch_conv_t<float>(a, cfg, scalar_loader, st);
 }
 
 size_t conv_lds_bytes(int cfg, int /*mode*/) {
+  if (cfg == kHaloCfg) return V2_LDS;
   const TileCfg& c = kTileCfgs[cfg];
   const size_t main_b = (size_t)2 * (c.bm + c.bn) * LDS_ROW;
   const size_t stg_b = (size_t)c.bm * (c.bn + STG_PAD) * 4;

@@ -145,6 +145,25 @@ def test_every_tile_configuration(kind, tile):
         check(g, ref, compute=compute, tile=tile)
 
 
+@pytest.mark.parametrize("kind,hw", [("conv3", 19), ("conv3", 7), ("cbrm2", 20), ("cbra2x3", 12), ("shortcut", 13), ("conv3", 40)])
+@pytest.mark.parametrize("compute", [0, 1])
+def test_halo_staged_3x3_kernel(kind, hw, compute):
+    # forced tile 5 = the halo-staged 3x3 kernel: tiles lie over the images stacked with their padding rows, so
+    # with these sizes tiles straddle two images, overhang the right edge and contain dummy rows
+    n, c, k = 5, 64, 136
+    if kind == "cbra2x3":
+        b = wg.builder("halo_avg", (n, c, hw, hw), 9, nonzero_bias=True)
+        g = b.finish(b.avgpool(b.cbr(0, k, 3, 1, 1, name="c"), 2, 2))
+    elif kind == "shortcut":
+        g = chain_graph(kind, n=n, c=c, hw=hw)
+    else:
+        g = chain_graph(kind, n=n, c=c, hw=hw, k=k)
+    y, info = check(g, compute=compute, tile=5)
+    assert any(ch.get("halo") for ch in info["chains"])
+    y1, _ = run_gpu(g, compute=compute, tile=5, split=0)
+    assert np.array_equal(y, y1)                       # split == unsplit, bit for bit
+
+
 def test_small_channel_first_layer_and_nchw_output():
     # C = 3 first layer: packed (r,s,c) reduction gathered element-wise from the NCHW fp32 graph input;
     # the output goes straight to the caller's NCHW fp32 buffer
