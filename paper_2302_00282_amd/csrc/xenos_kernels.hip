@@ -328,19 +328,22 @@ __global__ __launch_bounds__(NT, 2) void conv_kernel(const ConvArgs a) {
       // ReLU, pooling over the rows of its window, then one 16-byte store into the consumer's buffer.
       if (MODE != M_GAP) {
         const int nq = MODE == M_FLAT ? BM : MODE == M_ZIGZAG ? BM / 4 : a.pph * a.ppw;
+        // NT is a multiple of CG, so a thread keeps its channel group over all its output elements: the
+        // folded scale / shift are loaded once, outside the loop (the arrays are padded to the tile)
+        static_assert(NT % CG == 0, "channel group must be loop-invariant per thread");
+        const int cg = tid % CG, col0 = cg * CE, k0 = tile_n * BN + col0;
+        float sc[CE], sh[CE];
+        *(f32x4_t*)&sc[0] = *(const f32x4_t*)(a.scale + k0);
+        *(f32x4_t*)&sh[0] = *(const f32x4_t*)(a.shift + k0);
+        if (CE == 8) {
+          *(f32x4_t*)&sc[4] = *(const f32x4_t*)(a.scale + k0 + 4);
+          *(f32x4_t*)&sh[4] = *(const f32x4_t*)(a.shift + k0 + 4);
+        }
         for (int idx = tid; idx < nq * CG; idx += NT) {
-          const int cg = idx % CG, q = idx / CG;
-          const int col0 = cg * CE, k0 = tile_n * BN + col0;
-          if (k0 >= a.K) continue;
+          const int q = idx / CG;
+          if (k0 >= a.K) break;
           long long obase, rb_ = 0;
           float v[CE];
-          float sc[CE], sh[CE];
-          *(f32x4_t*)&sc[0] = *(const f32x4_t*)(a.scale + k0);
-          *(f32x4_t*)&sh[0] = *(const f32x4_t*)(a.shift + k0);
-          if (CE == 8) {
-            *(f32x4_t*)&sc[4] = *(const f32x4_t*)(a.scale + k0 + 4);
-            *(f32x4_t*)&sh[4] = *(const f32x4_t*)(a.shift + k0 + 4);
-          }
           if (MODE == M_FLAT) {
             const int m = tile_m * BM + q;
             if (m >= a.M_total) continue;
@@ -682,17 +685,19 @@ __global__ __launch_bounds__(V2_NT) void conv3x3_kernel(const ConvArgs a) {
       }
     __syncthreads();
     const int nq = MODE == M_FLAT ? a.th * a.tw : (a.th >> 1) * (a.tw >> 1);
+    static_assert(NTH % CG == 0, "channel group must be loop-invariant per thread");
+    const int cg = tid % CG, col0 = cg * CE, k0 = tile_n * BN + col0;
+    float sc[CE], sh[CE];
+    *(f32x4_t*)&sc[0] = *(const f32x4_t*)(a.scale + k0);
+    *(f32x4_t*)&sh[0] = *(const f32x4_t*)(a.shift + k0);
+    if (CE == 8) {
+      *(f32x4_t*)&sc[4] = *(const f32x4_t*)(a.scale + k0 + 4);
+      *(f32x4_t*)&sh[4] = *(const f32x4_t*)(a.shift + k0 + 4);
+    }
     for (int idx = tid; idx < nq * CG; idx += NTH) {
-      const int cg = idx % CG, q = idx / CG;
-      const int col0 = cg * CE, k0 = tile_n * BN + col0;
-      if (k0 >= a.K) continue;
-      float sc[CE], sh[CE], v[CE];
-      *(f32x4_t*)&sc[0] = *(const f32x4_t*)(a.scale + k0);
-      *(f32x4_t*)&sh[0] = *(const f32x4_t*)(a.shift + k0);
-      if (CE == 8) {
-        *(f32x4_t*)&sc[4] = *(const f32x4_t*)(a.scale + k0 + 4);
-        *(f32x4_t*)&sh[4] = *(const f32x4_t*)(a.shift + k0 + 4);
-      }
+      const int q = idx / CG;
+      if (k0 >= a.K) break;
+      float v[CE];
       long long obase;
       if (MODE == M_FLAT) {
         const int ty = q / a.tw, tx = q - ty * a.tw;
