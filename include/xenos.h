@@ -142,6 +142,12 @@ xenos_status xenos_plan_bind(xenos_plan* plan, void* d_weights, void* d_workspac
  * Asynchronous; allocates nothing; returns XENOS_EDEVICE if a launch fails. */
 xenos_status xenos_run(xenos_plan* plan, const void* d_input, void* d_output, void* hip_stream);
 
+/* Same result as xenos_run, for latency-bound (batch 1) use: the first call with a given (d_input, d_output)
+ * pair captures the kernel sequence into a HIP graph (kernel nodes only; the runtime allocates host-side graph
+ * objects on that call), later calls with the same pair replay it with one launch.  The pointers must stay
+ * valid and the plan bound to the same buffers for as long as the pair is reused.  Asynchronous on hip_stream. */
+xenos_status xenos_run_graph(xenos_plan* plan, const void* d_input, void* d_output, void* hip_stream);
+
 /* Runs only chain `chain` of a bound plan (0 <= chain < number of chains in the JSON), reading and
  * writing the same buffers xenos_run would; used for per-chain timing. */
 xenos_status xenos_run_chain(xenos_plan* plan, int chain, const void* d_input, void* d_output,

@@ -131,6 +131,13 @@ struct xenos_plan {
   void* d_weights = nullptr;
   void* d_workspace = nullptr;
   bool bound = false;
+  // xenos_run_graph: one instantiated HIP graph per (input, output) pointer pair, captured on a private stream
+  std::map<std::pair<const void*, void*>, hipGraphExec_t> graphs;
+  hipStream_t capture_stream = nullptr;
+  ~xenos_plan() {
+    for (auto& kv : graphs) (void)hipGraphExecDestroy(kv.second);
+    if (capture_stream) (void)hipStreamDestroy(capture_stream);
+  }
 };
 
 namespace {
@@ -1158,6 +1165,39 @@ xenos_status xenos_run(xenos_plan* plan, const void* d_input, void* d_output, vo
     xenos_status rc = launch_step(*plan, s, d_input, d_output, hip_stream);
     if (rc != XENOS_OK) return rc;
   }
+  return XENOS_OK;
+}
+
+xenos_status xenos_run_graph(xenos_plan* plan, const void* d_input, void* d_output, void* hip_stream) {
+  if (!plan || plan->magic != MAGIC_PLAN || !d_input || !d_output) return fail(XENOS_EINVAL, "xenos_run_graph: bad argument");
+  if (!plan->bound) return fail(XENOS_EINVAL, "xenos_run_graph: plan is not bound (call xenos_plan_bind)");
+  auto key = std::make_pair(d_input, d_output);
+  auto it = plan->graphs.find(key);
+  if (it == plan->graphs.end()) {
+    // capture the kernel sequence (kernel nodes only) on a private stream of default priority
+    if (!plan->capture_stream) {
+      hipError_t e = hipStreamCreateWithFlags(&plan->capture_stream, hipStreamNonBlocking);
+      if (e != hipSuccess) return fail(XENOS_EDEVICE, "stream create failed: %s", hipGetErrorString(e));
+    }
+    hipError_t e = hipStreamBeginCapture(plan->capture_stream, hipStreamCaptureModeThreadLocal);
+    if (e != hipSuccess) return fail(XENOS_EDEVICE, "graph capture failed to start: %s", hipGetErrorString(e));
+    xenos_status rc = XENOS_OK;
+    for (const Step& s : plan->steps) {
+      rc = launch_step(*plan, s, d_input, d_output, plan->capture_stream);
+      if (rc != XENOS_OK) break;
+    }
+    hipGraph_t graph = nullptr;
+    e = hipStreamEndCapture(plan->capture_stream, &graph);
+    if (rc != XENOS_OK) { if (graph) (void)hipGraphDestroy(graph); return rc; }
+    if (e != hipSuccess || !graph) return fail(XENOS_EDEVICE, "graph capture failed: %s", hipGetErrorString(e));
+    hipGraphExec_t exec = nullptr;
+    e = hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0);
+    (void)hipGraphDestroy(graph);
+    if (e != hipSuccess) return fail(XENOS_EDEVICE, "graph instantiate failed: %s", hipGetErrorString(e));
+    it = plan->graphs.emplace(key, exec).first;
+  }
+  hipError_t e = hipGraphLaunch(it->second, (hipStream_t)hip_stream);
+  if (e != hipSuccess) return fail(XENOS_EDEVICE, "graph launch failed: %s", hipGetErrorString(e));
   return XENOS_OK;
 }
 

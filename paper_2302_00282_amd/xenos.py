@@ -81,12 +81,13 @@ def lib():
                                        C.c_char_p, C.c_size_t, C.POINTER(C.c_size_t)]
         L.xenos_plan_bind.argtypes = [vp, vp, vp, vp]
         L.xenos_run.argtypes = [vp, vp, vp, vp]
+        L.xenos_run_graph.argtypes = [vp, vp, vp, vp]
         L.xenos_run_chain.argtypes = [vp, C.c_int, vp, vp, vp]
         L.xenos_destroy.argtypes = [vp]
         L.xenos_destroy.restype = None
         L.xenos_last_error.restype = C.c_char_p
         for f in ("xenos_graph_create", "xenos_plan_link_split", "xenos_plan_query", "xenos_plan_bind",
-                  "xenos_run", "xenos_run_chain"):
+                  "xenos_run", "xenos_run_graph", "xenos_run_chain"):
             getattr(L, f).restype = C.c_int
         _lib = L
     return _lib
@@ -140,6 +141,10 @@ def xenos_plan_bind(plan: int, d_weights: int, d_workspace: int, stream: int = 0
 
 def xenos_run(plan: int, d_input: int, d_output: int, stream: int = 0):
     _check(lib().xenos_run(plan, d_input, d_output, stream))
+
+
+def xenos_run_graph(plan: int, d_input: int, d_output: int, stream: int = 0):
+    _check(lib().xenos_run_graph(plan, d_input, d_output, stream))
 
 
 def xenos_run_chain(plan: int, chain: int, d_input: int, d_output: int, stream: int = 0):
@@ -240,6 +245,9 @@ class Session:
 
     def run(self):
         xenos_run(self.plan, self.x.data_ptr(), self.y.data_ptr(), self.stream())
+
+    def run_graph(self):
+        xenos_run_graph(self.plan, self.x.data_ptr(), self.y.data_ptr(), self.stream())
 
     def run_chain(self, i: int):
         xenos_run_chain(self.plan, i, self.x.data_ptr(), self.y.data_ptr(), self.stream())

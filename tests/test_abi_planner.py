@@ -135,7 +135,11 @@ def test_split_covers_the_output_and_fits_private_memory(cfg, batch, compute):
             continue
         assert c["lds"] <= X.MI355X["lds_bytes_per_cu"]
         assert c["tiles_n"] * c["bn"] >= c["K"] > (c["tiles_n"] - 1) * c["bn"]      # outC partition, no gap, no overlap
-        if c["mode"] == "flat":
+        if c.get("halo"):
+            # halo-staged kernel: TH x TW tiles over the images stacked with their two padding rows each
+            assert c["th"] * c["tw"] <= c["bm"] == 256
+            assert c["tiles_m"] == -(-(c["N"] * (c["H"] + 2)) // c["th"]) * -(-c["W"] // c["tw"])
+        elif c["mode"] == "flat":
             m = c["N"] * c["OH"] * c["OW"]
             assert c["tiles_m"] * c["bm"] >= m > (c["tiles_m"] - 1) * c["bm"]
         elif c["mode"] == "zigzag":

@@ -183,6 +183,28 @@ def test_deterministic_run_to_run():
     assert np.array_equal(a, b)
 
 
+def test_graph_replay_matches_eager_every_time():
+    # replayed several times with eager work and synchronisations in between; every replay must equal the eager result
+    import torch
+    X = _xenos()
+    g = wg.mobilenet_v1(batch=2, hw=64, width=0.25, classes=24, seed=31)
+    s = X.Session(g, link=2, compute=1)
+    try:
+        ref = s.forward(g.x).copy()
+        x2 = np.ascontiguousarray(g.x[::-1])
+        ref2 = s.forward(x2).copy()
+        for rep in range(4):
+            s.set_input(g.x if rep % 2 == 0 else x2)
+            s.y.zero_()
+            s.run_graph()
+            torch.cuda.synchronize()
+            assert np.array_equal(s.y.cpu().numpy(), ref if rep % 2 == 0 else ref2), rep
+            s.run()                                   # eager work between replays
+            torch.cuda.synchronize()
+    finally:
+        s.close()
+
+
 # ------------------------------------------------------------------------------------------ whole graphs
 def test_cfg0_single_chain():
     g = wg.build(0, 1)
