@@ -62,6 +62,10 @@ struct ConvArgs {
   long long out_sN, out_sP, out_sK;    // output strides (image, pixel, channel) in elements
   int out_f32;           // store fp32 instead of the compute type (graph output)
   int vec_out, vec_res;  // 16-byte channel-group stores / shortcut loads are legal (alignment, unit channel stride, K % group == 0)
+  // linked depthwise producer (nullptr = none): `in` is then the depthwise INPUT (NHWC), H x W the depthwise output
+  const void* dw_w; const float* dw_scale; const float* dw_shift;   // [k*k][C] compute type, folded scale / shift [C]
+  int dw_k, dw_stride, dw_pad, dw_H, dw_W, dw_relu;
+  long long dw_sN, dw_sP;
   int th, tw, tiles_y, tiles_x;   // halo kernel: spatial tile and tile grid over the stacked padded rows n*(H+2)+oh
   int M_total;           // rows enumerated over the whole problem (FLAT, ZIGZAG); per-image rows for GAP
   int tiles_m, tiles_n, ntiles;
@@ -114,5 +118,6 @@ int launch_pool(const PoolArgs& a, int dtype, void* stream);
 int launch_cvt(const CvtArgs& a, int dtype, void* stream);
 size_t conv_lds_bytes(int cfg, int mode);
 bool conv_cfg_has_scalar_loader(int cfg);
+bool conv_cfg_has_dw_prologue(int cfg, int mode);
 
 }  // namespace xenos

@@ -88,7 +88,10 @@ constexpr int STG_PAD = 4;       // staging row pitch = BN + 4 floats (keeps 16-
 template <int BM, int BN>
 __host__ __device__ constexpr int lds_conv_bytes() { return cmax(2 * (BM + BN) * LDS_ROW, BM * (BN + STG_PAD) * 4); }
 
-template <typename T, int BM, int BN, int WM, int WN, bool SCALAR, int MODE>
+// DWPRO: the A operand is not read from memory but produced on the fly by a linked depthwise 3x3 convolution
+// (+ scale/shift + ReLU) of the tensor `in`: the depthwise output never exists in HBM (Section 2.2: the depthwise
+// producer hands its result to the pointwise consumer in the consumer's channel-first order).
+template <typename T, int BM, int BN, int WM, int WN, bool SCALAR, int MODE, bool DWPRO = false>
 __global__ __launch_bounds__(NT, 2) void conv_kernel(const ConvArgs a) {
   using tr = Tr<T>;
   constexpr int CE = tr::CE, BKE = tr::BKE;
@@ -167,6 +170,7 @@ __global__ __launch_bounds__(NT, 2) void conv_kernel(const ConvArgs a) {
         iw0[it] = ow * a.stride - a.pad;
         // element offset of input pixel (ih0, iw0); only ever dereferenced together with an in-range tap
         rbase[it] = ok ? (long long)n * a.in_sN + (long long)ih0[it] * a.in_sH + (long long)iw0[it] * a.in_sW : 0;
+        if (DWPRO) rbase[it] = ok ? (long long)n * a.dw_sN : 0;    // image base of the depthwise input; (ih0, iw0) = pointwise pixel
       }
       // reduction position (r, s, c) of this thread's 16-byte chunk
       int kc, kr, ks;
@@ -200,7 +204,38 @@ __global__ __launch_bounds__(NT, 2) void conv_kernel(const ConvArgs a) {
 
       auto load_global = [&](int step, u32x4_t* ra, u32x4_t* rb, unsigned& okm) {
         const int bstep = step < nsteps ? step : nsteps - 1;      // steps past the end re-read valid weights
-        if constexpr (!SCALAR) {
+        if constexpr (DWPRO) {
+          // linked depthwise producer: this thread's CE channels of its pixels, nine taps, fp32 accumulate
+          okm = ~0u;
+#pragma unroll
+          for (int it = 0; it < A_IT; ++it) {
+            float d[CE];
+#pragma unroll
+            for (int e = 0; e < CE; ++e) d[e] = 0.f;
+            if (kc < a.C && ih0[it] >= 0) {
+              for (int r = 0; r < a.dw_k; ++r) {
+                const int ih = ih0[it] * a.dw_stride - a.dw_pad + r;
+                if ((unsigned)ih >= (unsigned)a.dw_H) continue;
+                for (int s2 = 0; s2 < a.dw_k; ++s2) {
+                  const int iw = iw0[it] * a.dw_stride - a.dw_pad + s2;
+                  if ((unsigned)iw >= (unsigned)a.dw_W) continue;
+                  float x[CE], w[CE];
+                  tr::unpack(*(const u32x4_t*)((const T*)a.in + rbase[it] + ((long long)ih * a.dw_W + iw) * a.dw_sP + kc), x);
+                  tr::unpack(*(const u32x4_t*)((const T*)a.dw_w + (long long)(r * a.dw_k + s2) * a.C + kc), w);
+#pragma unroll
+                  for (int e = 0; e < CE; ++e) d[e] = fmaf(x[e], w[e], d[e]);
+                }
+              }
+#pragma unroll
+              for (int e = 0; e < CE; ++e) {
+                const float v = d[e] * a.dw_scale[kc + e] + a.dw_shift[kc + e];
+                d[e] = a.dw_relu ? fmaxf(v, 0.f) : v;
+              }
+            }
+            ra[it] = tr::pack(d);
+          }
+          kc += BKE;
+        } else if constexpr (!SCALAR) {
           const bool kok = kr < a.R && kc < a.C;                  // false for every step past the end
           const long long koff = (long long)kr * a.in_sH + (long long)ks * a.in_sW + kc;
           okm = 0;
@@ -822,6 +857,31 @@ static int launch_conv_mode(const ConvArgs& a, hipStream_t st) {
   return (int)hipErrorInvalidValue;
 }
 
+template <typename T, int BM, int BN, int WM, int WN, int MODE>
+static int launch_conv_dwpro_inst(const ConvArgs& a, hipStream_t st) {
+  constexpr int lds = lds_conv_bytes<BM, BN>();
+  static bool raised = false;
+  if (lds > 64 * 1024 && !raised) {
+    hipError_t e = hipFuncSetAttribute((const void*)conv_kernel<T, BM, BN, WM, WN, false, MODE, true>,
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    if (e != hipSuccess) return (int)e;
+    raised = true;
+  }
+  hipLaunchKernelGGL((conv_kernel<T, BM, BN, WM, WN, false, MODE, true>), dim3(a.grid), dim3(NT), lds, st, a);
+  return (int)hipGetLastError();
+}
+
+// linked depthwise -> pointwise chain: 1x1 / stride 1 / pad 0 consumer, FLAT or GAP rows, two tile shapes
+template <typename T>
+static int launch_conv_dwpro_t(const ConvArgs& a, int cfg, hipStream_t st) {
+  if (a.R != 1 || a.S != 1 || a.stride != 1 || a.pad != 0 || a.kchunk || a.C % Tr<T>::CE != 0 || !a.dw_w || a.dw_k < 1)
+    return (int)hipErrorInvalidValue;
+  if (cfg == 1 && a.mode == M_FLAT) return launch_conv_dwpro_inst<T, 128, 64, 64, 32, M_FLAT>(a, st);
+  if (cfg == 2 && a.mode == M_FLAT) return launch_conv_dwpro_inst<T, 64, 64, 32, 32, M_FLAT>(a, st);
+  if (cfg == 2 && a.mode == M_GAP) return launch_conv_dwpro_inst<T, 64, 64, 32, 32, M_GAP>(a, st);
+  return (int)hipErrorInvalidValue;
+}
+
 template <typename T>
 static int launch_conv_t(const ConvArgs& a, int cfg, int scalar, hipStream_t st) {
   if (scalar) {   // the element-wise gather loader (odd channel counts, strided graph input) exists for the 64x64 tile only
@@ -839,6 +899,10 @@ static int launch_conv_t(const ConvArgs& a, int cfg, int scalar, hipStream_t st)
 
 int launch_conv(const ConvArgs& a, int dtype, int cfg, int scalar_loader, void* stream) {
   hipStream_t st = (hipStream_t)stream;
+  if (a.dw_w) {
+    if (scalar_loader) return (int)hipErrorInvalidValue;
+    return dtype == DT_BF16 ? launch_conv_dwpro_t<bf16_t>(a, cfg, st) : launch_conv_dwpro_t<float>(a, cfg, st);
+  }
   if (cfg == kHaloCfg) {
     if (scalar_loader) return (int)hipErrorInvalidValue;
     return dtype == DT_BF16 ? launch_conv3x3_t<bf16_t>(a, st) : launch_conv3x3_t<float>(a, st);
@@ -855,6 +919,7 @@ size_t conv_lds_bytes(int cfg, int /*mode*/) {
 }
 
 bool conv_cfg_has_scalar_loader(int cfg) { return cfg == 2; }
+bool conv_cfg_has_dw_prologue(int cfg, int mode) { return (mode == M_FLAT && (cfg == 1 || cfg == 2)) || (mode == M_GAP && cfg == 2); }
 
 // ---------------------------------------------------------------------------------------------
 // Depthwise convolution chain: one thread = one 16-byte channel vector of one output pixel.

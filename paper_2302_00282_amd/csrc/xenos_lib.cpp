@@ -101,6 +101,7 @@ struct Step {
   int cfg = 0, scalar = 0;
   int v_in = -1, v_in2 = -1, v_out = -1;
   long long w_off = -1, scale_off = -1, shift_off = -1, ktab_off = -1;   // byte offsets into the weight image
+  long long dw_w_off = -1, dw_scale_off = -1, dw_shift_off = -1;        // linked depthwise producer, if any
   double flops = 0;
   long long bytes_in = 0, bytes_w = 0, bytes_out = 0, bytes_res = 0;
   size_t lds = 0;
@@ -307,6 +308,17 @@ struct Planner {
   }
   bool need_export = false;
 
+  // A depthwise chain waiting to be linked into the pointwise convolution that consumes it (link level 3)
+  struct DwPro {
+    bool active = false;
+    int v_in = -1;
+    std::vector<int> ops;
+    long long w_off = -1, scale_off = -1, shift_off = -1;
+    int k = 0, stride = 0, pad = 0, H = 0, W = 0, relu = 0;
+    double flops = 0;
+    long long bytes_w = 0;
+  } dwpro;
+
   void touch(int view, int step) {
     Buffer& b = p.bufs[p.views[view].buf];
     b.first = std::min(b.first, step);
@@ -362,6 +374,7 @@ struct Planner {
       const TileCfg& tc = kTileCfgs[cfg];
       if (conv_lds_bytes(cfg, c.mode) > p.hw.lds_bytes_per_cu) continue;   // parameter split must fit private memory
       if (st.scalar && !conv_cfg_has_scalar_loader(cfg)) continue;
+      if (c.dw_w && !conv_cfg_has_dw_prologue(cfg, c.mode)) continue;
       ConvArgs t = c;
       if (c.mode == M_FLAT || c.mode == M_ZIGZAG) {
         t.tiles_m = (c.M_total + tc.bm - 1) / tc.bm;
@@ -385,7 +398,7 @@ struct Planner {
     }
     // halo-staged 3x3 kernel: a TH x TW block of output pixels (256 GEMM rows) x 128 channels per workgroup,
     // tiles laid over the images stacked with their padding rows
-    const bool halo_ok = c.R == 3 && c.S == 3 && c.stride == 1 && c.pad == 1 && !st.scalar && c.kchunk &&
+    const bool halo_ok = !c.dw_w && c.R == 3 && c.S == 3 && c.stride == 1 && c.pad == 1 && !st.scalar && c.kchunk &&
                          (c.mode == M_FLAT || (c.mode == M_ZIGZAG && c.H % 2 == 0 && c.W % 2 == 0)) &&
                          (long long)c.N * c.in_sN < (1ll << 31) && conv_lds_bytes(kHaloCfg, c.mode) <= p.hw.lds_bytes_per_cu &&
                          (p.opts.tile == 0 || p.opts.tile == kHaloCfg + 1);
@@ -653,6 +666,34 @@ struct Planner {
         int vin;
         xenos_status rc = need_internal_input(nd.in[0], st.name.c_str(), &vin);
         if (rc != XENOS_OK) return rc;
+        // link level 3: depthwise -> pointwise.  The depthwise result is produced tile by tile inside the
+        // pointwise kernel (as its A operand) and never written to memory.
+        const int pw = link >= 3 && !placed.count(cur) ? single_consumer(cur) : -1;
+        if (pw >= 0 && d.kh == d.kw && nodes[pw].kind == XENOS_OP_CONV) {
+          const xenos_op_desc& pd = desc(nodes[pw]);
+          if (pd.groups == 1 && pd.kh == 1 && pd.kw == 1 && pd.stride_h == 1 && pd.pad_h == 0 && node_step[pw] < 0 && p.opts.tile == 0) {
+            const int taps = d.kh * d.kw;
+            const size_t bytes = (size_t)taps * is.c * p.esz;
+            dwpro = DwPro{};
+            dwpro.active = true; dwpro.v_in = vin; dwpro.ops = st.ops;
+            dwpro.w_off = (long long)wpush(nullptr, bytes);
+            unsigned char* base = p.wimage.data() + dwpro.w_off;
+            for (int c = 0; c < is.c; ++c)
+              for (int t = 0; t < taps; ++t) {
+                const float v = go.weight[(size_t)c * taps + t];
+                if (p.dt == DT_BF16) ((uint16_t*)base)[(size_t)t * is.c + c] = f2bf_host(v);
+                else ((float*)base)[(size_t)t * is.c + c] = v;
+              }
+            push_affine(af, is.c, &dwpro.scale_off, &dwpro.shift_off);
+            dwpro.k = d.kh; dwpro.stride = d.stride_h; dwpro.pad = d.pad_h; dwpro.H = is.h; dwpro.W = is.w; dwpro.relu = relu;
+            dwpro.flops = 2.0 * is.n * tshape[i + 1].h * tshape[i + 1].w * is.c * taps;
+            dwpro.bytes_w = (long long)bytes;
+            const int mark = (int)p.steps.size();
+            node_step[i] = mark;
+            for (int a : absorbed) node_step[a] = mark;
+            return plan_node(pw);
+          }
+        }
         st.kind = S_DW;
         st.v_in = vin;
         finish(last, cur, false);
@@ -680,9 +721,13 @@ struct Planner {
         st.bytes_in = view_bytes(st.v_in); st.bytes_w = (long long)bytes; st.bytes_out = view_bytes(st.v_out);
       } else {
         st.kind = S_CONV;
-        const int vin = tview[nd.in[0]];
+        const bool from_dw = dwpro.active;
+        const DwPro pro = dwpro;
+        dwpro.active = false;
+        const int vin = from_dw ? pro.v_in : tview[nd.in[0]];
         if (vin < 0) return fail(XENOS_EINVAL, "%s: input not materialised", st.name.c_str());
         st.v_in = vin;
+        if (from_dw) st.ops.insert(st.ops.begin(), pro.ops.begin(), pro.ops.end());
         const View& iv = p.views[vin];
         ConvArgs& a = st.conv;
         a.N = is.n; a.C = std::max(is.c, iv.cphys); a.H = is.h; a.W = is.w;   // padding channels multiply zero weights
@@ -691,6 +736,13 @@ struct Planner {
         else { a.R = d.kh; a.S = d.kw; a.stride = d.stride_h; a.pad = d.pad_h; a.OH = tshape[i + 1].h; a.OW = tshape[i + 1].w; }
         st.scalar = !(iv.internal_nhwc() && !iv.f32 && iv.esz == p.esz && a.C % p.ce == 0 && iv.off % p.ce == 0 && iv.sP % p.ce == 0);
         a.in_sN = iv.sN; a.in_sH = iv.sP * is.w; a.in_sW = iv.sP; a.in_f32 = iv.f32;
+        if (from_dw) {
+          st.scalar = 0;
+          st.dw_w_off = pro.w_off; st.dw_scale_off = pro.scale_off; st.dw_shift_off = pro.shift_off;
+          a.dw_k = pro.k; a.dw_stride = pro.stride; a.dw_pad = pro.pad; a.dw_H = pro.H; a.dw_W = pro.W; a.dw_relu = pro.relu;
+          a.dw_sN = iv.sN; a.dw_sP = iv.sP;
+          a.dw_w = (const void*)1;           // marks the chain for the split planner; patched at launch
+        }
         a.relu = relu; a.has_res = has_res;
         if (has_res) {
           st.v_in2 = tview[res_tid];
@@ -738,7 +790,8 @@ struct Planner {
           const View& rv = p.views[st.v_in2];
           a.vec_res = K % p.ce == 0 && rv.off % p.ce == 0 && rv.sP % p.ce == 0 && rv.sN % p.ce == 0;
         }
-        st.flops = 2.0 * a.N * a.OH * a.OW * (double)K * a.R * a.S * is.c;
+        st.flops = 2.0 * a.N * a.OH * a.OW * (double)K * a.R * a.S * is.c + (from_dw ? pro.flops : 0.0);
+        if (from_dw) st.bytes_w += pro.bytes_w;
         st.bytes_in = view_bytes(st.v_in); st.bytes_out = view_bytes(st.v_out);
         if (has_res) st.bytes_res = view_bytes(st.v_in2);
       }
@@ -905,10 +958,10 @@ struct Planner {
         const TileCfg& tc = s.cfg == kHaloCfg ? halo_tc : kTileCfgs[s.cfg];
         snprintf(buf, sizeof buf, ",\"mode\":\"%s\",\"loader\":\"%s\",\"N\":%d,\"C\":%d,\"H\":%d,\"W\":%d,\"K\":%d,\"R\":%d,\"S\":%d,\"stride\":%d,"
                  "\"pad\":%d,\"OH\":%d,\"OW\":%d,\"PH\":%d,\"PW\":%d,\"pool\":%d,\"relu\":%d,\"res\":%d,\"bm\":%d,\"bn\":%d,\"tiles_m\":%d,"
-                 "\"tiles_n\":%d,\"grid\":%d,\"lds\":%zu,\"pph\":%d,\"ppw\":%d,\"patch_h\":%d,\"patch_w\":%d,\"out_c_off\":%lld,\"out_sP\":%lld,\"halo\":%d,\"th\":%d,\"tw\":%d",
+                 "\"tiles_n\":%d,\"grid\":%d,\"lds\":%zu,\"pph\":%d,\"ppw\":%d,\"patch_h\":%d,\"patch_w\":%d,\"out_c_off\":%lld,\"out_sP\":%lld,\"halo\":%d,\"th\":%d,\"tw\":%d,\"dw_linked\":%d",
                  kModeNames[c.mode], s.scalar ? "scalar" : "vector", c.N, c.C, c.H, c.W, c.K, c.R, c.S, c.stride, c.pad, c.OH, c.OW,
                  c.PH, c.PW, c.pool, c.relu, c.has_res, tc.bm, tc.bn, c.tiles_m, c.tiles_n, c.grid, s.lds, c.pph, c.ppw, c.patch_h,
-                 c.patch_w, p.views[s.v_out].off, c.out_sP, s.cfg == kHaloCfg ? 1 : 0, c.th, c.tw);
+                 c.patch_w, p.views[s.v_out].off, c.out_sP, s.cfg == kHaloCfg ? 1 : 0, c.th, c.tw, s.dw_w_off >= 0 ? 1 : 0);
         j += buf;
       }
       j += "}";
@@ -942,6 +995,9 @@ xenos_status launch_step(xenos_plan& p, const Step& s, const void* d_in, void* d
       a.scale = (const float*)(wb + s.scale_off);
       a.shift = (const float*)(wb + s.shift_off);
       a.ktab = s.ktab_off >= 0 ? (const int32_t*)(wb + s.ktab_off) : nullptr;
+      a.dw_w = s.dw_w_off >= 0 ? (const void*)(wb + s.dw_w_off) : nullptr;
+      a.dw_scale = s.dw_scale_off >= 0 ? (const float*)(wb + s.dw_scale_off) : nullptr;
+      a.dw_shift = s.dw_shift_off >= 0 ? (const float*)(wb + s.dw_shift_off) : nullptr;
       rc = launch_conv(a, p.dt, s.cfg, s.scalar, stream);
       break;
     }

@@ -183,6 +183,24 @@ def test_deterministic_run_to_run():
     assert np.array_equal(a, b)
 
 
+@pytest.mark.parametrize("compute", [0, 1])
+@pytest.mark.parametrize("stride,hw,c,k,tail", [(1, 13, 16, 24, ""), (2, 13, 32, 72, ""), (1, 7, 64, 40, "gap"), (2, 30, 24, 136, "gap")])
+def test_depthwise_pointwise_linked_on_chip(stride, hw, c, k, tail, compute):
+    # link level 3: the depthwise output is produced inside the pointwise kernel and never stored
+    b = wg.builder("dwpw", (3, c, hw, hw), 17, nonzero_bias=True)
+    t = b.cbr(0, c, 3, stride, 1, groups=c, name="dw")
+    t = b.cbr(t, k, 1, name="pw")
+    if tail == "gap":
+        t = b.gap(t)
+    g = b.finish(t)
+    ref = xo.forward(g)
+    y3, i3 = check(g, ref, compute=compute, link=3)
+    y2, i2 = check(g, ref, compute=compute, link=2)
+    assert i3["n_chains"] == i2["n_chains"] - 1 and any(ch.get("dw_linked") for ch in i3["chains"])
+    y3s, _ = run_gpu(g, compute=compute, link=3, split=0)
+    assert np.array_equal(y3, y3s)
+
+
 def test_graph_replay_matches_eager_every_time():
     # replayed several times with eager work and synchronisations in between; every replay must equal the eager result
     import torch
@@ -227,7 +245,7 @@ SMALL = [
 def test_reduced_networks_all_link_levels(builder, kw, compute):
     g = builder(batch=2, seed=21, nonzero_bias=True, **kw)
     ref = xo.forward(g)
-    for link in (2, 1, 0):
+    for link in (3, 2, 1, 0):
         check(g, ref, compute=compute, link=link)
 
 
@@ -237,3 +255,5 @@ def test_full_size_batch1(cfg, compute):
     ref = xo.forward(g)
     check(g, ref, compute=compute, link=2)
     check(g, ref, compute=compute, link=0)
+    if cfg == 1:
+        check(g, ref, compute=compute, link=3)
