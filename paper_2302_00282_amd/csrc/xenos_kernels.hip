@@ -205,14 +205,39 @@ __global__ __launch_bounds__(NT, 2) void conv_kernel(const ConvArgs a) {
       auto load_global = [&](int step, u32x4_t* ra, u32x4_t* rb, unsigned& okm) {
         const int bstep = step < nsteps ? step : nsteps - 1;      // steps past the end re-read valid weights
         if constexpr (DWPRO) {
-          // linked depthwise producer: this thread's CE channels of its pixels, nine taps, fp32 accumulate
+          // linked depthwise producer: this thread's CE channels of its pixels, fp32 accumulate.  All tap loads of
+          // a pixel are issued before any is used (out-of-range taps read a dummy address and are masked), so the
+          // step pays one memory latency, not one per tap.
           okm = ~0u;
+          const int kcc = kc < a.C ? kc : 0;
 #pragma unroll
           for (int it = 0; it < A_IT; ++it) {
             float d[CE];
 #pragma unroll
             for (int e = 0; e < CE; ++e) d[e] = 0.f;
-            if (kc < a.C && ih0[it] >= 0) {
+            const bool rowok = kc < a.C && ih0[it] >= 0;
+            if (a.dw_k == 3) {
+              u32x4_t xr[9], wr[9];
+              unsigned m = 0;
+#pragma unroll
+              for (int t9 = 0; t9 < 9; ++t9) {
+                const int ih = ih0[it] * a.dw_stride - a.dw_pad + t9 / 3, iw = iw0[it] * a.dw_stride - a.dw_pad + t9 % 3;
+                const bool ok = rowok && (unsigned)ih < (unsigned)a.dw_H && (unsigned)iw < (unsigned)a.dw_W;
+                const long long off = ok ? rbase[it] + ((long long)ih * a.dw_W + iw) * a.dw_sP + kcc : kcc;
+                xr[t9] = *(const u32x4_t*)((const T*)a.in + off);
+                wr[t9] = *(const u32x4_t*)((const T*)a.dw_w + (long long)t9 * a.C + kcc);
+                m |= (ok ? 1u : 0u) << t9;
+              }
+#pragma unroll
+              for (int t9 = 0; t9 < 9; ++t9) {
+                float x[CE], w[CE];
+                tr::unpack(xr[t9], x);
+                tr::unpack(wr[t9], w);
+                const float keep = ((m >> t9) & 1u) ? 1.f : 0.f;
+#pragma unroll
+                for (int e = 0; e < CE; ++e) d[e] = fmaf(x[e] * keep, w[e], d[e]);
+              }
+            } else if (rowok) {
               for (int r = 0; r < a.dw_k; ++r) {
                 const int ih = ih0[it] * a.dw_stride - a.dw_pad + r;
                 if ((unsigned)ih >= (unsigned)a.dw_H) continue;
@@ -226,11 +251,16 @@ __global__ __launch_bounds__(NT, 2) void conv_kernel(const ConvArgs a) {
                   for (int e = 0; e < CE; ++e) d[e] = fmaf(x[e], w[e], d[e]);
                 }
               }
+            }
+            if (rowok) {
 #pragma unroll
               for (int e = 0; e < CE; ++e) {
                 const float v = d[e] * a.dw_scale[kc + e] + a.dw_shift[kc + e];
                 d[e] = a.dw_relu ? fmaxf(v, 0.f) : v;
               }
+            } else {
+#pragma unroll
+              for (int e = 0; e < CE; ++e) d[e] = 0.f;
             }
             ra[it] = tr::pack(d);
           }
@@ -871,12 +901,11 @@ static int launch_conv_dwpro_inst(const ConvArgs& a, hipStream_t st) {
   return (int)hipGetLastError();
 }
 
-// linked depthwise -> pointwise chain: 1x1 / stride 1 / pad 0 consumer, FLAT or GAP rows, two tile shapes
+// linked depthwise -> pointwise chain: 1x1 / stride 1 / pad 0 consumer, FLAT or GAP rows, 64x64 tile
 template <typename T>
 static int launch_conv_dwpro_t(const ConvArgs& a, int cfg, hipStream_t st) {
   if (a.R != 1 || a.S != 1 || a.stride != 1 || a.pad != 0 || a.kchunk || a.C % Tr<T>::CE != 0 || !a.dw_w || a.dw_k < 1)
     return (int)hipErrorInvalidValue;
-  if (cfg == 1 && a.mode == M_FLAT) return launch_conv_dwpro_inst<T, 128, 64, 64, 32, M_FLAT>(a, st);
   if (cfg == 2 && a.mode == M_FLAT) return launch_conv_dwpro_inst<T, 64, 64, 32, 32, M_FLAT>(a, st);
   if (cfg == 2 && a.mode == M_GAP) return launch_conv_dwpro_inst<T, 64, 64, 32, 32, M_GAP>(a, st);
   return (int)hipErrorInvalidValue;
@@ -919,7 +948,7 @@ size_t conv_lds_bytes(int cfg, int /*mode*/) {
 }
 
 bool conv_cfg_has_scalar_loader(int cfg) { return cfg == 2; }
-bool conv_cfg_has_dw_prologue(int cfg, int mode) { return (mode == M_FLAT && (cfg == 1 || cfg == 2)) || (mode == M_GAP && cfg == 2); }
+bool conv_cfg_has_dw_prologue(int cfg, int mode) { return cfg == 2 && (mode == M_FLAT || mode == M_GAP); }
 
 // ---------------------------------------------------------------------------------------------
 // Depthwise convolution chain: one thread = one 16-byte channel vector of one output pixel.
