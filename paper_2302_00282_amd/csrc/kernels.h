@@ -66,9 +66,14 @@ struct ConvArgs {
   const void* dw_w; const float* dw_scale; const float* dw_shift;   // [k*k][C] compute type, folded scale / shift [C]
   int dw_k, dw_stride, dw_pad, dw_H, dw_W, dw_relu;
   long long dw_sN, dw_sP;
+  // reduction split across workgroups (ksplit > 1, M_FLAT only): share z covers steps [z*steps_per_split, ...) and
+  // writes raw fp32 sums to part[z][m][k] (row pitch part_ld); a splitk_finish pass completes the chain
+  int ksplit, steps_per_split, part_ld;
+  float* part;
   int th, tw, tiles_y, tiles_x;   // halo kernel: spatial tile and tile grid over the stacked padded rows n*(H+2)+oh
   int M_total;           // rows enumerated over the whole problem (FLAT, ZIGZAG); per-image rows for GAP
   int tiles_m, tiles_n, ntiles;
+  int xcd_m;             // dense-conv kernel: the 8 XCDs form an xcd_m x (8/xcd_m) grid over pixel tiles x (channel tiles x shares)
   int grid;              // workgroups launched (>= 1); tiles are visited with a stride of `grid`
 };
 
@@ -110,12 +115,22 @@ struct CvtArgs {
   int in_f32, out_f32;
 };
 
+struct SplitKArgs {
+  const float* part; int ksplit, part_ld;
+  int M, K, OHW;                     // rows (n*OH*OW), output channels, pixels per image
+  const float* scale; const float* shift;
+  const void* res; long long res_sN, res_sP;
+  void* out; long long out_sN, out_sP, out_sK;
+  int relu, out_f32;
+};
+
 // Launchers (defined in xenos_kernels.hip).  dtype = DT_*.  Return a hipError_t value as int.
 int launch_conv(const ConvArgs& a, int dtype, int cfg, int scalar_loader, void* stream);
 int launch_dw(const DwArgs& a, int dtype, void* stream);
 int launch_elt(const EltArgs& a, int dtype, void* stream);
 int launch_pool(const PoolArgs& a, int dtype, void* stream);
 int launch_cvt(const CvtArgs& a, int dtype, void* stream);
+int launch_splitk_finish(const SplitKArgs& a, int dtype, void* stream);
 size_t conv_lds_bytes(int cfg, int mode);
 bool conv_cfg_has_scalar_loader(int cfg);
 bool conv_cfg_has_dw_prologue(int cfg, int mode);

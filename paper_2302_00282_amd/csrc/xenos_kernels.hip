@@ -108,19 +108,31 @@ __global__ __launch_bounds__(NT, 2) void conv_kernel(const ConvArgs a) {
   const int wave_m = wave / WAVES_N, wave_n = wave % WAVES_N;
   const int l31 = lane & 31, lhalf = lane >> 5;
 
-  const int nsteps = a.Kred_pad / BKE;
+  const int nsteps_all = a.Kred_pad / BKE;
   const int OHW = a.OH * a.OW;
-  const int mchunk = (a.tiles_m + NUM_XCD - 1) / NUM_XCD;
-  const int slots = mchunk * NUM_XCD * a.tiles_n;
+  const int ksplit = a.ksplit > 1 ? a.ksplit : 1;                  // reduction split across workgroups (C/R/S split)
+  // Workgroups are dealt round-robin to the 8 XCDs.  The XCDs form an xm x (8/xm) grid over (pixel tiles) x
+  // (channel tiles x reduction shares); each owns a contiguous, balanced block of that space and walks its pixel
+  // tiles once per channel tile, so at any time the workgroups of one XCD share one weight slice in their L2 and
+  // neighbouring pixel tiles share their input halo.  xm = 8 when there are many pixel tiles; problems with few
+  // pixel tiles (batch 1, fully connected layers) spread the channel tiles over the XCDs instead.
+  const int xm = a.xcd_m, xn = NUM_XCD / xm;
+  const int NZ = a.tiles_n * ksplit;
+  const int mchunk = (a.tiles_m + xm - 1) / xm, zchunk = (NZ + xn - 1) / xn;
+  const int slots = mchunk * zchunk * NUM_XCD;
 
   for (int t = blockIdx.x; t < slots; t += gridDim.x) {
-    // Workgroups are dealt round-robin to the 8 XCDs.  Each XCD owns a contiguous range of pixel tiles and
-    // walks it once per output-channel tile, so at any time the workgroups of one XCD share one weight
-    // slice in their L2 and neighbouring pixel tiles share their input halo.
-    const int local = t / NUM_XCD;
-    const int tile_n = local / mchunk;
-    const int tile_m = (t % NUM_XCD) * mchunk + local % mchunk;
-    if (tile_m >= a.tiles_m) continue;                             // uniform per workgroup
+    const int xcd = t % NUM_XCD, j = t / NUM_XCD;
+    const int xi = xcd % xm, xj = xcd / xm;
+    const int m0 = xi * a.tiles_m / xm, m1 = (xi + 1) * a.tiles_m / xm;
+    const int z0 = xj * NZ / xn, z1 = (xj + 1) * NZ / xn;
+    const int lm = j % mchunk, lz = j / mchunk;
+    if (lm >= m1 - m0 || lz >= z1 - z0) continue;                  // uniform per workgroup
+    const int tile_m = m0 + lm;
+    const int tile_n = (z0 + lz) / ksplit, zsplit = (z0 + lz) % ksplit;
+    // this workgroup's share of the reduction steps: [s_begin, s_begin + nsteps)
+    const int s_begin = ksplit > 1 ? zsplit * a.steps_per_split : 0;
+    const int nsteps = ksplit > 1 ? (nsteps_all - s_begin < a.steps_per_split ? nsteps_all - s_begin : a.steps_per_split) : nsteps_all;
 
     // patch / gap geometry of this tile
     int img = 0, oy0 = 0, ox0 = 0, py = 0, px = 0;
@@ -175,9 +187,13 @@ __global__ __launch_bounds__(NT, 2) void conv_kernel(const ConvArgs a) {
       // reduction position (r, s, c) of this thread's 16-byte chunk
       int kc, kr, ks;
       {
-        const int kk = ch * CE;
-        if (a.kchunk) { kc = kk; ks = 0; kr = 0; }
-        else { kc = kk % a.C; const int rs = kk / a.C; ks = rs % a.S; kr = rs / a.S; }
+        if (a.kchunk) {
+          const int rs_n = a.R * a.S, cc = s_begin / rs_n, rs = s_begin - cc * rs_n;
+          kc = cc * BKE + ch * CE; kr = rs / a.S; ks = rs - kr * a.S;
+        } else {
+          const int kk = s_begin * BKE + ch * CE;
+          kc = kk % a.C; const int rs = kk / a.C; ks = rs % a.S; kr = rs / a.S;
+        }
       }
       const unsigned char* wrow[B_IT];
 #pragma unroll
@@ -203,7 +219,7 @@ __global__ __launch_bounds__(NT, 2) void conv_kernel(const ConvArgs a) {
       unsigned ok0 = 0, ok1 = 0;
 
       auto load_global = [&](int step, u32x4_t* ra, u32x4_t* rb, unsigned& okm) {
-        const int bstep = step < nsteps ? step : nsteps - 1;      // steps past the end re-read valid weights
+        const int bstep = s_begin + (step < nsteps ? step : nsteps - 1);   // steps past the end re-read valid weights
         if constexpr (DWPRO) {
           // linked depthwise producer: this thread's CE channels of its pixels, fp32 accumulate.  All tap loads of
           // a pixel are issued before any is used (out-of-range taps read a dummy address and are masked), so the
@@ -215,7 +231,7 @@ __global__ __launch_bounds__(NT, 2) void conv_kernel(const ConvArgs a) {
             float d[CE];
 #pragma unroll
             for (int e = 0; e < CE; ++e) d[e] = 0.f;
-            const bool rowok = kc < a.C && ih0[it] >= 0;
+            const bool rowok = step < nsteps && kc < a.C && ih0[it] >= 0;
             if (a.dw_k == 3) {
               u32x4_t xr[9], wr[9];
               unsigned m = 0;
@@ -266,7 +282,7 @@ __global__ __launch_bounds__(NT, 2) void conv_kernel(const ConvArgs a) {
           }
           kc += BKE;
         } else if constexpr (!SCALAR) {
-          const bool kok = kr < a.R && kc < a.C;                  // false for every step past the end
+          const bool kok = step < nsteps && kr < a.R && kc < a.C; // false for every step past the end of this share
           const long long koff = (long long)kr * a.in_sH + (long long)ks * a.in_sW + kc;
           okm = 0;
 #pragma unroll
@@ -391,7 +407,19 @@ __global__ __launch_bounds__(NT, 2) void conv_kernel(const ConvArgs a) {
 
       // Phase 2: each thread finishes CE consecutive channels of one output element: scale/shift, shortcut,
       // ReLU, pooling over the rows of its window, then one 16-byte store into the consumer's buffer.
-      if (MODE != M_GAP) {
+      if (MODE == M_FLAT && ksplit > 1) {
+        // reduction split: raw fp32 partial sums go to part[zsplit][m][k]; splitk_finish adds the shares in a fixed
+        // order and runs the rest of the chain
+        const int cg = tid % CG, col0 = cg * CE;
+        for (int idx = tid; idx < BM * CG; idx += NT) {
+          const int q = idx / CG, m = tile_m * BM + q;
+          if (m >= a.M_total) break;
+          float* dst = a.part + ((long long)zsplit * a.M_total + m) * a.part_ld + tile_n * BN + col0;
+          const float* sp = stg + q * SP + col0;
+#pragma unroll
+          for (int e = 0; e < CE; e += 4) *(f32x4_t*)(dst + e) = *(const f32x4_t*)(sp + e);
+        }
+      } else if (MODE != M_GAP) {
         const int nq = MODE == M_FLAT ? BM : MODE == M_ZIGZAG ? BM / 4 : a.pph * a.ppw;
         // NT is a multiple of CG, so a thread keeps its channel group over all its output elements: the
         // folded scale / shift are loaded once, outside the loop (the arrays are padded to the tile)
@@ -928,6 +956,9 @@ static int launch_conv_t(const ConvArgs& a, int cfg, int scalar, hipStream_t st)
 
 int launch_conv(const ConvArgs& a, int dtype, int cfg, int scalar_loader, void* stream) {
   hipStream_t st = (hipStream_t)stream;
+  if (a.grid < 1 || a.tiles_m < 1 || a.tiles_n < 1) return (int)hipErrorInvalidValue;
+  if (cfg != kHaloCfg && a.xcd_m != 1 && a.xcd_m != 2 && a.xcd_m != 4 && a.xcd_m != 8) return (int)hipErrorInvalidValue;
+  if (a.ksplit > 1 && (a.mode != M_FLAT || !a.part || a.steps_per_split < 1 || a.dw_w || cfg == kHaloCfg)) return (int)hipErrorInvalidValue;
   if (a.dw_w) {
     if (scalar_loader) return (int)hipErrorInvalidValue;
     return dtype == DT_BF16 ? launch_conv_dwpro_t<bf16_t>(a, cfg, st) : launch_conv_dwpro_t<float>(a, cfg, st);
@@ -1004,6 +1035,35 @@ int launch_dw(const DwArgs& a, int dtype, void* stream) {
   const int grid = grid_for(a.total_vec, NT);
   if (dtype == DT_BF16) hipLaunchKernelGGL(dw_kernel<bf16_t>, dim3(grid), dim3(NT), 0, st, a);
   else hipLaunchKernelGGL(dw_kernel<float>, dim3(grid), dim3(NT), 0, st, a);
+  return (int)hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------------
+// Second half of a reduction-split chain: sum the shares in index order, then scale/shift, shortcut, ReLU, store.
+// ---------------------------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(NT) void splitk_finish_kernel(const SplitKArgs a) {
+  using tr = Tr<T>;
+  const long long total = (long long)a.M * a.K;
+  for (long long idx = (long long)blockIdx.x * NT + threadIdx.x; idx < total; idx += (long long)gridDim.x * NT) {
+    const int k = (int)(idx % a.K);
+    const long long m = idx / a.K;
+    float v = 0.f;
+    for (int z = 0; z < a.ksplit; ++z) v += a.part[((long long)z * a.M + m) * a.part_ld + k];
+    v = v * a.scale[k] + a.shift[k];
+    const long long n = m / a.OHW, p = m - n * a.OHW;
+    if (a.res) v += tr::ld(a.res, n * a.res_sN + p * a.res_sP + k);
+    if (a.relu) v = fmaxf(v, 0.f);
+    const long long o = n * a.out_sN + p * a.out_sP + (long long)k * a.out_sK;
+    if (a.out_f32) ((float*)a.out)[o] = v; else tr::st(a.out, o, v);
+  }
+}
+
+int launch_splitk_finish(const SplitKArgs& a, int dtype, void* stream) {
+  hipStream_t st = (hipStream_t)stream;
+  const int grid = grid_for((long long)a.M * a.K, NT);
+  if (dtype == DT_BF16) hipLaunchKernelGGL(splitk_finish_kernel<bf16_t>, dim3(grid), dim3(NT), 0, st, a);
+  else hipLaunchKernelGGL(splitk_finish_kernel<float>, dim3(grid), dim3(NT), 0, st, a);
   return (int)hipGetLastError();
 }
 

@@ -66,8 +66,8 @@ struct xenos_graph {
 // ---------------------------------------------------------------------------------------------
 namespace {
 
-enum StepKind { S_CONV = 0, S_DW = 1, S_ELT = 2, S_POOL = 3, S_CVT = 4 };
-const char* kStepNames[] = {"conv", "dwconv", "elt", "pool", "cvt"};
+enum StepKind { S_CONV = 0, S_DW = 1, S_ELT = 2, S_POOL = 3, S_CVT = 4, S_SPLITK = 5 };
+const char* kStepNames[] = {"conv", "dwconv", "elt", "pool", "cvt", "splitk_finish"};
 const char* kModeNames[] = {"flat", "zigzag", "patch", "gap"};
 
 struct Buffer {
@@ -98,6 +98,7 @@ struct Step {
   EltArgs elt{};
   PoolArgs pool{};
   CvtArgs cvt{};
+  SplitKArgs splitk{};
   int cfg = 0, scalar = 0;
   int v_in = -1, v_in2 = -1, v_out = -1;
   long long w_off = -1, scale_off = -1, shift_off = -1, ktab_off = -1;   // byte offsets into the weight image
@@ -362,6 +363,27 @@ struct Planner {
     return best > 0;
   }
 
+  // Workgroup slots of a conv launch.  The dense-conv kernel deals its workgroups to an xcd_m x (8/xcd_m) grid of
+  // XCDs over pixel tiles x (channel tiles x reduction shares); pick the factorisation with the shortest longest
+  // queue, preferring the pixel split (workgroups of one XCD then share a weight slice).
+  void set_grid(ConvArgs& c, int cfg) {
+    const int ks = c.ksplit > 1 ? c.ksplit : 1;
+    if (cfg == kHaloCfg) {
+      c.xcd_m = 8;
+      c.grid = (c.tiles_m + 7) / 8 * 8 * c.tiles_n;
+    } else {
+      const int nz = c.tiles_n * ks;
+      long long best = -1;
+      for (int xm = 8; xm >= 1; xm /= 2) {
+        const int xn = 8 / xm;
+        const long long q = (long long)((c.tiles_m + xm - 1) / xm) * ((nz + xn - 1) / xn);
+        if (best < 0 || q < best) { best = q; c.xcd_m = xm; }
+      }
+      c.grid = (int)(best * 8);
+    }
+    if (!p.opts.split) c.grid = 1;
+  }
+
   xenos_status split_conv(Step& st) {
     ConvArgs& c = st.conv;
     const int num_cu = std::max(1, p.hw.num_cu);
@@ -431,8 +453,7 @@ struct Planner {
                               st.name.c_str(), p.hw.lds_bytes_per_cu);
     c = best_args;
     st.cfg = best;
-    const int slots = (c.tiles_m + 7) / 8 * 8 * c.tiles_n;      // 8 XCDs x (pixel tiles per XCD) x channel tiles
-    c.grid = p.opts.split ? slots : 1;
+    set_grid(c, best);
     st.lds = conv_lds_bytes(best, c.mode);
     return XENOS_OK;
   }
@@ -794,6 +815,45 @@ struct Planner {
         if (from_dw) st.bytes_w += pro.bytes_w;
         st.bytes_in = view_bytes(st.v_in); st.bytes_out = view_bytes(st.v_out);
         if (has_res) st.bytes_res = view_bytes(st.v_in2);
+
+        // Parameter split beyond K (Section 4.2.2: C, R, S splits need an extra reduction): when the outC x H/W
+        // partition leaves most compute units idle and the reduction is long, split it across workgroups too.
+        // Shares are summed in index order by a second pass, so the result does not depend on timing.
+        const int nsteps = a.Kred_pad / (kRowBytes / p.esz);
+        if (p.opts.split && st.cfg != kHaloCfg && a.mode == M_FLAT && !from_dw && a.ntiles * 2 <= p.hw.num_cu && nsteps >= 32) {
+          int ks = std::min({(2 * p.hw.num_cu + a.ntiles - 1) / a.ntiles, nsteps / 8, 32});
+          if (ks >= 4) {
+            const int spk = (nsteps + ks - 1) / ks;
+            ks = (nsteps + spk - 1) / spk;
+            const TileCfg& tc = kTileCfgs[st.cfg];
+            a.ksplit = ks; a.steps_per_split = spk; a.part_ld = a.tiles_n * tc.bn;
+            set_grid(a, st.cfg);
+            View pv;
+            pv.esz = 4; pv.f32 = 1; pv.s = Shape{1, 1, 1, 1};
+            const long long pbytes = (long long)ks * a.M_total * a.part_ld * 4;
+            pv.buf = new_buffer(pbytes, 0);
+            p.views.push_back(pv);
+            const int v_part = (int)p.views.size() - 1;
+            Step fin;
+            fin.kind = S_SPLITK; fin.name = st.name + ".sum";
+            fin.v_in = v_part; fin.v_in2 = st.v_in2; fin.v_out = st.v_out;
+            fin.scale_off = st.scale_off; fin.shift_off = st.shift_off;
+            SplitKArgs& f = fin.splitk;
+            f.ksplit = ks; f.part_ld = a.part_ld; f.M = a.M_total; f.K = K; f.OHW = a.OH * a.OW;
+            f.res_sN = a.res_sN; f.res_sP = a.res_sP;
+            f.out_sN = a.out_sN; f.out_sP = a.out_sP; f.out_sK = a.out_sK; f.relu = a.relu; f.out_f32 = a.out_f32;
+            fin.bytes_in = pbytes; fin.bytes_res = st.bytes_res; fin.bytes_out = st.bytes_out;
+            st.v_out = v_part; st.v_in2 = -1; a.has_res = 0;
+            st.bytes_out = pbytes; st.bytes_res = 0;
+            const int sidx = (int)p.steps.size();
+            node_step[i] = sidx + 1;
+            for (int ab : absorbed) node_step[ab] = sidx + 1;
+            node_final[last] = 1;
+            add_step(st);
+            add_step(fin);
+            return XENOS_OK;
+          }
+        }
       }
       const int sidx = (int)p.steps.size();
       node_step[i] = sidx;
@@ -958,10 +1018,10 @@ struct Planner {
         const TileCfg& tc = s.cfg == kHaloCfg ? halo_tc : kTileCfgs[s.cfg];
         snprintf(buf, sizeof buf, ",\"mode\":\"%s\",\"loader\":\"%s\",\"N\":%d,\"C\":%d,\"H\":%d,\"W\":%d,\"K\":%d,\"R\":%d,\"S\":%d,\"stride\":%d,"
                  "\"pad\":%d,\"OH\":%d,\"OW\":%d,\"PH\":%d,\"PW\":%d,\"pool\":%d,\"relu\":%d,\"res\":%d,\"bm\":%d,\"bn\":%d,\"tiles_m\":%d,"
-                 "\"tiles_n\":%d,\"grid\":%d,\"lds\":%zu,\"pph\":%d,\"ppw\":%d,\"patch_h\":%d,\"patch_w\":%d,\"out_c_off\":%lld,\"out_sP\":%lld,\"halo\":%d,\"th\":%d,\"tw\":%d,\"dw_linked\":%d",
+                 "\"tiles_n\":%d,\"grid\":%d,\"lds\":%zu,\"pph\":%d,\"ppw\":%d,\"patch_h\":%d,\"patch_w\":%d,\"out_c_off\":%lld,\"out_sP\":%lld,\"halo\":%d,\"th\":%d,\"tw\":%d,\"dw_linked\":%d,\"ksplit\":%d",
                  kModeNames[c.mode], s.scalar ? "scalar" : "vector", c.N, c.C, c.H, c.W, c.K, c.R, c.S, c.stride, c.pad, c.OH, c.OW,
                  c.PH, c.PW, c.pool, c.relu, c.has_res, tc.bm, tc.bn, c.tiles_m, c.tiles_n, c.grid, s.lds, c.pph, c.ppw, c.patch_h,
-                 c.patch_w, p.views[s.v_out].off, c.out_sP, s.cfg == kHaloCfg ? 1 : 0, c.th, c.tw, s.dw_w_off >= 0 ? 1 : 0);
+                 c.patch_w, p.views[s.v_out].off, c.out_sP, s.cfg == kHaloCfg ? 1 : 0, c.th, c.tw, s.dw_w_off >= 0 ? 1 : 0, c.ksplit > 1 ? c.ksplit : 1);
         j += buf;
       }
       j += "}";
@@ -995,6 +1055,7 @@ xenos_status launch_step(xenos_plan& p, const Step& s, const void* d_in, void* d
       a.scale = (const float*)(wb + s.scale_off);
       a.shift = (const float*)(wb + s.shift_off);
       a.ktab = s.ktab_off >= 0 ? (const int32_t*)(wb + s.ktab_off) : nullptr;
+      a.part = a.ksplit > 1 ? (float*)a.out : nullptr;
       a.dw_w = s.dw_w_off >= 0 ? (const void*)(wb + s.dw_w_off) : nullptr;
       a.dw_scale = s.dw_scale_off >= 0 ? (const float*)(wb + s.dw_scale_off) : nullptr;
       a.dw_shift = s.dw_shift_off >= 0 ? (const float*)(wb + s.dw_shift_off) : nullptr;
@@ -1026,6 +1087,16 @@ xenos_status launch_step(xenos_plan& p, const Step& s, const void* d_in, void* d
       a.in = view_ptr(p, s.v_in, d_in, d_out);
       a.out = (void*)view_ptr(p, s.v_out, d_in, d_out);
       rc = launch_pool(a, p.dt, stream);
+      break;
+    }
+    case S_SPLITK: {
+      SplitKArgs a = s.splitk;
+      a.part = (const float*)view_ptr(p, s.v_in, d_in, d_out);
+      a.res = s.v_in2 >= 0 ? view_ptr(p, s.v_in2, d_in, d_out) : nullptr;
+      a.out = (void*)view_ptr(p, s.v_out, d_in, d_out);
+      a.scale = (const float*)(wb + s.scale_off);
+      a.shift = (const float*)(wb + s.shift_off);
+      rc = launch_splitk_finish(a, p.dt, stream);
       break;
     }
     case S_CVT: {

@@ -113,9 +113,12 @@ def test_every_operator_runs_exactly_once(cfg, batch):
 
 
 def test_linking_patterns_of_the_workloads():
-    res = plan_json(wg.build(2, 1, draw=False), link=2, compute=X.XENOS_BF16)["plan"]
+    g2 = wg.build(2, 1, draw=False)
+    res = plan_json(g2, link=2, compute=X.XENOS_BF16)["plan"]
     convs = [c for c in res["chains"] if c["kind"] == "conv"]
-    assert sum(c["res"] for c in convs) == 8                   # every shortcut add runs in a conv epilogue
+    # every shortcut add is executed by a conv chain (in its epilogue, or in the summing pass of a reduction split)
+    assert sum(any(g2.ops[o].kind == "add" for o in c["ops"]) for c in convs) == 8
+    assert all(c["kind"] in ("conv", "splitk_finish") for c in res["chains"])
     assert convs[0]["mode"] == "patch" and convs[0]["pool"] == 1      # stem conv + 3x3/2 max-pool
     assert convs[-2]["mode"] == "gap"                          # last block + global average (CBRA)
     sq = plan_json(wg.build(4, 1, draw=False), link=2, compute=X.XENOS_BF16)["plan"]

@@ -201,6 +201,29 @@ def test_depthwise_pointwise_linked_on_chip(stride, hw, c, k, tail, compute):
     assert np.array_equal(y3, y3s)
 
 
+@pytest.mark.parametrize("compute", [0, 1])
+@pytest.mark.parametrize("kind", ["fc_big", "conv3_deep", "shortcut_deep"])
+def test_reduction_split_across_workgroups(kind, compute):
+    # few output tiles and a long reduction: the planner also splits C/R/S across workgroups and sums the shares in
+    # a second pass (Section 4.2.2: such splits need an additional reduction)
+    if kind == "fc_big":
+        b = wg.builder(kind, (4, 96, 6, 6), 23, nonzero_bias=True)
+        t = b.fc(b.relu(b.fc(0, 200, "fc1")), 24, "fc2")
+    elif kind == "conv3_deep":
+        b = wg.builder(kind, (1, 320, 7, 7), 23, nonzero_bias=True)
+        t = b.cbr(0, 72, 3, 1, 1, name="c")
+    else:
+        b = wg.builder(kind, (1, 256, 6, 6), 23, nonzero_bias=True)
+        u = b.cbr(0, 256, 3, 1, 1, name="c1")
+        v = b.cbr(u, 256, 3, 1, 1, name="c2", relu=False)
+        t = b.relu(b.add(v, u))
+    g = b.finish(t)
+    y, info = check(g, compute=compute)
+    assert any(ch["kind"] == "splitk_finish" for ch in info["chains"])
+    y2, _ = run_gpu(g, compute=compute)
+    assert np.array_equal(y, y2)                       # fixed summation order: run-to-run identical
+
+
 def test_graph_replay_matches_eager_every_time():
     # replayed several times with eager work and synchronisations in between; every replay must equal the eager result
     import torch
