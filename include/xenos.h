@@ -100,7 +100,8 @@ typedef struct {
  * split: 0 = every chain runs on ONE compute unit (no operator split; for tests)
  *        1 = DSP-aware operator split (Section 4.2): output channels first, then H/W
  * compute: element type of activations and weights in HBM; accumulation is always fp32.
- * tile: 0 = planner's choice, otherwise forces tile configuration tile-1 (tests, tuning). */
+ * tile: 0 = planner's choice; 1..4 force a tile shape of the general conv kernel, 5 the halo-staged 3x3 kernel,
+ *       6 the first-layer kernel, for every chain they apply to (tests, tuning). */
 typedef struct {
   int link;
   int split;

@@ -26,11 +26,12 @@ typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;
 struct bf16_t { uint16_t v; };
 
 __device__ __forceinline__ float bf2f(uint16_t v) { return __uint_as_float(((uint32_t)v) << 16); }
-// round-to-nearest-even; inputs are finite by contract
-__device__ __forceinline__ uint16_t f2bf(float f) {
-  uint32_t u = __float_as_uint(f);
-  u += 0x7fffu + ((u >> 16) & 1u);
-  return (uint16_t)(u >> 16);
+// fp32 -> bf16, round-to-nearest-even: gfx950 converts in hardware (one packed instruction per two values)
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
+typedef __attribute__((ext_vector_type(2))) float f32x2_t;
+__device__ __forceinline__ uint16_t f2bf(float f) { return __builtin_bit_cast(uint16_t, (__bf16)f); }
+__device__ __forceinline__ uint32_t f2bf2(float lo, float hi) {
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector((f32x2_t){lo, hi}, bf16x2_t));
 }
 
 template <typename T> struct Tr;
@@ -65,7 +66,7 @@ template <> struct Tr<bf16_t> {
   __device__ static __forceinline__ u32x4_t pack(const float* f) {
     u32x4_t v;
 #pragma unroll
-    for (int e = 0; e < 4; ++e) v[e] = (uint32_t)f2bf(f[2 * e]) | ((uint32_t)f2bf(f[2 * e + 1]) << 16);
+    for (int e = 0; e < 4; ++e) v[e] = f2bf2(f[2 * e], f[2 * e + 1]);
     return v;
   }
 };
@@ -888,6 +889,170 @@ static int launch_conv3x3_t(const ConvArgs& a, hipStream_t st) {
   return (int)hipErrorInvalidValue;
 }
 
+// ---------------------------------------------------------------------------------------------
+// First-layer chain: a dense convolution whose whole reduction C*R*S fits one 32-deep MFMA pass (the 3-channel
+// image layer), reading the caller's graph input where it lies (any strides, fp32 or the compute type) and
+// writing the consumer's NHWC layout: the layout transform at the graph boundary (transpose operator, Table 3)
+// is linked into its consumer (Section 4.1), so the input is read once and no converted copy is written.
+//
+// The GEMM is computed transposed (rows = output channels, columns = pixels): in the MFMA accumulator layout a
+// lane then owns 4 consecutive channels of one pixel, which it scales, shifts, clamps and stores directly.
+// One wavefront = 32 consecutive output pixels x all K = 32*KB channels; lane (p, h) holds the reduction slots
+// k(i) = (i/8)*16 + h*8 + i%8, i = 0..15, of pixel p (bf16: two 8-element MFMA operands; fp32: 16 single ones).
+// ---------------------------------------------------------------------------------------------
+template <typename T, int KB>
+__global__ __launch_bounds__(NT, 4) void stem_kernel(const ConvArgs a) {
+  using tr = Tr<T>;
+  __shared__ __align__(16) float s_scale[KB * 32];
+  __shared__ __align__(16) float s_shift[KB * 32];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l31 = lane & 31, h = lane >> 5;
+  constexpr int CPP = KB * 32 * (int)sizeof(T) / 16;                 // 16-byte chunks per output pixel
+  constexpr int PPI = 64 / CPP;                                      // pixels per store instruction
+  constexpr int SPITCH = KB * 32 * (int)sizeof(T) + 16;              // staging row pitch (odd number of 16-byte slots)
+  __shared__ __align__(16) unsigned char s_stage[(NT / 64) * 32 * SPITCH];
+  __shared__ int2 s_tab[2][16];                                     // per lane half and slot: {input offset, (r << 16) | s}
+  if (tid < KB * 32) { s_scale[tid] = a.scale[tid]; s_shift[tid] = a.shift[tid]; }
+  if (tid < 32) {
+    const int hh = tid >> 4, i = tid & 15, k = (i / 8) * 16 + hh * 8 + i % 8;
+    s_tab[hh][i] = make_int2(a.ktab[2 * k], a.ktab[2 * k + 1]);
+  }
+  __syncthreads();
+  // weight operands: channel 32*b + l31, the same reduction slots
+  constexpr int WV = sizeof(T) == 2 ? 1 : 2;                         // 16-byte vectors per 8 elements
+  u32x4_t wf[KB][2][WV];
+#pragma unroll
+  for (int b = 0; b < KB; ++b)
+#pragma unroll
+    for (int q = 0; q < 2; ++q)
+#pragma unroll
+      for (int v = 0; v < WV; ++v)
+        wf[b][q][v] = *(const u32x4_t*)((const unsigned char*)a.w +
+                                        ((size_t)(32 * b + l31) * a.Kred_pad + q * 16 + h * 8) * sizeof(T) + v * 16);
+
+  const int OHW = a.OH * a.OW, nblk = a.tiles_m, bstride = gridDim.x * (NT / 64);
+  auto gather = [&](int blk, float* v) {
+    const int m = blk * 32 + l31;
+    const bool valid = m < a.M_total;
+    const int mm = valid ? m : 0;
+    const int n = mm / OHW, p = mm - n * OHW, oy = p / a.OW, ox = p - oy * a.OW;
+    const int iy0 = oy * a.stride - a.pad, ix0 = ox * a.stride - a.pad;
+    const long long base = (long long)n * a.in_sN + (long long)iy0 * a.in_sH + (long long)ix0 * a.in_sW;
+    // blocks whose 32 windows lie inside the image (most of them) skip the per-tap bounds tests
+    const bool inside = valid && iy0 >= 0 && ix0 >= 0 && iy0 + a.R <= a.H && ix0 + a.S <= a.W;
+    if (__all(inside)) {
+      if (a.in_f32) {
+        const float* pb = (const float*)a.in + base;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          const int2 t = s_tab[h][i];
+          const float x = pb[(t.y >> 16) < a.R ? t.x : 0];            // padding slots of the reduction read a valid address ...
+          v[i] = (t.y >> 16) < a.R ? x : 0.f;                          // ... and contribute zero
+        }
+      } else {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          const int2 t = s_tab[h][i];
+          const float x = tr::ld(a.in, base + ((t.y >> 16) < a.R ? t.x : 0));
+          v[i] = (t.y >> 16) < a.R ? x : 0.f;
+        }
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const int2 t = s_tab[h][i];
+        const bool ok = valid && (unsigned)(iy0 + (t.y >> 16)) < (unsigned)a.H && (unsigned)(ix0 + (t.y & 0xffff)) < (unsigned)a.W;
+        const long long idx = ok ? base + t.x : 0;
+        const float x = a.in_f32 ? ((const float*)a.in)[idx] : tr::ld(a.in, idx);
+        v[i] = ok ? x : 0.f;
+      }
+    }
+  };
+
+  int blk = blockIdx.x * (NT / 64) + wave;
+  float vn[16];
+  if (blk < nblk) gather(blk, vn);
+  for (; blk < nblk; blk += bstride) {
+    f32x16_t acc[KB];
+#pragma unroll
+    for (int b = 0; b < KB; ++b)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[b][e] = 0.f;
+    if constexpr (sizeof(T) == 2) {
+      const u32x4_t p0 = tr::pack(vn), p1 = tr::pack(vn + 8);      // round the image to the compute type
+      if (blk + bstride < nblk) gather(blk + bstride, vn);
+#pragma unroll
+      for (int b = 0; b < KB; ++b) {
+        acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, wf[b][0][0]),
+                                                         __builtin_bit_cast(bf16x8_t, p0), acc[b], 0, 0, 0);
+        acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, wf[b][1][0]),
+                                                         __builtin_bit_cast(bf16x8_t, p1), acc[b], 0, 0, 0);
+      }
+    } else {
+      float v[16];
+#pragma unroll
+      for (int i = 0; i < 16; ++i) v[i] = vn[i];
+      if (blk + bstride < nblk) gather(blk + bstride, vn);
+#pragma unroll
+      for (int b = 0; b < KB; ++b)
+#pragma unroll
+        for (int i = 0; i < 16; ++i)
+          acc[b] = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(wf[b][i / 8][(i % 8) / 4][i % 4]), v[i], acc[b], 0, 0, 0);
+    }
+    // epilogue: lane = pixel l31, channels 32*b + 8*g + 4*h + (0..3) in accumulator elements 4*g + (0..3).  The
+    // finished values are transposed through this wavefront's LDS slice so that every store instruction writes
+    // whole pixels (contiguous K*sizeof(T)-byte rows) instead of 4-channel fragments of 32 different pixels.
+    unsigned char* stg = s_stage + wave * (32 * SPITCH);
+#pragma unroll
+    for (int b = 0; b < KB; ++b)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const int c0 = 32 * b + 8 * g + 4 * h;
+        const f32x4_t sc = *(const f32x4_t*)&s_scale[c0], sh = *(const f32x4_t*)&s_shift[c0];
+        float y[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          y[j] = acc[b][4 * g + j] * sc[j] + sh[j];
+          if (a.relu) y[j] = fmaxf(y[j], 0.f);
+        }
+        if constexpr (sizeof(T) == 2) {
+          uint2 o;
+          o.x = f2bf2(y[0], y[1]);
+          o.y = f2bf2(y[2], y[3]);
+          *(uint2*)(stg + l31 * SPITCH + c0 * 2) = o;
+        } else {
+          *(f32x4_t*)(stg + l31 * SPITCH + c0 * 4) = f32x4_t{y[0], y[1], y[2], y[3]};
+        }
+      }
+    __builtin_amdgcn_wave_barrier();
+#pragma unroll
+    for (int it = 0; it < 32 / PPI; ++it) {
+      const int px = it * PPI + lane / CPP, ch = lane % CPP;
+      const u32x4_t o = *(const u32x4_t*)(stg + px * SPITCH + ch * 16);
+      const int m = blk * 32 + px;
+      if (m < a.M_total) {
+        const int n = m / OHW, p = m - n * OHW;
+        *(u32x4_t*)((unsigned char*)a.out + ((long long)n * a.out_sN + (long long)p * a.out_sP) * (long long)sizeof(T) + ch * 16) = o;
+      }
+    }
+    __builtin_amdgcn_wave_barrier();
+  }
+}
+
+template <typename T>
+static int launch_stem_t(const ConvArgs& a, hipStream_t st) {
+  // what the kernel assumes: one 32-deep pass, K = 32 or 64, pixel-major rows, plain chain, aligned NHWC output
+  const int esz = (int)sizeof(T);
+  if (a.Kred > 32 || a.Kred_pad < 32 || !a.ktab || a.mode != M_FLAT || a.has_res || a.pool != POOL_NONE || a.dw_w || a.ksplit > 1 ||
+      a.out_sK != 1 || (a.out_f32 && esz != 4) || (a.out_sP * esz) % 16 != 0 || (a.out_sN * esz) % 16 != 0 ||
+      ((uintptr_t)a.out & 15) || ((uintptr_t)a.w & 15) || (a.Kred_pad * esz) % 16 != 0 || a.H > 8192 ||
+      a.tiles_m != (a.M_total + 31) / 32 || a.M_total != a.N * a.OH * a.OW)
+    return (int)hipErrorInvalidValue;
+  if (a.K == 32) hipLaunchKernelGGL((stem_kernel<T, 1>), dim3(a.grid), dim3(NT), 0, st, a);
+  else if (a.K == 64) hipLaunchKernelGGL((stem_kernel<T, 2>), dim3(a.grid), dim3(NT), 0, st, a);
+  else return (int)hipErrorInvalidValue;
+  return (int)hipGetLastError();
+}
+
 template <typename T, int BM, int BN, int WM, int WN, bool SCALAR, int MODE>
 static int launch_conv_inst(const ConvArgs& a, hipStream_t st) {
   constexpr int lds = lds_conv_bytes<BM, BN>();
@@ -957,7 +1122,7 @@ static int launch_conv_t(const ConvArgs& a, int cfg, int scalar, hipStream_t st)
 int launch_conv(const ConvArgs& a, int dtype, int cfg, int scalar_loader, void* stream) {
   hipStream_t st = (hipStream_t)stream;
   if (a.grid < 1 || a.tiles_m < 1 || a.tiles_n < 1) return (int)hipErrorInvalidValue;
-  if (cfg != kHaloCfg && a.xcd_m != 1 && a.xcd_m != 2 && a.xcd_m != 4 && a.xcd_m != 8) return (int)hipErrorInvalidValue;
+  if (cfg < kHaloCfg && a.xcd_m != 1 && a.xcd_m != 2 && a.xcd_m != 4 && a.xcd_m != 8) return (int)hipErrorInvalidValue;
   if (a.ksplit > 1 && (a.mode != M_FLAT || !a.part || a.steps_per_split < 1 || a.dw_w || cfg == kHaloCfg)) return (int)hipErrorInvalidValue;
   if (a.dw_w) {
     if (scalar_loader) return (int)hipErrorInvalidValue;
@@ -967,11 +1132,13 @@ int launch_conv(const ConvArgs& a, int dtype, int cfg, int scalar_loader, void* 
     if (scalar_loader) return (int)hipErrorInvalidValue;
     return dtype == DT_BF16 ? launch_conv3x3_t<bf16_t>(a, st) : launch_conv3x3_t<float>(a, st);
   }
+  if (cfg == kStemCfg) return dtype == DT_BF16 ? launch_stem_t<bf16_t>(a, st) : launch_stem_t<float>(a, st);
   return dtype == DT_BF16 ? launch_conv_t<bf16_t>(a, cfg, scalar_loader, st) : launch_conv_t<float>(a, cfg, scalar_loader, st);
 }
 
 size_t conv_lds_bytes(int cfg, int /*mode*/) {
   if (cfg == kHaloCfg) return V2_LDS;
+  if (cfg == kStemCfg) return 40 * 1024;   // static: staging slices (at most 4 x 32 x 272 bytes) + tables
   const TileCfg& c = kTileCfgs[cfg];
   const size_t main_b = (size_t)2 * (c.bm + c.bn) * LDS_ROW;
   const size_t stg_b = (size_t)c.bm * (c.bn + STG_PAD) * 4;

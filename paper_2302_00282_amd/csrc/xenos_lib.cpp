@@ -99,7 +99,7 @@ struct Step {
   PoolArgs pool{};
   CvtArgs cvt{};
   SplitKArgs splitk{};
-  int cfg = 0, scalar = 0;
+  int cfg = 0, scalar = 0, stem = 0;
   int v_in = -1, v_in2 = -1, v_out = -1;
   long long w_off = -1, scale_off = -1, shift_off = -1, ktab_off = -1;   // byte offsets into the weight image
   long long dw_w_off = -1, dw_scale_off = -1, dw_shift_off = -1;        // linked depthwise producer, if any
@@ -310,6 +310,8 @@ struct Planner {
   bool need_export = false;
 
   // A depthwise chain waiting to be linked into the pointwise convolution that consumes it (link level 3)
+  bool in_lazy = false, in_all_dense = false, in_gather = false;   // graph input not yet imported; see plan()
+
   struct DwPro {
     bool active = false;
     int v_in = -1;
@@ -387,6 +389,13 @@ struct Planner {
   xenos_status split_conv(Step& st) {
     ConvArgs& c = st.conv;
     const int num_cu = std::max(1, p.hw.num_cu);
+    if (st.stem) {   // one wavefront = 32 pixels x all channels; workgroups of 4 wavefronts stride over the pixel blocks
+      c.tiles_m = (c.M_total + 31) / 32; c.tiles_n = 1; c.ntiles = c.tiles_m; c.xcd_m = 8;
+      c.grid = p.opts.split ? std::max(1, std::min((c.tiles_m + 3) / 4, 4 * num_cu)) : 1;   // 4 resident workgroups per unit
+      st.cfg = kStemCfg;
+      st.lds = conv_lds_bytes(kStemCfg, c.mode);
+      return XENOS_OK;
+    }
     static const double eff[kNumTileCfgs] = {1.0, 0.85, 0.6, 0.55};
     double best_cost = 1e300;
     int best = -1;
@@ -535,29 +544,17 @@ struct Planner {
         if (!(nd.kind == XENOS_OP_CONV && desc(nd).groups == 1)) all_dense = false;
       }
       const int ev = ext_view(p.in, 1);
-      // small inputs: the first convolution gathers straight from the caller's tensor (one pass fewer);
-      // large inputs: a conversion pass pays for itself because the first layer then runs on the vector loader
-      const bool gather_direct = all_dense && p.in.c <= 8 && (long long)p.in.n * p.in.h * p.in.w < 100000;
+      tview[0] = ev;
       if (direct) {
         normalise_1x1(p.views[ev]);
         p.views[ev].f32 = 0;
-        tview[0] = ev;
-      } else if (gather_direct) {
-        tview[0] = ev;
       } else {
-        // import: convert to the internal NHWC layout of the compute type.  When only dense convolutions read
-        // the input (the usual 3-channel image), the channels are zero-padded to a whole 16-byte group so that
-        // the first layer runs on the vector loader like every other layer (its padded weights are zero).
-        const int cpad = all_dense ? (p.in.c + p.ce - 1) / p.ce * p.ce : p.in.c;
-        const int iv = internal_view(tshape[0], -1, cpad);
-        p.views[iv].cphys = cpad;
-        Step st;
-        st.kind = S_CVT; st.name = "import";
-        st.v_in = ev; st.v_out = iv;
-        fill_cvt(st);
-        st.cvt.Cout = cpad;
-        add_step(st);
-        tview[0] = iv;
+        // Otherwise each consumer decides when it is planned.  A first-layer chain whose reduction fits one MFMA
+        // pass reads the caller's tensor where it lies (stem kernel); with small inputs any dense convolution
+        // gathers from it element-wise (one pass fewer); everything else triggers one import pass.
+        in_lazy = true;
+        in_all_dense = all_dense;
+        in_gather = all_dense && p.in.c <= 8 && (long long)p.in.n * p.in.h * p.in.w < 100000;
       }
     }
 
@@ -610,6 +607,24 @@ struct Planner {
     return consumers[tid][0];
   }
 
+  // import: convert the graph input to the internal NHWC layout of the compute type.  When only dense
+  // convolutions read it (the usual 3-channel image), the channels are zero-padded to a whole 16-byte group so
+  // that the first layer runs on the vector loader like every other layer (its padded weights are zero).
+  int import_input() {
+    const int cpad = in_all_dense ? (p.in.c + p.ce - 1) / p.ce * p.ce : p.in.c;
+    const int iv = internal_view(tshape[0], -1, cpad);
+    p.views[iv].cphys = cpad;
+    Step st;
+    st.kind = S_CVT; st.name = "import";
+    st.v_in = tview[0]; st.v_out = iv;
+    fill_cvt(st);
+    st.cvt.Cout = cpad;
+    add_step(st);
+    tview[0] = iv;
+    in_lazy = false;
+    return iv;
+  }
+
   xenos_status need_internal_input(int tid, const char* who, int* view) {
     const int v = tview[tid];
     if (v < 0) return fail(XENOS_EINVAL, "%s: input tensor %d is not materialised", who, tid);
@@ -617,14 +632,7 @@ struct Planner {
     if (!vw.internal_nhwc() || vw.f32 != 0 || vw.esz != p.esz) {
       // the graph input reaches an operator that needs the internal layout: import once
       if (tid != 0) return fail(XENOS_EUNSUPPORTED, "%s: tensor %d has no internal layout", who, tid);
-      const int iv = internal_view(tshape[0]);
-      Step st;
-      st.kind = S_CVT; st.name = "import";
-      st.v_in = v; st.v_out = iv;
-      fill_cvt(st);
-      add_step(st);
-      tview[0] = iv;
-      *view = iv;
+      *view = import_input();
       return XENOS_OK;
     }
     *view = v;
@@ -745,6 +753,11 @@ struct Planner {
         const bool from_dw = dwpro.active;
         const DwPro pro = dwpro;
         dwpro.active = false;
+        if (!from_dw && nd.in[0] == 0 && in_lazy) {
+          st.stem = link >= 2 && !is_fc && pool_node < 0 && !has_res && is.c * d.kh * d.kw <= kStemRed && (K == 32 || K == 64) &&
+                    cur != out_tid && !placed.count(cur) && is.h <= 8192 && (p.opts.tile == 0 || p.opts.tile == kStemCfg + 1);
+          if (!st.stem && !in_gather) import_input();
+        }
         const int vin = from_dw ? pro.v_in : tview[nd.in[0]];
         if (vin < 0) return fail(XENOS_EINVAL, "%s: input not materialised", st.name.c_str());
         st.v_in = vin;
@@ -820,7 +833,7 @@ struct Planner {
         // partition leaves most compute units idle and the reduction is long, split it across workgroups too.
         // Shares are summed in index order by a second pass, so the result does not depend on timing.
         const int nsteps = a.Kred_pad / (kRowBytes / p.esz);
-        if (p.opts.split && st.cfg != kHaloCfg && a.mode == M_FLAT && !from_dw && a.ntiles * 2 <= p.hw.num_cu && nsteps >= 32) {
+        if (p.opts.split && st.cfg < kHaloCfg && a.mode == M_FLAT && !from_dw && a.ntiles * 2 <= p.hw.num_cu && nsteps >= 32) {
           int ks = std::min({(2 * p.hw.num_cu + a.ntiles - 1) / a.ntiles, nsteps / 8, 32});
           if (ks >= 4) {
             const int spk = (nsteps + ks - 1) / ks;
@@ -1015,11 +1028,12 @@ struct Planner {
       if (s.kind == S_CONV) {
         const ConvArgs& c = s.conv;
         const TileCfg halo_tc{kHaloRows, kHaloCols, 64, 64};
-        const TileCfg& tc = s.cfg == kHaloCfg ? halo_tc : kTileCfgs[s.cfg];
+        const TileCfg stem_tc{32, c.K, 32, c.K};
+        const TileCfg& tc = s.cfg == kHaloCfg ? halo_tc : s.cfg == kStemCfg ? stem_tc : kTileCfgs[s.cfg];
         snprintf(buf, sizeof buf, ",\"mode\":\"%s\",\"loader\":\"%s\",\"N\":%d,\"C\":%d,\"H\":%d,\"W\":%d,\"K\":%d,\"R\":%d,\"S\":%d,\"stride\":%d,"
                  "\"pad\":%d,\"OH\":%d,\"OW\":%d,\"PH\":%d,\"PW\":%d,\"pool\":%d,\"relu\":%d,\"res\":%d,\"bm\":%d,\"bn\":%d,\"tiles_m\":%d,"
                  "\"tiles_n\":%d,\"grid\":%d,\"lds\":%zu,\"pph\":%d,\"ppw\":%d,\"patch_h\":%d,\"patch_w\":%d,\"out_c_off\":%lld,\"out_sP\":%lld,\"halo\":%d,\"th\":%d,\"tw\":%d,\"dw_linked\":%d,\"ksplit\":%d",
-                 kModeNames[c.mode], s.scalar ? "scalar" : "vector", c.N, c.C, c.H, c.W, c.K, c.R, c.S, c.stride, c.pad, c.OH, c.OW,
+                 kModeNames[c.mode], s.stem ? "stem" : s.scalar ? "scalar" : "vector", c.N, c.C, c.H, c.W, c.K, c.R, c.S, c.stride, c.pad, c.OH, c.OW,
                  c.PH, c.PW, c.pool, c.relu, c.has_res, tc.bm, tc.bn, c.tiles_m, c.tiles_n, c.grid, s.lds, c.pph, c.ppw, c.patch_h,
                  c.patch_w, p.views[s.v_out].off, c.out_sP, s.cfg == kHaloCfg ? 1 : 0, c.th, c.tw, s.dw_w_off >= 0 ? 1 : 0, c.ksplit > 1 ? c.ksplit : 1);
         j += buf;
@@ -1234,7 +1248,7 @@ xenos_status xenos_graph_create(const xenos_tensor_desc* input, const xenos_op_d
 
 xenos_status xenos_plan_link_split(const xenos_graph* graph, const xenos_hw_info* hw, const xenos_plan_opts* opts, xenos_plan** out) {
   if (!graph || !hw || !opts || !out || graph->magic != MAGIC_GRAPH) return fail(XENOS_EINVAL, "xenos_plan_link_split: bad argument");
-  if (opts->link < 0 || opts->link > 3 || opts->tile < 0 || opts->tile > kNumTileCfgs + 1 || (opts->compute != XENOS_F32 && opts->compute != XENOS_BF16))
+  if (opts->link < 0 || opts->link > 3 || opts->tile < 0 || opts->tile > kNumTileCfgs + 2 || (opts->compute != XENOS_F32 && opts->compute != XENOS_BF16))
     return fail(XENOS_EINVAL, "xenos_plan_link_split: option out of range");
   if (hw->num_cu <= 0 || hw->lds_bytes_per_cu == 0) return fail(XENOS_EINVAL, "xenos_plan_link_split: hardware description is empty");
   if ((graph->in.dtype == XENOS_BF16 || graph->out.dtype == XENOS_BF16) && opts->compute != XENOS_BF16)

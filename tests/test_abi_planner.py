@@ -127,6 +127,11 @@ def test_linking_patterns_of_the_workloads():
     assert (64, 128) in offs and (256, 512) in offs            # expand3x3 halves land at their channel offset
     vgg = plan_json(wg.build(3, 2, draw=False), link=2, compute=X.XENOS_BF16)["plan"]
     assert [c["mode"] for c in vgg["chains"] if c["kind"] == "conv"].count("zigzag") == 5
+    # the layout transform of the graph input is linked into the first layer: no import pass, the caller's NCHW
+    # tensor is read where it lies; un-linked plans convert first
+    assert vgg["chains"][0]["kind"] == "conv" and vgg["chains"][0]["loader"] == "stem"
+    vgg1 = plan_json(wg.build(3, 2, draw=False), link=1, compute=X.XENOS_BF16)["plan"]
+    assert vgg1["chains"][0]["name"] == "import" and vgg1["chains"][1]["loader"] == "vector"
 
 
 @pytest.mark.parametrize("cfg,batch,compute", [(1, 1, 0), (2, 32, 1), (3, 32, 1), (4, 32, 0)])
@@ -152,7 +157,10 @@ def test_split_covers_the_output_and_fits_private_memory(cfg, batch, compute):
             assert c["patch_h"] * c["patch_w"] <= c["bm"]
             py, px = -(-c["PH"] // c["pph"]), -(-c["PW"] // c["ppw"])
             assert c["tiles_m"] == c["N"] * py * px
-        assert c["grid"] >= c["tiles_m"] * c["tiles_n"]
+        if c["loader"] == "stem":
+            assert c["bm"] == 32 and c["tiles_n"] == 1 and 1 <= c["grid"] <= -(-c["tiles_m"] // 4)   # wavefronts stride over 32-pixel blocks
+        else:
+            assert c["grid"] >= c["tiles_m"] * c["tiles_n"]
     assert q["workspace_bytes"] > 0 and q["weight_bytes"] > 0
 
 

@@ -176,6 +176,66 @@ def test_small_channel_first_layer_and_nchw_output():
         check(g, ref, compute=1)
 
 
+@pytest.mark.parametrize("compute", [0, 1])
+@pytest.mark.parametrize("k,ksz,stride,pad,hw,c", [(64, 3, 1, 1, 37, 3), (32, 3, 2, 1, 30, 3), (64, 3, 2, 0, 21, 3), (32, 5, 1, 2, 17, 1),
+                                                   (64, 1, 1, 0, 11, 4), (64, 2, 2, 0, 10, 8)])
+def test_first_layer_reads_the_graph_input_in_place(k, ksz, stride, pad, hw, c, compute):
+    # C*R*S <= 32 and K in {32, 64}: the first chain gathers from the caller's NCHW fp32 tensor (no import pass)
+    # and hands NHWC to the next chain; 3 images x odd sizes give ragged 32-pixel blocks
+    b = wg.builder("stem", (3, c, hw, hw), 17, nonzero_bias=True)
+    t = b.cbr(0, k, ksz, stride, pad, name="c0")
+    t = b.cbr(t, 24, 3, 1, 1, name="c1")
+    g = b.finish(t)
+    ref = xo.forward(g)
+    y, info = check(g, ref, compute=compute, link=2)
+    assert info["chains"][0]["loader"] == "stem" and info["n_chains"] == 2
+    y0, i0 = check(g, ref, compute=compute, link=1)          # un-linked: the general kernel (after an import pass if the input is large)
+    assert all(c.get("loader") != "stem" for c in i0["chains"])
+    ys, _ = run_gpu(g, compute=compute, link=2, split=0)
+    assert np.array_equal(y, ys)                              # one workgroup walking all blocks: same bits
+
+
+def _bf16_rne(x):
+    """fp32 -> bf16 -> fp32 with round-to-nearest-even, in integer arithmetic."""
+    u = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32).astype(np.uint64)
+    u = (u + 0x7FFF + ((u >> 16) & 1)) >> 16 << 16
+    return u.astype(np.uint32).view(np.float32)
+
+
+@pytest.mark.parametrize("hw", [5, 40])
+def test_bf16_path_rounds_to_nearest_even(hw):
+    # Identity 1x1 convolutions make every rounding of the bf16 path visible bit for bit: the graph input is rounded
+    # once when it is converted to bf16; the first chain's epilogue computes scale * x + shift as one fp32 fma
+    # (reproduced here in fp64, where the product is exact) and rounds it to bf16; the second chain returns that
+    # tensor unchanged as fp32.  hw = 40 takes the import pass, hw = 5 the element-wise gather.
+    c = 8
+    b = wg.builder("rne", (2, c, hw, hw), 41)
+    t = b.bn(b.conv(0, c, 1, 1, 0, name="id1"))
+    t = b.conv(t, c, 1, 1, 0, name="id2")
+    g = b.finish(t)
+    eye = np.eye(c, dtype=np.float32).reshape(c, c, 1, 1)
+    g.ops[0].params["weight"] = eye.copy()
+    g.ops[2].params["weight"] = eye.copy()
+    bn = g.ops[1].params
+    scale = (bn["gamma"].astype(np.float64) / np.sqrt(bn["var"].astype(np.float64) + float(np.float32(g.ops[1].attrs["eps"]))))
+    shift = bn["beta"].astype(np.float64) - bn["mean"].astype(np.float64) * scale
+    scale32, shift32 = scale.astype(np.float32), shift.astype(np.float32)
+    x = g.x.astype(np.float32)
+    # ties and near-ties: values exactly half-way between two bf16 numbers, and their neighbours
+    flat = x.reshape(-1)
+    base = _bf16_rne(flat[:64]).view(np.uint32)
+    flat[:64] = (base | 0x8000).view(np.float32)              # exact ties (round to even)
+    flat[64:128] = ((base | 0x8000) + 1).view(np.float32)     # just above a tie
+    flat[128:192] = ((base | 0x8000) - 1).view(np.float32)    # just below a tie
+    g.x = flat.reshape(x.shape)
+    xr = _bf16_rne(g.x).astype(np.float64)
+    y1 = (xr * scale32.astype(np.float64)[None, :, None, None] + shift32.astype(np.float64)[None, :, None, None]).astype(np.float32)
+    want = _bf16_rne(y1)
+    y, info = run_gpu(g, compute=1, link=2)
+    assert info["n_chains"] <= 3
+    assert np.array_equal(y.view(np.uint32), want.reshape(y.shape).view(np.uint32))
+
+
 def test_deterministic_run_to_run():
     g = chain_graph("cbrgap")
     a, _ = run_gpu(g, compute=1)
