@@ -34,7 +34,7 @@ static const TileCfg kTileCfgs[] = {
   {32, 128, 32, 32},
 };
 static const int kNumTileCfgs = 4;
-// Configuration index of the halo-staged 3x3 kernel: 256 pixels x 128 channels, 512 threads, TH x TW spatial tile.
+// Configuration index of the halo-staged 3x3 kernel: 256 pixels x 128 or 64 channels, 512 threads, TH x TW spatial tile.
 static const int kHaloCfg = 4;
 // Configuration index of the first-layer kernel: 32 pixels x K (32 or 64) channels per wavefront, reduction C*R*S <= 32,
 // gathered straight from the graph input through `ktab`.
@@ -75,6 +75,7 @@ struct ConvArgs {
   int ksplit, steps_per_split, part_ld;
   float* part;
   int th, tw, tiles_y, tiles_x;   // halo kernel: spatial tile and tile grid over the stacked padded rows n*(H+2)+oh
+  int halo_bn;           // halo kernel: output channels per tile (128 or 64)
   int M_total;           // rows enumerated over the whole problem (FLAT, ZIGZAG); per-image rows for GAP
   int tiles_m, tiles_n, ntiles;
   int xcd_m;             // dense-conv kernel: the 8 XCDs form an xcd_m x (8/xcd_m) grid over pixel tiles x (channel tiles x shares)

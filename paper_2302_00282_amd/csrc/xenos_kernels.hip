@@ -569,49 +569,80 @@ __global__ __launch_bounds__(NT, 2) void conv_kernel(const ConvArgs a) {
 // ---------------------------------------------------------------------------------------------
 // The im2col gather of conv_kernel re-reads every input pixel nine times through L2 and re-writes it nine
 // times into LDS; LDS writes (~75 B/clk/CU) and L2->CU traffic (~45 B/clk/CU) then cost as much as the MFMA
-// work.  Here a workgroup owns a TH x TW block of output pixels (256 GEMM rows) x 128 output channels, loads the
-// (TH+2) x (TW+2) input patch of one 64-element channel chunk ONCE, and runs the nine taps out of that patch
-// (the fragment address of a row only shifts by the tap offset).  This is the GPU form of the paper's halo
+// work.  Here a workgroup owns a TH x TW block of output pixels (256 GEMM rows) x BN (128 or 64) output channels,
+// loads the (TH+2) x (TW+2) input patch of one 64-element channel chunk ONCE, and runs the nine taps out of that
+// patch (the fragment address of a row only shifts by the tap offset).  This is the GPU form of the paper's halo
 // replication (Section 4.1, last paragraph): neighbouring tiles hold their own copy of the boundary rows and
 // columns instead of looking back.  Images are stacked with their padding rows (row q = n*(H+2) + oh), so a
 // tile may span two images and small maps still fill the 256 rows; rows with oh >= H are dummies.
-constexpr int V2_BM = 256, V2_BN = 128, V2_NT = 512, V2_PPMAX = 384;
-constexpr int V2_ABYTES = V2_PPMAX * LDS_ROW, V2_BBYTES = V2_BN * LDS_ROW;
-constexpr int V2_LDS = 2 * V2_ABYTES + 2 * V2_BBYTES;
-static_assert(V2_LDS >= V2_BM * (V2_BN + STG_PAD) * 4, "epilogue staging must fit in the operand buffers");
+//
+// Workgroups are persistent (one per compute unit) and walk their tiles as one long sequence of channel chunks:
+// during the last chunk of a tile the first patch and the first two weight steps of the NEXT tile are already
+// on their way, so a tile boundary costs the epilogue only.  The GEMM is computed transposed (accumulator rows =
+// output channels, columns = pixels): a lane then owns 4 consecutive channels of one pixel, the 2x2 pooling
+// window of the zig-zag enumeration is 4 neighbouring lanes (reduced with DPP quad permutes), and the finished
+// values go through LDS once, already in the output type, to be stored as whole 16-byte channel groups.
+constexpr int V2_BM = 256, V2_NT = 512, V2_PPMAX = 384;
+constexpr int V2_ABYTES = V2_PPMAX * LDS_ROW;
+__host__ __device__ constexpr int v2_lds(int bn) { return 2 * V2_ABYTES + 2 * bn * LDS_ROW; }   // operand buffers
+__host__ __device__ constexpr int v2_lds_total(int bn) { return v2_lds(bn) + 2 * bn * 4; }            // + scale / shift of the tile
+// passes of the epilogue staging (rows of the tile per pass = rows / passes), sized to one patch buffer
+__host__ __device__ constexpr int v2_passes(int rows, int pitch) {
+  return rows * pitch <= V2_ABYTES ? 1 : (rows / 2) * pitch <= V2_ABYTES ? 2 : 4;
+}
+
+template <int CTRL>
+__device__ __forceinline__ float quad_perm(float v) {
+  return __int_as_float(__builtin_amdgcn_mov_dpp(__float_as_int(v), CTRL, 0xf, 0xf, true));
+}
 
 // PWID = row pitch of the staged patch in pixels (compile time, so that every tap is an immediate LDS offset)
-template <typename T, int MODE, int PWID>
+template <typename T, int MODE, int PWID, int BN>
 __global__ __launch_bounds__(V2_NT) void conv3x3_kernel(const ConvArgs a) {
   using tr = Tr<T>;
-  constexpr int CE = tr::CE, BKE = tr::BKE;
-  constexpr int BM = V2_BM, BN = V2_BN, NTH = V2_NT;
+  constexpr int CE = tr::CE, BKE = tr::BKE, ESZ = (int)sizeof(T);
+  constexpr int BM = V2_BM, NTH = V2_NT;
+  constexpr int WN = BN / 2, TN = WN / 32;                         // 4 x 2 wavefronts of 64 pixels x WN channels
   constexpr int A_IT = V2_PPMAX * CPR / NTH;                       // 6 patch chunks per thread
-  constexpr int B_IT = BN * CPR / NTH;                             // 2 weight chunks per thread
-  constexpr int SP = BN + STG_PAD, CG = BN / CE;
+  constexpr int B_IT = BN * CPR / NTH;                             // 2 or 1 weight chunks per thread
+  constexpr int BBYTES = BN * LDS_ROW;
+  constexpr int CG = BN / CE;                                      // 16-byte channel groups per output row
+  constexpr int SPB = BN * ESZ + 16;                               // staging row pitch in bytes
+  constexpr int ROWS = MODE == M_FLAT ? BM : BM / 4;               // staged rows: pixels, or pooled windows
+  constexpr int NP = v2_passes(ROWS, SPB), RPP = ROWS / NP;        // staging passes, rows per pass
   static_assert(MODE == M_FLAT || MODE == M_ZIGZAG, "row enumerations of the halo kernel");
+  static_assert(A_IT % 2 == 0 && B_IT >= 1 && NTH % CG == 0, "loader shapes");
 
   extern __shared__ __align__(16) unsigned char smem[];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wave_m = wave >> 1, wave_n = wave & 1;                 // 4 x 2 wavefronts of 64 x 64
+  const int wave_m = wave >> 1, wave_n = wave & 1;
   const int l31 = lane & 31, lhalf = lane >> 5;
 
   const int PP = (a.th + 2) * PWID, Hp = a.H + 2;               // a.tw + 2 <= PWID
-  const int nchunks = a.C / BKE, nsteps = nchunks * 9;
-  const int mchunk = (a.tiles_m + NUM_XCD - 1) / NUM_XCD;
-  const int slots = mchunk * NUM_XCD * a.tiles_n;
+  const int nchunks = a.C / BKE;
 
-  for (int t = blockIdx.x; t < slots; t += gridDim.x) {
-    const int local = t / NUM_XCD;
-    const int tile_n = local / mchunk;
-    const int tile_m = (t % NUM_XCD) * mchunk + local % mchunk;
-    if (tile_m >= a.tiles_m) continue;                             // uniform per workgroup
+  // ---- this workgroup's tiles ---------------------------------------------------------------------
+  // Workgroups are dealt round-robin to the XCDs; each XCD owns a contiguous, balanced range of pixel tiles and
+  // walks it once per output-channel tile, so its workgroups share one weight slice in their L2 and neighbouring
+  // pixel tiles share their input halo.
+  const int G = gridDim.x, nx = G < NUM_XCD ? G : NUM_XCD;
+  const int xcd = blockIdx.x % nx, wgs = (G - xcd + nx - 1) / nx;   // workgroups of this XCD
+  const int m0 = xcd * a.tiles_m / nx, mlen = (xcd + 1) * a.tiles_m / nx - m0;
+  const int ntl = mlen * a.tiles_n;                                // tiles of this XCD, channel-tile major
+  int li = blockIdx.x / nx;
+  if (li >= ntl) return;                                           // uniform per workgroup
+
+  // ---- what this thread loads for a tile: 6 chunks of the input patch, B_IT chunks of the weight tile ------
+  int aoff[A_IT];
+  unsigned aok = 0;
+  int wrow0 = 0, wrow1 = 0, wnext0 = 0, wnext1 = 0;                // byte offsets into the packed weights of this thread's one or
+                                                                   // two chunks: this tile's, the next tile's (scalars, not arrays:
+                                                                   // arrays selected by a run-time flag end up in scratch memory)
+  auto patch_addr = [&](int l) __attribute__((always_inline)) {
+    const int tile_m = m0 + l % mlen;
     const int tyi = tile_m / a.tiles_x;
     const int q0 = tyi * a.th, x0 = (tile_m - tyi * a.tiles_x) * a.tw;
-
-    // ---- what this thread loads: 6 chunks of the input patch, 2 chunks of the weight tile ----------
-    int aoff[A_IT];
-    unsigned aok = 0;
+    aok = 0;
 #pragma unroll
     for (int it = 0; it < A_IT; ++it) {
       const int idx = tid + it * NTH;
@@ -622,270 +653,338 @@ __global__ __launch_bounds__(V2_NT) void conv3x3_kernel(const ConvArgs a) {
       aoff[it] = ok ? (int)((long long)n * a.in_sN + (long long)ih * a.in_sH + (long long)iw * a.in_sW) + c8 * CE : c8 * CE;
       aok |= (ok ? 1u : 0u) << it;
     }
-    const unsigned char* wrow[B_IT];
+  };
+  auto weight_addr = [&](int l, int it) __attribute__((always_inline)) -> int {
+    const int tile_n = l / mlen, idx = tid + it * NTH;
+    return ((tile_n * BN + idx / CPR) * a.Kred_pad + (idx % CPR) * CE) * ESZ;
+  };
+
+  // ---- fragment addresses of this lane's rows (pixels of the tile); the same for every tile --------------
+  int abase[2], bbase[TN];
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int m = wave_m * 64 + i * 32 + l31;
+    int ty, tx;
+    bool ok;
+    if (MODE == M_FLAT) { ty = m / a.tw; tx = m - ty * a.tw; ok = ty < a.th; }
+    else {
+      const int w = m >> 2, j = m & 3, hw = a.tw >> 1;
+      const int wy = w / hw, wx = w - wy * hw;
+      ty = 2 * wy + (j >> 1); tx = 2 * wx + (j & 1); ok = ty < a.th;
+    }
+    abase[i] = (ok ? ty * PWID + tx : 0) * LDS_ROW + lhalf * 16;
+  }
+#pragma unroll
+  for (int j = 0; j < TN; ++j) bbase[j] = (wave_n * WN + j * 32 + l31) * LDS_ROW + lhalf * 16;
+
+  f32x16_t acc[2][TN];
+  constexpr int A_HALF = A_IT / 2;
+  u32x4_t pa[A_HALF], rb0[B_IT], rb1[B_IT];
+
+  // the patch of a channel chunk travels in two halves of 3 chunks per thread (12 staging registers)
+  auto load_patch = [&](int c, int half) {
+#pragma unroll
+    for (int it = 0; it < A_HALF; ++it) pa[it] = *(const u32x4_t*)((const T*)a.in + aoff[half * A_HALF + it] + c);
+  };
+  auto store_patch = [&](int buf, int half) {
+    unsigned char* sa = smem + buf * V2_ABYTES;
+    const u32x4_t z = {0u, 0u, 0u, 0u};
+#pragma unroll
+    for (int it = 0; it < A_HALF; ++it) {
+      const int idx = tid + (half * A_HALF + it) * NTH;
+      *(u32x4_t*)(sa + (idx / CPR) * LDS_ROW + (idx % CPR) * 16) = ((aok >> (half * A_HALF + it)) & 1u) ? pa[it] : z;
+    }
+  };
+  auto load_w = [&](int step, u32x4_t* rb) {
+#pragma unroll
+    for (int it = 0; it < B_IT; ++it) rb[it] = *(const u32x4_t*)((const unsigned char*)a.w + (it == 0 ? wrow0 : wrow1) + step * ROWB);
+  };
+  auto store_w = [&](int stage, const u32x4_t* rb) {
+    unsigned char* sb = smem + 2 * V2_ABYTES + stage * BBYTES;
 #pragma unroll
     for (int it = 0; it < B_IT; ++it) {
       const int idx = tid + it * NTH;
-      wrow[it] = (const unsigned char*)a.w +
-                 ((long long)(tile_n * BN + idx / CPR) * a.Kred_pad + (idx % CPR) * CE) * (long long)sizeof(T);
+      *(u32x4_t*)(sb + (idx / CPR) * LDS_ROW + (idx % CPR) * 16) = rb[it];
     }
-    // ---- fragment addresses of this lane's rows (pixels of the tile) -------------------------------
-    int abase[2], bbase[2];
+  };
+  // one tap of one channel chunk: 4 k-groups, fragments of k-group g+1 are fetched before the MFMAs of g
+  auto compute = [&](int abuf, int bstage, int tapoff) {
+    const unsigned char* sa = smem + abuf * V2_ABYTES + tapoff;
+    const unsigned char* sb = smem + 2 * V2_ABYTES + bstage * BBYTES;
+    u32x4_t fa[2][2], fb[2][TN];
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
-      const int m = wave_m * 64 + i * 32 + l31;
-      int ty, tx;
-      bool ok;
-      if (MODE == M_FLAT) { ty = m / a.tw; tx = m - ty * a.tw; ok = ty < a.th; }
-      else {
-        const int w = m >> 2, j = m & 3, hw = a.tw >> 1;
-        const int wy = w / hw, wx = w - wy * hw;
-        ty = 2 * wy + (j >> 1); tx = 2 * wx + (j & 1); ok = ty < a.th;
-      }
-      abase[i] = (ok ? ty * PWID + tx : 0) * LDS_ROW + lhalf * 16;
-      bbase[i] = (wave_n * 64 + i * 32 + l31) * LDS_ROW + lhalf * 16;
-    }
-
-    f32x16_t acc[2][2];
+    for (int i = 0; i < 2; ++i) fa[0][i] = *(const u32x4_t*)(sa + abase[i]);
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int j = 0; j < TN; ++j) fb[0][j] = *(const u32x4_t*)(sb + bbase[j]);
 #pragma unroll
-      for (int j = 0; j < 2; ++j)
+    for (int kg = 0; kg < KG; ++kg) {
+      const int cur = kg & 1, nxt = cur ^ 1;
+      if (kg + 1 < KG) {
 #pragma unroll
-        for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
-
-    constexpr int A_HALF = A_IT / 2;
-    u32x4_t pa[A_HALF], rb0[B_IT], rb1[B_IT];
-
-    // the patch of a channel chunk travels in two halves of 3 chunks per thread (12 staging registers)
-    auto load_patch = [&](int cc, int half) {
-      const int c = (cc < nchunks ? cc : nchunks - 1) * BKE;
+        for (int i = 0; i < 2; ++i) fa[nxt][i] = *(const u32x4_t*)(sa + abase[i] + (kg + 1) * 32);
 #pragma unroll
-      for (int it = 0; it < A_HALF; ++it) pa[it] = *(const u32x4_t*)((const T*)a.in + aoff[half * A_HALF + it] + c);
-    };
-    auto store_patch = [&](int buf, int half) {
-      unsigned char* sa = smem + buf * V2_ABYTES;
-      const u32x4_t z = {0u, 0u, 0u, 0u};
-#pragma unroll
-      for (int it = 0; it < A_HALF; ++it) {
-        const int idx = tid + (half * A_HALF + it) * NTH;
-        *(u32x4_t*)(sa + (idx / CPR) * LDS_ROW + (idx % CPR) * 16) = ((aok >> (half * A_HALF + it)) & 1u) ? pa[it] : z;
-      }
-    };
-    auto load_w = [&](int step, u32x4_t* rb) {
-      const int bstep = step < nsteps ? step : nsteps - 1;
-#pragma unroll
-      for (int it = 0; it < B_IT; ++it) rb[it] = *(const u32x4_t*)(wrow[it] + (long long)bstep * ROWB);
-    };
-    auto store_w = [&](int stage, const u32x4_t* rb) {
-      unsigned char* sb = smem + 2 * V2_ABYTES + stage * V2_BBYTES;
-#pragma unroll
-      for (int it = 0; it < B_IT; ++it) {
-        const int idx = tid + it * NTH;
-        *(u32x4_t*)(sb + (idx / CPR) * LDS_ROW + (idx % CPR) * 16) = rb[it];
-      }
-    };
-    // one tap of one channel chunk: 4 k-groups, fragments of k-group g+1 are fetched before the MFMAs of g
-    auto compute = [&](int abuf, int bstage, int tapoff) {
-      const unsigned char* sa = smem + abuf * V2_ABYTES + tapoff;
-      const unsigned char* sb = smem + 2 * V2_ABYTES + bstage * V2_BBYTES;
-      u32x4_t fa[2][2], fb[2][2];
-#pragma unroll
-      for (int i = 0; i < 2; ++i) {
-        fa[0][i] = *(const u32x4_t*)(sa + abase[i]);
-        fb[0][i] = *(const u32x4_t*)(sb + bbase[i]);
+        for (int j = 0; j < TN; ++j) fb[nxt][j] = *(const u32x4_t*)(sb + bbase[j] + (kg + 1) * 32);
       }
 #pragma unroll
-      for (int kg = 0; kg < KG; ++kg) {
-        const int cur = kg & 1, nxt = cur ^ 1;
-        if (kg + 1 < KG) {
+      for (int i = 0; i < 2; ++i)
 #pragma unroll
-          for (int i = 0; i < 2; ++i) {
-            fa[nxt][i] = *(const u32x4_t*)(sa + abase[i] + (kg + 1) * 32);
-            fb[nxt][i] = *(const u32x4_t*)(sb + bbase[i] + (kg + 1) * 32);
+        for (int j = 0; j < TN; ++j) {
+          // operands swapped: accumulator rows = channels of block j, columns = pixels of block i
+          if constexpr (sizeof(T) == 2) {
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, fb[cur][j]),
+                                                                __builtin_bit_cast(bf16x8_t, fa[cur][i]), acc[i][j], 0, 0, 0);
+          } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+              acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(fb[cur][j][e]), __uint_as_float(fa[cur][i][e]),
+                                                               acc[i][j], 0, 0, 0);
           }
         }
+    }
+    // the schedule wanted: fragments of k-group g+1 are in flight while the MFMAs of k-group g issue
+    // (0x100 = LDS read, 0x008 = MFMA); without it the scheduler serialises read -> wait -> MFMA
+    __builtin_amdgcn_sched_group_barrier(0x100, 2 + TN, 0);
 #pragma unroll
-        for (int i = 0; i < 2; ++i)
+    for (int kg = 0; kg < KG; ++kg) {
+      if (kg + 1 < KG) __builtin_amdgcn_sched_group_barrier(0x100, 2 + TN, 0);
+      __builtin_amdgcn_sched_group_barrier(0x008, (sizeof(T) == 2 ? 2 : 8) * TN, 0);
+    }
+  };
+  // Nine statically unrolled taps of channel chunk cc.  PAR = parity of the chunk in the workgroup's whole chunk
+  // sequence: it selects the patch buffer, and (9 steps per chunk) the weight stage / register set of tap 0.
+  // `last`: the chunk after this one belongs to the next tile (aoff / aok / wnext already describe that tile).
+  auto chunk_body = [&](int cc, bool last, auto par) {
+    constexpr int PAR = decltype(par)::value;
+    const int step0 = cc * 9;
+    const int cnext = last ? 0 : (cc + 1) * BKE;
 #pragma unroll
-          for (int j = 0; j < 2; ++j) {
-            if constexpr (sizeof(T) == 2) {
-              acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, fa[cur][i]),
-                                                                  __builtin_bit_cast(bf16x8_t, fb[cur][j]), acc[i][j], 0, 0, 0);
-            } else {
+    for (int tap = 0; tap < 9; ++tap) {
+      const int sp = (PAR + tap) & 1;                              // weight stage / register set of this step
+      u32x4_t* rb = sp == 0 ? rb0 : rb1;
+      if (tap < 7) load_w(step0 + tap + 2, rb);              // weights of step + 2 ...
+      else {
+        // ... which for the last two taps of a tile are steps 0 and 1 of the next tile
 #pragma unroll
-              for (int e = 0; e < 4; ++e)
-                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(fa[cur][i][e]), __uint_as_float(fb[cur][j][e]),
-                                                                 acc[i][j], 0, 0, 0);
+        for (int it = 0; it < B_IT; ++it) {
+          const int src = last ? (it == 0 ? wnext0 : wnext1) + (tap - 7) * ROWB : (it == 0 ? wrow0 : wrow1) + (step0 + tap + 2) * ROWB;
+          rb[it] = *(const u32x4_t*)((const unsigned char*)a.w + src);
+        }
+      }
+      if (tap == 0) load_patch(cnext, 0);                          // next chunk's patch: half 0 in flight over taps 0-3,
+      if (tap == 4) load_patch(cnext, 1);                          // half 1 over taps 4-8
+      __builtin_amdgcn_sched_barrier(0);                           // keep the prefetch loads ahead of the MFMA block
+      compute(PAR, sp, ((tap / 3) * PWID + tap % 3) * LDS_ROW);
+      __builtin_amdgcn_sched_barrier(0);
+      if (sp == 0) store_w(1, rb1); else store_w(0, rb0);         // publish step + 1
+      if (tap == 3) store_patch(PAR ^ 1, 0);
+      if (tap == 8) store_patch(PAR ^ 1, 1);
+      __syncthreads();
+    }
+  };
+
+  // ---- pipeline start: chunk 0 and weight steps 0, 1 of the first tile ---------------------------------
+  patch_addr(li);
+  wrow0 = weight_addr(li, 0);
+  if (B_IT > 1) wrow1 = weight_addr(li, 1);
+  load_patch(0, 0);
+  load_w(0, rb0);
+  store_patch(0, 0);
+  load_patch(0, 1);
+  store_w(0, rb0);
+  store_patch(0, 1);
+  load_w(1, rb1);
+  __syncthreads();
+
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+  // The chain's epilogue for the tile `li`, run after its last chunk (of parity PAR).
+  auto epilogue = [&](auto par) {
+    constexpr int PAR = decltype(par)::value;
+    const int tile_n = li / mlen, tile_m = m0 + li % mlen;
+    const int tyi = tile_m / a.tiles_x;
+    const int q0 = tyi * a.th, x0 = (tile_m - tyi * a.tiles_x) * a.tw;
+    // The patch buffer of the chunk just finished is free (the other one holds the next tile's first patch).
+    unsigned char* stg = smem + PAR * V2_ABYTES;
+    // shortcut address of this lane's two pixels (rows outside the image read element 0)
+    long long rbase[2] = {0, 0};
+    if (MODE == M_FLAT && a.has_res) {
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        const int m = wave_m * 64 + i * 32 + l31;
+        const int ty = m / a.tw, tx = m - ty * a.tw;
+        const int qq = q0 + ty, n = qq / Hp, oh = qq - n * Hp, ow = x0 + tx;
+        const bool ok = ty < a.th && n < a.N && oh < a.H && ow < a.W;
+        rbase[i] = ok ? (long long)n * a.res_sN + (long long)(oh * a.OW + ow) * a.res_sP : 0;
+      }
+    }
+    const float lo = a.relu ? 0.f : -3.4028235e38f;                // ReLU as a clamp: no branch per value
+    // this tile's folded scale / shift, shared through LDS (every lane needs 32 of the BN values of each)
+    float* s_aff = (float*)(smem + v2_lds(BN));
+    if (tid < 2 * BN) s_aff[tid] = tid < BN ? a.scale[tile_n * BN + tid] : a.shift[tile_n * BN + tid - BN];
+    __syncthreads();
+    // first half of a pass: the wavefronts that own its rows finish their accumulators (scale, shift, shortcut,
+    // ReLU, pooling) and stage them in the output type.  RES / VEC / PMAX are compile-time copies of the chain's
+    // flags, so the 16 channel groups of a lane run without branches.
+    auto finish_rows = [&](int pass, auto res_c, auto max_c) {
+      constexpr bool RES = decltype(res_c)::value, PMAX = decltype(max_c)::value;
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        const int m = wave_m * 64 + i * 32 + l31;
+        const int srow = (MODE == M_FLAT ? m : (m >> 2)) - pass * RPP;
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+          for (int g = 0; g < 4; ++g) {
+            const int c = wave_n * WN + j * 32 + g * 8 + lhalf * 4, k0 = tile_n * BN + c;
+            const f32x4_t sc = *(const f32x4_t*)(s_aff + c), sh = *(const f32x4_t*)(s_aff + BN + c);
+            float y[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) y[e] = acc[i][j][4 * g + e] * sc[e] + sh[e];
+            if constexpr (RES) {
+              // rows outside the image and channel groups beyond K read a valid dummy address; they are never stored
+              const long long ra = rbase[i] + (k0 < a.K ? k0 : 0);
+              if constexpr (sizeof(T) == 2) {
+                const uint2 r = *(const uint2*)((const T*)a.res + ra);
+                y[0] += __uint_as_float(r.x << 16); y[1] += __uint_as_float(r.x & 0xffff0000u);
+                y[2] += __uint_as_float(r.y << 16); y[3] += __uint_as_float(r.y & 0xffff0000u);
+              } else {
+                const f32x4_t r = *(const f32x4_t*)((const T*)a.res + ra);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) y[e] += r[e];
+              }
+            }
+#pragma unroll
+            for (int e = 0; e < 4; ++e) y[e] = fmaxf(y[e], lo);
+            bool mine = true;                                      // does this lane hold the finished value?
+            if (MODE == M_ZIGZAG) {
+              // the window's four pixels are lanes 4w .. 4w+3: butterfly over the quad, lane j keeps group g == j
+#pragma unroll
+              for (int e = 0; e < 4; ++e) {
+                const float p1 = quad_perm<0xB1>(y[e]);            // lanes [1,0,3,2]
+                y[e] = PMAX ? fmaxf(y[e], p1) : y[e] + p1;
+                const float p2 = quad_perm<0x4E>(y[e]);            // lanes [2,3,0,1]
+                y[e] = PMAX ? fmaxf(y[e], p2) : (y[e] + p2) * 0.25f;
+              }
+              mine = (l31 & 3) == g;
+            }
+            if (mine) {
+              if constexpr (sizeof(T) == 2) {
+                uint2 o;
+                o.x = f2bf2(y[0], y[1]);
+                o.y = f2bf2(y[2], y[3]);
+                *(uint2*)(stg + srow * SPB + c * 2) = o;
+              } else {
+                *(f32x4_t*)(stg + srow * SPB + c * 4) = f32x4_t{y[0], y[1], y[2], y[3]};
+              }
             }
           }
       }
-      // the schedule wanted: fragments of k-group g+1 are in flight while the MFMAs of k-group g issue
-      // (0x100 = LDS read, 0x008 = MFMA); without it the scheduler serialises read -> wait -> MFMA
-      __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
-#pragma unroll
-      for (int kg = 0; kg < KG; ++kg) {
-        if (kg + 1 < KG) __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
-        __builtin_amdgcn_sched_group_barrier(0x008, sizeof(T) == 2 ? 4 : 16, 0);
-      }
     };
-    // nine statically unrolled taps of channel chunk cc; PAR = parity of the first step of the chunk
-    auto chunk_body = [&](int cc, auto par) {
-      constexpr int PAR = decltype(par)::value;
-      const int step0 = cc * 9;
-#pragma unroll
-      for (int tap = 0; tap < 9; ++tap) {
-        constexpr int dummy = 0; (void)dummy;
-        const int sp = (PAR + tap) & 1;                            // weight stage / register set of this step
-        if (sp == 0) load_w(step0 + tap + 2, rb0); else load_w(step0 + tap + 2, rb1);
-        if (tap == 0) load_patch(cc + 1, 0);                       // next chunk's patch: half 0 in flight over taps 0-3,
-        if (tap == 4) load_patch(cc + 1, 1);                       // half 1 over taps 4-8
-        __builtin_amdgcn_sched_barrier(0);                         // keep the prefetch loads ahead of the MFMA block
-        compute(cc & 1, sp, ((tap / 3) * PWID + tap % 3) * LDS_ROW);
-        __builtin_amdgcn_sched_barrier(0);
-        if (sp == 0) store_w(1, rb1); else store_w(0, rb0);       // publish step + 1
-        if (tap == 3) store_patch((cc + 1) & 1, 0);
-        if (tap == 8) store_patch((cc + 1) & 1, 1);
-        __syncthreads();
+    using std::true_type; using std::false_type;
+#pragma unroll 1
+    for (int pass = 0; pass < NP; ++pass) {
+      if (wave_m / (4 / NP) == pass) {                             // the wavefronts whose rows this pass stages
+        if (MODE == M_FLAT) {
+          if (a.has_res) finish_rows(pass, true_type{}, false_type{});
+          else finish_rows(pass, false_type{}, false_type{});
+        } else {
+          if (a.pool == POOL_MAX) finish_rows(pass, false_type{}, true_type{});
+          else finish_rows(pass, false_type{}, false_type{});
+        }
       }
-    };
-
-    load_patch(0, 0);
-    load_w(0, rb0);
-    store_patch(0, 0);
-    load_patch(0, 1);
-    store_w(0, rb0);
-    store_patch(0, 1);
-    load_w(1, rb1);
-    __syncthreads();
-    for (int cc = 0; cc < nchunks; cc += 2) {
-      chunk_body(cc, std::integral_constant<int, 0>{});
-      if (cc + 1 >= nchunks) break;
-      chunk_body(cc + 1, std::integral_constant<int, 1>{});
+      __syncthreads();
+      {
+        const int nq = MODE == M_FLAT ? a.th * a.tw : (a.th >> 1) * (a.tw >> 1);
+        for (int idx = tid; idx < RPP * CG; idx += NTH) {
+          const int lr = idx / CG, cg = idx - lr * CG, q = pass * RPP + lr;
+          const int k0 = tile_n * BN + cg * CE;
+          if (q >= nq || k0 >= a.K) continue;
+          long long ob;
+          if (MODE == M_FLAT) {
+            const int ty = q / a.tw, tx = q - ty * a.tw;
+            const int qq = q0 + ty, n = qq / Hp, oh = qq - n * Hp, ow = x0 + tx;
+            if (n >= a.N || oh >= a.H || ow >= a.W) continue;
+            ob = (long long)n * a.out_sN + (long long)(oh * a.OW + ow) * a.out_sP;
+          } else {
+            const int hw = a.tw >> 1;
+            const int wy = q / hw, wx = q - wy * hw;
+            const int qq = q0 + 2 * wy, n = qq / Hp, oh = qq - n * Hp, ow = x0 + 2 * wx;
+            if (n >= a.N || oh >= a.H || ow >= a.W) continue;
+            ob = (long long)n * a.out_sN + (long long)((oh >> 1) * a.PW + (ow >> 1)) * a.out_sP;
+          }
+          *(u32x4_t*)((T*)a.out + ob + k0) = *(const u32x4_t*)(stg + lr * SPB + cg * 16);
+        }
+      }
+      __syncthreads();
     }
 
-    // ---- epilogue ---------------------------------------------------------------------------------
-    float* stg = (float*)smem;
+  };
+
+  // One channel chunk of the workgroup's chunk sequence; returns true when the workgroup has finished its last tile.
+  // The two parities alternate in straight-line code, so the accumulators never meet at a control-flow join.
+  int cc = 0;
+  auto advance = [&](auto par) -> bool {
+    const bool last = cc == nchunks - 1;
+    if (last) {
+      const int lnext = li + wgs < ntl ? li + wgs : li;            // after the last tile: reload it (never used)
+      patch_addr(lnext);
+      wnext0 = weight_addr(lnext, 0);
+      if (B_IT > 1) wnext1 = weight_addr(lnext, 1);
+    }
+    chunk_body(cc, last, par);
+    if (!last) { ++cc; return false; }
+    wrow0 = wnext0; wrow1 = wnext1;
+    epilogue(par);
 #pragma unroll
     for (int i = 0; i < 2; ++i)
 #pragma unroll
-      for (int j = 0; j < 2; ++j) {
-        const int col = wave_n * 64 + j * 32 + l31;
+      for (int j = 0; j < TN; ++j)
 #pragma unroll
-        for (int e = 0; e < 16; ++e) {
-          const int row = wave_m * 64 + i * 32 + (e >> 2) * 8 + lhalf * 4 + (e & 3);
-          stg[row * SP + col] = acc[i][j][e];
-        }
-      }
-    __syncthreads();
-    const int nq = MODE == M_FLAT ? a.th * a.tw : (a.th >> 1) * (a.tw >> 1);
-    static_assert(NTH % CG == 0, "channel group must be loop-invariant per thread");
-    const int cg = tid % CG, col0 = cg * CE, k0 = tile_n * BN + col0;
-    float sc[CE], sh[CE];
-    *(f32x4_t*)&sc[0] = *(const f32x4_t*)(a.scale + k0);
-    *(f32x4_t*)&sh[0] = *(const f32x4_t*)(a.shift + k0);
-    if (CE == 8) {
-      *(f32x4_t*)&sc[4] = *(const f32x4_t*)(a.scale + k0 + 4);
-      *(f32x4_t*)&sh[4] = *(const f32x4_t*)(a.shift + k0 + 4);
-    }
-    for (int idx = tid; idx < nq * CG; idx += NTH) {
-      const int q = idx / CG;
-      if (k0 >= a.K) break;
-      float v[CE];
-      long long obase;
-      if (MODE == M_FLAT) {
-        const int ty = q / a.tw, tx = q - ty * a.tw;
-        const int qq = q0 + ty, n = qq / Hp, oh = qq - n * Hp, ow = x0 + tx;
-        if (n >= a.N || oh >= a.H || ow >= a.W) continue;
-        obase = (long long)n * a.out_sN + (long long)(oh * a.OW + ow) * a.out_sP;
-        const float* sp = stg + q * SP + col0;
-#pragma unroll
-        for (int e = 0; e < CE; e += 4) *(f32x4_t*)&v[e] = *(const f32x4_t*)(sp + e);
-#pragma unroll
-        for (int e = 0; e < CE; ++e) v[e] = v[e] * sc[e] + sh[e];
-        if (a.has_res) {
-          const long long rb_ = (long long)n * a.res_sN + (long long)(oh * a.OW + ow) * a.res_sP;
-          if (a.vec_res) {
-            float r[CE];
-            tr::unpack(*(const u32x4_t*)((const T*)a.res + rb_ + k0), r);
-#pragma unroll
-            for (int e = 0; e < CE; ++e) v[e] += r[e];
-          } else {
-#pragma unroll
-            for (int e = 0; e < CE; ++e) if (k0 + e < a.K) v[e] += tr::ld(a.res, rb_ + k0 + e);
-          }
-        }
-        if (a.relu) {
-#pragma unroll
-          for (int e = 0; e < CE; ++e) v[e] = fmaxf(v[e], 0.f);
-        }
-      } else {
-        const int hw = a.tw >> 1;
-        const int wy = q / hw, wx = q - wy * hw;
-        const int qq = q0 + 2 * wy, n = qq / Hp, oh = qq - n * Hp, ow = x0 + 2 * wx;
-        if (n >= a.N || oh >= a.H || ow >= a.W) continue;
-        obase = (long long)n * a.out_sN + (long long)((oh >> 1) * a.PW + (ow >> 1)) * a.out_sP;
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          float u[CE];
-          const float* sp = stg + (4 * q + j) * SP + col0;
-#pragma unroll
-          for (int e = 0; e < CE; e += 4) *(f32x4_t*)&u[e] = *(const f32x4_t*)(sp + e);
-#pragma unroll
-          for (int e = 0; e < CE; ++e) {
-            float x = u[e] * sc[e] + sh[e];
-            if (a.relu) x = fmaxf(x, 0.f);
-            v[e] = j == 0 ? x : (a.pool == POOL_MAX ? fmaxf(v[e], x) : v[e] + x);
-          }
-        }
-        if (a.pool == POOL_AVG) {
-#pragma unroll
-          for (int e = 0; e < CE; ++e) v[e] *= 0.25f;
-        }
-      }
-      if (a.vec_out) {
-        *(u32x4_t*)((T*)a.out + obase + k0) = tr::pack(v);
-      } else {
-#pragma unroll
-        for (int e = 0; e < CE; ++e) {
-          if (k0 + e >= a.K) continue;
-          const long long o = obase + (long long)(k0 + e) * a.out_sK;
-          if (a.out_f32) ((float*)a.out)[o] = v[e]; else tr::st(a.out, o, v[e]);
-        }
-      }
-    }
-    __syncthreads();
+        for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+    cc = 0;
+    li += wgs;
+    return li >= ntl;
+  };
+  for (;;) {
+    if (advance(std::integral_constant<int, 0>{})) break;
+    if (advance(std::integral_constant<int, 1>{})) break;
   }
 }
 
-template <typename T, int MODE, int PWID>
+template <typename T, int MODE, int PWID, int BN>
 static int launch_conv3x3_pw(const ConvArgs& a, hipStream_t st) {
   static bool raised = false;
   if (!raised) {
-    hipError_t e = hipFuncSetAttribute((const void*)conv3x3_kernel<T, MODE, PWID>, hipFuncAttributeMaxDynamicSharedMemorySize, V2_LDS);
+    hipError_t e = hipFuncSetAttribute((const void*)conv3x3_kernel<T, MODE, PWID, BN>, hipFuncAttributeMaxDynamicSharedMemorySize, v2_lds_total(BN));
     if (e != hipSuccess) return (int)e;
     raised = true;
   }
-  hipLaunchKernelGGL((conv3x3_kernel<T, MODE, PWID>), dim3(a.grid), dim3(V2_NT), V2_LDS, st, a);
+  hipLaunchKernelGGL((conv3x3_kernel<T, MODE, PWID, BN>), dim3(a.grid), dim3(V2_NT), v2_lds_total(BN), st, a);
   return (int)hipGetLastError();
 }
 
-template <typename T, int MODE>
+template <typename T, int MODE, int BN>
 static int launch_conv3x3_inst(const ConvArgs& a, hipStream_t st) {
-  if (a.tw + 2 <= kHaloPitchNarrow && (a.th + 2) * kHaloPitchNarrow <= V2_PPMAX) return launch_conv3x3_pw<T, MODE, kHaloPitchNarrow>(a, st);
-  if (a.tw + 2 <= kHaloPitchWide && (a.th + 2) * kHaloPitchWide <= V2_PPMAX) return launch_conv3x3_pw<T, MODE, kHaloPitchWide>(a, st);
+  if (a.tw + 2 <= kHaloPitchNarrow && (a.th + 2) * kHaloPitchNarrow <= V2_PPMAX) return launch_conv3x3_pw<T, MODE, kHaloPitchNarrow, BN>(a, st);
+  if (a.tw + 2 <= kHaloPitchWide && (a.th + 2) * kHaloPitchWide <= V2_PPMAX) return launch_conv3x3_pw<T, MODE, kHaloPitchWide, BN>(a, st);
   return (int)hipErrorInvalidValue;
 }
 
 template <typename T>
 static int launch_conv3x3_t(const ConvArgs& a, hipStream_t st) {
   // the host checks the preconditions again: a wrong shape here would index outside the patch buffers
-  if (a.R != 3 || a.S != 3 || a.stride != 1 || a.pad != 1 || !a.kchunk || a.C % Tr<T>::BKE != 0 || a.th < 1 || a.tw < 1 ||
-      a.th * a.tw > V2_BM || a.tiles_m != a.tiles_y * a.tiles_x ||
-      (a.mode == M_ZIGZAG && ((a.th | a.tw | a.H | a.W) & 1)))
+  if (a.R != 3 || a.S != 3 || a.stride != 1 || a.pad != 1 || !a.kchunk || a.C % Tr<T>::BKE != 0 || a.C < Tr<T>::BKE || a.th < 1 || a.tw < 1 ||
+      a.th * a.tw > V2_BM || a.tiles_m != a.tiles_y * a.tiles_x || (a.halo_bn != 64 && a.halo_bn != 128) ||
+      a.tiles_n != (a.K + a.halo_bn - 1) / a.halo_bn || a.ksplit > 1 || a.dw_w || !a.vec_out || (a.has_res && !a.vec_res) ||
+      (a.mode == M_ZIGZAG && (((a.th | a.tw | a.H | a.W) & 1) || a.has_res)))
     return (int)hipErrorInvalidValue;
-  if (a.mode == M_FLAT) return launch_conv3x3_inst<T, M_FLAT>(a, st);
-  if (a.mode == M_ZIGZAG) return launch_conv3x3_inst<T, M_ZIGZAG>(a, st);
+  if (a.mode == M_FLAT) return a.halo_bn == 128 ? launch_conv3x3_inst<T, M_FLAT, 128>(a, st) : launch_conv3x3_inst<T, M_FLAT, 64>(a, st);
+  if (a.mode == M_ZIGZAG) return a.halo_bn == 128 ? launch_conv3x3_inst<T, M_ZIGZAG, 128>(a, st) : launch_conv3x3_inst<T, M_ZIGZAG, 64>(a, st);
   return (int)hipErrorInvalidValue;
 }
 
@@ -1137,7 +1236,7 @@ int launch_conv(const ConvArgs& a, int dtype, int cfg, int scalar_loader, void* 
 }
 
 size_t conv_lds_bytes(int cfg, int /*mode*/) {
-  if (cfg == kHaloCfg) return V2_LDS;
+  if (cfg == kHaloCfg) return v2_lds_total(128);
   if (cfg == kStemCfg) return 40 * 1024;   // static: staging slices (at most 4 x 32 x 272 bytes) + tables
   const TileCfg& c = kTileCfgs[cfg];
   const size_t main_b = (size_t)2 * (c.bm + c.bn) * LDS_ROW;

@@ -371,8 +371,10 @@ struct Planner {
   void set_grid(ConvArgs& c, int cfg) {
     const int ks = c.ksplit > 1 ? c.ksplit : 1;
     if (cfg == kHaloCfg) {
+      // persistent workgroups, one per compute unit, an equal number on every XCD
       c.xcd_m = 8;
-      c.grid = (c.tiles_m + 7) / 8 * 8 * c.tiles_n;
+      const int per_xcd = std::max(1, std::min(std::max(1, p.hw.num_cu) / 8, (c.tiles_m + 7) / 8 * c.tiles_n));
+      c.grid = 8 * per_xcd;
     } else {
       const int nz = c.tiles_n * ks;
       long long best = -1;
@@ -396,12 +398,22 @@ struct Planner {
       st.lds = conv_lds_bytes(kStemCfg, c.mode);
       return XENOS_OK;
     }
+    // halo-staged 3x3 kernel: a TH x TW block of output pixels (256 GEMM rows) x 128 channels per workgroup,
+    // tiles laid over the images stacked with their padding rows
+    // (the halo kernel stores 16-byte channel groups only: outputs and shortcuts that cannot take them use conv_kernel)
+    const bool halo_ok = c.vec_out && (!c.has_res || c.vec_res) && !c.dw_w && c.R == 3 && c.S == 3 && c.stride == 1 && c.pad == 1 && !st.scalar && c.kchunk &&
+                         (c.mode == M_FLAT || (c.mode == M_ZIGZAG && c.H % 2 == 0 && c.W % 2 == 0)) &&
+                         (long long)c.N * c.in_sN < (1ll << 31) && conv_lds_bytes(kHaloCfg, c.mode) <= p.hw.lds_bytes_per_cu;
+    // a forced configuration binds the chains it applies to; the others get the planner's choice
+    const int force_tile = p.opts.tile >= 1 && p.opts.tile <= kNumTileCfgs ? p.opts.tile
+                           : (p.opts.tile == kHaloCfg + 1 || p.opts.tile == 7 || p.opts.tile == 8) && halo_ok ? kHaloCfg + 1 : 0;
+    const int force_halo_bn = p.opts.tile == 7 ? 128 : p.opts.tile == 8 ? 64 : 0;
     static const double eff[kNumTileCfgs] = {1.0, 0.85, 0.6, 0.55};
     double best_cost = 1e300;
     int best = -1;
     ConvArgs best_args{};
     for (int cfg = 0; cfg < kNumTileCfgs; ++cfg) {
-      if (p.opts.tile > 0 && cfg != p.opts.tile - 1) continue;
+      if (force_tile > 0 && cfg != force_tile - 1) continue;
       const TileCfg& tc = kTileCfgs[cfg];
       if (conv_lds_bytes(cfg, c.mode) > p.hw.lds_bytes_per_cu) continue;   // parameter split must fit private memory
       if (st.scalar && !conv_cfg_has_scalar_loader(cfg)) continue;
@@ -427,13 +439,7 @@ struct Planner {
       const double cost = std::max((double)t.ntiles / (2.0 * num_cu), 1.0) * per_tile;
       if (cost < best_cost) { best_cost = cost; best = cfg; best_args = t; }
     }
-    // halo-staged 3x3 kernel: a TH x TW block of output pixels (256 GEMM rows) x 128 channels per workgroup,
-    // tiles laid over the images stacked with their padding rows
-    const bool halo_ok = !c.dw_w && c.R == 3 && c.S == 3 && c.stride == 1 && c.pad == 1 && !st.scalar && c.kchunk &&
-                         (c.mode == M_FLAT || (c.mode == M_ZIGZAG && c.H % 2 == 0 && c.W % 2 == 0)) &&
-                         (long long)c.N * c.in_sN < (1ll << 31) && conv_lds_bytes(kHaloCfg, c.mode) <= p.hw.lds_bytes_per_cu &&
-                         (p.opts.tile == 0 || p.opts.tile == kHaloCfg + 1);
-    if (halo_ok) {
+    if (halo_ok && (force_tile == 0 || force_tile == kHaloCfg + 1)) {
       const int step = c.mode == M_ZIGZAG ? 2 : 1;
       const long long rows = (long long)c.N * (c.H + 2);
       double best_fill = 0;
@@ -450,12 +456,21 @@ struct Planner {
       }
       if (best_fill > 0) {
         t.tiles_m = t.tiles_y * t.tiles_x;
-        t.tiles_n = (c.K + kHaloCols - 1) / kHaloCols;
-        t.ntiles = t.tiles_m * t.tiles_n;
-        // one 512-thread workgroup per compute unit; measured about 1.6x the per-flop rate of the 128x128 gather tile
-        const double per_tile = (double)kHaloRows * kHaloCols / 3.2;
-        const double cost = std::max((double)t.ntiles / num_cu, 1.0) * per_tile;
-        if (cost < best_cost || p.opts.tile == kHaloCfg + 1) { best_cost = cost; best = kHaloCfg; best_args = t; }
+        // one persistent 512-thread workgroup per compute unit walks ceil(tiles / units) tiles.  Measured per-flop
+        // rate relative to the 128x128 gather tile: about 3.2x with 128 channels per tile, about 2.6x with 64
+        // (three LDS fragment reads per two MFMAs instead of one per MFMA).
+        static const int bns[2] = {128, 64};
+        static const double rate[2] = {3.2, 2.6};
+        for (int v = 0; v < 2; ++v) {
+          if (force_halo_bn && bns[v] != force_halo_bn) continue;
+          ConvArgs u = t;
+          u.halo_bn = bns[v];
+          u.tiles_n = (c.K + bns[v] - 1) / bns[v];
+          u.ntiles = u.tiles_m * u.tiles_n;
+          const double per_tile = (double)kHaloRows * bns[v] / rate[v];
+          const double cost = (double)((u.ntiles + num_cu - 1) / num_cu) * per_tile;
+          if (cost < best_cost) { best_cost = cost; best = kHaloCfg; best_args = u; }
+        }
       }
     }
     if (best < 0) return fail(XENOS_EUNSUPPORTED, "%s: no tile configuration fits %zu bytes of LDS (or the forced one does not apply)",
@@ -812,8 +827,6 @@ struct Planner {
           }
           st.ktab_off = (long long)wpush(tab.data(), tab.size() * 4);
         }
-        xenos_status rc = split_conv(st);
-        if (rc != XENOS_OK) return rc;
         finish(last, cur, true);
         const View& ov = p.views[st.v_out];
         a.out_sN = ov.sN; a.out_sP = ov.sP; a.out_sK = ov.sK; a.out_f32 = ov.f32;
@@ -824,6 +837,8 @@ struct Planner {
           const View& rv = p.views[st.v_in2];
           a.vec_res = K % p.ce == 0 && rv.off % p.ce == 0 && rv.sP % p.ce == 0 && rv.sN % p.ce == 0;
         }
+        xenos_status rc = split_conv(st);
+        if (rc != XENOS_OK) return rc;
         st.flops = 2.0 * a.N * a.OH * a.OW * (double)K * a.R * a.S * is.c + (from_dw ? pro.flops : 0.0);
         if (from_dw) st.bytes_w += pro.bytes_w;
         st.bytes_in = view_bytes(st.v_in); st.bytes_out = view_bytes(st.v_out);
@@ -1027,7 +1042,7 @@ struct Planner {
       j += buf;
       if (s.kind == S_CONV) {
         const ConvArgs& c = s.conv;
-        const TileCfg halo_tc{kHaloRows, kHaloCols, 64, 64};
+        const TileCfg halo_tc{kHaloRows, c.halo_bn, 64, c.halo_bn / 2};
         const TileCfg stem_tc{32, c.K, 32, c.K};
         const TileCfg& tc = s.cfg == kHaloCfg ? halo_tc : s.cfg == kStemCfg ? stem_tc : kTileCfgs[s.cfg];
         snprintf(buf, sizeof buf, ",\"mode\":\"%s\",\"loader\":\"%s\",\"N\":%d,\"C\":%d,\"H\":%d,\"W\":%d,\"K\":%d,\"R\":%d,\"S\":%d,\"stride\":%d,"
@@ -1248,7 +1263,7 @@ xenos_status xenos_graph_create(const xenos_tensor_desc* input, const xenos_op_d
 
 xenos_status xenos_plan_link_split(const xenos_graph* graph, const xenos_hw_info* hw, const xenos_plan_opts* opts, xenos_plan** out) {
   if (!graph || !hw || !opts || !out || graph->magic != MAGIC_GRAPH) return fail(XENOS_EINVAL, "xenos_plan_link_split: bad argument");
-  if (opts->link < 0 || opts->link > 3 || opts->tile < 0 || opts->tile > kNumTileCfgs + 2 || (opts->compute != XENOS_F32 && opts->compute != XENOS_BF16))
+  if (opts->link < 0 || opts->link > 3 || opts->tile < 0 || opts->tile > kNumTileCfgs + 4 || (opts->compute != XENOS_F32 && opts->compute != XENOS_BF16))
     return fail(XENOS_EINVAL, "xenos_plan_link_split: option out of range");
   if (hw->num_cu <= 0 || hw->lds_bytes_per_cu == 0) return fail(XENOS_EINVAL, "xenos_plan_link_split: hardware description is empty");
   if ((graph->in.dtype == XENOS_BF16 || graph->out.dtype == XENOS_BF16) && opts->compute != XENOS_BF16)

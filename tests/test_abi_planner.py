@@ -157,7 +157,9 @@ def test_split_covers_the_output_and_fits_private_memory(cfg, batch, compute):
             assert c["patch_h"] * c["patch_w"] <= c["bm"]
             py, px = -(-c["PH"] // c["pph"]), -(-c["PW"] // c["ppw"])
             assert c["tiles_m"] == c["N"] * py * px
-        if c["loader"] == "stem":
+        if c.get("halo"):
+            assert 1 <= c["grid"] <= max(8, X.MI355X["num_cu"])      # persistent workgroups walk the tiles
+        elif c["loader"] == "stem":
             assert c["bm"] == 32 and c["tiles_n"] == 1 and 1 <= c["grid"] <= -(-c["tiles_m"] // 4)   # wavefronts stride over 32-pixel blocks
         else:
             assert c["grid"] >= c["tiles_m"] * c["tiles_n"]

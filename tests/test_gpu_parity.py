@@ -22,9 +22,11 @@ def rel_err(y, ref):
     return float(np.abs(y.astype(np.float64) - ref).max() / max(np.abs(ref).max(), 1e-30))
 
 
-def run_gpu(g, link=2, split=1, compute=0, tile=0):
+def run_gpu(g, link=2, split=1, compute=0, tile=0, hw=None):
     X = _xenos()
-    s = X.Session(g, link=link, split=split, compute=compute, tile=tile)
+    if hw is not None and hw.get("X_small"):             # a machine description with 8 compute units: long tile walks
+        hw = dict(X.MI355X, num_cu=8)
+    s = X.Session(g, link=link, split=split, compute=compute, tile=tile, hw=hw)
     try:
         y = s.forward(g.x)
         return y, s.info
@@ -145,23 +147,39 @@ def test_every_tile_configuration(kind, tile):
         check(g, ref, compute=compute, tile=tile)
 
 
-@pytest.mark.parametrize("kind,hw", [("conv3", 19), ("conv3", 7), ("cbrm2", 20), ("cbra2x3", 12), ("shortcut", 13), ("conv3", 40)])
+@pytest.mark.parametrize("kind,hw,k,bn", [("conv3", 19, 136, 128), ("conv3", 7, 136, 64), ("cbrm2", 20, 136, 128), ("cbra2", 12, 136, 128),
+                                          ("shortcut", 13, 64, 128), ("shortcut", 13, 64, 64), ("conv3", 40, 136, 128), ("conv3", 21, 64, 64),
+                                          ("cbrm2", 18, 40, 64), ("cbra2", 14, 72, 64), ("conv3x2", 11, 192, 128), ("conv3x2", 11, 192, 64)])
 @pytest.mark.parametrize("compute", [0, 1])
-def test_halo_staged_3x3_kernel(kind, hw, compute):
-    # forced tile 5 = the halo-staged 3x3 kernel: tiles lie over the images stacked with their padding rows, so
-    # with these sizes tiles straddle two images, overhang the right edge and contain dummy rows
-    n, c, k = 5, 64, 136
-    if kind == "cbra2x3":
-        b = wg.builder("halo_avg", (n, c, hw, hw), 9, nonzero_bias=True)
-        g = b.finish(b.avgpool(b.cbr(0, k, 3, 1, 1, name="c"), 2, 2))
-    elif kind == "shortcut":
-        g = chain_graph(kind, n=n, c=c, hw=hw)
+def test_halo_staged_3x3_kernel(kind, hw, k, bn, compute):
+    # forced tile 7 / 8 = the halo-staged 3x3 kernel with 128- / 64-channel tiles wherever it applies (3x3/s1/p1 chains
+    # that feed another chain): tiles lie over the images stacked with their padding rows, so with these sizes tiles
+    # straddle two images, overhang the right edge and contain dummy rows; k = 136 / 192 / 72 / 40 leave a ragged
+    # last channel tile; "conv3x2" has two channel chunks per tile; persistent workgroups walk several tiles
+    n, c = 5, 64
+    b = wg.builder("halo_" + kind, (n, c, hw, hw), 9, nonzero_bias=True)
+    if kind == "conv3":
+        t = b.cbr(0, k, 3, 1, 1, name="c")
+    elif kind == "conv3x2":
+        t = b.cbr(b.cbr(0, 128, 3, 1, 1, name="c0"), k, 3, 1, 1, name="c")
+    elif kind == "cbrm2":
+        t = b.maxpool(b.cbr(0, k, 3, 1, 1, name="c"), 2, 2)
+    elif kind == "cbra2":
+        t = b.avgpool(b.cbr(0, k, 3, 1, 1, name="c"), 2, 2)
     else:
-        g = chain_graph(kind, n=n, c=c, hw=hw, k=k)
-    y, info = check(g, compute=compute, tile=5)
-    assert any(ch.get("halo") for ch in info["chains"])
-    y1, _ = run_gpu(g, compute=compute, tile=5, split=0)
-    assert np.array_equal(y, y1)                       # split == unsplit, bit for bit
+        u = b.cbr(0, k, 3, 1, 1, name="c1")
+        v = b.cbr(u, k, 3, 1, 1, name="c2", relu=False)
+        t = b.relu(b.add(v, u))
+    t = b.cbr(t, 24, 1, 1, 0, name="head")            # the halo chains hand NHWC to this chain
+    g = b.finish(t)
+    tile = 7 if bn == 128 else 8
+    y, info = check(g, compute=compute, tile=tile)
+    halo = [ch for ch in info["chains"] if ch.get("halo")]
+    assert len(halo) == (2 if kind in ("shortcut", "conv3x2") else 1) and all(ch["bn"] == bn for ch in halo)
+    y1, _ = run_gpu(g, compute=compute, tile=tile, split=0)
+    assert np.array_equal(y, y1)                       # one workgroup walking every tile == split, bit for bit
+    y2, info2 = check(g, compute=compute, tile=tile, hw=dict(X_small=True))
+    assert np.array_equal(y, y2)                       # 8 persistent workgroups, many tiles each
 
 
 def test_small_channel_first_layer_and_nchw_output():
