@@ -92,13 +92,26 @@ def run_workload(name, steps, warmup, links=(2,), chains=False, wg=None, X=None,
             rec["chains"] = [dict(i=c["i"], name=c["name"], kind=c["kind"], ms=float(cms[c["i"]]), gflop=c["flops"] / 1e9,
                                   mb=(c["bytes_in"] + c["bytes_w"] + c["bytes_out"] + c["bytes_res"]) / 1e6,
                                   mode=c.get("mode"), tile=[c.get("bm"), c.get("bn")] if c["kind"] == "conv" else None,
-                                  loader=c.get("loader"))
+                                  loader=c.get("loader"), halo=c.get("halo", 0), ksplit=c.get("ksplit", 1))
                              for c in s.info["chains"]]
         out[LINK_NAMES[link]] = rec
         s.close()
         del s
         torch.cuda.empty_cache()
     return out, g
+
+
+def pmc_traffic(workload):
+    """HBM bytes per launch of the dominant kernel from the committed counter summary (rocprofv3 --pmc FETCH_SIZE /
+    WRITE_SIZE runs of this script), or None when no summary for this workload exists."""
+    path = os.path.join(ROOT, "profiles", "conv3x3_kernel_%s_pmc.txt" % workload)
+    try:
+        for ln in open(path):
+            if ln.startswith("traffic_bytes_per_launch:"):
+                return float(ln.split(":", 1)[1])
+    except OSError:
+        pass
+    return None
 
 
 def cpu_baseline(g, images):
@@ -119,8 +132,10 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="vgg16_n32_bf16", choices=sorted(WORKLOADS))
     ap.add_argument("--quick", action="store_true", help="headline workload, linked mode only, no CPU baseline")
-    ap.add_argument("--cpu-images", type=int, default=2)
+    ap.add_argument("--cpu-images", type=int, default=16)
     ap.add_argument("--detail", default="", help="write the full per-chain report (JSON) to this file")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="run a plain device copy of 256 MiB three times and exit (reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no collectives, no sharding); --gpus must be 1", file=sys.stderr)
@@ -134,6 +149,14 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(2)
     torch.cuda.set_device(0)
+    if args.calibrate_copy:
+        src = torch.ones(64 << 20, dtype=torch.float32, device="cuda:0")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_bytes_read": src.numel() * 4, "copy_bytes_written": dst.numel() * 4, "copies": 3}))
+        return
 
     name = args.workload
     cfg, batch, compute = WORKLOADS[name]
@@ -141,20 +164,28 @@ def main():
     head, g = run_workload(name, args.steps, args.warmup, links, chains=True, wg=wg, X=X, torch=torch)
     lk = head["linked"]
 
-    # roofline of the dominant kernel: all launches of the dense-conv MFMA kernel in one step
+    # Roofline of the dominant kernel: conv3x3_kernel (halo-staged 3x3 convolution chains on MFMA), over all its
+    # launches in one step.  achieved = algorithmic flops of those chains / their summed launch durations, measured
+    # with HIP events around every launch on the launch stream.  The other conv kernels are reported beside it.
     conv = [c for c in lk["chains"] if c["kind"] == "conv"]
-    conv_ms = sum(c["ms"] for c in conv)
-    conv_gflop = sum(c["gflop"] for c in conv)
-    compute_bound = [c for c in conv if c["gflop"] / max(c["mb"], 1e-9) * 1e3 > PEAK[compute] * 1e3 / HBM_PEAK]
-    roof = {"bound": "mfma", "kernel": "conv_kernel (implicit-GEMM MFMA, all %d launches of one step)" % len(conv),
-            "achieved": conv_gflop / conv_ms, "peak": PEAK[compute], "unit": "TFLOP/s",
-            "frac": conv_gflop / conv_ms / PEAK[compute], "traffic": None,
-            "avg_launch_ms": conv_ms / len(conv), "flops_per_launch": conv_gflop * 1e9 / len(conv),
-            "share_of_step": conv_ms / sum(c["ms"] for c in lk["chains"])}
-    if compute_bound:
-        cb_ms = sum(c["ms"] for c in compute_bound)
-        cb_gf = sum(c["gflop"] for c in compute_bound)
-        roof["compute_bound_layers"] = {"n": len(compute_bound), "achieved": cb_gf / cb_ms, "frac": cb_gf / cb_ms / PEAK[compute]}
+    dom = [c for c in conv if c.get("halo")] or conv
+    dom_ms, dom_gf = sum(c["ms"] for c in dom), sum(c["gflop"] for c in dom)
+    conv_ms, conv_gf = sum(c["ms"] for c in conv), sum(c["gflop"] for c in conv)
+    step_ms = sum(c["ms"] for c in lk["chains"])
+    roof = {"bound": "mfma", "kernel": "conv3x3_kernel (halo-staged 3x3 conv chains, %d launches per step)" % len(dom),
+            "achieved": dom_gf / dom_ms, "peak": PEAK[compute], "unit": "TFLOP/s",
+            "frac": dom_gf / dom_ms / PEAK[compute], "traffic": pmc_traffic(name),
+            "avg_launch_ms": dom_ms / len(dom), "flops_per_launch": dom_gf * 1e9 / len(dom),
+            "algorithmic_bytes_per_launch": sum(c["mb"] for c in dom) * 1e6 / len(dom),
+            "share_of_step": dom_ms / step_ms,
+            "all_conv_chains": {"n": len(conv), "achieved": conv_gf / conv_ms, "frac": conv_gf / conv_ms / PEAK[compute],
+                                "share_of_step": conv_ms / step_ms},
+            "best_layer": max(({"name": c["name"], "achieved": c["gflop"] / c["ms"], "frac": c["gflop"] / c["ms"] / PEAK[compute]}
+                               for c in dom), key=lambda d: d["achieved"])}
+    memb = [c for c in conv if c["gflop"] / max(c["mb"], 1e-9) * 1e3 < PEAK[compute] * 1e3 / HBM_PEAK]
+    if memb:    # chains whose arithmetic intensity puts them under the HBM roof (first layer, FC layers)
+        roof["memory_bound_chains"] = [{"name": c["name"], "gb_per_s": c["mb"] / c["ms"], "frac_of_hbm": c["mb"] / c["ms"] / HBM_PEAK}
+                                       for c in memb]
 
     line = {
         "metric": "images/sec + % MFMA/HBM roofline, linked vs unlinked, batch 1 and 32",

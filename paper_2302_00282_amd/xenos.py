@@ -258,6 +258,11 @@ class Session:
         self.torch.cuda.synchronize(self.device)
         return self.y.cpu().numpy()
 
+    def output(self) -> np.ndarray:
+        """Synchronises and returns the output buffer of the last run / run_graph."""
+        self.torch.cuda.synchronize(self.device)
+        return self.y.cpu().numpy()
+
     def close(self):
         xenos_destroy(self.plan)
         xenos_destroy(self.graph)

@@ -358,3 +358,28 @@ def test_full_size_batch1(cfg, compute):
     check(g, ref, compute=compute, link=0)
     if cfg == 1:
         check(g, ref, compute=compute, link=3)
+
+
+@pytest.mark.parametrize("cfg,compute,images", [(3, 1, (0, 17, 31)), (2, 1, (0, 13, 31)), (4, 0, (5, 31)), (4, 1, (0, 30))])
+def test_full_size_batch32_sampled_images(cfg, compute, images):
+    # the benchmark's launch configuration (batch 32, linked + split, graph replay) at full size; an image's result
+    # does not depend on its batch neighbours, so the oracle checks sampled images one by one
+    g = wg.build(cfg, 32)
+    X = _xenos()
+    s = X.Session(g, link=2, split=1, compute=compute)
+    try:
+        y = s.forward(g.x)                      # eager launches
+        s.y.zero_()
+        s.run_graph()
+        yg = s.output()                          # HIP-graph replay of the same plan
+    finally:
+        s.close()
+    assert np.array_equal(y, yg)
+    worst = 0.0
+    for n in images:
+        ref = xo.forward(g, g.x[n:n + 1])
+        e = rel_err(y[n:n + 1], ref)
+        worst = max(worst, e)
+        assert e <= TOL[compute], (g.name, n, e)
+    assert np.isfinite(y).all()
+    print(f"{g.name} batch 32 compute={compute} sampled images {images}: worst rel_err={worst:.3e}", flush=True)
