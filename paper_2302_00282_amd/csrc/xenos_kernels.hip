@@ -662,19 +662,48 @@ __global__ __launch_bounds__(V2_NT) void conv3x3_kernel(const ConvArgs a) {
     return ((tile_n * BN + idx / CPR) * a.Kred_pad + (idx % CPR) * CE) * ESZ;
   };
 
+  // ---- which pixel of the tile a GEMM row is ---------------------------------------------------------------
+  // A ds_read_b128 serves 16 lanes per pass and is conflict-free when their LDS rows differ mod 16 (row pitch 144 B).
+  // A pixel (ty, tx) sits in patch row ty * PWID + tx = 2 * ty + tx (mod 16), so the rows of a tile are enumerated in
+  // blocks whose 16 pixels have 16 different residues: 8 rows x 2 columns for the pixel-major enumeration, 4
+  // vertically adjacent 2x2 windows for the zig-zag one (a window covers 4 consecutive residues).  Rows left over
+  // when TH is not a multiple of 8 follow in plain order.  Any enumeration is legal: every pixel carries its own
+  // output address.
+  static_assert(PWID % 16 == 2, "the conflict-free enumeration assumes patch pitch = 2 mod 16");
+  auto flat_px = [&](int m, int& ty, int& tx) __attribute__((always_inline)) {
+    const int nbx = a.tw >> 1, rows8 = (a.tw & 1) ? 0 : (a.th >> 3) * 8, full = rows8 * a.tw;
+    if (m < full) {
+      const int b = m >> 4, i = m & 15, by = b / nbx, bx = b - by * nbx;
+      ty = by * 8 + (i >> 1); tx = bx * 2 + (i & 1);
+    } else {
+      const int r = m - full, y = r / a.tw;
+      ty = rows8 + y; tx = r - y * a.tw;
+    }
+  };
+  auto zz_win = [&](int w, int& wy, int& wx) __attribute__((always_inline)) {
+    const int hw = a.tw >> 1, rows4 = (a.th >> 3) * 4, full = rows4 * hw;
+    if (w < full) {
+      const int g = w / (4 * hw), r = w - g * 4 * hw;
+      wx = r >> 2; wy = g * 4 + (r & 3);
+    } else {
+      const int r = w - full, y = r / hw;
+      wy = rows4 + y; wx = r - y * hw;
+    }
+  };
+
   // ---- fragment addresses of this lane's rows (pixels of the tile); the same for every tile --------------
   int abase[2], bbase[TN];
 #pragma unroll
   for (int i = 0; i < 2; ++i) {
     const int m = wave_m * 64 + i * 32 + l31;
     int ty, tx;
-    bool ok;
-    if (MODE == M_FLAT) { ty = m / a.tw; tx = m - ty * a.tw; ok = ty < a.th; }
+    if (MODE == M_FLAT) flat_px(m, ty, tx);
     else {
-      const int w = m >> 2, j = m & 3, hw = a.tw >> 1;
-      const int wy = w / hw, wx = w - wy * hw;
-      ty = 2 * wy + (j >> 1); tx = 2 * wx + (j & 1); ok = ty < a.th;
+      int wy, wx;
+      zz_win(m >> 2, wy, wx);
+      ty = 2 * wy + ((m >> 1) & 1); tx = 2 * wx + (m & 1);
     }
+    const bool ok = ty < a.th && tx < a.tw;
     abase[i] = (ok ? ty * PWID + tx : 0) * LDS_ROW + lhalf * 16;
   }
 #pragma unroll
@@ -825,7 +854,8 @@ __global__ __launch_bounds__(V2_NT) void conv3x3_kernel(const ConvArgs a) {
 #pragma unroll
       for (int i = 0; i < 2; ++i) {
         const int m = wave_m * 64 + i * 32 + l31;
-        const int ty = m / a.tw, tx = m - ty * a.tw;
+        int ty, tx;
+        flat_px(m, ty, tx);
         const int qq = q0 + ty, n = qq / Hp, oh = qq - n * Hp, ow = x0 + tx;
         const bool ok = ty < a.th && n < a.N && oh < a.H && ow < a.W;
         rbase[i] = ok ? (long long)n * a.res_sN + (long long)(oh * a.OW + ow) * a.res_sP : 0;
@@ -915,13 +945,14 @@ __global__ __launch_bounds__(V2_NT) void conv3x3_kernel(const ConvArgs a) {
           if (q >= nq || k0 >= a.K) continue;
           long long ob;
           if (MODE == M_FLAT) {
-            const int ty = q / a.tw, tx = q - ty * a.tw;
+            int ty, tx;
+            flat_px(q, ty, tx);
             const int qq = q0 + ty, n = qq / Hp, oh = qq - n * Hp, ow = x0 + tx;
             if (n >= a.N || oh >= a.H || ow >= a.W) continue;
             ob = (long long)n * a.out_sN + (long long)(oh * a.OW + ow) * a.out_sP;
           } else {
-            const int hw = a.tw >> 1;
-            const int wy = q / hw, wx = q - wy * hw;
+            int wy, wx;
+            zz_win(q, wy, wx);
             const int qq = q0 + 2 * wy, n = qq / Hp, oh = qq - n * Hp, ow = x0 + 2 * wx;
             if (n >= a.N || oh >= a.H || ow >= a.W) continue;
             ob = (long long)n * a.out_sN + (long long)((oh >> 1) * a.PW + (ow >> 1)) * a.out_sP;
