@@ -582,7 +582,11 @@ __global__ __launch_bounds__(NT, 2) void conv_kernel(const ConvArgs a) {
 // output channels, columns = pixels): a lane then owns 4 consecutive channels of one pixel, the 2x2 pooling
 // window of the zig-zag enumeration is 4 neighbouring lanes (reduced with DPP quad permutes), and the finished
 // values go through LDS once, already in the output type, to be stored as whole 16-byte channel groups.
-constexpr int V2_BM = 256, V2_NT = 512, V2_PPMAX = 384;
+constexpr int V2_BM = 256, V2_PPMAX = 384;
+// wavefronts per workgroup: 8 (4 x 2 of 64 pixels x BN/2 channels).  4 wavefronts of 64 x BN (a quarter fewer LDS
+// fragment reads per MFMA) were measured 20-60 % slower: one wavefront per SIMD cannot hide the fragment-read latency.
+constexpr int V2_NW = 8;
+constexpr int V2_NT = 64 * V2_NW;
 // 0: the LDS writes that publish the next step follow the MFMAs of a tap; 1: they are interleaved after the first
 // k-group.  Measured on VGG-16 layers (batch 32, bf16): 1 is 4-7 % slower (the writes then delay the fragment reads).
 constexpr int V2_SCHED = 0;
@@ -605,9 +609,10 @@ __global__ __launch_bounds__(V2_NT) void conv3x3_kernel(const ConvArgs a) {
   using tr = Tr<T>;
   constexpr int CE = tr::CE, BKE = tr::BKE, ESZ = (int)sizeof(T);
   constexpr int BM = V2_BM, NTH = V2_NT;
-  constexpr int WN = BN / 2, TN = WN / 32;                         // 4 x 2 wavefronts of 64 pixels x WN channels
-  constexpr int A_IT = V2_PPMAX * CPR / NTH;                       // 6 patch chunks per thread
-  constexpr int B_IT = BN * CPR / NTH;                             // 2 or 1 weight chunks per thread
+  constexpr int WAVES_N = V2_NW / 4;                               // 4 x WAVES_N wavefronts of 64 pixels x WN channels
+  constexpr int WN = BN / WAVES_N, TN = WN / 32;
+  constexpr int A_IT = V2_PPMAX * CPR / NTH;                       // patch chunks per thread
+  constexpr int B_IT = BN * CPR / NTH;                             // weight chunks per thread
   constexpr int BBYTES = BN * LDS_ROW;
   constexpr int CG = BN / CE;                                      // 16-byte channel groups per output row
   constexpr int SPB = BN * ESZ + 16;                               // staging row pitch in bytes
@@ -618,7 +623,7 @@ __global__ __launch_bounds__(V2_NT) void conv3x3_kernel(const ConvArgs a) {
 
   extern __shared__ __align__(16) unsigned char smem[];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wave_m = wave >> 1, wave_n = wave & 1;
+  const int wave_m = wave / WAVES_N, wave_n = wave % WAVES_N;
   const int l31 = lane & 31, lhalf = lane >> 5;
 
   const int PP = (a.th + 2) * PWID, Hp = a.H + 2;               // a.tw + 2 <= PWID
@@ -638,9 +643,10 @@ __global__ __launch_bounds__(V2_NT) void conv3x3_kernel(const ConvArgs a) {
   // ---- what this thread loads for a tile: 6 chunks of the input patch, B_IT chunks of the weight tile ------
   int aoff[A_IT];
   unsigned aok = 0;
-  int wrow0 = 0, wrow1 = 0, wnext0 = 0, wnext1 = 0;                // byte offsets into the packed weights of this thread's one or
-                                                                   // two chunks: this tile's, the next tile's (scalars, not arrays:
-                                                                   // arrays selected by a run-time flag end up in scratch memory)
+  // byte offset of this thread's first weight chunk in the packed weights, for this tile and for the next one; its
+  // other chunks lie NTH / 8 rows further each
+  int wrow = 0, wnext = 0;
+  const int wstride = (NTH / CPR) * a.Kred_pad * ESZ;
   auto patch_addr = [&](int l) __attribute__((always_inline)) {
     const int tile_m = m0 + l % mlen;
     const int tyi = tile_m / a.tiles_x;
@@ -657,9 +663,9 @@ __global__ __launch_bounds__(V2_NT) void conv3x3_kernel(const ConvArgs a) {
       aok |= (ok ? 1u : 0u) << it;
     }
   };
-  auto weight_addr = [&](int l, int it) __attribute__((always_inline)) -> int {
-    const int tile_n = l / mlen, idx = tid + it * NTH;
-    return ((tile_n * BN + idx / CPR) * a.Kred_pad + (idx % CPR) * CE) * ESZ;
+  auto weight_addr = [&](int l) __attribute__((always_inline)) -> int {
+    const int tile_n = l / mlen;
+    return ((tile_n * BN + tid / CPR) * a.Kred_pad + (tid % CPR) * CE) * ESZ;
   };
 
   // ---- which pixel of the tile a GEMM row is ---------------------------------------------------------------
@@ -729,7 +735,7 @@ __global__ __launch_bounds__(V2_NT) void conv3x3_kernel(const ConvArgs a) {
   };
   auto load_w = [&](int step, u32x4_t* rb) {
 #pragma unroll
-    for (int it = 0; it < B_IT; ++it) rb[it] = *(const u32x4_t*)((const unsigned char*)a.w + (it == 0 ? wrow0 : wrow1) + step * ROWB);
+    for (int it = 0; it < B_IT; ++it) rb[it] = *(const u32x4_t*)((const unsigned char*)a.w + wrow + it * wstride + step * ROWB);
   };
   auto store_w = [&](int stage, const u32x4_t* rb) {
     unsigned char* sb = smem + 2 * V2_ABYTES + stage * BBYTES;
@@ -803,7 +809,7 @@ __global__ __launch_bounds__(V2_NT) void conv3x3_kernel(const ConvArgs a) {
         // ... which for the last two taps of a tile are steps 0 and 1 of the next tile
 #pragma unroll
         for (int it = 0; it < B_IT; ++it) {
-          const int src = last ? (it == 0 ? wnext0 : wnext1) + (tap - 7) * ROWB : (it == 0 ? wrow0 : wrow1) + (step0 + tap + 2) * ROWB;
+          const int src = (last ? wnext + (tap - 7) * ROWB : wrow + (step0 + tap + 2) * ROWB) + it * wstride;
           rb[it] = *(const u32x4_t*)((const unsigned char*)a.w + src);
         }
       }
@@ -822,8 +828,7 @@ __global__ __launch_bounds__(V2_NT) void conv3x3_kernel(const ConvArgs a) {
 
   // ---- pipeline start: chunk 0 and weight steps 0, 1 of the first tile ---------------------------------
   patch_addr(li);
-  wrow0 = weight_addr(li, 0);
-  if (B_IT > 1) wrow1 = weight_addr(li, 1);
+  wrow = weight_addr(li);
   load_patch(0, 0);
   load_w(0, rb0);
   store_patch(0, 0);
@@ -973,12 +978,11 @@ __global__ __launch_bounds__(V2_NT) void conv3x3_kernel(const ConvArgs a) {
     if (last) {
       const int lnext = li + wgs < ntl ? li + wgs : li;            // after the last tile: reload it (never used)
       patch_addr(lnext);
-      wnext0 = weight_addr(lnext, 0);
-      if (B_IT > 1) wnext1 = weight_addr(lnext, 1);
+      wnext = weight_addr(lnext);
     }
     chunk_body(cc, last, par);
     if (!last) { ++cc; return false; }
-    wrow0 = wnext0; wrow1 = wnext1;
+    wrow = wnext;
     epilogue(par);
 #pragma unroll
     for (int i = 0; i < 2; ++i)
