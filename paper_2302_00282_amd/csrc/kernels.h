@@ -36,10 +36,11 @@ static const TileCfg kTileCfgs[] = {
 static const int kNumTileCfgs = 4;
 // Configuration index of the halo-staged 3x3 kernel: 256 pixels x 128 or 64 channels, 512 threads, TH x TW spatial tile.
 static const int kHaloCfg = 4;
-// Configuration index of the first-layer kernel: 32 pixels x K (32 or 64) channels per wavefront, reduction C*R*S <= 32,
-// gathered straight from the graph input through `ktab`.
+// Configuration index of the first-layer kernel: 32 pixels x K (32 or 64) channels per wavefront, the reduction
+// C*R*S (at most kStemRed, in up to kStemPasses MFMA passes of 32) gathered straight from the graph input through `ktab`.
 static const int kStemCfg = 5;
-static const int kStemRed = 32;
+static const int kStemPasses = 5;
+static const int kStemRed = 32 * kStemPasses;
 static const int kHaloRows = 256, kHaloCols = 128, kHaloPatchMax = 384;
 // the staged patch has one of two fixed row pitches (pixels): tiles up to 16 or up to 32 pixels wide
 static const int kHaloPitchNarrow = 18, kHaloPitchWide = 34;

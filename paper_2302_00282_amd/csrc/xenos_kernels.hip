@@ -1033,18 +1033,19 @@ static int launch_conv3x3_t(const ConvArgs& a, hipStream_t st) {
 }
 
 // ---------------------------------------------------------------------------------------------
-// First-layer chain: a dense convolution whose whole reduction C*R*S fits one 32-deep MFMA pass (the 3-channel
-// image layer), reading the caller's graph input where it lies (any strides, fp32 or the compute type) and
-// writing the consumer's NHWC layout: the layout transform at the graph boundary (transpose operator, Table 3)
-// is linked into its consumer (Section 4.1), so the input is read once and no converted copy is written.
+// First-layer chain: a dense convolution with a short reduction C*R*S <= 160 (the 3-channel image layer: 3x3 -> 27,
+// 7x7 -> 147), reading the caller's graph input where it lies (any strides, fp32 or the compute type) and writing
+// the consumer's NHWC layout: the layout transform at the graph boundary (transpose operator, Table 3) is linked
+// into its consumer (Section 4.1), so the input is read once and no converted copy is written.
 //
 // The GEMM is computed transposed (rows = output channels, columns = pixels): in the MFMA accumulator layout a
-// lane then owns 4 consecutive channels of one pixel, which it scales, shifts, clamps and stores directly.
-// One wavefront = 32 consecutive output pixels x all K = 32*KB channels; lane (p, h) holds the reduction slots
-// k(i) = (i/8)*16 + h*8 + i%8, i = 0..15, of pixel p (bf16: two 8-element MFMA operands; fp32: 16 single ones).
+// lane then owns 4 consecutive channels of one pixel, which it scales, shifts and clamps in registers.
+// One wavefront = 32 consecutive output pixels x all K = 32*KB channels; the reduction runs in passes of 32: in
+// pass p lane (pixel, h) holds the slots k(i) = 32*p + (i/8)*16 + h*8 + i%8, i = 0..15 (bf16: two 8-element MFMA
+// operands; fp32: 16 single ones), gathered through the table `ktab` = {input offset, tap row / column} per slot.
 // ---------------------------------------------------------------------------------------------
 template <typename T, int KB>
-__global__ __launch_bounds__(NT, 4) void stem_kernel(const ConvArgs a) {
+__global__ __launch_bounds__(NT, sizeof(T) == 2 ? 4 : 2) void stem_kernel(const ConvArgs a) {
   using tr = Tr<T>;
   __shared__ __align__(16) float s_scale[KB * 32];
   __shared__ __align__(16) float s_shift[KB * 32];
@@ -1053,27 +1054,30 @@ __global__ __launch_bounds__(NT, 4) void stem_kernel(const ConvArgs a) {
   constexpr int PPI = 64 / CPP;                                      // pixels per store instruction
   constexpr int SPITCH = KB * 32 * (int)sizeof(T) + 16;              // staging row pitch (odd number of 16-byte slots)
   __shared__ __align__(16) unsigned char s_stage[(NT / 64) * 32 * SPITCH];
-  __shared__ int2 s_tab[2][16];                                     // per lane half and slot: {input offset, (r << 16) | s}
+  __shared__ int2 s_tab[kStemPasses][2][16];                        // per pass, lane half and slot: {input offset, (r << 16) | s}
+  const int npass = (a.Kred + 31) / 32;                             // 32-deep MFMA passes over the reduction (<= kStemPasses)
   if (tid < KB * 32) { s_scale[tid] = a.scale[tid]; s_shift[tid] = a.shift[tid]; }
-  if (tid < 32) {
-    const int hh = tid >> 4, i = tid & 15, k = (i / 8) * 16 + hh * 8 + i % 8;
-    s_tab[hh][i] = make_int2(a.ktab[2 * k], a.ktab[2 * k + 1]);
+  if (tid < npass * 32) {
+    const int p = tid >> 5, hh = (tid >> 4) & 1, i = tid & 15, k = p * 32 + (i / 8) * 16 + hh * 8 + i % 8;
+    s_tab[p][hh][i] = make_int2(a.ktab[2 * k], a.ktab[2 * k + 1]);
   }
   __syncthreads();
-  // weight operands: channel 32*b + l31, the same reduction slots
+  // weight operands of one pass: channel 32*b + l31, the same reduction slots
   constexpr int WV = sizeof(T) == 2 ? 1 : 2;                         // 16-byte vectors per 8 elements
-  u32x4_t wf[KB][2][WV];
+  u32x4_t wn[KB][2][WV];
+  auto load_w = [&](int p) {
 #pragma unroll
-  for (int b = 0; b < KB; ++b)
+    for (int b = 0; b < KB; ++b)
 #pragma unroll
-    for (int q = 0; q < 2; ++q)
+      for (int q = 0; q < 2; ++q)
 #pragma unroll
-      for (int v = 0; v < WV; ++v)
-        wf[b][q][v] = *(const u32x4_t*)((const unsigned char*)a.w +
-                                        ((size_t)(32 * b + l31) * a.Kred_pad + q * 16 + h * 8) * sizeof(T) + v * 16);
+        for (int v = 0; v < WV; ++v)
+          wn[b][q][v] = *(const u32x4_t*)((const unsigned char*)a.w +
+                                          ((size_t)(32 * b + l31) * a.Kred_pad + p * 32 + q * 16 + h * 8) * sizeof(T) + v * 16);
+  };
 
   const int OHW = a.OH * a.OW, nblk = a.tiles_m, bstride = gridDim.x * (NT / 64);
-  auto gather = [&](int blk, float* v) {
+  auto gather = [&](int blk, int pass, float* v) {
     const int m = blk * 32 + l31;
     const bool valid = m < a.M_total;
     const int mm = valid ? m : 0;
@@ -1087,14 +1091,14 @@ __global__ __launch_bounds__(NT, 4) void stem_kernel(const ConvArgs a) {
         const float* pb = (const float*)a.in + base;
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
-          const int2 t = s_tab[h][i];
+          const int2 t = s_tab[pass][h][i];
           const float x = pb[(t.y >> 16) < a.R ? t.x : 0];            // padding slots of the reduction read a valid address ...
           v[i] = (t.y >> 16) < a.R ? x : 0.f;                          // ... and contribute zero
         }
       } else {
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
-          const int2 t = s_tab[h][i];
+          const int2 t = s_tab[pass][h][i];
           const float x = tr::ld(a.in, base + ((t.y >> 16) < a.R ? t.x : 0));
           v[i] = (t.y >> 16) < a.R ? x : 0.f;
         }
@@ -1102,7 +1106,7 @@ __global__ __launch_bounds__(NT, 4) void stem_kernel(const ConvArgs a) {
     } else {
 #pragma unroll
       for (int i = 0; i < 16; ++i) {
-        const int2 t = s_tab[h][i];
+        const int2 t = s_tab[pass][h][i];
         const bool ok = valid && (unsigned)(iy0 + (t.y >> 16)) < (unsigned)a.H && (unsigned)(ix0 + (t.y & 0xffff)) < (unsigned)a.W;
         const long long idx = ok ? base + t.x : 0;
         const float x = a.in_f32 ? ((const float*)a.in)[idx] : tr::ld(a.in, idx);
@@ -1111,18 +1115,36 @@ __global__ __launch_bounds__(NT, 4) void stem_kernel(const ConvArgs a) {
     }
   };
 
-  int blk = blockIdx.x * (NT / 64) + wave;
+  // Steps = (pixel block, pass) pairs in sequence; the gather (and, with several passes, the weights) of the next
+  // step are in flight while the current one is multiplied.
+  int blk = blockIdx.x * (NT / 64) + wave, pass = 0;
   float vn[16];
-  if (blk < nblk) gather(blk, vn);
-  for (; blk < nblk; blk += bstride) {
-    f32x16_t acc[KB];
+  if (blk < nblk) { gather(blk, 0, vn); load_w(0); }
+  f32x16_t acc[KB];
+#pragma unroll
+  for (int b = 0; b < KB; ++b)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) acc[b][e] = 0.f;
+  while (blk < nblk) {
+    float v[16];
+    u32x4_t wf[KB][2][WV];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) v[i] = vn[i];
 #pragma unroll
     for (int b = 0; b < KB; ++b)
 #pragma unroll
-      for (int e = 0; e < 16; ++e) acc[b][e] = 0.f;
+      for (int q = 0; q < 2; ++q)
+#pragma unroll
+        for (int w = 0; w < WV; ++w) wf[b][q][w] = wn[b][q][w];
+    const int cur_blk = blk;
+    const bool last_pass = pass == npass - 1;
+    if (last_pass) { blk += bstride; pass = 0; } else ++pass;
+    if (blk < nblk) {
+      gather(blk, pass, vn);
+      if (npass > 1) load_w(pass);
+    }
     if constexpr (sizeof(T) == 2) {
-      const u32x4_t p0 = tr::pack(vn), p1 = tr::pack(vn + 8);      // round the image to the compute type
-      if (blk + bstride < nblk) gather(blk + bstride, vn);
+      const u32x4_t p0 = tr::pack(v), p1 = tr::pack(v + 8);        // round the image to the compute type
 #pragma unroll
       for (int b = 0; b < KB; ++b) {
         acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, wf[b][0][0]),
@@ -1131,16 +1153,13 @@ __global__ __launch_bounds__(NT, 4) void stem_kernel(const ConvArgs a) {
                                                          __builtin_bit_cast(bf16x8_t, p1), acc[b], 0, 0, 0);
       }
     } else {
-      float v[16];
-#pragma unroll
-      for (int i = 0; i < 16; ++i) v[i] = vn[i];
-      if (blk + bstride < nblk) gather(blk + bstride, vn);
 #pragma unroll
       for (int b = 0; b < KB; ++b)
 #pragma unroll
         for (int i = 0; i < 16; ++i)
           acc[b] = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(wf[b][i / 8][(i % 8) / 4][i % 4]), v[i], acc[b], 0, 0, 0);
     }
+    if (!last_pass) continue;
     // epilogue: lane = pixel l31, channels 32*b + 8*g + 4*h + (0..3) in accumulator elements 4*g + (0..3).  The
     // finished values are transposed through this wavefront's LDS slice so that every store instruction writes
     // whole pixels (contiguous K*sizeof(T)-byte rows) instead of 4-channel fragments of 32 different pixels.
@@ -1171,13 +1190,17 @@ __global__ __launch_bounds__(NT, 4) void stem_kernel(const ConvArgs a) {
     for (int it = 0; it < 32 / PPI; ++it) {
       const int px = it * PPI + lane / CPP, ch = lane % CPP;
       const u32x4_t o = *(const u32x4_t*)(stg + px * SPITCH + ch * 16);
-      const int m = blk * 32 + px;
+      const int m = cur_blk * 32 + px;
       if (m < a.M_total) {
         const int n = m / OHW, p = m - n * OHW;
         *(u32x4_t*)((unsigned char*)a.out + ((long long)n * a.out_sN + (long long)p * a.out_sP) * (long long)sizeof(T) + ch * 16) = o;
       }
     }
     __builtin_amdgcn_wave_barrier();
+#pragma unroll
+    for (int b = 0; b < KB; ++b)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[b][e] = 0.f;
   }
 }
 
@@ -1185,7 +1208,7 @@ template <typename T>
 static int launch_stem_t(const ConvArgs& a, hipStream_t st) {
   // what the kernel assumes: one 32-deep pass, K = 32 or 64, pixel-major rows, plain chain, aligned NHWC output
   const int esz = (int)sizeof(T);
-  if (a.Kred > 32 || a.Kred_pad < 32 || !a.ktab || a.mode != M_FLAT || a.has_res || a.pool != POOL_NONE || a.dw_w || a.ksplit > 1 ||
+  if (a.Kred > kStemRed || a.Kred_pad < (a.Kred + 31) / 32 * 32 || !a.ktab || a.mode != M_FLAT || a.has_res || a.pool != POOL_NONE || a.dw_w || a.ksplit > 1 ||
       a.out_sK != 1 || (a.out_f32 && esz != 4) || (a.out_sP * esz) % 16 != 0 || (a.out_sN * esz) % 16 != 0 ||
       ((uintptr_t)a.out & 15) || ((uintptr_t)a.w & 15) || (a.Kred_pad * esz) % 16 != 0 || a.H > 8192 ||
       a.tiles_m != (a.M_total + 31) / 32 || a.M_total != a.N * a.OH * a.OW)
@@ -1476,8 +1499,54 @@ __global__ __launch_bounds__(NT) void pool_kernel(const PoolArgs a) {
   }
 }
 
+// Window pooling over whole 16-byte channel groups: one thread = one channel group of one output pixel.
+template <typename T>
+__global__ __launch_bounds__(NT) void pool_vec_kernel(const PoolArgs a) {
+  using tr = Tr<T>;
+  constexpr int CE = tr::CE;
+  const int CV = a.C / CE;
+  const long long total = (long long)a.N * a.OH * a.OW * CV;
+  for (long long idx = (long long)blockIdx.x * NT + threadIdx.x; idx < total; idx += (long long)gridDim.x * NT) {
+    const int cv = (int)(idx % CV);
+    long long q = idx / CV;
+    const int ow = (int)(q % a.OW); q /= a.OW;
+    const int oh = (int)(q % a.OH);
+    const int n = (int)(q / a.OH);
+    const T* ib = (const T*)a.in + (long long)n * a.in_sN + cv * CE;
+    float mx[CE], sum[CE];
+#pragma unroll
+    for (int e = 0; e < CE; ++e) { mx[e] = -INFINITY; sum[e] = 0.f; }
+    int cnt = 0, cntp = 0;
+    for (int i = 0; i < a.k; ++i)
+      for (int j = 0; j < a.k; ++j) {
+        const int ih = oh * a.s - a.p + i, iw = ow * a.s - a.p + j;
+        if (ih < a.H + a.p && iw < a.W + a.p) ++cntp;
+        if (ih < 0 || ih >= a.H || iw < 0 || iw >= a.W) continue;
+        float v[CE];
+        tr::unpack(*(const u32x4_t*)(ib + ((long long)ih * a.W + iw) * a.in_sP), v);
+#pragma unroll
+        for (int e = 0; e < CE; ++e) { mx[e] = fmaxf(mx[e], v[e]); sum[e] += v[e]; }
+        ++cnt;
+      }
+    float r[CE];
+    const float div = (float)(a.cip ? cntp : cnt);
+#pragma unroll
+    for (int e = 0; e < CE; ++e) r[e] = a.kind == POOL_MAX ? mx[e] : sum[e] / div;
+    *(u32x4_t*)((T*)a.out + (long long)n * a.out_sN + ((long long)oh * a.OW + ow) * a.out_sP + cv * CE) = tr::pack(r);
+  }
+}
+
 int launch_pool(const PoolArgs& a, int dtype, void* stream) {
   hipStream_t st = (hipStream_t)stream;
+  const int ce = dtype == DT_BF16 ? 8 : 4, esz = dtype == DT_BF16 ? 2 : 4;
+  const bool vec = a.kind != POOL_GAP && a.C % ce == 0 && a.in_sP % ce == 0 && a.in_sN % ce == 0 && a.out_sP % ce == 0 &&
+                   a.out_sN % ce == 0 && ((uintptr_t)a.in & 15) == 0 && ((uintptr_t)a.out & 15) == 0 && esz > 0;
+  if (vec) {
+    const int grid = grid_for((long long)a.N * a.OH * a.OW * (a.C / ce), NT);
+    if (dtype == DT_BF16) hipLaunchKernelGGL(pool_vec_kernel<bf16_t>, dim3(grid), dim3(NT), 0, st, a);
+    else hipLaunchKernelGGL(pool_vec_kernel<float>, dim3(grid), dim3(NT), 0, st, a);
+    return (int)hipGetLastError();
+  }
   const int grid = grid_for((long long)a.N * a.OH * a.OW * a.C, NT);
   if (dtype == DT_BF16) hipLaunchKernelGGL(pool_kernel<bf16_t>, dim3(grid), dim3(NT), 0, st, a);
   else hipLaunchKernelGGL(pool_kernel<float>, dim3(grid), dim3(NT), 0, st, a);

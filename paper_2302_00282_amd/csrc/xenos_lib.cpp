@@ -467,6 +467,9 @@ struct Planner {
           u.halo_bn = bns[v];
           u.tiles_n = (c.K + bns[v] - 1) / bns[v];
           u.ntiles = u.tiles_m * u.tiles_n;
+          // Below half a tile per unit the long per-tile pipeline of this kernel (and its 512-thread epilogue) loses
+          // to the small gather tiles, which can also split the reduction (measured on the batch-1 networks).
+          if (2 * u.ntiles < num_cu && force_tile == 0) continue;
           const double per_tile = (double)kHaloRows * bns[v] / rate[v];
           const double cost = (double)((u.ntiles + num_cu - 1) / num_cu) * per_tile;
           if (cost < best_cost) { best_cost = cost; best = kHaloCfg; best_args = u; }
@@ -704,6 +707,21 @@ struct Planner {
         cur = nx + 1; last = nx;
         if (stage == 4) break;
       }
+      // A first layer that can read the graph input in place (stem kernel) does so; that kernel has no pooling
+      // epilogue, so a pooling that follows it runs as its own pass over the (NHWC, compute-type) result.  Measured
+      // on the 7x7/2 + 3x3/2-pool and 3x3/2 + 3x3/2-pool first layers, the two passes take about a third of the time
+      // of import + a pooled gather chain.
+      bool stem = false;
+      if (!dw && !is_fc && nd.in[0] == 0 && in_lazy && link >= 2 && !has_res && is.c * d.kh * d.kw <= kStemRed && (K == 32 || K == 64) &&
+          is.h <= 8192 && (p.opts.tile == 0 || p.opts.tile == kStemCfg + 1)) {
+        // l2 = last node of the chain without its pooling, c2 = that node's output tensor
+        const int l2 = pool_node < 0 ? last : absorbed.size() >= 2 ? absorbed[absorbed.size() - 2] : i;
+        const int c2 = l2 + 1;
+        if (c2 != out_tid && !placed.count(c2)) {
+          stem = true;
+          if (pool_node >= 0) { absorbed.pop_back(); pool_node = -1; cur = c2; last = l2; }
+        }
+      }
       for (int a : absorbed) st.ops.push_back(nodes[a].src);
 
       if (dw) {
@@ -769,8 +787,7 @@ struct Planner {
         const DwPro pro = dwpro;
         dwpro.active = false;
         if (!from_dw && nd.in[0] == 0 && in_lazy) {
-          st.stem = link >= 2 && !is_fc && pool_node < 0 && !has_res && is.c * d.kh * d.kw <= kStemRed && (K == 32 || K == 64) &&
-                    cur != out_tid && !placed.count(cur) && is.h <= 8192 && (p.opts.tile == 0 || p.opts.tile == kStemCfg + 1);
+          st.stem = stem;
           if (!st.stem && !in_gather) import_input();
         }
         const int vin = from_dw ? pro.v_in : tview[nd.in[0]];

@@ -118,11 +118,14 @@ def test_linking_patterns_of_the_workloads():
     convs = [c for c in res["chains"] if c["kind"] == "conv"]
     # every shortcut add is executed by a conv chain (in its epilogue, or in the summing pass of a reduction split)
     assert sum(any(g2.ops[o].kind == "add" for o in c["ops"]) for c in convs) == 8
-    assert all(c["kind"] in ("conv", "splitk_finish") for c in res["chains"])
-    assert convs[0]["mode"] == "patch" and convs[0]["pool"] == 1      # stem conv + 3x3/2 max-pool
+    # the 7x7/2 first layer reads the caller's NCHW tensor in place; its 3x3/2 max-pool is the only stand-alone pass
+    assert convs[0]["loader"] == "stem" and res["chains"][1]["kind"] == "pool"
+    assert all(c["kind"] in ("conv", "splitk_finish") for c in res["chains"][2:])
     assert convs[-2]["mode"] == "gap"                          # last block + global average (CBRA)
     sq = plan_json(wg.build(4, 1, draw=False), link=2, compute=X.XENOS_BF16)["plan"]
-    assert all(c["kind"] == "conv" for c in sq["chains"] if c["name"] != "import")   # concat and pools cost no pass
+    assert sq["chains"][0]["loader"] == "stem" and sq["chains"][1]["kind"] == "pool"
+    assert all(c["kind"] == "conv" for c in sq["chains"][2:])            # concat and the later pools cost no pass
+    assert sum(c["mode"] == "patch" for c in sq["chains"][2:]) == 4      # 3x3/2 ceil-mode pools linked into both expand convs, twice
     offs = sorted({(c["out_c_off"], c["out_sP"]) for c in sq["chains"] if c["kind"] == "conv" and c["out_c_off"]})
     assert (64, 128) in offs and (256, 512) in offs            # expand3x3 halves land at their channel offset
     vgg = plan_json(wg.build(3, 2, draw=False), link=2, compute=X.XENOS_BF16)["plan"]

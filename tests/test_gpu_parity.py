@@ -195,18 +195,25 @@ def test_small_channel_first_layer_and_nchw_output():
 
 
 @pytest.mark.parametrize("compute", [0, 1])
-@pytest.mark.parametrize("k,ksz,stride,pad,hw,c", [(64, 3, 1, 1, 37, 3), (32, 3, 2, 1, 30, 3), (64, 3, 2, 0, 21, 3), (32, 5, 1, 2, 17, 1),
-                                                   (64, 1, 1, 0, 11, 4), (64, 2, 2, 0, 10, 8)])
-def test_first_layer_reads_the_graph_input_in_place(k, ksz, stride, pad, hw, c, compute):
-    # C*R*S <= 32 and K in {32, 64}: the first chain gathers from the caller's NCHW fp32 tensor (no import pass)
-    # and hands NHWC to the next chain; 3 images x odd sizes give ragged 32-pixel blocks
+@pytest.mark.parametrize("k,ksz,stride,pad,hw,c,pool", [(64, 3, 1, 1, 37, 3, 0), (32, 3, 2, 1, 30, 3, 0), (64, 3, 2, 0, 21, 3, 0), (32, 5, 1, 2, 17, 1, 0),
+                                                        (64, 1, 1, 0, 11, 4, 0), (64, 2, 2, 0, 10, 8, 0), (64, 7, 2, 3, 45, 3, 0), (32, 5, 1, 2, 19, 3, 0),
+                                                        (64, 3, 1, 1, 14, 8, 0), (64, 7, 2, 3, 50, 3, 1), (64, 3, 2, 0, 41, 3, 2), (32, 4, 1, 1, 12, 10, 0)])
+def test_first_layer_reads_the_graph_input_in_place(k, ksz, stride, pad, hw, c, pool, compute):
+    # C*R*S <= 160 (1 to 5 MFMA passes of 32) and K in {32, 64}: the first chain gathers from the caller's NCHW fp32
+    # tensor (no import pass) and hands NHWC to the next chain; 3 images x odd sizes give ragged 32-pixel blocks.
+    # pool 1 / 2: a 3x3/2 max-pool (pad 1 / ceil mode) follows and runs as its own vectorised pass.
     b = wg.builder("stem", (3, c, hw, hw), 17, nonzero_bias=True)
     t = b.cbr(0, k, ksz, stride, pad, name="c0")
+    if pool == 1:
+        t = b.maxpool(t, 3, 2, 1)
+    elif pool == 2:
+        t = b.maxpool(t, 3, 2, 0, ceil=1)
     t = b.cbr(t, 24, 3, 1, 1, name="c1")
     g = b.finish(t)
     ref = xo.forward(g)
     y, info = check(g, ref, compute=compute, link=2)
-    assert info["chains"][0]["loader"] == "stem" and info["n_chains"] == 2
+    assert info["chains"][0]["loader"] == "stem" and info["n_chains"] == (3 if pool else 2)
+    assert not pool or info["chains"][1]["kind"] == "pool"
     y0, i0 = check(g, ref, compute=compute, link=1)          # un-linked: the general kernel (after an import pass if the input is large)
     assert all(c.get("loader") != "stem" for c in i0["chains"])
     ys, _ = run_gpu(g, compute=compute, link=2, split=0)
