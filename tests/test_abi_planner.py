@@ -193,3 +193,23 @@ def test_planning_time_is_reported_scale():
     X.xenos_destroy(P)
     X.xenos_destroy(G)
     assert dt < 5.0            # the paper reports 0.11 s for MobileNet (Table 2); same order of magnitude
+
+
+def test_table4_graphs_follow_the_printed_shapes():
+    # tests/golden/table4_shapes.txt holds the shapes printed in Table 4 (first row with the stated reading)
+    import os
+    rows = {}
+    for ln in open(os.path.join(os.path.dirname(__file__), "golden", "table4_shapes.txt")):
+        if ln.startswith("#") or not ln.strip():
+            continue
+        f = ln.split()
+        rows[f[0]] = [int(x) for x in f[1:8]]
+    names = {"cbr_maxpool": "CBR-MaxPooling", "cbr_avgpool": "CBR-AvgPooling", "fully_connected": "FullyConnected", "cbr": "CBR"}
+    assert set(names) == set(wg.TABLE4)
+    for key, printed in names.items():
+        h, w, c, r, s_, c2, k = rows[printed]
+        assert wg.TABLE4[key][:6] == (h, w, c, r, s_, k) and c2 == c
+        g = wg.table4(key, batch=1, draw=False)
+        q = plan_json(g, link=2, compute=X.XENOS_BF16)["plan"]
+        assert sum(ch["kind"] == "conv" for ch in q["chains"]) == 1                  # one linked chain each (plus the input conversion)
+        assert all(ch["kind"] in ("conv", "cvt", "splitk_finish") for ch in q["chains"])

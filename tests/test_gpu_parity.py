@@ -390,3 +390,16 @@ def test_full_size_batch32_sampled_images(cfg, compute, images):
         assert e <= TOL[compute], (g.name, n, e)
     assert np.isfinite(y).all()
     print(f"{g.name} batch 32 compute={compute} sampled images {images}: worst rel_err={worst:.3e}", flush=True)
+
+
+@pytest.mark.parametrize("name", sorted(wg.TABLE4))
+@pytest.mark.parametrize("compute", [0, 1])
+def test_table4_micro_benchmark_operators(name, compute):
+    # the operators of the paper's micro-benchmark (Table 4), with and without the optimisation each row measures
+    g = wg.table4(name, batch=2, nonzero_bias=True)
+    ref = xo.forward(g)
+    y, info = check(g, ref, compute=compute, link=2, split=1)
+    check(g, ref, compute=compute, link=1, split=1)            # without linking
+    y0, _ = check(g, ref, compute=compute, link=2, split=0)    # without the operator split
+    if not any(c["kind"] == "splitk_finish" for c in info["chains"]):
+        assert np.array_equal(y, y0)

@@ -286,6 +286,31 @@ def squeezenet11(batch=1, seed=None, hw=224, classes=1000, nonzero_bias=False, d
     return b.finish(t)
 
 
+# Operator micro-benchmark shapes (Table 4): name -> (feature map H, W, C; kernel R, S; out channels K; what follows)
+TABLE4 = {
+    "cbr_maxpool": (224, 224, 3, 3, 3, 24, "maxpool"),      # printed with inC 24 / outC 224; read as 3 -> 24 (inC must be 3)
+    "cbr_avgpool": (7, 7, 1024, 1, 1, 1024, "gap"),         # CBRA: pointwise conv + global average (MobileNet tail)
+    "fully_connected": (1, 1, 1536, 1, 1, 1000, "fc"),
+    "cbr": (112, 112, 32, 1, 1, 64, "none"),
+}
+
+
+def table4(name: str, batch=1, seed=None, nonzero_bias=False, draw=True) -> Graph:
+    """One operator of the paper's micro-benchmark (Table 4) as a graph of its own."""
+    h, w, c, r, s_, k, tail = TABLE4[name]
+    idx = sorted(TABLE4).index(name)
+    b = _Builder("table4_" + name, (batch, c, h, w), seed_for(10 + idx, batch) if seed is None else seed, nonzero_bias, draw)
+    if tail == "fc":
+        t = b.fc(0, k, name="fc")
+    else:
+        t = b.cbr(0, k, r, 1, r // 2, name="c0")
+        if tail == "maxpool":
+            t = b.maxpool(t, 2, 2, name="pool")
+        elif tail == "gap":
+            t = b.gap(t, name="gap")
+    return b.finish(t)
+
+
 CONFIGS = {0: single_chain, 1: mobilenet_v1, 2: resnet18, 3: vgg16, 4: squeezenet11}
 
 
