@@ -309,11 +309,18 @@ def test_reduction_split_across_workgroups(kind, compute):
     assert np.array_equal(y, y2)                       # fixed summation order: run-to-run identical
 
 
-def test_graph_replay_matches_eager_every_time():
-    # replayed several times with eager work and synchronisations in between; every replay must equal the eager result
+@pytest.mark.parametrize("net", ["mobilenet", "squeezenet", "resnet"])
+def test_graph_replay_matches_eager_every_time(net):
+    # replayed several times with eager work and synchronisations in between; every replay must equal the eager result.
+    # The graph carries the plan's dependences (squeezenet / resnet: parallel branches on a second capture stream).
     import torch
     X = _xenos()
-    g = wg.mobilenet_v1(batch=2, hw=64, width=0.25, classes=24, seed=31)
+    if net == "mobilenet":
+        g = wg.mobilenet_v1(batch=2, hw=64, width=0.25, classes=24, seed=31)
+    elif net == "squeezenet":
+        g = wg.squeezenet11(batch=2, hw=95, classes=24, seed=31)
+    else:
+        g = wg.resnet18(batch=2, hw=64, width=0.5, classes=24, seed=31)
     s = X.Session(g, link=2, compute=1)
     try:
         ref = s.forward(g.x).copy()
