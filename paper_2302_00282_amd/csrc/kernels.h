@@ -71,8 +71,8 @@ struct ConvArgs {
   const void* dw_w; const float* dw_scale; const float* dw_shift;   // [k*k][C] compute type, folded scale / shift [C]
   int dw_k, dw_stride, dw_pad, dw_H, dw_W, dw_relu;
   long long dw_sN, dw_sP;
-  // reduction split across workgroups (ksplit > 1, M_FLAT only): share z covers steps [z*steps_per_split, ...) and
-  // writes raw fp32 sums to part[z][m][k] (row pitch part_ld); a splitk_finish pass completes the chain
+  // reduction split across workgroups (ksplit >= 1, M_FLAT only; 0 = none): share z covers steps [z*steps_per_split, ...)
+  // and writes raw fp32 sums to part[z][m][k] (row pitch part_ld); a splitk_finish pass completes the chain
   int ksplit, steps_per_split, part_ld;
   float* part;
   int th, tw, tiles_y, tiles_x;   // halo kernel: spatial tile and tile grid over the stacked padded rows n*(H+2)+oh
@@ -128,6 +128,7 @@ struct SplitKArgs {
   const void* res; long long res_sN, res_sP;
   void* out; long long out_sN, out_sP, out_sK;
   int relu, out_f32;
+  int gap;                           // 1: average the finished pixels of every image (linked global average), out = [image][K]
 };
 
 // Launchers (defined in xenos_kernels.hip).  dtype = DT_*.  Return a hipError_t value as int.

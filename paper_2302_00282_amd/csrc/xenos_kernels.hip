@@ -111,7 +111,8 @@ __global__ __launch_bounds__(NT, 2) void conv_kernel(const ConvArgs a) {
 
   const int nsteps_all = a.Kred_pad / BKE;
   const int OHW = a.OH * a.OW;
-  const int ksplit = a.ksplit > 1 ? a.ksplit : 1;                  // reduction split across workgroups (C/R/S split)
+  const int ksplit = a.ksplit >= 1 ? a.ksplit : 1;                 // reduction split across workgroups (C/R/S split)
+  const bool partial = a.ksplit >= 1;                              // raw fp32 sums go to `part` (even with a single share)
   // Workgroups are dealt round-robin to the 8 XCDs.  The XCDs form an xm x (8/xm) grid over (pixel tiles) x
   // (channel tiles x reduction shares); each owns a contiguous, balanced block of that space and walks its pixel
   // tiles once per channel tile, so at any time the workgroups of one XCD share one weight slice in their L2 and
@@ -132,8 +133,8 @@ __global__ __launch_bounds__(NT, 2) void conv_kernel(const ConvArgs a) {
     const int tile_m = m0 + lm;
     const int tile_n = (z0 + lz) / ksplit, zsplit = (z0 + lz) % ksplit;
     // this workgroup's share of the reduction steps: [s_begin, s_begin + nsteps)
-    const int s_begin = ksplit > 1 ? zsplit * a.steps_per_split : 0;
-    const int nsteps = ksplit > 1 ? (nsteps_all - s_begin < a.steps_per_split ? nsteps_all - s_begin : a.steps_per_split) : nsteps_all;
+    const int s_begin = partial ? zsplit * a.steps_per_split : 0;
+    const int nsteps = partial ? (nsteps_all - s_begin < a.steps_per_split ? nsteps_all - s_begin : a.steps_per_split) : nsteps_all;
 
     // patch / gap geometry of this tile
     int img = 0, oy0 = 0, ox0 = 0, py = 0, px = 0;
@@ -408,7 +409,7 @@ __global__ __launch_bounds__(NT, 2) void conv_kernel(const ConvArgs a) {
 
       // Phase 2: each thread finishes CE consecutive channels of one output element: scale/shift, shortcut,
       // ReLU, pooling over the rows of its window, then one 16-byte store into the consumer's buffer.
-      if (MODE == M_FLAT && ksplit > 1) {
+      if (MODE == M_FLAT && partial) {
         // reduction split: raw fp32 partial sums go to part[zsplit][m][k]; splitk_finish adds the shares in a fixed
         // order and runs the rest of the chain
         const int cg = tid % CG, col0 = cg * CE;
@@ -1024,7 +1025,7 @@ static int launch_conv3x3_t(const ConvArgs& a, hipStream_t st) {
   // the host checks the preconditions again: a wrong shape here would index outside the patch buffers
   if (a.R != 3 || a.S != 3 || a.stride != 1 || a.pad != 1 || !a.kchunk || a.C % Tr<T>::BKE != 0 || a.C < Tr<T>::BKE || a.th < 1 || a.tw < 1 ||
       a.th * a.tw > V2_BM || a.tiles_m != a.tiles_y * a.tiles_x || (a.halo_bn != 64 && a.halo_bn != 128) ||
-      a.tiles_n != (a.K + a.halo_bn - 1) / a.halo_bn || a.ksplit > 1 || a.dw_w || !a.vec_out || (a.has_res && !a.vec_res) ||
+      a.tiles_n != (a.K + a.halo_bn - 1) / a.halo_bn || a.ksplit >= 1 || a.dw_w || !a.vec_out || (a.has_res && !a.vec_res) ||
       (a.mode == M_ZIGZAG && (((a.th | a.tw | a.H | a.W) & 1) || a.has_res)))
     return (int)hipErrorInvalidValue;
   if (a.mode == M_FLAT) return a.halo_bn == 128 ? launch_conv3x3_inst<T, M_FLAT, 128>(a, st) : launch_conv3x3_inst<T, M_FLAT, 64>(a, st);
@@ -1208,7 +1209,7 @@ template <typename T>
 static int launch_stem_t(const ConvArgs& a, hipStream_t st) {
   // what the kernel assumes: one 32-deep pass, K = 32 or 64, pixel-major rows, plain chain, aligned NHWC output
   const int esz = (int)sizeof(T);
-  if (a.Kred > kStemRed || a.Kred_pad < (a.Kred + 31) / 32 * 32 || !a.ktab || a.mode != M_FLAT || a.has_res || a.pool != POOL_NONE || a.dw_w || a.ksplit > 1 ||
+  if (a.Kred > kStemRed || a.Kred_pad < (a.Kred + 31) / 32 * 32 || !a.ktab || a.mode != M_FLAT || a.has_res || a.pool != POOL_NONE || a.dw_w || a.ksplit >= 1 ||
       a.out_sK != 1 || (a.out_f32 && esz != 4) || (a.out_sP * esz) % 16 != 0 || (a.out_sN * esz) % 16 != 0 ||
       ((uintptr_t)a.out & 15) || ((uintptr_t)a.w & 15) || (a.Kred_pad * esz) % 16 != 0 || a.H > 8192 ||
       a.tiles_m != (a.M_total + 31) / 32 || a.M_total != a.N * a.OH * a.OW)
@@ -1289,7 +1290,7 @@ int launch_conv(const ConvArgs& a, int dtype, int cfg, int scalar_loader, void* 
   hipStream_t st = (hipStream_t)stream;
   if (a.grid < 1 || a.tiles_m < 1 || a.tiles_n < 1) return (int)hipErrorInvalidValue;
   if (cfg < kHaloCfg && a.xcd_m != 1 && a.xcd_m != 2 && a.xcd_m != 4 && a.xcd_m != 8) return (int)hipErrorInvalidValue;
-  if (a.ksplit > 1 && (a.mode != M_FLAT || !a.part || a.steps_per_split < 1 || a.dw_w || cfg == kHaloCfg)) return (int)hipErrorInvalidValue;
+  if (a.ksplit >= 1 && (a.mode != M_FLAT || !a.part || a.steps_per_split < 1 || a.dw_w || cfg == kHaloCfg)) return (int)hipErrorInvalidValue;
   if (a.dw_w) {
     if (scalar_loader) return (int)hipErrorInvalidValue;
     return dtype == DT_BF16 ? launch_conv_dwpro_t<bf16_t>(a, cfg, st) : launch_conv_dwpro_t<float>(a, cfg, st);
@@ -1377,6 +1378,42 @@ int launch_dw(const DwArgs& a, int dtype, void* stream) {
 template <typename T>
 __global__ __launch_bounds__(NT) void splitk_finish_kernel(const SplitKArgs a) {
   using tr = Tr<T>;
+  if (a.gap) {
+    // linked global average (CBRA): a workgroup owns 16 channels of one image; 16 thread groups finish the pixels
+    // p = g, g + 16, ... and the 16 partial sums are added in group order
+    constexpr int CH = 16, PG = NT / CH;
+    __shared__ float s_sum[NT];
+    const int kt = (a.K + CH - 1) / CH;
+    const int kk = threadIdx.x % CH, pg = threadIdx.x / CH;
+    for (int blk = blockIdx.x; blk < (a.M / a.OHW) * kt; blk += gridDim.x) {
+      const long long n = blk / kt;
+      const int k = (blk % kt) * CH + kk;
+      float s = 0.f;
+      if (k < a.K) {
+        const float sc = a.scale[k], sh = a.shift[k];
+        for (int p = pg; p < a.OHW; p += PG) {
+          const long long m = n * a.OHW + p;
+          float v = 0.f;
+          for (int z = 0; z < a.ksplit; ++z) v += a.part[((long long)z * a.M + m) * a.part_ld + k];
+          v = v * sc + sh;
+          if (a.res) v += tr::ld(a.res, n * a.res_sN + p * a.res_sP + k);
+          if (a.relu) v = fmaxf(v, 0.f);
+          s += v;
+        }
+      }
+      s_sum[threadIdx.x] = s;
+      __syncthreads();
+      if (pg == 0 && k < a.K) {
+        float t = 0.f;
+        for (int w = 0; w < PG; ++w) t += s_sum[w * CH + kk];
+        t /= (float)a.OHW;
+        const long long o = n * a.out_sN + (long long)k * a.out_sK;
+        if (a.out_f32) ((float*)a.out)[o] = t; else tr::st(a.out, o, t);
+      }
+      __syncthreads();
+    }
+    return;
+  }
   const long long total = (long long)a.M * a.K;
   for (long long idx = (long long)blockIdx.x * NT + threadIdx.x; idx < total; idx += (long long)gridDim.x * NT) {
     const int k = (int)(idx % a.K);
@@ -1394,7 +1431,8 @@ __global__ __launch_bounds__(NT) void splitk_finish_kernel(const SplitKArgs a) {
 
 int launch_splitk_finish(const SplitKArgs& a, int dtype, void* stream) {
   hipStream_t st = (hipStream_t)stream;
-  const int grid = grid_for((long long)a.M * a.K, NT);
+  if (a.ksplit < 1 || a.OHW < 1 || a.M % a.OHW != 0) return (int)hipErrorInvalidValue;
+  const int grid = a.gap ? grid_for((long long)(a.M / a.OHW) * ((a.K + 15) / 16), 1) : grid_for((long long)a.M * a.K, NT);
   if (dtype == DT_BF16) hipLaunchKernelGGL(splitk_finish_kernel<bf16_t>, dim3(grid), dim3(NT), 0, st, a);
   else hipLaunchKernelGGL(splitk_finish_kernel<float>, dim3(grid), dim3(NT), 0, st, a);
   return (int)hipGetLastError();

@@ -100,6 +100,7 @@ struct Step {
   CvtArgs cvt{};
   SplitKArgs splitk{};
   int cfg = 0, scalar = 0, stem = 0;
+  int gap_finish = 0;          // global average linked through the summing pass of a reduction split (few images)
   int v_in = -1, v_in2 = -1, v_out = -1;
   long long w_off = -1, scale_off = -1, shift_off = -1, ktab_off = -1;   // byte offsets into the weight image
   long long dw_w_off = -1, dw_scale_off = -1, dw_shift_off = -1;        // linked depthwise producer, if any
@@ -401,7 +402,7 @@ struct Planner {
     // halo-staged 3x3 kernel: a TH x TW block of output pixels (256 GEMM rows) x 128 channels per workgroup,
     // tiles laid over the images stacked with their padding rows
     // (the halo kernel stores 16-byte channel groups only: outputs and shortcuts that cannot take them use conv_kernel)
-    const bool halo_ok = c.vec_out && (!c.has_res || c.vec_res) && !c.dw_w && c.R == 3 && c.S == 3 && c.stride == 1 && c.pad == 1 && !st.scalar && c.kchunk &&
+    const bool halo_ok = !st.gap_finish && c.vec_out && (!c.has_res || c.vec_res) && !c.dw_w && c.R == 3 && c.S == 3 && c.stride == 1 && c.pad == 1 && !st.scalar && c.kchunk &&
                          (c.mode == M_FLAT || (c.mode == M_ZIGZAG && c.H % 2 == 0 && c.W % 2 == 0)) &&
                          (long long)c.N * c.in_sN < (1ll << 31) && conv_lds_bytes(kHaloCfg, c.mode) <= p.hw.lds_bytes_per_cu;
     // a forced configuration binds the chains it applies to; the others get the planner's choice
@@ -827,6 +828,14 @@ struct Planner {
             a.mode = (a.pk == 2 && a.ps == 2 && a.pp == 0 && 2 * a.PH <= a.OH && 2 * a.PW <= a.OW) ? M_ZIGZAG : M_PATCH;
           }
         }
+        // With few images the one-workgroup-per-(image, channel tile) form of the linked global average leaves the chip
+        // idle and walks the whole reduction serially; the chain then runs as a pixel-major convolution whose reduction
+        // is split across workgroups, and the summing pass applies the epilogue and averages (same single chain of
+        // operators, two launches).
+        if (a.mode == M_GAP && p.opts.split && !from_dw && 2 * a.N * ((K + 63) / 64) <= std::max(1, p.hw.num_cu) && p.opts.tile == 0) {
+          st.gap_finish = 1;
+          a.mode = M_FLAT; a.pool = POOL_NONE;
+        }
         a.M_total = a.mode == M_FLAT ? a.N * a.OH * a.OW : a.mode == M_ZIGZAG ? a.N * a.PH * a.PW * 4 : a.OH * a.OW;
         pack_dense(st, go, is_fc ? is.c : is.c, a.C, a.R, a.S, K);
         push_affine(af, (K + 127) / 128 * 128, &st.scale_off, &st.shift_off);
@@ -865,9 +874,10 @@ struct Planner {
         // partition leaves most compute units idle and the reduction is long, split it across workgroups too.
         // Shares are summed in index order by a second pass, so the result does not depend on timing.
         const int nsteps = a.Kred_pad / (kRowBytes / p.esz);
-        if (p.opts.split && st.cfg < kHaloCfg && a.mode == M_FLAT && !from_dw && a.ntiles * 2 <= p.hw.num_cu && nsteps >= 32) {
+        if (p.opts.split && st.cfg < kHaloCfg && a.mode == M_FLAT && !from_dw && (st.gap_finish || (a.ntiles * 2 <= p.hw.num_cu && nsteps >= 32))) {
           int ks = std::min({(2 * p.hw.num_cu + a.ntiles - 1) / a.ntiles, nsteps / 8, 32});
-          if (ks >= 4) {
+          if (st.gap_finish) ks = std::max(ks, 1);
+          if (ks >= 4 || st.gap_finish) {
             const int spk = (nsteps + ks - 1) / ks;
             ks = (nsteps + spk - 1) / spk;
             const TileCfg& tc = kTileCfgs[st.cfg];
@@ -887,6 +897,7 @@ struct Planner {
             f.ksplit = ks; f.part_ld = a.part_ld; f.M = a.M_total; f.K = K; f.OHW = a.OH * a.OW;
             f.res_sN = a.res_sN; f.res_sP = a.res_sP;
             f.out_sN = a.out_sN; f.out_sP = a.out_sP; f.out_sK = a.out_sK; f.relu = a.relu; f.out_f32 = a.out_f32;
+            f.gap = st.gap_finish;
             fin.bytes_in = pbytes; fin.bytes_res = st.bytes_res; fin.bytes_out = st.bytes_out;
             st.v_out = v_part; st.v_in2 = -1; a.has_res = 0;
             st.bytes_out = pbytes; st.bytes_res = 0;
@@ -1101,7 +1112,7 @@ xenos_status launch_step(xenos_plan& p, const Step& s, const void* d_in, void* d
       a.scale = (const float*)(wb + s.scale_off);
       a.shift = (const float*)(wb + s.shift_off);
       a.ktab = s.ktab_off >= 0 ? (const int32_t*)(wb + s.ktab_off) : nullptr;
-      a.part = a.ksplit > 1 ? (float*)a.out : nullptr;
+      a.part = a.ksplit >= 1 ? (float*)a.out : nullptr;
       a.dw_w = s.dw_w_off >= 0 ? (const void*)(wb + s.dw_w_off) : nullptr;
       a.dw_scale = s.dw_scale_off >= 0 ? (const float*)(wb + s.dw_scale_off) : nullptr;
       a.dw_shift = s.dw_shift_off >= 0 ? (const float*)(wb + s.dw_shift_off) : nullptr;

@@ -121,11 +121,16 @@ def test_linking_patterns_of_the_workloads():
     # the 7x7/2 first layer reads the caller's NCHW tensor in place; its 3x3/2 max-pool is the only stand-alone pass
     assert convs[0]["loader"] == "stem" and res["chains"][1]["kind"] == "pool"
     assert all(c["kind"] in ("conv", "splitk_finish") for c in res["chains"][2:])
-    assert convs[-2]["mode"] == "gap"                          # last block + global average (CBRA)
+    # last block + global average (CBRA): at batch 1 through the summing pass of a reduction split, at batch 32 in the
+    # convolution's own epilogue; either way the average is an operator of that chain, not a pass of its own
+    assert any(g2.ops[o].kind == "gap" for o in convs[-2]["ops"]) and convs[-2]["mode"] == "flat"
+    assert res["chains"][convs[-2]["i"] + 1]["kind"] == "splitk_finish"
+    res32 = plan_json(wg.build(2, 32, draw=False), link=2, compute=X.XENOS_BF16)["plan"]
+    assert [c for c in res32["chains"] if c["kind"] == "conv"][-2]["mode"] == "gap"
     sq = plan_json(wg.build(4, 1, draw=False), link=2, compute=X.XENOS_BF16)["plan"]
     assert sq["chains"][0]["loader"] == "stem" and sq["chains"][1]["kind"] == "pool"
-    assert all(c["kind"] == "conv" for c in sq["chains"][2:])            # concat and the later pools cost no pass
-    assert sum(c["mode"] == "patch" for c in sq["chains"][2:]) == 4      # 3x3/2 ceil-mode pools linked into both expand convs, twice
+    assert all(c["kind"] in ("conv", "splitk_finish") for c in sq["chains"][2:])   # concat and the later pools cost no pass
+    assert sum(c.get("mode") == "patch" for c in sq["chains"][2:]) == 4      # 3x3/2 ceil-mode pools linked into both expand convs, twice
     offs = sorted({(c["out_c_off"], c["out_sP"]) for c in sq["chains"] if c["kind"] == "conv" and c["out_c_off"]})
     assert (64, 128) in offs and (256, 512) in offs            # expand3x3 halves land at their channel offset
     vgg = plan_json(wg.build(3, 2, draw=False), link=2, compute=X.XENOS_BF16)["plan"]

@@ -133,9 +133,14 @@ def test_split_equals_unsplit_bitwise(kind, compute):
     # outC / H / W splits involve no cross-tile reduction (Section 4.2.1), so one workgroup walking all
     # tiles must reproduce the split run bit for bit
     g = chain_graph(kind, n=1, hw=9)
-    y1, _ = run_gpu(g, compute=compute, split=1)
+    y1, i1 = run_gpu(g, compute=compute, split=1)
     y0, _ = run_gpu(g, compute=compute, split=0)
-    assert np.array_equal(y1, y0)
+    if any(c["kind"] == "splitk_finish" for c in i1["chains"]):
+        # with few images the split plan averages in the summing pass of a reduction split: another (fixed) summation
+        # order, so equal only to rounding
+        assert np.abs(y1 - y0).max() <= (4e-6 if compute == 0 else 1e-2) * np.abs(y0).max()
+    else:
+        assert np.array_equal(y1, y0)
 
 
 @pytest.mark.parametrize("tile", [1, 2, 3, 4])
@@ -281,7 +286,8 @@ def test_depthwise_pointwise_linked_on_chip(stride, hw, c, k, tail, compute):
     ref = xo.forward(g)
     y3, i3 = check(g, ref, compute=compute, link=3)
     y2, i2 = check(g, ref, compute=compute, link=2)
-    assert i3["n_chains"] == i2["n_chains"] - 1 and any(ch.get("dw_linked") for ch in i3["chains"])
+    assert i3["n_chains"] < i2["n_chains"] and any(ch.get("dw_linked") for ch in i3["chains"])
+    assert not any(ch["kind"] == "dwconv" for ch in i3["chains"])
     y3s, _ = run_gpu(g, compute=compute, link=3, split=0)
     assert np.array_equal(y3, y3s)
 
