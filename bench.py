@@ -72,6 +72,9 @@ def time_chains(sess, torch, steps):
     return tot / steps
 
 
+TUNE = True     # profiling-driven partition choice (xenos_plan_tune) before timing; --no-tune keeps the cost model's choice
+
+
 def run_workload(name, steps, warmup, links=(2,), chains=False, wg=None, X=None, torch=None, graph=None):
     cfg, batch, compute = WORKLOADS[name]
     g = graph if graph is not None else wg.build(cfg, batch)
@@ -80,6 +83,7 @@ def run_workload(name, steps, warmup, links=(2,), chains=False, wg=None, X=None,
     for link in links:
         s = X.Session(g, link=link, split=1, compute=compute)
         s.set_input(g.x)
+        retuned = s.tune(reps=5) if TUNE else 0
         # both ways of enqueueing a pass are product entry points (xenos_run_graph / xenos_run); the step time is the
         # better of the two, and the line says which
         ms_graph, wall_g = time_steps(s, torch, steps, warmup, graph=True)
@@ -87,7 +91,7 @@ def run_workload(name, steps, warmup, links=(2,), chains=False, wg=None, X=None,
         ms, wall = (ms_graph, wall_g) if ms_graph <= ms_eager else (ms_eager, wall_e)
         rec = {"ms_per_step": ms, "wall_ms_per_step": wall, "ms_per_step_eager_launches": ms_eager,
                "ms_per_step_graph_replay": ms_graph, "launch": "graph_replay" if ms_graph <= ms_eager else "eager",
-               "images_per_s": batch / ms * 1e3,
+               "images_per_s": batch / ms * 1e3, "tuned": bool(TUNE), "chains_retuned": retuned,
                "tflops": out["gflop"] / ms, "n_chains": s.info["n_chains"],
                "algorithmic_hbm_mb": s.info["hbm_bytes"] / 1e6,
                "algorithmic_gb_per_s": s.info["hbm_bytes"] / ms / 1e6}
@@ -159,9 +163,12 @@ def main():
     ap.add_argument("--quick", action="store_true", help="headline workload, linked mode only, no CPU baseline")
     ap.add_argument("--cpu-images", type=int, default=16)
     ap.add_argument("--detail", default="", help="write the full per-chain report (JSON) to this file")
+    ap.add_argument("--no-tune", action="store_true", help="skip xenos_plan_tune: time the cost model's partition choice")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run a plain device copy of 256 MiB three times and exit (reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
+    global TUNE
+    TUNE = not args.no_tune
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no collectives, no sharding); --gpus must be 1", file=sys.stderr)
         sys.exit(2)
@@ -219,7 +226,8 @@ def main():
         "dtype": head["dtype"], "data": "synthetic",
         "config": {"workload": f"config {cfg}: {g.name}-style, batch {batch}, {head['dtype']}, linked+split, "
                                f"synthetic seeded weights and input", "batch": batch, "mode": "linked+split",
-                   "gflop_per_step": head["gflop"], "launch": lk["launch"]},
+                   "gflop_per_step": head["gflop"], "launch": lk["launch"],
+                   "partition": "profiled per chain (xenos_plan_tune)" if TUNE else "cost model"},
         "tflops": lk["tflops"],
         "roofline": roof,
         "linked_vs_unlinked": {k: {"images_per_s": head[k]["images_per_s"], "ms_per_step": head[k]["ms_per_step"],

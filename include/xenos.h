@@ -150,6 +150,17 @@ xenos_status xenos_run(xenos_plan* plan, const void* d_input, void* d_output, vo
  * valid and the plan bound to the same buffers for as long as the pair is reused.  Asynchronous on hip_stream. */
 xenos_status xenos_run_graph(xenos_plan* plan, const void* d_input, void* d_output, void* hip_stream);
 
+/* Profiling-driven choice of the partition (the single-device form of Algorithm 1, Section 5: enumerate the legal
+ * partition schemes of an operator, profile each, keep the fastest; a one-off search per model and platform).
+ * For every convolution chain of a bound plan whose split planner found more than one legal tile shape / kernel,
+ * each candidate is launched `reps` times on hip_stream on the chain's real input (one full pass runs first) and
+ * the fastest replaces the cost model's choice.  Chains whose plan structure depends on the choice (reduction
+ * split, first-layer kernel, linked depthwise producer) keep it.  d_output is overwritten; the JSON of
+ * xenos_plan_query reflects the result ("tuned":1); *n_changed (may be NULL) = chains whose choice changed.
+ * Synchronises hip_stream.  Allocates no device memory. */
+xenos_status xenos_plan_tune(xenos_plan* plan, const void* d_input, void* d_output, void* hip_stream,
+                             int reps, int* n_changed);
+
 /* Runs only chain `chain` of a bound plan (0 <= chain < number of chains in the JSON), reading and
  * writing the same buffers xenos_run would; used for per-chain timing. */
 xenos_status xenos_run_chain(xenos_plan* plan, int chain, const void* d_input, void* d_output,

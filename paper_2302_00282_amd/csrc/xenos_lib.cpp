@@ -101,6 +101,11 @@ struct Step {
   SplitKArgs splitk{};
   int cfg = 0, scalar = 0, stem = 0;
   int gap_finish = 0;          // global average linked through the summing pass of a reduction split (few images)
+  // every partition the split planner found legal for this chain (tile shape x kernel), for profiling-driven choice;
+  // empty when the choice is forced or tied to the structure of the plan (reduction split, stem, linked depthwise)
+  struct Cand { int cfg; ConvArgs a; size_t lds; };
+  std::vector<Cand> cands;
+  int tuned = 0;               // chosen by measurement (xenos_plan_tune)
   int v_in = -1, v_in2 = -1, v_out = -1;
   long long w_off = -1, scale_off = -1, shift_off = -1, ktab_off = -1;   // byte offsets into the weight image
   long long dw_w_off = -1, dw_scale_off = -1, dw_shift_off = -1;        // linked depthwise producer, if any
@@ -153,6 +158,8 @@ uint16_t f2bf_host(float f) {
   u += 0x7fffu + ((u >> 16) & 1u);
   return (uint16_t)(u >> 16);
 }
+
+void write_plan_json(xenos_plan& p);
 
 // ---------------------------------------------------------------------------------------------
 // Planner
@@ -439,6 +446,7 @@ struct Planner {
       // two workgroups fit on a compute unit; below that, a smaller tile only shortens the critical path
       const double cost = std::max((double)t.ntiles / (2.0 * num_cu), 1.0) * per_tile;
       if (cost < best_cost) { best_cost = cost; best = cfg; best_args = t; }
+      if (p.opts.tile == 0) { set_grid(t, cfg); st.cands.push_back(Step::Cand{cfg, t, conv_lds_bytes(cfg, c.mode)}); }
     }
     if (halo_ok && (force_tile == 0 || force_tile == kHaloCfg + 1)) {
       const int step = c.mode == M_ZIGZAG ? 2 : 1;
@@ -474,6 +482,7 @@ struct Planner {
           const double per_tile = (double)kHaloRows * bns[v] / rate[v];
           const double cost = (double)((u.ntiles + num_cu - 1) / num_cu) * per_tile;
           if (cost < best_cost) { best_cost = cost; best = kHaloCfg; best_args = u; }
+          if (p.opts.tile == 0) { set_grid(u, kHaloCfg); st.cands.push_back(Step::Cand{kHaloCfg, u, conv_lds_bytes(kHaloCfg, c.mode)}); }
         }
       }
     }
@@ -881,6 +890,7 @@ struct Planner {
             const int spk = (nsteps + ks - 1) / ks;
             ks = (nsteps + spk - 1) / spk;
             const TileCfg& tc = kTileCfgs[st.cfg];
+            st.cands.clear();                                      // the plan's structure now depends on this tile shape
             a.ksplit = ks; a.steps_per_split = spk; a.part_ld = a.tiles_n * tc.bn;
             set_grid(a, st.cfg);
             View pv;
@@ -1050,42 +1060,45 @@ struct Planner {
     p.workspace_bytes = std::max<size_t>(top, 256);
   }
 
-  void write_json() {
-    std::string& j = p.json;
-    char buf[1024];
-    double tf = 0; long long tb = 0;
-    for (const Step& s : p.steps) { tf += s.flops; tb += s.bytes_in + s.bytes_w + s.bytes_out + s.bytes_res; }
-    snprintf(buf, sizeof buf, "{\"link\":%d,\"split\":%d,\"compute\":\"%s\",\"num_cu\":%d,\"n_chains\":%d,\"flops\":%.0f,\"hbm_bytes\":%lld,"
-             "\"weight_bytes\":%zu,\"workspace_bytes\":%zu,\"chains\":[",
-             p.opts.link, p.opts.split, p.dt == DT_BF16 ? "bf16" : "f32", p.hw.num_cu, (int)p.steps.size(), tf, tb,
-             p.wimage.size(), p.workspace_bytes);
-    j = buf;
-    for (size_t i = 0; i < p.steps.size(); ++i) {
-      const Step& s = p.steps[i];
-      std::string ops;
-      for (size_t k = 0; k < s.ops.size(); ++k) ops += (k ? "," : "") + std::to_string(s.ops[k]);
-      snprintf(buf, sizeof buf, "%s{\"i\":%d,\"name\":\"%s\",\"kind\":\"%s\",\"ops\":[%s],\"flops\":%.0f,\"bytes_in\":%lld,\"bytes_w\":%lld,"
-               "\"bytes_out\":%lld,\"bytes_res\":%lld",
-               i ? "," : "", (int)i, s.name.c_str(), kStepNames[s.kind], ops.c_str(), s.flops, s.bytes_in, s.bytes_w, s.bytes_out, s.bytes_res);
-      j += buf;
-      if (s.kind == S_CONV) {
-        const ConvArgs& c = s.conv;
-        const TileCfg halo_tc{kHaloRows, c.halo_bn, 64, c.halo_bn / 2};
-        const TileCfg stem_tc{32, c.K, 32, c.K};
-        const TileCfg& tc = s.cfg == kHaloCfg ? halo_tc : s.cfg == kStemCfg ? stem_tc : kTileCfgs[s.cfg];
-        snprintf(buf, sizeof buf, ",\"mode\":\"%s\",\"loader\":\"%s\",\"N\":%d,\"C\":%d,\"H\":%d,\"W\":%d,\"K\":%d,\"R\":%d,\"S\":%d,\"stride\":%d,"
-                 "\"pad\":%d,\"OH\":%d,\"OW\":%d,\"PH\":%d,\"PW\":%d,\"pool\":%d,\"relu\":%d,\"res\":%d,\"bm\":%d,\"bn\":%d,\"tiles_m\":%d,"
-                 "\"tiles_n\":%d,\"grid\":%d,\"lds\":%zu,\"pph\":%d,\"ppw\":%d,\"patch_h\":%d,\"patch_w\":%d,\"out_c_off\":%lld,\"out_sP\":%lld,\"halo\":%d,\"th\":%d,\"tw\":%d,\"dw_linked\":%d,\"ksplit\":%d",
-                 kModeNames[c.mode], s.stem ? "stem" : s.scalar ? "scalar" : "vector", c.N, c.C, c.H, c.W, c.K, c.R, c.S, c.stride, c.pad, c.OH, c.OW,
-                 c.PH, c.PW, c.pool, c.relu, c.has_res, tc.bm, tc.bn, c.tiles_m, c.tiles_n, c.grid, s.lds, c.pph, c.ppw, c.patch_h,
-                 c.patch_w, p.views[s.v_out].off, c.out_sP, s.cfg == kHaloCfg ? 1 : 0, c.th, c.tw, s.dw_w_off >= 0 ? 1 : 0, c.ksplit > 1 ? c.ksplit : 1);
-        j += buf;
-      }
-      j += "}";
-    }
-    j += "]}";
-  }
+  void write_json() { write_plan_json(p); }
 };
+
+// The plan's metadata as JSON (Section 4.1 "metadata"): chains, tiles, layouts, algorithmic work.
+void write_plan_json(xenos_plan& p) {
+  std::string& j = p.json;
+  char buf[1024];
+  double tf = 0; long long tb = 0;
+  for (const Step& s : p.steps) { tf += s.flops; tb += s.bytes_in + s.bytes_w + s.bytes_out + s.bytes_res; }
+  snprintf(buf, sizeof buf, "{\"link\":%d,\"split\":%d,\"compute\":\"%s\",\"num_cu\":%d,\"n_chains\":%d,\"flops\":%.0f,\"hbm_bytes\":%lld,"
+           "\"weight_bytes\":%zu,\"workspace_bytes\":%zu,\"chains\":[",
+           p.opts.link, p.opts.split, p.dt == DT_BF16 ? "bf16" : "f32", p.hw.num_cu, (int)p.steps.size(), tf, tb,
+           p.wimage.size(), p.workspace_bytes);
+  j = buf;
+  for (size_t i = 0; i < p.steps.size(); ++i) {
+    const Step& s = p.steps[i];
+    std::string ops;
+    for (size_t k = 0; k < s.ops.size(); ++k) ops += (k ? "," : "") + std::to_string(s.ops[k]);
+    snprintf(buf, sizeof buf, "%s{\"i\":%d,\"name\":\"%s\",\"kind\":\"%s\",\"ops\":[%s],\"flops\":%.0f,\"bytes_in\":%lld,\"bytes_w\":%lld,"
+             "\"bytes_out\":%lld,\"bytes_res\":%lld",
+             i ? "," : "", (int)i, s.name.c_str(), kStepNames[s.kind], ops.c_str(), s.flops, s.bytes_in, s.bytes_w, s.bytes_out, s.bytes_res);
+    j += buf;
+    if (s.kind == S_CONV) {
+      const ConvArgs& c = s.conv;
+      const TileCfg halo_tc{kHaloRows, c.halo_bn, 64, c.halo_bn / 2};
+      const TileCfg stem_tc{32, c.K, 32, c.K};
+      const TileCfg& tc = s.cfg == kHaloCfg ? halo_tc : s.cfg == kStemCfg ? stem_tc : kTileCfgs[s.cfg];
+      snprintf(buf, sizeof buf, ",\"mode\":\"%s\",\"loader\":\"%s\",\"N\":%d,\"C\":%d,\"H\":%d,\"W\":%d,\"K\":%d,\"R\":%d,\"S\":%d,\"stride\":%d,"
+               "\"pad\":%d,\"OH\":%d,\"OW\":%d,\"PH\":%d,\"PW\":%d,\"pool\":%d,\"relu\":%d,\"res\":%d,\"bm\":%d,\"bn\":%d,\"tiles_m\":%d,"
+               "\"tiles_n\":%d,\"grid\":%d,\"lds\":%zu,\"pph\":%d,\"ppw\":%d,\"patch_h\":%d,\"patch_w\":%d,\"out_c_off\":%lld,\"out_sP\":%lld,\"halo\":%d,\"th\":%d,\"tw\":%d,\"dw_linked\":%d,\"ksplit\":%d,\"candidates\":%d,\"tuned\":%d",
+               kModeNames[c.mode], s.stem ? "stem" : s.scalar ? "scalar" : "vector", c.N, c.C, c.H, c.W, c.K, c.R, c.S, c.stride, c.pad, c.OH, c.OW,
+               c.PH, c.PW, c.pool, c.relu, c.has_res, tc.bm, tc.bn, c.tiles_m, c.tiles_n, c.grid, s.lds, c.pph, c.ppw, c.patch_h,
+               c.patch_w, p.views[s.v_out].off, c.out_sP, s.cfg == kHaloCfg ? 1 : 0, c.th, c.tw, s.dw_w_off >= 0 ? 1 : 0, c.ksplit > 1 ? c.ksplit : 1, (int)s.cands.size(), s.tuned);
+      j += buf;
+    }
+    j += "}";
+  }
+  j += "]}";
+}
 
 // ---------------------------------------------------------------------------------------------
 // Runtime
@@ -1383,6 +1396,60 @@ xenos_status xenos_run_graph(xenos_plan* plan, const void* d_input, void* d_outp
   hipError_t e = hipGraphLaunch(it->second, (hipStream_t)hip_stream);
   if (e != hipSuccess) return fail(XENOS_EDEVICE, "graph launch failed: %s", hipGetErrorString(e));
   return XENOS_OK;
+}
+
+xenos_status xenos_plan_tune(xenos_plan* plan, const void* d_input, void* d_output, void* hip_stream, int reps, int* n_changed) {
+  if (!plan || plan->magic != MAGIC_PLAN || !d_input || !d_output || reps < 1) return fail(XENOS_EINVAL, "xenos_plan_tune: bad argument");
+  if (!plan->bound) return fail(XENOS_EINVAL, "xenos_plan_tune: plan is not bound (call xenos_plan_bind)");
+  hipStream_t st = (hipStream_t)hip_stream;
+  // one full pass first: every chain then finds its real input in the workspace
+  for (const Step& s : plan->steps) {
+    xenos_status rc = launch_step(*plan, s, d_input, d_output, hip_stream);
+    if (rc != XENOS_OK) return rc;
+  }
+  hipEvent_t e0 = nullptr, e1 = nullptr;
+  if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) {
+    if (e0) (void)hipEventDestroy(e0);
+    return fail(XENOS_EDEVICE, "xenos_plan_tune: event create failed");
+  }
+  int changed = 0;
+  xenos_status rc = XENOS_OK;
+  for (Step& s : plan->steps) {
+    if (s.kind != S_CONV || s.cands.size() < 2) continue;
+    int best = -1;
+    float best_ms = 0.f;
+    for (size_t ci = 0; ci < s.cands.size() && rc == XENOS_OK; ++ci) {
+      Step trial = s;
+      trial.cfg = s.cands[ci].cfg; trial.conv = s.cands[ci].a; trial.lds = s.cands[ci].lds;
+      if (launch_step(*plan, trial, d_input, d_output, hip_stream) != XENOS_OK) continue;   // warm-up; a candidate that cannot launch is skipped
+      if (hipEventRecord(e0, st) != hipSuccess) { rc = fail(XENOS_EDEVICE, "xenos_plan_tune: event record failed"); break; }
+      for (int r = 0; r < reps; ++r) (void)launch_step(*plan, trial, d_input, d_output, hip_stream);
+      float ms = 0.f;
+      if (hipEventRecord(e1, st) != hipSuccess || hipEventSynchronize(e1) != hipSuccess || hipEventElapsedTime(&ms, e0, e1) != hipSuccess) {
+        rc = fail(XENOS_EDEVICE, "xenos_plan_tune: timing failed");
+        break;
+      }
+      if (best < 0 || ms < best_ms) { best = (int)ci; best_ms = ms; }
+    }
+    if (rc != XENOS_OK) break;
+    if (best >= 0) {
+      const Step::Cand& c = s.cands[best];
+      const bool same = c.cfg == s.cfg && c.a.tiles_m == s.conv.tiles_m && c.a.tiles_n == s.conv.tiles_n && c.a.halo_bn == s.conv.halo_bn;
+      if (!same) ++changed;
+      s.cfg = c.cfg; s.conv = c.a; s.lds = c.lds; s.tuned = 1;
+      // the last trial may not have been the winner: leave the winner's output in the workspace for the next chain
+      if (launch_step(*plan, s, d_input, d_output, hip_stream) != XENOS_OK) { rc = fail(XENOS_EDEVICE, "xenos_plan_tune: launch failed"); break; }
+    }
+  }
+  (void)hipStreamSynchronize(st);
+  (void)hipEventDestroy(e0);
+  (void)hipEventDestroy(e1);
+  // graphs captured before the choice are stale
+  for (auto& kv : plan->graphs) (void)hipGraphExecDestroy(kv.second);
+  plan->graphs.clear();
+  write_plan_json(*plan);
+  if (n_changed) *n_changed = changed;
+  return rc;
 }
 
 xenos_status xenos_run_chain(xenos_plan* plan, int chain, const void* d_input, void* d_output, void* hip_stream) {

@@ -83,11 +83,12 @@ def lib():
         L.xenos_run.argtypes = [vp, vp, vp, vp]
         L.xenos_run_graph.argtypes = [vp, vp, vp, vp]
         L.xenos_run_chain.argtypes = [vp, C.c_int, vp, vp, vp]
+        L.xenos_plan_tune.argtypes = [vp, vp, vp, vp, C.c_int, C.POINTER(C.c_int)]
         L.xenos_destroy.argtypes = [vp]
         L.xenos_destroy.restype = None
         L.xenos_last_error.restype = C.c_char_p
         for f in ("xenos_graph_create", "xenos_plan_link_split", "xenos_plan_query", "xenos_plan_bind",
-                  "xenos_run", "xenos_run_graph", "xenos_run_chain"):
+                  "xenos_run", "xenos_run_graph", "xenos_run_chain", "xenos_plan_tune"):
             getattr(L, f).restype = C.c_int
         _lib = L
     return _lib
@@ -145,6 +146,13 @@ def xenos_run(plan: int, d_input: int, d_output: int, stream: int = 0):
 
 def xenos_run_graph(plan: int, d_input: int, d_output: int, stream: int = 0):
     _check(lib().xenos_run_graph(plan, d_input, d_output, stream))
+
+
+def xenos_plan_tune(plan: int, d_input: int, d_output: int, stream: int = 0, reps: int = 5) -> int:
+    """Profiles every legal partition of every tunable chain and keeps the fastest; returns how many choices changed."""
+    n = C.c_int(0)
+    _check(lib().xenos_plan_tune(plan, d_input, d_output, stream, reps, C.byref(n)))
+    return n.value
 
 
 def xenos_run_chain(plan: int, chain: int, d_input: int, d_output: int, stream: int = 0):
@@ -257,6 +265,12 @@ class Session:
         self.run()
         self.torch.cuda.synchronize(self.device)
         return self.y.cpu().numpy()
+
+    def tune(self, reps: int = 5) -> int:
+        """xenos_plan_tune on the session's current input; refreshes `info`."""
+        n = xenos_plan_tune(self.plan, self.x.data_ptr(), self.y.data_ptr(), self.stream(), reps)
+        self.info = xenos_plan_query(self.plan)["plan"]
+        return n
 
     def output(self) -> np.ndarray:
         """Synchronises and returns the output buffer of the last run / run_graph."""

@@ -218,3 +218,27 @@ def test_table4_graphs_follow_the_printed_shapes():
         q = plan_json(g, link=2, compute=X.XENOS_BF16)["plan"]
         assert sum(ch["kind"] == "conv" for ch in q["chains"]) == 1                  # one linked chain each (plus the input conversion)
         assert all(ch["kind"] in ("conv", "cvt", "splitk_finish") for ch in q["chains"])
+
+
+def test_partition_candidates_and_tune_argument_checks():
+    # every convolution chain carries the legal partitions the split planner found (what xenos_plan_tune profiles);
+    # chains whose plan structure depends on the choice carry none
+    q = plan_json(wg.build(3, 32, draw=False), link=2, compute=X.XENOS_BF16)["plan"]
+    convs = [c for c in q["chains"] if c["kind"] == "conv"]
+    assert convs[0]["loader"] == "stem" and convs[0]["candidates"] == 0
+    assert all(c["candidates"] >= 3 for c in convs[1:13])              # general tiles + halo tiles for the 3x3 layers
+    assert all(c["candidates"] == 0 for c in convs if c["ksplit"] > 1)
+    assert all(c["tuned"] == 0 for c in convs)
+    forced = plan_json(wg.build(0, 1), link=2, tile=3)["plan"]
+    assert all(c["candidates"] == 0 for c in forced["chains"] if c["kind"] == "conv")
+    G = X.graph_from_workload(wg.build(0, 1))
+    P = X.xenos_plan_link_split(G)
+    try:
+        with pytest.raises(X.XenosError) as e:
+            X.xenos_plan_tune(P, 256, 256)                             # not bound: rejected before anything is launched
+        assert e.value.status == X.XENOS_EINVAL
+        with pytest.raises(X.XenosError):
+            X.xenos_plan_tune(P, 0, 256)
+    finally:
+        X.xenos_destroy(P)
+        X.xenos_destroy(G)

@@ -416,3 +416,34 @@ def test_table4_micro_benchmark_operators(name, compute):
     y0, _ = check(g, ref, compute=compute, link=2, split=0)    # without the operator split
     if not any(c["kind"] == "splitk_finish" for c in info["chains"]):
         assert np.array_equal(y, y0)
+
+
+@pytest.mark.parametrize("net,compute", [("resnet", 1), ("squeezenet", 0), ("vgg", 1)])
+def test_profiling_driven_partition_choice(net, compute):
+    # xenos_plan_tune: every legal partition of every tunable chain is profiled on the device and the fastest kept
+    # (single-device form of Algorithm 1); the tuned plan must compute the same function
+    if net == "resnet":
+        g = wg.resnet18(batch=4, hw=96, width=1.0, classes=24, seed=51)
+    elif net == "squeezenet":
+        g = wg.squeezenet11(batch=4, hw=95, classes=24, seed=51)
+    else:
+        g = wg.vgg16(batch=4, hw=64, width=1.0, fc_dim=128, classes=24, seed=51)
+    ref = xo.forward(g)
+    X = _xenos()
+    s = X.Session(g, link=2, compute=compute)
+    try:
+        y0 = s.forward(g.x)
+        assert rel_err(y0, ref) <= TOL[compute]
+        s.tune(reps=3)
+        tun = [c for c in s.info["chains"] if c["kind"] == "conv" and c["candidates"] >= 2]
+        assert tun and all(c["tuned"] == 1 for c in tun)
+        assert all(c["tuned"] == 0 for c in s.info["chains"] if c["kind"] == "conv" and c["candidates"] < 2)
+        y1 = s.forward(g.x)
+        e = rel_err(y1, ref)
+        print(f"{g.name} tuned: rel_err={e:.3e}", flush=True)
+        assert e <= TOL[compute]
+        s.y.zero_()
+        s.run_graph()                                   # graphs are re-captured after tuning
+        assert np.array_equal(s.output(), y1)
+    finally:
+        s.close()
