@@ -71,6 +71,7 @@ struct ConvArgs {
   const void* dw_w; const float* dw_scale; const float* dw_shift;   // [k*k][C] compute type, folded scale / shift [C]
   int dw_k, dw_stride, dw_pad, dw_H, dw_W, dw_relu;
   long long dw_sN, dw_sP;
+  int dw_panel;          // > 0: the depthwise result of a whole panel of this many channels is staged in LDS (dwpw_kernel)
   // reduction split across workgroups (ksplit >= 1, M_FLAT only; 0 = none): share z covers steps [z*steps_per_split, ...)
   // and writes raw fp32 sums to part[z][m][k] (row pitch part_ld); a splitk_finish pass completes the chain
   int ksplit, steps_per_split, part_ld;
@@ -141,5 +142,6 @@ int launch_splitk_finish(const SplitKArgs& a, int dtype, void* stream);
 size_t conv_lds_bytes(int cfg, int mode);
 bool conv_cfg_has_scalar_loader(int cfg);
 bool conv_cfg_has_dw_prologue(int cfg, int mode);
+size_t dwpw_lds_bytes(int panel_channels, int esz);   // LDS of the depthwise-panel kernel for a panel of that many channels
 
 }  // namespace xenos

@@ -1247,6 +1247,235 @@ static int launch_conv_mode(const ConvArgs& a, hipStream_t st) {
   return (int)hipErrorInvalidValue;
 }
 
+// ---------------------------------------------------------------------------------------------
+// Depthwise -> pointwise chain with the depthwise result kept on chip (Section 2.2: the depthwise producer hands
+// its output to the pointwise consumer in the consumer's channel-first order; here it never reaches memory).
+// A workgroup owns 64 output pixels x 64 output channels.  Phase A computes the depthwise convolution
+// (+ scale/shift + ReLU) of its 64 pixels for a whole panel of input channels straight into LDS, in the row-major
+// [pixel][channel] form the GEMM reads, with every tap load of several pixels in flight at once, so the memory
+// latency is paid once per panel rather than once per reduction step.  Phase B is the pointwise GEMM over the
+// panel: A fragments come from the panel, weight tiles are double-buffered through registers.  The GEMM is
+// computed transposed (accumulator rows = channels), the epilogue runs in registers and the finished tile goes
+// through LDS once, in the output type, to be stored as 16-byte channel groups.
+// Workgroups that share a pixel tile (different channel tiles) recompute its depthwise panel: 9 MACs per element
+// against 64 per element and channel tile of the pointwise GEMM.
+// ---------------------------------------------------------------------------------------------
+__host__ __device__ constexpr int dwpw_panel_pitch(int cp, int esz) { return cp * esz + 16; }   // odd number of 16-byte slots
+__host__ __device__ constexpr int dwpw_lds(int cp, int esz) { return 64 * dwpw_panel_pitch(cp, esz) + 2 * 64 * LDS_ROW; }
+
+template <typename T>
+__global__ __launch_bounds__(NT) void dwpw_kernel(const ConvArgs a) {
+  using tr = Tr<T>;
+  constexpr int CE = tr::CE, BKE = tr::BKE, ESZ = (int)sizeof(T);
+  constexpr int BM = 64, BN = 64;
+  constexpr int B_IT = BN * CPR / NT;                              // 2 weight chunks per thread and step
+  extern __shared__ __align__(16) unsigned char smem[];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wave_m = wave >> 1, wave_n = wave & 1;                 // 2 x 2 wavefronts of 32 pixels x 32 channels
+  const int l31 = lane & 31, lhalf = lane >> 5;
+
+  const int CP = a.dw_panel;                                       // panel width in channels (multiple of BKE)
+  const int PP = dwpw_panel_pitch(CP, ESZ);
+  unsigned char* s_panel = smem;
+  unsigned char* s_w = smem + BM * PP;
+  const int OHW = a.OH * a.OW;
+  const int Cpad = (a.C + BKE - 1) / BKE * BKE;                    // the packed weights are zero beyond C
+
+  for (int t = blockIdx.x; t < a.ntiles; t += gridDim.x) {
+    const int tile_m = t % a.tiles_m, tile_n = t / a.tiles_m;      // neighbours share a weight tile
+    f32x16_t acc;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) acc[e] = 0.f;
+
+    for (int p0 = 0; p0 < Cpad; p0 += CP) {
+      const int cp = Cpad - p0 < CP ? Cpad - p0 : CP;              // channels of this panel (multiple of BKE)
+      const int cpc = cp / CE;                                     // 16-byte chunks per pixel
+      // ---- phase A: depthwise chain of 64 pixels x cp channels into the panel -------------------------
+      for (int it = tid; it < BM * cpc; it += NT) {
+        const int px = it / cpc, c0 = p0 + (it - px * cpc) * CE;
+        const int m = tile_m * BM + px;
+        const bool valid = m < a.M_total && c0 < a.C;
+        const int mm = m < a.M_total ? m : 0;
+        const int n = mm / OHW, q = mm - n * OHW, oh = q / a.OW, ow = q - oh * a.OW;
+        const int ih0 = oh * a.dw_stride - a.dw_pad, iw0 = ow * a.dw_stride - a.dw_pad;
+        const long long base = (long long)n * a.dw_sN;
+        const int cc = c0 < a.C ? c0 : 0;
+        float d[CE];
+#pragma unroll
+        for (int e = 0; e < CE; ++e) d[e] = 0.f;
+        if (a.dw_k == 3) {
+          // all tap loads of the pixel are issued before any is used (masked taps read a valid dummy address): one
+          // memory latency per pixel, not one per tap.  (Unrolling over several pixels and keeping the tap weights
+          // in registers was measured slower: the register pressure costs more than the extra loads in flight gain.)
+          u32x4_t xr[9], wr[9];
+          unsigned msk = 0;
+#pragma unroll
+          for (int t9 = 0; t9 < 9; ++t9) {
+            const int ih = ih0 + t9 / 3, iw = iw0 + t9 % 3;
+            const bool ok = valid && (unsigned)ih < (unsigned)a.dw_H && (unsigned)iw < (unsigned)a.dw_W;
+            const long long off = ok ? base + ((long long)ih * a.dw_W + iw) * a.dw_sP + cc : cc;
+            xr[t9] = *(const u32x4_t*)((const T*)a.in + off);
+            wr[t9] = *(const u32x4_t*)((const T*)a.dw_w + (long long)t9 * a.C + cc);
+            msk |= (ok ? 1u : 0u) << t9;
+          }
+#pragma unroll
+          for (int t9 = 0; t9 < 9; ++t9) {
+            float x[CE], w[CE];
+            tr::unpack(xr[t9], x);
+            tr::unpack(wr[t9], w);
+            const float keep = ((msk >> t9) & 1u) ? 1.f : 0.f;
+#pragma unroll
+            for (int e = 0; e < CE; ++e) d[e] = fmaf(x[e] * keep, w[e], d[e]);
+          }
+        } else {
+          for (int t9 = 0; t9 < a.dw_k * a.dw_k; ++t9) {
+            const int ih = ih0 + t9 / a.dw_k, iw = iw0 + t9 % a.dw_k;
+            const bool ok = valid && (unsigned)ih < (unsigned)a.dw_H && (unsigned)iw < (unsigned)a.dw_W;
+            const long long off = ok ? base + ((long long)ih * a.dw_W + iw) * a.dw_sP + cc : cc;
+            float x[CE], w[CE];
+            tr::unpack(*(const u32x4_t*)((const T*)a.in + off), x);
+            tr::unpack(*(const u32x4_t*)((const T*)a.dw_w + (long long)t9 * a.C + cc), w);
+            const float keep = ok ? 1.f : 0.f;
+#pragma unroll
+            for (int e = 0; e < CE; ++e) d[e] = fmaf(x[e] * keep, w[e], d[e]);
+          }
+        }
+        float sc[CE], sh[CE];
+#pragma unroll
+        for (int e = 0; e < CE; e += 4) {
+          *(f32x4_t*)&sc[e] = *(const f32x4_t*)(a.dw_scale + cc + e);
+          *(f32x4_t*)&sh[e] = *(const f32x4_t*)(a.dw_shift + cc + e);
+        }
+#pragma unroll
+        for (int e = 0; e < CE; ++e) {
+          float y = d[e] * sc[e] + sh[e];
+          if (a.dw_relu) y = fmaxf(y, 0.f);
+          d[e] = valid ? y : 0.f;                                  // rows past the end and padding channels are exact zeros
+        }
+        *(u32x4_t*)(s_panel + px * PP + (c0 - p0) * ESZ) = tr::pack(d);
+      }
+      // ---- phase B: pointwise GEMM over the panel --------------------------------------------------
+      const int nst = cp / BKE, step0 = p0 / BKE;
+      const unsigned char* wrow[B_IT];
+#pragma unroll
+      for (int it = 0; it < B_IT; ++it) {
+        const int idx = tid + it * NT;
+        wrow[it] = (const unsigned char*)a.w + ((long long)(tile_n * BN + idx / CPR) * a.Kred_pad + (idx % CPR) * CE) * (long long)ESZ +
+                   (long long)step0 * ROWB;
+      }
+      u32x4_t rb0[B_IT], rb1[B_IT];
+      auto load_w = [&](int s, u32x4_t* rb) {
+        const int ss = s < nst ? s : nst - 1;                      // steps past the end re-read valid weights
+#pragma unroll
+        for (int it = 0; it < B_IT; ++it) rb[it] = *(const u32x4_t*)(wrow[it] + (long long)ss * ROWB);
+      };
+      auto store_w = [&](int stage, const u32x4_t* rb) {
+#pragma unroll
+        for (int it = 0; it < B_IT; ++it) {
+          const int idx = tid + it * NT;
+          *(u32x4_t*)(s_w + stage * BN * LDS_ROW + (idx / CPR) * LDS_ROW + (idx % CPR) * 16) = rb[it];
+        }
+      };
+      auto compute = [&](int s, int stage) {
+        const unsigned char* sa = s_panel + (wave_m * 32 + l31) * PP + s * ROWB + lhalf * 16;
+        const unsigned char* sb = s_w + stage * BN * LDS_ROW + (wave_n * 32 + l31) * LDS_ROW + lhalf * 16;
+#pragma unroll
+        for (int kg = 0; kg < KG; ++kg) {
+          const u32x4_t fa = *(const u32x4_t*)(sa + kg * 32), fb = *(const u32x4_t*)(sb + kg * 32);
+          if constexpr (sizeof(T) == 2) {
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, fb), __builtin_bit_cast(bf16x8_t, fa), acc, 0, 0, 0);
+          } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+              acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(fb[e]), __uint_as_float(fa[e]), acc, 0, 0, 0);
+          }
+        }
+      };
+      load_w(0, rb0);
+      store_w(0, rb0);
+      load_w(1, rb1);
+      __syncthreads();                                             // panel and weight step 0 are visible
+      for (int s = 0; s < nst; s += 2) {
+        load_w(s + 2, rb0);
+        compute(s, 0);
+        store_w(1, rb1);
+        __syncthreads();
+        if (s + 1 >= nst) break;
+        load_w(s + 3, rb1);
+        compute(s + 1, 1);
+        store_w(0, rb0);
+        __syncthreads();
+      }
+      __syncthreads();                                             // everyone is done with the panel before it is overwritten
+    }
+
+    // ---- epilogue: lane = pixel wave_m*32 + l31, channels wave_n*32 + 8*g + 4*lhalf + (0..3) ---------------
+    if (a.ksplit >= 1) {
+      // the chain is finished by a summing pass (linked global average): hand it the raw fp32 sums
+      const int m = tile_m * BM + wave_m * 32 + l31;
+      if (m < a.M_total) {
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const int k0 = tile_n * BN + wave_n * 32 + g * 8 + lhalf * 4;
+          *(f32x4_t*)(a.part + (long long)m * a.part_ld + k0) = f32x4_t{acc[4 * g], acc[4 * g + 1], acc[4 * g + 2], acc[4 * g + 3]};
+        }
+      }
+      continue;                                                    // uniform: no barrier is skipped by part of a workgroup
+    }
+    constexpr int SPB = BN * ESZ + 16;
+    unsigned char* stg = s_panel;                                  // 64 rows x SPB bytes, inside the operand buffers
+    const float lo = a.relu ? 0.f : -3.4028235e38f;
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      const int c = wave_n * 32 + g * 8 + lhalf * 4, k0 = tile_n * BN + c;
+      const f32x4_t sc = *(const f32x4_t*)(a.scale + k0), sh = *(const f32x4_t*)(a.shift + k0);
+      float y[4];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) y[e] = fmaxf(acc[4 * g + e] * sc[e] + sh[e], lo);
+      const int srow = wave_m * 32 + l31;
+      if constexpr (sizeof(T) == 2) {
+        uint2 o;
+        o.x = f2bf2(y[0], y[1]);
+        o.y = f2bf2(y[2], y[3]);
+        *(uint2*)(stg + srow * SPB + c * 2) = o;
+      } else {
+        *(f32x4_t*)(stg + srow * SPB + c * 4) = f32x4_t{y[0], y[1], y[2], y[3]};
+      }
+    }
+    __syncthreads();
+    constexpr int CG = BN / CE;
+    for (int idx = tid; idx < BM * CG; idx += NT) {
+      const int r = idx / CG, cg = idx - r * CG;
+      const int m = tile_m * BM + r, k0 = tile_n * BN + cg * CE;
+      if (m >= a.M_total || k0 >= a.K) continue;
+      const int n = m / OHW, q = m - n * OHW;
+      *(u32x4_t*)((T*)a.out + (long long)n * a.out_sN + (long long)q * a.out_sP + k0) = *(const u32x4_t*)(stg + r * SPB + cg * 16);
+    }
+    __syncthreads();
+  }
+}
+
+template <typename T>
+static int launch_dwpw_t(const ConvArgs& a, hipStream_t st) {
+  constexpr int ESZ = (int)sizeof(T), BKE = Tr<T>::BKE, CE = Tr<T>::CE;
+  const int lds = dwpw_lds(a.dw_panel, ESZ);
+  // what the kernel assumes; anything else must take the general prologue path
+  const bool raw = a.ksplit == 1 && a.part && a.part_ld >= a.tiles_n * 64 && a.part_ld % 4 == 0 && ((uintptr_t)a.part & 15) == 0;
+  if (a.mode != M_FLAT || a.has_res || a.pool != POOL_NONE || (!a.vec_out && !raw) || (a.ksplit >= 1 && !raw) || a.kchunk || a.R != 1 || a.S != 1 || a.stride != 1 || a.pad != 0 ||
+      a.C % CE != 0 || a.K % CE != 0 || a.dw_panel < BKE || a.dw_panel % BKE != 0 || lds > 160 * 1024 || a.dw_k < 1 ||
+      a.tiles_m != (a.M_total + 63) / 64 || a.tiles_n != (a.K + 63) / 64 || a.ntiles != a.tiles_m * a.tiles_n || a.grid < 1 ||
+      a.Kred_pad < (a.C + BKE - 1) / BKE * BKE || !a.dw_w || !a.dw_scale || !a.dw_shift)
+    return (int)hipErrorInvalidValue;
+  static int raised = 0;
+  if (lds > raised) {
+    hipError_t e = hipFuncSetAttribute((const void*)dwpw_kernel<T>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    if (e != hipSuccess) return (int)e;
+    raised = lds;
+  }
+  hipLaunchKernelGGL((dwpw_kernel<T>), dim3(a.grid < a.ntiles ? a.grid : a.ntiles), dim3(NT), lds, st, a);
+  return (int)hipGetLastError();
+}
+
 template <typename T, int BM, int BN, int WM, int WN, int MODE>
 static int launch_conv_dwpro_inst(const ConvArgs& a, hipStream_t st) {
   constexpr int lds = lds_conv_bytes<BM, BN>();
@@ -1266,6 +1495,7 @@ template <typename T>
 static int launch_conv_dwpro_t(const ConvArgs& a, int cfg, hipStream_t st) {
   if (a.R != 1 || a.S != 1 || a.stride != 1 || a.pad != 0 || a.kchunk || a.C % Tr<T>::CE != 0 || !a.dw_w || a.dw_k < 1)
     return (int)hipErrorInvalidValue;
+  if (cfg == 2 && a.dw_panel > 0) return launch_dwpw_t<T>(a, st);       // depthwise panel on chip
   if (cfg == 2 && a.mode == M_FLAT) return launch_conv_dwpro_inst<T, 64, 64, 32, 32, M_FLAT>(a, st);
   if (cfg == 2 && a.mode == M_GAP) return launch_conv_dwpro_inst<T, 64, 64, 32, 32, M_GAP>(a, st);
   return (int)hipErrorInvalidValue;
@@ -1290,7 +1520,7 @@ int launch_conv(const ConvArgs& a, int dtype, int cfg, int scalar_loader, void* 
   hipStream_t st = (hipStream_t)stream;
   if (a.grid < 1 || a.tiles_m < 1 || a.tiles_n < 1) return (int)hipErrorInvalidValue;
   if (cfg < kHaloCfg && a.xcd_m != 1 && a.xcd_m != 2 && a.xcd_m != 4 && a.xcd_m != 8) return (int)hipErrorInvalidValue;
-  if (a.ksplit >= 1 && (a.mode != M_FLAT || !a.part || a.steps_per_split < 1 || a.dw_w || cfg == kHaloCfg)) return (int)hipErrorInvalidValue;
+  if (a.ksplit >= 1 && (a.mode != M_FLAT || !a.part || a.steps_per_split < 1 || (a.dw_w && a.dw_panel <= 0) || cfg == kHaloCfg)) return (int)hipErrorInvalidValue;
   if (a.dw_w) {
     if (scalar_loader) return (int)hipErrorInvalidValue;
     return dtype == DT_BF16 ? launch_conv_dwpro_t<bf16_t>(a, cfg, st) : launch_conv_dwpro_t<float>(a, cfg, st);
@@ -1314,6 +1544,7 @@ size_t conv_lds_bytes(int cfg, int /*mode*/) {
 
 bool conv_cfg_has_scalar_loader(int cfg) { return cfg == 2; }
 bool conv_cfg_has_dw_prologue(int cfg, int mode) { return cfg == 2 && (mode == M_FLAT || mode == M_GAP); }
+size_t dwpw_lds_bytes(int panel_channels, int esz) { return (size_t)dwpw_lds(panel_channels, esz); }
 
 // ---------------------------------------------------------------------------------------------
 // Depthwise convolution chain: one thread = one 16-byte channel vector of one output pixel.

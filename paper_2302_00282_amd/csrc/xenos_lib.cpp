@@ -743,7 +743,11 @@ struct Planner {
         const int pw = link >= 3 && !placed.count(cur) ? single_consumer(cur) : -1;
         if (pw >= 0 && d.kh == d.kw && nodes[pw].kind == XENOS_OP_CONV) {
           const xenos_op_desc& pd = desc(nodes[pw]);
-          if (pd.groups == 1 && pd.kh == 1 && pd.kw == 1 && pd.stride_h == 1 && pd.pad_h == 0 && node_step[pw] < 0 && p.opts.tile == 0) {
+          // Every workgroup of the pointwise chain recomputes the depthwise result of its 64 pixels for all input
+          // channels; beyond 32 channel groups per pixel (8 pixels per thread) that serial work costs more than the
+          // saved pass (measured on MobileNet, batch 1: pairs up to 256 channels gain 5-11 us each, wider ones lose 6).
+          if (pd.groups == 1 && pd.kh == 1 && pd.kw == 1 && pd.stride_h == 1 && pd.pad_h == 0 && node_step[pw] < 0 && p.opts.tile == 0 &&
+              is.c / p.ce <= 32) {
             const int taps = d.kh * d.kw;
             const size_t bytes = (size_t)taps * is.c * p.esz;
             dwpro = DwPro{};
@@ -841,7 +845,11 @@ struct Planner {
         // idle and walks the whole reduction serially; the chain then runs as a pixel-major convolution whose reduction
         // is split across workgroups, and the summing pass applies the epilogue and averages (same single chain of
         // operators, two launches).
-        if (a.mode == M_GAP && p.opts.split && !from_dw && 2 * a.N * ((K + 63) / 64) <= std::max(1, p.hw.num_cu) && p.opts.tile == 0) {
+        // (a linked depthwise producer needs the depthwise-panel kernel for this, which takes whole channel groups)
+        const bool dw_panel_fits = from_dw && a.C % p.ce == 0 && K % p.ce == 0 && !has_res &&
+                                   dwpw_lds_bytes(kRowBytes / p.esz, p.esz) <= std::min<size_t>(p.hw.lds_bytes_per_cu, 160 * 1024);
+        if (a.mode == M_GAP && p.opts.split && (!from_dw || dw_panel_fits) && 2 * a.N * ((K + 63) / 64) <= std::max(1, p.hw.num_cu) &&
+            p.opts.tile == 0) {
           st.gap_finish = 1;
           a.mode = M_FLAT; a.pool = POOL_NONE;
         }
@@ -872,8 +880,16 @@ struct Planner {
           const View& rv = p.views[st.v_in2];
           a.vec_res = K % p.ce == 0 && rv.off % p.ce == 0 && rv.sP % p.ce == 0 && rv.sN % p.ce == 0;
         }
+        if (dw_panel_fits && a.mode == M_FLAT && (a.vec_out || st.gap_finish)) {
+          // depthwise panel on chip: as many input channels as fit the unit's private memory beside the weight stages
+          const int bke = kRowBytes / p.esz, cpad = (a.C + bke - 1) / bke * bke;
+          int cp = cpad;
+          while (cp > bke && dwpw_lds_bytes(cp, p.esz) > std::min<size_t>(p.hw.lds_bytes_per_cu, 160 * 1024)) cp -= bke;
+          if (dwpw_lds_bytes(cp, p.esz) <= std::min<size_t>(p.hw.lds_bytes_per_cu, 160 * 1024)) a.dw_panel = cp;
+        }
         xenos_status rc = split_conv(st);
         if (rc != XENOS_OK) return rc;
+        if (a.dw_panel > 0) st.lds = dwpw_lds_bytes(a.dw_panel, p.esz);
         st.flops = 2.0 * a.N * a.OH * a.OW * (double)K * a.R * a.S * is.c + (from_dw ? pro.flops : 0.0);
         if (from_dw) st.bytes_w += pro.bytes_w;
         st.bytes_in = view_bytes(st.v_in); st.bytes_out = view_bytes(st.v_out);
@@ -883,9 +899,11 @@ struct Planner {
         // partition leaves most compute units idle and the reduction is long, split it across workgroups too.
         // Shares are summed in index order by a second pass, so the result does not depend on timing.
         const int nsteps = a.Kred_pad / (kRowBytes / p.esz);
-        if (p.opts.split && st.cfg < kHaloCfg && a.mode == M_FLAT && !from_dw && (st.gap_finish || (a.ntiles * 2 <= p.hw.num_cu && nsteps >= 32))) {
+        if (p.opts.split && st.cfg < kHaloCfg && a.mode == M_FLAT && (!from_dw || (st.gap_finish && a.dw_panel > 0)) &&
+            (st.gap_finish || (a.ntiles * 2 <= p.hw.num_cu && nsteps >= 32))) {
           int ks = std::min({(2 * p.hw.num_cu + a.ntiles - 1) / a.ntiles, nsteps / 8, 32});
           if (st.gap_finish) ks = std::max(ks, 1);
+          if (from_dw) ks = 1;                                     // the depthwise-panel kernel hands over one share
           if (ks >= 4 || st.gap_finish) {
             const int spk = (nsteps + ks - 1) / ks;
             ks = (nsteps + spk - 1) / spk;

@@ -289,7 +289,10 @@ def test_depthwise_pointwise_linked_on_chip(stride, hw, c, k, tail, compute):
     assert i3["n_chains"] < i2["n_chains"] and any(ch.get("dw_linked") for ch in i3["chains"])
     assert not any(ch["kind"] == "dwconv" for ch in i3["chains"])
     y3s, _ = run_gpu(g, compute=compute, link=3, split=0)
-    assert np.array_equal(y3, y3s)
+    if any(ch["kind"] == "splitk_finish" for ch in i3["chains"]):      # the average then runs in another (fixed) order
+        assert np.abs(y3 - y3s).max() <= (4e-6 if compute == 0 else 1e-2) * np.abs(y3s).max()
+    else:
+        assert np.array_equal(y3, y3s)
 
 
 @pytest.mark.parametrize("compute", [0, 1])
