@@ -450,3 +450,84 @@ def test_profiling_driven_partition_choice(net, compute):
         assert np.array_equal(s.output(), y1)
     finally:
         s.close()
+
+
+def _random_graph(seed):
+    """A small random CNN (seeded): odd channel counts, kernel sizes 1-5, strides 1-3, all pooling forms, shortcuts,
+    concats, depthwise layers and an optional FC tail, so that the planner meets shapes nobody wrote a case for."""
+    r = np.random.default_rng(1000 + seed)
+    n = int(r.integers(1, 4))
+    c = int(r.choice([1, 3, 4, 5, 8, 16, 24, 64]))
+    hw = int(r.integers(5, 30))
+    b = wg.builder(f"rand{seed}", (n, c, hw, hw), 100 + seed, nonzero_bias=bool(r.integers(0, 2)))
+    t, ch, size = 0, c, hw
+    for layer in range(int(r.integers(2, 6))):
+        kind = r.choice(["conv", "conv", "conv", "dw", "res", "fire", "pool"])
+        if kind == "conv":
+            k = int(r.choice([1, 3, 7, 16, 24, 40, 64, 72, 136]))
+            ks = int(r.choice([1, 1, 3, 3, 3, 5]))
+            st = int(r.choice([1, 1, 1, 2, 3]))
+            pad = int(r.choice([0, ks // 2]))
+            if (size + 2 * pad - ks) // st + 1 < 1:
+                continue
+            t = b.cbr(t, k, ks, st, pad, name=f"c{layer}", bn=bool(r.integers(0, 2)), relu=bool(r.integers(0, 2)))
+            ch, size = k, (size + 2 * pad - ks) // st + 1
+        elif kind == "dw" and ch % 8 == 0 and size >= 3:
+            st = int(r.choice([1, 2]))
+            t = b.cbr(t, ch, 3, st, 1, groups=ch, name=f"dw{layer}")
+            size = (size + 2 - 3) // st + 1
+        elif kind == "res" and size >= 3:
+            u = b.cbr(t, ch, 3, 1, 1, name=f"r{layer}a")
+            v = b.cbr(u, ch, 3, 1, 1, name=f"r{layer}b", relu=False)
+            t = b.relu(b.add(v, t)) if t != 0 else b.relu(b.add(v, u))
+        elif kind == "fire" and size >= 3:
+            q = b.cbr(t, 8, 1, name=f"f{layer}s", bn=False)
+            e1 = b.cbr(q, 16, 1, name=f"f{layer}e1", bn=False)
+            e3 = b.cbr(q, 24, 3, 1, 1, name=f"f{layer}e3", bn=False)
+            t = b.concat([e1, e3])
+            ch = 40
+        elif kind == "pool" and t != 0 and size >= 3:
+            form = int(r.integers(0, 4))
+            if form == 0:
+                t = b.maxpool(t, 2, 2); size = size // 2
+            elif form == 1:
+                t = b.maxpool(t, 3, 2, 1); size = (size + 2 - 3) // 2 + 1
+            elif form == 2:
+                t = b.maxpool(t, 3, 2, 0, ceil=1); size = -(-(size - 3) // 2) + 1
+            else:
+                t = b.avgpool(t, 2, 2); size = size // 2
+            if size < 1:
+                return None
+    if t == 0:
+        t = b.cbr(0, 8, 1, name="only")
+    tail = int(r.integers(0, 3))
+    if tail == 1:
+        t = b.gap(t)
+    elif tail == 2:
+        t = b.fc(t, int(r.choice([10, 33])), "fc")
+    return b.finish(t)
+
+
+@pytest.mark.parametrize("seed", range(48))
+def test_random_graphs_all_modes(seed):
+    try:
+        g = _random_graph(seed)
+    except Exception:
+        pytest.skip("generator produced an invalid shape")
+    if g is None:
+        pytest.skip("generator produced an empty map")
+    ref = xo.forward(g)
+    # bf16 on odd seeds; outputs of a handful of values go through fp32 (max|ref| of two or three numbers that are sums
+    # with cancellation is no scale for a 2e-2 bound)
+    compute = seed % 2 if ref.size >= 64 else 0
+    for link, split in ((3, 1), (2, 1), (2, 0), (1, 1), (0, 1)):
+        check(g, ref, compute=compute, link=link, split=split)
+    X = _xenos()
+    s = X.Session(g, link=2, compute=compute)
+    try:
+        s.set_input(g.x)
+        s.tune(reps=1)
+        y = s.forward(g.x)
+        assert rel_err(y, ref) <= TOL[compute]
+    finally:
+        s.close()
