@@ -593,7 +593,7 @@ constexpr int V2_NT = 64 * V2_NW;
 constexpr int V2_SCHED = 0;
 constexpr int V2_ABYTES = V2_PPMAX * LDS_ROW;
 __host__ __device__ constexpr int v2_lds(int bn) { return 2 * V2_ABYTES + 2 * bn * LDS_ROW; }   // operand buffers
-__host__ __device__ constexpr int v2_lds_total(int bn) { return v2_lds(bn) + 2 * bn * 4; }            // + scale / shift of the tile
+__host__ __device__ constexpr int v2_lds_total(int bn) { return v2_lds(bn) + 2 * bn * 4 + V2_BM * 12; }  // + scale / shift of the tile, + the row tables
 // passes of the epilogue staging (rows of the tile per pass = rows / passes), sized to one patch buffer
 __host__ __device__ constexpr int v2_passes(int rows, int pitch) {
   return rows * pitch <= V2_ABYTES ? 1 : (rows / 2) * pitch <= V2_ABYTES ? 2 : 4;
@@ -618,7 +618,12 @@ __global__ __launch_bounds__(V2_NT) void conv3x3_kernel(const ConvArgs a) {
   constexpr int CG = BN / CE;                                      // 16-byte channel groups per output row
   constexpr int SPB = BN * ESZ + 16;                               // staging row pitch in bytes
   constexpr int ROWS = MODE == M_FLAT ? BM : BM / 4;               // staged rows: pixels, or pooled windows
-  constexpr int NP = v2_passes(ROWS, SPB), RPP = ROWS / NP;        // staging passes, rows per pass
+  // The finished tile is staged in the patch buffer that is free at the end of a tile; when the free weight stage can
+  // take the rows that do not fit there (bf16, 128 channels: 192 + 64 rows), the whole tile is staged at once,
+  // otherwise in NP passes of RPP rows.
+  constexpr int R1 = ROWS * SPB <= V2_ABYTES ? ROWS : (V2_ABYTES / SPB) / 64 * 64;   // rows staged in the patch buffer
+  constexpr bool SPLIT_STG = R1 < ROWS && R1 > 0 && (ROWS - R1) * SPB <= BBYTES;
+  constexpr int NP = SPLIT_STG ? 1 : v2_passes(ROWS, SPB), RPP = ROWS / NP;
   static_assert(MODE == M_FLAT || MODE == M_ZIGZAG, "row enumerations of the halo kernel");
   static_assert(A_IT % 2 == 0 && B_IT >= 1 && NTH % CG == 0, "loader shapes");
 
@@ -697,6 +702,17 @@ __global__ __launch_bounds__(V2_NT) void conv3x3_kernel(const ConvArgs a) {
       wy = rows4 + y; wx = r - y * hw;
     }
   };
+
+  // which pixel (or pooling window) of the tile each staged row is: the same for every tile, so it is worked out once
+  // (the integer divisions of the enumeration would otherwise be paid per stored channel group)
+  int* s_rowpos = (int*)(smem + v2_lds(BN) + 2 * BN * 4);
+  for (int q = tid; q < ROWS; q += NTH) {
+    int y, x;
+    if (MODE == M_FLAT) flat_px(q, y, x); else zz_win(q, y, x);
+    const bool ok = MODE == M_FLAT ? (y < a.th && x < a.tw) : (2 * y < a.th && 2 * x < a.tw);
+    s_rowpos[q] = ok ? (y << 16) | x : -1;
+  }
+  __syncthreads();
 
   // ---- fragment addresses of this lane's rows (pixels of the tile); the same for every tile --------------
   int abase[2], bbase[TN];
@@ -846,6 +862,7 @@ __global__ __launch_bounds__(V2_NT) void conv3x3_kernel(const ConvArgs a) {
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
+  int aff_tile_n = -1;                                             // channel tile whose scale / shift are in LDS
   // The chain's epilogue for the tile `li`, run after its last chunk (of parity PAR).
   auto epilogue = [&](auto par) {
     constexpr int PAR = decltype(par)::value;
@@ -854,6 +871,9 @@ __global__ __launch_bounds__(V2_NT) void conv3x3_kernel(const ConvArgs a) {
     const int q0 = tyi * a.th, x0 = (tile_m - tyi * a.tiles_x) * a.tw;
     // The patch buffer of the chunk just finished is free (the other one holds the next tile's first patch).
     unsigned char* stg = smem + PAR * V2_ABYTES;
+    // (the weight stage read at the last tap is free as well: the next tile's first step went to the other one)
+    unsigned char* stg2 = smem + 2 * V2_ABYTES + PAR * BBYTES;
+    auto stage_row = [&](int r) -> unsigned char* { return (!SPLIT_STG || r < R1) ? stg + r * SPB : stg2 + (r - R1) * SPB; };
     // shortcut address of this lane's two pixels (rows outside the image read element 0)
     long long rbase[2] = {0, 0};
     if (MODE == M_FLAT && a.has_res) {
@@ -870,7 +890,23 @@ __global__ __launch_bounds__(V2_NT) void conv3x3_kernel(const ConvArgs a) {
     const float lo = a.relu ? 0.f : -3.4028235e38f;                // ReLU as a clamp: no branch per value
     // this tile's folded scale / shift, shared through LDS (every lane needs 32 of the BN values of each)
     float* s_aff = (float*)(smem + v2_lds(BN));
-    if (tid < 2 * BN) s_aff[tid] = tid < BN ? a.scale[tile_n * BN + tid] : a.shift[tile_n * BN + tid - BN];
+    if (tile_n != aff_tile_n) {   // a workgroup walks pixel tiles within a channel tile: reloaded (one memory latency) only when that changes
+      if (tid < 2 * BN) s_aff[tid] = tid < BN ? a.scale[tile_n * BN + tid] : a.shift[tile_n * BN + tid - BN];
+      aff_tile_n = tile_n;
+    }
+    // where each staged row goes in the output (element offset of its channel 0; -1 = not an output of this tile)
+    long long* s_rowoff = (long long*)(smem + v2_lds(BN) + 2 * BN * 4 + V2_BM * 4);
+    for (int q = tid; q < ROWS; q += NTH) {
+      const int pos = s_rowpos[q];
+      long long ob = -1;
+      if (pos >= 0) {
+        const int y = pos >> 16, x = pos & 0xffff;
+        const int qq = q0 + (MODE == M_FLAT ? y : 2 * y), n = qq / Hp, oh = qq - n * Hp, ow = x0 + (MODE == M_FLAT ? x : 2 * x);
+        if (n < a.N && oh < a.H && ow < a.W)
+          ob = (long long)n * a.out_sN + (MODE == M_FLAT ? (long long)(oh * a.OW + ow) : (long long)((oh >> 1) * a.PW + (ow >> 1))) * a.out_sP;
+      }
+      s_rowoff[q] = ob;
+    }
     __syncthreads();
     // first half of a pass: the wavefronts that own its rows finish their accumulators (scale, shift, shortcut,
     // ReLU, pooling) and stage them in the output type.  RES / VEC / PMAX are compile-time copies of the chain's
@@ -922,9 +958,9 @@ __global__ __launch_bounds__(V2_NT) void conv3x3_kernel(const ConvArgs a) {
                 uint2 o;
                 o.x = f2bf2(y[0], y[1]);
                 o.y = f2bf2(y[2], y[3]);
-                *(uint2*)(stg + srow * SPB + c * 2) = o;
+                *(uint2*)(stage_row(srow) + c * 2) = o;
               } else {
-                *(f32x4_t*)(stg + srow * SPB + c * 4) = f32x4_t{y[0], y[1], y[2], y[3]};
+                *(f32x4_t*)(stage_row(srow) + c * 4) = f32x4_t{y[0], y[1], y[2], y[3]};
               }
             }
           }
@@ -944,26 +980,12 @@ __global__ __launch_bounds__(V2_NT) void conv3x3_kernel(const ConvArgs a) {
       }
       __syncthreads();
       {
-        const int nq = MODE == M_FLAT ? a.th * a.tw : (a.th >> 1) * (a.tw >> 1);
         for (int idx = tid; idx < RPP * CG; idx += NTH) {
           const int lr = idx / CG, cg = idx - lr * CG, q = pass * RPP + lr;
           const int k0 = tile_n * BN + cg * CE;
-          if (q >= nq || k0 >= a.K) continue;
-          long long ob;
-          if (MODE == M_FLAT) {
-            int ty, tx;
-            flat_px(q, ty, tx);
-            const int qq = q0 + ty, n = qq / Hp, oh = qq - n * Hp, ow = x0 + tx;
-            if (n >= a.N || oh >= a.H || ow >= a.W) continue;
-            ob = (long long)n * a.out_sN + (long long)(oh * a.OW + ow) * a.out_sP;
-          } else {
-            int wy, wx;
-            zz_win(q, wy, wx);
-            const int qq = q0 + 2 * wy, n = qq / Hp, oh = qq - n * Hp, ow = x0 + 2 * wx;
-            if (n >= a.N || oh >= a.H || ow >= a.W) continue;
-            ob = (long long)n * a.out_sN + (long long)((oh >> 1) * a.PW + (ow >> 1)) * a.out_sP;
-          }
-          *(u32x4_t*)((T*)a.out + ob + k0) = *(const u32x4_t*)(stg + lr * SPB + cg * 16);
+          const long long ob = s_rowoff[q];
+          if (ob < 0 || k0 >= a.K) continue;
+          *(u32x4_t*)((T*)a.out + ob + k0) = *(const u32x4_t*)(stage_row(lr) + cg * 16);
         }
       }
       __syncthreads();
