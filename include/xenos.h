@@ -101,7 +101,8 @@ typedef struct {
  *        1 = DSP-aware operator split (Section 4.2): output channels first, then H/W
  * compute: element type of activations and weights in HBM; accumulation is always fp32.
  * tile: 0 = planner's choice; 1..4 force a tile shape of the general conv kernel; 5 the halo-staged 3x3 kernel
- *       (7 / 8: with 128- / 64-channel tiles) and 6 the first-layer kernel for every chain they apply to, the other
+ *       (7 / 8: with 128- / 64-channel tiles; 9 / 10: the same in its patch-linear form where one exists) and 6 the
+ *       first-layer kernel for every chain they apply to, the other
  *       chains keep the planner's choice (tests, tuning). */
 typedef struct {
   int link;

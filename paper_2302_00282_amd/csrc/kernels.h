@@ -78,6 +78,7 @@ struct ConvArgs {
   float* part;
   int th, tw, tiles_y, tiles_x;   // halo kernel: spatial tile and tile grid over the stacked padded rows n*(H+2)+oh
   int halo_bn;           // halo kernel: output channels per tile (128 or 64)
+  int halo_plin;         // halo kernel: patch-linear rows (GEMM row = patch position, pitch TW + 2; pixel-major chains only)
   int M_total;           // rows enumerated over the whole problem (FLAT, ZIGZAG); per-image rows for GAP
   int tiles_m, tiles_n, ntiles;
   int xcd_m;             // dense-conv kernel: the 8 XCDs form an xcd_m x (8/xcd_m) grid over pixel tiles x (channel tiles x shares)

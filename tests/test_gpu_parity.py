@@ -178,9 +178,16 @@ def test_halo_staged_3x3_kernel(kind, hw, k, bn, compute):
     t = b.cbr(t, 24, 1, 1, 0, name="head")            # the halo chains hand NHWC to this chain
     g = b.finish(t)
     tile = 7 if bn == 128 else 8
+    if kind in ("conv3", "conv3x2", "shortcut"):
+        # the same chains in the patch-linear form (GEMM row = patch position, two junk rows per patch row)
+        yl, il = check(g, compute=compute, tile=tile + 2)
+        assert all(ch["plin"] == 1 and ch["bn"] == bn for ch in il["chains"] if ch.get("halo"))
+        assert sum(1 for ch in il["chains"] if ch.get("halo")) == (2 if kind in ("shortcut", "conv3x2") else 1)
+        yl0, _ = run_gpu(g, compute=compute, tile=tile + 2, split=0)
+        assert np.array_equal(yl, yl0)
     y, info = check(g, compute=compute, tile=tile)
     halo = [ch for ch in info["chains"] if ch.get("halo")]
-    assert len(halo) == (2 if kind in ("shortcut", "conv3x2") else 1) and all(ch["bn"] == bn for ch in halo)
+    assert len(halo) == (2 if kind in ("shortcut", "conv3x2") else 1) and all(ch["bn"] == bn and ch["plin"] == 0 for ch in halo)
     y1, _ = run_gpu(g, compute=compute, tile=tile, split=0)
     assert np.array_equal(y, y1)                       # one workgroup walking every tile == split, bit for bit
     y2, info2 = check(g, compute=compute, tile=tile, hw=dict(X_small=True))
