@@ -497,13 +497,13 @@ struct Planner {
           u.ntiles = u.tiles_m * u.tiles_n;
           // Below half a tile per unit the long per-tile pipeline of this kernel (and its 512-thread epilogue) loses
           // to the small gather tiles, which can also split the reduction (measured on the batch-1 networks).
-          if (2 * u.ntiles < num_cu && force_tile == 0) continue;
+          const bool thin = 2 * u.ntiles < num_cu && force_tile == 0;   // (still a candidate for the tuner when at least 32 tiles)
           // (the patch-linear form measured within +-3 % of the plain one, 6 % faster on 14x14 maps: same model, ties go
           // to the plain form, the tuner decides by measurement)
           const double per_tile = (double)kHaloRows * bns[v] / rate[v];
           const double cost = (double)((u.ntiles + num_cu - 1) / num_cu) * per_tile;
-          if (cost < best_cost) { best_cost = cost; best = kHaloCfg; best_args = u; }
-          if (p.opts.tile == 0) { set_grid(u, kHaloCfg); st.cands.push_back(Step::Cand{kHaloCfg, u, conv_lds_bytes(kHaloCfg, c.mode)}); }
+          if (cost < best_cost && !thin) { best_cost = cost; best = kHaloCfg; best_args = u; }
+          if (p.opts.tile == 0 && (!thin || u.ntiles >= 32)) { set_grid(u, kHaloCfg); st.cands.push_back(Step::Cand{kHaloCfg, u, conv_lds_bytes(kHaloCfg, c.mode)}); }
         }
       }
     }
