@@ -41,7 +41,11 @@ static const int kHaloCfg = 4;
 static const int kStemCfg = 5;
 static const int kStemPasses = 5;
 static const int kStemRed = 32 * kStemPasses;
-static const int kHaloRows = 256, kHaloCols = 128, kHaloPatchMax = 384;
+// Configuration index of the kernel that links the first two 3x3 convolutions (intermediate tensor kept in LDS): at most
+// 4 input channels -> kPairChannels -> kPairChannels; the first convolution reduces over kPairRed slots = tap * 4 + channel.
+static const int kPairCfg = 6;
+static const int kPairChannels = 64, kPairRed = 48;
+static const int kHaloRows = 256, kHaloCols = 128, kHaloPatchMax = 360;
 // the staged patch has one of two fixed row pitches (pixels): tiles up to 16 or up to 32 pixels wide
 static const int kHaloPitchNarrow = 18, kHaloPitchWide = 34;
 
@@ -71,6 +75,11 @@ struct ConvArgs {
   const void* dw_w; const float* dw_scale; const float* dw_shift;   // [k*k][C] compute type, folded scale / shift [C]
   int dw_k, dw_stride, dw_pad, dw_H, dw_W, dw_relu;
   long long dw_sN, dw_sP;
+  // linked first-layer producer (pair kernel): `in` is the caller's fp32 NCHW tensor (unit stride along W) with pair_C
+  // channels, dw_w its packed weights [kPairChannels][kPairRed], dw_scale / dw_shift / dw_relu its epilogue; C, H, W
+  // describe the intermediate tensor
+  int pair, pair_C;
+  long long pair_sN, pair_sC, pair_sH;
   int dw_panel;          // > 0: the depthwise result of a whole panel of this many channels is staged in LDS (dwpw_kernel)
   // reduction split across workgroups (ksplit >= 1, M_FLAT only; 0 = none): share z covers steps [z*steps_per_split, ...)
   // and writes raw fp32 sums to part[z][m][k] (row pitch part_ld); a splitk_finish pass completes the chain

@@ -583,16 +583,19 @@ __global__ __launch_bounds__(NT, 2) void conv_kernel(const ConvArgs a) {
 // output channels, columns = pixels): a lane then owns 4 consecutive channels of one pixel, the 2x2 pooling
 // window of the zig-zag enumeration is 4 neighbouring lanes (reduced with DPP quad permutes), and the finished
 // values go through LDS once, already in the output type, to be stored as whole 16-byte channel groups.
-constexpr int V2_BM = 256, V2_PPMAX = 384;
+constexpr int V2_BM = 256, V2_PPMAX = kHaloPatchMax;
 // wavefronts per workgroup: 8 (4 x 2 of 64 pixels x BN/2 channels).  4 wavefronts of 64 x BN (a quarter fewer LDS
 // fragment reads per MFMA) were measured 20-60 % slower: one wavefront per SIMD cannot hide the fragment-read latency.
 constexpr int V2_NW = 8;
 constexpr int V2_NT = 64 * V2_NW;
-// 0: the LDS writes that publish the next step follow the MFMAs of a tap; 1: they are interleaved after the first
-// k-group.  Measured on VGG-16 layers (batch 32, bf16): 1 is 4-7 % slower (the writes then delay the fragment reads).
-constexpr int V2_SCHED = 0;
+// The LDS writes that publish a later step follow the MFMAs of a tap (interleaved after the first k-group they were
+// measured 4-7 % slower on VGG-16 layers, batch 32, bf16: the writes then delay the fragment reads).
+// Weight stages in LDS: step s is read from stage s % 3 while step s + 2 is written to stage (s + 2) % 3, so stage
+// (s + 1) % 3 is already visible during step s and the first fragments of step s + 1 are fetched before the barrier
+// that ends step s: the MFMAs of a step start right after the barrier instead of after an LDS round trip.
+constexpr int V2_WST = 3;
 constexpr int V2_ABYTES = V2_PPMAX * LDS_ROW;
-__host__ __device__ constexpr int v2_lds(int bn) { return 2 * V2_ABYTES + 2 * bn * LDS_ROW; }   // operand buffers
+__host__ __device__ constexpr int v2_lds(int bn) { return 2 * V2_ABYTES + V2_WST * bn * LDS_ROW; }   // operand buffers
 __host__ __device__ constexpr int v2_lds_total(int bn) { return v2_lds(bn) + 2 * bn * 4 + V2_BM * 12; }  // + scale / shift of the tile, + the row tables
 // passes of the epilogue staging (rows of the tile per pass = rows / passes), sized to one patch buffer
 __host__ __device__ constexpr int v2_passes(int rows, int pitch) {
@@ -617,7 +620,7 @@ __global__ __launch_bounds__(V2_NT) void conv3x3_kernel(const ConvArgs a) {
   constexpr int BM = V2_BM, NTH = V2_NT;
   constexpr int WAVES_N = V2_NW / 4;                               // 4 x WAVES_N wavefronts of 64 pixels x WN channels
   constexpr int WN = BN / WAVES_N, TN = WN / 32;
-  constexpr int A_IT = V2_PPMAX * CPR / NTH;                       // patch chunks per thread
+  constexpr int A_IT = (V2_PPMAX * CPR + 2 * NTH - 1) / (2 * NTH) * 2;   // patch chunks per thread (an even count; the last may lie beyond the buffer)
   constexpr int B_IT = BN * CPR / NTH;                             // weight chunks per thread
   constexpr int BBYTES = BN * LDS_ROW;
   constexpr int CG = BN / CE;                                      // 16-byte channel groups per output row
@@ -626,7 +629,7 @@ __global__ __launch_bounds__(V2_NT) void conv3x3_kernel(const ConvArgs a) {
   // The finished tile is staged in the patch buffer that is free at the end of a tile; when the free weight stage can
   // take the rows that do not fit there (bf16, 128 channels: 192 + 64 rows), the whole tile is staged at once,
   // otherwise in NP passes of RPP rows.
-  constexpr int R1 = ROWS * SPB <= V2_ABYTES ? ROWS : (V2_ABYTES / SPB) / 64 * 64;   // rows staged in the patch buffer
+  constexpr int R1 = ROWS * SPB <= V2_ABYTES ? ROWS : V2_ABYTES / SPB;   // rows staged in the patch buffer
   constexpr bool SPLIT_STG = R1 < ROWS && R1 > 0 && (ROWS - R1) * SPB <= BBYTES;
   constexpr int NP = SPLIT_STG ? 1 : v2_passes(ROWS, SPB), RPP = ROWS / NP;
   static_assert(MODE == M_FLAT || MODE == M_ZIGZAG, "row enumerations of the halo kernel");
@@ -756,6 +759,7 @@ __global__ __launch_bounds__(V2_NT) void conv3x3_kernel(const ConvArgs a) {
 #pragma unroll
     for (int it = 0; it < A_HALF; ++it) {
       const int idx = tid + (half * A_HALF + it) * NTH;
+      if ((half * A_HALF + it + 1) * NTH > V2_PPMAX * CPR && idx >= V2_PPMAX * CPR) continue;   // beyond the buffer
       *(u32x4_t*)(sa + (idx / CPR) * LDS_ROW + (idx % CPR) * 16) = ((aok >> (half * A_HALF + it)) & 1u) ? pa[it] : z;
     }
   };
@@ -771,24 +775,23 @@ __global__ __launch_bounds__(V2_NT) void conv3x3_kernel(const ConvArgs a) {
       *(u32x4_t*)(sb + (idx / CPR) * LDS_ROW + (idx % CPR) * 16) = rb[it];
     }
   };
-  // one tap of one channel chunk: 4 k-groups, fragments of k-group g+1 are fetched before the MFMAs of g
-  auto compute = [&](int abuf, int bstage, int tapoff) {
-    const unsigned char* sa = smem + abuf * V2_ABYTES + tapoff;
-    const unsigned char* sb = smem + 2 * V2_ABYTES + bstage * BBYTES;
-    u32x4_t fa[2][2], fb[2][TN];
+  // one tap of one channel chunk: 4 k-groups, fragments of k-group g+1 are fetched before the MFMAs of g; the fragments
+  // of k-group 0 were fetched during the previous step, and the last k-group fetches those of the next step (`nsa`, `nsb`:
+  // its patch position and weight stage, both published at least one barrier ago)
+  u32x4_t fa[2][2], fb[2][TN];
+  static_assert(KG % 2 == 0, "the fragment slots alternate per k-group and must line up across steps");
+  auto fetch = [&](int slot, const unsigned char* sa, const unsigned char* sb, int kg) __attribute__((always_inline)) {
 #pragma unroll
-    for (int i = 0; i < 2; ++i) fa[0][i] = *(const u32x4_t*)(sa + abase[i]);
+    for (int i = 0; i < 2; ++i) fa[slot][i] = *(const u32x4_t*)(sa + abase[i] + kg * 32);
 #pragma unroll
-    for (int j = 0; j < TN; ++j) fb[0][j] = *(const u32x4_t*)(sb + bbase[j]);
+    for (int j = 0; j < TN; ++j) fb[slot][j] = *(const u32x4_t*)(sb + bbase[j] + kg * 32);
+  };
+  auto compute = [&](const unsigned char* sa, const unsigned char* sb, const unsigned char* nsa, const unsigned char* nsb) {
 #pragma unroll
     for (int kg = 0; kg < KG; ++kg) {
       const int cur = kg & 1, nxt = cur ^ 1;
-      if (kg + 1 < KG) {
-#pragma unroll
-        for (int i = 0; i < 2; ++i) fa[nxt][i] = *(const u32x4_t*)(sa + abase[i] + (kg + 1) * 32);
-#pragma unroll
-        for (int j = 0; j < TN; ++j) fb[nxt][j] = *(const u32x4_t*)(sb + bbase[j] + (kg + 1) * 32);
-      }
+      if (kg + 1 < KG) fetch(nxt, sa, sb, kg + 1);
+      else fetch(nxt, nsa, nsb, 0);
 #pragma unroll
       for (int i = 0; i < 2; ++i)
 #pragma unroll
@@ -806,63 +809,66 @@ __global__ __launch_bounds__(V2_NT) void conv3x3_kernel(const ConvArgs a) {
         }
     }
   };
-  // The schedule wanted for one tap (0x100 = LDS read, 0x200 = LDS write, 0x008 = MFMA): fragments of k-group g+1
-  // are in flight while the MFMAs of k-group g issue.  Without the directives the scheduler serialises
-  // read -> wait -> MFMA.
-  auto tap_schedule = [&](int patch_writes) {
-    __builtin_amdgcn_sched_group_barrier(0x100, 2 + TN, 0);
+  // The schedule wanted for one tap (0x100 = LDS read, 0x008 = MFMA): the fragments of the following k-group are in
+  // flight while the MFMAs of a k-group issue.  Without the directives the scheduler serialises read -> wait -> MFMA.
+  auto tap_schedule = [&]() {
 #pragma unroll
     for (int kg = 0; kg < KG; ++kg) {
-      if (kg + 1 < KG) __builtin_amdgcn_sched_group_barrier(0x100, 2 + TN, 0);
+      __builtin_amdgcn_sched_group_barrier(0x100, 2 + TN, 0);
       __builtin_amdgcn_sched_group_barrier(0x008, (sizeof(T) == 2 ? 2 : 8) * TN, 0);
-      if (V2_SCHED == 1 && kg == 0) __builtin_amdgcn_sched_group_barrier(0x200, B_IT, 0);
-      if (V2_SCHED == 1 && kg == 1 && patch_writes) __builtin_amdgcn_sched_group_barrier(0x200, A_HALF, 0);
     }
   };
   // Nine statically unrolled taps of channel chunk cc.  PAR = parity of the chunk in the workgroup's whole chunk
-  // sequence: it selects the patch buffer, and (9 steps per chunk) the weight stage / register set of tap 0.
+  // sequence: it selects the patch buffer, and (9 steps per chunk) the register set of tap 0; the weight stage of a tap
+  // is tap % 3 in every chunk.
   // `last`: the chunk after this one belongs to the next tile (aoff / aok / wnext already describe that tile).
   auto chunk_body = [&](int cc, bool last, auto par) {
     constexpr int PAR = decltype(par)::value;
     const int step0 = cc * 9;
     const int cnext = last ? 0 : (cc + 1) * BKE;
+    unsigned char* const sw = smem + 2 * V2_ABYTES;
 #pragma unroll
     for (int tap = 0; tap < 9; ++tap) {
-      const int sp = (PAR + tap) & 1;                              // weight stage / register set of this step
+      const int sp = (PAR + tap) & 1;                              // register set of this step
       u32x4_t* rb = sp == 0 ? rb0 : rb1;
-      if (tap < 7) load_w(step0 + tap + 2, rb);              // weights of step + 2 ...
+      if (tap < 6) load_w(step0 + tap + 3, rb);                    // weights of step + 3 ...
       else {
-        // ... which for the last two taps of a tile are steps 0 and 1 of the next tile
+        // ... which for the last three taps of a tile are steps 0, 1, 2 of the next tile
 #pragma unroll
         for (int it = 0; it < B_IT; ++it) {
-          const int src = (last ? wnext + (tap - 7) * ROWB : wrow + (step0 + tap + 2) * ROWB) + it * wstride;
+          const int src = (last ? wnext + (tap - 6) * ROWB : wrow + (step0 + tap + 3) * ROWB) + it * wstride;
           rb[it] = *(const u32x4_t*)((const unsigned char*)a.w + src);
         }
       }
       if (tap == 0) load_patch(cnext, 0);                          // next chunk's patch: half 0 in flight over taps 0-3,
-      if (tap == 4) load_patch(cnext, 1);                          // half 1 over taps 4-8
+      if (tap == 4) load_patch(cnext, 1);                          // half 1 over taps 4-7
       __builtin_amdgcn_sched_barrier(0);                           // keep the prefetch loads ahead of the MFMA block
-      compute(PAR, sp, ((tap / 3) * PW_ + tap % 3) * LDS_ROW);
-      if (V2_SCHED == 0) { tap_schedule(0); __builtin_amdgcn_sched_barrier(0); }
-      if (sp == 0) store_w(1, rb1); else store_w(0, rb0);         // publish step + 1
+      const int tapoff = ((tap / 3) * PW_ + tap % 3) * LDS_ROW, ntapoff = (((tap + 1) / 3) * PW_ + (tap + 1) % 3) * LDS_ROW;
+      compute(smem + PAR * V2_ABYTES + tapoff, sw + (tap % 3) * BBYTES,
+              tap < 8 ? smem + PAR * V2_ABYTES + ntapoff : smem + (PAR ^ 1) * V2_ABYTES, sw + ((tap + 1) % 3) * BBYTES);
+      tap_schedule();
+      __builtin_amdgcn_sched_barrier(0);
+      store_w((tap + 2) % 3, sp == 0 ? rb1 : rb0);                 // publish step + 2 (loaded during the previous step)
       if (tap == 3) store_patch(PAR ^ 1, 0);
-      if (tap == 8) store_patch(PAR ^ 1, 1);
-      if (V2_SCHED == 1) { tap_schedule(tap == 3 || tap == 8); __builtin_amdgcn_sched_barrier(0); }
+      if (tap == 7) store_patch(PAR ^ 1, 1);                       // (complete one barrier before tap 8 fetches from it)
       __syncthreads();
     }
   };
 
-  // ---- pipeline start: chunk 0 and weight steps 0, 1 of the first tile ---------------------------------
+  // ---- pipeline start: chunk 0, weight steps 0, 1 (in LDS) and 2 (in registers), first fragments of the first tile ----
   patch_addr(li);
   wrow = weight_addr(li);
   load_patch(0, 0);
   load_w(0, rb0);
+  load_w(1, rb1);
   store_patch(0, 0);
   load_patch(0, 1);
   store_w(0, rb0);
+  store_w(1, rb1);
   store_patch(0, 1);
-  load_w(1, rb1);
+  load_w(2, rb1);
   __syncthreads();
+  fetch(0, smem, smem + 2 * V2_ABYTES, 0);
 
 #pragma unroll
   for (int i = 0; i < 2; ++i)
@@ -880,8 +886,8 @@ __global__ __launch_bounds__(V2_NT) void conv3x3_kernel(const ConvArgs a) {
     const int q0 = tyi * a.th, x0 = (tile_m - tyi * a.tiles_x) * a.tw;
     // The patch buffer of the chunk just finished is free (the other one holds the next tile's first patch).
     unsigned char* stg = smem + PAR * V2_ABYTES;
-    // (the weight stage read at the last tap is free as well: the next tile's first step went to the other one)
-    unsigned char* stg2 = smem + 2 * V2_ABYTES + PAR * BBYTES;
+    // (the weight stage read at the last tap is free as well: the next tile's first two steps are in the other two)
+    unsigned char* stg2 = smem + 2 * V2_ABYTES + 2 * BBYTES;
     auto stage_row = [&](int r) -> unsigned char* { return (!SPLIT_STG || r < R1) ? stg + r * SPB : stg2 + (r - R1) * SPB; };
     // shortcut address of this lane's two pixels (rows outside the image read element 0)
     long long rbase[2] = {0, 0};
@@ -1071,6 +1077,339 @@ static int launch_conv3x3_t(const ConvArgs& a, hipStream_t st) {
   if (a.mode == M_FLAT) return a.halo_bn == 128 ? launch_conv3x3_inst<T, M_FLAT, 128>(a, st) : launch_conv3x3_inst<T, M_FLAT, 64>(a, st);
   if (a.mode == M_ZIGZAG) return a.halo_bn == 128 ? launch_conv3x3_inst<T, M_ZIGZAG, 128>(a, st) : launch_conv3x3_inst<T, M_ZIGZAG, 64>(a, st);
   return (int)hipErrorInvalidValue;
+}
+
+// ---------------------------------------------------------------------------------------------
+// Two linked 3x3 / stride 1 / pad 1 convolution chains (Table 1, ConvX -> ConvY; Section 4.1): the first layer
+// (at most 4 input channels, read from the caller's fp32 NCHW tensor) -> 64 channels -> 64 channels [-> 2x2 pooling].
+// The intermediate tensor is never written to memory: a workgroup owns a TH x TW block of output pixels, computes the
+// (TH+2) x (TW+2) block of the intermediate that those pixels read (halo recomputed per tile, the paper's halo
+// replication) straight into the LDS patch of the second convolution, and runs the second convolution out of it.
+// Both weight tensors stay resident in LDS for all tiles of the (persistent) workgroup, so the nine taps of the second
+// convolution run without a barrier.  bf16 operands, fp32 accumulation; the intermediate is rounded to bf16 exactly as
+// it would be when stored between two separate chains.
+//
+// Phases per tile (barriers between them): P1 first convolution as a transposed MFMA GEMM over the patch positions
+// (reduction slot = tap * 4 + channel, 48 slots), scale / shift / ReLU, positions outside the image forced to zero (they
+// are the padding of the second convolution); P2 second convolution, 32 pixels x 64 channels per wavefront; then the
+// epilogue of the halo kernel (scale / shift / ReLU, zig-zag pooling over lane quads, staging, 16-byte stores).  The
+// fp32 input block of the next tile is fetched during P2.
+// ---------------------------------------------------------------------------------------------
+constexpr int PR_PW = kHaloPitchNarrow;       // patch row pitch in pixels
+constexpr int PR_C = kPairChannels;           // channels of the intermediate and of the output
+constexpr int PR_K1 = kPairRed;               // reduction slots of the first convolution (3 MFMA steps of 16)
+constexpr int PR_W1ROW = PR_K1 * 2 + 16;      // LDS row pitch of its weights: an odd number of 16-byte slots
+constexpr int PR_INMAX = 640;                 // pixels of the staged input block, (TH+4) x (TW+4)
+constexpr int PR_W2BYTES = 9 * PR_C * LDS_ROW;
+constexpr int PR_OFF_PATCH = PR_W2BYTES;
+constexpr int PR_OFF_W1 = PR_OFF_PATCH + V2_ABYTES;
+constexpr int PR_OFF_XIN = PR_OFF_W1 + PR_C * PR_W1ROW;
+constexpr int PR_OFF_AFF = PR_OFF_XIN + PR_INMAX * 8;
+constexpr int PR_OFF_ROWPOS = PR_OFF_AFF + 4 * PR_C * 4;
+constexpr int PR_OFF_ROWOFF = PR_OFF_ROWPOS + V2_BM * 4;
+constexpr int PR_LDS = PR_OFF_ROWOFF + V2_BM * 8;
+
+template <int MODE>
+__global__ __launch_bounds__(V2_NT) void conv_pair_kernel(const ConvArgs a) {
+  constexpr int BM = V2_BM, NTH = V2_NT, CE = 8;
+  constexpr int ROWS = MODE == M_FLAT ? BM : BM / 4;               // staged rows: pixels, or pooled windows
+  constexpr int SPB = PR_C * 2 + 16;                               // staging row pitch in bytes
+  constexpr int CG = PR_C / CE;
+  constexpr int NI = (PR_INMAX * 4 + NTH - 1) / NTH;               // input elements per thread
+  static_assert(MODE == M_FLAT || MODE == M_ZIGZAG, "row enumerations of the pair kernel");
+  static_assert(BM * SPB <= V2_ABYTES, "the finished tile is staged in the patch buffer");
+
+  extern __shared__ __align__(16) unsigned char smem[];
+  unsigned char* s_w2 = smem;
+  unsigned char* s_patch = smem + PR_OFF_PATCH;
+  unsigned char* s_w1 = smem + PR_OFF_W1;
+  unsigned char* s_xin = smem + PR_OFF_XIN;
+  float* s_aff = (float*)(smem + PR_OFF_AFF);                     // scale1, shift1, scale2, shift2
+  int* s_rowpos = (int*)(smem + PR_OFF_ROWPOS);
+  long long* s_rowoff = (long long*)(smem + PR_OFF_ROWOFF);
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int l31 = lane & 31, lhalf = lane >> 5;
+  const int Hp = a.H + 2, IW = a.tw + 4, npix = (a.th + 4) * IW, PP = (a.th + 2) * PR_PW;
+  const int nin = a.pair_C * npix;
+
+  // ---- this workgroup's tiles: each XCD owns a contiguous, balanced range (neighbouring tiles share input rows) ----
+  const int G = gridDim.x, nx = G < NUM_XCD ? G : NUM_XCD;
+  const int xcd = blockIdx.x % nx, wgs = (G - xcd + nx - 1) / nx;
+  const int m0 = xcd * a.tiles_m / nx, mlen = (xcd + 1) * a.tiles_m / nx - m0;
+  int li = blockIdx.x / nx;
+  if (li >= mlen) return;                                          // uniform per workgroup
+
+  // ---- the fp32 input block of a tile: element e = (channel, block row, block column) ------------------------
+  float xr[NI];
+  auto load_xin = [&](int l) __attribute__((always_inline)) {
+    const int tile_m = m0 + l, tyi = tile_m / a.tiles_x;
+    const int q0 = tyi * a.th, x0 = (tile_m - tyi * a.tiles_x) * a.tw;
+#pragma unroll
+    for (int it = 0; it < NI; ++it) {
+      const int e = tid + it * NTH;
+      float v = 0.f;
+      if (e < nin) {
+        const int c = e / npix, rem = e - c * npix, ir = rem / IW, ic = rem - ir * IW;
+        const int sr = q0 - 1 + ir;                                // stacked row: image n = sr / (H+2), input row sr % (H+2) - 1
+        const int n = sr >= 0 ? sr / Hp : 0, ih = sr - n * Hp - 1, iw = x0 - 2 + ic;
+        if (sr >= 0 && n < a.N && (unsigned)ih < (unsigned)a.H && (unsigned)iw < (unsigned)a.W)
+          v = ((const float*)a.in)[(long long)n * a.pair_sN + (long long)c * a.pair_sC + (long long)ih * a.pair_sH + iw];
+      }
+      xr[it] = v;
+    }
+  };
+  auto store_xin = [&]() __attribute__((always_inline)) {
+#pragma unroll
+    for (int it = 0; it < NI; ++it) {
+      const int e = tid + it * NTH;
+      if (e < nin) {
+        const int c = e / npix, rem = e - c * npix;
+        *(uint16_t*)(s_xin + rem * 8 + c * 2) = f2bf(xr[it]);
+      }
+    }
+  };
+
+  // ---- which pixel of the tile a GEMM row is (the conflict-free enumerations of the halo kernel, pitch 18) ----
+  auto flat_px = [&](int m, int& ty, int& tx) __attribute__((always_inline)) {
+    const int nbx = a.tw >> 1, rows8 = (a.tw & 1) ? 0 : (a.th >> 3) * 8, full = rows8 * a.tw;
+    if (m < full) {
+      const int b = m >> 4, i = m & 15, by = b / nbx, bx = b - by * nbx;
+      ty = by * 8 + (i >> 1); tx = bx * 2 + (i & 1);
+    } else {
+      const int r = m - full, y = r / a.tw;
+      ty = rows8 + y; tx = r - y * a.tw;
+    }
+  };
+  auto zz_win = [&](int w, int& wy, int& wx) __attribute__((always_inline)) {
+    const int hw = a.tw >> 1, rows4 = (a.th >> 3) * 4, full = rows4 * hw;
+    if (w < full) {
+      const int g = w / (4 * hw), r = w - g * 4 * hw;
+      wx = r >> 2; wy = g * 4 + (r & 3);
+    } else {
+      const int r = w - full, y = r / hw;
+      wy = rows4 + y; wx = r - y * hw;
+    }
+  };
+
+  // ---- set-up: resident weights, scale / shift, row table, zeroed input block ---------------------------------
+  for (int i = tid; i < PR_INMAX * 2; i += NTH) ((uint32_t*)s_xin)[i] = 0u;   // channel slots beyond pair_C stay zero
+  for (int idx = tid; idx < 9 * PR_C * CPR; idx += NTH) {
+    const int c8 = idx % CPR, row = idx / CPR, tap = row / PR_C, k = row - tap * PR_C;
+    *(u32x4_t*)(s_w2 + row * LDS_ROW + c8 * 16) =
+        *(const u32x4_t*)((const unsigned char*)a.w + ((long long)k * a.Kred_pad + tap * PR_C + c8 * 8) * 2);
+  }
+  for (int idx = tid; idx < PR_C * (PR_K1 / 8); idx += NTH) {
+    const int c6 = idx % (PR_K1 / 8), k = idx / (PR_K1 / 8);
+    *(u32x4_t*)(s_w1 + k * PR_W1ROW + c6 * 16) = *(const u32x4_t*)((const unsigned char*)a.dw_w + (k * PR_K1 + c6 * 8) * 2);
+  }
+  if (tid < 4 * PR_C) {
+    const int w = tid / PR_C, c = tid - w * PR_C;
+    s_aff[tid] = w == 0 ? a.dw_scale[c] : w == 1 ? a.dw_shift[c] : w == 2 ? a.scale[c] : a.shift[c];
+  }
+  for (int q = tid; q < ROWS; q += NTH) {
+    int y, x;
+    if (MODE == M_FLAT) flat_px(q, y, x); else zz_win(q, y, x);
+    const bool ok = MODE == M_FLAT ? (y < a.th && x < a.tw) : (2 * y < a.th && 2 * x < a.tw);
+    s_rowpos[q] = ok ? (y << 16) | x : -1;
+  }
+  __syncthreads();
+  load_xin(li);
+  store_xin();
+
+  // ---- per-lane constants -------------------------------------------------------------------------------------
+  // P1: the two taps (4 slots each) this half-wavefront feeds to MFMA step j are taps 4j + 2*lhalf and the next one;
+  // taps 9..11 do not exist (zero operand)
+  int toff[3][2];
+#pragma unroll
+  for (int j = 0; j < 3; ++j)
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      const int t = 4 * j + 2 * lhalf + h;
+      toff[j][h] = t < 9 ? ((t / 3) * IW + t % 3) * 8 : -1;
+    }
+  const int w1b = l31 * PR_W1ROW + lhalf * 16;
+  // P2: this lane's pixel and weight rows
+  int abase;
+  {
+    const int m = wave * 32 + l31;
+    int ty, tx;
+    if (MODE == M_FLAT) flat_px(m, ty, tx);
+    else {
+      int wy, wx;
+      zz_win(m >> 2, wy, wx);
+      ty = 2 * wy + ((m >> 1) & 1); tx = 2 * wx + (m & 1);
+    }
+    abase = ((ty < a.th && tx < a.tw) ? ty * PR_PW + tx : 0) * LDS_ROW + lhalf * 16;
+  }
+  const int bbase = l31 * LDS_ROW + lhalf * 16;
+  const int nunits = (PP + 31) / 32;
+  const float lo1 = a.dw_relu ? 0.f : -3.4028235e38f, lo2 = a.relu ? 0.f : -3.4028235e38f;
+  __syncthreads();
+
+  for (;;) {
+    const int tile_m = m0 + li, tyi = tile_m / a.tiles_x;
+    const int q0 = tyi * a.th, x0 = (tile_m - tyi * a.tiles_x) * a.tw;
+
+    // where each staged row goes in the output (element offset of its channel 0; -1 = not an output of this tile)
+    for (int q = tid; q < ROWS; q += NTH) {
+      const int pos = s_rowpos[q];
+      long long ob = -1;
+      if (pos >= 0) {
+        const int y = pos >> 16, x = pos & 0xffff;
+        const int qq = q0 + (MODE == M_FLAT ? y : 2 * y), n = qq / Hp, oh = qq - n * Hp, ow = x0 + (MODE == M_FLAT ? x : 2 * x);
+        if (n < a.N && oh < a.H && ow < a.W)
+          ob = (long long)n * a.out_sN + (MODE == M_FLAT ? (long long)(oh * a.OW + ow) : (long long)((oh >> 1) * a.PW + (ow >> 1))) * a.out_sP;
+      }
+      s_rowoff[q] = ob;
+    }
+
+    // ---- P1: the intermediate at the patch positions p = 32 * unit + lane % 32 ---------------------------------
+    for (int u = wave; u < nunits; u += V2_NW) {
+      const int p = u * 32 + l31, pcl = p < PP ? p : PP - 1;
+      const int pr = pcl / PR_PW, pc = pcl - pr * PR_PW;
+      const unsigned char* xb = s_xin + (pr * IW + pc) * 8;
+      f32x16_t c1[2];
+#pragma unroll
+      for (int j2 = 0; j2 < 2; ++j2)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) c1[j2][e] = 0.f;
+#pragma unroll
+      for (int j = 0; j < 3; ++j) {
+        uint2 t0 = *(const uint2*)(xb + (toff[j][0] >= 0 ? toff[j][0] : 0));
+        uint2 t1 = *(const uint2*)(xb + (toff[j][1] >= 0 ? toff[j][1] : 0));
+        if (toff[j][0] < 0) t0 = uint2{0u, 0u};
+        if (toff[j][1] < 0) t1 = uint2{0u, 0u};
+        const u32x4_t fa = {t0.x, t0.y, t1.x, t1.y};
+#pragma unroll
+        for (int j2 = 0; j2 < 2; ++j2) {
+          const u32x4_t fb = *(const u32x4_t*)(s_w1 + w1b + j2 * 32 * PR_W1ROW + j * 32);
+          c1[j2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, fb), __builtin_bit_cast(bf16x8_t, fa), c1[j2], 0, 0, 0);
+        }
+      }
+      const int P = q0 + pr, n = P / Hp, ih = P - n * Hp - 1, iw = x0 - 1 + pc;
+      const bool inside = n < a.N && (unsigned)ih < (unsigned)a.H && (unsigned)iw < (unsigned)a.W;
+      if (p < PP) {
+#pragma unroll
+        for (int j2 = 0; j2 < 2; ++j2)
+#pragma unroll
+          for (int g = 0; g < 4; ++g) {
+            const int c = j2 * 32 + g * 8 + lhalf * 4;
+            const f32x4_t sc = *(const f32x4_t*)(s_aff + c), sh = *(const f32x4_t*)(s_aff + PR_C + c);
+            float y[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              y[e] = fmaxf(c1[j2][4 * g + e] * sc[e] + sh[e], lo1);
+              y[e] = inside ? y[e] : 0.f;                          // padding of the second convolution
+            }
+            uint2 o;
+            o.x = f2bf2(y[0], y[1]);
+            o.y = f2bf2(y[2], y[3]);
+            *(uint2*)(s_patch + p * LDS_ROW + c * 2) = o;
+          }
+      }
+    }
+    __syncthreads();
+
+    // ---- P2: the second convolution out of the patch; the next tile's input block is on its way meanwhile --------
+    const bool more = li + wgs < mlen;
+    if (more) load_xin(li + wgs);
+    f32x16_t acc[2];
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[j][e] = 0.f;
+    {
+      constexpr int NS = 36, DEPTH = 2;                            // (tap, k-group) steps; fragments fetched DEPTH steps ahead
+      u32x4_t fa[DEPTH + 1], fb[DEPTH + 1][2];
+      auto fetch = [&](int s, int slot) __attribute__((always_inline)) {
+        const int tap = s >> 2, kg = s & 3;
+        fa[slot] = *(const u32x4_t*)(s_patch + abase + ((tap / 3) * PR_PW + tap % 3) * LDS_ROW + kg * 32);
+#pragma unroll
+        for (int j = 0; j < 2; ++j) fb[slot][j] = *(const u32x4_t*)(s_w2 + (tap * PR_C + j * 32) * LDS_ROW + bbase + kg * 32);
+      };
+#pragma unroll
+      for (int s = 0; s < DEPTH; ++s) fetch(s, s);
+#pragma unroll
+      for (int s = 0; s < NS; ++s) {
+        if (s + DEPTH < NS) fetch(s + DEPTH, (s + DEPTH) % (DEPTH + 1));
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+          acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, fb[s % (DEPTH + 1)][j]),
+                                                           __builtin_bit_cast(bf16x8_t, fa[s % (DEPTH + 1)]), acc[j], 0, 0, 0);
+      }
+    }
+    if (more) store_xin();
+    __syncthreads();                                               // the patch is free: it becomes the output staging
+
+    // ---- epilogue: scale / shift / ReLU, pooling over the lane quad, staging in the output type -----------------
+    {
+      const int m = wave * 32 + l31;
+      const int srow = MODE == M_FLAT ? m : (m >> 2);
+      const bool pmax = a.pool == POOL_MAX;
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const int c = j * 32 + g * 8 + lhalf * 4;
+          const f32x4_t sc = *(const f32x4_t*)(s_aff + 2 * PR_C + c), sh = *(const f32x4_t*)(s_aff + 3 * PR_C + c);
+          float y[4];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) y[e] = fmaxf(acc[j][4 * g + e] * sc[e] + sh[e], lo2);
+          bool mine = true;
+          if (MODE == M_ZIGZAG) {
+            // the window's four pixels are lanes 4w .. 4w+3: butterfly over the quad, lane i keeps group g == i
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              const float p1 = quad_perm<0xB1>(y[e]);
+              y[e] = pmax ? fmaxf(y[e], p1) : y[e] + p1;
+              const float p2 = quad_perm<0x4E>(y[e]);
+              y[e] = pmax ? fmaxf(y[e], p2) : (y[e] + p2) * 0.25f;
+            }
+            mine = (l31 & 3) == g;
+          }
+          if (mine) {
+            uint2 o;
+            o.x = f2bf2(y[0], y[1]);
+            o.y = f2bf2(y[2], y[3]);
+            *(uint2*)(s_patch + srow * SPB + c * 2) = o;
+          }
+        }
+    }
+    __syncthreads();
+    for (int idx = tid; idx < ROWS * CG; idx += NTH) {
+      const int lr = idx / CG, cg = idx - lr * CG;
+      const long long ob = s_rowoff[lr];
+      if (ob < 0) continue;
+      *(u32x4_t*)((bf16_t*)a.out + ob + cg * CE) = *(const u32x4_t*)(s_patch + lr * SPB + cg * 16);
+    }
+    li += wgs;
+    if (li >= mlen) break;
+    __syncthreads();                                               // the staging becomes the next tile's patch
+  }
+}
+
+static int launch_pair(const ConvArgs& a, int dtype, hipStream_t st) {
+  // the host checks every shape the kernel's LDS layout and indexing assume
+  if (dtype != DT_BF16 || !a.pair || a.pair_C < 1 || a.pair_C > 4 || a.C != PR_C || a.K != PR_C || a.R != 3 || a.S != 3 || a.stride != 1 ||
+      a.pad != 1 || !a.kchunk || a.Kred_pad != 9 * PR_C || !a.dw_w || !a.dw_scale || !a.dw_shift || !a.vec_out || a.out_f32 || a.has_res ||
+      a.ksplit >= 1 || a.th < 1 || a.tw < 1 || a.th * a.tw > V2_BM || a.tw + 2 > PR_PW || (a.th + 2) * PR_PW > V2_PPMAX ||
+      (a.th + 4) * (a.tw + 4) > PR_INMAX || a.tiles_x != (a.W + a.tw - 1) / a.tw ||
+      (long long)a.tiles_y * a.th < (long long)a.N * (a.H + 2) || a.tiles_m != a.tiles_y * a.tiles_x || a.tiles_n != 1 ||
+      (long long)a.N * (a.H + 2) + a.th + 4 >= (1ll << 31) || a.OH != a.H || a.OW != a.W ||
+      (a.mode == M_ZIGZAG && (((a.th | a.tw | a.H | a.W) & 1) || (a.pool != POOL_MAX && a.pool != POOL_AVG) || 2 * a.PH != a.H || 2 * a.PW != a.W)) ||
+      (a.mode == M_FLAT && a.pool != POOL_NONE) || (a.mode != M_FLAT && a.mode != M_ZIGZAG))
+    return (int)hipErrorInvalidValue;
+  static bool raised = false;
+  if (!raised) {
+    hipError_t e = hipFuncSetAttribute((const void*)conv_pair_kernel<M_FLAT>, hipFuncAttributeMaxDynamicSharedMemorySize, PR_LDS);
+    if (e == hipSuccess) e = hipFuncSetAttribute((const void*)conv_pair_kernel<M_ZIGZAG>, hipFuncAttributeMaxDynamicSharedMemorySize, PR_LDS);
+    if (e != hipSuccess) return (int)e;
+    raised = true;
+  }
+  if (a.mode == M_FLAT) hipLaunchKernelGGL((conv_pair_kernel<M_FLAT>), dim3(a.grid), dim3(V2_NT), PR_LDS, st, a);
+  else hipLaunchKernelGGL((conv_pair_kernel<M_ZIGZAG>), dim3(a.grid), dim3(V2_NT), PR_LDS, st, a);
+  return (int)hipGetLastError();
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -1561,6 +1900,10 @@ int launch_conv(const ConvArgs& a, int dtype, int cfg, int scalar_loader, void* 
   if (a.grid < 1 || a.tiles_m < 1 || a.tiles_n < 1) return (int)hipErrorInvalidValue;
   if (cfg < kHaloCfg && a.xcd_m != 1 && a.xcd_m != 2 && a.xcd_m != 4 && a.xcd_m != 8) return (int)hipErrorInvalidValue;
   if (a.ksplit >= 1 && (a.mode != M_FLAT || !a.part || a.steps_per_split < 1 || (a.dw_w && a.dw_panel <= 0) || cfg == kHaloCfg)) return (int)hipErrorInvalidValue;
+  if (cfg == kPairCfg || a.pair) {
+    if (cfg != kPairCfg || scalar_loader) return (int)hipErrorInvalidValue;
+    return launch_pair(a, dtype, st);
+  }
   if (a.dw_w) {
     if (scalar_loader) return (int)hipErrorInvalidValue;
     return dtype == DT_BF16 ? launch_conv_dwpro_t<bf16_t>(a, cfg, st) : launch_conv_dwpro_t<float>(a, cfg, st);
@@ -1575,6 +1918,7 @@ int launch_conv(const ConvArgs& a, int dtype, int cfg, int scalar_loader, void* 
 
 size_t conv_lds_bytes(int cfg, int /*mode*/) {
   if (cfg == kHaloCfg) return v2_lds_total(128);
+  if (cfg == kPairCfg) return PR_LDS;
   if (cfg == kStemCfg) return 40 * 1024;   // static: staging slices (at most 4 x 32 x 272 bytes) + tables
   const TileCfg& c = kTileCfgs[cfg];
   const size_t main_b = (size_t)2 * (c.bm + c.bn) * LDS_ROW;
