@@ -594,6 +594,10 @@ constexpr int V2_NT = 64 * V2_NW;
 // (s + 1) % 3 is already visible during step s and the first fragments of step s + 1 are fetched before the barrier
 // that ends step s: the MFMAs of a step start right after the barrier instead of after an LDS round trip.
 constexpr int V2_WST = 3;
+// how many k-groups ahead of the MFMAs the fragments are fetched from LDS
+constexpr int V2_FD = 1;
+// 1: the global loads and LDS writes of a step are spread between its MFMAs; 0: loads before, writes behind them
+constexpr int V2_SPREAD = 1;
 constexpr int V2_ABYTES = V2_PPMAX * LDS_ROW;
 __host__ __device__ constexpr int v2_lds(int bn) { return 2 * V2_ABYTES + V2_WST * bn * LDS_ROW; }   // operand buffers
 __host__ __device__ constexpr int v2_lds_total(int bn) { return v2_lds(bn) + 2 * bn * 4 + V2_BM * 12; }  // + scale / shift of the tile, + the row tables
@@ -634,11 +638,17 @@ __global__ __launch_bounds__(V2_NT) void conv3x3_kernel(const ConvArgs a) {
   constexpr int NP = SPLIT_STG ? 1 : v2_passes(ROWS, SPB), RPP = ROWS / NP;
   static_assert(MODE == M_FLAT || MODE == M_ZIGZAG, "row enumerations of the halo kernel");
   static_assert(A_IT % 2 == 0 && B_IT >= 1 && NTH % CG == 0, "loader shapes");
+  static_assert((A_IT - 1) * NTH <= V2_PPMAX * CPR && A_IT >= 4, "only the last chunk of a thread may lie beyond the patch buffer");
 
   extern __shared__ __align__(16) unsigned char smem[];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wave_m = wave / WAVES_N, wave_n = wave % WAVES_N;
   const int l31 = lane & 31, lhalf = lane >> 5;
+  // Which GEMM row (pixel) of a 32-row block this lane holds.  `ds_read_b128` serves a half-wavefront in two passes of 16
+  // lanes, lanes {0-7, 24-31} and {8-15, 16-23} (measured: 245 B/clk/CU when the 16 lanes of each pass read LDS rows that
+  // differ mod 16 at the 144-byte pitch, 127 otherwise), so the two 16-pixel blocks of the enumerations below, whose
+  // pixels have 16 different residues each, are dealt to those lane sets: lanes 8-15 and 24-31 trade places.
+  const int lp = (l31 & 7) | (((0x78 >> (2 * ((l31 >> 3) & 3))) & 3) << 3);
 
   constexpr bool PLIN = PWID == 0;
   static_assert(!PLIN || MODE == M_FLAT, "the patch-linear form exists for the pixel-major enumeration");
@@ -686,7 +696,7 @@ __global__ __launch_bounds__(V2_NT) void conv3x3_kernel(const ConvArgs a) {
   };
 
   // ---- which pixel of the tile a GEMM row is ---------------------------------------------------------------
-  // A ds_read_b128 serves 16 lanes per pass and is conflict-free when their LDS rows differ mod 16 (row pitch 144 B).
+  // A ds_read_b128 pass of 16 lanes is conflict-free when their LDS rows differ mod 16 (row pitch 144 B).
   // A pixel (ty, tx) sits in patch row ty * PWID + tx = 2 * ty + tx (mod 16), so the rows of a tile are enumerated in
   // blocks whose 16 pixels have 16 different residues: 8 rows x 2 columns for the pixel-major enumeration, 4
   // vertically adjacent 2x2 windows for the zig-zag one (a window covers 4 consecutive residues).  Rows left over
@@ -730,7 +740,7 @@ __global__ __launch_bounds__(V2_NT) void conv3x3_kernel(const ConvArgs a) {
   int abase[2], bbase[TN];
 #pragma unroll
   for (int i = 0; i < 2; ++i) {
-    const int m = wave_m * 64 + i * 32 + l31;
+    const int m = wave_m * 64 + i * 32 + lp;
     int ty, tx;
     if (MODE == M_FLAT) flat_px(m, ty, tx);
     else {
@@ -758,9 +768,19 @@ __global__ __launch_bounds__(V2_NT) void conv3x3_kernel(const ConvArgs a) {
     const u32x4_t z = {0u, 0u, 0u, 0u};
 #pragma unroll
     for (int it = 0; it < A_HALF; ++it) {
-      const int idx = tid + (half * A_HALF + it) * NTH;
-      if ((half * A_HALF + it + 1) * NTH > V2_PPMAX * CPR && idx >= V2_PPMAX * CPR) continue;   // beyond the buffer
-      *(u32x4_t*)(sa + (idx / CPR) * LDS_ROW + (idx % CPR) * 16) = ((aok >> (half * A_HALF + it)) & 1u) ? pa[it] : z;
+      const int g = half * A_HALF + it;
+      int idx = tid + g * NTH;
+      u32x4_t v = ((aok >> g) & 1u) ? pa[it] : z;
+      if ((g + 1) * NTH > V2_PPMAX * CPR) {
+        // the last chunks of some threads lie beyond the buffer: those threads write their previous chunk once more
+        // (same address, same value) instead of branching around the store
+        const bool in = idx < V2_PPMAX * CPR;
+        const u32x4_t vp = ((aok >> (g - 1)) & 1u) ? pa[it - 1] : z;
+        idx = in ? idx : idx - NTH;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[e] = in ? v[e] : vp[e];
+      }
+      *(u32x4_t*)(sa + (idx / CPR) * LDS_ROW + (idx % CPR) * 16) = v;
     }
   };
   auto load_w = [&](int step, u32x4_t* rb) {
@@ -775,23 +795,24 @@ __global__ __launch_bounds__(V2_NT) void conv3x3_kernel(const ConvArgs a) {
       *(u32x4_t*)(sb + (idx / CPR) * LDS_ROW + (idx % CPR) * 16) = rb[it];
     }
   };
-  // one tap of one channel chunk: 4 k-groups, fragments of k-group g+1 are fetched before the MFMAs of g; the fragments
-  // of k-group 0 were fetched during the previous step, and the last k-group fetches those of the next step (`nsa`, `nsb`:
-  // its patch position and weight stage, both published at least one barrier ago)
-  u32x4_t fa[2][2], fb[2][TN];
-  static_assert(KG % 2 == 0, "the fragment slots alternate per k-group and must line up across steps");
+  // one tap of one channel chunk: 4 k-groups, fragments of k-group g + V2_FD are fetched before the MFMAs of g; the
+  // fragments of the first k-groups were fetched during the previous step, and the last k-groups fetch those of the next
+  // step (`nsa`, `nsb`: its patch position and weight stage, both published at least one barrier ago)
+  u32x4_t fa[V2_FD + 1][2], fb[V2_FD + 1][TN];
+  static_assert((9 * KG) % (V2_FD + 1) == 0, "the fragment slots rotate per k-group and must line up across chunks");
   auto fetch = [&](int slot, const unsigned char* sa, const unsigned char* sb, int kg) __attribute__((always_inline)) {
 #pragma unroll
     for (int i = 0; i < 2; ++i) fa[slot][i] = *(const u32x4_t*)(sa + abase[i] + kg * 32);
 #pragma unroll
     for (int j = 0; j < TN; ++j) fb[slot][j] = *(const u32x4_t*)(sb + bbase[j] + kg * 32);
   };
-  auto compute = [&](const unsigned char* sa, const unsigned char* sb, const unsigned char* nsa, const unsigned char* nsb) {
+  // `tap` is a constant of the unrolled tap loop: the slot of k-group g of tap t is (t * KG + g) % (V2_FD + 1)
+  auto compute = [&](int tap, const unsigned char* sa, const unsigned char* sb, const unsigned char* nsa, const unsigned char* nsb) {
 #pragma unroll
     for (int kg = 0; kg < KG; ++kg) {
-      const int cur = kg & 1, nxt = cur ^ 1;
-      if (kg + 1 < KG) fetch(nxt, sa, sb, kg + 1);
-      else fetch(nxt, nsa, nsb, 0);
+      const int cur = (tap * KG + kg) % (V2_FD + 1), nxt = (tap * KG + kg + V2_FD) % (V2_FD + 1);
+      if (kg + V2_FD < KG) fetch(nxt, sa, sb, kg + V2_FD);
+      else fetch(nxt, nsa, nsb, kg + V2_FD - KG);
 #pragma unroll
       for (int i = 0; i < 2; ++i)
 #pragma unroll
@@ -809,13 +830,37 @@ __global__ __launch_bounds__(V2_NT) void conv3x3_kernel(const ConvArgs a) {
         }
     }
   };
-  // The schedule wanted for one tap (0x100 = LDS read, 0x008 = MFMA): the fragments of the following k-group are in
-  // flight while the MFMAs of a k-group issue.  Without the directives the scheduler serialises read -> wait -> MFMA.
-  auto tap_schedule = [&]() {
+  // The schedule wanted for one tap (0x100 = LDS read, 0x200 = LDS write, 0x020 = global load, 0x008 = MFMA): the
+  // fragments of the following k-group are in flight while the MFMAs of a k-group issue; the global loads of the step
+  // are spread between the first MFMAs and the LDS writes that publish a later step between the last ones, so that no
+  // wavefront spends a stretch of the step issuing memory instructions with its MFMA pipe idle (an MFMA occupies the
+  // pipe for 32 cycles and the wavefront is free to issue other instructions meanwhile).  Without the directives the
+  // scheduler serialises read -> wait -> MFMA.
+  auto tap_schedule = [&](bool patch_loads, bool patch_writes) {
+    constexpr int NM = (sizeof(T) == 2 ? 2 : 8) * TN;              // MFMAs per k-group
+    static_assert(NM >= 2, "the memory instructions go behind the first two MFMAs of a k-group");
 #pragma unroll
     for (int kg = 0; kg < KG; ++kg) {
       __builtin_amdgcn_sched_group_barrier(0x100, 2 + TN, 0);
-      __builtin_amdgcn_sched_group_barrier(0x008, (sizeof(T) == 2 ? 2 : 8) * TN, 0);
+      if (V2_SPREAD && kg == 0) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        if (patch_loads) __builtin_amdgcn_sched_group_barrier(0x020, (B_IT + A_HALF + 1) / 2, 0);
+        else __builtin_amdgcn_sched_group_barrier(0x020, (B_IT + 1) / 2, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        if (patch_loads) __builtin_amdgcn_sched_group_barrier(0x020, (B_IT + A_HALF) / 2, 0);
+        else if (B_IT / 2 > 0) __builtin_amdgcn_sched_group_barrier(0x020, B_IT / 2, 0);
+        if (NM > 2) __builtin_amdgcn_sched_group_barrier(0x008, NM - 2, 0);
+      } else if (V2_SPREAD && kg == KG - 1) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        if (patch_writes) __builtin_amdgcn_sched_group_barrier(0x200, (B_IT + A_HALF + 1) / 2, 0);
+        else __builtin_amdgcn_sched_group_barrier(0x200, (B_IT + 1) / 2, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        if (patch_writes) __builtin_amdgcn_sched_group_barrier(0x200, (B_IT + A_HALF) / 2, 0);
+        else if (B_IT / 2 > 0) __builtin_amdgcn_sched_group_barrier(0x200, B_IT / 2, 0);
+        if (NM > 2) __builtin_amdgcn_sched_group_barrier(0x008, NM - 2, 0);
+      } else {
+        __builtin_amdgcn_sched_group_barrier(0x008, NM, 0);
+      }
     }
   };
   // Nine statically unrolled taps of channel chunk cc.  PAR = parity of the chunk in the workgroup's whole chunk
@@ -842,15 +887,15 @@ __global__ __launch_bounds__(V2_NT) void conv3x3_kernel(const ConvArgs a) {
       }
       if (tap == 0) load_patch(cnext, 0);                          // next chunk's patch: half 0 in flight over taps 0-3,
       if (tap == 4) load_patch(cnext, 1);                          // half 1 over taps 4-7
-      __builtin_amdgcn_sched_barrier(0);                           // keep the prefetch loads ahead of the MFMA block
+      if (!V2_SPREAD) __builtin_amdgcn_sched_barrier(0);           // keep the prefetch loads ahead of the MFMA block
       const int tapoff = ((tap / 3) * PW_ + tap % 3) * LDS_ROW, ntapoff = (((tap + 1) / 3) * PW_ + (tap + 1) % 3) * LDS_ROW;
-      compute(smem + PAR * V2_ABYTES + tapoff, sw + (tap % 3) * BBYTES,
+      compute(tap, smem + PAR * V2_ABYTES + tapoff, sw + (tap % 3) * BBYTES,
               tap < 8 ? smem + PAR * V2_ABYTES + ntapoff : smem + (PAR ^ 1) * V2_ABYTES, sw + ((tap + 1) % 3) * BBYTES);
-      tap_schedule();
-      __builtin_amdgcn_sched_barrier(0);
       store_w((tap + 2) % 3, sp == 0 ? rb1 : rb0);                 // publish step + 2 (loaded during the previous step)
       if (tap == 3) store_patch(PAR ^ 1, 0);
       if (tap == 7) store_patch(PAR ^ 1, 1);                       // (complete one barrier before tap 8 fetches from it)
+      tap_schedule(tap == 0 || tap == 4, tap == 3 || tap == 7);
+      __builtin_amdgcn_sched_barrier(0);
       __syncthreads();
     }
   };
@@ -868,7 +913,8 @@ __global__ __launch_bounds__(V2_NT) void conv3x3_kernel(const ConvArgs a) {
   store_patch(0, 1);
   load_w(2, rb1);
   __syncthreads();
-  fetch(0, smem, smem + 2 * V2_ABYTES, 0);
+#pragma unroll
+  for (int g = 0; g < V2_FD; ++g) fetch(g, smem, smem + 2 * V2_ABYTES, g);
 
 #pragma unroll
   for (int i = 0; i < 2; ++i)
@@ -894,7 +940,7 @@ __global__ __launch_bounds__(V2_NT) void conv3x3_kernel(const ConvArgs a) {
     if (MODE == M_FLAT && a.has_res) {
 #pragma unroll
       for (int i = 0; i < 2; ++i) {
-        const int m = wave_m * 64 + i * 32 + l31;
+        const int m = wave_m * 64 + i * 32 + lp;
         int ty, tx;
         flat_px(m, ty, tx);
         const int qq = q0 + ty, n = qq / Hp, oh = qq - n * Hp, ow = x0 + tx;
@@ -930,7 +976,7 @@ __global__ __launch_bounds__(V2_NT) void conv3x3_kernel(const ConvArgs a) {
       constexpr bool RES = decltype(res_c)::value, PMAX = decltype(max_c)::value;
 #pragma unroll
       for (int i = 0; i < 2; ++i) {
-        const int m = wave_m * 64 + i * 32 + l31;
+        const int m = wave_m * 64 + i * 32 + lp;
         const int srow = (MODE == M_FLAT ? m : (m >> 2)) - pass * RPP;
 #pragma unroll
         for (int j = 0; j < TN; ++j)
@@ -1095,6 +1141,7 @@ static int launch_conv3x3_t(const ConvArgs& a, hipStream_t st) {
 // epilogue of the halo kernel (scale / shift / ReLU, zig-zag pooling over lane quads, staging, 16-byte stores).  The
 // fp32 input block of the next tile is fetched during P2.
 // ---------------------------------------------------------------------------------------------
+constexpr int PR_NW = 8, PR_NT = 64 * PR_NW;          // 8 wavefronts of 32 pixels x 64 channels
 constexpr int PR_PW = kHaloPitchNarrow;       // patch row pitch in pixels
 constexpr int PR_C = kPairChannels;           // channels of the intermediate and of the output
 constexpr int PR_K1 = kPairRed;               // reduction slots of the first convolution (3 MFMA steps of 16)
@@ -1110,8 +1157,8 @@ constexpr int PR_OFF_ROWOFF = PR_OFF_ROWPOS + V2_BM * 4;
 constexpr int PR_LDS = PR_OFF_ROWOFF + V2_BM * 8;
 
 template <int MODE>
-__global__ __launch_bounds__(V2_NT) void conv_pair_kernel(const ConvArgs a) {
-  constexpr int BM = V2_BM, NTH = V2_NT, CE = 8;
+__global__ __launch_bounds__(PR_NT) void conv_pair_kernel(const ConvArgs a) {
+  constexpr int BM = V2_BM, NTH = PR_NT, CE = 8;
   constexpr int ROWS = MODE == M_FLAT ? BM : BM / 4;               // staged rows: pixels, or pooled windows
   constexpr int SPB = PR_C * 2 + 16;                               // staging row pitch in bytes
   constexpr int CG = PR_C / CE;
@@ -1130,6 +1177,7 @@ __global__ __launch_bounds__(V2_NT) void conv_pair_kernel(const ConvArgs a) {
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l31 = lane & 31, lhalf = lane >> 5;
+  const int lp = (l31 & 7) | (((0x78 >> (2 * ((l31 >> 3) & 3))) & 3) << 3);   // pixel of a 32-row block held by this lane (as in the halo kernel)
   const int Hp = a.H + 2, IW = a.tw + 4, npix = (a.th + 4) * IW, PP = (a.th + 2) * PR_PW;
   const int nin = a.pair_C * npix;
 
@@ -1232,7 +1280,7 @@ __global__ __launch_bounds__(V2_NT) void conv_pair_kernel(const ConvArgs a) {
   // P2: this lane's pixel and weight rows
   int abase;
   {
-    const int m = wave * 32 + l31;
+    const int m = wave * 32 + lp;
     int ty, tx;
     if (MODE == M_FLAT) flat_px(m, ty, tx);
     else {
@@ -1265,7 +1313,7 @@ __global__ __launch_bounds__(V2_NT) void conv_pair_kernel(const ConvArgs a) {
     }
 
     // ---- P1: the intermediate at the patch positions p = 32 * unit + lane % 32 ---------------------------------
-    for (int u = wave; u < nunits; u += V2_NW) {
+    for (int u = wave; u < nunits; u += PR_NW) {
       const int p = u * 32 + l31, pcl = p < PP ? p : PP - 1;
       const int pr = pcl / PR_PW, pc = pcl - pr * PR_PW;
       const unsigned char* xb = s_xin + (pr * IW + pc) * 8;
@@ -1344,7 +1392,7 @@ __global__ __launch_bounds__(V2_NT) void conv_pair_kernel(const ConvArgs a) {
 
     // ---- epilogue: scale / shift / ReLU, pooling over the lane quad, staging in the output type -----------------
     {
-      const int m = wave * 32 + l31;
+      const int m = wave * 32 + lp;
       const int srow = MODE == M_FLAT ? m : (m >> 2);
       const bool pmax = a.pool == POOL_MAX;
 #pragma unroll
@@ -1407,8 +1455,8 @@ static int launch_pair(const ConvArgs& a, int dtype, hipStream_t st) {
     if (e != hipSuccess) return (int)e;
     raised = true;
   }
-  if (a.mode == M_FLAT) hipLaunchKernelGGL((conv_pair_kernel<M_FLAT>), dim3(a.grid), dim3(V2_NT), PR_LDS, st, a);
-  else hipLaunchKernelGGL((conv_pair_kernel<M_ZIGZAG>), dim3(a.grid), dim3(V2_NT), PR_LDS, st, a);
+  if (a.mode == M_FLAT) hipLaunchKernelGGL((conv_pair_kernel<M_FLAT>), dim3(a.grid), dim3(PR_NT), PR_LDS, st, a);
+  else hipLaunchKernelGGL((conv_pair_kernel<M_ZIGZAG>), dim3(a.grid), dim3(PR_NT), PR_LDS, st, a);
   return (int)hipGetLastError();
 }
 
