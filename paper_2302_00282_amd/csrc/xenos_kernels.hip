@@ -1146,7 +1146,7 @@ constexpr int PR_PW = kHaloPitchNarrow;       // patch row pitch in pixels
 constexpr int PR_C = kPairChannels;           // channels of the intermediate and of the output
 constexpr int PR_K1 = kPairRed;               // reduction slots of the first convolution (3 MFMA steps of 16)
 constexpr int PR_W1ROW = PR_K1 * 2 + 16;      // LDS row pitch of its weights: an odd number of 16-byte slots
-constexpr int PR_INMAX = 640;                 // pixels of the staged input block, (TH+4) x (TW+4)
+constexpr int PR_INMAX = kPairInMax;          // positions of the staged input block, (TH+4) x (TW+4)
 constexpr int PR_W2BYTES = 9 * PR_C * LDS_ROW;
 constexpr int PR_OFF_PATCH = PR_W2BYTES;
 constexpr int PR_OFF_W1 = PR_OFF_PATCH + V2_ABYTES;
@@ -1442,7 +1442,7 @@ static int launch_pair(const ConvArgs& a, int dtype, hipStream_t st) {
   if (dtype != DT_BF16 || !a.pair || a.pair_C < 1 || a.pair_C > 4 || a.C != PR_C || a.K != PR_C || a.R != 3 || a.S != 3 || a.stride != 1 ||
       a.pad != 1 || !a.kchunk || a.Kred_pad != 9 * PR_C || !a.dw_w || !a.dw_scale || !a.dw_shift || !a.vec_out || a.out_f32 || a.has_res ||
       a.ksplit >= 1 || a.th < 1 || a.tw < 1 || a.th * a.tw > V2_BM || a.tw + 2 > PR_PW || (a.th + 2) * PR_PW > V2_PPMAX ||
-      (a.th + 4) * (a.tw + 4) > PR_INMAX || a.tiles_x != (a.W + a.tw - 1) / a.tw ||
+      (a.th + 4) * (a.tw + 4) + 20 > PR_INMAX || a.tiles_x != (a.W + a.tw - 1) / a.tw ||
       (long long)a.tiles_y * a.th < (long long)a.N * (a.H + 2) || a.tiles_m != a.tiles_y * a.tiles_x || a.tiles_n != 1 ||
       (long long)a.N * (a.H + 2) + a.th + 4 >= (1ll << 31) || a.OH != a.H || a.OW != a.W ||
       (a.mode == M_ZIGZAG && (((a.th | a.tw | a.H | a.W) & 1) || (a.pool != POOL_MAX && a.pool != POOL_AVG) || 2 * a.PH != a.H || 2 * a.PW != a.W)) ||

@@ -330,6 +330,53 @@ struct Planner {
     long long bytes_w = 0;
   } dwpro;
 
+  // A first-layer 3x3 chain waiting to be linked into the 3x3 convolution that consumes it (link level 3; Table 1,
+  // ConvX -> ConvY): its output tensor is then never materialised
+  struct PairPro {
+    bool active = false;
+    std::vector<int> ops;
+    long long w_off = -1, scale_off = -1, shift_off = -1;
+    int relu = 0;
+    double flops = 0;
+    long long bytes_w = 0;
+  } pairpro;
+
+  // Can the dense convolution node `nx` take a linked first-layer producer?  It must be a 3x3 / stride 1 / pad 1
+  // convolution kPairChannels -> kPairChannels whose own chain ends in nothing or a 2x2 / stride 2 pooling of an even map,
+  // takes no shortcut, and writes a plain internal tensor (the walk mirrors the link pass of plan_node).
+  bool pair_consumer_ok(int nx) {
+    const Node& nd = nodes[nx];
+    if (nd.kind != XENOS_OP_CONV || node_step[nx] >= 0) return false;
+    const xenos_op_desc& d = desc(nd);
+    const Shape is = tshape[nd.in[0]];
+    if (d.groups != 1 || d.kh != 3 || d.kw != 3 || d.stride_h != 1 || d.stride_w != 1 || d.pad_h != 1 || d.pad_w != 1 ||
+        d.out_c != kPairChannels || is.c != kPairChannels) return false;
+    int cur = nx + 1, stage = 0;
+    for (;;) {
+      if (cur == out_tid || placed.count(cur)) return false;
+      const int c = single_consumer(cur);
+      if (c < 0) return true;
+      const Node& nn_ = nodes[c];
+      if ((nn_.kind == XENOS_OP_BIAS || nn_.kind == XENOS_OP_BN) && stage == 0) {
+      } else if (nn_.kind == XENOS_OP_ADD && stage <= 1) {
+        return false;
+      } else if (nn_.kind == XENOS_OP_RELU && stage <= 2) {
+        stage = 3;
+      } else if (nn_.kind == XENOS_OP_GLOBAL_AVGPOOL && stage <= 3) {
+        return false;
+      } else if ((nn_.kind == XENOS_OP_MAXPOOL || nn_.kind == XENOS_OP_AVGPOOL) && stage <= 3) {
+        const xenos_op_desc& pd = desc(nn_);
+        const Shape ps = tshape[c + 1];
+        if (pd.kh != 2 || pd.kw != 2 || pd.stride_h != 2 || pd.stride_w != 2 || pd.pad_h != 0 || pd.pad_w != 0 || is.h % 2 || is.w % 2 ||
+            2 * ps.h != is.h || 2 * ps.w != is.w) return false;
+        return c + 1 != out_tid && !placed.count(c + 1);
+      } else {
+        return true;
+      }
+      cur = c + 1;
+    }
+  }
+
   void touch(int view, int step) {
     Buffer& b = p.bufs[p.views[view].buf];
     b.first = std::min(b.first, step);
@@ -404,6 +451,31 @@ struct Planner {
       c.grid = p.opts.split ? std::max(1, std::min((c.tiles_m + 3) / 4, 4 * num_cu)) : 1;   // 4 resident workgroups per unit
       st.cfg = kStemCfg;
       st.lds = conv_lds_bytes(kStemCfg, c.mode);
+      return XENOS_OK;
+    }
+    if (c.pair) {
+      // two linked 3x3 convolutions: a TH x TW block of output pixels (at most 256) x all 64 channels per workgroup, tiles
+      // laid over the images stacked with their padding rows; the kernel stages a (TH+4) x (TW+4) block of the graph
+      // input and a (TH+2) x 18 patch of the intermediate tensor, and keeps both weight tensors resident
+      if (!c.vec_out || c.has_res || (c.mode != M_FLAT && c.mode != M_ZIGZAG) || (c.mode == M_ZIGZAG && (c.H % 2 || c.W % 2)) ||
+          conv_lds_bytes(kPairCfg, c.mode) > p.hw.lds_bytes_per_cu)
+        return fail(XENOS_EUNSUPPORTED, "%s: chain cannot take a linked first-layer producer", st.name.c_str());
+      const int step = c.mode == M_ZIGZAG ? 2 : 1;
+      const long long rows = (long long)c.N * (c.H + 2);
+      double best_fill = 0;
+      for (int tw = step; tw + 2 <= kHaloPitchNarrow && tw < c.W + step; tw += step) {
+        int th = kHaloRows / tw / step * step;
+        while (th >= step && ((th + 2) * kHaloPitchNarrow > kHaloPatchMax || (th + 4) * (tw + 4) + 20 > kPairInMax)) th -= step;
+        if (th < step) continue;
+        const long long ty = (rows + th - 1) / th, tx = (c.W + tw - 1) / tw;
+        const double fill = (double)c.N * c.H * c.W / ((double)ty * tx * kHaloRows);
+        if (fill > best_fill + 1e-9) { best_fill = fill; c.th = th; c.tw = tw; c.tiles_y = (int)ty; c.tiles_x = (int)tx; }
+      }
+      if (best_fill <= 0) return fail(XENOS_EUNSUPPORTED, "%s: no tile of the pair kernel fits", st.name.c_str());
+      c.tiles_m = c.tiles_y * c.tiles_x; c.tiles_n = 1; c.ntiles = c.tiles_m; c.xcd_m = 8;
+      c.grid = p.opts.split ? 8 * std::max(1, std::min(num_cu / 8, (c.tiles_m + 7) / 8)) : 1;
+      st.cfg = kPairCfg;
+      st.lds = conv_lds_bytes(kPairCfg, c.mode);
       return XENOS_OK;
     }
     // halo-staged 3x3 kernel: a TH x TW block of output pixels (256 GEMM rows) x 128 channels per workgroup,
@@ -755,6 +827,30 @@ struct Planner {
       }
       for (int a : absorbed) st.ops.push_back(nodes[a].src);
 
+      // link level 3, ConvX -> ConvY: a 3x3 first layer whose only consumer is a 3x3 convolution of the same 64 channels
+      // is produced tile by tile (halo recomputed) inside that convolution's kernel and never written to memory
+      if (stem && link >= 3 && p.dt == DT_BF16 && p.opts.tile == 0 && K == kPairChannels && is.c <= 4 && d.kh == 3 && d.kw == 3 &&
+          d.stride_h == 1 && d.stride_w == 1 && d.pad_h == 1 && d.pad_w == 1 && pool_node < 0 && !placed.count(cur) && cur != out_tid) {
+        const View& gv = p.views[tview[0]];
+        const int nx = single_consumer(cur);
+        if (gv.f32 && gv.sP == 1 && nx >= 0 && pair_consumer_ok(nx)) {
+          std::vector<uint16_t> w1((size_t)kPairChannels * kPairRed, 0);
+          for (int k = 0; k < K; ++k)
+            for (int c = 0; c < is.c; ++c)
+              for (int t = 0; t < 9; ++t) w1[(size_t)k * kPairRed + t * 4 + c] = f2bf_host(go.weight[((size_t)k * is.c + c) * 9 + t]);
+          pairpro = PairPro{};
+          pairpro.active = true; pairpro.ops = st.ops; pairpro.relu = relu;
+          pairpro.w_off = (long long)wpush(w1.data(), w1.size() * 2);
+          push_affine(af, kPairChannels, &pairpro.scale_off, &pairpro.shift_off);
+          pairpro.flops = 2.0 * is.n * is.h * is.w * (double)K * 9 * is.c;
+          pairpro.bytes_w = (long long)K * 9 * is.c * 2;
+          const int mark = (int)p.steps.size();
+          node_step[i] = mark;
+          for (int a : absorbed) node_step[a] = mark;
+          return plan_node(nx);
+        }
+      }
+
       if (dw) {
         int vin;
         xenos_status rc = need_internal_input(nd.in[0], st.name.c_str(), &vin);
@@ -821,14 +917,18 @@ struct Planner {
         const bool from_dw = dwpro.active;
         const DwPro pro = dwpro;
         dwpro.active = false;
+        const bool from_pair = pairpro.active;
+        const PairPro ppro = pairpro;
+        pairpro.active = false;
         if (!from_dw && nd.in[0] == 0 && in_lazy) {
           st.stem = stem;
           if (!st.stem && !in_gather) import_input();
         }
-        const int vin = from_dw ? pro.v_in : tview[nd.in[0]];
+        const int vin = from_dw ? pro.v_in : from_pair ? tview[0] : tview[nd.in[0]];
         if (vin < 0) return fail(XENOS_EINVAL, "%s: input not materialised", st.name.c_str());
         st.v_in = vin;
         if (from_dw) st.ops.insert(st.ops.begin(), pro.ops.begin(), pro.ops.end());
+        if (from_pair) st.ops.insert(st.ops.begin(), ppro.ops.begin(), ppro.ops.end());
         const View& iv = p.views[vin];
         ConvArgs& a = st.conv;
         a.N = is.n; a.C = std::max(is.c, iv.cphys); a.H = is.h; a.W = is.w;   // padding channels multiply zero weights
@@ -843,6 +943,14 @@ struct Planner {
           a.dw_k = pro.k; a.dw_stride = pro.stride; a.dw_pad = pro.pad; a.dw_H = pro.H; a.dw_W = pro.W; a.dw_relu = pro.relu;
           a.dw_sN = iv.sN; a.dw_sP = iv.sP;
           a.dw_w = (const void*)1;           // marks the chain for the split planner; patched at launch
+        }
+        if (from_pair) {
+          // `in` is the caller's tensor (fp32, unit stride along W); C, H, W describe the intermediate tensor
+          st.scalar = 0;
+          a.C = is.c;
+          a.pair = 1; a.pair_C = p.in.c; a.pair_sN = iv.sN; a.pair_sC = iv.sK; a.pair_sH = iv.sP * is.w;
+          st.dw_w_off = ppro.w_off; st.dw_scale_off = ppro.scale_off; st.dw_shift_off = ppro.shift_off;
+          a.dw_relu = ppro.relu;
         }
         a.relu = relu; a.has_res = has_res;
         if (has_res) {
@@ -911,8 +1019,9 @@ struct Planner {
         xenos_status rc = split_conv(st);
         if (rc != XENOS_OK) return rc;
         if (a.dw_panel > 0) st.lds = dwpw_lds_bytes(a.dw_panel, p.esz);
-        st.flops = 2.0 * a.N * a.OH * a.OW * (double)K * a.R * a.S * is.c + (from_dw ? pro.flops : 0.0);
+        st.flops = 2.0 * a.N * a.OH * a.OW * (double)K * a.R * a.S * is.c + (from_dw ? pro.flops : 0.0) + (from_pair ? ppro.flops : 0.0);
         if (from_dw) st.bytes_w += pro.bytes_w;
+        if (from_pair) st.bytes_w += ppro.bytes_w;
         st.bytes_in = view_bytes(st.v_in); st.bytes_out = view_bytes(st.v_out);
         if (has_res) st.bytes_res = view_bytes(st.v_in2);
 
@@ -1125,11 +1234,12 @@ void write_plan_json(xenos_plan& p) {
       const ConvArgs& c = s.conv;
       const TileCfg halo_tc{kHaloRows, c.halo_bn, 64, c.halo_bn / 2};
       const TileCfg stem_tc{32, c.K, 32, c.K};
-      const TileCfg& tc = s.cfg == kHaloCfg ? halo_tc : s.cfg == kStemCfg ? stem_tc : kTileCfgs[s.cfg];
+      const TileCfg pair_tc{kHaloRows, kPairChannels, 32, kPairChannels};
+      const TileCfg& tc = s.cfg == kHaloCfg ? halo_tc : s.cfg == kStemCfg ? stem_tc : s.cfg == kPairCfg ? pair_tc : kTileCfgs[s.cfg];
       snprintf(buf, sizeof buf, ",\"mode\":\"%s\",\"loader\":\"%s\",\"N\":%d,\"C\":%d,\"H\":%d,\"W\":%d,\"K\":%d,\"R\":%d,\"S\":%d,\"stride\":%d,"
                "\"pad\":%d,\"OH\":%d,\"OW\":%d,\"PH\":%d,\"PW\":%d,\"pool\":%d,\"relu\":%d,\"res\":%d,\"bm\":%d,\"bn\":%d,\"tiles_m\":%d,"
                "\"tiles_n\":%d,\"grid\":%d,\"lds\":%zu,\"pph\":%d,\"ppw\":%d,\"patch_h\":%d,\"patch_w\":%d,\"out_c_off\":%lld,\"out_sP\":%lld,\"halo\":%d,\"th\":%d,\"tw\":%d,\"dw_linked\":%d,\"ksplit\":%d,\"candidates\":%d,\"tuned\":%d,\"plin\":%d",
-               kModeNames[c.mode], s.stem ? "stem" : s.scalar ? "scalar" : "vector", c.N, c.C, c.H, c.W, c.K, c.R, c.S, c.stride, c.pad, c.OH, c.OW,
+               kModeNames[c.mode], s.stem ? "stem" : c.pair ? "pair" : s.scalar ? "scalar" : "vector", c.N, c.C, c.H, c.W, c.K, c.R, c.S, c.stride, c.pad, c.OH, c.OW,
                c.PH, c.PW, c.pool, c.relu, c.has_res, tc.bm, tc.bn, c.tiles_m, c.tiles_n, c.grid, s.lds, c.pph, c.ppw, c.patch_h,
                c.patch_w, p.views[s.v_out].off, c.out_sP, s.cfg == kHaloCfg ? 1 : 0, c.th, c.tw, s.dw_w_off >= 0 ? 1 : 0, c.ksplit > 1 ? c.ksplit : 1, (int)s.cands.size(), s.tuned, s.cfg == kHaloCfg ? c.halo_plin : 0);
       j += buf;

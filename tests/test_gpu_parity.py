@@ -232,6 +232,35 @@ def test_first_layer_reads_the_graph_input_in_place(k, ksz, stride, pad, hw, c, 
     assert np.array_equal(y, ys)                              # one workgroup walking all blocks: same bits
 
 
+@pytest.mark.parametrize("h,w,n,c,pool,bn", [(16, 16, 2, 3, 0, True), (37, 21, 3, 3, 0, True), (40, 28, 3, 3, 1, False), (18, 50, 2, 1, 2, True),
+                                             (64, 64, 5, 4, 1, True), (9, 7, 1, 3, 0, False)])
+def test_first_two_3x3_convolutions_linked_on_chip(h, w, n, c, pool, bn):
+    # link level 3, ConvX -> ConvY of Table 1: conv3x3 (<= 4 -> 64) -> conv3x3 (64 -> 64) [-> 2x2 pooling] runs as ONE chain;
+    # the 64-channel intermediate lives only in LDS (halo recomputed per tile, rounded to bf16 as a stored tensor would be).
+    # Ragged sizes give clipped tiles and tiles spanning two images; a third chain consumes the result.
+    b = wg.builder("pair", (n, c, h, w), 23, nonzero_bias=True)
+    t = b.cbr(0, 64, 3, 1, 1, name="c0", bn=bn)
+    t = b.cbr(t, 64, 3, 1, 1, name="c1", bn=bn)
+    if pool == 1:
+        t = b.maxpool(t, 2, 2)
+    elif pool == 2:
+        t = b.avgpool(t, 2, 2)
+    t = b.cbr(t, 24, 1, name="c2")
+    g = b.finish(t)
+    ref = xo.forward(g)
+    y, info = check(g, ref, compute=1, link=3)
+    assert info["n_chains"] == 2 and info["chains"][0]["loader"] == "pair"
+    assert len(info["chains"][0]["ops"]) >= 4
+    y2, i2 = check(g, ref, compute=1, link=2)                 # the same chains as two passes
+    assert i2["n_chains"] == 3 and i2["chains"][0]["loader"] == "stem"
+    # both round the intermediate to bf16 at the same point, so they differ by summation order only
+    assert rel_err(y, y2.astype(np.float64)) <= 4e-3
+    ys, _ = run_gpu(g, compute=1, link=3, split=0)
+    assert np.array_equal(y, ys)                              # one workgroup walking all tiles: same bits
+    y3, i3 = check(g, ref, compute=0, link=3)                 # fp32 path: the pair kernel is bf16 only, chains stay separate
+    assert all(ch.get("loader") != "pair" for ch in i3["chains"])
+
+
 def _bf16_rne(x):
     """fp32 -> bf16 -> fp32 with round-to-nearest-even, in integer arithmetic."""
     u = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32).astype(np.uint64)
