@@ -45,7 +45,8 @@ static const int kStemRed = 32 * kStemPasses;
 // 4 input channels -> kPairChannels -> kPairChannels; the first convolution reduces over kPairRed slots = tap * 4 + channel.
 static const int kPairCfg = 6;
 static const int kPairChannels = 64, kPairRed = 48;
-static const int kPairInMax = 640;   // positions of the staged block of the graph input, (TH+4) x (TW+4) plus slack for the pitch columns
+static const int kPairRows = 128, kPairPatchMax = 180;   // output pixels and patch positions ((TH+2) x 18) of a tile
+static const int kPairInMax = 256;   // positions of the staged block of the graph input, (TH+4) x (TW+4) plus slack for the pitch columns
 static const int kHaloRows = 256, kHaloCols = 128, kHaloPatchMax = 360;
 // the staged patch has one of two fixed row pitches (pixels): tiles up to 16 or up to 32 pixels wide
 static const int kHaloPitchNarrow = 18, kHaloPitchWide = 34;

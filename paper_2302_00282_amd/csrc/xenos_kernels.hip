@@ -1128,54 +1128,60 @@ static int launch_conv3x3_t(const ConvArgs& a, hipStream_t st) {
 // ---------------------------------------------------------------------------------------------
 // Two linked 3x3 / stride 1 / pad 1 convolution chains (Table 1, ConvX -> ConvY; Section 4.1): the first layer
 // (at most 4 input channels, read from the caller's fp32 NCHW tensor) -> 64 channels -> 64 channels [-> 2x2 pooling].
-// The intermediate tensor is never written to memory: a workgroup owns a TH x TW block of output pixels, computes the
-// (TH+2) x (TW+2) block of the intermediate that those pixels read (halo recomputed per tile, the paper's halo
-// replication) straight into the LDS patch of the second convolution, and runs the second convolution out of it.
-// Both weight tensors stay resident in LDS for all tiles of the (persistent) workgroup, so the nine taps of the second
-// convolution run without a barrier.  bf16 operands, fp32 accumulation; the intermediate is rounded to bf16 exactly as
-// it would be when stored between two separate chains.
+// The intermediate tensor is never written to memory: a workgroup owns a TH x TW block of output pixels (at most 128),
+// computes the (TH+2) x (TW+2) block of the intermediate that those pixels read (halo recomputed per tile, the paper's
+// halo replication) straight into the LDS patch of the second convolution, and runs the second convolution out of it.
+// bf16 operands, fp32 accumulation; the intermediate is rounded to bf16 exactly as it would be when stored between two
+// separate chains.
+//
+// Both weight tensors stay in REGISTERS for all tiles of the (persistent) workgroup: a wavefront owns 32 of the 64 output
+// channels (4 wavefronts = 2 pixel halves x 2 channel halves), so its B operands of the second convolution are 36
+// fragments (9 taps x 4 k-groups) and of the first 3.  The second convolution therefore reads only pixel fragments from
+// LDS (one read per MFMA, no barrier between its nine taps), and LDS holds little more than the patch: two workgroups
+// share a compute unit, and while one runs the MFMA-bound second convolution the other runs the VALU-bound phases
+// (first convolution's epilogue, the chain's epilogue, the import of the next input block).
 //
 // Phases per tile (barriers between them): P1 first convolution as a transposed MFMA GEMM over the patch positions
 // (reduction slot = tap * 4 + channel, 48 slots), scale / shift / ReLU, positions outside the image forced to zero (they
-// are the padding of the second convolution); P2 second convolution, 32 pixels x 64 channels per wavefront; then the
+// are the padding of the second convolution); P2 second convolution, 64 pixels x 32 channels per wavefront; then the
 // epilogue of the halo kernel (scale / shift / ReLU, zig-zag pooling over lane quads, staging, 16-byte stores).  The
 // fp32 input block of the next tile is fetched during P2.
 // ---------------------------------------------------------------------------------------------
-constexpr int PR_NW = 8, PR_NT = 64 * PR_NW;          // 8 wavefronts of 32 pixels x 64 channels
+constexpr int PR_NW = 4, PR_NT = 64 * PR_NW;
+constexpr int PR_DEPHASE = 1;                 // start delay of the second workgroup of a unit, in sleeps of 127 x 64 cycles
+constexpr int PR_BM = kPairRows;              // GEMM rows (output pixels) of a tile
+constexpr int PR_PPMAX = kPairPatchMax;       // patch positions, (TH+2) x 18
 constexpr int PR_PW = kHaloPitchNarrow;       // patch row pitch in pixels
 constexpr int PR_C = kPairChannels;           // channels of the intermediate and of the output
 constexpr int PR_K1 = kPairRed;               // reduction slots of the first convolution (3 MFMA steps of 16)
-constexpr int PR_W1ROW = PR_K1 * 2 + 16;      // LDS row pitch of its weights: an odd number of 16-byte slots
 constexpr int PR_INMAX = kPairInMax;          // positions of the staged input block, (TH+4) x (TW+4)
-constexpr int PR_W2BYTES = 9 * PR_C * LDS_ROW;
-constexpr int PR_OFF_PATCH = PR_W2BYTES;
-constexpr int PR_OFF_W1 = PR_OFF_PATCH + V2_ABYTES;
-constexpr int PR_OFF_XIN = PR_OFF_W1 + PR_C * PR_W1ROW;
+constexpr int PR_PBYTES = PR_PPMAX * LDS_ROW;
+constexpr int PR_OFF_XIN = PR_PBYTES;
 constexpr int PR_OFF_AFF = PR_OFF_XIN + PR_INMAX * 8;
 constexpr int PR_OFF_ROWPOS = PR_OFF_AFF + 4 * PR_C * 4;
-constexpr int PR_OFF_ROWOFF = PR_OFF_ROWPOS + V2_BM * 4;
-constexpr int PR_LDS = PR_OFF_ROWOFF + V2_BM * 8;
+constexpr int PR_OFF_ROWOFF = PR_OFF_ROWPOS + PR_BM * 4;
+constexpr int PR_LDS = PR_OFF_ROWOFF + PR_BM * 8;
 
-template <int MODE>
-__global__ __launch_bounds__(PR_NT) void conv_pair_kernel(const ConvArgs a) {
-  constexpr int BM = V2_BM, NTH = PR_NT, CE = 8;
+template <int MODE, bool PMAX>
+__global__ __launch_bounds__(PR_NT, 2) void conv_pair_kernel(const ConvArgs a) {
+  constexpr int BM = PR_BM, NTH = PR_NT, CE = 8;
   constexpr int ROWS = MODE == M_FLAT ? BM : BM / 4;               // staged rows: pixels, or pooled windows
   constexpr int SPB = PR_C * 2 + 16;                               // staging row pitch in bytes
   constexpr int CG = PR_C / CE;
   constexpr int NI = (PR_INMAX * 4 + NTH - 1) / NTH;               // input elements per thread
   static_assert(MODE == M_FLAT || MODE == M_ZIGZAG, "row enumerations of the pair kernel");
-  static_assert(BM * SPB <= V2_ABYTES, "the finished tile is staged in the patch buffer");
+  static_assert(BM * SPB <= PR_PBYTES, "the finished tile is staged in the patch buffer");
+  static_assert(PR_OFF_ROWOFF % 8 == 0 && PR_OFF_AFF % 16 == 0, "alignment of the tables");
 
   extern __shared__ __align__(16) unsigned char smem[];
-  unsigned char* s_w2 = smem;
-  unsigned char* s_patch = smem + PR_OFF_PATCH;
-  unsigned char* s_w1 = smem + PR_OFF_W1;
+  unsigned char* s_patch = smem;
   unsigned char* s_xin = smem + PR_OFF_XIN;
   float* s_aff = (float*)(smem + PR_OFF_AFF);                     // scale1, shift1, scale2, shift2
   int* s_rowpos = (int*)(smem + PR_OFF_ROWPOS);
   long long* s_rowoff = (long long*)(smem + PR_OFF_ROWOFF);
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wave_n = wave & 1, wave_m = wave >> 1;
   const int l31 = lane & 31, lhalf = lane >> 5;
   const int lp = (l31 & 7) | (((0x78 >> (2 * ((l31 >> 3) & 3))) & 3) << 3);   // pixel of a 32-row block held by this lane (as in the halo kernel)
   const int Hp = a.H + 2, IW = a.tw + 4, npix = (a.th + 4) * IW, PP = (a.th + 2) * PR_PW;
@@ -1187,33 +1193,73 @@ __global__ __launch_bounds__(PR_NT) void conv_pair_kernel(const ConvArgs a) {
   const int m0 = xcd * a.tiles_m / nx, mlen = (xcd + 1) * a.tiles_m / nx - m0;
   int li = blockIdx.x / nx;
   if (li >= mlen) return;                                          // uniform per workgroup
+  // Two workgroups share a compute unit and would walk their tiles in lockstep (same start, same phase lengths), both in
+  // the MFMA-bound phase or both in the VALU-bound ones.  The later half of an XCD's workgroups (the second residents
+  // of its units) therefore starts about half a tile late, once.
+  if (PR_DEPHASE && 2 * li >= wgs && wgs > 1) {
+#pragma unroll 1
+    for (int i = 0; i < PR_DEPHASE; ++i) __builtin_amdgcn_s_sleep(127);
+  }
 
-  // ---- the fp32 input block of a tile: element e = (channel, block row, block column) ------------------------
+  // ---- resident weights: this wavefront's 32 channels -------------------------------------------------------------
+  u32x4_t w2[36], w1[3];
+  {
+    const unsigned char* wp = (const unsigned char*)a.w + ((long long)(wave_n * 32 + l31) * a.Kred_pad + lhalf * 8) * 2;
+#pragma unroll
+    for (int s = 0; s < 36; ++s) w2[s] = *(const u32x4_t*)(wp + ((s >> 2) * PR_C + (s & 3) * 16) * 2);
+    const unsigned char* w1p = (const unsigned char*)a.dw_w + ((wave_n * 32 + l31) * PR_K1 + lhalf * 8) * 2;
+#pragma unroll
+    for (int j = 0; j < 3; ++j) w1[j] = *(const u32x4_t*)(w1p + j * 32);
+  }
+
+  // ---- the fp32 input block of a tile: element e = (channel, block row, block column), the same for every tile ------
+  // Per element only what does not depend on the tile is kept: its offset from the block's first element in the caller's
+  // tensor and its position in the block.  A tile's rows lie in at most two images of the stack (TH + 4 <= H + 2, checked
+  // by the host); rows of the second image are `xdelta` elements further than the stacked row count says.
+  int xe[NI], xg[NI];                                              // channel << 24 | block row << 12 | block column (-1 = none); offset
+#pragma unroll
+  for (int it = 0; it < NI; ++it) {
+    const int e = tid + it * NTH;
+    const int c = e / npix, rem = e - c * npix, ir = rem / IW, ic = rem - ir * IW;
+    xe[it] = e < nin ? (c << 24) | (ir << 12) | ic : -1;
+    xg[it] = (int)(c * a.pair_sC + ir * a.pair_sH + ic);
+  }
+  const int xdelta = (int)(a.pair_sN - (long long)Hp * a.pair_sH);
   float xr[NI];
+  // image and input row of a stacked row `sr` of a tile whose first row lies in image n0
+  auto split_row = [&](int sr, int n0, int& n, int& ih) __attribute__((always_inline)) {
+    const int rel = sr - n0 * Hp;
+    const bool next = rel >= Hp;
+    n = n0 + (next ? 1 : 0);
+    ih = rel - (next ? Hp : 0) - 1;
+  };
   auto load_xin = [&](int l) __attribute__((always_inline)) {
     const int tile_m = m0 + l, tyi = tile_m / a.tiles_x;
     const int q0 = tyi * a.th, x0 = (tile_m - tyi * a.tiles_x) * a.tw;
+    const int n0 = q0 > 0 ? (q0 - 1) / Hp : 0;
+    const int rel0 = q0 - 1 - n0 * Hp;                             // block row 0 relative to image n0's first stacked row (-1 at the very top)
+    // element offset of block position (0, 0) of channel 0 (may point before the tensor: only valid elements are read)
+    const long long base = (long long)n0 * a.pair_sN + (long long)(rel0 - 1) * a.pair_sH + (x0 - 2);
+    const float* src = (const float*)a.in + base;
 #pragma unroll
     for (int it = 0; it < NI; ++it) {
-      const int e = tid + it * NTH;
-      float v = 0.f;
-      if (e < nin) {
-        const int c = e / npix, rem = e - c * npix, ir = rem / IW, ic = rem - ir * IW;
-        const int sr = q0 - 1 + ir;                                // stacked row: image n = sr / (H+2), input row sr % (H+2) - 1
-        const int n = sr >= 0 ? sr / Hp : 0, ih = sr - n * Hp - 1, iw = x0 - 2 + ic;
-        if (sr >= 0 && n < a.N && (unsigned)ih < (unsigned)a.H && (unsigned)iw < (unsigned)a.W)
-          v = ((const float*)a.in)[(long long)n * a.pair_sN + (long long)c * a.pair_sC + (long long)ih * a.pair_sH + iw];
-      }
-      xr[it] = v;
+      const int ir = (xe[it] >> 12) & 0xfff, ic = xe[it] & 0xfff;
+      const int rel = rel0 + ir;
+      const bool next = rel >= Hp;
+      const int ih = rel - (next ? Hp : 0) - 1, n = n0 + (next ? 1 : 0), iw = x0 - 2 + ic;
+      const bool ok = xe[it] >= 0 && n < a.N && (unsigned)ih < (unsigned)a.H && (unsigned)iw < (unsigned)a.W;
+      // (elements outside the images read the tensor's first element instead, so the load needs no branch)
+      const float* ptr = ok ? src + (xg[it] + (next ? xdelta : 0)) : (const float*)a.in;
+      const float v = *ptr;
+      xr[it] = ok ? v : 0.f;
     }
   };
   auto store_xin = [&]() __attribute__((always_inline)) {
 #pragma unroll
     for (int it = 0; it < NI; ++it) {
-      const int e = tid + it * NTH;
-      if (e < nin) {
-        const int c = e / npix, rem = e - c * npix;
-        *(uint16_t*)(s_xin + rem * 8 + c * 2) = f2bf(xr[it]);
+      if (xe[it] >= 0) {
+        const int c = xe[it] >> 24, ir = (xe[it] >> 12) & 0xfff, ic = xe[it] & 0xfff;
+        *(uint16_t*)(s_xin + (ir * IW + ic) * 8 + c * 2) = f2bf(xr[it]);
       }
     }
   };
@@ -1240,19 +1286,11 @@ __global__ __launch_bounds__(PR_NT) void conv_pair_kernel(const ConvArgs a) {
     }
   };
 
-  // ---- set-up: resident weights, scale / shift, row table, zeroed input block ---------------------------------
+  // ---- set-up: scale / shift, row table, zeroed input block ---------------------------------------------------
   for (int i = tid; i < PR_INMAX * 2; i += NTH) ((uint32_t*)s_xin)[i] = 0u;   // channel slots beyond pair_C stay zero
-  for (int idx = tid; idx < 9 * PR_C * CPR; idx += NTH) {
-    const int c8 = idx % CPR, row = idx / CPR, tap = row / PR_C, k = row - tap * PR_C;
-    *(u32x4_t*)(s_w2 + row * LDS_ROW + c8 * 16) =
-        *(const u32x4_t*)((const unsigned char*)a.w + ((long long)k * a.Kred_pad + tap * PR_C + c8 * 8) * 2);
-  }
-  for (int idx = tid; idx < PR_C * (PR_K1 / 8); idx += NTH) {
-    const int c6 = idx % (PR_K1 / 8), k = idx / (PR_K1 / 8);
-    *(u32x4_t*)(s_w1 + k * PR_W1ROW + c6 * 16) = *(const u32x4_t*)((const unsigned char*)a.dw_w + (k * PR_K1 + c6 * 8) * 2);
-  }
-  if (tid < 4 * PR_C) {
-    const int w = tid / PR_C, c = tid - w * PR_C;
+  {
+    const int w = tid / PR_C, c = tid - w * PR_C;                  // NTH == 4 * PR_C
+    static_assert(NTH == 4 * PR_C, "one thread per folded scale / shift value");
     s_aff[tid] = w == 0 ? a.dw_scale[c] : w == 1 ? a.dw_shift[c] : w == 2 ? a.scale[c] : a.shift[c];
   }
   for (int q = tid; q < ROWS; q += NTH) {
@@ -1268,19 +1306,15 @@ __global__ __launch_bounds__(PR_NT) void conv_pair_kernel(const ConvArgs a) {
   // ---- per-lane constants -------------------------------------------------------------------------------------
   // P1: the two taps (4 slots each) this half-wavefront feeds to MFMA step j are taps 4j + 2*lhalf and the next one;
   // taps 9..11 do not exist (zero operand)
-  int toff[3][2];
+  auto tap_off = [&](int j, int h) __attribute__((always_inline)) -> int {
+    const int t = 4 * j + 2 * lhalf + h;
+    return t < 9 ? ((t / 3) * IW + t % 3) * 8 : -1;
+  };
+  // P2: this lane's two pixels
+  int abase[2];
 #pragma unroll
-  for (int j = 0; j < 3; ++j)
-#pragma unroll
-    for (int h = 0; h < 2; ++h) {
-      const int t = 4 * j + 2 * lhalf + h;
-      toff[j][h] = t < 9 ? ((t / 3) * IW + t % 3) * 8 : -1;
-    }
-  const int w1b = l31 * PR_W1ROW + lhalf * 16;
-  // P2: this lane's pixel and weight rows
-  int abase;
-  {
-    const int m = wave * 32 + lp;
+  for (int i = 0; i < 2; ++i) {
+    const int m = wave_m * 64 + i * 32 + lp;
     int ty, tx;
     if (MODE == M_FLAT) flat_px(m, ty, tx);
     else {
@@ -1288,9 +1322,8 @@ __global__ __launch_bounds__(PR_NT) void conv_pair_kernel(const ConvArgs a) {
       zz_win(m >> 2, wy, wx);
       ty = 2 * wy + ((m >> 1) & 1); tx = 2 * wx + (m & 1);
     }
-    abase = ((ty < a.th && tx < a.tw) ? ty * PR_PW + tx : 0) * LDS_ROW + lhalf * 16;
+    abase[i] = ((ty < a.th && tx < a.tw) ? ty * PR_PW + tx : 0) * LDS_ROW + lhalf * 16;
   }
-  const int bbase = l31 * LDS_ROW + lhalf * 16;
   const int nunits = (PP + 31) / 32;
   const float lo1 = a.dw_relu ? 0.f : -3.4028235e38f, lo2 = a.relu ? 0.f : -3.4028235e38f;
   __syncthreads();
@@ -1298,6 +1331,11 @@ __global__ __launch_bounds__(PR_NT) void conv_pair_kernel(const ConvArgs a) {
   for (;;) {
     const int tile_m = m0 + li, tyi = tile_m / a.tiles_x;
     const int q0 = tyi * a.th, x0 = (tile_m - tyi * a.tiles_x) * a.tw;
+    const int n0 = q0 / Hp;                                        // image of the tile's first output row
+    // the next tile's input block is fetched now (first-touch reads from device memory: their latency is covered by
+    // both convolutions of this tile) and written to LDS after the second convolution
+    const bool more = li + wgs < mlen;
+    if (more) load_xin(li + wgs);
 
     // where each staged row goes in the output (element offset of its channel 0; -1 = not an output of this tile)
     for (int q = tid; q < ROWS; q += NTH) {
@@ -1305,76 +1343,71 @@ __global__ __launch_bounds__(PR_NT) void conv_pair_kernel(const ConvArgs a) {
       long long ob = -1;
       if (pos >= 0) {
         const int y = pos >> 16, x = pos & 0xffff;
-        const int qq = q0 + (MODE == M_FLAT ? y : 2 * y), n = qq / Hp, oh = qq - n * Hp, ow = x0 + (MODE == M_FLAT ? x : 2 * x);
+        int n, oh;
+        split_row(q0 + (MODE == M_FLAT ? y : 2 * y), n0, n, oh);
+        oh += 1;                                                   // (split_row returns the input row of a patch position)
+        const int ow = x0 + (MODE == M_FLAT ? x : 2 * x);
         if (n < a.N && oh < a.H && ow < a.W)
           ob = (long long)n * a.out_sN + (MODE == M_FLAT ? (long long)(oh * a.OW + ow) : (long long)((oh >> 1) * a.PW + (ow >> 1))) * a.out_sP;
       }
       s_rowoff[q] = ob;
     }
 
-    // ---- P1: the intermediate at the patch positions p = 32 * unit + lane % 32 ---------------------------------
-    for (int u = wave; u < nunits; u += PR_NW) {
+    // ---- P1: this wavefront's 32 channels of the intermediate at the patch positions p = 32 * unit + lane % 32 -------
+    for (int u = wave_m; u < nunits; u += PR_NW / 2) {
       const int p = u * 32 + l31, pcl = p < PP ? p : PP - 1;
       const int pr = pcl / PR_PW, pc = pcl - pr * PR_PW;
       const unsigned char* xb = s_xin + (pr * IW + pc) * 8;
-      f32x16_t c1[2];
+      f32x16_t c1;
 #pragma unroll
-      for (int j2 = 0; j2 < 2; ++j2)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) c1[j2][e] = 0.f;
+      for (int e = 0; e < 16; ++e) c1[e] = 0.f;
 #pragma unroll
       for (int j = 0; j < 3; ++j) {
-        uint2 t0 = *(const uint2*)(xb + (toff[j][0] >= 0 ? toff[j][0] : 0));
-        uint2 t1 = *(const uint2*)(xb + (toff[j][1] >= 0 ? toff[j][1] : 0));
-        if (toff[j][0] < 0) t0 = uint2{0u, 0u};
-        if (toff[j][1] < 0) t1 = uint2{0u, 0u};
+        const int o0 = tap_off(j, 0), o1 = tap_off(j, 1);
+        uint2 t0 = *(const uint2*)(xb + (o0 >= 0 ? o0 : 0));
+        uint2 t1 = *(const uint2*)(xb + (o1 >= 0 ? o1 : 0));
+        if (o0 < 0) t0 = uint2{0u, 0u};
+        if (o1 < 0) t1 = uint2{0u, 0u};
         const u32x4_t fa = {t0.x, t0.y, t1.x, t1.y};
-#pragma unroll
-        for (int j2 = 0; j2 < 2; ++j2) {
-          const u32x4_t fb = *(const u32x4_t*)(s_w1 + w1b + j2 * 32 * PR_W1ROW + j * 32);
-          c1[j2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, fb), __builtin_bit_cast(bf16x8_t, fa), c1[j2], 0, 0, 0);
-        }
+        c1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, w1[j]), __builtin_bit_cast(bf16x8_t, fa), c1, 0, 0, 0);
       }
-      const int P = q0 + pr, n = P / Hp, ih = P - n * Hp - 1, iw = x0 - 1 + pc;
+      int n, ih;
+      split_row(q0 + pr, n0, n, ih);
+      const int iw = x0 - 1 + pc;
       const bool inside = n < a.N && (unsigned)ih < (unsigned)a.H && (unsigned)iw < (unsigned)a.W;
       if (p < PP) {
 #pragma unroll
-        for (int j2 = 0; j2 < 2; ++j2)
+        for (int g = 0; g < 4; ++g) {
+          const int c = wave_n * 32 + g * 8 + lhalf * 4;
+          const f32x4_t sc = *(const f32x4_t*)(s_aff + c), sh = *(const f32x4_t*)(s_aff + PR_C + c);
+          float y[4];
 #pragma unroll
-          for (int g = 0; g < 4; ++g) {
-            const int c = j2 * 32 + g * 8 + lhalf * 4;
-            const f32x4_t sc = *(const f32x4_t*)(s_aff + c), sh = *(const f32x4_t*)(s_aff + PR_C + c);
-            float y[4];
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-              y[e] = fmaxf(c1[j2][4 * g + e] * sc[e] + sh[e], lo1);
-              y[e] = inside ? y[e] : 0.f;                          // padding of the second convolution
-            }
-            uint2 o;
-            o.x = f2bf2(y[0], y[1]);
-            o.y = f2bf2(y[2], y[3]);
-            *(uint2*)(s_patch + p * LDS_ROW + c * 2) = o;
+          for (int e = 0; e < 4; ++e) {
+            y[e] = fmaxf(c1[4 * g + e] * sc[e] + sh[e], lo1);
+            y[e] = inside ? y[e] : 0.f;                            // padding of the second convolution
           }
+          uint2 o;
+          o.x = f2bf2(y[0], y[1]);
+          o.y = f2bf2(y[2], y[3]);
+          *(uint2*)(s_patch + p * LDS_ROW + c * 2) = o;
+        }
       }
     }
     __syncthreads();
 
-    // ---- P2: the second convolution out of the patch; the next tile's input block is on its way meanwhile --------
-    const bool more = li + wgs < mlen;
-    if (more) load_xin(li + wgs);
+    // ---- P2: the second convolution out of the patch ------------------------------------------------------------
     f32x16_t acc[2];
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
+    for (int i = 0; i < 2; ++i)
 #pragma unroll
-      for (int e = 0; e < 16; ++e) acc[j][e] = 0.f;
+      for (int e = 0; e < 16; ++e) acc[i][e] = 0.f;
     {
-      constexpr int NS = 36, DEPTH = 2;                            // (tap, k-group) steps; fragments fetched DEPTH steps ahead
-      u32x4_t fa[DEPTH + 1], fb[DEPTH + 1][2];
+      constexpr int NS = 36, DEPTH = 1;                            // (tap, k-group) steps; fragments fetched DEPTH steps ahead
+      u32x4_t fa[DEPTH + 1][2];
       auto fetch = [&](int s, int slot) __attribute__((always_inline)) {
         const int tap = s >> 2, kg = s & 3;
-        fa[slot] = *(const u32x4_t*)(s_patch + abase + ((tap / 3) * PR_PW + tap % 3) * LDS_ROW + kg * 32);
 #pragma unroll
-        for (int j = 0; j < 2; ++j) fb[slot][j] = *(const u32x4_t*)(s_w2 + (tap * PR_C + j * 32) * LDS_ROW + bbase + kg * 32);
+        for (int i = 0; i < 2; ++i) fa[slot][i] = *(const u32x4_t*)(s_patch + abase[i] + ((tap / 3) * PR_PW + tap % 3) * LDS_ROW + kg * 32);
       };
 #pragma unroll
       for (int s = 0; s < DEPTH; ++s) fetch(s, s);
@@ -1382,47 +1415,45 @@ __global__ __launch_bounds__(PR_NT) void conv_pair_kernel(const ConvArgs a) {
       for (int s = 0; s < NS; ++s) {
         if (s + DEPTH < NS) fetch(s + DEPTH, (s + DEPTH) % (DEPTH + 1));
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
-          acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, fb[s % (DEPTH + 1)][j]),
-                                                           __builtin_bit_cast(bf16x8_t, fa[s % (DEPTH + 1)]), acc[j], 0, 0, 0);
+        for (int i = 0; i < 2; ++i)
+          acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, w2[s]),
+                                                           __builtin_bit_cast(bf16x8_t, fa[s % (DEPTH + 1)][i]), acc[i], 0, 0, 0);
       }
     }
     if (more) store_xin();
     __syncthreads();                                               // the patch is free: it becomes the output staging
 
     // ---- epilogue: scale / shift / ReLU, pooling over the lane quad, staging in the output type -----------------
-    {
-      const int m = wave * 32 + lp;
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const int m = wave_m * 64 + i * 32 + lp;
       const int srow = MODE == M_FLAT ? m : (m >> 2);
-      const bool pmax = a.pool == POOL_MAX;
 #pragma unroll
-      for (int j = 0; j < 2; ++j)
+      for (int g = 0; g < 4; ++g) {
+        const int c = wave_n * 32 + g * 8 + lhalf * 4;
+        const f32x4_t sc = *(const f32x4_t*)(s_aff + 2 * PR_C + c), sh = *(const f32x4_t*)(s_aff + 3 * PR_C + c);
+        float y[4];
 #pragma unroll
-        for (int g = 0; g < 4; ++g) {
-          const int c = j * 32 + g * 8 + lhalf * 4;
-          const f32x4_t sc = *(const f32x4_t*)(s_aff + 2 * PR_C + c), sh = *(const f32x4_t*)(s_aff + 3 * PR_C + c);
-          float y[4];
+        for (int e = 0; e < 4; ++e) y[e] = fmaxf(acc[i][4 * g + e] * sc[e] + sh[e], lo2);
+        bool mine = true;
+        if (MODE == M_ZIGZAG) {
+          // the window's four pixels are lanes 4w .. 4w+3: butterfly over the quad, lane i keeps group g == i
 #pragma unroll
-          for (int e = 0; e < 4; ++e) y[e] = fmaxf(acc[j][4 * g + e] * sc[e] + sh[e], lo2);
-          bool mine = true;
-          if (MODE == M_ZIGZAG) {
-            // the window's four pixels are lanes 4w .. 4w+3: butterfly over the quad, lane i keeps group g == i
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-              const float p1 = quad_perm<0xB1>(y[e]);
-              y[e] = pmax ? fmaxf(y[e], p1) : y[e] + p1;
-              const float p2 = quad_perm<0x4E>(y[e]);
-              y[e] = pmax ? fmaxf(y[e], p2) : (y[e] + p2) * 0.25f;
-            }
-            mine = (l31 & 3) == g;
+          for (int e = 0; e < 4; ++e) {
+            const float p1 = quad_perm<0xB1>(y[e]);
+            y[e] = PMAX ? fmaxf(y[e], p1) : y[e] + p1;
+            const float p2 = quad_perm<0x4E>(y[e]);
+            y[e] = PMAX ? fmaxf(y[e], p2) : (y[e] + p2) * 0.25f;
           }
-          if (mine) {
-            uint2 o;
-            o.x = f2bf2(y[0], y[1]);
-            o.y = f2bf2(y[2], y[3]);
-            *(uint2*)(s_patch + srow * SPB + c * 2) = o;
-          }
+          mine = (l31 & 3) == g;
         }
+        if (mine) {
+          uint2 o;
+          o.x = f2bf2(y[0], y[1]);
+          o.y = f2bf2(y[2], y[3]);
+          *(uint2*)(s_patch + srow * SPB + c * 2) = o;
+        }
+      }
     }
     __syncthreads();
     for (int idx = tid; idx < ROWS * CG; idx += NTH) {
@@ -1441,22 +1472,17 @@ static int launch_pair(const ConvArgs& a, int dtype, hipStream_t st) {
   // the host checks every shape the kernel's LDS layout and indexing assume
   if (dtype != DT_BF16 || !a.pair || a.pair_C < 1 || a.pair_C > 4 || a.C != PR_C || a.K != PR_C || a.R != 3 || a.S != 3 || a.stride != 1 ||
       a.pad != 1 || !a.kchunk || a.Kred_pad != 9 * PR_C || !a.dw_w || !a.dw_scale || !a.dw_shift || !a.vec_out || a.out_f32 || a.has_res ||
-      a.ksplit >= 1 || a.th < 1 || a.tw < 1 || a.th * a.tw > V2_BM || a.tw + 2 > PR_PW || (a.th + 2) * PR_PW > V2_PPMAX ||
-      (a.th + 4) * (a.tw + 4) + 20 > PR_INMAX || a.tiles_x != (a.W + a.tw - 1) / a.tw ||
+      a.ksplit >= 1 || a.th < 1 || a.tw < 1 || a.th * a.tw > PR_BM || a.tw + 2 > PR_PW || (a.th + 2) * PR_PW > PR_PPMAX ||
+      (a.th + 4) * (a.tw + 4) > PR_INMAX || (a.th + 3) * (a.tw + 4) + 20 > PR_INMAX || a.th + 4 >= 4096 || a.tw + 4 >= 4096 || a.tiles_x != (a.W + a.tw - 1) / a.tw ||
       (long long)a.tiles_y * a.th < (long long)a.N * (a.H + 2) || a.tiles_m != a.tiles_y * a.tiles_x || a.tiles_n != 1 ||
-      (long long)a.N * (a.H + 2) + a.th + 4 >= (1ll << 31) || a.OH != a.H || a.OW != a.W ||
+      (long long)a.N * (a.H + 2) + a.th + 4 >= (1ll << 31) || a.OH != a.H || a.OW != a.W || a.th + 4 > a.H + 2 ||
+      (long long)a.N * a.pair_sN + (long long)4 * a.pair_sC >= (1ll << 31) || a.pair_sN < 0 || a.pair_sC < 0 || a.pair_sH < 0 ||
       (a.mode == M_ZIGZAG && (((a.th | a.tw | a.H | a.W) & 1) || (a.pool != POOL_MAX && a.pool != POOL_AVG) || 2 * a.PH != a.H || 2 * a.PW != a.W)) ||
       (a.mode == M_FLAT && a.pool != POOL_NONE) || (a.mode != M_FLAT && a.mode != M_ZIGZAG))
     return (int)hipErrorInvalidValue;
-  static bool raised = false;
-  if (!raised) {
-    hipError_t e = hipFuncSetAttribute((const void*)conv_pair_kernel<M_FLAT>, hipFuncAttributeMaxDynamicSharedMemorySize, PR_LDS);
-    if (e == hipSuccess) e = hipFuncSetAttribute((const void*)conv_pair_kernel<M_ZIGZAG>, hipFuncAttributeMaxDynamicSharedMemorySize, PR_LDS);
-    if (e != hipSuccess) return (int)e;
-    raised = true;
-  }
-  if (a.mode == M_FLAT) hipLaunchKernelGGL((conv_pair_kernel<M_FLAT>), dim3(a.grid), dim3(PR_NT), PR_LDS, st, a);
-  else hipLaunchKernelGGL((conv_pair_kernel<M_ZIGZAG>), dim3(a.grid), dim3(PR_NT), PR_LDS, st, a);
+  if (a.mode == M_FLAT) hipLaunchKernelGGL((conv_pair_kernel<M_FLAT, false>), dim3(a.grid), dim3(PR_NT), PR_LDS, st, a);
+  else if (a.pool == POOL_MAX) hipLaunchKernelGGL((conv_pair_kernel<M_ZIGZAG, true>), dim3(a.grid), dim3(PR_NT), PR_LDS, st, a);
+  else hipLaunchKernelGGL((conv_pair_kernel<M_ZIGZAG, false>), dim3(a.grid), dim3(PR_NT), PR_LDS, st, a);
   return (int)hipGetLastError();
 }
 

@@ -350,7 +350,7 @@ struct Planner {
     const xenos_op_desc& d = desc(nd);
     const Shape is = tshape[nd.in[0]];
     if (d.groups != 1 || d.kh != 3 || d.kw != 3 || d.stride_h != 1 || d.stride_w != 1 || d.pad_h != 1 || d.pad_w != 1 ||
-        d.out_c != kPairChannels || is.c != kPairChannels) return false;
+        d.out_c != kPairChannels || is.c != kPairChannels || is.h < 4) return false;
     int cur = nx + 1, stage = 0;
     for (;;) {
       if (cur == out_tid || placed.count(cur)) return false;
@@ -454,9 +454,9 @@ struct Planner {
       return XENOS_OK;
     }
     if (c.pair) {
-      // two linked 3x3 convolutions: a TH x TW block of output pixels (at most 256) x all 64 channels per workgroup, tiles
+      // two linked 3x3 convolutions: a TH x TW block of output pixels (at most 128) x all 64 channels per workgroup, tiles
       // laid over the images stacked with their padding rows; the kernel stages a (TH+4) x (TW+4) block of the graph
-      // input and a (TH+2) x 18 patch of the intermediate tensor, and keeps both weight tensors resident
+      // input and a (TH+2) x 18 patch of the intermediate tensor, and keeps both weight tensors in registers
       if (!c.vec_out || c.has_res || (c.mode != M_FLAT && c.mode != M_ZIGZAG) || (c.mode == M_ZIGZAG && (c.H % 2 || c.W % 2)) ||
           conv_lds_bytes(kPairCfg, c.mode) > p.hw.lds_bytes_per_cu)
         return fail(XENOS_EUNSUPPORTED, "%s: chain cannot take a linked first-layer producer", st.name.c_str());
@@ -464,16 +464,16 @@ struct Planner {
       const long long rows = (long long)c.N * (c.H + 2);
       double best_fill = 0;
       for (int tw = step; tw + 2 <= kHaloPitchNarrow && tw < c.W + step; tw += step) {
-        int th = kHaloRows / tw / step * step;
-        while (th >= step && ((th + 2) * kHaloPitchNarrow > kHaloPatchMax || (th + 4) * (tw + 4) + 20 > kPairInMax)) th -= step;
+        int th = std::min(kPairRows / tw, c.H - 2) / step * step;   // a tile's input rows lie in at most two images
+        while (th >= step && ((th + 2) * kHaloPitchNarrow > kPairPatchMax || (th + 4) * (tw + 4) > kPairInMax || (th + 3) * (tw + 4) + 20 > kPairInMax)) th -= step;
         if (th < step) continue;
         const long long ty = (rows + th - 1) / th, tx = (c.W + tw - 1) / tw;
-        const double fill = (double)c.N * c.H * c.W / ((double)ty * tx * kHaloRows);
+        const double fill = (double)c.N * c.H * c.W / ((double)ty * tx * kPairRows);
         if (fill > best_fill + 1e-9) { best_fill = fill; c.th = th; c.tw = tw; c.tiles_y = (int)ty; c.tiles_x = (int)tx; }
       }
       if (best_fill <= 0) return fail(XENOS_EUNSUPPORTED, "%s: no tile of the pair kernel fits", st.name.c_str());
       c.tiles_m = c.tiles_y * c.tiles_x; c.tiles_n = 1; c.ntiles = c.tiles_m; c.xcd_m = 8;
-      c.grid = p.opts.split ? 8 * std::max(1, std::min(num_cu / 8, (c.tiles_m + 7) / 8)) : 1;
+      c.grid = p.opts.split ? 8 * std::max(1, std::min(2 * num_cu / 8, (c.tiles_m + 7) / 8)) : 1;   // two workgroups per unit
       st.cfg = kPairCfg;
       st.lds = conv_lds_bytes(kPairCfg, c.mode);
       return XENOS_OK;
@@ -1234,7 +1234,7 @@ void write_plan_json(xenos_plan& p) {
       const ConvArgs& c = s.conv;
       const TileCfg halo_tc{kHaloRows, c.halo_bn, 64, c.halo_bn / 2};
       const TileCfg stem_tc{32, c.K, 32, c.K};
-      const TileCfg pair_tc{kHaloRows, kPairChannels, 32, kPairChannels};
+      const TileCfg pair_tc{kPairRows, kPairChannels, 64, kPairChannels / 2};
       const TileCfg& tc = s.cfg == kHaloCfg ? halo_tc : s.cfg == kStemCfg ? stem_tc : s.cfg == kPairCfg ? pair_tc : kTileCfgs[s.cfg];
       snprintf(buf, sizeof buf, ",\"mode\":\"%s\",\"loader\":\"%s\",\"N\":%d,\"C\":%d,\"H\":%d,\"W\":%d,\"K\":%d,\"R\":%d,\"S\":%d,\"stride\":%d,"
                "\"pad\":%d,\"OH\":%d,\"OW\":%d,\"PH\":%d,\"PW\":%d,\"pool\":%d,\"relu\":%d,\"res\":%d,\"bm\":%d,\"bn\":%d,\"tiles_m\":%d,"
