@@ -44,6 +44,11 @@ static const int kStemRed = 32 * kStemPasses;
 // Configuration index of the kernel that links the first two 3x3 convolutions (intermediate tensor kept in LDS): at most
 // 4 input channels -> kPairChannels -> kPairChannels; the first convolution reduces over kPairRed slots = tap * 4 + channel.
 static const int kPairCfg = 6;
+// Configuration index of the kernel that streams the weights of a fully connected chain with at most 32 rows (128 channels per
+// workgroup, reduction shared out over workgroups; always followed by the summing pass)
+static const int kFcCfg = 7;
+static const int kFcChannels = 128;
+static const int kFcWgPerCu = 1;    // workgroups per compute unit the reduction split of such a chain aims at
 static const int kPairChannels = 64, kPairRed = 48;
 static const int kPairRows = 128, kPairPatchMax = 180;   // output pixels and patch positions ((TH+2) x 18) of a tile
 static const int kPairInMax = 256;   // positions of the staged block of the graph input, (TH+4) x (TW+4) plus slack for the pitch columns

@@ -1490,6 +1490,82 @@ static int launch_pair(const ConvArgs& a, int dtype, hipStream_t st) {
 }
 
 // ---------------------------------------------------------------------------------------------
+// Fully connected chain with few rows (a batch of at most 32 images; Table 4, FullyConnected): out[m][k] = sum_i x[m][i] *
+// w[k][i].  Every weight is used once per image, so the chain is bound by streaming the weights from device memory and
+// what matters is how many bytes are in flight and that memory is read in long sequential runs: a wavefront owns 32
+// output channels and a share of the reduction, its weight fragments are packed in the order it loads them (every
+// load instruction reads 1 KB of consecutive memory, a share is one sequential stream) and go straight from memory
+// into the registers the MFMA reads them from, FC_DEPTH steps of 64 reduction elements ahead (16 KB in flight per
+// wavefront), with no LDS and no barrier anywhere; the activation fragments (a few MB, cache resident) travel the same way.  The operator split is output channels first, then the
+// reduction (Section 4.2.2: a C / R / S split needs an additional reduction): the shares are raw fp32 sums in
+// part[z][m][k], added in index order by the summing pass, which also applies the chain's epilogue.
+// bf16 operands, fp32 accumulation.  Rows m >= M read row 0 and are not stored.
+// ---------------------------------------------------------------------------------------------
+constexpr int FC_NW = 4, FC_NT = 64 * FC_NW, FC_BN = 32 * FC_NW, FC_DEPTH = 4;
+
+__global__ __launch_bounds__(FC_NT, 2) void fc_stream_kernel(const ConvArgs a) {
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int l31 = lane & 31, lhalf = lane >> 5;
+  const int tile_n = blockIdx.x % a.tiles_n, z = blockIdx.x / a.tiles_n;
+  const int nsteps_all = a.Kred_pad / 64;
+  const int s0 = z * a.steps_per_split;
+  const int ns = nsteps_all - s0 < a.steps_per_split ? nsteps_all - s0 : a.steps_per_split;
+  if (ns <= 0) return;
+  const int k0 = tile_n * FC_BN + wave * 32;                       // first output channel of this wavefront
+  // weights: [32-channel block][step][k-group][lane][8 elements], the order in which this wavefront loads them
+  const unsigned char* wp = (const unsigned char*)a.w + ((((long long)(k0 / 32) * nsteps_all + s0) * 4 * 64 + lane) * 16);
+  // activations: row m of the flattened input (reduction index = position in the NHWC tensor of an image)
+  const int m = l31 < a.M_total ? l31 : 0;
+  const unsigned char* xp = (const unsigned char*)a.in + (((long long)m * a.in_sN + (long long)s0 * 64 + lhalf * 8) * 2);
+
+  u32x4_t fw[FC_DEPTH][4], fx[FC_DEPTH][4];
+  auto fetch = [&](int slot, int step) __attribute__((always_inline)) {
+    const int sc = step < ns ? step : ns - 1;                      // beyond the share: re-read its last step (never used)
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      fw[slot][g] = *(const u32x4_t*)(wp + (sc * 4 + g) * 1024);
+      fx[slot][g] = *(const u32x4_t*)(xp + sc * 128 + g * 32);
+    }
+  };
+  f32x16_t acc;
+#pragma unroll
+  for (int e = 0; e < 16; ++e) acc[e] = 0.f;
+#pragma unroll
+  for (int d = 0; d < FC_DEPTH; ++d) fetch(d, d);
+  for (int s = 0; s < ns; s += FC_DEPTH) {
+#pragma unroll
+    for (int d = 0; d < FC_DEPTH; ++d) {
+      if (s + d < ns) {
+#pragma unroll
+        for (int g = 0; g < 4; ++g)
+          acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, fw[d][g]), __builtin_bit_cast(bf16x8_t, fx[d][g]), acc, 0, 0, 0);
+      }
+      fetch(d, s + d + FC_DEPTH);
+    }
+  }
+  // accumulator rows = channels, columns = images: this lane holds 4 groups of 4 consecutive channels of image l31
+  if (l31 < a.M_total) {
+    float* dst = a.part + ((long long)z * a.M_total + l31) * a.part_ld + k0;
+#pragma unroll
+    for (int g = 0; g < 4; ++g)
+      *(f32x4_t*)(dst + g * 8 + lhalf * 4) = f32x4_t{acc[4 * g], acc[4 * g + 1], acc[4 * g + 2], acc[4 * g + 3]};
+  }
+}
+
+static int launch_fc(const ConvArgs& a, int dtype, hipStream_t st) {
+  // the host checks what the kernel's indexing assumes
+  if (dtype != DT_BF16 || a.mode != M_FLAT || a.OH != 1 || a.OW != 1 || a.R != a.H || a.S != a.W || a.pad != 0 || a.M_total < 1 || a.M_total > 32 ||
+      a.M_total != a.N || a.kchunk || a.Kred != a.R * a.S * a.C || a.Kred_pad != a.Kred || a.Kred % 64 != 0 || a.in_f32 || a.dw_w || a.pair ||
+      (a.H * a.W > 1 && (a.in_sW != a.C || a.in_sH != (long long)a.W * a.C)) || a.in_sN < a.Kred || a.in_sN % 8 != 0 || ((uintptr_t)a.in & 15) != 0 ||
+      a.ksplit < 1 || a.steps_per_split < 1 || (long long)a.ksplit * a.steps_per_split < a.Kred_pad / 64 || !a.part ||
+      a.tiles_n != (a.K + FC_BN - 1) / FC_BN || a.part_ld < a.tiles_n * FC_BN || a.part_ld % 4 != 0 || ((uintptr_t)a.part & 15) != 0 ||
+      a.grid != a.tiles_n * a.ksplit)
+    return (int)hipErrorInvalidValue;
+  hipLaunchKernelGGL(fc_stream_kernel, dim3(a.grid), dim3(FC_NT), 0, st, a);
+  return (int)hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------------
 // First-layer chain: a dense convolution with a short reduction C*R*S <= 160 (the 3-channel image layer: 3x3 -> 27,
 // 7x7 -> 147), reading the caller's graph input where it lies (any strides, fp32 or the compute type) and writing
 // the consumer's NHWC layout: the layout transform at the graph boundary (transpose operator, Table 3) is linked
@@ -1981,6 +2057,10 @@ int launch_conv(const ConvArgs& a, int dtype, int cfg, int scalar_loader, void* 
     if (cfg != kPairCfg || scalar_loader) return (int)hipErrorInvalidValue;
     return launch_pair(a, dtype, st);
   }
+  if (cfg == kFcCfg) {
+    if (scalar_loader) return (int)hipErrorInvalidValue;
+    return launch_fc(a, dtype, st);
+  }
   if (a.dw_w) {
     if (scalar_loader) return (int)hipErrorInvalidValue;
     return dtype == DT_BF16 ? launch_conv_dwpro_t<bf16_t>(a, cfg, st) : launch_conv_dwpro_t<float>(a, cfg, st);
@@ -1996,6 +2076,7 @@ int launch_conv(const ConvArgs& a, int dtype, int cfg, int scalar_loader, void* 
 size_t conv_lds_bytes(int cfg, int /*mode*/) {
   if (cfg == kHaloCfg) return v2_lds_total(128);
   if (cfg == kPairCfg) return PR_LDS;
+  if (cfg == kFcCfg) return 0;
   if (cfg == kStemCfg) return 40 * 1024;   // static: staging slices (at most 4 x 32 x 272 bytes) + tables
   const TileCfg& c = kTileCfgs[cfg];
   const size_t main_b = (size_t)2 * (c.bm + c.bn) * LDS_ROW;

@@ -100,6 +100,7 @@ struct Step {
   CvtArgs cvt{};
   SplitKArgs splitk{};
   int cfg = 0, scalar = 0, stem = 0;
+  int fc_stream = 0;           // fully connected chain with few rows: weights streamed by fc_stream_kernel, finished by the summing pass
   int gap_finish = 0;          // global average linked through the summing pass of a reduction split (few images)
   // every partition the split planner found legal for this chain (tile shape x kernel), for profiling-driven choice;
   // empty when the choice is forced or tied to the structure of the plan (reduction split, stem, linked depthwise)
@@ -602,11 +603,29 @@ struct Planner {
     // source [K][C][R][S] -> destination [K][reduction index]; the reduction index is (r*S+s)*C + c, or, when
     // the channels divide into whole steps, ((c/step)*R*S + r*S + s)*step + c%step so that the R*S taps of
     // one channel chunk are consecutive steps and re-read the same input pixels while they are still cached
-    const bool kchunk = C % bke == 0 && R * S > 1 && !st.scalar;
+    const bool kchunk = C % bke == 0 && R * S > 1 && !st.scalar && !st.fc_stream;
     st.conv.kchunk = kchunk ? 1 : 0;
     auto kidx = [&](int c, int rs) -> size_t {
       return kchunk ? ((size_t)(c / bke) * R * S + rs) * bke + c % bke : (size_t)rs * C + c;
     };
+    if (st.fc_stream) {
+      // Weight-streaming kernel: the fragments of a 32-channel block are stored in the order its wavefront loads them,
+      // [block][step of 64][k-group of 16][lane = 32 * (half of the k-group) + channel][8 elements], so every load
+      // instruction reads 1 KB of consecutive memory and a block's share of the reduction is one sequential stream
+      const int nsteps = kred_pad / 64;
+      uint16_t* dst = (uint16_t*)base;
+      for (int k = 0; k < K; ++k) {
+        const float* src = o.weight.data() + (size_t)k * Csrc * R * S;
+        for (int c = 0; c < Csrc; ++c)
+          for (int rs = 0; rs < R * S; ++rs) {
+            const size_t kk = (size_t)rs * C + c;
+            const size_t step = kk / 64, g = (kk % 64) / 16, half = (kk % 16) / 8, e = kk % 8;
+            dst[(((((size_t)(k / 32) * nsteps + step) * 4 + g) * 64 + half * 32 + k % 32) * 8) + e] = f2bf_host(src[(size_t)c * R * S + rs]);
+          }
+      }
+      st.bytes_w = (long long)K * R * S * Csrc * p.esz;
+      return;
+    }
     for (int k = 0; k < K; ++k) {
       const float* src = o.weight.data() + (size_t)k * Csrc * R * S;
       if (p.dt == DT_BF16) {
@@ -983,6 +1002,12 @@ struct Planner {
           a.mode = M_FLAT; a.pool = POOL_NONE;
         }
         a.M_total = a.mode == M_FLAT ? a.N * a.OH * a.OW : a.mode == M_ZIGZAG ? a.N * a.PH * a.PW * 4 : a.OH * a.OW;
+        // A fully connected chain over at most 32 images streams its weights once: the kernel made for that keeps many
+        // loads in flight per unit and shares the reduction out over workgroups (the summing pass finishes the chain)
+        st.fc_stream = p.dt == DT_BF16 && p.opts.split && p.opts.tile == 0 && !from_dw && !from_pair && a.mode == M_FLAT && !st.gap_finish &&
+                       a.OH == 1 && a.OW == 1 && a.R == is.h && a.S == is.w && a.pad == 0 && is.n <= 32 && !st.scalar && a.C == is.c &&
+                       ((long long)a.R * a.S * a.C) % 64 == 0 && (long long)a.R * a.S * a.C >= 512 && (long long)a.R * a.S * a.C < (1ll << 30) &&
+                       iv.sN % p.ce == 0 && iv.sN >= (long long)a.R * a.S * a.C && (a.R * a.S == 1 || (iv.sP == a.C && iv.sN == (long long)a.R * a.S * a.C));
         pack_dense(st, go, is_fc ? is.c : is.c, a.C, a.R, a.S, K);
         push_affine(af, (K + 127) / 128 * 128, &st.scale_off, &st.shift_off);
         if (st.scalar) {
@@ -1029,18 +1054,28 @@ struct Planner {
         // partition leaves most compute units idle and the reduction is long, split it across workgroups too.
         // Shares are summed in index order by a second pass, so the result does not depend on timing.
         const int nsteps = a.Kred_pad / (kRowBytes / p.esz);
-        if (p.opts.split && st.cfg < kHaloCfg && a.mode == M_FLAT && (!from_dw || (st.gap_finish && a.dw_panel > 0)) &&
-            (st.gap_finish || (a.ntiles * 2 <= p.hw.num_cu && nsteps >= 32))) {
+        if (st.fc_stream || (p.opts.split && st.cfg < kHaloCfg && a.mode == M_FLAT && (!from_dw || (st.gap_finish && a.dw_panel > 0)) &&
+            (st.gap_finish || (a.ntiles * 2 <= p.hw.num_cu && nsteps >= 32)))) {
           int ks = std::min({(2 * p.hw.num_cu + a.ntiles - 1) / a.ntiles, nsteps / 8, 32});
           if (st.gap_finish) ks = std::max(ks, 1);
           if (from_dw) ks = 1;                                     // the depthwise-panel kernel hands over one share
-          if (ks >= 4 || st.gap_finish) {
+          const int fc_tiles = (K + kFcChannels - 1) / kFcChannels;
+          // (two workgroups per unit, each with at least 4 steps = 32 KB of weights to stream)
+          if (st.fc_stream) ks = std::max(1, std::min((kFcWgPerCu * std::max(1, p.hw.num_cu) + fc_tiles - 1) / fc_tiles, nsteps / 4));
+          if (st.fc_stream || ks >= 4 || st.gap_finish) {
             const int spk = (nsteps + ks - 1) / ks;
             ks = (nsteps + spk - 1) / spk;
-            const TileCfg& tc = kTileCfgs[st.cfg];
             st.cands.clear();                                      // the plan's structure now depends on this tile shape
-            a.ksplit = ks; a.steps_per_split = spk; a.part_ld = a.tiles_n * tc.bn;
-            set_grid(a, st.cfg);
+            a.ksplit = ks; a.steps_per_split = spk;
+            if (st.fc_stream) {
+              st.cfg = kFcCfg; st.lds = 0;
+              a.tiles_m = 1; a.tiles_n = fc_tiles; a.ntiles = fc_tiles; a.xcd_m = 1;
+              a.part_ld = fc_tiles * kFcChannels;
+              a.grid = fc_tiles * ks;
+            } else {
+              a.part_ld = a.tiles_n * kTileCfgs[st.cfg].bn;
+              set_grid(a, st.cfg);
+            }
             View pv;
             pv.esz = 4; pv.f32 = 1; pv.s = Shape{1, 1, 1, 1};
             const long long pbytes = (long long)ks * a.M_total * a.part_ld * 4;
@@ -1235,11 +1270,12 @@ void write_plan_json(xenos_plan& p) {
       const TileCfg halo_tc{kHaloRows, c.halo_bn, 64, c.halo_bn / 2};
       const TileCfg stem_tc{32, c.K, 32, c.K};
       const TileCfg pair_tc{kPairRows, kPairChannels, 64, kPairChannels / 2};
-      const TileCfg& tc = s.cfg == kHaloCfg ? halo_tc : s.cfg == kStemCfg ? stem_tc : s.cfg == kPairCfg ? pair_tc : kTileCfgs[s.cfg];
+      const TileCfg fc_tc{32, kFcChannels, 32, 32};
+      const TileCfg& tc = s.cfg == kHaloCfg ? halo_tc : s.cfg == kStemCfg ? stem_tc : s.cfg == kPairCfg ? pair_tc : s.cfg == kFcCfg ? fc_tc : kTileCfgs[s.cfg];
       snprintf(buf, sizeof buf, ",\"mode\":\"%s\",\"loader\":\"%s\",\"N\":%d,\"C\":%d,\"H\":%d,\"W\":%d,\"K\":%d,\"R\":%d,\"S\":%d,\"stride\":%d,"
                "\"pad\":%d,\"OH\":%d,\"OW\":%d,\"PH\":%d,\"PW\":%d,\"pool\":%d,\"relu\":%d,\"res\":%d,\"bm\":%d,\"bn\":%d,\"tiles_m\":%d,"
                "\"tiles_n\":%d,\"grid\":%d,\"lds\":%zu,\"pph\":%d,\"ppw\":%d,\"patch_h\":%d,\"patch_w\":%d,\"out_c_off\":%lld,\"out_sP\":%lld,\"halo\":%d,\"th\":%d,\"tw\":%d,\"dw_linked\":%d,\"ksplit\":%d,\"candidates\":%d,\"tuned\":%d,\"plin\":%d",
-               kModeNames[c.mode], s.stem ? "stem" : c.pair ? "pair" : s.scalar ? "scalar" : "vector", c.N, c.C, c.H, c.W, c.K, c.R, c.S, c.stride, c.pad, c.OH, c.OW,
+               kModeNames[c.mode], s.stem ? "stem" : c.pair ? "pair" : s.fc_stream ? "stream" : s.scalar ? "scalar" : "vector", c.N, c.C, c.H, c.W, c.K, c.R, c.S, c.stride, c.pad, c.OH, c.OW,
                c.PH, c.PW, c.pool, c.relu, c.has_res, tc.bm, tc.bn, c.tiles_m, c.tiles_n, c.grid, s.lds, c.pph, c.ppw, c.patch_h,
                c.patch_w, p.views[s.v_out].off, c.out_sP, s.cfg == kHaloCfg ? 1 : 0, c.th, c.tw, s.dw_w_off >= 0 ? 1 : 0, c.ksplit > 1 ? c.ksplit : 1, (int)s.cands.size(), s.tuned, s.cfg == kHaloCfg ? c.halo_plin : 0);
       j += buf;

@@ -261,6 +261,26 @@ def test_first_two_3x3_convolutions_linked_on_chip(h, w, n, c, pool, bn):
     assert all(ch.get("loader") != "pair" for ch in i3["chains"])
 
 
+@pytest.mark.parametrize("n,c,hw,k1,k2", [(32, 64, 7, 200, 72), (5, 512, 1, 1024, 40), (1, 512, 2, 136, 24), (17, 8, 8, 1088, 1000)])
+def test_fully_connected_streaming_kernel(n, c, hw, k1, k2):
+    # FC chains over at most 32 images (bf16): the weight-streaming kernel (128 channels per workgroup, the reduction shared
+    # out over workgroups) writes fp32 shares, the summing pass applies bias / ReLU.  Two FC layers in a row: the second
+    # reads the first one's N x 1 x 1 x K output; channel counts that are not multiples of 128 leave ragged channel tiles.
+    b = wg.builder("fcs", (n, c, hw, hw), 29, nonzero_bias=True)
+    t = b.cbr(0, c, 3, 1, 1, name="c0")
+    t = b.relu(b.fc(t, k1, "fc1"))
+    t = b.fc(t, k2, "fc2")
+    g = b.finish(t)
+    ref = xo.forward(g)
+    y, info = check(g, ref, compute=1, link=2)
+    loaders = [ch.get("loader") for ch in info["chains"] if ch["kind"] == "conv"]
+    want = sum(1 for kred in (c * hw * hw, k1) if kred % 64 == 0 and kred >= 512)   # whole 64-element steps, enough of them
+    assert want >= 1 and loaders.count("stream") == want, loaders
+    y2, _ = run_gpu(g, compute=1, link=2)
+    assert np.array_equal(y, y2)                              # shares are summed in index order: run-to-run identical
+    check(g, ref, compute=0, link=2)                          # fp32 path: general kernel
+
+
 def _bf16_rne(x):
     """fp32 -> bf16 -> fp32 with round-to-nearest-even, in integer arithmetic."""
     u = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32).astype(np.uint64)
