@@ -163,6 +163,8 @@ def main():
     ap.add_argument("--quick", action="store_true", help="headline workload, linked mode only, no CPU baseline")
     ap.add_argument("--cpu-images", type=int, default=16)
     ap.add_argument("--detail", default="", help="write the full per-chain report (JSON) to this file")
+    ap.add_argument("--link-level", type=int, default=0, choices=(0, 2, 3),
+                    help="time the linked path at this link level only (0: both, the headline is the faster one); for profiling runs")
     ap.add_argument("--no-tune", action="store_true", help="skip xenos_plan_tune: time the cost model's partition choice")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run a plain device copy of 256 MiB three times and exit (reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
@@ -192,11 +194,11 @@ def main():
 
     name = args.workload
     cfg, batch, compute = WORKLOADS[name]
-    links = (3, 2) if args.quick else (3, 2, 1, 0)
+    links = ((3, 2) if not args.link_level else (args.link_level,)) + (() if args.quick else (1, 0))
     head, g = run_workload(name, args.steps, args.warmup, links, chains=True, wg=wg, X=X, torch=torch)
     # the headline is the linked + split path at the link level that is faster on this workload (level 3 keeps the first
     # two 3x3 convolutions of a VGG-style stack in one chain; where no such pair exists the two levels plan the same chains)
-    level = 3 if head["linked_deep"]["ms_per_step"] <= head["linked"]["ms_per_step"] else 2
+    level = args.link_level or (3 if head["linked_deep"]["ms_per_step"] <= head["linked"]["ms_per_step"] else 2)
     lk = head[LINK_NAMES[level]]
 
     # Roofline of the dominant kernel: conv3x3_kernel (halo-staged 3x3 convolution chains on MFMA), over all its

@@ -96,7 +96,8 @@ typedef struct {
 /* link:  0 = operator by operator (the paper's Vanilla dataflow: every operator is one pass)
  *        1 = fused CBR only; pooling / add / concat stay separate passes (the "HO baseline")
  *        2 = operator linking on (Section 4.1): CBR + pool, shortcut add, concat-by-offset
- *        3 = 2 plus depthwise -> pointwise chains kept on chip (Section 2.2 example)
+ *        3 = 2 plus the chains whose intermediate tensor stays on chip: depthwise -> pointwise (Section 2.2 example) and,
+ *            on the bf16 path, a first-layer 3x3 convolution -> 3x3 convolution pair (Table 1, ConvX -> ConvY)
  * split: 0 = every chain runs on ONE compute unit (no operator split; for tests)
  *        1 = DSP-aware operator split (Section 4.2): output channels first, then H/W
  * compute: element type of activations and weights in HBM; accumulation is always fp32.
