@@ -48,6 +48,10 @@ static const int kPairCfg = 6;
 // workgroup, reduction shared out over workgroups; always followed by the summing pass)
 static const int kFcCfg = 7;
 static const int kFcChannels = 128;
+// Configuration index of the first-layer kernel that stages its input block in LDS (bf16 path, fp32 NCHW graph input with at most 4
+// channels, square kernel up to 7x7, stride 1 or 2): tiles of kStemLdsTh x kStemLdsTw output pixels of one image
+static const int kStemLdsCfg = 8;
+static const int kStemLdsTh = 8, kStemLdsTw = 16, kStemLdsInMax = 784;   // (7 * 2 + 7) x (15 * 2 + 7) = 777 positions at most
 static const int kFcWgPerCu = 1;    // workgroups per compute unit the reduction split of such a chain aims at
 static const int kPairChannels = 64, kPairRed = 48;
 static const int kPairRows = 128, kPairPatchMax = 180;   // output pixels and patch positions ((TH+2) x 18) of a tile

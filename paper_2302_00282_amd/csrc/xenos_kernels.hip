@@ -1752,6 +1752,175 @@ static int launch_stem_t(const ConvArgs& a, hipStream_t st) {
   return (int)hipGetLastError();
 }
 
+// ---------------------------------------------------------------------------------------------
+// First-layer chain with the input block staged on chip (bf16 path; at most 4 input channels read from the caller's
+// fp32 NCHW tensor, square kernel up to 7x7, stride 1 or 2, K = 32 or 64).  stem_kernel gathers every element of every
+// window from memory (up to 80 single loads per pixel for a 7x7 kernel: bound by address processing, not by bytes);
+// here a workgroup owns a TH x TW block of output pixels of one image, reads the input block those windows cover ONCE
+// (coalesced along W), keeps it in LDS as [position][4 channels] bf16, and gathers the MFMA operands from LDS: the
+// reduction slot is tap * 4 + channel, so one 8-byte LDS read is one tap of one pixel, two taps per lane and MFMA
+// step.  The weights of all steps stay in registers for all tiles of the workgroup.  One wavefront = 32 pixels (two
+// tile rows of 16) x all K channels; epilogue and whole-pixel stores as in stem_kernel.
+// ---------------------------------------------------------------------------------------------
+constexpr int SL_NW = 4, SL_NT = 64 * SL_NW;
+constexpr int SL_TH = kStemLdsTh, SL_TW = kStemLdsTw;             // output pixels of a tile: 8 x 16 = 4 wavefronts x 32
+constexpr int SL_INMAX = kStemLdsInMax;                            // positions of the staged input block
+static_assert(SL_TH * SL_TW == 32 * SL_NW && SL_TW == 16, "one wavefront = two tile rows of 16 pixels");
+
+template <int KB, int NSTEP>
+__global__ __launch_bounds__(SL_NT, 2) void stem_lds_kernel(const ConvArgs a) {
+  constexpr int K = KB * 32;
+  constexpr int SPITCH = K * 2 + 16;                               // staging row pitch (odd number of 16-byte slots)
+  constexpr int CPP = K * 2 / 16, PPI = 64 / CPP;                  // 16-byte chunks per output pixel, pixels per store instruction
+  __shared__ __align__(16) unsigned char s_xin[SL_INMAX * 8];
+  __shared__ __align__(16) unsigned char s_stage[SL_NW * 32 * SPITCH];
+  __shared__ __align__(16) float s_aff[2 * K];
+  __shared__ int2 s_tap[NSTEP][2];                                 // per step and lane half: LDS byte offsets of its two taps (-1 = none)
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l31 = lane & 31, lhalf = lane >> 5;
+  const int st = a.stride, IH = (SL_TH - 1) * st + a.R, IW = (SL_TW - 1) * st + a.S, npos = IH * IW, nin = a.pair_C * npos;
+  const int ntaps = a.R * a.S;
+
+  for (int i = tid; i < SL_INMAX * 2; i += SL_NT) ((uint32_t*)s_xin)[i] = 0u;   // channel slots beyond pair_C stay zero
+  if (tid < 2 * K) s_aff[tid] = tid < K ? a.scale[tid] : a.shift[tid - K];
+  if (tid < NSTEP * 2) {
+    const int j = tid >> 1, hh = tid & 1, t0 = 4 * j + 2 * hh, t1 = t0 + 1;
+    s_tap[j][hh] = make_int2(t0 < ntaps ? ((t0 / a.S) * IW + t0 % a.S) * 8 : -1, t1 < ntaps ? ((t1 / a.S) * IW + t1 % a.S) * 8 : -1);
+  }
+  // resident weights: rows = channels 32 * b + l31, [K][NSTEP * 16] with slot = tap * 4 + channel
+  u32x4_t w[NSTEP][KB];
+#pragma unroll
+  for (int j = 0; j < NSTEP; ++j)
+#pragma unroll
+    for (int b = 0; b < KB; ++b)
+      w[j][b] = *(const u32x4_t*)((const unsigned char*)a.dw_w + ((32 * b + l31) * (NSTEP * 16) + j * 16 + lhalf * 8) * 2);
+  // this lane's pixel of the tile and where its window starts in the staged block
+  const int ty = 2 * wave + (l31 >> 4), tx = l31 & 15;
+  const int xbase = ((ty * st) * IW + tx * st) * 8;
+  const float lo = a.relu ? 0.f : -3.4028235e38f;
+  unsigned char* stg = s_stage + wave * (32 * SPITCH);
+  const int tiles_img = a.tiles_y * a.tiles_x;
+
+  // ---- the input block of a tile: element e = (channel, block row, block column), consecutive threads along W; what does
+  // not depend on the tile (position in the block, offset from the block's first element) is worked out once ----------
+  constexpr int NI = (SL_INMAX * 4 + SL_NT - 1) / SL_NT;
+  int xe[NI], xg[NI];
+#pragma unroll
+  for (int it = 0; it < NI; ++it) {
+    const int e = tid + it * SL_NT;
+    const int c = e / npos, rem = e - c * npos, ir = rem / IW, ic = rem - ir * IW;
+    xe[it] = e < nin ? (c << 24) | (ir << 12) | ic : -1;
+    xg[it] = (int)(c * a.pair_sC + ir * a.pair_sH + ic);
+  }
+  float xr[NI];
+  auto load_block = [&](int tile) __attribute__((always_inline)) {
+    const int n = tile / tiles_img, tr = tile - n * tiles_img, tyi = tr / a.tiles_x, txi = tr - tyi * a.tiles_x;
+    const int iy0 = tyi * SL_TH * st - a.pad, ix0 = txi * SL_TW * st - a.pad;
+    // (may point before the tensor: only elements inside the image are read, the others read the tensor's first element)
+    const float* src = (const float*)a.in + ((long long)n * a.pair_sN + (long long)iy0 * a.pair_sH + ix0);
+#pragma unroll
+    for (int it = 0; it < NI; ++it) {
+      const int ir = (xe[it] >> 12) & 0xfff, ic = xe[it] & 0xfff;
+      const bool ok = xe[it] >= 0 && (unsigned)(iy0 + ir) < (unsigned)a.H && (unsigned)(ix0 + ic) < (unsigned)a.W;
+      const float* ptr = ok ? src + xg[it] : (const float*)a.in;
+      const float v = *ptr;
+      xr[it] = ok ? v : 0.f;
+    }
+  };
+  auto store_block = [&]() __attribute__((always_inline)) {
+#pragma unroll
+    for (int it = 0; it < NI; ++it) {
+      if (xe[it] >= 0) {
+        const int c = xe[it] >> 24, ir = (xe[it] >> 12) & 0xfff, ic = xe[it] & 0xfff;
+        *(uint16_t*)(s_xin + (ir * IW + ic) * 8 + c * 2) = f2bf(xr[it]);
+      }
+    }
+  };
+
+  int tile = blockIdx.x;
+  if (tile < a.tiles_m) load_block(tile);
+  while (tile < a.tiles_m) {
+    const int n = tile / tiles_img, tr = tile - n * tiles_img, tyi = tr / a.tiles_x, txi = tr - tyi * a.tiles_x;
+    const int oy0 = tyi * SL_TH, ox0 = txi * SL_TW;
+    __syncthreads();                                               // the previous tile's reads of the block are done
+    store_block();
+    __syncthreads();
+    const int next = tile + gridDim.x;
+    if (next < a.tiles_m) load_block(next);                        // in flight during this tile's convolution and stores
+    // ---- the convolution of this wavefront's 32 pixels ----------------------------------------------------------
+    f32x16_t acc[KB];
+#pragma unroll
+    for (int b = 0; b < KB; ++b)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[b][e] = 0.f;
+#pragma unroll
+    for (int j = 0; j < NSTEP; ++j) {
+      const int2 t = s_tap[j][lhalf];
+      uint2 t0 = *(const uint2*)(s_xin + xbase + (t.x >= 0 ? t.x : 0));
+      uint2 t1 = *(const uint2*)(s_xin + xbase + (t.y >= 0 ? t.y : 0));
+      if (t.x < 0) t0 = uint2{0u, 0u};
+      if (t.y < 0) t1 = uint2{0u, 0u};
+      const u32x4_t fa = {t0.x, t0.y, t1.x, t1.y};
+#pragma unroll
+      for (int b = 0; b < KB; ++b)
+        acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, w[j][b]), __builtin_bit_cast(bf16x8_t, fa), acc[b], 0, 0, 0);
+    }
+    // ---- epilogue: lane = pixel l31, channels 32*b + 8*g + 4*lhalf + (0..3); transposed through this wavefront's LDS
+    // slice so that every store instruction writes whole pixels ------------------------------------------------
+#pragma unroll
+    for (int b = 0; b < KB; ++b)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const int c0 = 32 * b + 8 * g + 4 * lhalf;
+        const f32x4_t sc = *(const f32x4_t*)&s_aff[c0], sh = *(const f32x4_t*)&s_aff[K + c0];
+        float y[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) y[e] = fmaxf(acc[b][4 * g + e] * sc[e] + sh[e], lo);
+        uint2 o;
+        o.x = f2bf2(y[0], y[1]);
+        o.y = f2bf2(y[2], y[3]);
+        *(uint2*)(stg + l31 * SPITCH + c0 * 2) = o;
+      }
+    __builtin_amdgcn_wave_barrier();
+#pragma unroll
+    for (int it = 0; it < 32 / PPI; ++it) {
+      const int px = it * PPI + lane / CPP, ch = lane % CPP;
+      const u32x4_t o = *(const u32x4_t*)(stg + px * SPITCH + ch * 16);
+      const int oy = oy0 + 2 * wave + (px >> 4), ox = ox0 + (px & 15);
+      if (oy < a.OH && ox < a.OW)
+        *(u32x4_t*)((unsigned char*)a.out + ((long long)n * a.out_sN + (long long)(oy * a.OW + ox) * a.out_sP) * 2 + ch * 16) = o;
+    }
+    __builtin_amdgcn_wave_barrier();
+    tile = next;
+  }
+}
+
+template <int KB>
+static int launch_stem_lds_kb(const ConvArgs& a, hipStream_t st) {
+  const int taps = a.R * a.S;
+  if (taps <= 12) hipLaunchKernelGGL((stem_lds_kernel<KB, 3>), dim3(a.grid), dim3(SL_NT), 0, st, a);
+  else if (taps <= 28) hipLaunchKernelGGL((stem_lds_kernel<KB, 7>), dim3(a.grid), dim3(SL_NT), 0, st, a);
+  else if (taps <= 52) hipLaunchKernelGGL((stem_lds_kernel<KB, 13>), dim3(a.grid), dim3(SL_NT), 0, st, a);
+  else return (int)hipErrorInvalidValue;
+  return (int)hipGetLastError();
+}
+
+static int launch_stem_lds(const ConvArgs& a, int dtype, hipStream_t st) {
+  // the host checks what the kernel's LDS layout and indexing assume
+  const int IH = (SL_TH - 1) * a.stride + a.R, IW = (SL_TW - 1) * a.stride + a.S;
+  if (dtype != DT_BF16 || a.pair_C < 1 || a.pair_C > 4 || a.C != a.pair_C || a.R != a.S || a.R < 1 || a.R > 7 || (a.stride != 1 && a.stride != 2) ||
+      a.pad < 0 || a.pad > a.R || IH * IW > SL_INMAX || !a.dw_w || a.mode != M_FLAT || a.has_res || a.pool != POOL_NONE || a.ksplit >= 1 ||
+      a.out_sK != 1 || a.out_f32 || (a.out_sP * 2) % 16 != 0 || (a.out_sN * 2) % 16 != 0 || ((uintptr_t)a.out & 15) || ((uintptr_t)a.dw_w & 15) ||
+      a.th != SL_TH || a.tw != SL_TW || a.tiles_y != (a.OH + SL_TH - 1) / SL_TH || a.tiles_x != (a.OW + SL_TW - 1) / SL_TW ||
+      a.tiles_m != a.N * a.tiles_y * a.tiles_x || a.pair_sN < 0 || a.pair_sC < 0 || a.pair_sH < 0 ||
+      (long long)4 * a.pair_sC + (long long)(a.H + 32) * a.pair_sH >= (1ll << 31) ||
+      a.OH != (a.H + 2 * a.pad - a.R) / a.stride + 1 || a.OW != (a.W + 2 * a.pad - a.S) / a.stride + 1)
+    return (int)hipErrorInvalidValue;
+  if (a.K == 32) return launch_stem_lds_kb<1>(a, st);
+  if (a.K == 64) return launch_stem_lds_kb<2>(a, st);
+  return (int)hipErrorInvalidValue;
+}
+
+
 template <typename T, int BM, int BN, int WM, int WN, bool SCALAR, int MODE>
 static int launch_conv_inst(const ConvArgs& a, hipStream_t st) {
   constexpr int lds = lds_conv_bytes<BM, BN>();
@@ -2061,6 +2230,7 @@ int launch_conv(const ConvArgs& a, int dtype, int cfg, int scalar_loader, void* 
     if (scalar_loader) return (int)hipErrorInvalidValue;
     return launch_fc(a, dtype, st);
   }
+  if (cfg == kStemLdsCfg) return launch_stem_lds(a, dtype, st);
   if (a.dw_w) {
     if (scalar_loader) return (int)hipErrorInvalidValue;
     return dtype == DT_BF16 ? launch_conv_dwpro_t<bf16_t>(a, cfg, st) : launch_conv_dwpro_t<float>(a, cfg, st);
@@ -2077,6 +2247,7 @@ size_t conv_lds_bytes(int cfg, int /*mode*/) {
   if (cfg == kHaloCfg) return v2_lds_total(128);
   if (cfg == kPairCfg) return PR_LDS;
   if (cfg == kFcCfg) return 0;
+  if (cfg == kStemLdsCfg) return 32 * 1024;   // static: input block, staging slices, tables
   if (cfg == kStemCfg) return 40 * 1024;   // static: staging slices (at most 4 x 32 x 272 bytes) + tables
   const TileCfg& c = kTileCfgs[cfg];
   const size_t main_b = (size_t)2 * (c.bm + c.bn) * LDS_ROW;

@@ -155,6 +155,9 @@ def test_split_covers_the_output_and_fits_private_memory(cfg, batch, compute):
             # halo-staged kernel: TH x TW tiles over the images stacked with their two padding rows each
             assert c["th"] * c["tw"] <= c["bm"] == 256
             assert c["tiles_m"] == -(-(c["N"] * (c["H"] + 2)) // c["th"]) * -(-c["W"] // c["tw"])
+        elif c["loader"] == "stem" and c["bm"] == 128:
+            # first layer with its input block staged on chip: 8 x 16 tiles of output pixels per image
+            assert c["tiles_m"] == c["N"] * -(-c["OH"] // 8) * -(-c["OW"] // 16)
         elif c["mode"] == "flat":
             m = c["N"] * c["OH"] * c["OW"]
             assert c["tiles_m"] * c["bm"] >= m > (c["tiles_m"] - 1) * c["bm"]
@@ -167,6 +170,8 @@ def test_split_covers_the_output_and_fits_private_memory(cfg, batch, compute):
             assert c["tiles_m"] == c["N"] * py * px
         if c.get("halo"):
             assert 1 <= c["grid"] <= max(8, X.MI355X["num_cu"])      # persistent workgroups walk the tiles
+        elif c["loader"] == "stem" and c["bm"] == 128:
+            assert c["tiles_n"] == 1 and 1 <= c["grid"] <= c["tiles_m"]                               # persistent workgroups walk the tiles
         elif c["loader"] == "stem":
             assert c["bm"] == 32 and c["tiles_n"] == 1 and 1 <= c["grid"] <= -(-c["tiles_m"] // 4)   # wavefronts stride over 32-pixel blocks
         else:
