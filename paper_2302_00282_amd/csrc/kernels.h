@@ -51,6 +51,7 @@ static const int kFcChannels = 128;
 // Configuration index of the first-layer kernel that stages its input block in LDS (bf16 path, fp32 NCHW graph input with at most 4
 // channels, square kernel up to 7x7, stride 1 or 2): tiles of kStemLdsTh x kStemLdsTw output pixels of one image
 static const int kStemLdsCfg = 8;
+static const int kStemLdsPph = 3, kStemLdsPpw = 8;   // pooling windows per tile when a max-pooling is linked
 static const int kStemLdsTh = 8, kStemLdsTw = 16, kStemLdsInMax = 784;   // (7 * 2 + 7) x (15 * 2 + 7) = 777 positions at most
 static const int kFcWgPerCu = 1;    // workgroups per compute unit the reduction split of such a chain aims at
 static const int kPairChannels = 64, kPairRed = 48;

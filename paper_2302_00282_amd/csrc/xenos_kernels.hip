@@ -1767,7 +1767,7 @@ constexpr int SL_TH = kStemLdsTh, SL_TW = kStemLdsTw;             // output pixe
 constexpr int SL_INMAX = kStemLdsInMax;                            // positions of the staged input block
 static_assert(SL_TH * SL_TW == 32 * SL_NW && SL_TW == 16, "one wavefront = two tile rows of 16 pixels");
 
-template <int KB, int NSTEP>
+template <int KB, int NSTEP, bool POOL>
 __global__ __launch_bounds__(SL_NT, 2) void stem_lds_kernel(const ConvArgs a) {
   constexpr int K = KB * 32;
   constexpr int SPITCH = K * 2 + 16;                               // staging row pitch (odd number of 16-byte slots)
@@ -1777,7 +1777,11 @@ __global__ __launch_bounds__(SL_NT, 2) void stem_lds_kernel(const ConvArgs a) {
   __shared__ __align__(16) float s_aff[2 * K];
   __shared__ int2 s_tap[NSTEP][2];                                 // per step and lane half: LDS byte offsets of its two taps (-1 = none)
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l31 = lane & 31, lhalf = lane >> 5;
-  const int st = a.stride, IH = (SL_TH - 1) * st + a.R, IW = (SL_TW - 1) * st + a.S, npos = IH * IW, nin = a.pair_C * npos;
+  const int st = a.stride;
+  // convolution pixels of a tile: TH x TW, or, with a linked max-pooling, the CH x CW block that the tile's pph x ppw
+  // pooling windows cover (window overlap recomputed per tile; at most 128 pixels = one per lane of the 4 wavefronts)
+  const int CH = POOL ? (a.pph - 1) * a.ps + a.pk : SL_TH, CW = POOL ? (a.ppw - 1) * a.ps + a.pk : SL_TW;
+  const int IH = (CH - 1) * st + a.R, IW = (CW - 1) * st + a.S, npos = IH * IW, nin = a.pair_C * npos;
   const int ntaps = a.R * a.S;
 
   for (int i = tid; i < SL_INMAX * 2; i += SL_NT) ((uint32_t*)s_xin)[i] = 0u;   // channel slots beyond pair_C stay zero
@@ -1793,8 +1797,10 @@ __global__ __launch_bounds__(SL_NT, 2) void stem_lds_kernel(const ConvArgs a) {
 #pragma unroll
     for (int b = 0; b < KB; ++b)
       w[j][b] = *(const u32x4_t*)((const unsigned char*)a.dw_w + ((32 * b + l31) * (NSTEP * 16) + j * 16 + lhalf * 8) * 2);
-  // this lane's pixel of the tile and where its window starts in the staged block
-  const int ty = 2 * wave + (l31 >> 4), tx = l31 & 15;
+  // this lane's convolution pixel of the tile and where its window starts in the staged block
+  const int q = wave * 32 + l31;
+  const bool qok = q < CH * CW;
+  const int ty = qok ? q / CW : 0, tx = qok ? q - ty * CW : 0;
   const int xbase = ((ty * st) * IW + tx * st) * 8;
   const float lo = a.relu ? 0.f : -3.4028235e38f;
   unsigned char* stg = s_stage + wave * (32 * SPITCH);
@@ -1812,9 +1818,17 @@ __global__ __launch_bounds__(SL_NT, 2) void stem_lds_kernel(const ConvArgs a) {
     xg[it] = (int)(c * a.pair_sC + ir * a.pair_sH + ic);
   }
   float xr[NI];
+  // first convolution pixel of a tile (may lie outside the map when the pooling is padded)
+  auto tile_origin = [&](int tile, int& n, int& cy0, int& cx0) __attribute__((always_inline)) {
+    n = tile / tiles_img;
+    const int tr = tile - n * tiles_img, tyi = tr / a.tiles_x, txi = tr - tyi * a.tiles_x;
+    cy0 = POOL ? tyi * a.pph * a.ps - a.pp : tyi * SL_TH;
+    cx0 = POOL ? txi * a.ppw * a.ps - a.pp : txi * SL_TW;
+  };
   auto load_block = [&](int tile) __attribute__((always_inline)) {
-    const int n = tile / tiles_img, tr = tile - n * tiles_img, tyi = tr / a.tiles_x, txi = tr - tyi * a.tiles_x;
-    const int iy0 = tyi * SL_TH * st - a.pad, ix0 = txi * SL_TW * st - a.pad;
+    int n, cy0, cx0;
+    tile_origin(tile, n, cy0, cx0);
+    const int iy0 = cy0 * st - a.pad, ix0 = cx0 * st - a.pad;
     // (may point before the tensor: only elements inside the image are read, the others read the tensor's first element)
     const float* src = (const float*)a.in + ((long long)n * a.pair_sN + (long long)iy0 * a.pair_sH + ix0);
 #pragma unroll
@@ -1839,9 +1853,9 @@ __global__ __launch_bounds__(SL_NT, 2) void stem_lds_kernel(const ConvArgs a) {
   int tile = blockIdx.x;
   if (tile < a.tiles_m) load_block(tile);
   while (tile < a.tiles_m) {
-    const int n = tile / tiles_img, tr = tile - n * tiles_img, tyi = tr / a.tiles_x, txi = tr - tyi * a.tiles_x;
-    const int oy0 = tyi * SL_TH, ox0 = txi * SL_TW;
-    __syncthreads();                                               // the previous tile's reads of the block are done
+    int n, cy0, cx0;
+    tile_origin(tile, n, cy0, cx0);
+    __syncthreads();                                               // the previous tile's reads of the block and of the staging are done
     store_block();
     __syncthreads();
     const int next = tile + gridDim.x;
@@ -1865,7 +1879,9 @@ __global__ __launch_bounds__(SL_NT, 2) void stem_lds_kernel(const ConvArgs a) {
         acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, w[j][b]), __builtin_bit_cast(bf16x8_t, fa), acc[b], 0, 0, 0);
     }
     // ---- epilogue: lane = pixel l31, channels 32*b + 8*g + 4*lhalf + (0..3); transposed through this wavefront's LDS
-    // slice so that every store instruction writes whole pixels ------------------------------------------------
+    // slice so that every store instruction writes whole pixels.  With a linked pooling, pixels outside the map are
+    // staged as -infinity (padding never wins a maximum) ------------------------------------------------------------
+    const bool inmap = !POOL || (qok && (unsigned)(cy0 + ty) < (unsigned)a.OH && (unsigned)(cx0 + tx) < (unsigned)a.OW);
 #pragma unroll
     for (int b = 0; b < KB; ++b)
 #pragma unroll
@@ -1878,45 +1894,82 @@ __global__ __launch_bounds__(SL_NT, 2) void stem_lds_kernel(const ConvArgs a) {
         uint2 o;
         o.x = f2bf2(y[0], y[1]);
         o.y = f2bf2(y[2], y[3]);
+        if (POOL && !inmap) o = uint2{0xff80ff80u, 0xff80ff80u};
         *(uint2*)(stg + l31 * SPITCH + c0 * 2) = o;
       }
-    __builtin_amdgcn_wave_barrier();
+    if constexpr (POOL) {
+      // ---- linked max-pooling: one thread = one 16-byte channel group of one pooling window of the tile -------------
+      __syncthreads();
+      const int tr = tile - n * tiles_img, tyi = tr / a.tiles_x, txi = tr - tyi * a.tiles_x;
+      for (int idx = tid; idx < a.pph * a.ppw * CPP; idx += SL_NT) {
+        const int wi = idx / CPP, ch = idx - wi * CPP, wy = wi / a.ppw, wx = wi - wy * a.ppw;
+        const int py = tyi * a.pph + wy, px = txi * a.ppw + wx;
+        if (py >= a.PH || px >= a.PW) continue;
+        float m[8];
 #pragma unroll
-    for (int it = 0; it < 32 / PPI; ++it) {
-      const int px = it * PPI + lane / CPP, ch = lane % CPP;
-      const u32x4_t o = *(const u32x4_t*)(stg + px * SPITCH + ch * 16);
-      const int oy = oy0 + 2 * wave + (px >> 4), ox = ox0 + (px & 15);
-      if (oy < a.OH && ox < a.OW)
-        *(u32x4_t*)((unsigned char*)a.out + ((long long)n * a.out_sN + (long long)(oy * a.OW + ox) * a.out_sP) * 2 + ch * 16) = o;
+        for (int e = 0; e < 8; ++e) m[e] = -INFINITY;
+        for (int i = 0; i < a.pk; ++i)
+          for (int j = 0; j < a.pk; ++j) {
+            float v[8];
+            Tr<bf16_t>::unpack(*(const u32x4_t*)(s_stage + ((wy * a.ps + i) * CW + wx * a.ps + j) * SPITCH + ch * 16), v);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) m[e] = fmaxf(m[e], v[e]);
+          }
+        *(u32x4_t*)((unsigned char*)a.out + ((long long)n * a.out_sN + (long long)(py * a.PW + px) * a.out_sP) * 2 + ch * 16) = Tr<bf16_t>::pack(m);
+      }
+    } else {
+      __builtin_amdgcn_wave_barrier();
+#pragma unroll
+      for (int it = 0; it < 32 / PPI; ++it) {
+        const int px = it * PPI + lane / CPP, ch = lane % CPP;
+        const u32x4_t o = *(const u32x4_t*)(stg + px * SPITCH + ch * 16);
+        const int oy = cy0 + 2 * wave + (px >> 4), ox = cx0 + (px & 15);
+        if (oy < a.OH && ox < a.OW)
+          *(u32x4_t*)((unsigned char*)a.out + ((long long)n * a.out_sN + (long long)(oy * a.OW + ox) * a.out_sP) * 2 + ch * 16) = o;
+      }
+      __builtin_amdgcn_wave_barrier();
     }
-    __builtin_amdgcn_wave_barrier();
     tile = next;
   }
 }
 
-template <int KB>
+template <int KB, bool POOL>
 static int launch_stem_lds_kb(const ConvArgs& a, hipStream_t st) {
   const int taps = a.R * a.S;
-  if (taps <= 12) hipLaunchKernelGGL((stem_lds_kernel<KB, 3>), dim3(a.grid), dim3(SL_NT), 0, st, a);
-  else if (taps <= 28) hipLaunchKernelGGL((stem_lds_kernel<KB, 7>), dim3(a.grid), dim3(SL_NT), 0, st, a);
-  else if (taps <= 52) hipLaunchKernelGGL((stem_lds_kernel<KB, 13>), dim3(a.grid), dim3(SL_NT), 0, st, a);
+  if (taps <= 12) hipLaunchKernelGGL((stem_lds_kernel<KB, 3, POOL>), dim3(a.grid), dim3(SL_NT), 0, st, a);
+  else if (taps <= 28) hipLaunchKernelGGL((stem_lds_kernel<KB, 7, POOL>), dim3(a.grid), dim3(SL_NT), 0, st, a);
+  else if (taps <= 52) hipLaunchKernelGGL((stem_lds_kernel<KB, 13, POOL>), dim3(a.grid), dim3(SL_NT), 0, st, a);
   else return (int)hipErrorInvalidValue;
   return (int)hipGetLastError();
 }
 
 static int launch_stem_lds(const ConvArgs& a, int dtype, hipStream_t st) {
   // the host checks what the kernel's LDS layout and indexing assume
-  const int IH = (SL_TH - 1) * a.stride + a.R, IW = (SL_TW - 1) * a.stride + a.S;
+  const bool pool = a.pool != POOL_NONE;
+  const int CH = pool ? (a.pph - 1) * a.ps + a.pk : SL_TH, CW = pool ? (a.ppw - 1) * a.ps + a.pk : SL_TW;
+  const int IH = (CH - 1) * a.stride + a.R, IW = (CW - 1) * a.stride + a.S;
   if (dtype != DT_BF16 || a.pair_C < 1 || a.pair_C > 4 || a.C != a.pair_C || a.R != a.S || a.R < 1 || a.R > 7 || (a.stride != 1 && a.stride != 2) ||
-      a.pad < 0 || a.pad > a.R || IH * IW > SL_INMAX || !a.dw_w || a.mode != M_FLAT || a.has_res || a.pool != POOL_NONE || a.ksplit >= 1 ||
+      a.pad < 0 || a.pad > a.R || IH * IW > SL_INMAX || IH >= 4096 || IW >= 4096 || !a.dw_w || a.has_res || a.ksplit >= 1 ||
       a.out_sK != 1 || a.out_f32 || (a.out_sP * 2) % 16 != 0 || (a.out_sN * 2) % 16 != 0 || ((uintptr_t)a.out & 15) || ((uintptr_t)a.dw_w & 15) ||
-      a.th != SL_TH || a.tw != SL_TW || a.tiles_y != (a.OH + SL_TH - 1) / SL_TH || a.tiles_x != (a.OW + SL_TW - 1) / SL_TW ||
-      a.tiles_m != a.N * a.tiles_y * a.tiles_x || a.pair_sN < 0 || a.pair_sC < 0 || a.pair_sH < 0 ||
-      (long long)4 * a.pair_sC + (long long)(a.H + 32) * a.pair_sH >= (1ll << 31) ||
+      a.pair_sN < 0 || a.pair_sC < 0 || a.pair_sH < 0 || (long long)4 * a.pair_sC + (long long)(a.H + 64) * a.pair_sH >= (1ll << 31) ||
       a.OH != (a.H + 2 * a.pad - a.R) / a.stride + 1 || a.OW != (a.W + 2 * a.pad - a.S) / a.stride + 1)
     return (int)hipErrorInvalidValue;
-  if (a.K == 32) return launch_stem_lds_kb<1>(a, st);
-  if (a.K == 64) return launch_stem_lds_kb<2>(a, st);
+  if (pool) {
+    // linked max-pooling: windows of 2 or 3, stride 2, padding 0 or 1; pph x ppw windows per tile whose convolution block
+    // is at most 128 pixels; every window starts inside the map
+    if (a.pool != POOL_MAX || a.pk < 2 || a.pk > 3 || a.ps != 2 || a.pp < 0 || a.pp > 1 || a.pph < 1 || a.ppw < 1 || CH * CW > 32 * SL_NW ||
+        a.PH < 1 || a.PW < 1 || (a.PH - 1) * a.ps - a.pp >= a.OH || (a.PW - 1) * a.ps - a.pp >= a.OW ||
+        a.tiles_y != (a.PH + a.pph - 1) / a.pph || a.tiles_x != (a.PW + a.ppw - 1) / a.ppw || a.tiles_m != a.N * a.tiles_y * a.tiles_x)
+      return (int)hipErrorInvalidValue;
+    if (a.K == 32) return launch_stem_lds_kb<1, true>(a, st);
+    if (a.K == 64) return launch_stem_lds_kb<2, true>(a, st);
+    return (int)hipErrorInvalidValue;
+  }
+  if (a.mode != M_FLAT || a.th != SL_TH || a.tw != SL_TW || a.tiles_y != (a.OH + SL_TH - 1) / SL_TH || a.tiles_x != (a.OW + SL_TW - 1) / SL_TW ||
+      a.tiles_m != a.N * a.tiles_y * a.tiles_x)
+    return (int)hipErrorInvalidValue;
+  if (a.K == 32) return launch_stem_lds_kb<1, false>(a, st);
+  if (a.K == 64) return launch_stem_lds_kb<2, false>(a, st);
   return (int)hipErrorInvalidValue;
 }
 

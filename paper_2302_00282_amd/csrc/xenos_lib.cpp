@@ -448,9 +448,13 @@ struct Planner {
   xenos_status split_conv(Step& st) {
     ConvArgs& c = st.conv;
     const int num_cu = std::max(1, p.hw.num_cu);
-    if (st.stem && st.stem_lds) {   // tiles of 8 x 16 output pixels of one image, persistent workgroups
+    if (st.stem && st.stem_lds) {   // tiles of 8 x 16 output pixels (3 x 8 pooling windows) of one image, persistent workgroups
       c.th = kStemLdsTh; c.tw = kStemLdsTw;
       c.tiles_y = (c.OH + c.th - 1) / c.th; c.tiles_x = (c.OW + c.tw - 1) / c.tw;
+      if (c.pool != POOL_NONE) {
+        c.pph = kStemLdsPph; c.ppw = kStemLdsPpw;
+        c.tiles_y = (c.PH + c.pph - 1) / c.pph; c.tiles_x = (c.PW + c.ppw - 1) / c.ppw;
+      }
       c.tiles_m = c.N * c.tiles_y * c.tiles_x; c.tiles_n = 1; c.ntiles = c.tiles_m; c.xcd_m = 8;
       c.grid = p.opts.split ? std::max(1, std::min(c.tiles_m, 4 * num_cu)) : 1;
       st.cfg = kStemLdsCfg;
@@ -843,15 +847,33 @@ struct Planner {
       // epilogue, so a pooling that follows it runs as its own pass over the (NHWC, compute-type) result.  Measured
       // on the 7x7/2 + 3x3/2-pool and 3x3/2 + 3x3/2-pool first layers, the two passes take about a third of the time
       // of import + a pooled gather chain.
-      bool stem = false;
+      bool stem = false, stem_lds = false;
       if (!dw && !is_fc && nd.in[0] == 0 && in_lazy && link >= 2 && !has_res && is.c * d.kh * d.kw <= kStemRed && (K == 32 || K == 64) &&
           is.h <= 8192 && (p.opts.tile == 0 || p.opts.tile == kStemCfg + 1)) {
         // l2 = last node of the chain without its pooling, c2 = that node's output tensor
         const int l2 = pool_node < 0 ? last : absorbed.size() >= 2 ? absorbed[absorbed.size() - 2] : i;
         const int c2 = l2 + 1;
-        if (c2 != out_tid && !placed.count(c2)) {
+        // The kernel that stages the input block in LDS (bf16 path, fp32 NCHW input with unit stride along W, at most 4
+        // channels, square kernel of 4x4 to 7x7, stride 1 or 2; measured at batch 32: 7x7 / 2 on 224x224 0.043 ms against
+        // 0.077 ms for the gather form, while 3x3 kernels, 9 gathers per pixel and channel, are faster on the gather form)
+        // takes a linked max-pooling of 2 or 3 wide windows at stride 2: 3 x 8 windows per tile, their convolution block
+        // recomputed per tile.
+        const View& gv = p.views[tview[0]];
+        stem_lds = p.dt == DT_BF16 && p.opts.tile == 0 && is.c <= 4 && d.kh == d.kw && d.kh >= 4 && d.kh <= 7 && d.stride_h == d.stride_w &&
+                   (d.stride_h == 1 || d.stride_h == 2) && d.pad_h == d.pad_w && d.pad_h <= d.kh && gv.f32 && gv.sP == 1;
+        bool keep_pool = false;
+        if (stem_lds && pool_node >= 0 && !placed.count(cur) && cur != out_tid) {
+          const xenos_op_desc& pd = desc(nodes[pool_node]);
+          const int chh = (kStemLdsPph - 1) * 2 + pd.kh, cww = (kStemLdsPpw - 1) * 2 + pd.kw;
+          keep_pool = pd.kind == XENOS_OP_MAXPOOL && pd.kh == pd.kw && (pd.kh == 2 || pd.kh == 3) && pd.stride_h == 2 && pd.stride_w == 2 &&
+                      pd.pad_h == pd.pad_w && pd.pad_h >= 0 && pd.pad_h <= 1 && chh * cww <= kStemLdsTh * kStemLdsTw &&
+                      ((chh - 1) * d.stride_h + d.kh) * ((cww - 1) * d.stride_h + d.kw) <= kStemLdsInMax;
+        }
+        if (keep_pool || (c2 != out_tid && !placed.count(c2))) {
           stem = true;
-          if (pool_node >= 0) { absorbed.pop_back(); pool_node = -1; cur = c2; last = l2; }
+          if (pool_node >= 0 && !keep_pool) { absorbed.pop_back(); pool_node = -1; cur = c2; last = l2; }
+        } else {
+          stem_lds = false;
         }
       }
       for (int a : absorbed) st.ops.push_back(nodes[a].src);
@@ -952,13 +974,7 @@ struct Planner {
         if (!from_dw && nd.in[0] == 0 && in_lazy) {
           st.stem = stem;
           if (!st.stem && !in_gather) import_input();
-          // (bf16 path, fp32 NCHW input with unit stride along W, at most 4 channels, square kernel of 4x4 to 7x7, stride 1 or
-          // 2: the input block of a tile is staged in LDS instead of gathered element by element from memory.  Measured at
-          // batch 32: 7x7 / 2 on 224x224 0.043 ms against 0.077 ms; 3x3 kernels, 9 gathers per pixel and channel, are faster
-          // on the gather form, 0.027 against 0.036 ms for 3x3 / 2 and 0.078 against 0.090 ms for 3x3 / 1)
-          const View& gv = p.views[tview[0]];
-          st.stem_lds = st.stem && p.dt == DT_BF16 && p.opts.tile == 0 && is.c <= 4 && d.kh == d.kw && d.kh >= 4 && d.kh <= 7 && d.stride_h == d.stride_w &&
-                        (d.stride_h == 1 || d.stride_h == 2) && d.pad_h == d.pad_w && d.pad_h <= d.kh && gv.f32 && gv.sP == 1;
+          st.stem_lds = st.stem && stem_lds;
         }
         const int vin = from_dw ? pro.v_in : from_pair ? tview[0] : tview[nd.in[0]];
         if (vin < 0) return fail(XENOS_EINVAL, "%s: input not materialised", st.name.c_str());

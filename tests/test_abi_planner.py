@@ -118,9 +118,13 @@ def test_linking_patterns_of_the_workloads():
     convs = [c for c in res["chains"] if c["kind"] == "conv"]
     # every shortcut add is executed by a conv chain (in its epilogue, or in the summing pass of a reduction split)
     assert sum(any(g2.ops[o].kind == "add" for o in c["ops"]) for c in convs) == 8
-    # the 7x7/2 first layer reads the caller's NCHW tensor in place; its 3x3/2 max-pool is the only stand-alone pass
-    assert convs[0]["loader"] == "stem" and res["chains"][1]["kind"] == "pool"
-    assert all(c["kind"] in ("conv", "splitk_finish") for c in res["chains"][2:])
+    # the 7x7/2 first layer reads the caller's NCHW tensor in place with its 3x3/2 max-pool linked (CBRM): no pass of its own
+    assert convs[0]["loader"] == "stem" and any(g2.ops[o].kind == "maxpool" for o in convs[0]["ops"]) and convs[0]["pool"] != 0
+    assert all(c["kind"] in ("conv", "splitk_finish") for c in res["chains"])
+    # (on the fp32 path the first layer gathers from memory and its pooling is the only stand-alone pass)
+    r32 = plan_json(g2, link=2, compute=X.XENOS_F32)["plan"]
+    assert r32["chains"][0]["loader"] == "stem" and r32["chains"][1]["kind"] == "pool"
+    assert all(c["kind"] in ("conv", "splitk_finish") for c in r32["chains"][2:])
     # last block + global average (CBRA): at batch 1 through the summing pass of a reduction split, at batch 32 in the
     # convolution's own epilogue; either way the average is an operator of that chain, not a pass of its own
     assert any(g2.ops[o].kind == "gap" for o in convs[-2]["ops"]) and convs[-2]["mode"] == "flat"
@@ -156,8 +160,11 @@ def test_split_covers_the_output_and_fits_private_memory(cfg, batch, compute):
             assert c["th"] * c["tw"] <= c["bm"] == 256
             assert c["tiles_m"] == -(-(c["N"] * (c["H"] + 2)) // c["th"]) * -(-c["W"] // c["tw"])
         elif c["loader"] == "stem" and c["bm"] == 128:
-            # first layer with its input block staged on chip: 8 x 16 tiles of output pixels per image
-            assert c["tiles_m"] == c["N"] * -(-c["OH"] // 8) * -(-c["OW"] // 16)
+            # first layer with its input block staged on chip: 8 x 16 tiles of output pixels (3 x 8 pooling windows) per image
+            if c["pool"]:
+                assert c["tiles_m"] == c["N"] * -(-c["PH"] // 3) * -(-c["PW"] // 8)
+            else:
+                assert c["tiles_m"] == c["N"] * -(-c["OH"] // 8) * -(-c["OW"] // 16)
         elif c["mode"] == "flat":
             m = c["N"] * c["OH"] * c["OW"]
             assert c["tiles_m"] * c["bm"] >= m > (c["tiles_m"] - 1) * c["bm"]
