@@ -53,7 +53,8 @@ static const int kFcChannels = 128;
 static const int kStemLdsCfg = 8;
 static const int kStemLdsPph = 3, kStemLdsPpw = 8;   // pooling windows per tile when a max-pooling is linked
 static const int kStemLdsTh = 8, kStemLdsTw = 16, kStemLdsInMax = 784;   // (7 * 2 + 7) x (15 * 2 + 7) = 777 positions at most
-static const int kFcWgPerCu = 1;    // workgroups per compute unit the reduction split of such a chain aims at
+static const int kFcWgPerCu = 1;
+static const int kFcDirectSteps = 16;   // reductions of at most this many 64-element steps are not shared out (no summing pass)    // workgroups per compute unit the reduction split of such a chain aims at
 static const int kPairChannels = 64, kPairRed = 48;
 static const int kPairRows = 128, kPairPatchMax = 180;   // output pixels and patch positions ((TH+2) x 18) of a tile
 static const int kPairInMax = 256;   // positions of the staged block of the graph input, (TH+4) x (TW+4) plus slack for the pitch columns

@@ -1544,6 +1544,22 @@ __global__ __launch_bounds__(FC_NT, 2) void fc_stream_kernel(const ConvArgs a) {
     }
   }
   // accumulator rows = channels, columns = images: this lane holds 4 groups of 4 consecutive channels of image l31
+  if (a.ksplit < 1) {
+    // short reduction, not shared out: the chain's epilogue runs here and no summing pass follows
+    if (l31 < a.M_total) {
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const int k = k0 + (e >> 2) * 8 + lhalf * 4 + (e & 3);
+        if (k < a.K) {
+          float v = acc[e] * a.scale[k] + a.shift[k];
+          if (a.relu) v = fmaxf(v, 0.f);
+          const long long o = (long long)l31 * a.out_sN + (long long)k * a.out_sK;
+          if (a.out_f32) ((float*)a.out)[o] = v; else ((uint16_t*)a.out)[o] = f2bf(v);
+        }
+      }
+    }
+    return;
+  }
   if (l31 < a.M_total) {
     float* dst = a.part + ((long long)z * a.M_total + l31) * a.part_ld + k0;
 #pragma unroll
@@ -1557,9 +1573,10 @@ static int launch_fc(const ConvArgs& a, int dtype, hipStream_t st) {
   if (dtype != DT_BF16 || a.mode != M_FLAT || a.OH != 1 || a.OW != 1 || a.R != a.H || a.S != a.W || a.pad != 0 || a.M_total < 1 || a.M_total > 32 ||
       a.M_total != a.N || a.kchunk || a.Kred != a.R * a.S * a.C || a.Kred_pad != a.Kred || a.Kred % 64 != 0 || a.in_f32 || a.dw_w || a.pair ||
       (a.H * a.W > 1 && (a.in_sW != a.C || a.in_sH != (long long)a.W * a.C)) || a.in_sN < a.Kred || a.in_sN % 8 != 0 || ((uintptr_t)a.in & 15) != 0 ||
-      a.ksplit < 1 || a.steps_per_split < 1 || (long long)a.ksplit * a.steps_per_split < a.Kred_pad / 64 || !a.part ||
-      a.tiles_n != (a.K + FC_BN - 1) / FC_BN || a.part_ld < a.tiles_n * FC_BN || a.part_ld % 4 != 0 || ((uintptr_t)a.part & 15) != 0 ||
-      a.grid != a.tiles_n * a.ksplit)
+      a.steps_per_split < 1 || a.tiles_n != (a.K + FC_BN - 1) / FC_BN ||
+      (a.ksplit >= 1 && ((long long)a.ksplit * a.steps_per_split < a.Kred_pad / 64 || !a.part || a.part_ld < a.tiles_n * FC_BN || a.part_ld % 4 != 0 ||
+                         ((uintptr_t)a.part & 15) != 0 || a.grid != a.tiles_n * a.ksplit)) ||
+      (a.ksplit < 1 && (a.steps_per_split < a.Kred_pad / 64 || a.grid != a.tiles_n || a.has_res || !a.out || !a.scale || !a.shift)))
     return (int)hipErrorInvalidValue;
   hipLaunchKernelGGL(fc_stream_kernel, dim3(a.grid), dim3(FC_NT), 0, st, a);
   return (int)hipGetLastError();

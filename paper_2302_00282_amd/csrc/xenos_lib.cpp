@@ -1105,6 +1105,14 @@ struct Planner {
           const int fc_tiles = (K + kFcChannels - 1) / kFcChannels;
           // (two workgroups per unit, each with at least 4 steps = 32 KB of weights to stream)
           if (st.fc_stream) ks = std::max(1, std::min((kFcWgPerCu * std::max(1, p.hw.num_cu) + fc_tiles - 1) / fc_tiles, nsteps / 4));
+          if (st.fc_stream && nsteps <= kFcDirectSteps && !has_res) {
+            // short reduction: one share per channel tile, epilogue in the streaming kernel, no summing pass (one launch
+            // fewer where launches are what a pass costs: the classifier of a batch-1 network)
+            st.cands.clear();
+            st.cfg = kFcCfg; st.lds = 0;
+            a.ksplit = 0; a.steps_per_split = nsteps;
+            a.tiles_m = 1; a.tiles_n = fc_tiles; a.ntiles = fc_tiles; a.xcd_m = 1; a.grid = fc_tiles;
+          } else
           if (st.fc_stream || ks >= 4 || st.gap_finish) {
             const int spk = (nsteps + ks - 1) / ks;
             ks = (nsteps + spk - 1) / spk;
