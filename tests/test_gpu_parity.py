@@ -449,23 +449,28 @@ def test_full_size_batch32_sampled_images(cfg, compute, images):
     # does not depend on its batch neighbours, so the oracle checks sampled images one by one
     g = wg.build(cfg, 32)
     X = _xenos()
-    s = X.Session(g, link=2, split=1, compute=compute)
-    try:
-        y = s.forward(g.x)                      # eager launches
-        s.y.zero_()
-        s.run_graph()
-        yg = s.output()                          # HIP-graph replay of the same plan
-    finally:
-        s.close()
-    assert np.array_equal(y, yg)
-    worst = 0.0
-    for n in images:
-        ref = xo.forward(g, g.x[n:n + 1])
-        e = rel_err(y[n:n + 1], ref)
-        worst = max(worst, e)
-        assert e <= TOL[compute], (g.name, n, e)
-    assert np.isfinite(y).all()
-    print(f"{g.name} batch 32 compute={compute} sampled images {images}: worst rel_err={worst:.3e}", flush=True)
+    refs = {n: xo.forward(g, g.x[n:n + 1]) for n in images}
+    # link level 3 where it plans other chains than level 2 (VGG-style: the first two convolutions as one chain; the
+    # bench headline runs at that level)
+    for link in ((2, 3) if cfg == 3 else (2,)):
+        s = X.Session(g, link=link, split=1, compute=compute)
+        try:
+            y = s.forward(g.x)                      # eager launches
+            s.y.zero_()
+            s.run_graph()
+            yg = s.output()                          # HIP-graph replay of the same plan
+            loaders = [c.get("loader") for c in s.info["chains"]]
+        finally:
+            s.close()
+        assert np.array_equal(y, yg)
+        assert (link == 3) == ("pair" in loaders)
+        worst = 0.0
+        for n in images:
+            e = rel_err(y[n:n + 1], refs[n])
+            worst = max(worst, e)
+            assert e <= TOL[compute], (g.name, link, n, e)
+        assert np.isfinite(y).all()
+        print(f"{g.name} batch 32 compute={compute} link={link} sampled images {images}: worst rel_err={worst:.3e}", flush=True)
 
 
 @pytest.mark.parametrize("name", sorted(wg.TABLE4))
