@@ -71,6 +71,17 @@ template <> struct Tr<bf16_t> {
   }
 };
 
+// max(a, b).  `fmaxf` must quiet signalling NaNs, which costs an extra `v_max x, x, x` per operand whose origin the compiler
+// cannot see: values moved between lanes by DPP or unpacked from bf16 with bit operations, i.e. every operand of the
+// pooling reductions (two thirds of their instructions).  fmx_raw is the bare instruction for those places; NaN inputs are
+// outside the contract of the library.
+__device__ __forceinline__ float fmx(float a, float b) { return __builtin_fmaxf(a, b); }
+__device__ __forceinline__ float fmx_raw(float a, float b) {
+  float r;
+  asm("v_max_f32 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+  return r;
+}
+
 constexpr int NT = 256;          // threads per workgroup (4 wavefronts of 64)
 constexpr int ROWB = kRowBytes;  // data bytes per tile row per reduction step
 constexpr int CPR = ROWB / 16;   // 16-byte chunks per tile row
@@ -274,7 +285,7 @@ __global__ __launch_bounds__(NT, 2) void conv_kernel(const ConvArgs a) {
 #pragma unroll
               for (int e = 0; e < CE; ++e) {
                 const float v = d[e] * a.dw_scale[kc + e] + a.dw_shift[kc + e];
-                d[e] = a.dw_relu ? fmaxf(v, 0.f) : v;
+                d[e] = a.dw_relu ? fmx(v, 0.f) : v;
               }
             } else {
 #pragma unroll
@@ -463,7 +474,7 @@ __global__ __launch_bounds__(NT, 2) void conv_kernel(const ConvArgs a) {
             }
             if (a.relu) {
 #pragma unroll
-              for (int e = 0; e < CE; ++e) v[e] = fmaxf(v[e], 0.f);
+              for (int e = 0; e < CE; ++e) v[e] = fmx(v[e], 0.f);
             }
           } else if (MODE == M_ZIGZAG) {
             const int wdx = ((tile_m * BM) >> 2) + q;
@@ -480,8 +491,8 @@ __global__ __launch_bounds__(NT, 2) void conv_kernel(const ConvArgs a) {
 #pragma unroll
               for (int e = 0; e < CE; ++e) {
                 float x = u[e] * sc[e] + sh[e];
-                if (a.relu) x = fmaxf(x, 0.f);
-                v[e] = j == 0 ? x : (a.pool == POOL_MAX ? fmaxf(v[e], x) : v[e] + x);
+                if (a.relu) x = fmx(x, 0.f);
+                v[e] = j == 0 ? x : (a.pool == POOL_MAX ? fmx_raw(v[e], x) : v[e] + x);
               }
             }
             if (a.pool == POOL_AVG) {
@@ -510,8 +521,8 @@ __global__ __launch_bounds__(NT, 2) void conv_kernel(const ConvArgs a) {
 #pragma unroll
                 for (int e = 0; e < CE; ++e) {
                   float x = u[e] * sc[e] + sh[e];
-                  if (a.relu) x = fmaxf(x, 0.f);
-                  mx[e] = fmaxf(mx[e], x); sum[e] += x;
+                  if (a.relu) x = fmx(x, 0.f);
+                  mx[e] = fmx_raw(mx[e], x); sum[e] += x;
                 }
                 ++cnt;
               }
@@ -539,7 +550,7 @@ __global__ __launch_bounds__(NT, 2) void conv_kernel(const ConvArgs a) {
           if (mc * BM + row >= OHW) break;
           float x = stg[row * SP + col] * sc + sh;
           if (a.has_res && k < a.K) x += tr::ld(a.res, (long long)img * a.res_sN + (long long)(mc * BM + row) * a.res_sP + k);
-          if (a.relu) x = fmaxf(x, 0.f);
+          if (a.relu) x = fmx(x, 0.f);
           gsum += x;
         }
       }
@@ -1003,16 +1014,16 @@ __global__ __launch_bounds__(V2_NT) void conv3x3_kernel(const ConvArgs a) {
               }
             }
 #pragma unroll
-            for (int e = 0; e < 4; ++e) y[e] = fmaxf(y[e], lo);
+            for (int e = 0; e < 4; ++e) y[e] = fmx(y[e], lo);
             bool mine = true;                                      // does this lane hold the finished value?
             if (MODE == M_ZIGZAG) {
               // the window's four pixels are lanes 4w .. 4w+3: butterfly over the quad, lane j keeps group g == j
 #pragma unroll
               for (int e = 0; e < 4; ++e) {
                 const float p1 = quad_perm<0xB1>(y[e]);            // lanes [1,0,3,2]
-                y[e] = PMAX ? fmaxf(y[e], p1) : y[e] + p1;
+                y[e] = PMAX ? fmx_raw(y[e], p1) : y[e] + p1;
                 const float p2 = quad_perm<0x4E>(y[e]);            // lanes [2,3,0,1]
-                y[e] = PMAX ? fmaxf(y[e], p2) : (y[e] + p2) * 0.25f;
+                y[e] = PMAX ? fmx_raw(y[e], p2) : (y[e] + p2) * 0.25f;
               }
               mine = (l31 & 3) == g;
             }
@@ -1366,11 +1377,10 @@ __global__ __launch_bounds__(PR_NT, 2) void conv_pair_kernel(const ConvArgs a) {
       for (int e = 0; e < 16; ++e) c1[e] = 0.f;
 #pragma unroll
       for (int j = 0; j < 3; ++j) {
+        // (taps beyond the ninth read position 0 of the window: their weight slots are zero and the block holds finite values)
         const int o0 = tap_off(j, 0), o1 = tap_off(j, 1);
-        uint2 t0 = *(const uint2*)(xb + (o0 >= 0 ? o0 : 0));
-        uint2 t1 = *(const uint2*)(xb + (o1 >= 0 ? o1 : 0));
-        if (o0 < 0) t0 = uint2{0u, 0u};
-        if (o1 < 0) t1 = uint2{0u, 0u};
+        const uint2 t0 = *(const uint2*)(xb + (o0 >= 0 ? o0 : 0));
+        const uint2 t1 = *(const uint2*)(xb + (o1 >= 0 ? o1 : 0));
         const u32x4_t fa = {t0.x, t0.y, t1.x, t1.y};
         c1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, w1[j]), __builtin_bit_cast(bf16x8_t, fa), c1, 0, 0, 0);
       }
@@ -1385,13 +1395,10 @@ __global__ __launch_bounds__(PR_NT, 2) void conv_pair_kernel(const ConvArgs a) {
           const f32x4_t sc = *(const f32x4_t*)(s_aff + c), sh = *(const f32x4_t*)(s_aff + PR_C + c);
           float y[4];
 #pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            y[e] = fmaxf(c1[4 * g + e] * sc[e] + sh[e], lo1);
-            y[e] = inside ? y[e] : 0.f;                            // padding of the second convolution
-          }
+          for (int e = 0; e < 4; ++e) y[e] = fmx(c1[4 * g + e] * sc[e] + sh[e], lo1);
           uint2 o;
-          o.x = f2bf2(y[0], y[1]);
-          o.y = f2bf2(y[2], y[3]);
+          o.x = inside ? f2bf2(y[0], y[1]) : 0u;                   // positions outside the image: padding of the second convolution
+          o.y = inside ? f2bf2(y[2], y[3]) : 0u;
           *(uint2*)(s_patch + p * LDS_ROW + c * 2) = o;
         }
       }
@@ -1437,16 +1444,16 @@ __global__ __launch_bounds__(PR_NT, 2) void conv_pair_kernel(const ConvArgs a) {
         const f32x4_t sc = *(const f32x4_t*)(s_aff + 2 * PR_C + c), sh = *(const f32x4_t*)(s_aff + 3 * PR_C + c);
         float y[4];
 #pragma unroll
-        for (int e = 0; e < 4; ++e) y[e] = fmaxf(acc[i][4 * g + e] * sc[e] + sh[e], lo2);
+        for (int e = 0; e < 4; ++e) y[e] = fmx(acc[i][4 * g + e] * sc[e] + sh[e], lo2);
         bool mine = true;
         if (MODE == M_ZIGZAG) {
           // the window's four pixels are lanes 4w .. 4w+3: butterfly over the quad, lane i keeps group g == i
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
             const float p1 = quad_perm<0xB1>(y[e]);
-            y[e] = PMAX ? fmaxf(y[e], p1) : y[e] + p1;
+            y[e] = PMAX ? fmx_raw(y[e], p1) : y[e] + p1;
             const float p2 = quad_perm<0x4E>(y[e]);
-            y[e] = PMAX ? fmaxf(y[e], p2) : (y[e] + p2) * 0.25f;
+            y[e] = PMAX ? fmx_raw(y[e], p2) : (y[e] + p2) * 0.25f;
           }
           mine = (l31 & 3) == g;
         }
@@ -1552,7 +1559,7 @@ __global__ __launch_bounds__(FC_NT, 2) void fc_stream_kernel(const ConvArgs a) {
         const int k = k0 + (e >> 2) * 8 + lhalf * 4 + (e & 3);
         if (k < a.K) {
           float v = acc[e] * a.scale[k] + a.shift[k];
-          if (a.relu) v = fmaxf(v, 0.f);
+          if (a.relu) v = fmx(v, 0.f);
           const long long o = (long long)l31 * a.out_sN + (long long)k * a.out_sK;
           if (a.out_f32) ((float*)a.out)[o] = v; else ((uint16_t*)a.out)[o] = f2bf(v);
         }
@@ -1724,7 +1731,7 @@ __global__ __launch_bounds__(NT, sizeof(T) == 2 ? 4 : 2) void stem_kernel(const 
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
           y[j] = acc[b][4 * g + j] * sc[j] + sh[j];
-          if (a.relu) y[j] = fmaxf(y[j], 0.f);
+          if (a.relu) y[j] = fmx(y[j], 0.f);
         }
         if constexpr (sizeof(T) == 2) {
           uint2 o;
@@ -1886,10 +1893,9 @@ __global__ __launch_bounds__(SL_NT, 2) void stem_lds_kernel(const ConvArgs a) {
 #pragma unroll
     for (int j = 0; j < NSTEP; ++j) {
       const int2 t = s_tap[j][lhalf];
-      uint2 t0 = *(const uint2*)(s_xin + xbase + (t.x >= 0 ? t.x : 0));
-      uint2 t1 = *(const uint2*)(s_xin + xbase + (t.y >= 0 ? t.y : 0));
-      if (t.x < 0) t0 = uint2{0u, 0u};
-      if (t.y < 0) t1 = uint2{0u, 0u};
+      // (slots beyond the last tap read position 0 of the window: their weights are zero and the block holds finite values)
+      const uint2 t0 = *(const uint2*)(s_xin + xbase + (t.x >= 0 ? t.x : 0));
+      const uint2 t1 = *(const uint2*)(s_xin + xbase + (t.y >= 0 ? t.y : 0));
       const u32x4_t fa = {t0.x, t0.y, t1.x, t1.y};
 #pragma unroll
       for (int b = 0; b < KB; ++b)
@@ -1907,7 +1913,7 @@ __global__ __launch_bounds__(SL_NT, 2) void stem_lds_kernel(const ConvArgs a) {
         const f32x4_t sc = *(const f32x4_t*)&s_aff[c0], sh = *(const f32x4_t*)&s_aff[K + c0];
         float y[4];
 #pragma unroll
-        for (int e = 0; e < 4; ++e) y[e] = fmaxf(acc[b][4 * g + e] * sc[e] + sh[e], lo);
+        for (int e = 0; e < 4; ++e) y[e] = fmx(acc[b][4 * g + e] * sc[e] + sh[e], lo);
         uint2 o;
         o.x = f2bf2(y[0], y[1]);
         o.y = f2bf2(y[2], y[3]);
@@ -1930,7 +1936,7 @@ __global__ __launch_bounds__(SL_NT, 2) void stem_lds_kernel(const ConvArgs a) {
             float v[8];
             Tr<bf16_t>::unpack(*(const u32x4_t*)(s_stage + ((wy * a.ps + i) * CW + wx * a.ps + j) * SPITCH + ch * 16), v);
 #pragma unroll
-            for (int e = 0; e < 8; ++e) m[e] = fmaxf(m[e], v[e]);
+            for (int e = 0; e < 8; ++e) m[e] = fmx_raw(m[e], v[e]);
           }
         *(u32x4_t*)((unsigned char*)a.out + ((long long)n * a.out_sN + (long long)(py * a.PW + px) * a.out_sP) * 2 + ch * 16) = Tr<bf16_t>::pack(m);
       }
@@ -2120,7 +2126,7 @@ __global__ __launch_bounds__(NT) void dwpw_kernel(const ConvArgs a) {
 #pragma unroll
         for (int e = 0; e < CE; ++e) {
           float y = d[e] * sc[e] + sh[e];
-          if (a.dw_relu) y = fmaxf(y, 0.f);
+          if (a.dw_relu) y = fmx(y, 0.f);
           d[e] = valid ? y : 0.f;                                  // rows past the end and padding channels are exact zeros
         }
         *(u32x4_t*)(s_panel + px * PP + (c0 - p0) * ESZ) = tr::pack(d);
@@ -2202,7 +2208,7 @@ __global__ __launch_bounds__(NT) void dwpw_kernel(const ConvArgs a) {
       const f32x4_t sc = *(const f32x4_t*)(a.scale + k0), sh = *(const f32x4_t*)(a.shift + k0);
       float y[4];
 #pragma unroll
-      for (int e = 0; e < 4; ++e) y[e] = fmaxf(acc[4 * g + e] * sc[e] + sh[e], lo);
+      for (int e = 0; e < 4; ++e) y[e] = fmx(acc[4 * g + e] * sc[e] + sh[e], lo);
       const int srow = wave_m * 32 + l31;
       if constexpr (sizeof(T) == 2) {
         uint2 o;
@@ -2364,7 +2370,7 @@ __global__ __launch_bounds__(NT) void dw_kernel(const DwArgs a) {
 #pragma unroll
     for (int e = 0; e < CE; ++e) {
       float v = acc[e] * a.scale[c0 + e] + a.shift[c0 + e];
-      acc[e] = a.relu ? fmaxf(v, 0.f) : v;
+      acc[e] = a.relu ? fmx(v, 0.f) : v;
     }
     T* o = (T*)a.out + (long long)n * a.out_sN + ((long long)oh * a.OW + ow) * a.out_sP + c0;
     *(u32x4_t*)o = tr::pack(acc);
@@ -2411,7 +2417,7 @@ __global__ __launch_bounds__(NT) void splitk_finish_kernel(const SplitKArgs a) {
           for (int z = 0; z < a.ksplit; ++z) v += a.part[((long long)z * a.M + m) * a.part_ld + k];
           v = v * sc + sh;
           if (a.res) v += tr::ld(a.res, n * a.res_sN + p * a.res_sP + k);
-          if (a.relu) v = fmaxf(v, 0.f);
+          if (a.relu) v = fmx(v, 0.f);
           s += v;
         }
       }
@@ -2437,7 +2443,7 @@ __global__ __launch_bounds__(NT) void splitk_finish_kernel(const SplitKArgs a) {
     v = v * a.scale[k] + a.shift[k];
     const long long n = m / a.OHW, p = m - n * a.OHW;
     if (a.res) v += tr::ld(a.res, n * a.res_sN + p * a.res_sP + k);
-    if (a.relu) v = fmaxf(v, 0.f);
+    if (a.relu) v = fmx(v, 0.f);
     const long long o = n * a.out_sN + p * a.out_sP + (long long)k * a.out_sK;
     if (a.out_f32) ((float*)a.out)[o] = v; else tr::st(a.out, o, v);
   }
@@ -2465,7 +2471,7 @@ __global__ __launch_bounds__(NT) void elt_kernel(const EltArgs a) {
     float v = tr::ld(a.a, p * a.a_sP + c);
     if (a.op == ELT_AFFINE) v = v * a.scale[c] + a.shift[c];
     else if (a.op == ELT_ADD) v += tr::ld(a.b, p * a.b_sP + c);
-    if (a.relu || a.op == ELT_RELU) v = fmaxf(v, 0.f);
+    if (a.relu || a.op == ELT_RELU) v = fmx(v, 0.f);
     tr::st(a.out, p * a.out_sP + c, v);
   }
 }
@@ -2492,7 +2498,7 @@ __global__ __launch_bounds__(NT) void elt_vec_kernel(const EltArgs a) {
     }
     if (a.relu || a.op == ELT_RELU) {
 #pragma unroll
-      for (int e = 0; e < CE; ++e) v[e] = fmaxf(v[e], 0.f);
+      for (int e = 0; e < CE; ++e) v[e] = fmx(v[e], 0.f);
     }
     *(u32x4_t*)((T*)a.out + p * a.out_sP + c) = tr::pack(v);
   }
@@ -2543,7 +2549,7 @@ __global__ __launch_bounds__(NT) void pool_kernel(const PoolArgs a) {
           if (ih < a.H + a.p && iw < a.W + a.p) ++cntp;
           if (ih < 0 || ih >= a.H || iw < 0 || iw >= a.W) continue;
           const float v = tr::ld(a.in, ib + ((long long)ih * a.W + iw) * a.in_sP);
-          mx = fmaxf(mx, v); sum += v; ++cnt;
+          mx = fmx_raw(mx, v); sum += v; ++cnt;
         }
       r = a.kind == POOL_MAX ? mx : sum / (float)(a.cip ? cntp : cnt);
     }
@@ -2577,7 +2583,7 @@ __global__ __launch_bounds__(NT) void pool_vec_kernel(const PoolArgs a) {
         float v[CE];
         tr::unpack(*(const u32x4_t*)(ib + ((long long)ih * a.W + iw) * a.in_sP), v);
 #pragma unroll
-        for (int e = 0; e < CE; ++e) { mx[e] = fmaxf(mx[e], v[e]); sum[e] += v[e]; }
+        for (int e = 0; e < CE; ++e) { mx[e] = fmx_raw(mx[e], v[e]); sum[e] += v[e]; }
         ++cnt;
       }
     float r[CE];
