@@ -691,15 +691,23 @@ __global__ __launch_bounds__(V2_NT) void conv3x3_kernel(const ConvArgs a) {
     const int tile_m = m0 + l % mlen;
     const int tyi = tile_m / a.tiles_x;
     const int q0 = tyi * a.th, x0 = (tile_m - tyi * a.tiles_x) * a.tw;
+    // image and row of a stacked row: one division per tile (uniform), then compares per chunk as long as a patch spans
+    // at most four images (this runs between the MFMA streams of two tiles: with one channel chunk per tile it was a tenth
+    // of the tile's time when every chunk divided)
+    const int n0 = q0 / Hp, r0 = q0 - n0 * Hp;
+    const bool few = a.th + 2 <= 3 * Hp;
+    const int sN = (int)a.in_sN, sH = (int)a.in_sH, sW = (int)a.in_sW;   // (N * in_sN < 2^31 is checked by the host)
     aok = 0;
 #pragma unroll
     for (int it = 0; it < A_IT; ++it) {
       const int idx = tid + it * NTH;
       const int pp = idx / CPR, c8 = idx % CPR;
       const int pr = pp / PW_, pc = pp - pr * PW_;
-      const int P = q0 + pr, n = P / Hp, ih = P - n * Hp - 1, iw = x0 - 1 + pc;
+      const int rel = r0 + pr;
+      const int k = few ? (rel >= Hp ? 1 : 0) + (rel >= 2 * Hp ? 1 : 0) + (rel >= 3 * Hp ? 1 : 0) : rel / Hp;
+      const int n = n0 + k, ih = rel - k * Hp - 1, iw = x0 - 1 + pc;
       const bool ok = pp < PP && n < a.N && (unsigned)ih < (unsigned)a.H && (unsigned)iw < (unsigned)a.W;
-      aoff[it] = ok ? (int)((long long)n * a.in_sN + (long long)ih * a.in_sH + (long long)iw * a.in_sW) + c8 * CE : c8 * CE;
+      aoff[it] = ok ? n * sN + ih * sH + iw * sW + c8 * CE : c8 * CE;
       aok |= (ok ? 1u : 0u) << it;
     }
   };
@@ -1131,6 +1139,7 @@ static int launch_conv3x3_t(const ConvArgs& a, hipStream_t st) {
   if (a.R != 3 || a.S != 3 || a.stride != 1 || a.pad != 1 || !a.kchunk || a.C % Tr<T>::BKE != 0 || a.C < Tr<T>::BKE || a.th < 1 || a.tw < 1 ||
       a.th * a.tw > V2_BM || a.tiles_m != a.tiles_y * a.tiles_x || (a.halo_bn != 64 && a.halo_bn != 128) ||
       a.tiles_n != (a.K + a.halo_bn - 1) / a.halo_bn || a.ksplit >= 1 || a.dw_w || !a.vec_out || (a.has_res && !a.vec_res) ||
+      (long long)a.N * a.in_sN >= (1ll << 31) || a.in_sN < 0 || a.in_sH < 0 || a.in_sW < 0 ||
       (a.mode == M_ZIGZAG && (((a.th | a.tw | a.H | a.W) & 1) || a.has_res)))
     return (int)hipErrorInvalidValue;
   if (a.mode == M_FLAT) return a.halo_bn == 128 ? launch_conv3x3_inst<T, M_FLAT, 128>(a, st) : launch_conv3x3_inst<T, M_FLAT, 64>(a, st);
