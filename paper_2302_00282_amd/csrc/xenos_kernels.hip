@@ -621,6 +621,24 @@ template <int CTRL>
 __device__ __forceinline__ float quad_perm(float v) {
   return __int_as_float(__builtin_amdgcn_mov_dpp(__float_as_int(v), CTRL, 0xf, 0xf, true));
 }
+// One step of the reduction over a lane quad in ONE instruction: v (op) v of the lane that the quad permutation names
+// (the DPP modifier on the arithmetic instruction instead of a separate lane move).  SWAP1 = lanes [1,0,3,2], else [2,3,0,1].
+// The two wait states a DPP read needs after a VALU write of its source are inside the asm, where the compiler's hazard
+// recogniser does not look.
+template <bool SWAP1>
+__device__ __forceinline__ float quad_max(float v) {
+  float r;
+  if (SWAP1) asm("s_nop 1\n\tv_max_f32_dpp %0, %1, %1 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf" : "=v"(r) : "v"(v));
+  else asm("s_nop 1\n\tv_max_f32_dpp %0, %1, %1 quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf" : "=v"(r) : "v"(v));
+  return r;
+}
+template <bool SWAP1>
+__device__ __forceinline__ float quad_add(float v) {
+  float r;
+  if (SWAP1) asm("s_nop 1\n\tv_add_f32_dpp %0, %1, %1 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf" : "=v"(r) : "v"(v));
+  else asm("s_nop 1\n\tv_add_f32_dpp %0, %1, %1 quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf" : "=v"(r) : "v"(v));
+  return r;
+}
 
 // PWID = row pitch of the staged patch in pixels (compile time, so that every tap is an immediate LDS offset).
 // PWID = 0 selects the patch-linear form (pixel-major enumeration only): the pitch is TW + 2 at run time and GEMM row m
@@ -1028,10 +1046,8 @@ __global__ __launch_bounds__(V2_NT) void conv3x3_kernel(const ConvArgs a) {
               // the window's four pixels are lanes 4w .. 4w+3: butterfly over the quad, lane j keeps group g == j
 #pragma unroll
               for (int e = 0; e < 4; ++e) {
-                const float p1 = quad_perm<0xB1>(y[e]);            // lanes [1,0,3,2]
-                y[e] = PMAX ? fmx_raw(y[e], p1) : y[e] + p1;
-                const float p2 = quad_perm<0x4E>(y[e]);            // lanes [2,3,0,1]
-                y[e] = PMAX ? fmx_raw(y[e], p2) : (y[e] + p2) * 0.25f;
+                y[e] = PMAX ? quad_max<true>(y[e]) : quad_add<true>(y[e]);              // with lanes [1,0,3,2]
+                y[e] = PMAX ? quad_max<false>(y[e]) : quad_add<false>(y[e]) * 0.25f;   // with lanes [2,3,0,1]
               }
               mine = (l31 & 3) == g;
             }
@@ -1459,10 +1475,8 @@ __global__ __launch_bounds__(PR_NT, 2) void conv_pair_kernel(const ConvArgs a) {
           // the window's four pixels are lanes 4w .. 4w+3: butterfly over the quad, lane i keeps group g == i
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
-            const float p1 = quad_perm<0xB1>(y[e]);
-            y[e] = PMAX ? fmx_raw(y[e], p1) : y[e] + p1;
-            const float p2 = quad_perm<0x4E>(y[e]);
-            y[e] = PMAX ? fmx_raw(y[e], p2) : (y[e] + p2) * 0.25f;
+            y[e] = PMAX ? quad_max<true>(y[e]) : quad_add<true>(y[e]);
+            y[e] = PMAX ? quad_max<false>(y[e]) : quad_add<false>(y[e]) * 0.25f;
           }
           mine = (l31 & 3) == g;
         }
