@@ -848,8 +848,9 @@ struct Planner {
       // on the 7x7/2 + 3x3/2-pool and 3x3/2 + 3x3/2-pool first layers, the two passes take about a third of the time
       // of import + a pooled gather chain.
       bool stem = false, stem_lds = false;
-      if (!dw && !is_fc && nd.in[0] == 0 && in_lazy && link >= 2 && !has_res && is.c * d.kh * d.kw <= kStemRed && (K == 32 || K == 64) &&
-          is.h <= 8192 && (p.opts.tile == 0 || p.opts.tile == kStemCfg + 1)) {
+      // (the gather form takes reductions up to kStemRed elements, the LDS-staged form up to 4 channels x 7 x 7 taps)
+      if (!dw && !is_fc && nd.in[0] == 0 && in_lazy && link >= 2 && !has_res && (is.c * d.kh * d.kw <= kStemRed || (is.c <= 4 && d.kh <= 7 && d.kw <= 7)) &&
+          (K == 32 || K == 64) && is.h <= 8192 && (p.opts.tile == 0 || p.opts.tile == kStemCfg + 1)) {
         // l2 = last node of the chain without its pooling, c2 = that node's output tensor
         const int l2 = pool_node < 0 ? last : absorbed.size() >= 2 ? absorbed[absorbed.size() - 2] : i;
         const int c2 = l2 + 1;
@@ -869,7 +870,7 @@ struct Planner {
                       pd.pad_h == pd.pad_w && pd.pad_h >= 0 && pd.pad_h <= 1 && chh * cww <= kStemLdsTh * kStemLdsTw &&
                       ((chh - 1) * d.stride_h + d.kh) * ((cww - 1) * d.stride_h + d.kw) <= kStemLdsInMax;
         }
-        if (keep_pool || (c2 != out_tid && !placed.count(c2))) {
+        if ((stem_lds || is.c * d.kh * d.kw <= kStemRed) && (keep_pool || (c2 != out_tid && !placed.count(c2)))) {
           stem = true;
           if (pool_node >= 0 && !keep_pool) { absorbed.pop_back(); pool_node = -1; cur = c2; last = l2; }
         } else {

@@ -573,6 +573,53 @@ def _random_graph(seed):
     return b.finish(t)
 
 
+def _random_chip_resident_case(case):
+    """Seeded random shapes for the chains whose kernels keep something on chip that the general kernels stream: the linked
+    first-layer pair (link level 3), the first layer with its input block (and pooling) staged in LDS, the fully connected
+    weight-streaming kernel.  Returns (graph, loader name expected in the plan)."""
+    r = np.random.default_rng(7000 + case)
+    kind = ["pair", "stem", "fc"][case % 3]
+    if kind == "pair":
+        n, c, pool = int(r.integers(1, 6)), int(r.integers(1, 5)), int(r.integers(0, 3))
+        h, w = int(r.integers(4, 72)), int(r.integers(3, 72))
+        if pool:
+            h, w = h // 2 * 2, max(4, w // 2 * 2)
+        b = wg.builder("rpair", (n, c, h, w), 1000 + case, nonzero_bias=True)
+        t = b.cbr(0, 64, 3, 1, 1, name="c0", bn=bool(r.integers(0, 2)), relu=bool(r.integers(0, 2)))
+        t = b.cbr(t, 64, 3, 1, 1, name="c1", bn=bool(r.integers(0, 2)), relu=bool(r.integers(0, 2)))
+        t = b.maxpool(t, 2, 2) if pool == 1 else b.avgpool(t, 2, 2) if pool == 2 else t
+        return b.finish(b.cbr(t, 16, 1, name="c2")), "pair"
+    if kind == "stem":
+        n, c = int(r.integers(1, 5)), int(r.integers(1, 5))
+        ks, st, K = int(r.integers(4, 8)), int(r.integers(1, 3)), int(r.choice([32, 64]))
+        pad, hw, pool = int(r.integers(0, ks // 2 + 1)), int(r.integers(ks + 8, 90)), int(r.integers(0, 4))
+        b = wg.builder("rstem", (n, c, hw, hw), 2000 + case, nonzero_bias=True)
+        t = b.cbr(0, K, ks, st, pad, name="c0", bn=bool(r.integers(0, 2)), relu=bool(r.integers(0, 2)))
+        t = b.maxpool(t, 3, 2, 1) if pool == 1 else b.maxpool(t, 3, 2, 0, ceil=1) if pool == 2 else b.maxpool(t, 2, 2) if pool == 3 else t
+        return b.finish(b.cbr(t, 24, 3, 1, 1, name="c1")), "stem"
+    n, c, hw = int(r.integers(1, 33)), int(r.choice([8, 16, 64, 128])), int(r.choice([1, 2, 4, 7, 8]))
+    if (c * hw * hw) % 64 or c * hw * hw < 512:
+        c, hw = 64, 4
+    k1, k2 = int(r.choice([64, 128, 200, 1000, 1024, 520])), int(r.choice([10, 33, 128, 1000]))
+    b = wg.builder("rfc", (n, c, hw, hw), 3000 + case, nonzero_bias=True)
+    t = b.fc(b.cbr(0, c, 1, name="c0"), k1, "fc1")
+    t = b.relu(t) if r.integers(0, 2) else t
+    return b.finish(b.fc(t, k2, "fc2")), "stream"
+
+
+@pytest.mark.parametrize("case", range(36))
+def test_random_shapes_of_the_chip_resident_kernels(case):
+    g, want = _random_chip_resident_case(case)
+    ref = xo.forward(g)
+    y, info = check(g, ref, compute=1, link=3)
+    assert want in [ch.get("loader") for ch in info["chains"]]
+    ys, _ = run_gpu(g, compute=1, link=3, split=0)           # one workgroup walking every tile
+    if want == "stream":
+        assert rel_err(ys, ref) <= TOL[1]                    # (a different reduction split: compared with the oracle)
+    else:
+        assert np.array_equal(y, ys)
+
+
 @pytest.mark.parametrize("seed", range(48))
 def test_random_graphs_all_modes(seed):
     try:
