@@ -1186,7 +1186,6 @@ static int launch_conv3x3_t(const ConvArgs& a, hipStream_t st) {
 // fp32 input block of the next tile is fetched during P2.
 // ---------------------------------------------------------------------------------------------
 constexpr int PR_NW = 4, PR_NT = 64 * PR_NW;
-constexpr int PR_DEPHASE = 1;                 // start delay of the second workgroup of a unit, in sleeps of 127 x 64 cycles
 constexpr int PR_BM = kPairRows;              // GEMM rows (output pixels) of a tile
 constexpr int PR_PPMAX = kPairPatchMax;       // patch positions, (TH+2) x 18
 constexpr int PR_PW = kHaloPitchNarrow;       // patch row pitch in pixels
@@ -1232,14 +1231,6 @@ __global__ __launch_bounds__(PR_NT, 2) void conv_pair_kernel(const ConvArgs a) {
   const int m0 = xcd * a.tiles_m / nx, mlen = (xcd + 1) * a.tiles_m / nx - m0;
   int li = blockIdx.x / nx;
   if (li >= mlen) return;                                          // uniform per workgroup
-  // Two workgroups share a compute unit and would walk their tiles in lockstep (same start, same phase lengths), both in
-  // the MFMA-bound phase or both in the VALU-bound ones.  The later half of an XCD's workgroups (the second residents
-  // of its units) therefore starts about half a tile late, once.
-  if (PR_DEPHASE && 2 * li >= wgs && wgs > 1) {
-#pragma unroll 1
-    for (int i = 0; i < PR_DEPHASE; ++i) __builtin_amdgcn_s_sleep(127);
-  }
-
   // ---- resident weights: this wavefront's 32 channels -------------------------------------------------------------
   u32x4_t w2[36], w1[3];
   {
