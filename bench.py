@@ -166,6 +166,9 @@ def main():
     ap.add_argument("--link-level", type=int, default=0, choices=(0, 2, 3),
                     help="time the linked path at this link level only (0: both, the headline is the faster one); for profiling runs")
     ap.add_argument("--no-tune", action="store_true", help="skip xenos_plan_tune: time the cost model's partition choice")
+    ap.add_argument("--passes-only", type=int, default=-1, choices=(-1, 0, 1, 2, 3),
+                    help="run the headline workload at this link level (0 = U0, 1 = U1, 2, 3) for --steps eager passes and exit: "
+                         "the process whose HBM traffic rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE counts per link level")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run a plain device copy of 256 MiB three times and exit (reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
@@ -194,6 +197,17 @@ def main():
 
     name = args.workload
     cfg, batch, compute = WORKLOADS[name]
+    if args.passes_only >= 0:
+        g = wg.build(cfg, batch)
+        s = X.Session(g, link=args.passes_only, split=1, compute=compute)
+        s.set_input(g.x)
+        for _ in range(args.steps):
+            s.run()
+        torch.cuda.synchronize()
+        print(json.dumps({"workload": name, "link": args.passes_only, "passes": args.steps, "n_chains": s.info["n_chains"],
+                          "algorithmic_hbm_mb_per_pass": s.info["hbm_bytes"] / 1e6}))
+        s.close()
+        return
     links = ((3, 2) if not args.link_level else (args.link_level,)) + (() if args.quick else (1, 0))
     head, g = run_workload(name, args.steps, args.warmup, links, chains=True, wg=wg, X=X, torch=torch)
     # the headline is the linked + split path at the link level that is faster on this workload (level 3 keeps the first

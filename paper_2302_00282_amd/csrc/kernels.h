@@ -59,6 +59,7 @@ static const int kPairChannels = 64, kPairRed = 48;
 static const int kPairRows = 128, kPairPatchMax = 180;   // output pixels and patch positions ((TH+2) x 18) of a tile
 static const int kPairInMax = 256;   // positions of the staged block of the graph input, (TH+4) x (TW+4) plus slack for the pitch columns
 static const int kHaloRows = 256, kHaloCols = 128, kHaloPatchMax = 360;
+static const long long kL2BytesPerXcd = 4ll << 20;   // gfx950: one 4 MB L2 per XCD
 // the staged patch has one of two fixed row pitches (pixels): tiles up to 16 or up to 32 pixels wide
 static const int kHaloPitchNarrow = 18, kHaloPitchWide = 34;
 
@@ -100,6 +101,8 @@ struct ConvArgs {
   float* part;
   int th, tw, tiles_y, tiles_x;   // halo kernel: spatial tile and tile grid over the stacked padded rows n*(H+2)+oh
   int halo_bn;           // halo kernel: output channels per tile (128 or 64)
+  int halo_mgroup;       // halo kernel: an XCD walks its pixel tiles in groups of this many, every output-channel tile of a group
+                         // before the next group (>= 1; a value of at least the XCD's tile count = one sweep per channel tile)
   int halo_plin;         // halo kernel: patch-linear rows (GEMM row = patch position, pitch TW + 2; pixel-major chains only)
   int M_total;           // rows enumerated over the whole problem (FLAT, ZIGZAG); per-image rows for GAP
   int tiles_m, tiles_n, ntiles;

@@ -694,7 +694,18 @@ __global__ __launch_bounds__(V2_NT) void conv3x3_kernel(const ConvArgs a) {
   const int G = gridDim.x, nx = G < NUM_XCD ? G : NUM_XCD;
   const int xcd = blockIdx.x % nx, wgs = (G - xcd + nx - 1) / nx;   // workgroups of this XCD
   const int m0 = xcd * a.tiles_m / nx, mlen = (xcd + 1) * a.tiles_m / nx - m0;
-  const int ntl = mlen * a.tiles_n;                                // tiles of this XCD, channel-tile major
+  const int ntl = mlen * a.tiles_n;                                // tiles of this XCD
+  // Order of an XCD's tiles: groups of `mg` pixel tiles, each group once per output-channel tile before the next group.
+  // With a group as large as the XCD's range this is one sweep per channel tile (one weight slice live in the L2 at a
+  // time); a group that the XCD's workgroups cover in one or two rounds reads its input patches while they are still
+  // in the L2 instead of once per channel tile.
+  const int mg = a.halo_mgroup < mlen ? a.halo_mgroup : mlen;
+  auto tile_of = [&](int l, int& tile_m, int& tile_n) __attribute__((always_inline)) {
+    const int per = mg * a.tiles_n, grp = l / per, r = l - grp * per;
+    const int left = mlen - grp * mg, glen = left < mg ? left : mg;   // the last group of the range may be short
+    tile_n = r / glen;
+    tile_m = m0 + grp * mg + (r - tile_n * glen);
+  };
   int li = blockIdx.x / nx;
   if (li >= ntl) return;                                           // uniform per workgroup
 
@@ -706,7 +717,8 @@ __global__ __launch_bounds__(V2_NT) void conv3x3_kernel(const ConvArgs a) {
   int wrow = 0, wnext = 0;
   const int wstride = (NTH / CPR) * a.Kred_pad * ESZ;
   auto patch_addr = [&](int l) __attribute__((always_inline)) {
-    const int tile_m = m0 + l % mlen;
+    int tile_m, tile_n;
+    tile_of(l, tile_m, tile_n);
     const int tyi = tile_m / a.tiles_x;
     const int q0 = tyi * a.th, x0 = (tile_m - tyi * a.tiles_x) * a.tw;
     // image and row of a stacked row: one division per tile (uniform), then compares per chunk as long as a patch spans
@@ -730,7 +742,8 @@ __global__ __launch_bounds__(V2_NT) void conv3x3_kernel(const ConvArgs a) {
     }
   };
   auto weight_addr = [&](int l) __attribute__((always_inline)) -> int {
-    const int tile_n = l / mlen;
+    int tile_m, tile_n;
+    tile_of(l, tile_m, tile_n);
     return ((tile_n * BN + tid / CPR) * a.Kred_pad + (tid % CPR) * CE) * ESZ;
   };
 
@@ -966,7 +979,8 @@ __global__ __launch_bounds__(V2_NT) void conv3x3_kernel(const ConvArgs a) {
   // The chain's epilogue for the tile `li`, run after its last chunk (of parity PAR).
   auto epilogue = [&](auto par) {
     constexpr int PAR = decltype(par)::value;
-    const int tile_n = li / mlen, tile_m = m0 + li % mlen;
+    int tile_m, tile_n;
+    tile_of(li, tile_m, tile_n);
     const int tyi = tile_m / a.tiles_x;
     const int q0 = tyi * a.th, x0 = (tile_m - tyi * a.tiles_x) * a.tw;
     // The patch buffer of the chunk just finished is free (the other one holds the next tile's first patch).
@@ -2326,6 +2340,7 @@ int launch_conv(const ConvArgs& a, int dtype, int cfg, int scalar_loader, void* 
     return dtype == DT_BF16 ? launch_conv_dwpro_t<bf16_t>(a, cfg, st) : launch_conv_dwpro_t<float>(a, cfg, st);
   }
   if (cfg == kHaloCfg) {
+    if (a.halo_mgroup < 1) return (int)hipErrorInvalidValue;
     if (scalar_loader) return (int)hipErrorInvalidValue;
     return dtype == DT_BF16 ? launch_conv3x3_t<bf16_t>(a, st) : launch_conv3x3_t<float>(a, st);
   }

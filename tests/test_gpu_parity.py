@@ -26,6 +26,8 @@ def run_gpu(g, link=2, split=1, compute=0, tile=0, hw=None):
     X = _xenos()
     if hw is not None and hw.get("X_small"):             # a machine description with 8 compute units: long tile walks
         hw = dict(X.MI355X, num_cu=8)
+    elif hw is not None and hw.get("X_mid"):             # 32 compute units: 4 workgroups per XCD
+        hw = dict(X.MI355X, num_cu=32)
     s = X.Session(g, link=link, split=split, compute=compute, tile=tile, hw=hw)
     try:
         y = s.forward(g.x)
@@ -192,6 +194,10 @@ def test_halo_staged_3x3_kernel(kind, hw, k, bn, compute):
     assert np.array_equal(y, y1)                       # one workgroup walking every tile == split, bit for bit
     y2, info2 = check(g, compute=compute, tile=tile, hw=dict(X_small=True))
     assert np.array_equal(y, y2)                       # 8 persistent workgroups, many tiles each
+    # 4 workgroups per XCD: with two channel tiles an XCD walks its pixel tiles in groups of two, both channel tiles of
+    # a group before the next group, and 5 or 6 pixel tiles per XCD (hw = 40) leave a short last group
+    y3, _ = check(g, compute=compute, tile=tile, hw=dict(X_mid=True))
+    assert np.array_equal(y, y3)
 
 
 def test_small_channel_first_layer_and_nchw_output():
