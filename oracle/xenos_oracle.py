@@ -139,6 +139,30 @@ def concat(xs) -> np.ndarray:
     return y
 
 
+def channel_slice(x, c_begin, out_c) -> np.ndarray:
+    """Channels [c_begin, c_begin + out_c) of an NCHW tensor (the inverse of concat: Section 4.2.2, Eq. 1 read backwards)."""
+    x = _f64(x)
+    assert 0 <= c_begin and out_c >= 1 and c_begin + out_c <= x.shape[1]
+    y = np.empty((x.shape[0], out_c) + x.shape[2:], np.float64)
+    for k in range(out_c):
+        y[:, k] = x[:, c_begin + k]
+    return y
+
+
+def channel_shuffle(x, groups) -> np.ndarray:
+    """Channel shuffle of the ShuffleNet models (Section 7.1 lists ShuffleNet; the paper gives no formula, this is the
+    operator's published definition): with C = groups * m, output channel i * groups + j is input channel j * m + i."""
+    x = _f64(x)
+    c = x.shape[1]
+    assert groups >= 1 and c % groups == 0
+    m = c // groups
+    y = np.empty_like(x)
+    for j in range(groups):
+        for i in range(m):
+            y[:, i * groups + j] = x[:, j * m + i]
+    return y
+
+
 def fc(x, w, bias=None) -> np.ndarray:
     x, w = _f64(x), _f64(w)
     n = x.shape[0]
@@ -175,6 +199,10 @@ def apply_op(op, ins: List[np.ndarray]) -> np.ndarray:
         return concat(ins)
     if op.kind == "fc":
         return fc(ins[0], p["weight"], p.get("bias"))
+    if op.kind == "slice":
+        return channel_slice(ins[0], a["c_begin"], a["out_c"])
+    if op.kind == "shuffle":
+        return channel_shuffle(ins[0], a["groups"])
     raise ValueError(op.kind)
 
 

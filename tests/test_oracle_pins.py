@@ -293,6 +293,39 @@ def test_k_split_identity_eq1():
     assert np.array_equal(xo.add(y1, y1), 2 * y1)
 
 
+def test_channel_slice_is_the_inverse_of_concat():
+    x = rnd(2, 7, 3, 4)
+    a, b, c = xo.channel_slice(x, 0, 2), xo.channel_slice(x, 2, 4), xo.channel_slice(x, 6, 1)
+    assert np.array_equal(xo.concat([a, b, c]), x)
+    assert np.array_equal(b, x[:, 2:6])
+    with pytest.raises(AssertionError):
+        xo.channel_slice(x, 5, 3)
+
+
+@pytest.mark.parametrize("c,g", [(6, 2), (6, 3), (12, 4), (8, 1), (8, 8), (10, 5)])
+def test_channel_shuffle_closed_forms(c, g):
+    # every channel holds its own index: the shuffled tensor lists, group-interleaved, 0, m, 2m, ..., 1, m+1, ...
+    m = c // g
+    x = np.broadcast_to(np.arange(c, dtype=np.float64)[None, :, None, None], (2, c, 3, 2)).copy()
+    y = xo.channel_shuffle(x, g)
+    want = [j * m + i for i in range(m) for j in range(g)]
+    assert np.array_equal(y[1, :, 2, 1], np.array(want, np.float64))
+    assert sorted(y[0, :, 0, 0].tolist()) == list(range(c))            # a permutation of the channels
+    # shuffling with g groups and then with C / g groups is the identity (the two transposes cancel)
+    z = rnd(2, c, 3, 2)
+    assert np.array_equal(xo.channel_shuffle(xo.channel_shuffle(z, g), m), z)
+    # one group, or one channel per group, moves nothing
+    if g == 1 or g == c:
+        assert np.array_equal(xo.channel_shuffle(z, g), z)
+    # the reshape / transpose form of the same definition, and the library routine
+    assert np.array_equal(xo.channel_shuffle(z, g), z.reshape(2, g, m, 3, 2).transpose(0, 2, 1, 3, 4).reshape(2, c, 3, 2))
+    assert np.array_equal(xo.channel_shuffle(z, g), F.channel_shuffle(torch.from_numpy(z), g).numpy())
+    # with two groups the shuffle of concat(a, b) interleaves a and b
+    if g == 2:
+        a, b = z[:, :m], z[:, m:]
+        assert np.array_equal(y := xo.channel_shuffle(xo.concat([a, b]), 2), y) and np.array_equal(y[:, 0::2], a) and np.array_equal(y[:, 1::2], b)
+
+
 def test_spatial_split_identity():
     # inH split needs boundary rows (Section 4.2.1): rows 0-3 of the output depend on input rows 0-4 only
     x, w = rnd(1, 2, 8, 8), rnd(3, 2, 3, 3)
@@ -363,6 +396,10 @@ def _torch_forward(g):
             y = torch.cat(ins, 1)
         elif op.kind == "fc":
             y = F.linear(ins[0].flatten(1), p["weight"], p.get("bias"))[:, :, None, None]
+        elif op.kind == "slice":
+            y = torch.narrow(ins[0], 1, a["c_begin"], a["out_c"])
+        elif op.kind == "shuffle":
+            y = F.channel_shuffle(ins[0], a["groups"])
         else:
             raise ValueError(op.kind)
         t[i + 1] = y
@@ -374,6 +411,7 @@ def _torch_forward(g):
     (wg.resnet18, dict(hw=32, width=0.125, classes=10)),
     (wg.vgg16, dict(hw=32, width=0.125, fc_dim=32, classes=10)),
     (wg.squeezenet11, dict(hw=63, classes=10)),
+    (wg.shufflenet_v2, dict(hw=64, channels=(16, 24, 48), repeats=(2, 3, 2), stem=8, last=64, classes=10)),
 ])
 def test_graph_runner_against_library_and_batch_independence(builder, kw):
     g = builder(batch=2, seed=11, nonzero_bias=True, **kw)

@@ -39,7 +39,7 @@ def seed_for(config: int, batch: int) -> int:
 
 @dataclass
 class Op:
-    kind: str                      # conv bias bn relu maxpool avgpool gap add concat fc
+    kind: str                      # conv bias bn relu maxpool avgpool gap add concat fc slice shuffle
     inputs: List[int]
     attrs: Dict[str, float] = field(default_factory=dict)
     params: Dict[str, np.ndarray] = field(default_factory=dict)
@@ -93,6 +93,12 @@ def _infer(op: Op, ins):
         return (n, sum(i[1] for i in ins), h, w)
     if op.kind == "fc":
         return (n, a["out_c"], 1, 1)
+    if op.kind == "slice":
+        assert 0 <= a["c_begin"] and a["out_c"] >= 1 and a["c_begin"] + a["out_c"] <= c, (ins, a)
+        return (n, a["out_c"], h, w)
+    if op.kind == "shuffle":
+        assert a["groups"] >= 1 and c % a["groups"] == 0, (ins, a)
+        return (n, c, h, w)
     raise ValueError(op.kind)
 
 
@@ -165,6 +171,14 @@ class _Builder:
 
     def concat(self, xs, name=""):
         return self._push(Op("concat", list(xs), {}, {}, name))
+
+    def slice(self, x, c_begin, out_c, name=""):
+        """Channels [c_begin, c_begin + out_c) of x."""
+        return self._push(Op("slice", [x], dict(c_begin=c_begin, out_c=out_c), {}, name))
+
+    def shuffle(self, x, groups, name=""):
+        """Channel shuffle: the channels seen as [groups][C / groups] are written out as [C / groups][groups]."""
+        return self._push(Op("shuffle", [x], dict(groups=groups), {}, name))
 
     def fc(self, x, out_c, name="", bias=None):
         n, c, h, w = self._shapes[x]
@@ -286,6 +300,37 @@ def squeezenet11(batch=1, seed=None, hw=224, classes=1000, nonzero_bias=False, d
     return b.finish(t)
 
 
+def shufflenet_v2(batch=1, seed=None, hw=224, channels=(176, 352, 704), repeats=(4, 8, 4), stem=24, last=1024,
+                  classes=1000, nonzero_bias=False, draw=True) -> Graph:
+    """ShuffleNet-style graph (one of the paper's seven evaluation models, Section 7.1): units that split the channels in
+    two halves, run a 1x1 -> depthwise 3x3 -> 1x1 branch on one half, concatenate and shuffle the channels in two groups.
+    The shuffle moves no data when linked: it is the order in which the two halves are written."""
+    b = _Builder("shufflenet_v2", (batch, 3, hw, hw), seed_for(5, batch) if seed is None else seed, nonzero_bias, draw)
+    t = b.cbr(0, stem, 3, 2, 1, name="conv1")
+    t = b.maxpool(t, 3, 2, 1, name="pool1")
+    for si, (c, reps) in enumerate(zip(channels, repeats), 2):
+        h = c // 2
+        for u in range(reps):
+            nm = f"s{si}u{u}"
+            if u == 0:           # down-sampling unit: both branches read the whole input
+                l = b.cbr(t, b.shape(t)[1], 3, 2, 1, groups=b.shape(t)[1], name=nm + ".l.dw", relu=False)
+                l = b.cbr(l, h, 1, name=nm + ".l.pw")
+                r = b.cbr(t, h, 1, name=nm + ".r.pw1")
+                r = b.cbr(r, h, 3, 2, 1, groups=h, name=nm + ".r.dw", relu=False)
+                r = b.cbr(r, h, 1, name=nm + ".r.pw2")
+            else:
+                l = b.slice(t, 0, h, nm + ".lo")
+                r = b.slice(t, h, h, nm + ".hi")
+                r = b.cbr(r, h, 1, name=nm + ".r.pw1")
+                r = b.cbr(r, h, 3, 1, 1, groups=h, name=nm + ".r.dw", relu=False)
+                r = b.cbr(r, h, 1, name=nm + ".r.pw2")
+            t = b.shuffle(b.concat([l, r], nm + ".cat"), 2, nm + ".shuffle")
+    t = b.cbr(t, last, 1, name="conv5")
+    t = b.gap(t, "gap")
+    t = b.fc(t, classes, "fc")
+    return b.finish(t)
+
+
 # Operator micro-benchmark shapes (Table 4): name -> (feature map H, W, C; kernel R, S; out channels K; what follows)
 TABLE4 = {
     "cbr_maxpool": (224, 224, 3, 3, 3, 24, "maxpool"),      # printed with inC 24 / outC 224; read as 3 -> 24 (inC must be 3)
@@ -311,7 +356,7 @@ def table4(name: str, batch=1, seed=None, nonzero_bias=False, draw=True) -> Grap
     return b.finish(t)
 
 
-CONFIGS = {0: single_chain, 1: mobilenet_v1, 2: resnet18, 3: vgg16, 4: squeezenet11}
+CONFIGS = {0: single_chain, 1: mobilenet_v1, 2: resnet18, 3: vgg16, 4: squeezenet11, 5: shufflenet_v2}
 
 
 def build(config: int, batch: int, **kw) -> Graph:
