@@ -33,6 +33,8 @@ WORKLOADS = {
     "squeezenet_n32_bf16": (4, 32, 1),
     "squeezenet_n32_f32": (4, 32, 0),
     "single_chain_n1_f32": (0, 1, 0),
+    "shufflenet_n1_bf16": (5, 1, 1),
+    "shufflenet_n32_bf16": (5, 32, 1),
 }
 PEAK = {1: 2500.0, 0: 157.3}          # dense MFMA TFLOP/s: bf16, fp32
 HBM_PEAK = 8000.0                     # GB/s
@@ -261,7 +263,7 @@ def main():
         for other in WORKLOADS:
             if other == name:
                 continue
-            olinks = (3, 2, 1, 0) if other.startswith("mobilenet") else (2, 1, 0)   # level 3 only differs where depthwise convs exist
+            olinks = (3, 2, 1, 0) if other.startswith(("mobilenet", "shufflenet")) else (2, 1, 0)   # level 3 only differs where depthwise convs exist
             r, _ = run_workload(other, args.steps, args.warmup, olinks, chains=True, wg=wg, X=X, torch=torch)
             detail[other] = r
             others.append({"workload": other, "gflop": r["gflop"],

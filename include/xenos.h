@@ -52,7 +52,10 @@ typedef enum {
   XENOS_OP_GLOBAL_AVGPOOL = 6,
   XENOS_OP_ADD = 7,             /* x.add, two inputs of equal shape                                  */
   XENOS_OP_CONCAT = 8,          /* x.concat along channels, 2..4 inputs                              */
-  XENOS_OP_FC = 9               /* x.matmul as FullyConnected over the NCHW flattening of its input  */
+  XENOS_OP_FC = 9,              /* x.matmul as FullyConnected over the NCHW flattening of its input  */
+  XENOS_OP_SLICE = 10,          /* channels [c_begin, c_begin + out_c) of the input (the inverse of x.concat) */
+  XENOS_OP_SHUFFLE = 11         /* channel shuffle of the ShuffleNet models (Section 7.1): with C = groups * m,
+                                   output channel i * groups + j is input channel j * m + i                  */
 } xenos_op_kind;
 
 typedef struct {
@@ -67,13 +70,14 @@ typedef struct {
   xenos_op_kind kind;
   int n_inputs;
   int inputs[4];
-  int out_c;                    /* conv, fc                                        */
+  int out_c;                    /* conv, fc, slice                                 */
   int kh, kw;                   /* conv, pool                                      */
   int stride_h, stride_w;       /* conv, pool (must be equal)                      */
   int pad_h, pad_w;             /* conv, pool (must be equal)                      */
-  int groups;                   /* conv: 1 (dense) or == channels (depthwise)      */
+  int groups;                   /* conv: 1 (dense) or == channels (depthwise); shuffle: number of groups */
   int ceil_mode;                /* pool                                            */
   int count_include_pad;        /* avgpool                                         */
+  int c_begin;                  /* slice: first channel                            */
   float eps;                    /* bn                                              */
   const float* weight;          /* conv: [out_c][c/groups][kh][kw]; fc: [out_c][c*h*w] */
   const float* bias;            /* conv, fc (optional); bias op (required): [c]    */

@@ -130,6 +130,7 @@ struct EltArgs {
   int C;                             // channels of the view
   long long pixels;                  // N*H*W
   long long a_sP, b_sP, out_sP;      // pixel strides of the NHWC views
+  long long a_sK, out_sK;            // channel strides of a and out (1 except for the strided copies of a channel shuffle)
 };
 
 struct PoolArgs {

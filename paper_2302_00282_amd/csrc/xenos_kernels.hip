@@ -2497,11 +2497,11 @@ __global__ __launch_bounds__(NT) void elt_kernel(const EltArgs a) {
   for (long long idx = (long long)blockIdx.x * NT + threadIdx.x; idx < total; idx += (long long)gridDim.x * NT) {
     const int c = (int)(idx % a.C);
     const long long p = idx / a.C;
-    float v = tr::ld(a.a, p * a.a_sP + c);
+    float v = tr::ld(a.a, p * a.a_sP + c * a.a_sK);
     if (a.op == ELT_AFFINE) v = v * a.scale[c] + a.shift[c];
     else if (a.op == ELT_ADD) v += tr::ld(a.b, p * a.b_sP + c);
     if (a.relu || a.op == ELT_RELU) v = fmx(v, 0.f);
-    tr::st(a.out, p * a.out_sP + c, v);
+    tr::st(a.out, p * a.out_sP + c * a.out_sK, v);
   }
 }
 
@@ -2536,7 +2536,8 @@ __global__ __launch_bounds__(NT) void elt_vec_kernel(const EltArgs a) {
 int launch_elt(const EltArgs& a, int dtype, void* stream) {
   hipStream_t st = (hipStream_t)stream;
   const int ce = dtype == DT_BF16 ? 8 : 4;
-  const bool vec = a.C % ce == 0 && a.a_sP % ce == 0 && a.out_sP % ce == 0 && (a.op != ELT_ADD || a.b_sP % ce == 0) &&
+  if (a.a_sK < 1 || a.out_sK < 1) return (int)hipErrorInvalidValue;
+  const bool vec = a.a_sK == 1 && a.out_sK == 1 && a.C % ce == 0 && a.a_sP % ce == 0 && a.out_sP % ce == 0 && (a.op != ELT_ADD || a.b_sP % ce == 0) &&
                    ((uintptr_t)a.a % 16 == 0) && ((uintptr_t)a.out % 16 == 0) && (a.op != ELT_ADD || (uintptr_t)a.b % 16 == 0);
   if (vec) {
     const int grid = grid_for(a.pixels * (a.C / ce), NT);

@@ -132,6 +132,7 @@ struct xenos_plan {
   xenos_hw_info hw{};
   xenos_tensor_desc in{}, out{};
   int dt = DT_F32, esz = 4, ce = 4;
+  int n_linked_shuffles = 0;   // channel shuffles realised as the store order of their concat (no pass of their own)
   std::vector<Buffer> bufs;
   std::vector<View> views;
   std::vector<Step> steps;
@@ -176,9 +177,12 @@ struct Planner {
   std::vector<int> tview;                    // tensor id -> view index (-1 = not materialised)
   std::vector<int> node_step;                // node -> step index (-1 = not yet planned)
   std::vector<int> node_final;               // node -> 1 if its output is its step's output
-  struct Place { int cat_tid; int c_off; };
-  std::map<int, Place> placed;               // tensor id -> slice of a concat output
+  struct Place { int cat_tid; int c_off; int c_stride; };
+  std::map<int, Place> placed;               // tensor id -> slice of a concat output (channel c of it at c_off + c * c_stride)
   std::vector<char> free_concat;             // node -> concat realised by offset writes
+  std::vector<int> ileave;                   // concat node -> groups of the channel shuffle linked into it (0 = none):
+                                             // part j of the concat is written to channels j, j + groups, j + 2 groups, ...
+  std::vector<char> alias_shuffle;           // shuffle node whose output IS its (already interleaved) concat input
 
   Planner(const xenos_graph& g_, xenos_plan& p_) : g(g_), p(p_) {}
 
@@ -300,7 +304,7 @@ struct Planner {
       const int cv = out_view_for(cat, false);
       const View& c = p.views[cv];
       View sl = c;
-      sl.s = s; sl.off = c.off + it->second.c_off;
+      sl.s = s; sl.off = c.off + it->second.c_off * c.sK; sl.sK = c.sK * it->second.c_stride;
       p.views.push_back(sl);
       v = (int)p.views.size() - 1;
     } else if (tid == out_tid) {
@@ -346,6 +350,39 @@ struct Planner {
   // Can the dense convolution node `nx` take a linked first-layer producer?  It must be a 3x3 / stride 1 / pad 1
   // convolution kPairChannels -> kPairChannels whose own chain ends in nothing or a 2x2 / stride 2 pooling of an even map,
   // takes no shortcut, and writes a plain internal tensor (the walk mirrors the link pass of plan_node).
+  // Can the chain that produces tensor `tid` store it with a channel stride?  True for conv -> (bias | bn)* -> [relu]
+  // on a dense convolution that does not read the graph input (the general convolution kernel stores single elements
+  // at any stride; the first-layer, halo, depthwise and pooling epilogues store 16-byte channel groups only), when
+  // nothing else reads the tensor or the intermediate ones.
+  bool stores_strided(int tid) const {
+    if (tid < 1 || tid == out_tid || placed.count(tid) || consumers[tid].size() != 1) return false;
+    int t = tid;
+    if (nodes[t - 1].kind == XENOS_OP_RELU) {
+      t = nodes[t - 1].in[0];
+      if (t < 1 || t == out_tid || consumers[t].size() != 1) return false;
+    }
+    while (nodes[t - 1].kind == XENOS_OP_BIAS || nodes[t - 1].kind == XENOS_OP_BN) {
+      t = nodes[t - 1].in[0];
+      if (t < 1 || t == out_tid || consumers[t].size() != 1) return false;
+    }
+    const Node& c = nodes[t - 1];
+    return c.kind == XENOS_OP_CONV && desc(c).groups == 1 && c.in[0] != 0;
+  }
+
+  // Does the chain that starts at convolution node `c` end in a tensor stored with a channel stride?
+  bool chain_stores_strided(int c) const {
+    int cur = c + 1;
+    for (;;) {
+      auto it = placed.find(cur);
+      if (it != placed.end()) return it->second.c_stride > 1;
+      const int nx = single_consumer(cur);
+      if (nx < 0) return false;
+      const int k = nodes[nx].kind;
+      if (k != XENOS_OP_BIAS && k != XENOS_OP_BN && k != XENOS_OP_RELU) return false;
+      cur = nx + 1;
+    }
+  }
+
   bool pair_consumer_ok(int nx) {
     const Node& nd = nodes[nx];
     if (nd.kind != XENOS_OP_CONV || node_step[nx] >= 0) return false;
@@ -674,12 +711,38 @@ struct Planner {
     node_step.assign(nn, -1);
     node_final.assign(nn, 0);
     free_concat.assign(nn, 0);
+    ileave.assign(nn, 0);
+    alias_shuffle.assign(nn, 0);
+
+    // Channel shuffle as a layout-only link: shuffle(concat(x_0 .. x_{g-1})) with g groups and g equal parts puts channel
+    // i of part j at position i * g + j, so the concat buffer is written interleaved and the shuffle moves nothing.  A
+    // part that ends a plain dense-convolution chain is stored that way by the chain itself (channel stride g in its
+    // epilogue); any other part (the pass-through half of a ShuffleNet unit) is copied into its positions.
+    if (p.opts.link >= 2)
+      for (int j = 0; j < nn; ++j) {
+        if (nodes[j].kind != XENOS_OP_SHUFFLE || j + 1 == out_tid) continue;
+        const int t = nodes[j].in[0], g = desc(nodes[j]).groups;
+        if (t < 1 || t == out_tid || nodes[t - 1].kind != XENOS_OP_CONCAT || consumers[t].size() != 1 || g < 2) continue;
+        const Node& cat = nodes[t - 1];
+        if ((int)cat.in.size() != g) continue;
+        bool ok = true;
+        for (size_t a = 0; a < cat.in.size(); ++a) {
+          if (tshape[cat.in[a]].c * g != cat.out.c) ok = false;
+          for (size_t b = a + 1; b < cat.in.size(); ++b)
+            if (cat.in[a] == cat.in[b]) ok = false;
+        }
+        if (!ok) continue;
+        ileave[t - 1] = g;
+        alias_shuffle[j] = 1;
+        for (int a = 0; a < g; ++a)
+          if (stores_strided(cat.in[a])) placed[cat.in[a]] = Place{t, a, g};
+      }
 
     // concat realised as channel-offset stores of its producers (Eq. 1: split halves join without a
     // layout transformation)
     if (p.opts.link >= 2)
       for (int i = 0; i < nn; ++i) {
-        if (nodes[i].kind != XENOS_OP_CONCAT) continue;
+        if (nodes[i].kind != XENOS_OP_CONCAT || ileave[i]) continue;
         const int ctot = nodes[i].out.c;
         bool ok = ctot % p.ce == 0;
         int off = 0;
@@ -694,7 +757,7 @@ struct Planner {
         if (!ok) continue;
         free_concat[i] = 1;
         off = 0;
-        for (int t : nodes[i].in) { placed[t] = Place{i + 1, off}; off += tshape[t].c; }
+        for (int t : nodes[i].in) { placed[t] = Place{i + 1, off, 1}; off += tshape[t].c; }
       }
 
     // graph input
@@ -918,7 +981,9 @@ struct Planner {
         // link level 3: depthwise -> pointwise.  The depthwise result is produced tile by tile inside the
         // pointwise kernel (as its A operand) and never written to memory.
         const int pw = link >= 3 && !placed.count(cur) ? single_consumer(cur) : -1;
-        if (pw >= 0 && d.kh == d.kw && nodes[pw].kind == XENOS_OP_CONV) {
+        // (a pointwise chain that stores with a channel stride, a part of a shuffled concat, has no 16-byte stores, which
+        // the depthwise-panel kernel needs; the element-wise form of the linked pair is slower than two chains)
+        if (pw >= 0 && d.kh == d.kw && nodes[pw].kind == XENOS_OP_CONV && !chain_stores_strided(pw)) {
           const xenos_op_desc& pd = desc(nodes[pw]);
           // Every workgroup of the pointwise chain recomputes the depthwise result of its 64 pixels for all input
           // channels; beyond 32 channel groups per pixel (8 pixels per thread) that serial work costs more than the
@@ -1179,6 +1244,91 @@ struct Planner {
       node_final[i] = 1;
       return XENOS_OK;
     }
+    if (nd.kind == XENOS_OP_CONCAT && ileave[i]) {
+      // interleaved concat (a channel shuffle linked into it): parts stored by their chains are in place already,
+      // the others are copied to their channel positions
+      const int ov = out_view_for(i + 1, false);
+      if (!p.views[ov].internal_nhwc() || p.views[ov].f32) return fail(XENOS_EUNSUPPORTED, "concat output must be internal");
+      for (size_t j = 0; j < nd.in.size(); ++j) {
+        if (placed.count(nd.in[j])) continue;
+        Step cs;
+        cs.kind = S_ELT; cs.name = st.name + ".part" + std::to_string(j);
+        cs.ops.push_back(nd.src);
+        xenos_status rc = need_internal_input(nd.in[j], cs.name.c_str(), &cs.v_in);
+        if (rc != XENOS_OK) return rc;
+        View sl = p.views[ov];
+        sl.s = tshape[nd.in[j]]; sl.off += (long long)j; sl.sK = ileave[i];
+        p.views.push_back(sl);
+        cs.v_out = (int)p.views.size() - 1;
+        fill_elt(cs, ELT_COPY, 0);
+        add_step(cs);
+      }
+      node_step[i] = std::max(0, (int)p.steps.size() - 1);
+      node_final[i] = 1;
+      return XENOS_OK;
+    }
+    if (nd.kind == XENOS_OP_SHUFFLE && alias_shuffle[i]) {
+      if (tview[nd.in[0]] < 0) return fail(XENOS_EINVAL, "%s: input not materialised", st.name.c_str());
+      tview[i + 1] = tview[nd.in[0]];
+      node_step[i] = std::max(0, (int)p.steps.size() - 1);
+      node_final[i] = 1;
+      ++p.n_linked_shuffles;
+      return XENOS_OK;
+    }
+    if (nd.kind == XENOS_OP_SHUFFLE) {
+      // stand-alone shuffle: one strided copy per group (group j of the input goes to channels j, j + g, ...)
+      const int g = d.groups, m = is.c / g;
+      int vin;
+      xenos_status rc = need_internal_input(nd.in[0], st.name.c_str(), &vin);
+      if (rc != XENOS_OK) return rc;
+      const int ov = out_view_for(i + 1, false);
+      if (!p.views[ov].internal_nhwc() || p.views[ov].f32) return fail(XENOS_EUNSUPPORTED, "%s: output must be internal", st.name.c_str());
+      const bool whole = g == 1 || m == 1;                         // one group, or one channel per group: a plain copy
+      for (int j = 0; j < (whole ? 1 : g); ++j) {
+        Step cs;
+        cs.kind = S_ELT; cs.name = st.name + ".group" + std::to_string(j);
+        cs.ops.push_back(nd.src);
+        View a = p.views[vin], o = p.views[ov];
+        if (!whole) {
+          a.s.c = m; a.off += (long long)j * m * a.sK;
+          o.s.c = m; o.off += (long long)j * o.sK; o.sK *= g;
+        }
+        p.views.push_back(a); cs.v_in = (int)p.views.size() - 1;
+        p.views.push_back(o); cs.v_out = (int)p.views.size() - 1;
+        fill_elt(cs, ELT_COPY, 0);
+        add_step(cs);
+      }
+      node_step[i] = (int)p.steps.size() - 1;
+      node_final[i] = 1;
+      return XENOS_OK;
+    }
+    if (nd.kind == XENOS_OP_SLICE) {
+      // a channel range of a tensor is a view of it; only a slice that is the graph output is copied
+      int vin;
+      xenos_status rc = need_internal_input(nd.in[0], st.name.c_str(), &vin);
+      if (rc != XENOS_OK) return rc;
+      View sl = p.views[vin];
+      sl.s = tshape[i + 1]; sl.off += (long long)d.c_begin * sl.sK;
+      if (sl.cphys) sl.cphys = 0;
+      p.views.push_back(sl);
+      const int sv = (int)p.views.size() - 1;
+      // (a range that does not start and end on a 16-byte channel group is copied too: the vector loaders of its
+      // consumers need aligned groups)
+      if (i + 1 == out_tid || placed.count(i + 1) || sl.off % p.ce != 0 || sl.s.c % p.ce != 0) {
+        st.kind = S_ELT;
+        st.v_in = sv;
+        st.v_out = out_view_for(i + 1, false);
+        if (p.views[st.v_out].f32) return fail(XENOS_EUNSUPPORTED, "%s: output must be internal", st.name.c_str());
+        fill_elt(st, ELT_COPY, 0);
+        add_step(st);
+        node_step[i] = (int)p.steps.size() - 1;
+      } else {
+        tview[i + 1] = sv;
+        node_step[i] = std::max(0, (int)p.steps.size() - 1);
+      }
+      node_final[i] = 1;
+      return XENOS_OK;
+    }
     if (nd.kind == XENOS_OP_CONCAT) {
       const int ov = out_view_for(i + 1, false);
       if (!p.views[ov].internal_nhwc() || p.views[ov].f32) return fail(XENOS_EUNSUPPORTED, "concat output must be internal");
@@ -1254,7 +1404,7 @@ struct Planner {
     const View& o = p.views[st.v_out];
     e.op = op; e.relu = relu; e.C = a.s.c;
     e.pixels = (long long)a.s.n * a.s.h * a.s.w;
-    e.a_sP = a.sP; e.out_sP = o.sP;
+    e.a_sP = a.sP; e.out_sP = o.sP; e.a_sK = a.sK; e.out_sK = o.sK;
     if (st.v_in2 >= 0) e.b_sP = p.views[st.v_in2].sP;
     st.bytes_in = view_bytes(st.v_in) + (st.v_in2 >= 0 ? view_bytes(st.v_in2) : 0);
     st.bytes_out = view_bytes(st.v_out);
@@ -1313,9 +1463,9 @@ void write_plan_json(xenos_plan& p) {
   double tf = 0; long long tb = 0;
   for (const Step& s : p.steps) { tf += s.flops; tb += s.bytes_in + s.bytes_w + s.bytes_out + s.bytes_res; }
   snprintf(buf, sizeof buf, "{\"link\":%d,\"split\":%d,\"compute\":\"%s\",\"num_cu\":%d,\"n_chains\":%d,\"flops\":%.0f,\"hbm_bytes\":%lld,"
-           "\"weight_bytes\":%zu,\"workspace_bytes\":%zu,\"chains\":[",
+           "\"linked_shuffles\":%d,\"weight_bytes\":%zu,\"workspace_bytes\":%zu,\"chains\":[",
            p.opts.link, p.opts.split, p.dt == DT_BF16 ? "bf16" : "f32", p.hw.num_cu, (int)p.steps.size(), tf, tb,
-           p.wimage.size(), p.workspace_bytes);
+           p.n_linked_shuffles, p.wimage.size(), p.workspace_bytes);
   j = buf;
   for (size_t i = 0; i < p.steps.size(); ++i) {
     const Step& s = p.steps[i];
@@ -1523,6 +1673,14 @@ xenos_status xenos_graph_create(const xenos_tensor_desc* input, const xenos_op_d
           os.c = ct;
           break;
         }
+        case XENOS_OP_SLICE:
+          if (d.c_begin < 0 || d.out_c <= 0 || (long long)d.c_begin + d.out_c > s.c)
+            { rc = fail(XENOS_ESHAPE, "op %d: slice [%d, %d + %d) outside the %d channels of its input", i, d.c_begin, d.c_begin, d.out_c, s.c); break; }
+          os.c = d.out_c;
+          break;
+        case XENOS_OP_SHUFFLE:
+          if (d.groups <= 0 || s.c % d.groups) { rc = fail(XENOS_ESHAPE, "op %d: %d channels not divisible by %d shuffle groups", i, s.c, d.groups); break; }
+          break;
         default: rc = fail(XENOS_EINVAL, "op %d: unknown kind %d", i, (int)d.kind);
       }
       if (rc != XENOS_OK) break;

@@ -21,11 +21,12 @@ XENOS_OK, XENOS_EINVAL, XENOS_ESHAPE, XENOS_EUNSUPPORTED, XENOS_ENOMEM, XENOS_ED
 XENOS_F32, XENOS_BF16 = 0, 1
 XENOS_NCHW, XENOS_NHWC = 0, 1
 (XENOS_OP_CONV, XENOS_OP_BIAS, XENOS_OP_BN, XENOS_OP_RELU, XENOS_OP_MAXPOOL, XENOS_OP_AVGPOOL,
- XENOS_OP_GLOBAL_AVGPOOL, XENOS_OP_ADD, XENOS_OP_CONCAT, XENOS_OP_FC) = range(10)
+ XENOS_OP_GLOBAL_AVGPOOL, XENOS_OP_ADD, XENOS_OP_CONCAT, XENOS_OP_FC, XENOS_OP_SLICE, XENOS_OP_SHUFFLE) = range(12)
 
 _KIND = {"conv": XENOS_OP_CONV, "bias": XENOS_OP_BIAS, "bn": XENOS_OP_BN, "relu": XENOS_OP_RELU,
          "maxpool": XENOS_OP_MAXPOOL, "avgpool": XENOS_OP_AVGPOOL, "gap": XENOS_OP_GLOBAL_AVGPOOL,
-         "add": XENOS_OP_ADD, "concat": XENOS_OP_CONCAT, "fc": XENOS_OP_FC}
+         "add": XENOS_OP_ADD, "concat": XENOS_OP_CONCAT, "fc": XENOS_OP_FC, "slice": XENOS_OP_SLICE,
+         "shuffle": XENOS_OP_SHUFFLE}
 
 _FP = C.POINTER(C.c_float)
 
@@ -39,7 +40,7 @@ class OpDesc(C.Structure):
     _fields_ = [("kind", C.c_int), ("n_inputs", C.c_int), ("inputs", C.c_int * 4),
                 ("out_c", C.c_int), ("kh", C.c_int), ("kw", C.c_int),
                 ("stride_h", C.c_int), ("stride_w", C.c_int), ("pad_h", C.c_int), ("pad_w", C.c_int),
-                ("groups", C.c_int), ("ceil_mode", C.c_int), ("count_include_pad", C.c_int),
+                ("groups", C.c_int), ("ceil_mode", C.c_int), ("count_include_pad", C.c_int), ("c_begin", C.c_int),
                 ("eps", C.c_float),
                 ("weight", _FP), ("bias", _FP), ("gamma", _FP), ("beta", _FP), ("mean", _FP), ("var", _FP)]
 
@@ -198,6 +199,10 @@ def op_descs(g, keep: List[np.ndarray]) -> List[OpDesc]:
             d.count_include_pad = a.get("count_include_pad", 0)
         elif op.kind == "fc":
             d.out_c = a["out_c"]
+        elif op.kind == "slice":
+            d.out_c, d.c_begin = a["out_c"], a["c_begin"]
+        elif op.kind == "shuffle":
+            d.groups = a["groups"]
         elif op.kind == "bn":
             d.eps = a["eps"]
         d.weight = _fp(p.get("weight"), keep)

@@ -73,6 +73,22 @@ def test_graph_validation_errors():
     assert X.xenos_destroy(None) is None
 
 
+def test_slice_and_shuffle_validation():
+    g = wg.single_chain(batch=1)                                   # 16 output channels
+    g.ops.append(wg.Op("slice", [len(g.ops)], dict(c_begin=10, out_c=8), {}, "s"))
+    g.output = len(g.ops)
+    with pytest.raises(X.XenosError) as e:
+        X.graph_from_workload(g)
+    assert e.value.status == X.XENOS_ESHAPE and "slice" in str(e.value)
+    g.ops[-1] = wg.Op("shuffle", [len(g.ops) - 1], dict(groups=3), {}, "s")
+    with pytest.raises(X.XenosError) as e:
+        X.graph_from_workload(g)
+    assert e.value.status == X.XENOS_ESHAPE and "shuffle" in str(e.value)
+    g.ops[-1] = wg.Op("shuffle", [len(g.ops) - 1], dict(groups=4), {}, "s")
+    j = plan_json(g, link=2)["plan"]
+    assert j["linked_shuffles"] == 0 and sum(1 for c in j["chains"] if c["kind"] == "elt") == 4   # one strided copy per group
+
+
 def test_plan_option_errors():
     G = X.graph_from_workload(wg.single_chain(batch=1))
     try:
@@ -144,6 +160,31 @@ def test_linking_patterns_of_the_workloads():
     assert vgg["chains"][0]["kind"] == "conv" and vgg["chains"][0]["loader"] == "stem"
     vgg1 = plan_json(wg.build(3, 2, draw=False), link=1, compute=X.XENOS_BF16)["plan"]
     assert vgg1["chains"][0]["name"] == "import" and vgg1["chains"][1]["loader"] == "vector"
+
+
+def test_shufflenet_units_link_their_shuffles():
+    # ShuffleNet (Section 7.1): every unit ends in concat -> channel shuffle.  Linked, the shuffle is the order in which
+    # the concat's parts are stored: no pass of its own, one copy per unit for the half that no chain produces (the 13
+    # units that pass half their input through), none for the 3 down-sampling units.
+    g = wg.shufflenet_v2(batch=1, draw=False)
+    n_shuffle = sum(1 for op in g.ops if op.kind == "shuffle")
+    assert n_shuffle == 16
+    plans = {link: plan_json(g, link=link, compute=1)["plan"] for link in (0, 1, 2, 3)}
+    for link in (2, 3):
+        j = plans[link]
+        assert j["linked_shuffles"] == n_shuffle
+        assert sum(1 for c in j["chains"] if c["kind"] == "elt") == 13
+        ran = sorted(o for c in j["chains"] for o in c["ops"])
+        gone = {i for i, op in enumerate(g.ops) if op.kind in ("shuffle", "slice")}    # views and store orders: no pass
+        cats = {i for i, op in enumerate(g.ops) if op.kind == "concat"}
+        assert set(ran) | gone | cats == set(range(len(g.ops))) and not (set(ran) & {i for i in gone if g.ops[i].kind == "shuffle"})
+    for link in (0, 1):
+        j = plans[link]
+        assert j["linked_shuffles"] == 0
+        # un-linked: concat copies both parts, the shuffle copies both groups
+        assert sum(1 for c in j["chains"] if c["kind"] == "elt" and "group" in c["name"]) == 2 * n_shuffle
+    assert plans[2]["hbm_bytes"] < plans[1]["hbm_bytes"] < plans[0]["hbm_bytes"]
+    assert plans[2]["n_chains"] < plans[1]["n_chains"] < plans[0]["n_chains"]
 
 
 @pytest.mark.parametrize("cfg,batch,compute", [(1, 1, 0), (2, 32, 1), (3, 32, 1), (4, 32, 0)])

@@ -413,6 +413,74 @@ def test_graph_replay_matches_eager_every_time(net):
         s.close()
 
 
+# ------------------------------------------------------------------------------------------ channel slice / shuffle
+def shuffle_graph(kind, n=2, c=32, hw=13, seed=5):
+    b = wg.builder("shuffle_" + kind, (n, c, hw, hw), seed, nonzero_bias=True)
+    x = b.cbr(0, c, 1, name="pre")                           # an internal tensor to slice
+    h = c // 2
+    if kind == "unit":                                        # ShuffleNet unit: pass-through half + 1x1 -> dw 3x3 -> 1x1 branch
+        lo, hi = b.slice(x, 0, h), b.slice(x, h, h)
+        r = b.cbr(hi, h, 1, name="pw1")
+        r = b.cbr(r, h, 3, 1, 1, groups=h, name="dw", relu=False)
+        r = b.cbr(r, h, 1, name="pw2")
+        t = b.shuffle(b.concat([lo, r]), 2)
+    elif kind == "down":                                      # down-sampling unit: both parts end dense convolution chains
+        l = b.cbr(x, c, 3, 2, 1, groups=c, name="l.dw", relu=False)
+        l = b.cbr(l, h, 1, name="l.pw")
+        r = b.cbr(x, h, 1, name="r.pw1")
+        r = b.cbr(r, h, 3, 2, 1, groups=h, name="r.dw", relu=False)
+        r = b.cbr(r, h, 1, name="r.pw2")
+        t = b.shuffle(b.concat([l, r]), 2)
+    elif kind == "three":                                     # three groups; parts: 3x3 convolution, pooled tensor, plain 1x1
+        p1 = b.cbr(x, 24, 3, 1, 1, name="a")
+        p2 = b.slice(b.maxpool(x, 3, 1, 1), 8, 24)
+        p3 = b.cbr(x, 24, 1, name="c", relu=False)
+        t = b.shuffle(b.concat([p1, p2, p3]), 3)
+    elif kind == "alone":                                     # shuffle with no concat before it: strided copies
+        t = b.shuffle(b.cbr(x, 24, 3, 1, 1, name="a"), 4)
+    elif kind == "shared":                                    # the concat has a second reader: the shuffle cannot be linked
+        cat = b.concat([b.cbr(x, h, 1, name="a"), b.cbr(x, h, 1, name="b")])
+        t = b.add(b.shuffle(cat, 2), cat)
+    elif kind == "odd":                                       # ranges off the 16-byte channel groups
+        lo, hi = b.slice(x, 3, 13), b.slice(x, 16, 13)
+        r = b.cbr(hi, 13, 3, 1, 1, name="a")
+        t = b.shuffle(b.concat([lo, r]), 2)
+    elif kind == "slice_out":
+        return b.finish(b.slice(x, 8, 16))
+    elif kind == "shuffle_out":
+        return b.finish(b.shuffle(b.concat([b.cbr(x, h, 1, name="a"), b.cbr(x, h, 1, name="b")]), 2))
+    else:
+        raise ValueError(kind)
+    t = b.cbr(t, 24, 3, 1, 1, name="post")                    # a consumer that mixes the channels: their order matters
+    return b.finish(t)
+
+
+SHUFFLE_KINDS = ["unit", "down", "three", "alone", "shared", "odd", "slice_out", "shuffle_out"]
+
+
+@pytest.mark.parametrize("compute", [0, 1])
+@pytest.mark.parametrize("kind", SHUFFLE_KINDS)
+def test_channel_slice_and_shuffle(kind, compute):
+    # ShuffleNet (one of the evaluation models of Section 7.1): the shuffle after a concat is the order in which the
+    # concat's parts are stored, a slice is a view; every other arrangement falls back to strided copies
+    g = shuffle_graph(kind)
+    ref = xo.forward(g)
+    linked = {"unit": 1, "down": 1, "three": 1, "odd": 1}.get(kind, 0)
+    for link in (3, 2, 1, 0):
+        y, info = check(g, ref, compute=compute, link=link)
+        assert info["linked_shuffles"] == (linked if link >= 2 else 0)
+    y1, _ = run_gpu(g, compute=compute, link=2, split=0)
+    y2, _ = run_gpu(g, compute=compute, link=2)
+    assert np.array_equal(y1, y2)
+    if kind == "unit":
+        # the only passes of the unit besides its chains: the copy of the pass-through half
+        _, info = run_gpu(g, compute=compute, link=2)
+        assert sum(1 for ch in info["chains"] if ch["kind"] == "elt") == 1
+    if kind == "down":
+        _, info = run_gpu(g, compute=compute, link=2)
+        assert sum(1 for ch in info["chains"] if ch["kind"] == "elt") == 0
+
+
 # ------------------------------------------------------------------------------------------ whole graphs
 def test_cfg0_single_chain():
     g = wg.build(0, 1)
@@ -427,6 +495,7 @@ SMALL = [
     (wg.resnet18, dict(hw=64, width=0.25, classes=24)),
     (wg.vgg16, dict(hw=32, width=0.25, fc_dim=64, classes=24)),
     (wg.squeezenet11, dict(hw=95, classes=24)),
+    (wg.shufflenet_v2, dict(hw=64, channels=(32, 64, 112), repeats=(2, 3, 2), stem=8, last=128, classes=24)),
 ]
 
 
@@ -439,13 +508,13 @@ def test_reduced_networks_all_link_levels(builder, kw, compute):
         check(g, ref, compute=compute, link=link)
 
 
-@pytest.mark.parametrize("cfg,compute", [(1, 0), (1, 1), (2, 1), (4, 0), (4, 1)])
+@pytest.mark.parametrize("cfg,compute", [(1, 0), (1, 1), (2, 1), (4, 0), (4, 1), (5, 0), (5, 1)])
 def test_full_size_batch1(cfg, compute):
     g = wg.build(cfg, 1)
     ref = xo.forward(g)
     check(g, ref, compute=compute, link=2)
     check(g, ref, compute=compute, link=0)
-    if cfg == 1:
+    if cfg in (1, 5):
         check(g, ref, compute=compute, link=3)
 
 
