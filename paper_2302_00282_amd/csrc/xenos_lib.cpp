@@ -183,6 +183,11 @@ struct Planner {
   std::vector<int> ileave;                   // concat node -> groups of the channel shuffle linked into it (0 = none):
                                              // part j of the concat is written to channels j, j + groups, j + 2 groups, ...
   std::vector<char> alias_shuffle;           // shuffle node whose output IS its (already interleaved) concat input
+  // Two-group shuffle finished by one chain: the chain that ends in tensor `key` stores its channels AND those of the
+  // other part (tensor `other`, complete before the chain runs) alternately into the concat buffer `cat_tid`
+  struct Fin { int cat_tid; int pos; int other; };
+  std::map<int, Fin> fin;
+  std::vector<char> fin_concat;              // concat node whose two parts are written by such a chain
 
   Planner(const xenos_graph& g_, xenos_plan& p_) : g(g_), p(p_) {}
 
@@ -299,7 +304,10 @@ struct Planner {
     const Shape s = tshape[tid];
     int v;
     auto it = placed.find(tid);
-    if (it != placed.end()) {
+    auto fi = fin.find(tid);
+    if (fi != fin.end()) {
+      v = out_view_for(fi->second.cat_tid, false);               // the chain writes the whole concat buffer
+    } else if (it != placed.end()) {
       const int cat = it->second.cat_tid;
       const int cv = out_view_for(cat, false);
       const View& c = p.views[cv];
@@ -354,19 +362,21 @@ struct Planner {
   // on a dense convolution that does not read the graph input (the general convolution kernel stores single elements
   // at any stride; the first-layer, halo, depthwise and pooling epilogues store 16-byte channel groups only), when
   // nothing else reads the tensor or the intermediate ones.
-  bool stores_strided(int tid) const {
-    if (tid < 1 || tid == out_tid || placed.count(tid) || consumers[tid].size() != 1) return false;
+  bool stores_strided(int tid) const { return plain_chain_conv(tid) >= 0; }
+  // (the convolution node of that chain, or -1)
+  int plain_chain_conv(int tid) const {
+    if (tid < 1 || tid == out_tid || placed.count(tid) || consumers[tid].size() != 1) return -1;
     int t = tid;
     if (nodes[t - 1].kind == XENOS_OP_RELU) {
       t = nodes[t - 1].in[0];
-      if (t < 1 || t == out_tid || consumers[t].size() != 1) return false;
+      if (t < 1 || t == out_tid || consumers[t].size() != 1) return -1;
     }
     while (nodes[t - 1].kind == XENOS_OP_BIAS || nodes[t - 1].kind == XENOS_OP_BN) {
       t = nodes[t - 1].in[0];
-      if (t < 1 || t == out_tid || consumers[t].size() != 1) return false;
+      if (t < 1 || t == out_tid || consumers[t].size() != 1) return -1;
     }
     const Node& c = nodes[t - 1];
-    return c.kind == XENOS_OP_CONV && desc(c).groups == 1 && c.in[0] != 0;
+    return c.kind == XENOS_OP_CONV && desc(c).groups == 1 && c.in[0] != 0 ? t - 1 : -1;
   }
 
   // Does the chain that starts at convolution node `c` end in a tensor stored with a channel stride?
@@ -375,6 +385,7 @@ struct Planner {
     for (;;) {
       auto it = placed.find(cur);
       if (it != placed.end()) return it->second.c_stride > 1;
+      if (fin.count(cur)) return true;
       const int nx = single_consumer(cur);
       if (nx < 0) return false;
       const int k = nodes[nx].kind;
@@ -541,7 +552,7 @@ struct Planner {
     // halo-staged 3x3 kernel: a TH x TW block of output pixels (256 GEMM rows) x 128 channels per workgroup,
     // tiles laid over the images stacked with their padding rows
     // (the halo kernel stores 16-byte channel groups only: outputs and shortcuts that cannot take them use conv_kernel)
-    const bool halo_ok = !st.gap_finish && c.vec_out && (!c.has_res || c.vec_res) && !c.dw_w && c.R == 3 && c.S == 3 && c.stride == 1 && c.pad == 1 && !st.scalar && c.kchunk &&
+    const bool halo_ok = !st.gap_finish && !c.ileave && c.vec_out && (!c.has_res || c.vec_res) && !c.dw_w && c.R == 3 && c.S == 3 && c.stride == 1 && c.pad == 1 && !st.scalar && c.kchunk &&
                          (c.mode == M_FLAT || (c.mode == M_ZIGZAG && c.H % 2 == 0 && c.W % 2 == 0)) &&
                          (long long)c.N * c.in_sN < (1ll << 31) && conv_lds_bytes(kHaloCfg, c.mode) <= p.hw.lds_bytes_per_cu;
     // a forced configuration binds the chains it applies to; the others get the planner's choice
@@ -713,6 +724,7 @@ struct Planner {
     free_concat.assign(nn, 0);
     ileave.assign(nn, 0);
     alias_shuffle.assign(nn, 0);
+    fin_concat.assign(nn, 0);
 
     // Channel shuffle as a layout-only link: shuffle(concat(x_0 .. x_{g-1})) with g groups and g equal parts puts channel
     // i of part j at position i * g + j, so the concat buffer is written interleaved and the shuffle moves nothing.  A
@@ -734,6 +746,22 @@ struct Planner {
         if (!ok) continue;
         ileave[t - 1] = g;
         alias_shuffle[j] = 1;
+        // Two groups of whole 16-byte channel groups: the part whose plain convolution chain runs last reads the other
+        // part (complete by then) in its epilogue and stores both, alternating, with 16-byte stores; nothing else is
+        // copied or stored with a stride.
+        if (g == 2 && tshape[cat.in[0]].c % p.ce == 0) {
+          int best = -1, best_conv = -1;
+          for (int a = 0; a < 2; ++a) {
+            const int cv = plain_chain_conv(cat.in[a]), other = cat.in[1 - a];
+            if (cv < 0 || other < 1 || other == out_tid || other - 1 >= cv) continue;   // the other part must be complete first
+            if (cv > best_conv) { best = a; best_conv = cv; }
+          }
+          if (best >= 0) {
+            fin[cat.in[best]] = Fin{t, best, cat.in[1 - best]};
+            fin_concat[t - 1] = 1;
+            continue;
+          }
+        }
         for (int a = 0; a < g; ++a)
           if (stores_strided(cat.in[a])) placed[cat.in[a]] = Place{t, a, g};
       }
@@ -747,8 +775,9 @@ struct Planner {
         bool ok = ctot % p.ce == 0;
         int off = 0;
         for (int t : nodes[i].in) {
-          if (t == 0 || t == out_tid || placed.count(t) || off % p.ce != 0) ok = false;
+          if (t == 0 || t == out_tid || placed.count(t) || fin.count(t) || off % p.ce != 0) ok = false;
           else if (nodes[t - 1].kind == XENOS_OP_CONCAT) ok = false;
+          else if (nodes[t - 1].kind == XENOS_OP_SHUFFLE && alias_shuffle[t - 1]) ok = false;   // (its tensor is its concat's buffer)
           off += tshape[t].c;
         }
         for (size_t a = 0; a < nodes[i].in.size(); ++a)
@@ -1093,6 +1122,20 @@ struct Planner {
           st.v_in2 = tview[res_tid];
           a.res_sN = p.views[st.v_in2].sN; a.res_sP = p.views[st.v_in2].sP;
         }
+        const auto fit = fin.find(cur);
+        if (fit != fin.end()) {
+          // this chain finishes a two-group shuffle: the other part of the concat comes in where a shortcut would
+          const int other = fit->second.other;
+          if (has_res || pool_node >= 0 || from_dw || from_pair || is_fc || !available(other))
+            return fail(XENOS_EUNSUPPORTED, "%s: cannot finish the channel shuffle of its concat", st.name.c_str());
+          xenos_status rc = need_internal_input(other, st.name.c_str(), &st.v_in2);
+          if (rc != XENOS_OK) return rc;
+          const View& rv = p.views[st.v_in2];
+          if (K % p.ce || rv.off % p.ce || rv.sP % p.ce || rv.sN % p.ce || rv.sK != 1)
+            return fail(XENOS_EUNSUPPORTED, "%s: the other half of its shuffled concat is not aligned", st.name.c_str());
+          a.res_sN = rv.sN; a.res_sP = rv.sP;
+          a.ileave = fit->second.pos + 1;
+        }
         a.pool = POOL_NONE; a.mode = M_FLAT;
         a.PH = a.OH; a.PW = a.OW;
         if (pool_node >= 0) {
@@ -1121,7 +1164,7 @@ struct Planner {
         a.M_total = a.mode == M_FLAT ? a.N * a.OH * a.OW : a.mode == M_ZIGZAG ? a.N * a.PH * a.PW * 4 : a.OH * a.OW;
         // A fully connected chain over at most 32 images streams its weights once: the kernel made for that keeps many
         // loads in flight per unit and shares the reduction out over workgroups (the summing pass finishes the chain)
-        st.fc_stream = p.dt == DT_BF16 && p.opts.split && p.opts.tile == 0 && !from_dw && !from_pair && a.mode == M_FLAT && !st.gap_finish &&
+        st.fc_stream = !a.ileave && p.dt == DT_BF16 && p.opts.split && p.opts.tile == 0 && !from_dw && !from_pair && a.mode == M_FLAT && !st.gap_finish &&
                        a.OH == 1 && a.OW == 1 && a.R == is.h && a.S == is.w && a.pad == 0 && is.n <= 32 && !st.scalar && a.C == is.c &&
                        ((long long)a.R * a.S * a.C) % 64 == 0 && (long long)a.R * a.S * a.C >= 512 && (long long)a.R * a.S * a.C < (1ll << 30) &&
                        iv.sN % p.ce == 0 && iv.sN >= (long long)a.R * a.S * a.C && (a.R * a.S == 1 || (iv.sP == a.C && iv.sN == (long long)a.R * a.S * a.C));
@@ -1147,6 +1190,7 @@ struct Planner {
         // 16-byte channel-group accesses need unit channel stride, the compute type and aligned slices
         a.vec_out = ov.sK == 1 && (!ov.f32 || p.dt == DT_F32) && ov.esz == p.esz && K % p.ce == 0 && ov.off % p.ce == 0 &&
                     ov.sP % p.ce == 0 && ov.sN % p.ce == 0;
+        if (a.ileave && !a.vec_out) return fail(XENOS_EUNSUPPORTED, "%s: shuffled concat buffer is not aligned", st.name.c_str());
         if (has_res) {
           const View& rv = p.views[st.v_in2];
           a.vec_res = K % p.ce == 0 && rv.off % p.ce == 0 && rv.sP % p.ce == 0 && rv.sN % p.ce == 0;
@@ -1165,13 +1209,13 @@ struct Planner {
         if (from_dw) st.bytes_w += pro.bytes_w;
         if (from_pair) st.bytes_w += ppro.bytes_w;
         st.bytes_in = view_bytes(st.v_in); st.bytes_out = view_bytes(st.v_out);
-        if (has_res) st.bytes_res = view_bytes(st.v_in2);
+        if (has_res || a.ileave) st.bytes_res = view_bytes(st.v_in2);
 
         // Parameter split beyond K (Section 4.2.2: C, R, S splits need an extra reduction): when the outC x H/W
         // partition leaves most compute units idle and the reduction is long, split it across workgroups too.
         // Shares are summed in index order by a second pass, so the result does not depend on timing.
         const int nsteps = a.Kred_pad / (kRowBytes / p.esz);
-        if (st.fc_stream || (p.opts.split && st.cfg < kHaloCfg && a.mode == M_FLAT && (!from_dw || (st.gap_finish && a.dw_panel > 0)) &&
+        if (st.fc_stream || (p.opts.split && !a.ileave && st.cfg < kHaloCfg && a.mode == M_FLAT && (!from_dw || (st.gap_finish && a.dw_panel > 0)) &&
             (st.gap_finish || (a.ntiles * 2 <= p.hw.num_cu && nsteps >= 32)))) {
           int ks = std::min({(2 * p.hw.num_cu + a.ntiles - 1) / a.ntiles, nsteps / 8, 32});
           if (st.gap_finish) ks = std::max(ks, 1);
@@ -1250,7 +1294,7 @@ struct Planner {
       const int ov = out_view_for(i + 1, false);
       if (!p.views[ov].internal_nhwc() || p.views[ov].f32) return fail(XENOS_EUNSUPPORTED, "concat output must be internal");
       for (size_t j = 0; j < nd.in.size(); ++j) {
-        if (placed.count(nd.in[j])) continue;
+        if (placed.count(nd.in[j]) || fin_concat[i]) continue;
         Step cs;
         cs.kind = S_ELT; cs.name = st.name + ".part" + std::to_string(j);
         cs.ops.push_back(nd.src);
@@ -1485,10 +1529,10 @@ void write_plan_json(xenos_plan& p) {
       const TileCfg& tc = s.cfg == kHaloCfg ? halo_tc : s.cfg == kStemCfg ? stem_tc : s.cfg == kStemLdsCfg ? stem_lds_tc : s.cfg == kPairCfg ? pair_tc : s.cfg == kFcCfg ? fc_tc : kTileCfgs[s.cfg];
       snprintf(buf, sizeof buf, ",\"mode\":\"%s\",\"loader\":\"%s\",\"N\":%d,\"C\":%d,\"H\":%d,\"W\":%d,\"K\":%d,\"R\":%d,\"S\":%d,\"stride\":%d,"
                "\"pad\":%d,\"OH\":%d,\"OW\":%d,\"PH\":%d,\"PW\":%d,\"pool\":%d,\"relu\":%d,\"res\":%d,\"bm\":%d,\"bn\":%d,\"tiles_m\":%d,"
-               "\"tiles_n\":%d,\"grid\":%d,\"lds\":%zu,\"pph\":%d,\"ppw\":%d,\"patch_h\":%d,\"patch_w\":%d,\"out_c_off\":%lld,\"out_sP\":%lld,\"halo\":%d,\"th\":%d,\"tw\":%d,\"dw_linked\":%d,\"ksplit\":%d,\"candidates\":%d,\"tuned\":%d,\"plin\":%d",
+               "\"tiles_n\":%d,\"grid\":%d,\"lds\":%zu,\"pph\":%d,\"ppw\":%d,\"patch_h\":%d,\"patch_w\":%d,\"out_c_off\":%lld,\"out_sP\":%lld,\"halo\":%d,\"th\":%d,\"tw\":%d,\"dw_linked\":%d,\"ksplit\":%d,\"candidates\":%d,\"tuned\":%d,\"plin\":%d,\"shuffle_store\":%d",
                kModeNames[c.mode], s.stem ? "stem" : c.pair ? "pair" : s.fc_stream ? "stream" : s.scalar ? "scalar" : "vector", c.N, c.C, c.H, c.W, c.K, c.R, c.S, c.stride, c.pad, c.OH, c.OW,
                c.PH, c.PW, c.pool, c.relu, c.has_res, tc.bm, tc.bn, c.tiles_m, c.tiles_n, c.grid, s.lds, c.pph, c.ppw, c.patch_h,
-               c.patch_w, p.views[s.v_out].off, c.out_sP, s.cfg == kHaloCfg ? 1 : 0, c.th, c.tw, s.dw_w_off >= 0 ? 1 : 0, c.ksplit > 1 ? c.ksplit : 1, (int)s.cands.size(), s.tuned, s.cfg == kHaloCfg ? c.halo_plin : 0);
+               c.patch_w, p.views[s.v_out].off, c.out_sP, s.cfg == kHaloCfg ? 1 : 0, c.th, c.tw, s.dw_w_off >= 0 ? 1 : 0, c.ksplit > 1 ? c.ksplit : 1, (int)s.cands.size(), s.tuned, s.cfg == kHaloCfg ? c.halo_plin : 0, c.ileave);
       j += buf;
     }
     j += "}";

@@ -164,8 +164,8 @@ def test_linking_patterns_of_the_workloads():
 
 def test_shufflenet_units_link_their_shuffles():
     # ShuffleNet (Section 7.1): every unit ends in concat -> channel shuffle.  Linked, the shuffle is the order in which
-    # the concat's parts are stored: no pass of its own, one copy per unit for the half that no chain produces (the 13
-    # units that pass half their input through), none for the 3 down-sampling units.
+    # the concat's parts are stored: no pass of its own.  The last chain of a unit reads the other half (the pass-through
+    # half, or the other branch of a down-sampling unit) in its epilogue and stores both, alternating: no copy either.
     g = wg.shufflenet_v2(batch=1, draw=False)
     n_shuffle = sum(1 for op in g.ops if op.kind == "shuffle")
     assert n_shuffle == 16
@@ -173,7 +173,8 @@ def test_shufflenet_units_link_their_shuffles():
     for link in (2, 3):
         j = plans[link]
         assert j["linked_shuffles"] == n_shuffle
-        assert sum(1 for c in j["chains"] if c["kind"] == "elt") == 13
+        assert sum(1 for c in j["chains"] if c["kind"] == "elt") == 0
+        assert sum(1 for c in j["chains"] if c.get("shuffle_store")) == n_shuffle
         ran = sorted(o for c in j["chains"] for o in c["ops"])
         gone = {i for i, op in enumerate(g.ops) if op.kind in ("shuffle", "slice")}    # views and store orders: no pass
         cats = {i for i, op in enumerate(g.ops) if op.kind == "concat"}

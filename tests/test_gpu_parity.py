@@ -415,13 +415,16 @@ def test_graph_replay_matches_eager_every_time(net):
 
 # ------------------------------------------------------------------------------------------ channel slice / shuffle
 def shuffle_graph(kind, n=2, c=32, hw=13, seed=5):
+    mid_groups = 0
+    if kind == "unit24":                                      # halves of 12 channels: whole 16-byte groups in fp32 only
+        kind, c, mid_groups = "unit", 24, 1                   # (a dense 3x3 in the branch: depthwise needs whole groups)
     b = wg.builder("shuffle_" + kind, (n, c, hw, hw), seed, nonzero_bias=True)
     x = b.cbr(0, c, 1, name="pre")                           # an internal tensor to slice
     h = c // 2
     if kind == "unit":                                        # ShuffleNet unit: pass-through half + 1x1 -> dw 3x3 -> 1x1 branch
         lo, hi = b.slice(x, 0, h), b.slice(x, h, h)
         r = b.cbr(hi, h, 1, name="pw1")
-        r = b.cbr(r, h, 3, 1, 1, groups=h, name="dw", relu=False)
+        r = b.cbr(r, h, 3, 1, 1, groups=mid_groups or h, name="dw", relu=False)
         r = b.cbr(r, h, 1, name="pw2")
         t = b.shuffle(b.concat([lo, r]), 2)
     elif kind == "down":                                      # down-sampling unit: both parts end dense convolution chains
@@ -455,30 +458,36 @@ def shuffle_graph(kind, n=2, c=32, hw=13, seed=5):
     return b.finish(t)
 
 
-SHUFFLE_KINDS = ["unit", "down", "three", "alone", "shared", "odd", "slice_out", "shuffle_out"]
+SHUFFLE_KINDS = ["unit", "unit24", "down", "three", "alone", "shared", "odd", "slice_out", "shuffle_out"]
 
 
 @pytest.mark.parametrize("compute", [0, 1])
 @pytest.mark.parametrize("kind", SHUFFLE_KINDS)
 def test_channel_slice_and_shuffle(kind, compute):
     # ShuffleNet (one of the evaluation models of Section 7.1): the shuffle after a concat is the order in which the
-    # concat's parts are stored, a slice is a view; every other arrangement falls back to strided copies
+    # concat's parts are stored, a slice is a view; every other arrangement falls back to strided copies.  With two
+    # groups of whole 16-byte channel groups the chain that ends the unit stores both halves, alternating, with vector
+    # stores ("shuffle_store"); otherwise each chain stores its part with a channel stride and other parts are copied.
     g = shuffle_graph(kind)
     ref = xo.forward(g)
-    linked = {"unit": 1, "down": 1, "three": 1, "odd": 1}.get(kind, 0)
+    linked = {"unit": 1, "unit24": 1, "down": 1, "three": 1, "odd": 1}.get(kind, 0)
     for link in (3, 2, 1, 0):
         y, info = check(g, ref, compute=compute, link=link)
         assert info["linked_shuffles"] == (linked if link >= 2 else 0)
     y1, _ = run_gpu(g, compute=compute, link=2, split=0)
     y2, _ = run_gpu(g, compute=compute, link=2)
     assert np.array_equal(y1, y2)
-    if kind == "unit":
-        # the only passes of the unit besides its chains: the copy of the pass-through half
-        _, info = run_gpu(g, compute=compute, link=2)
-        assert sum(1 for ch in info["chains"] if ch["kind"] == "elt") == 1
-    if kind == "down":
-        _, info = run_gpu(g, compute=compute, link=2)
-        assert sum(1 for ch in info["chains"] if ch["kind"] == "elt") == 0
+    _, info = run_gpu(g, compute=compute, link=2)
+    n_copy = sum(1 for ch in info["chains"] if ch["kind"] == "elt")
+    n_fin = sum(1 for ch in info["chains"] if ch.get("shuffle_store"))
+    if kind in ("unit", "down"):
+        assert (n_copy, n_fin) == (0, 1)                       # no pass besides the unit's chains
+    if kind == "unit24":
+        # fp32: 12 channels are three 16-byte groups; bf16: the slices are copied (they end inside a group), the branch
+        # stores with a channel stride and the pass-through half is copied to its positions
+        assert (n_copy, n_fin) == ((0, 1) if compute == 0 else (3, 0))
+    if kind in ("three", "odd"):
+        assert n_fin == 0 and n_copy >= 1
 
 
 # ------------------------------------------------------------------------------------------ whole graphs
