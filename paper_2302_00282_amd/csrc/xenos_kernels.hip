@@ -82,6 +82,28 @@ __device__ __forceinline__ float fmx_raw(float a, float b) {
   return r;
 }
 
+// Two-group channel shuffle done by a store: CE finished channels of a pixel (`mine`) and the same channels of the other
+// part of the concat (`oth`) alternate in the output, `first` = mine at the even positions.  Two 16-byte stores.
+template <typename T>
+__device__ __forceinline__ void ileave_store(T* dst, const u32x4_t& mine, const u32x4_t& oth, bool first) {
+  u32x4_t w[2];
+  if (sizeof(T) == 2) {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const uint32_t m = (mine[e >> 1] >> ((e & 1) * 16)) & 0xffffu, o = (oth[e >> 1] >> ((e & 1) * 16)) & 0xffffu;
+      w[e >> 2][e & 3] = first ? (m | (o << 16)) : (o | (m << 16));
+    }
+  } else {
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      w[e >> 1][(e & 1) * 2] = first ? mine[e] : oth[e];
+      w[e >> 1][(e & 1) * 2 + 1] = first ? oth[e] : mine[e];
+    }
+  }
+  *(u32x4_t*)dst = w[0];
+  *(u32x4_t*)(dst + Tr<T>::CE) = w[1];
+}
+
 constexpr int NT = 256;          // threads per workgroup (4 wavefronts of 64)
 constexpr int ROWB = kRowBytes;  // data bytes per tile row per reduction step
 constexpr int CPR = ROWB / 16;   // 16-byte chunks per tile row
@@ -533,26 +555,7 @@ __global__ __launch_bounds__(NT, 2) void conv_kernel(const ConvArgs a) {
           if (MODE == M_FLAT && a.ileave) {
             // two-group channel shuffle of concat(this chain, other part) done by the store: the finished channels and
             // the other part's channels of the same pixel alternate, 2 CE channels = two 16-byte stores
-            const u32x4_t mine = tr::pack(v);
-            const u32x4_t oth = *(const u32x4_t*)((const T*)a.res + rb_ + k0);
-            const bool first = a.ileave == 1;                      // this chain's channels take the even positions
-            u32x4_t w[2];
-            if (sizeof(T) == 2) {
-#pragma unroll
-              for (int e = 0; e < 8; ++e) {
-                const uint32_t m = (mine[e >> 1] >> ((e & 1) * 16)) & 0xffffu, o = (oth[e >> 1] >> ((e & 1) * 16)) & 0xffffu;
-                w[e >> 2][e & 3] = first ? (m | (o << 16)) : (o | (m << 16));
-              }
-            } else {
-#pragma unroll
-              for (int e = 0; e < 4; ++e) {
-                w[e >> 1][(e & 1) * 2] = first ? mine[e] : oth[e];
-                w[e >> 1][(e & 1) * 2 + 1] = first ? oth[e] : mine[e];
-              }
-            }
-            T* dst = (T*)a.out + obase + 2 * k0;
-            *(u32x4_t*)dst = w[0];
-            *(u32x4_t*)(dst + CE) = w[1];
+            ileave_store<T>((T*)a.out + obase + 2 * k0, tr::pack(v), *(const u32x4_t*)((const T*)a.res + rb_ + k0), a.ileave == 1);
           } else if (a.vec_out) {
             *(u32x4_t*)((T*)a.out + obase + k0) = tr::pack(v);
           } else {
@@ -2277,7 +2280,12 @@ __global__ __launch_bounds__(NT) void dwpw_kernel(const ConvArgs a) {
       const int m = tile_m * BM + r, k0 = tile_n * BN + cg * CE;
       if (m >= a.M_total || k0 >= a.K) continue;
       const int n = m / OHW, q = m - n * OHW;
-      *(u32x4_t*)((T*)a.out + (long long)n * a.out_sN + (long long)q * a.out_sP + k0) = *(const u32x4_t*)(stg + r * SPB + cg * 16);
+      const u32x4_t mine = *(const u32x4_t*)(stg + r * SPB + cg * 16);
+      if (a.ileave)
+        ileave_store<T>((T*)a.out + (long long)n * a.out_sN + (long long)q * a.out_sP + 2 * k0, mine,
+                        *(const u32x4_t*)((const T*)a.res + (long long)n * a.res_sN + (long long)q * a.res_sP + k0), a.ileave == 1);
+      else
+        *(u32x4_t*)((T*)a.out + (long long)n * a.out_sN + (long long)q * a.out_sP + k0) = mine;
     }
     __syncthreads();
   }
@@ -2350,9 +2358,10 @@ int launch_conv(const ConvArgs& a, int dtype, int cfg, int scalar_loader, void* 
   if (cfg < kHaloCfg && a.xcd_m != 1 && a.xcd_m != 2 && a.xcd_m != 4 && a.xcd_m != 8) return (int)hipErrorInvalidValue;
   if (a.ksplit >= 1 && (a.mode != M_FLAT || !a.part || a.steps_per_split < 1 || (a.dw_w && a.dw_panel <= 0) || cfg == kHaloCfg)) return (int)hipErrorInvalidValue;
   if (a.ileave) {
-    // the interleaving store exists in the general kernel's pixel-major epilogue only; it moves whole 16-byte groups
+    // the interleaving store exists in the pixel-major epilogues of the general kernel and of the depthwise-panel kernel;
+    // it moves whole 16-byte groups
     const int ce = dtype == DT_BF16 ? 8 : 4, esz = dtype == DT_BF16 ? 2 : 4;
-    if (cfg >= kHaloCfg || a.mode != M_FLAT || a.has_res || a.ksplit >= 1 || a.dw_w || a.pair || !a.res || a.out_f32 || a.out_sK != 1 ||
+    if (cfg >= kHaloCfg || a.mode != M_FLAT || a.has_res || a.ksplit >= 1 || a.pair || !a.res || a.out_f32 || a.out_sK != 1 ||
         (a.ileave != 1 && a.ileave != 2) || a.K % ce != 0 || a.out_sP % ce != 0 || a.out_sN % ce != 0 || a.res_sP % ce != 0 || a.res_sN % ce != 0 ||
         ((uintptr_t)a.out % 16) != 0 || ((uintptr_t)a.res % 16) != 0 || a.out_sP < 2 * a.K || a.res_sP < a.K || esz * ce != 16)
       return (int)hipErrorInvalidValue;

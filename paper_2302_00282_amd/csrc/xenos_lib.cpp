@@ -385,7 +385,6 @@ struct Planner {
     for (;;) {
       auto it = placed.find(cur);
       if (it != placed.end()) return it->second.c_stride > 1;
-      if (fin.count(cur)) return true;
       const int nx = single_consumer(cur);
       if (nx < 0) return false;
       const int k = nodes[nx].kind;
@@ -1010,8 +1009,9 @@ struct Planner {
         // link level 3: depthwise -> pointwise.  The depthwise result is produced tile by tile inside the
         // pointwise kernel (as its A operand) and never written to memory.
         const int pw = link >= 3 && !placed.count(cur) ? single_consumer(cur) : -1;
-        // (a pointwise chain that stores with a channel stride, a part of a shuffled concat, has no 16-byte stores, which
-        // the depthwise-panel kernel needs; the element-wise form of the linked pair is slower than two chains)
+        // (a pointwise chain that stores with a channel stride, a part of a shuffled concat of more than two groups, has no
+        // 16-byte stores, which the depthwise-panel kernel needs; the element-wise form of the linked pair is slower than
+        // two chains.  The chain that finishes a two-group shuffle stores whole groups and can take the depthwise.)
         if (pw >= 0 && d.kh == d.kw && nodes[pw].kind == XENOS_OP_CONV && !chain_stores_strided(pw)) {
           const xenos_op_desc& pd = desc(nodes[pw]);
           // Every workgroup of the pointwise chain recomputes the depthwise result of its 64 pixels for all input
@@ -1126,7 +1126,7 @@ struct Planner {
         if (fit != fin.end()) {
           // this chain finishes a two-group shuffle: the other part of the concat comes in where a shortcut would
           const int other = fit->second.other;
-          if (has_res || pool_node >= 0 || from_dw || from_pair || is_fc || !available(other))
+          if (has_res || pool_node >= 0 || from_pair || is_fc || !available(other))
             return fail(XENOS_EUNSUPPORTED, "%s: cannot finish the channel shuffle of its concat", st.name.c_str());
           xenos_status rc = need_internal_input(other, st.name.c_str(), &st.v_in2);
           if (rc != XENOS_OK) return rc;
