@@ -949,7 +949,9 @@ struct Planner {
       bool stem = false, stem_lds = false;
       // (the gather form takes reductions up to kStemRed elements, the LDS-staged form up to 4 channels x 7 x 7 taps)
       if (!dw && !is_fc && nd.in[0] == 0 && in_lazy && link >= 2 && !has_res && (is.c * d.kh * d.kw <= kStemRed || (is.c <= 4 && d.kh <= 7 && d.kw <= 7)) &&
-          (K == 32 || K == 64) && is.h <= 8192 && (p.opts.tile == 0 || p.opts.tile == kStemCfg + 1)) {
+          // (32 or 64 output channels, or up to a quarter fewer: the kernels compute the padded count)
+          K <= 64 && K % p.ce == 0 && 4 * ((K <= 32 ? 32 : 64) - K) <= (K <= 32 ? 32 : 64) && is.h <= 8192 &&
+          conv_lds_bytes(kStemCfg, M_FLAT) <= p.hw.lds_bytes_per_cu && (p.opts.tile == 0 || p.opts.tile == kStemCfg + 1)) {
         // l2 = last node of the chain without its pooling, c2 = that node's output tensor
         const int l2 = pool_node < 0 ? last : absorbed.size() >= 2 ? absorbed[absorbed.size() - 2] : i;
         const int c2 = l2 + 1;
@@ -959,7 +961,7 @@ struct Planner {
         // takes a linked max-pooling of 2 or 3 wide windows at stride 2: 3 x 8 windows per tile, their convolution block
         // recomputed per tile.
         const View& gv = p.views[tview[0]];
-        stem_lds = p.dt == DT_BF16 && p.opts.tile == 0 && is.c <= 4 && d.kh == d.kw && d.kh >= 4 && d.kh <= 7 && d.stride_h == d.stride_w &&
+        stem_lds = p.dt == DT_BF16 && p.opts.tile == 0 && is.c <= 4 && d.kh == d.kw && d.kh >= 3 && d.kh <= 7 && d.stride_h == d.stride_w &&
                    (d.stride_h == 1 || d.stride_h == 2) && d.pad_h == d.pad_w && d.pad_h <= d.kh && gv.f32 && gv.sP == 1;
         bool keep_pool = false;
         if (stem_lds && pool_node >= 0 && !placed.count(cur) && cur != out_tid) {
@@ -969,7 +971,12 @@ struct Planner {
                       pd.pad_h == pd.pad_w && pd.pad_h >= 0 && pd.pad_h <= 1 && chh * cww <= kStemLdsTh * kStemLdsTw &&
                       ((chh - 1) * d.stride_h + d.kh) * ((cww - 1) * d.stride_h + d.kw) <= kStemLdsInMax;
         }
-        if ((stem_lds || is.c * d.kh * d.kw <= kStemRed) && (keep_pool || (c2 != out_tid && !placed.count(c2)))) {
+        // (a 3x3 layer takes the LDS-staged form only for its linked pooling: one launch for two, the same time at batch 32;
+        // without pooling the gather form is faster)
+        if (stem_lds && d.kh < 4 && !keep_pool) stem_lds = false;
+        // (a padded channel count only where the chain stays as linked as the general kernel would have it)
+        const bool padded = K != 32 && K != 64;
+        if ((stem_lds || is.c * d.kh * d.kw <= kStemRed) && (keep_pool || (c2 != out_tid && !placed.count(c2) && !(padded && pool_node >= 0)))) {
           stem = true;
           if (pool_node >= 0 && !keep_pool) { absorbed.pop_back(); pool_node = -1; cur = c2; last = l2; }
         } else {
@@ -1086,7 +1093,8 @@ struct Planner {
         if (from_pair) st.ops.insert(st.ops.begin(), ppro.ops.begin(), ppro.ops.end());
         const View& iv = p.views[vin];
         ConvArgs& a = st.conv;
-        a.N = is.n; a.C = std::max(is.c, iv.cphys); a.H = is.h; a.W = is.w;   // padding channels multiply zero weights
+        // padding channels multiply zero weights (not behind a linked depthwise producer: it has no weights for them)
+        a.N = is.n; a.C = from_dw ? is.c : std::max(is.c, iv.cphys); a.H = is.h; a.W = is.w;
         a.K = K;
         if (is_fc) { a.R = is.h; a.S = is.w; a.stride = 1; a.pad = 0; a.OH = 1; a.OW = 1; }
         else { a.R = d.kh; a.S = d.kw; a.stride = d.stride_h; a.pad = d.pad_h; a.OH = tshape[i + 1].h; a.OW = tshape[i + 1].w; }
@@ -1099,10 +1107,19 @@ struct Planner {
           a.dw_sN = iv.sN; a.dw_sP = iv.sP;
           a.dw_w = (const void*)1;           // marks the chain for the split planner; patched at launch
         }
+        // The first-layer kernels compute 32 or 64 channels: another channel count (24 in the ShuffleNet graph) is padded
+        // with zero weights, and the output tensor gets the padded channel pitch (its consumers read the first K).
+        const int Kk = st.stem ? (K <= 32 ? 32 : 64) : K;
+        a.K = Kk;
+        if (Kk != K) {
+          if (tview[cur] >= 0 || placed.count(cur) || cur == out_tid) return fail(XENOS_EUNSUPPORTED, "%s: padded first layer needs a tensor of its own", st.name.c_str());
+          tview[cur] = internal_view(tshape[cur], -1, Kk);
+          p.views[tview[cur]].cphys = Kk;
+        }
         if (st.stem_lds) {
           // weights [K][steps * 16] with reduction slot = tap * 4 + channel (4 taps per MFMA step of 16)
           const int taps = d.kh * d.kw, nstep = taps <= 12 ? 3 : taps <= 28 ? 7 : 13;
-          std::vector<uint16_t> ws((size_t)K * nstep * 16, 0);
+          std::vector<uint16_t> ws((size_t)Kk * nstep * 16, 0);
           for (int k = 0; k < K; ++k)
             for (int c = 0; c < is.c; ++c)
               for (int t = 0; t < taps; ++t) ws[(size_t)k * nstep * 16 + t * 4 + c] = f2bf_host(go.weight[((size_t)k * is.c + c) * taps + t]);

@@ -148,9 +148,17 @@ def test_linking_patterns_of_the_workloads():
     res32 = plan_json(wg.build(2, 32, draw=False), link=2, compute=X.XENOS_BF16)["plan"]
     assert [c for c in res32["chains"] if c["kind"] == "conv"][-2]["mode"] == "gap"
     sq = plan_json(wg.build(4, 1, draw=False), link=2, compute=X.XENOS_BF16)["plan"]
-    assert sq["chains"][0]["loader"] == "stem" and sq["chains"][1]["kind"] == "pool"
-    assert all(c["kind"] in ("conv", "splitk_finish") for c in sq["chains"][2:])   # concat and the later pools cost no pass
-    assert sum(c.get("mode") == "patch" for c in sq["chains"][2:]) == 4      # 3x3/2 ceil-mode pools linked into both expand convs, twice
+    # bf16: the 3x3/2 first layer stages its input block in LDS and its 3x3/2 ceil-mode pool is linked into it; fp32: the
+    # gather form of the first-layer kernel, then the pool as the only stand-alone pass
+    assert sq["chains"][0]["loader"] == "stem" and sq["chains"][0]["pool"] != 0
+    assert all(c["kind"] in ("conv", "splitk_finish") for c in sq["chains"])   # concat and the pools cost no pass
+    assert sum(c.get("mode") == "patch" for c in sq["chains"][1:]) == 4      # 3x3/2 ceil-mode pools linked into both expand convs, twice
+    sq32 = plan_json(wg.build(4, 1, draw=False), link=2, compute=X.XENOS_F32)["plan"]
+    assert sq32["chains"][0]["loader"] == "stem" and sq32["chains"][1]["kind"] == "pool"
+    assert all(c["kind"] in ("conv", "splitk_finish") for c in sq32["chains"][2:])
+    # a first layer of 24 channels (ShuffleNet-style graph) runs on the same kernel, padded to 32
+    sh = plan_json(wg.shufflenet_v2(batch=1, draw=False), link=2, compute=X.XENOS_BF16)["plan"]
+    assert sh["chains"][0]["loader"] == "stem" and sh["chains"][0]["K"] == 32 and sh["chains"][0]["pool"] != 0
     offs = sorted({(c["out_c_off"], c["out_sP"]) for c in sq["chains"] if c["kind"] == "conv" and c["out_c_off"]})
     assert (64, 128) in offs and (256, 512) in offs            # expand3x3 halves land at their channel offset
     vgg = plan_json(wg.build(3, 2, draw=False), link=2, compute=X.XENOS_BF16)["plan"]

@@ -216,10 +216,13 @@ def test_small_channel_first_layer_and_nchw_output():
 @pytest.mark.parametrize("k,ksz,stride,pad,hw,c,pool", [(64, 3, 1, 1, 37, 3, 0), (32, 3, 2, 1, 30, 3, 0), (64, 3, 2, 0, 21, 3, 0), (32, 5, 1, 2, 17, 1, 0),
                                                         (64, 1, 1, 0, 11, 4, 0), (64, 2, 2, 0, 10, 8, 0), (64, 7, 2, 3, 45, 3, 0), (32, 5, 1, 2, 19, 3, 0),
                                                         (64, 3, 1, 1, 14, 8, 0), (64, 7, 2, 3, 50, 3, 1), (64, 3, 2, 0, 41, 3, 2), (32, 4, 1, 1, 12, 10, 0),
-                                                        (32, 5, 1, 2, 37, 3, 1), (64, 7, 2, 3, 61, 1, 2), (64, 4, 2, 1, 64, 4, 1)])
+                                                        (32, 5, 1, 2, 37, 3, 1), (64, 7, 2, 3, 61, 1, 2), (64, 4, 2, 1, 64, 4, 1),
+                                                        (24, 3, 2, 1, 45, 3, 1), (24, 3, 1, 1, 23, 3, 0), (48, 5, 2, 2, 33, 3, 2), (56, 3, 2, 0, 40, 3, 0),
+                                                        (64, 3, 2, 0, 47, 3, 1)])
 def test_first_layer_reads_the_graph_input_in_place(k, ksz, stride, pad, hw, c, pool, compute):
-    # C*R*S <= 160 (1 to 5 MFMA passes of 32) and K in {32, 64}: the first chain gathers from the caller's NCHW fp32
-    # tensor (no import pass) and hands NHWC to the next chain; 3 images x odd sizes give ragged 32-pixel blocks.
+    # C*R*S <= 160 (1 to 5 MFMA passes of 32) and K in {32, 64} (or up to a quarter fewer: 24, 48, 56 are computed as 32 /
+    # 64 with zero weights, the tensor keeps the padded channel pitch): the first chain gathers from the caller's NCHW
+    # fp32 tensor (no import pass) and hands NHWC to the next chain; 3 images x odd sizes give ragged 32-pixel blocks.
     # pool 1 / 2: a 3x3/2 max-pool (pad 1 / ceil mode) follows and runs as its own vectorised pass.
     b = wg.builder("stem", (3, c, hw, hw), 17, nonzero_bias=True)
     t = b.cbr(0, k, ksz, stride, pad, name="c0")
@@ -231,15 +234,41 @@ def test_first_layer_reads_the_graph_input_in_place(k, ksz, stride, pad, hw, c, 
     g = b.finish(t)
     ref = xo.forward(g)
     y, info = check(g, ref, compute=compute, link=2)
-    # (bf16, kernels of 4x4 and larger: the input block is staged in LDS and a 3x3/2 max-pool is linked into the chain)
-    linked_pool = bool(pool) and compute == 1 and ksz >= 4 and c <= 4
+    # (bf16, at most 4 input channels: the input block is staged in LDS and a 3x3/2 max-pool is linked into the chain)
+    linked_pool = bool(pool) and compute == 1 and ksz >= 3 and c <= 4
+    if pool and not linked_pool and k not in (32, 64):
+        # a padded channel count is not worth a pooling pass of its own: the general kernel keeps the pool linked
+        assert info["chains"][0]["loader"] != "stem"
+        return
     assert info["chains"][0]["loader"] == "stem" and info["n_chains"] == (3 if pool and not linked_pool else 2)
+    assert info["chains"][0]["K"] == (32 if k <= 32 else 64)
     assert not pool or linked_pool or info["chains"][1]["kind"] == "pool"
     assert not linked_pool or info["chains"][0]["pool"] != 0
     y0, i0 = check(g, ref, compute=compute, link=1)          # un-linked: the general kernel (after an import pass if the input is large)
     assert all(c.get("loader") != "stem" for c in i0["chains"])
     ys, _ = run_gpu(g, compute=compute, link=2, split=0)
     assert np.array_equal(y, ys)                              # one workgroup walking all blocks: same bits
+
+
+@pytest.mark.parametrize("compute", [0, 1])
+@pytest.mark.parametrize("pool", [0, 1])
+def test_padded_first_layer_feeds_a_linked_depthwise_pair(pool, compute):
+    # a 24-channel first layer runs as 32 channels with zero weights and leaves 8 padding channels per pixel; a
+    # depthwise -> pointwise pair linked on chip behind it (link level 3) must reduce over the 24 real channels only
+    b = wg.builder("stem24_dwpw", (2, 3, 29, 29), 23, nonzero_bias=True)
+    t = b.cbr(0, 24, 3, 2, 1, name="c0")
+    if pool:
+        t = b.maxpool(t, 3, 2, 1)
+    t = b.cbr(t, 24, 3, 1, 1, groups=24, name="dw", relu=False)
+    t = b.cbr(t, 40, 1, name="pw")
+    g = b.finish(b.cbr(t, 16, 3, 1, 1, name="post"))
+    ref = xo.forward(g)
+    for link in (3, 2, 1, 0):
+        y, info = check(g, ref, compute=compute, link=link)
+        if link >= 2 and (compute == 1 or not pool):
+            assert info["chains"][0]["loader"] == "stem" and info["chains"][0]["K"] == 32
+        if link == 3:
+            assert any(ch.get("dw_linked") for ch in info["chains"])
 
 
 @pytest.mark.parametrize("h,w,n,c,pool,bn", [(16, 16, 2, 3, 0, True), (37, 21, 3, 3, 0, True), (40, 28, 3, 3, 1, False), (18, 50, 2, 1, 2, True),
