@@ -733,6 +733,75 @@ def test_random_shapes_of_the_chip_resident_kernels(case):
         assert np.array_equal(y, ys)
 
 
+def _random_shuffle_graph(seed):
+    """Seeded random graphs of channel slices, concats and shuffles around convolution chains: ShuffleNet units in both
+    part orders, down-sampling units, shuffles of 2 to 4 groups after and without a concat, slices off the 16-byte
+    channel groups, a concat read twice."""
+    r = np.random.default_rng(5000 + seed)
+    n, hw = int(r.integers(1, 4)), int(r.integers(6, 21))
+    c = int(r.choice([16, 24, 32, 48]))
+    b = wg.builder(f"shufrand{seed}", (n, 3, hw, hw), 300 + seed, nonzero_bias=bool(r.integers(0, 2)))
+    t = b.cbr(0, c, 3, int(r.choice([1, 2])), 1, name="pre", bn=bool(r.integers(0, 2)))
+    size = b.shape(t)[2]
+    for u in range(int(r.integers(2, 5))):
+        c = b.shape(t)[1]
+        kind = r.choice(["v2", "v2", "down", "groups", "slices", "alone", "shared"])
+        nm = f"u{u}"
+        if kind == "v2" and c % 2 == 0:
+            h = c // 2
+            lo, hi = b.slice(t, 0, h), b.slice(t, h, h)
+            br = b.cbr(hi, h, 1, name=nm + "a", relu=bool(r.integers(0, 2)))
+            mid = int(r.integers(0, 3))
+            if mid == 0 and h % 8 == 0:
+                br = b.cbr(br, h, 3, 1, 1, groups=h, name=nm + "dw", relu=False)
+            elif mid == 1:
+                br = b.cbr(br, h, 3, 1, 1, name=nm + "c3")
+            br = b.cbr(br, h, 1, name=nm + "b", bn=bool(r.integers(0, 2)), relu=bool(r.integers(0, 2)))
+            t = b.shuffle(b.concat([lo, br] if r.integers(0, 2) else [br, lo]), 2)
+        elif kind == "down" and size >= 4 and c % 8 == 0:
+            h = int(r.choice([c // 2, c]))
+            l = b.cbr(t, c, 3, 2, 1, groups=c, name=nm + "ldw", relu=False)
+            l = b.cbr(l, h, 1, name=nm + "lpw")
+            q = b.cbr(t, h, 1, name=nm + "rpw1")
+            q = b.cbr(q, h, 3, 2, 1, name=nm + "rc3")
+            t = b.shuffle(b.concat([l, q]), 2)
+            size = (size + 2 - 3) // 2 + 1
+        elif kind == "groups":
+            g_ = int(r.choice([2, 3, 4]))
+            ch = int(r.choice([4, 8, 12]))
+            parts = [b.cbr(t, ch, 1, name=f"{nm}p{j}", relu=bool(r.integers(0, 2))) for j in range(g_)]
+            if r.integers(0, 2) and size >= 3:
+                parts[0] = b.slice(b.maxpool(t, 3, 1, 1), 0, ch) if c >= ch else parts[0]
+            t = b.shuffle(b.concat(parts), g_)
+        elif kind == "slices" and c >= 12:
+            a0 = int(r.integers(1, c // 3))
+            a1 = int(r.integers(a0 + 1, c - 1))
+            parts = [b.cbr(b.slice(t, 0, a0), 8, 1, name=nm + "s0"), b.slice(t, a0, a1 - a0), b.cbr(b.slice(t, a1, c - a1), 8, 3, 1, 1, name=nm + "s2")]
+            t = b.concat(parts)
+        elif kind == "alone":
+            gs = [g_ for g_ in (2, 3, 4, 8) if c % g_ == 0]
+            if gs:
+                t = b.shuffle(t, int(r.choice(gs)))
+        elif kind == "shared" and c % 2 == 0:
+            cat = b.concat([b.cbr(t, c // 2, 1, name=nm + "x"), b.cbr(t, c // 2, 1, name=nm + "y")])
+            t = b.relu(b.add(b.shuffle(cat, 2), cat))
+    tail = int(r.integers(0, 3))
+    if tail == 0:
+        t = b.cbr(t, 24, 3, 1, 1, name="post")
+    elif tail == 1:
+        t = b.fc(b.gap(t), 10, "fc")
+    return b.finish(t)
+
+
+@pytest.mark.parametrize("seed", range(32))
+def test_random_slice_concat_shuffle_graphs(seed):
+    g = _random_shuffle_graph(seed)
+    ref = xo.forward(g)
+    compute = seed % 2 if ref.size >= 64 else 0
+    for link, split in ((3, 1), (2, 1), (2, 0), (1, 1), (0, 1)):
+        check(g, ref, compute=compute, link=link, split=split)
+
+
 @pytest.mark.parametrize("seed", range(48))
 def test_random_graphs_all_modes(seed):
     try:
