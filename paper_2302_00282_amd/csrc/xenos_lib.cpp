@@ -188,6 +188,8 @@ struct Planner {
   struct Fin { int cat_tid; int pos; int other; };
   std::map<int, Fin> fin;
   std::vector<char> fin_concat;              // concat node whose two parts are written by such a chain
+  std::vector<char> fold_shuffle;            // shuffle node folded into the weights of the dense convolutions that read it
+  int pack_shuffle_groups = 0;               // pack_dense: the input channels are read through a shuffle of this many groups
 
   Planner(const xenos_graph& g_, xenos_plan& p_) : g(g_), p(p_) {}
 
@@ -674,6 +676,10 @@ struct Planner {
     // one channel chunk are consecutive steps and re-read the same input pixels while they are still cached
     const bool kchunk = C % bke == 0 && R * S > 1 && !st.scalar && !st.fc_stream;
     st.conv.kchunk = kchunk ? 1 : 0;
+    // channel of the operator's weights that multiplies channel c of the tensor in memory: the same one, or, behind a
+    // folded shuffle of g groups (tensor channel j * m + i is the operator's channel i * g + j), its shuffled position
+    const int shg = pack_shuffle_groups, shm = shg ? Csrc / shg : 1;
+    auto wch = [&](int c) -> size_t { return shg ? (size_t)(c % shm) * shg + c / shm : (size_t)c; };
     auto kidx = [&](int c, int rs) -> size_t {
       return kchunk ? ((size_t)(c / bke) * R * S + rs) * bke + c % bke : (size_t)rs * C + c;
     };
@@ -689,7 +695,7 @@ struct Planner {
           for (int rs = 0; rs < R * S; ++rs) {
             const size_t kk = (size_t)rs * C + c;
             const size_t step = kk / 64, g = (kk % 64) / 16, half = (kk % 16) / 8, e = kk % 8;
-            dst[(((((size_t)(k / 32) * nsteps + step) * 4 + g) * 64 + half * 32 + k % 32) * 8) + e] = f2bf_host(src[(size_t)c * R * S + rs]);
+            dst[(((((size_t)(k / 32) * nsteps + step) * 4 + g) * 64 + half * 32 + k % 32) * 8) + e] = f2bf_host(src[wch(c) * R * S + rs]);
           }
       }
       st.bytes_w = (long long)K * R * S * Csrc * p.esz;
@@ -700,11 +706,11 @@ struct Planner {
       if (p.dt == DT_BF16) {
         uint16_t* dst = (uint16_t*)base + (size_t)k * kred_pad;
         for (int c = 0; c < Csrc; ++c)
-          for (int rs = 0; rs < R * S; ++rs) dst[kidx(c, rs)] = f2bf_host(src[(size_t)c * R * S + rs]);
+          for (int rs = 0; rs < R * S; ++rs) dst[kidx(c, rs)] = f2bf_host(src[wch(c) * R * S + rs]);
       } else {
         float* dst = (float*)base + (size_t)k * kred_pad;
         for (int c = 0; c < Csrc; ++c)
-          for (int rs = 0; rs < R * S; ++rs) dst[kidx(c, rs)] = src[(size_t)c * R * S + rs];
+          for (int rs = 0; rs < R * S; ++rs) dst[kidx(c, rs)] = src[wch(c) * R * S + rs];
       }
     }
     st.bytes_w = (long long)K * R * S * Csrc * p.esz;
@@ -724,6 +730,7 @@ struct Planner {
     ileave.assign(nn, 0);
     alias_shuffle.assign(nn, 0);
     fin_concat.assign(nn, 0);
+    fold_shuffle.assign(nn, 0);
 
     // Channel shuffle as a layout-only link: shuffle(concat(x_0 .. x_{g-1})) with g groups and g equal parts puts channel
     // i of part j at position i * g + j, so the concat buffer is written interleaved and the shuffle moves nothing.  A
@@ -786,6 +793,16 @@ struct Planner {
         free_concat[i] = 1;
         off = 0;
         for (int t : nodes[i].in) { placed[t] = Place{i + 1, off, 1}; off += tshape[t].c; }
+      }
+
+    // A shuffle read by dense convolutions only is a permutation of their input channels: the weights are packed in the
+    // order of the un-shuffled tensor and the shuffle moves nothing (a layout-only link on the consumer side).
+    if (p.opts.link >= 2)
+      for (int j = 0; j < nn; ++j) {
+        if (nodes[j].kind != XENOS_OP_SHUFFLE || alias_shuffle[j] || j + 1 == out_tid || nodes[j].in[0] < 1 || consumers[j + 1].empty()) continue;
+        bool ok = true;
+        for (int c : consumers[j + 1]) ok = ok && nodes[c].kind == XENOS_OP_CONV && desc(nodes[c]).groups == 1;
+        if (ok) fold_shuffle[j] = 1;
       }
 
     // graph input
@@ -1185,7 +1202,12 @@ struct Planner {
                        a.OH == 1 && a.OW == 1 && a.R == is.h && a.S == is.w && a.pad == 0 && is.n <= 32 && !st.scalar && a.C == is.c &&
                        ((long long)a.R * a.S * a.C) % 64 == 0 && (long long)a.R * a.S * a.C >= 512 && (long long)a.R * a.S * a.C < (1ll << 30) &&
                        iv.sN % p.ce == 0 && iv.sN >= (long long)a.R * a.S * a.C && (a.R * a.S == 1 || (iv.sP == a.C && iv.sN == (long long)a.R * a.S * a.C));
+        {
+          const int src_node = nd.in[0] - 1;
+          pack_shuffle_groups = !is_fc && src_node >= 0 && nodes[src_node].kind == XENOS_OP_SHUFFLE && fold_shuffle[src_node] ? desc(nodes[src_node]).groups : 0;
+        }
         pack_dense(st, go, is_fc ? is.c : is.c, a.C, a.R, a.S, K);
+        pack_shuffle_groups = 0;
         push_affine(af, (K + 127) / 128 * 128, &st.scale_off, &st.shift_off);
         if (st.scalar) {
           std::vector<int32_t> tab((size_t)2 * a.Kred_pad);
@@ -1328,7 +1350,7 @@ struct Planner {
       node_final[i] = 1;
       return XENOS_OK;
     }
-    if (nd.kind == XENOS_OP_SHUFFLE && alias_shuffle[i]) {
+    if (nd.kind == XENOS_OP_SHUFFLE && (alias_shuffle[i] || fold_shuffle[i])) {
       if (tview[nd.in[0]] < 0) return fail(XENOS_EINVAL, "%s: input not materialised", st.name.c_str());
       tview[i + 1] = tview[nd.in[0]];
       node_step[i] = std::max(0, (int)p.steps.size() - 1);

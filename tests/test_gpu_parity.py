@@ -447,6 +447,12 @@ def shuffle_graph(kind, n=2, c=32, hw=13, seed=5):
     mid_groups = 0
     if kind == "unit24":                                      # halves of 12 channels: whole 16-byte groups in fp32 only
         kind, c, mid_groups = "unit", 24, 1                   # (a dense 3x3 in the branch: depthwise needs whole groups)
+    if kind == "alone64":                                     # 64 channels: the readers' weights are packed chunk-major
+        b = wg.builder("shuffle_" + kind, (n, 16, hw, hw), seed, nonzero_bias=True)
+        x = b.cbr(0, 64, 1, name="pre")
+        s8 = b.shuffle(x, 8)
+        t = b.concat([b.cbr(s8, 72, 3, 1, 1, name="a"), b.cbr(s8, 24, 1, name="b")])   # two readers, 3x3 and 1x1
+        return b.finish(b.cbr(t, 24, 3, 1, 1, name="post"))
     b = wg.builder("shuffle_" + kind, (n, c, hw, hw), seed, nonzero_bias=True)
     x = b.cbr(0, c, 1, name="pre")                           # an internal tensor to slice
     h = c // 2
@@ -487,7 +493,7 @@ def shuffle_graph(kind, n=2, c=32, hw=13, seed=5):
     return b.finish(t)
 
 
-SHUFFLE_KINDS = ["unit", "unit24", "down", "three", "alone", "shared", "odd", "slice_out", "shuffle_out"]
+SHUFFLE_KINDS = ["unit", "unit24", "down", "three", "alone", "alone64", "shared", "odd", "slice_out", "shuffle_out"]
 
 
 @pytest.mark.parametrize("compute", [0, 1])
@@ -499,7 +505,8 @@ def test_channel_slice_and_shuffle(kind, compute):
     # stores ("shuffle_store"); otherwise each chain stores its part with a channel stride and other parts are copied.
     g = shuffle_graph(kind)
     ref = xo.forward(g)
-    linked = {"unit": 1, "unit24": 1, "down": 1, "three": 1, "odd": 1}.get(kind, 0)
+    # ("alone": the shuffle is read by a dense convolution only and becomes the order of that convolution's weights)
+    linked = {"unit": 1, "unit24": 1, "down": 1, "three": 1, "odd": 1, "alone": 1, "alone64": 1}.get(kind, 0)
     for link in (3, 2, 1, 0):
         y, info = check(g, ref, compute=compute, link=link)
         assert info["linked_shuffles"] == (linked if link >= 2 else 0)
@@ -517,6 +524,11 @@ def test_channel_slice_and_shuffle(kind, compute):
         assert (n_copy, n_fin) == ((0, 1) if compute == 0 else (3, 0))
     if kind in ("three", "odd"):
         assert n_fin == 0 and n_copy >= 1
+    if kind in ("alone", "alone64"):
+        assert n_copy == 0
+    if kind == "alone64":
+        y7, i7 = check(g, ref, compute=compute, link=2, tile=7)   # the 3x3 reader on the halo kernel (chunk-major weights too)
+        assert any(ch.get("halo") for ch in i7["chains"])
 
 
 # ------------------------------------------------------------------------------------------ whole graphs
