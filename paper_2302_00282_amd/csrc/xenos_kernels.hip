@@ -1002,6 +1002,34 @@ __global__ __launch_bounds__(V2_NT) void conv3x3_kernel(const ConvArgs a) {
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
   int aff_tile_n = -1;                                             // channel tile whose scale / shift are in LDS
+  // What the epilogue of tile `l` reads from LDS, written at the start of the tile's last chunk so that the barriers of
+  // that chunk's taps publish it (the previous tile's epilogue has passed its last barrier by then) and the integer
+  // division per row is paid beside the MFMAs of the chunk, not between two tiles.
+  auto epilogue_tables = [&](int l) __attribute__((always_inline)) {
+    int tile_m, tile_n;
+    tile_of(l, tile_m, tile_n);
+    const int tyi = tile_m / a.tiles_x;
+    const int q0 = tyi * a.th, x0 = (tile_m - tyi * a.tiles_x) * a.tw;
+    // this tile's folded scale / shift, shared through LDS (every lane needs 32 of the BN values of each)
+    float* s_aff = (float*)(smem + v2_lds(BN));
+    if (tile_n != aff_tile_n) {   // a workgroup walks pixel tiles within a channel tile: reloaded only when that changes
+      if (tid < 2 * BN) s_aff[tid] = tid < BN ? a.scale[tile_n * BN + tid] : a.shift[tile_n * BN + tid - BN];
+      aff_tile_n = tile_n;
+    }
+    // where each staged row goes in the output (element offset of its channel 0; -1 = not an output of this tile)
+    long long* s_rowoff = (long long*)(smem + v2_lds(BN) + 2 * BN * 4 + V2_BM * 4);
+    for (int q = tid; q < ROWS; q += NTH) {
+      const int pos = s_rowpos[q];
+      long long ob = -1;
+      if (pos >= 0) {
+        const int y = pos >> 16, x = pos & 0xffff;
+        const int qq = q0 + (MODE == M_FLAT ? y : 2 * y), n = qq / Hp, oh = qq - n * Hp, ow = x0 + (MODE == M_FLAT ? x : 2 * x);
+        if (n < a.N && oh < a.H && ow < a.W)
+          ob = (long long)n * a.out_sN + (MODE == M_FLAT ? (long long)(oh * a.OW + ow) : (long long)((oh >> 1) * a.PW + (ow >> 1))) * a.out_sP;
+      }
+      s_rowoff[q] = ob;
+    }
+  };
   // The chain's epilogue for the tile `li`, run after its last chunk (of parity PAR).
   auto epilogue = [&](auto par) {
     constexpr int PAR = decltype(par)::value;
@@ -1028,41 +1056,26 @@ __global__ __launch_bounds__(V2_NT) void conv3x3_kernel(const ConvArgs a) {
       }
     }
     const float lo = a.relu ? 0.f : -3.4028235e38f;                // ReLU as a clamp: no branch per value
-    // this tile's folded scale / shift, shared through LDS (every lane needs 32 of the BN values of each)
-    float* s_aff = (float*)(smem + v2_lds(BN));
-    if (tile_n != aff_tile_n) {   // a workgroup walks pixel tiles within a channel tile: reloaded (one memory latency) only when that changes
-      if (tid < 2 * BN) s_aff[tid] = tid < BN ? a.scale[tile_n * BN + tid] : a.shift[tile_n * BN + tid - BN];
-      aff_tile_n = tile_n;
-    }
-    // where each staged row goes in the output (element offset of its channel 0; -1 = not an output of this tile)
-    long long* s_rowoff = (long long*)(smem + v2_lds(BN) + 2 * BN * 4 + V2_BM * 4);
-    for (int q = tid; q < ROWS; q += NTH) {
-      const int pos = s_rowpos[q];
-      long long ob = -1;
-      if (pos >= 0) {
-        const int y = pos >> 16, x = pos & 0xffff;
-        const int qq = q0 + (MODE == M_FLAT ? y : 2 * y), n = qq / Hp, oh = qq - n * Hp, ow = x0 + (MODE == M_FLAT ? x : 2 * x);
-        if (n < a.N && oh < a.H && ow < a.W)
-          ob = (long long)n * a.out_sN + (MODE == M_FLAT ? (long long)(oh * a.OW + ow) : (long long)((oh >> 1) * a.PW + (ow >> 1))) * a.out_sP;
-      }
-      s_rowoff[q] = ob;
-    }
-    __syncthreads();
+    // (the tile's scale / shift and the output offsets of its rows were put into LDS by epilogue_tables() at the start of
+    // the tile's last chunk: at least nine barriers ago)
+    const float* s_aff = (const float*)(smem + v2_lds(BN));
+    const long long* s_rowoff = (const long long*)(smem + v2_lds(BN) + 2 * BN * 4 + V2_BM * 4);
     // first half of a pass: the wavefronts that own its rows finish their accumulators (scale, shift, shortcut,
     // ReLU, pooling) and stage them in the output type.  RES / VEC / PMAX are compile-time copies of the chain's
     // flags, so the 16 channel groups of a lane run without branches.
     auto finish_rows = [&](int pass, auto res_c, auto max_c) {
       constexpr bool RES = decltype(res_c)::value, PMAX = decltype(max_c)::value;
+      // (channel groups outermost: a group's scale and shift are read from LDS once for both pixel blocks)
 #pragma unroll
-      for (int i = 0; i < 2; ++i) {
-        const int m = wave_m * 64 + i * 32 + lp;
-        const int srow = (MODE == M_FLAT ? m : (m >> 2)) - pass * RPP;
+      for (int j = 0; j < TN; ++j)
 #pragma unroll
-        for (int j = 0; j < TN; ++j)
+        for (int g = 0; g < 4; ++g) {
+          const int c = wave_n * WN + j * 32 + g * 8 + lhalf * 4, k0 = tile_n * BN + c;
+          const f32x4_t sc = *(const f32x4_t*)(s_aff + c), sh = *(const f32x4_t*)(s_aff + BN + c);
 #pragma unroll
-          for (int g = 0; g < 4; ++g) {
-            const int c = wave_n * WN + j * 32 + g * 8 + lhalf * 4, k0 = tile_n * BN + c;
-            const f32x4_t sc = *(const f32x4_t*)(s_aff + c), sh = *(const f32x4_t*)(s_aff + BN + c);
+          for (int i = 0; i < 2; ++i) {
+            const int m = wave_m * 64 + i * 32 + lp;
+            const int srow = (MODE == M_FLAT ? m : (m >> 2)) - pass * RPP;
             float y[4];
 #pragma unroll
             for (int e = 0; e < 4; ++e) y[e] = acc[i][j][4 * g + e] * sc[e] + sh[e];
@@ -1102,7 +1115,7 @@ __global__ __launch_bounds__(V2_NT) void conv3x3_kernel(const ConvArgs a) {
               }
             }
           }
-      }
+        }
     };
     using std::true_type; using std::false_type;
 #pragma unroll 1
@@ -1118,12 +1131,28 @@ __global__ __launch_bounds__(V2_NT) void conv3x3_kernel(const ConvArgs a) {
       }
       __syncthreads();
       {
-        for (int idx = tid; idx < RPP * CG; idx += NTH) {
-          const int lr = idx / CG, cg = idx - lr * CG, q = pass * RPP + lr;
-          const int k0 = tile_n * BN + cg * CE;
-          const long long ob = s_rowoff[q];
-          if (ob < 0 || k0 >= a.K) continue;
-          *(u32x4_t*)((T*)a.out + ob + k0) = *(const u32x4_t*)(stage_row(lr) + cg * 16);
+        // every thread stores the same number of 16-byte groups: all their LDS reads (row offset and data) are issued
+        // before the first store, one LDS round trip per pass instead of one per group
+        // (in batches of EB groups: their LDS reads are in flight together)
+        constexpr int NG = (RPP * CG + NTH - 1) / NTH, EB = NG % 4 == 0 ? 4 : NG % 2 == 0 ? 2 : 1;
+#pragma unroll 1
+        for (int u0 = 0; u0 < NG; u0 += EB) {
+          long long ob[EB];
+          u32x4_t v[EB];
+#pragma unroll
+          for (int u = 0; u < EB; ++u) {
+            const int idx = tid + (u0 + u) * NTH;
+            const bool in = (RPP * CG) % NTH == 0 || idx < RPP * CG;
+            const int lr = in ? idx / CG : 0, cg = idx - (idx / CG) * CG;
+            ob[u] = in ? s_rowoff[pass * RPP + lr] : -1;
+            v[u] = *(const u32x4_t*)(stage_row(lr) + cg * 16);
+          }
+#pragma unroll
+          for (int u = 0; u < EB; ++u) {
+            const int idx = tid + (u0 + u) * NTH;
+            const int cg = idx - (idx / CG) * CG, k0 = tile_n * BN + cg * CE;
+            if (ob[u] >= 0 && k0 < a.K) *(u32x4_t*)((T*)a.out + ob[u] + k0) = v[u];
+          }
         }
       }
       __syncthreads();
@@ -1140,6 +1169,7 @@ __global__ __launch_bounds__(V2_NT) void conv3x3_kernel(const ConvArgs a) {
       const int lnext = li + wgs < ntl ? li + wgs : li;            // after the last tile: reload it (never used)
       patch_addr(lnext);
       wnext = weight_addr(lnext);
+      epilogue_tables(li);
     }
     chunk_body(cc, last, par);
     if (!last) { ++cc; return false; }
