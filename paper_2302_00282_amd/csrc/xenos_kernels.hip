@@ -941,6 +941,34 @@ __global__ __launch_bounds__(V2_NT) void conv3x3_kernel(const ConvArgs a) {
       }
     }
   };
+  int aff_tile_n = -1;                                             // channel tile whose scale / shift are in LDS
+  // What the epilogue of tile `l` reads from LDS, written during the tile's last chunk so that the barriers of that
+  // chunk's taps publish it and the integer division per row is paid beside the MFMAs of the chunk, not between two tiles.
+  auto epilogue_tables = [&](int l) __attribute__((always_inline)) {
+    int tile_m, tile_n;
+    tile_of(l, tile_m, tile_n);
+    const int tyi = tile_m / a.tiles_x;
+    const int q0 = tyi * a.th, x0 = (tile_m - tyi * a.tiles_x) * a.tw;
+    // this tile's folded scale / shift, shared through LDS (every lane needs 32 of the BN values of each)
+    float* s_aff = (float*)(smem + v2_lds(BN));
+    if (tile_n != aff_tile_n) {   // a workgroup walks pixel tiles within a channel tile: reloaded only when that changes
+      if (tid < 2 * BN) s_aff[tid] = tid < BN ? a.scale[tile_n * BN + tid] : a.shift[tile_n * BN + tid - BN];
+      aff_tile_n = tile_n;
+    }
+    // where each staged row goes in the output (element offset of its channel 0; -1 = not an output of this tile)
+    long long* s_rowoff = (long long*)(smem + v2_lds(BN) + 2 * BN * 4 + V2_BM * 4);
+    for (int q = tid; q < ROWS; q += NTH) {
+      const int pos = s_rowpos[q];
+      long long ob = -1;
+      if (pos >= 0) {
+        const int y = pos >> 16, x = pos & 0xffff;
+        const int qq = q0 + (MODE == M_FLAT ? y : 2 * y), n = qq / Hp, oh = qq - n * Hp, ow = x0 + (MODE == M_FLAT ? x : 2 * x);
+        if (n < a.N && oh < a.H && ow < a.W)
+          ob = (long long)n * a.out_sN + (MODE == M_FLAT ? (long long)(oh * a.OW + ow) : (long long)((oh >> 1) * a.PW + (ow >> 1))) * a.out_sP;
+      }
+      s_rowoff[q] = ob;
+    }
+  };
   // Nine statically unrolled taps of channel chunk cc.  PAR = parity of the chunk in the workgroup's whole chunk
   // sequence: it selects the patch buffer, and (9 steps per chunk) the register set of tap 0; the weight stage of a tap
   // is tap % 3 in every chunk.
@@ -975,6 +1003,9 @@ __global__ __launch_bounds__(V2_NT) void conv3x3_kernel(const ConvArgs a) {
       tap_schedule(tap == 0 || tap == 4, tap == 3 || tap == 7);
       __builtin_amdgcn_sched_barrier(0);
       __syncthreads();
+      // the tables of this tile's epilogue: after a barrier that every wavefront reaches only when it has finished the
+      // previous tile's epilogue (which has no barrier of its own), and eight barriers before they are read
+      if (tap == 0 && last) epilogue_tables(li);
     }
   };
 
@@ -1001,35 +1032,6 @@ __global__ __launch_bounds__(V2_NT) void conv3x3_kernel(const ConvArgs a) {
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-  int aff_tile_n = -1;                                             // channel tile whose scale / shift are in LDS
-  // What the epilogue of tile `l` reads from LDS, written at the start of the tile's last chunk so that the barriers of
-  // that chunk's taps publish it (the previous tile's epilogue has passed its last barrier by then) and the integer
-  // division per row is paid beside the MFMAs of the chunk, not between two tiles.
-  auto epilogue_tables = [&](int l) __attribute__((always_inline)) {
-    int tile_m, tile_n;
-    tile_of(l, tile_m, tile_n);
-    const int tyi = tile_m / a.tiles_x;
-    const int q0 = tyi * a.th, x0 = (tile_m - tyi * a.tiles_x) * a.tw;
-    // this tile's folded scale / shift, shared through LDS (every lane needs 32 of the BN values of each)
-    float* s_aff = (float*)(smem + v2_lds(BN));
-    if (tile_n != aff_tile_n) {   // a workgroup walks pixel tiles within a channel tile: reloaded only when that changes
-      if (tid < 2 * BN) s_aff[tid] = tid < BN ? a.scale[tile_n * BN + tid] : a.shift[tile_n * BN + tid - BN];
-      aff_tile_n = tile_n;
-    }
-    // where each staged row goes in the output (element offset of its channel 0; -1 = not an output of this tile)
-    long long* s_rowoff = (long long*)(smem + v2_lds(BN) + 2 * BN * 4 + V2_BM * 4);
-    for (int q = tid; q < ROWS; q += NTH) {
-      const int pos = s_rowpos[q];
-      long long ob = -1;
-      if (pos >= 0) {
-        const int y = pos >> 16, x = pos & 0xffff;
-        const int qq = q0 + (MODE == M_FLAT ? y : 2 * y), n = qq / Hp, oh = qq - n * Hp, ow = x0 + (MODE == M_FLAT ? x : 2 * x);
-        if (n < a.N && oh < a.H && ow < a.W)
-          ob = (long long)n * a.out_sN + (MODE == M_FLAT ? (long long)(oh * a.OW + ow) : (long long)((oh >> 1) * a.PW + (ow >> 1))) * a.out_sP;
-      }
-      s_rowoff[q] = ob;
-    }
-  };
   // The chain's epilogue for the tile `li`, run after its last chunk (of parity PAR).
   auto epilogue = [&](auto par) {
     constexpr int PAR = decltype(par)::value;
@@ -1037,11 +1039,17 @@ __global__ __launch_bounds__(V2_NT) void conv3x3_kernel(const ConvArgs a) {
     tile_of(li, tile_m, tile_n);
     const int tyi = tile_m / a.tiles_x;
     const int q0 = tyi * a.th, x0 = (tile_m - tyi * a.tiles_x) * a.tw;
-    // The patch buffer of the chunk just finished is free (the other one holds the next tile's first patch).
-    unsigned char* stg = smem + PAR * V2_ABYTES;
-    // (the weight stage read at the last tap is free as well: the next tile's first two steps are in the other two)
-    unsigned char* stg2 = smem + 2 * V2_ABYTES + 2 * BBYTES;
-    auto stage_row = [&](int r) -> unsigned char* { return (!SPLIT_STG || r < R1) ? stg + r * SPB : stg2 + (r - R1) * SPB; };
+    // Every wavefront finishes and stores its own 64 pixels x WN channels: a row of its block holds whole 16-byte channel
+    // groups, so the values pass through LDS only to change hands between the lanes of that wavefront (LDS serves a
+    // wavefront's requests in order) and the epilogue has no barrier.  A pass stages 32 pixels (8 pooling windows) x at
+    // most 128 bytes of channels per wavefront in the patch buffer of the chunk just finished, which nobody writes before
+    // tap 3 of the next chunk, three barriers later; the other buffer holds the next tile's first patch.
+    constexpr int JP = WN * ESZ <= 128 ? TN : 1;                   // 32-channel blocks per pass
+    constexpr int RB = JP * 32 * ESZ;                              // bytes of channels per staged row
+    constexpr int SPW = RB + (ESZ == 2 ? 8 : 16);                  // row pitch: 34 dwords (bf16) puts the 32 rows of an 8-byte store pass in 32 different bank pairs
+    constexpr int PROWS = MODE == M_FLAT ? 32 : 8;                 // staged rows per pass
+    static_assert(8 * 32 * SPW <= V2_ABYTES, "the per-wavefront staging areas must fit the free patch buffer");
+    unsigned char* wstg = smem + PAR * V2_ABYTES + wave * (32 * SPW);
     // shortcut address of this lane's two pixels (rows outside the image read element 0)
     long long rbase[2] = {0, 0};
     if (MODE == M_FLAT && a.has_res) {
@@ -1056,108 +1064,102 @@ __global__ __launch_bounds__(V2_NT) void conv3x3_kernel(const ConvArgs a) {
       }
     }
     const float lo = a.relu ? 0.f : -3.4028235e38f;                // ReLU as a clamp: no branch per value
-    // (the tile's scale / shift and the output offsets of its rows were put into LDS by epilogue_tables() at the start of
-    // the tile's last chunk: at least nine barriers ago)
+    // (the tile's scale / shift and the output offsets of its rows were put into LDS by epilogue_tables() after the first
+    // tap of the tile's last chunk: eight barriers ago)
     const float* s_aff = (const float*)(smem + v2_lds(BN));
     const long long* s_rowoff = (const long long*)(smem + v2_lds(BN) + 2 * BN * 4 + V2_BM * 4);
-    // first half of a pass: the wavefronts that own its rows finish their accumulators (scale, shift, shortcut,
-    // ReLU, pooling) and stage them in the output type.  RES / VEC / PMAX are compile-time copies of the chain's
-    // flags, so the 16 channel groups of a lane run without branches.
-    auto finish_rows = [&](int pass, auto res_c, auto max_c) {
+    // a pass: the lanes finish their accumulators of pixel block i, channel blocks j0 .. j0 + JP - 1 (scale, shift,
+    // shortcut, ReLU, pooling), stage them in the output type, and the wavefront stores the staged rows as whole groups.
+    // RES / PMAX are compile-time copies of the chain's flags, so the channel groups of a lane run without branches.
+    auto finish_store = [&](auto res_c, auto max_c) {
       constexpr bool RES = decltype(res_c)::value, PMAX = decltype(max_c)::value;
-      // (channel groups outermost: a group's scale and shift are read from LDS once for both pixel blocks)
 #pragma unroll
-      for (int j = 0; j < TN; ++j)
+      for (int i = 0; i < 2; ++i)
 #pragma unroll
-        for (int g = 0; g < 4; ++g) {
-          const int c = wave_n * WN + j * 32 + g * 8 + lhalf * 4, k0 = tile_n * BN + c;
-          const f32x4_t sc = *(const f32x4_t*)(s_aff + c), sh = *(const f32x4_t*)(s_aff + BN + c);
+        for (int j0 = 0; j0 < TN; j0 += JP) {
+          const int m = wave_m * 64 + i * 32 + lp;
+          const int srow = MODE == M_FLAT ? lp : (lp >> 2);
 #pragma unroll
-          for (int i = 0; i < 2; ++i) {
-            const int m = wave_m * 64 + i * 32 + lp;
-            const int srow = (MODE == M_FLAT ? m : (m >> 2)) - pass * RPP;
-            float y[4];
+          for (int jj = 0; jj < JP; ++jj)
 #pragma unroll
-            for (int e = 0; e < 4; ++e) y[e] = acc[i][j][4 * g + e] * sc[e] + sh[e];
-            if constexpr (RES) {
-              // rows outside the image and channel groups beyond K read a valid dummy address; they are never stored
-              const long long ra = rbase[i] + (k0 < a.K ? k0 : 0);
-              if constexpr (sizeof(T) == 2) {
-                const uint2 r = *(const uint2*)((const T*)a.res + ra);
-                y[0] += __uint_as_float(r.x << 16); y[1] += __uint_as_float(r.x & 0xffff0000u);
-                y[2] += __uint_as_float(r.y << 16); y[3] += __uint_as_float(r.y & 0xffff0000u);
-              } else {
-                const f32x4_t r = *(const f32x4_t*)((const T*)a.res + ra);
+            for (int g = 0; g < 4; ++g) {
+              const int j = j0 + jj;
+              const int cl = jj * 32 + g * 8 + lhalf * 4;          // channel within the staged row
+              const int c = wave_n * WN + j * 32 + g * 8 + lhalf * 4, k0 = tile_n * BN + c;
+              const f32x4_t sc = *(const f32x4_t*)(s_aff + c), sh = *(const f32x4_t*)(s_aff + BN + c);
+              float y[4];
 #pragma unroll
-                for (int e = 0; e < 4; ++e) y[e] += r[e];
+              for (int e = 0; e < 4; ++e) y[e] = acc[i][j][4 * g + e] * sc[e] + sh[e];
+              if constexpr (RES) {
+                // rows outside the image and channel groups beyond K read a valid dummy address; they are never stored
+                const long long ra = rbase[i] + (k0 < a.K ? k0 : 0);
+                if constexpr (sizeof(T) == 2) {
+                  const uint2 r = *(const uint2*)((const T*)a.res + ra);
+                  y[0] += __uint_as_float(r.x << 16); y[1] += __uint_as_float(r.x & 0xffff0000u);
+                  y[2] += __uint_as_float(r.y << 16); y[3] += __uint_as_float(r.y & 0xffff0000u);
+                } else {
+                  const f32x4_t r = *(const f32x4_t*)((const T*)a.res + ra);
+#pragma unroll
+                  for (int e = 0; e < 4; ++e) y[e] += r[e];
+                }
+              }
+#pragma unroll
+              for (int e = 0; e < 4; ++e) y[e] = fmx(y[e], lo);
+              bool mine = true;                                    // does this lane hold the finished value?
+              if (MODE == M_ZIGZAG) {
+                // the window's four pixels are lanes 4w .. 4w+3: butterfly over the quad, lane j keeps group g == j
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                  y[e] = PMAX ? quad_max<true>(y[e]) : quad_add<true>(y[e]);              // with lanes [1,0,3,2]
+                  y[e] = PMAX ? quad_max<false>(y[e]) : quad_add<false>(y[e]) * 0.25f;   // with lanes [2,3,0,1]
+                }
+                mine = (l31 & 3) == g;
+              }
+              if (mine) {
+                if constexpr (sizeof(T) == 2) {
+                  uint2 o;
+                  o.x = f2bf2(y[0], y[1]);
+                  o.y = f2bf2(y[2], y[3]);
+                  *(uint2*)(wstg + srow * SPW + cl * 2) = o;
+                } else {
+                  // (stored through the type the read-back uses: nothing but program order keeps the two apart)
+                  *(u32x4_t*)(wstg + srow * SPW + cl * 4) = u32x4_t{__float_as_uint(y[0]), __float_as_uint(y[1]), __float_as_uint(y[2]), __float_as_uint(y[3])};
+                }
               }
             }
+          // the wavefront's staged rows, one 16-byte channel group per lane and turn
+          constexpr int G = RB / 16, NGW = PROWS * G / 64 > 0 ? PROWS * G / 64 : 1;
+          const int qbase = MODE == M_FLAT ? wave_m * 64 + i * 32 : (wave_m * 64 + i * 32) / 4;
+          long long ob[NGW];
+          u32x4_t v[NGW];
 #pragma unroll
-            for (int e = 0; e < 4; ++e) y[e] = fmx(y[e], lo);
-            bool mine = true;                                      // does this lane hold the finished value?
-            if (MODE == M_ZIGZAG) {
-              // the window's four pixels are lanes 4w .. 4w+3: butterfly over the quad, lane j keeps group g == j
+          for (int u = 0; u < NGW; ++u) {
+            const int idx = lane + u * 64;
+            const bool in = idx < PROWS * G;
+            const int r = in ? idx / G : 0, cg = idx % G;
+            ob[u] = in ? s_rowoff[qbase + r] : -1;
+            if constexpr (sizeof(T) == 2) {
+              const uint2 lo8 = *(const uint2*)(wstg + r * SPW + cg * 16), hi8 = *(const uint2*)(wstg + r * SPW + cg * 16 + 8);
+              v[u] = u32x4_t{lo8.x, lo8.y, hi8.x, hi8.y};
+            } else {
+              v[u] = *(const u32x4_t*)(wstg + r * SPW + cg * 16);
+            }
+          }
 #pragma unroll
-              for (int e = 0; e < 4; ++e) {
-                y[e] = PMAX ? quad_max<true>(y[e]) : quad_add<true>(y[e]);              // with lanes [1,0,3,2]
-                y[e] = PMAX ? quad_max<false>(y[e]) : quad_add<false>(y[e]) * 0.25f;   // with lanes [2,3,0,1]
-              }
-              mine = (l31 & 3) == g;
-            }
-            if (mine) {
-              if constexpr (sizeof(T) == 2) {
-                uint2 o;
-                o.x = f2bf2(y[0], y[1]);
-                o.y = f2bf2(y[2], y[3]);
-                *(uint2*)(stage_row(srow) + c * 2) = o;
-              } else {
-                *(f32x4_t*)(stage_row(srow) + c * 4) = f32x4_t{y[0], y[1], y[2], y[3]};
-              }
-            }
+          for (int u = 0; u < NGW; ++u) {
+            const int cg = (lane + u * 64) % G, k0 = tile_n * BN + wave_n * WN + j0 * 32 + cg * CE;
+            if (ob[u] >= 0 && k0 < a.K) *(u32x4_t*)((T*)a.out + ob[u] + k0) = v[u];
           }
         }
     };
     using std::true_type; using std::false_type;
-#pragma unroll 1
-    for (int pass = 0; pass < NP; ++pass) {
-      if (wave_m / (4 / NP) == pass) {                             // the wavefronts whose rows this pass stages
-        if (MODE == M_FLAT) {
-          if (a.has_res) finish_rows(pass, true_type{}, false_type{});
-          else finish_rows(pass, false_type{}, false_type{});
-        } else {
-          if (a.pool == POOL_MAX) finish_rows(pass, false_type{}, true_type{});
-          else finish_rows(pass, false_type{}, false_type{});
-        }
-      }
-      __syncthreads();
-      {
-        // every thread stores the same number of 16-byte groups: all their LDS reads (row offset and data) are issued
-        // before the first store, one LDS round trip per pass instead of one per group
-        // (in batches of EB groups: their LDS reads are in flight together)
-        constexpr int NG = (RPP * CG + NTH - 1) / NTH, EB = NG % 4 == 0 ? 4 : NG % 2 == 0 ? 2 : 1;
-#pragma unroll 1
-        for (int u0 = 0; u0 < NG; u0 += EB) {
-          long long ob[EB];
-          u32x4_t v[EB];
-#pragma unroll
-          for (int u = 0; u < EB; ++u) {
-            const int idx = tid + (u0 + u) * NTH;
-            const bool in = (RPP * CG) % NTH == 0 || idx < RPP * CG;
-            const int lr = in ? idx / CG : 0, cg = idx - (idx / CG) * CG;
-            ob[u] = in ? s_rowoff[pass * RPP + lr] : -1;
-            v[u] = *(const u32x4_t*)(stage_row(lr) + cg * 16);
-          }
-#pragma unroll
-          for (int u = 0; u < EB; ++u) {
-            const int idx = tid + (u0 + u) * NTH;
-            const int cg = idx - (idx / CG) * CG, k0 = tile_n * BN + cg * CE;
-            if (ob[u] >= 0 && k0 < a.K) *(u32x4_t*)((T*)a.out + ob[u] + k0) = v[u];
-          }
-        }
-      }
-      __syncthreads();
+    if (MODE == M_FLAT) {
+      if (a.has_res) finish_store(true_type{}, false_type{});
+      else finish_store(false_type{}, false_type{});
+    } else {
+      if (a.pool == POOL_MAX) finish_store(false_type{}, true_type{});
+      else finish_store(false_type{}, false_type{});
     }
-
   };
 
   // One channel chunk of the workgroup's chunk sequence; returns true when the workgroup has finished its last tile.
@@ -1169,7 +1171,6 @@ __global__ __launch_bounds__(V2_NT) void conv3x3_kernel(const ConvArgs a) {
       const int lnext = li + wgs < ntl ? li + wgs : li;            // after the last tile: reload it (never used)
       patch_addr(lnext);
       wnext = weight_addr(lnext);
-      epilogue_tables(li);
     }
     chunk_body(cc, last, par);
     if (!last) { ++cc; return false; }
