@@ -81,8 +81,8 @@ struct ConvArgs {
   int relu, has_res;
   // != 0: the chain also performs the two-group channel shuffle of the concat it ends in.  `res` is the other part of the
   // concat (strides res_sN / res_sP), `out` the concat buffer (2 K channels per pixel); channel k of this chain is stored
-  // at output channel 2k + (ileave - 1) and channel k of the other part at 2k + (2 - ileave).  M_FLAT, general kernel,
-  // 16-byte aligned channel groups only.
+  // at output channel 2k + (ileave - 1) and channel k of the other part at 2k + (2 - ileave).  M_FLAT, general and
+  // depthwise-panel kernels, 16-byte aligned channel groups only.
   int ileave;
   long long res_sN, res_sP;        // residual strides (image, pixel); channel stride 1
   int pool, pk, ps, pp, PH, PW, cip;   // linked pooling (POOL_*), window, stride, pad, pooled size, count_include_pad
