@@ -1268,18 +1268,17 @@ constexpr int PR_OFF_XIN = PR_PBYTES;
 constexpr int PR_OFF_AFF = PR_OFF_XIN + PR_INMAX * 8;
 constexpr int PR_OFF_ROWPOS = PR_OFF_AFF + 4 * PR_C * 4;
 constexpr int PR_OFF_ROWOFF = PR_OFF_ROWPOS + PR_BM * 4;
-constexpr int PR_LDS = PR_OFF_ROWOFF + PR_BM * 8;
+constexpr int PR_SPW = 32 * 2 + 8;              // staging row pitch: a wavefront's 32 channels + 8 bytes (18 dwords: the 32 rows of a store pass hit 32 bank pairs)
+constexpr int PR_OFF_STAGE = PR_OFF_ROWOFF + PR_BM * 8;   // per wavefront 64 rows (pixels; 16 pooling windows when pooled)
+constexpr int PR_LDS = PR_OFF_STAGE + PR_NW * 64 * PR_SPW;
 
 template <int MODE, bool PMAX>
 __global__ __launch_bounds__(PR_NT, 2) void conv_pair_kernel(const ConvArgs a) {
   constexpr int BM = PR_BM, NTH = PR_NT, CE = 8;
   constexpr int ROWS = MODE == M_FLAT ? BM : BM / 4;               // staged rows: pixels, or pooled windows
-  constexpr int SPB = PR_C * 2 + 16;                               // staging row pitch in bytes
-  constexpr int CG = PR_C / CE;
   constexpr int NI = (PR_INMAX * 4 + NTH - 1) / NTH;               // input elements per thread
   static_assert(MODE == M_FLAT || MODE == M_ZIGZAG, "row enumerations of the pair kernel");
-  static_assert(BM * SPB <= PR_PBYTES, "the finished tile is staged in the patch buffer");
-  static_assert(PR_OFF_ROWOFF % 8 == 0 && PR_OFF_AFF % 16 == 0, "alignment of the tables");
+  static_assert(PR_OFF_ROWOFF % 8 == 0 && PR_OFF_AFF % 16 == 0 && PR_OFF_STAGE % 8 == 0, "alignment of the tables");
 
   extern __shared__ __align__(16) unsigned char smem[];
   unsigned char* s_patch = smem;
@@ -1289,6 +1288,7 @@ __global__ __launch_bounds__(PR_NT, 2) void conv_pair_kernel(const ConvArgs a) {
   long long* s_rowoff = (long long*)(smem + PR_OFF_ROWOFF);
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  unsigned char* wstg = smem + PR_OFF_STAGE + wave * (64 * PR_SPW);   // this wavefront's staging slice
   const int wave_n = wave & 1, wave_m = wave >> 1;
   const int l31 = lane & 31, lhalf = lane >> 5;
   const int lq = l31 >> 2;
@@ -1438,22 +1438,6 @@ __global__ __launch_bounds__(PR_NT, 2) void conv_pair_kernel(const ConvArgs a) {
     const bool more = li + wgs < mlen;
     if (more) load_xin(li + wgs);
 
-    // where each staged row goes in the output (element offset of its channel 0; -1 = not an output of this tile)
-    for (int q = tid; q < ROWS; q += NTH) {
-      const int pos = s_rowpos[q];
-      long long ob = -1;
-      if (pos >= 0) {
-        const int y = pos >> 16, x = pos & 0xffff;
-        int n, oh;
-        split_row(q0 + (MODE == M_FLAT ? y : 2 * y), n0, n, oh);
-        oh += 1;                                                   // (split_row returns the input row of a patch position)
-        const int ow = x0 + (MODE == M_FLAT ? x : 2 * x);
-        if (n < a.N && oh < a.H && ow < a.W)
-          ob = (long long)n * a.out_sN + (MODE == M_FLAT ? (long long)(oh * a.OW + ow) : (long long)((oh >> 1) * a.PW + (ow >> 1))) * a.out_sP;
-      }
-      s_rowoff[q] = ob;
-    }
-
     // ---- P1: this wavefront's 32 channels of the intermediate at the patch positions p = 32 * unit + lane % 32 -------
     for (int u = wave_m; u < nunits; u += PR_NW / 2) {
       const int p = u * 32 + l31, pcl = p < PP ? p : PP - 1;
@@ -1492,6 +1476,24 @@ __global__ __launch_bounds__(PR_NT, 2) void conv_pair_kernel(const ConvArgs a) {
     }
     __syncthreads();
 
+    // (after a barrier that every wavefront reaches only when it has finished the previous tile's epilogue, which has
+    // no barrier of its own; published by the barrier after P2)
+    // where each staged row goes in the output (element offset of its channel 0; -1 = not an output of this tile)
+    for (int q = tid; q < ROWS; q += NTH) {
+      const int pos = s_rowpos[q];
+      long long ob = -1;
+      if (pos >= 0) {
+        const int y = pos >> 16, x = pos & 0xffff;
+        int n, oh;
+        split_row(q0 + (MODE == M_FLAT ? y : 2 * y), n0, n, oh);
+        oh += 1;                                                   // (split_row returns the input row of a patch position)
+        const int ow = x0 + (MODE == M_FLAT ? x : 2 * x);
+        if (n < a.N && oh < a.H && ow < a.W)
+          ob = (long long)n * a.out_sN + (MODE == M_FLAT ? (long long)(oh * a.OW + ow) : (long long)((oh >> 1) * a.PW + (ow >> 1))) * a.out_sP;
+      }
+      s_rowoff[q] = ob;
+    }
+
     // ---- P2: the second convolution out of the patch ------------------------------------------------------------
     f32x16_t acc[2];
 #pragma unroll
@@ -1518,16 +1520,17 @@ __global__ __launch_bounds__(PR_NT, 2) void conv_pair_kernel(const ConvArgs a) {
       }
     }
     if (more) store_xin();
-    __syncthreads();                                               // the patch is free: it becomes the output staging
+    __syncthreads();                                               // the patch is free: the next tile's P1 may write it
 
-    // ---- epilogue: scale / shift / ReLU, pooling over the lane quad, staging in the output type -----------------
+    // ---- epilogue: scale / shift / ReLU, pooling over the lane quad; every wavefront stages its own 64 pixels x 32
+    // channels in the output type in a private LDS slice (LDS serves a wavefront's requests in order) and stores them as
+    // whole 16-byte channel groups: no barrier
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
-      const int m = wave_m * 64 + i * 32 + lp;
-      const int srow = MODE == M_FLAT ? m : (m >> 2);
+      const int srow = MODE == M_FLAT ? i * 32 + lp : ((i * 32 + lp) >> 2);
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
-        const int c = wave_n * 32 + g * 8 + lhalf * 4;
+        const int cl = g * 8 + lhalf * 4, c = wave_n * 32 + cl;
         const f32x4_t sc = *(const f32x4_t*)(s_aff + 2 * PR_C + c), sh = *(const f32x4_t*)(s_aff + 3 * PR_C + c);
         float y[4];
 #pragma unroll
@@ -1546,20 +1549,30 @@ __global__ __launch_bounds__(PR_NT, 2) void conv_pair_kernel(const ConvArgs a) {
           uint2 o;
           o.x = f2bf2(y[0], y[1]);
           o.y = f2bf2(y[2], y[3]);
-          *(uint2*)(s_patch + srow * SPB + c * 2) = o;
+          *(uint2*)(wstg + srow * PR_SPW + cl * 2) = o;
         }
       }
     }
-    __syncthreads();
-    for (int idx = tid; idx < ROWS * CG; idx += NTH) {
-      const int lr = idx / CG, cg = idx - lr * CG;
-      const long long ob = s_rowoff[lr];
-      if (ob < 0) continue;
-      *(u32x4_t*)((bf16_t*)a.out + ob + cg * CE) = *(const u32x4_t*)(s_patch + lr * SPB + cg * 16);
+    {
+      constexpr int PROWS = MODE == M_FLAT ? 64 : 16, G = 4, NGW = PROWS * G / 64;   // 16-byte groups of the slice per lane
+      const int qbase = MODE == M_FLAT ? wave_m * 64 : wave_m * 16;
+      long long ob[NGW];
+      u32x4_t v[NGW];
+#pragma unroll
+      for (int u = 0; u < NGW; ++u) {
+        const int idx = lane + u * 64, r = idx / G, cg = idx % G;
+        ob[u] = s_rowoff[qbase + r];
+        const uint2 lo8 = *(const uint2*)(wstg + r * PR_SPW + cg * 16), hi8 = *(const uint2*)(wstg + r * PR_SPW + cg * 16 + 8);
+        v[u] = u32x4_t{lo8.x, lo8.y, hi8.x, hi8.y};
+      }
+#pragma unroll
+      for (int u = 0; u < NGW; ++u) {
+        const int cg = (lane + u * 64) % G;
+        if (ob[u] >= 0) *(u32x4_t*)((bf16_t*)a.out + ob[u] + wave_n * 32 + cg * CE) = v[u];
+      }
     }
     li += wgs;
     if (li >= mlen) break;
-    __syncthreads();                                               // the staging becomes the next tile's patch
   }
 }
 
