@@ -717,9 +717,15 @@ __global__ __launch_bounds__(V2_NT) void conv3x3_kernel(const ConvArgs a) {
   // Workgroups are dealt round-robin to the XCDs; each XCD owns a contiguous, balanced range of pixel tiles and
   // walks it once per output-channel tile, so its workgroups share one weight slice in their L2 and neighbouring
   // pixel tiles share their input halo.
-  const int G = gridDim.x, nx = G < NUM_XCD ? G : NUM_XCD;
-  const int xcd = blockIdx.x % nx, wgs = (G - xcd + nx - 1) / nx;   // workgroups of this XCD
-  const int m0 = xcd * a.tiles_m / nx, mlen = (xcd + 1) * a.tiles_m / nx - m0;
+  // (with at least 8 workgroups, the usual case, the divisions by the XCD count are shifts; every scalar division in this
+  // set-up is a long dependent chain in front of the kernel's first load)
+  const int G = gridDim.x;
+  const bool full = G >= NUM_XCD;
+  const int nx = full ? NUM_XCD : G;
+  const int xcd = full ? (int)(blockIdx.x & (NUM_XCD - 1)) : (int)blockIdx.x;
+  const int wgs = full ? (G - xcd + NUM_XCD - 1) / NUM_XCD : 1;    // workgroups of this XCD
+  const int m0 = full ? xcd * a.tiles_m / NUM_XCD : xcd * a.tiles_m / nx;
+  const int mlen = (full ? (xcd + 1) * a.tiles_m / NUM_XCD : (xcd + 1) * a.tiles_m / nx) - m0;
   const int ntl = mlen * a.tiles_n;                                // tiles of this XCD
   // Order of an XCD's tiles: groups of `mg` pixel tiles, each group once per output-channel tile before the next group.
   // With a group as large as the XCD's range this is one sweep per channel tile (one weight slice live in the L2 at a
@@ -732,8 +738,26 @@ __global__ __launch_bounds__(V2_NT) void conv3x3_kernel(const ConvArgs a) {
     tile_n = r / glen;
     tile_m = m0 + grp * mg + (r - tile_n * glen);
   };
-  int li = blockIdx.x / nx;
+  int li = full ? (int)(blockIdx.x / NUM_XCD) : 0;
   if (li >= ntl) return;                                           // uniform per workgroup
+  // A tile of the workgroup's sequence, decoded once (three uniform divisions) and kept for everything that needs it:
+  // loads, weights, epilogue tables, epilogue
+  struct Tile { int tile_n, q0, x0, n0, r0; };
+  auto decode = [&](int l) __attribute__((always_inline)) -> Tile {
+    int tile_m, tile_n;
+    tile_of(l, tile_m, tile_n);
+    const int tyi = tile_m / a.tiles_x;
+    const int q0 = tyi * a.th, n0 = q0 / Hp;
+    return Tile{tile_n, q0, (tile_m - tyi * a.tiles_x) * a.tw, n0, q0 - n0 * Hp};
+  };
+  // image and row of stacked row t.q0 + y: compares as long as a tile spans at most four images
+  const bool few = a.th + 2 <= 3 * Hp;
+  auto image_row = [&](const Tile& t, int y, int& n, int& row) __attribute__((always_inline)) {
+    const int rel = t.r0 + y;
+    const int k = few ? (rel >= Hp ? 1 : 0) + (rel >= 2 * Hp ? 1 : 0) + (rel >= 3 * Hp ? 1 : 0) : rel / Hp;
+    n = t.n0 + k; row = rel - k * Hp;
+  };
+  Tile tcur = decode(li), tnext = tcur;
 
   // ---- what this thread loads for a tile: 6 chunks of the input patch, B_IT chunks of the weight tile ------
   int aoff[A_IT];
@@ -742,16 +766,11 @@ __global__ __launch_bounds__(V2_NT) void conv3x3_kernel(const ConvArgs a) {
   // other chunks lie NTH / 8 rows further each
   int wrow = 0, wnext = 0;
   const int wstride = (NTH / CPR) * a.Kred_pad * ESZ;
-  auto patch_addr = [&](int l) __attribute__((always_inline)) {
-    int tile_m, tile_n;
-    tile_of(l, tile_m, tile_n);
-    const int tyi = tile_m / a.tiles_x;
-    const int q0 = tyi * a.th, x0 = (tile_m - tyi * a.tiles_x) * a.tw;
-    // image and row of a stacked row: one division per tile (uniform), then compares per chunk as long as a patch spans
-    // at most four images (this runs between the MFMA streams of two tiles: with one channel chunk per tile it was a tenth
-    // of the tile's time when every chunk divided)
-    const int n0 = q0 / Hp, r0 = q0 - n0 * Hp;
-    const bool few = a.th + 2 <= 3 * Hp;
+  auto patch_addr = [&](const Tile& t) __attribute__((always_inline)) {
+    // image and row of a stacked row: one division per tile (uniform, in decode()), then compares per chunk as long as a
+    // patch spans at most four images (this runs between the MFMA streams of two tiles: with one channel chunk per tile it
+    // was a tenth of the tile's time when every chunk divided)
+    const int n0 = t.n0, r0 = t.r0, x0 = t.x0;
     const int sN = (int)a.in_sN, sH = (int)a.in_sH, sW = (int)a.in_sW;   // (N * in_sN < 2^31 is checked by the host)
     aok = 0;
 #pragma unroll
@@ -767,10 +786,8 @@ __global__ __launch_bounds__(V2_NT) void conv3x3_kernel(const ConvArgs a) {
       aok |= (ok ? 1u : 0u) << it;
     }
   };
-  auto weight_addr = [&](int l) __attribute__((always_inline)) -> int {
-    int tile_m, tile_n;
-    tile_of(l, tile_m, tile_n);
-    return ((tile_n * BN + tid / CPR) * a.Kred_pad + (tid % CPR) * CE) * ESZ;
+  auto weight_addr = [&](const Tile& t) __attribute__((always_inline)) -> int {
+    return ((t.tile_n * BN + tid / CPR) * a.Kred_pad + (tid % CPR) * CE) * ESZ;
   };
 
   // ---- which pixel of the tile a GEMM row is ---------------------------------------------------------------
@@ -805,32 +822,11 @@ __global__ __launch_bounds__(V2_NT) void conv3x3_kernel(const ConvArgs a) {
 
   // which pixel (or pooling window) of the tile each staged row is: the same for every tile, so it is worked out once
   // (the integer divisions of the enumeration would otherwise be paid per stored channel group)
-  int* s_rowpos = (int*)(smem + v2_lds(BN) + 2 * BN * 4);
-  for (int q = tid; q < ROWS; q += NTH) {
-    int y, x;
-    if (MODE == M_FLAT) flat_px(q, y, x); else zz_win(q, y, x);
-    const bool ok = MODE == M_FLAT ? (y < a.th && x < a.tw) : (2 * y < a.th && 2 * x < a.tw);
-    s_rowpos[q] = ok ? (y << 16) | x : -1;
-  }
-  __syncthreads();
+  int* s_rowpos = (int*)(smem + v2_lds(BN) + 2 * BN * 4);          // (filled at the pipeline start, beside its first loads)
 
-  // ---- fragment addresses of this lane's rows (pixels of the tile); the same for every tile --------------
+  // ---- fragment addresses of this lane's rows (pixels of the tile); the same for every tile (worked out at the
+  // pipeline start, while its first loads are on their way) --------------
   int abase[2], bbase[TN];
-#pragma unroll
-  for (int i = 0; i < 2; ++i) {
-    const int m = wave_m * 64 + i * 32 + lp;
-    int ty, tx;
-    if (MODE == M_FLAT) flat_px(m, ty, tx);
-    else {
-      int wy, wx;
-      zz_win(m >> 2, wy, wx);
-      ty = 2 * wy + ((m >> 1) & 1); tx = 2 * wx + (m & 1);
-    }
-    const bool ok = ty < a.th && tx < a.tw;
-    abase[i] = (PLIN ? m : ok ? ty * PW_ + tx : 0) * LDS_ROW + lhalf * 16;
-  }
-#pragma unroll
-  for (int j = 0; j < TN; ++j) bbase[j] = (wave_n * WN + j * 32 + l31) * LDS_ROW + lhalf * 16;
 
   f32x16_t acc[2][TN];
   constexpr int A_HALF = A_IT / 2;
@@ -944,11 +940,8 @@ __global__ __launch_bounds__(V2_NT) void conv3x3_kernel(const ConvArgs a) {
   int aff_tile_n = -1;                                             // channel tile whose scale / shift are in LDS
   // What the epilogue of tile `l` reads from LDS, written during the tile's last chunk so that the barriers of that
   // chunk's taps publish it and the integer division per row is paid beside the MFMAs of the chunk, not between two tiles.
-  auto epilogue_tables = [&](int l) __attribute__((always_inline)) {
-    int tile_m, tile_n;
-    tile_of(l, tile_m, tile_n);
-    const int tyi = tile_m / a.tiles_x;
-    const int q0 = tyi * a.th, x0 = (tile_m - tyi * a.tiles_x) * a.tw;
+  auto epilogue_tables = [&](const Tile& t) __attribute__((always_inline)) {
+    const int tile_n = t.tile_n, x0 = t.x0;
     // this tile's folded scale / shift, shared through LDS (every lane needs 32 of the BN values of each)
     float* s_aff = (float*)(smem + v2_lds(BN));
     if (tile_n != aff_tile_n) {   // a workgroup walks pixel tiles within a channel tile: reloaded only when that changes
@@ -962,7 +955,9 @@ __global__ __launch_bounds__(V2_NT) void conv3x3_kernel(const ConvArgs a) {
       long long ob = -1;
       if (pos >= 0) {
         const int y = pos >> 16, x = pos & 0xffff;
-        const int qq = q0 + (MODE == M_FLAT ? y : 2 * y), n = qq / Hp, oh = qq - n * Hp, ow = x0 + (MODE == M_FLAT ? x : 2 * x);
+        int n, oh;
+        image_row(t, MODE == M_FLAT ? y : 2 * y, n, oh);
+        const int ow = x0 + (MODE == M_FLAT ? x : 2 * x);
         if (n < a.N && oh < a.H && ow < a.W)
           ob = (long long)n * a.out_sN + (MODE == M_FLAT ? (long long)(oh * a.OW + ow) : (long long)((oh >> 1) * a.PW + (ow >> 1))) * a.out_sP;
       }
@@ -1005,18 +1000,45 @@ __global__ __launch_bounds__(V2_NT) void conv3x3_kernel(const ConvArgs a) {
       __syncthreads();
       // the tables of this tile's epilogue: after a barrier that every wavefront reaches only when it has finished the
       // previous tile's epilogue (which has no barrier of its own), and eight barriers before they are read
-      if (tap == 0 && last) epilogue_tables(li);
+      if (tap == 0 && last) epilogue_tables(tcur);
     }
   };
 
   // ---- pipeline start: chunk 0, weight steps 0, 1 (in LDS) and 2 (in registers), first fragments of the first tile ----
-  patch_addr(li);
-  wrow = weight_addr(li);
+  // Both halves of the first patch and the first two weight steps are requested together (one memory round trip, from
+  // memory nobody has touched yet, instead of two), and the row table is worked out while they are on their way.
+  patch_addr(tcur);
+  wrow = weight_addr(tcur);
   load_patch(0, 0);
+  u32x4_t pb[A_HALF];
+#pragma unroll
+  for (int it = 0; it < A_HALF; ++it) pb[it] = *(const u32x4_t*)((const T*)a.in + aoff[A_HALF + it]);   // = load_patch(0, 1)
   load_w(0, rb0);
   load_w(1, rb1);
+  for (int q = tid; q < ROWS; q += NTH) {
+    int y, x;
+    if (MODE == M_FLAT) flat_px(q, y, x); else zz_win(q, y, x);
+    const bool ok = MODE == M_FLAT ? (y < a.th && x < a.tw) : (2 * y < a.th && 2 * x < a.tw);
+    s_rowpos[q] = ok ? (y << 16) | x : -1;
+  }
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int m = wave_m * 64 + i * 32 + lp;
+    int ty, tx;
+    if (MODE == M_FLAT) flat_px(m, ty, tx);
+    else {
+      int wy, wx;
+      zz_win(m >> 2, wy, wx);
+      ty = 2 * wy + ((m >> 1) & 1); tx = 2 * wx + (m & 1);
+    }
+    const bool ok = ty < a.th && tx < a.tw;
+    abase[i] = (PLIN ? m : ok ? ty * PW_ + tx : 0) * LDS_ROW + lhalf * 16;
+  }
+#pragma unroll
+  for (int j = 0; j < TN; ++j) bbase[j] = (wave_n * WN + j * 32 + l31) * LDS_ROW + lhalf * 16;
   store_patch(0, 0);
-  load_patch(0, 1);
+#pragma unroll
+  for (int it = 0; it < A_HALF; ++it) pa[it] = pb[it];
   store_w(0, rb0);
   store_w(1, rb1);
   store_patch(0, 1);
@@ -1035,10 +1057,7 @@ __global__ __launch_bounds__(V2_NT) void conv3x3_kernel(const ConvArgs a) {
   // The chain's epilogue for the tile `li`, run after its last chunk (of parity PAR).
   auto epilogue = [&](auto par) {
     constexpr int PAR = decltype(par)::value;
-    int tile_m, tile_n;
-    tile_of(li, tile_m, tile_n);
-    const int tyi = tile_m / a.tiles_x;
-    const int q0 = tyi * a.th, x0 = (tile_m - tyi * a.tiles_x) * a.tw;
+    const int tile_n = tcur.tile_n, x0 = tcur.x0;
     // Every wavefront finishes and stores its own 64 pixels x WN channels: a row of its block holds whole 16-byte channel
     // groups, so the values pass through LDS only to change hands between the lanes of that wavefront (LDS serves a
     // wavefront's requests in order) and the epilogue has no barrier.  A pass stages 32 pixels (8 pooling windows) x at
@@ -1058,7 +1077,9 @@ __global__ __launch_bounds__(V2_NT) void conv3x3_kernel(const ConvArgs a) {
         const int m = wave_m * 64 + i * 32 + lp;
         int ty, tx;
         flat_px(m, ty, tx);
-        const int qq = q0 + ty, n = qq / Hp, oh = qq - n * Hp, ow = x0 + tx;
+        int n, oh;
+        image_row(tcur, ty < a.th ? ty : 0, n, oh);
+        const int ow = x0 + tx;
         const bool ok = ty < a.th && n < a.N && oh < a.H && ow < a.W;
         rbase[i] = ok ? (long long)n * a.res_sN + (long long)(oh * a.OW + ow) * a.res_sP : 0;
       }
@@ -1169,8 +1190,9 @@ __global__ __launch_bounds__(V2_NT) void conv3x3_kernel(const ConvArgs a) {
     const bool last = cc == nchunks - 1;
     if (last) {
       const int lnext = li + wgs < ntl ? li + wgs : li;            // after the last tile: reload it (never used)
-      patch_addr(lnext);
-      wnext = weight_addr(lnext);
+      tnext = decode(lnext);
+      patch_addr(tnext);
+      wnext = weight_addr(tnext);
     }
     chunk_body(cc, last, par);
     if (!last) { ++cc; return false; }
@@ -1184,6 +1206,7 @@ __global__ __launch_bounds__(V2_NT) void conv3x3_kernel(const ConvArgs a) {
         for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
     cc = 0;
     li += wgs;
+    tcur = tnext;
     return li >= ntl;
   };
   for (;;) {
