@@ -1903,8 +1903,8 @@ xenos_status xenos_plan_tune(xenos_plan* plan, const void* d_input, void* d_outp
   xenos_status rc = XENOS_OK;
   for (Step& s : plan->steps) {
     if (s.kind != S_CONV || s.cands.size() < 2) continue;
-    int best = -1;
-    float best_ms = 0.f;
+    int best = -1, incumbent = -1;                                // incumbent: the cost model's choice among the candidates
+    float best_ms = 0.f, incumbent_ms = 0.f;
     for (size_t ci = 0; ci < s.cands.size() && rc == XENOS_OK; ++ci) {
       Step trial = s;
       trial.cfg = s.cands[ci].cfg; trial.conv = s.cands[ci].a; trial.lds = s.cands[ci].lds;
@@ -1917,8 +1917,13 @@ xenos_status xenos_plan_tune(xenos_plan* plan, const void* d_input, void* d_outp
         break;
       }
       if (best < 0 || ms < best_ms) { best = (int)ci; best_ms = ms; }
+      const Step::Cand& cc = s.cands[ci];
+      if (cc.cfg == s.cfg && cc.a.tiles_m == s.conv.tiles_m && cc.a.tiles_n == s.conv.tiles_n && cc.a.halo_bn == s.conv.halo_bn &&
+          cc.a.halo_plin == s.conv.halo_plin) { incumbent = (int)ci; incumbent_ms = ms; }
     }
     if (rc != XENOS_OK) break;
+    // a few short trials time a chain to 2-3 %: the cost model's choice is given up only for a clear win
+    if (best >= 0 && incumbent >= 0 && best != incumbent && best_ms > 0.96f * incumbent_ms) { best = incumbent; best_ms = incumbent_ms; }
     if (best >= 0) {
       const Step::Cand& c = s.cands[best];
       const bool same = c.cfg == s.cfg && c.a.tiles_m == s.conv.tiles_m && c.a.tiles_n == s.conv.tiles_n && c.a.halo_bn == s.conv.halo_bn && c.a.halo_plin == s.conv.halo_plin;
