@@ -2474,28 +2474,33 @@ size_t dwpw_lds_bytes(int panel_channels, int esz) { return (size_t)dwpw_lds(pan
 // ---------------------------------------------------------------------------------------------
 // Depthwise convolution chain: one thread = one 16-byte channel vector of one output pixel.
 // ---------------------------------------------------------------------------------------------
-template <typename T>
+// K3: the 3x3 kernel with its nine taps unrolled; IDX = int when the work items fit 31 bits (three 32-bit divisions per
+// item instead of three 64-bit ones, which cost more than the nine taps).
+template <typename T, bool K3, typename IDX>
 __global__ __launch_bounds__(NT) void dw_kernel(const DwArgs a) {
   using tr = Tr<T>;
   constexpr int CE = tr::CE;
   const int cv = a.C / CE;
-  for (long long idx = (long long)blockIdx.x * NT + threadIdx.x; idx < a.total_vec; idx += (long long)gridDim.x * NT) {
+  const int R = K3 ? 3 : a.R, S = K3 ? 3 : a.S;
+  for (IDX idx = (IDX)blockIdx.x * NT + threadIdx.x; idx < (IDX)a.total_vec; idx += (IDX)gridDim.x * NT) {
     const int c0 = (int)(idx % cv) * CE;
-    long long pix = idx / cv;
+    IDX pix = idx / cv;
     const int ow = (int)(pix % a.OW); pix /= a.OW;
     const int oh = (int)(pix % a.OH);
     const int n = (int)(pix / a.OH);
     float acc[CE];
 #pragma unroll
     for (int e = 0; e < CE; ++e) acc[e] = 0.f;
-    for (int r = 0; r < a.R; ++r) {
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
       const int ih = oh * a.stride - a.pad + r;
       if ((unsigned)ih >= (unsigned)a.H) continue;
-      for (int s = 0; s < a.S; ++s) {
+#pragma unroll
+      for (int s = 0; s < S; ++s) {
         const int iw = ow * a.stride - a.pad + s;
         if ((unsigned)iw >= (unsigned)a.W) continue;
         const T* p = (const T*)a.in + (long long)n * a.in_sN + ((long long)ih * a.W + iw) * a.in_sP + c0;
-        const T* q = (const T*)a.w + (long long)(r * a.S + s) * a.C + c0;
+        const T* q = (const T*)a.w + (long long)(r * S + s) * a.C + c0;
         float x[CE], w[CE];
         tr::unpack(*(const u32x4_t*)p, x);
         tr::unpack(*(const u32x4_t*)q, w);
@@ -2523,8 +2528,18 @@ static int grid_for(long long work_items, int per_block) {
 int launch_dw(const DwArgs& a, int dtype, void* stream) {
   hipStream_t st = (hipStream_t)stream;
   const int grid = grid_for(a.total_vec, NT);
-  if (dtype == DT_BF16) hipLaunchKernelGGL(dw_kernel<bf16_t>, dim3(grid), dim3(NT), 0, st, a);
-  else hipLaunchKernelGGL(dw_kernel<float>, dim3(grid), dim3(NT), 0, st, a);
+  if (a.total_vec < 0 || a.R < 1 || a.S < 1) return (int)hipErrorInvalidValue;
+  const bool k3 = a.R == 3 && a.S == 3;
+  const bool small = a.total_vec + (long long)grid * NT < (1ll << 31);   // (the grid-stride loop steps past the end once)
+  if (dtype == DT_BF16) {
+    if (k3 && small) hipLaunchKernelGGL((dw_kernel<bf16_t, true, int>), dim3(grid), dim3(NT), 0, st, a);
+    else if (small) hipLaunchKernelGGL((dw_kernel<bf16_t, false, int>), dim3(grid), dim3(NT), 0, st, a);
+    else hipLaunchKernelGGL((dw_kernel<bf16_t, false, long long>), dim3(grid), dim3(NT), 0, st, a);
+  } else {
+    if (k3 && small) hipLaunchKernelGGL((dw_kernel<float, true, int>), dim3(grid), dim3(NT), 0, st, a);
+    else if (small) hipLaunchKernelGGL((dw_kernel<float, false, int>), dim3(grid), dim3(NT), 0, st, a);
+    else hipLaunchKernelGGL((dw_kernel<float, false, long long>), dim3(grid), dim3(NT), 0, st, a);
+  }
   return (int)hipGetLastError();
 }
 
