@@ -87,8 +87,9 @@ typedef struct {
   const float* var;
 } xenos_op_desc;
 
-/* Hardware description (Section 6: "memory hierarchy, number of DSP units").  The planner
- * sizes tiles from these numbers; nothing about the chip is hard-coded in the planner. */
+/* Hardware description the optimiser is given beside the graph (Section 6).  The planner sizes its partitions
+ * from num_cu, lds_bytes_per_cu and l2_bytes; llc_bytes and hbm_bytes are informative.  Fixed for gfx950 and
+ * not taken from here: 8 XCDs (workgroups are dealt to them round-robin) and the 160 KiB LDS limit of a launch. */
 typedef struct {
   int num_cu;                   /* compute units that share the work (MI355X: 256)          */
   size_t lds_bytes_per_cu;      /* private memory per unit (MI355X: 160 KiB LDS)            */
@@ -119,7 +120,7 @@ typedef struct {
 typedef struct xenos_graph xenos_graph;
 typedef struct xenos_plan xenos_plan;
 
-/* Section 6, "users need to provide a computation graph": validates the operator list, infers
+/* Section 6 (the user supplies the computation graph): validates the operator list, infers
  * every tensor shape and copies descriptors and parameters.  output_tensor_id names the graph
  * output; output gives the dtype/layout the caller wants it in (n,c,h,w are checked if non-zero). */
 xenos_status xenos_graph_create(const xenos_tensor_desc* input, const xenos_op_desc* ops, int n_ops,
@@ -159,8 +160,10 @@ xenos_status xenos_run_graph(xenos_plan* plan, const void* d_input, void* d_outp
 /* Profiling-driven choice of the partition (the single-device form of Algorithm 1, Section 5: enumerate the legal
  * partition schemes of an operator, profile each, keep the fastest; a one-off search per model and platform).
  * For every convolution chain of a bound plan whose split planner found more than one legal tile shape / kernel,
- * each candidate is launched `reps` times on hip_stream on the chain's real input (one full pass runs first) and
- * the fastest replaces the cost model's choice.  Chains whose plan structure depends on the choice (reduction
+ * each candidate is launched `reps` times on hip_stream and the fastest replaces the cost model's choice.  One full
+ * pass runs first so that every buffer holds finite values of the real shapes; since workspace blocks are reused
+ * along the pass, a chain is not guaranteed to be timed on its own input (the kernels' run time does not depend on
+ * the values), and the call ends with a full pass that leaves d_output valid.  Chains whose plan structure depends on the choice (reduction
  * split, first-layer kernel, linked depthwise producer) keep it.  d_output is overwritten; the JSON of
  * xenos_plan_query reflects the result ("tuned":1); *n_changed (may be NULL) = chains whose choice changed.
  * Synchronises hip_stream.  Allocates no device memory. */

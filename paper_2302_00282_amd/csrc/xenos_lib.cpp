@@ -2,6 +2,7 @@
 // linking, DSP-aware operator split; Sections 4.1-4.4 of the paper) and the runtime that enqueues
 // the planned kernel sequence (Section 3).  Pure C++ plus the HIP runtime API; all arithmetic on
 // tensor data happens in the gfx950 kernels.
+#include <hip/hip_runtime.h>
 #include <hip/hip_runtime_api.h>
 #include <math.h>
 #include <stdarg.h>
@@ -86,6 +87,9 @@ struct View {
   int esz = 4;
   Shape s;
   int cphys = 0;               // channels physically present per pixel (> s.c: zero-filled padding channels follow)
+  // which tensor of the caller's graph the view holds (plan metadata, for per-chain checks): channel c of the view is
+  // channel gc0 + c * gcs of graph tensor gt; gt < 0 = no graph tensor (partial sums of a reduction split)
+  int gt = -1, gc0 = 0, gcs = 1;
   bool internal_nhwc() const { return sK == 1; }
 };
 
@@ -172,6 +176,8 @@ struct Planner {
   xenos_plan& p;
   std::vector<Node> nodes;
   std::vector<Shape> tshape;                 // by tensor id (node list numbering)
+  struct GraphRef { int gt, c0; };
+  std::vector<GraphRef> tgraph;              // by tensor id: the graph tensor (and first channel of it) the tensor is
   std::vector<std::vector<int>> consumers;   // tensor id -> node indices
   int out_tid = 0;
   std::vector<int> tview;                    // tensor id -> view index (-1 = not materialised)
@@ -225,9 +231,12 @@ struct Planner {
     remap[0] = 0;
     tshape.clear();
     tshape.push_back(g.shapes[0]);
-    auto push = [&](Node nd) {
+    tgraph.clear();
+    tgraph.push_back(GraphRef{0, 0});
+    auto push = [&](Node nd, int gt, int c0) {
       nodes.push_back(nd);
       tshape.push_back(nd.out);
+      tgraph.push_back(GraphRef{gt, c0});
       return (int)nodes.size();
     };
     for (int i = 0; i < n_ops; ++i) {
@@ -237,15 +246,17 @@ struct Planner {
         const int po = hoist_pool[i];
         Node cat;
         cat.kind = XENOS_OP_CONCAT; cat.src = i; cat.out = g.shapes[po + 1];
+        int c0 = 0;
         for (int j = 0; j < d.n_inputs; ++j) {
           Node pl;
           pl.kind = g.ops[po].d.kind; pl.src = po;
           pl.in = {remap[d.inputs[j]]};
           pl.out = g.shapes[po + 1];
           pl.out.c = g.shapes[d.inputs[j]].c;
-          cat.in.push_back(push(pl));
+          cat.in.push_back(push(pl, po + 1, c0));   // the pooled part = a channel range of the pooled concat
+          c0 += pl.out.c;
         }
-        const int t = push(cat);
+        const int t = push(cat, po + 1, 0);
         remap[i + 1] = t;
         remap[po + 1] = t;
         continue;
@@ -253,7 +264,7 @@ struct Planner {
       Node nd;
       nd.kind = d.kind; nd.src = i; nd.out = g.shapes[i + 1];
       for (int j = 0; j < d.n_inputs; ++j) nd.in.push_back(remap[d.inputs[j]]);
-      remap[i + 1] = push(nd);
+      remap[i + 1] = push(nd, i + 1, 0);
     }
     out_tid = remap[g.output_id];
     consumers.assign(nodes.size() + 1, {});
@@ -300,6 +311,12 @@ struct Planner {
     if (v.s.h == 1 && v.s.w == 1) { v.sK = 1; v.sP = v.s.c; v.sN = v.s.c; }
   }
 
+  // records which graph tensor view `v` holds: tensor `tid` of the node list, from its channel `c_first` on
+  int tag(int v, int tid, int c_first = 0, int c_stride = 1) {
+    p.views[v].gt = tgraph[tid].gt; p.views[v].gc0 = tgraph[tid].c0 + c_first; p.views[v].gcs = c_stride;
+    return v;
+  }
+
   // View a step should write tensor `tid` to.  Creates it on first request.
   int out_view_for(int tid, bool producer_is_conv) {
     if (tview[tid] >= 0) return tview[tid];
@@ -327,6 +344,11 @@ struct Planner {
       }
     } else {
       v = internal_view(s);
+    }
+    if (fi == fin.end()) {
+      tag(v, tid);
+      // a concat written interleaved holds the output of the channel shuffle linked into it
+      if (tid >= 1 && nodes[tid - 1].kind == XENOS_OP_CONCAT && ileave[tid - 1] && consumers[tid].size() == 1) tag(v, consumers[tid][0] + 1);
     }
     tview[tid] = v;
     return v;
@@ -391,6 +413,24 @@ struct Planner {
       if (nx < 0) return false;
       const int k = nodes[nx].kind;
       if (k != XENOS_OP_BIAS && k != XENOS_OP_BN && k != XENOS_OP_RELU) return false;
+      cur = nx + 1;
+    }
+  }
+
+  // Does the chain that starts at convolution node `c` link a window pooling (max / average with a window, not the
+  // global average)?  Mirrors the link pass of plan_node.
+  bool chain_links_window_pool(int c) const {
+    int cur = c + 1, stage = 0;
+    for (;;) {
+      if (cur == out_tid || placed.count(cur)) return false;
+      const int nx = single_consumer(cur);
+      if (nx < 0) return false;
+      const int k = nodes[nx].kind;
+      if ((k == XENOS_OP_BIAS || k == XENOS_OP_BN) && stage == 0) {
+      } else if (k == XENOS_OP_ADD && stage <= 1) { stage = 2;
+      } else if (k == XENOS_OP_RELU && stage <= 2) { stage = 3;
+      } else if ((k == XENOS_OP_MAXPOOL || k == XENOS_OP_AVGPOOL) && stage <= 3) { return true;
+      } else return false;
       cur = nx + 1;
     }
   }
@@ -488,7 +528,8 @@ struct Planner {
       // fetch counter on 56x56 maps of 256 channels: 2.5 -> 1.2-1.7 times the input; layers with larger weights
       // fetch the same or a little more that way, and run times do not differ).
       const long long w_bytes = (long long)c.K * c.C * 9 * p.esz;
-      c.halo_mgroup = c.tiles_n >= 2 && w_bytes <= kL2BytesPerXcd / 2 ? std::max(1, per_xcd / c.tiles_n) : 1 << 30;
+      const long long l2 = p.hw.l2_bytes ? (long long)p.hw.l2_bytes : kL2BytesPerXcd;
+      c.halo_mgroup = c.tiles_n >= 2 && w_bytes <= l2 / 2 ? std::max(1, per_xcd / c.tiles_n) : 1 << 30;
     } else {
       const int nz = c.tiles_n * ks;
       long long best = -1;
@@ -813,7 +854,7 @@ struct Planner {
         const Node& nd = nodes[ci];
         if (!(nd.kind == XENOS_OP_CONV && desc(nd).groups == 1)) all_dense = false;
       }
-      const int ev = ext_view(p.in, 1);
+      const int ev = tag(ext_view(p.in, 1), 0);
       tview[0] = ev;
       if (direct) {
         normalise_1x1(p.views[ev]);
@@ -838,7 +879,7 @@ struct Planner {
       Step st;
       st.kind = S_CVT; st.name = "export";
       st.v_in = tview[out_tid];
-      st.v_out = ext_view(p.out, 2);
+      st.v_out = tag(ext_view(p.out, 2), out_tid);
       fill_cvt(st);
       add_step(st);
     }
@@ -882,7 +923,7 @@ struct Planner {
   // that the first layer runs on the vector loader like every other layer (its padded weights are zero).
   int import_input() {
     const int cpad = in_all_dense ? (p.in.c + p.ce - 1) / p.ce * p.ce : p.in.c;
-    const int iv = internal_view(tshape[0], -1, cpad);
+    const int iv = tag(internal_view(tshape[0], -1, cpad), 0);
     p.views[iv].cphys = cpad;
     Step st;
     st.kind = S_CVT; st.name = "import";
@@ -1036,7 +1077,8 @@ struct Planner {
         // (a pointwise chain that stores with a channel stride, a part of a shuffled concat of more than two groups, has no
         // 16-byte stores, which the depthwise-panel kernel needs; the element-wise form of the linked pair is slower than
         // two chains.  The chain that finishes a two-group shuffle stores whole groups and can take the depthwise.)
-        if (pw >= 0 && d.kh == d.kw && nodes[pw].kind == XENOS_OP_CONV && !chain_stores_strided(pw)) {
+        // (nor one that links a window pooling: the kernels with a depthwise producer enumerate pixel-major rows)
+        if (pw >= 0 && d.kh == d.kw && nodes[pw].kind == XENOS_OP_CONV && !chain_stores_strided(pw) && !chain_links_window_pool(pw)) {
           const xenos_op_desc& pd = desc(nodes[pw]);
           // Every workgroup of the pointwise chain recomputes the depthwise result of its 64 pixels for all input
           // channels; beyond 32 channel groups per pixel (8 pixels per thread) that serial work costs more than the
@@ -1130,7 +1172,7 @@ struct Planner {
         a.K = Kk;
         if (Kk != K) {
           if (tview[cur] >= 0 || placed.count(cur) || cur == out_tid) return fail(XENOS_EUNSUPPORTED, "%s: padded first layer needs a tensor of its own", st.name.c_str());
-          tview[cur] = internal_view(tshape[cur], -1, Kk);
+          tview[cur] = tag(internal_view(tshape[cur], -1, Kk), cur);
           p.views[tview[cur]].cphys = Kk;
         }
         if (st.stem_lds) {
@@ -1292,6 +1334,7 @@ struct Planner {
             const int v_part = (int)p.views.size() - 1;
             Step fin;
             fin.kind = S_SPLITK; fin.name = st.name + ".sum";
+            fin.ops = st.ops;                                      // the summing pass completes the same chain
             fin.v_in = v_part; fin.v_in2 = st.v_in2; fin.v_out = st.v_out;
             fin.scale_off = st.scale_off; fin.shift_off = st.shift_off;
             SplitKArgs& f = fin.splitk;
@@ -1342,7 +1385,7 @@ struct Planner {
         View sl = p.views[ov];
         sl.s = tshape[nd.in[j]]; sl.off += (long long)j; sl.sK = ileave[i];
         p.views.push_back(sl);
-        cs.v_out = (int)p.views.size() - 1;
+        cs.v_out = tag((int)p.views.size() - 1, nd.in[j]);
         fill_elt(cs, ELT_COPY, 0);
         add_step(cs);
       }
@@ -1378,6 +1421,10 @@ struct Planner {
         }
         p.views.push_back(a); cs.v_in = (int)p.views.size() - 1;
         p.views.push_back(o); cs.v_out = (int)p.views.size() - 1;
+        if (!whole) {   // group j of the input; its channels land at j, j + g, ... of the output
+          p.views[cs.v_in].gc0 += j * m * p.views[cs.v_in].gcs;
+          tag(cs.v_out, i + 1, j, g);
+        }
         fill_elt(cs, ELT_COPY, 0);
         add_step(cs);
       }
@@ -1394,7 +1441,7 @@ struct Planner {
       sl.s = tshape[i + 1]; sl.off += (long long)d.c_begin * sl.sK;
       if (sl.cphys) sl.cphys = 0;
       p.views.push_back(sl);
-      const int sv = (int)p.views.size() - 1;
+      const int sv = tag((int)p.views.size() - 1, i + 1);
       // (a range that does not start and end on a 16-byte channel group is copied too: the vector loaders of its
       // consumers need aligned groups)
       if (i + 1 == out_tid || placed.count(i + 1) || sl.off % p.ce != 0 || sl.s.c % p.ce != 0) {
@@ -1425,7 +1472,7 @@ struct Planner {
         View sl = p.views[ov];
         sl.s = tshape[nd.in[j]]; sl.off += off;
         p.views.push_back(sl);
-        cs.v_out = (int)p.views.size() - 1;
+        cs.v_out = tag((int)p.views.size() - 1, nd.in[j]);
         fill_elt(cs, ELT_COPY, 0);
         add_step(cs);
         off += tshape[nd.in[j]].c;
@@ -1574,6 +1621,21 @@ void write_plan_json(xenos_plan& p) {
                c.patch_w, p.views[s.v_out].off, c.out_sP, s.cfg == kHaloCfg ? 1 : 0, c.th, c.tw, s.dw_w_off >= 0 ? 1 : 0, c.ksplit > 1 ? c.ksplit : 1, (int)s.cands.size(), s.tuned, s.cfg == kHaloCfg ? c.halo_plin : 0, c.ileave);
       j += buf;
     }
+    // where the chain's tensors lie (byte offset into the workspace / the caller's input or output buffer, element
+    // strides) and which graph tensor each one is
+    auto view_json = [&](const char* key, int v) {
+      if (v < 0) return;
+      const View& vw = p.views[v];
+      const Buffer& bf = p.bufs[vw.buf];
+      snprintf(buf, sizeof buf, ",\"%s\":{\"mem\":\"%s\",\"byte_off\":%lld,\"sN\":%lld,\"sP\":%lld,\"sK\":%lld,\"esz\":%d,\"f32\":%d,"
+               "\"n\":%d,\"c\":%d,\"h\":%d,\"w\":%d,\"cphys\":%d,\"tensor\":%d,\"c0\":%d,\"cs\":%d}",
+               key, bf.ext == 1 ? "input" : bf.ext == 2 ? "output" : "workspace", (long long)(bf.ext ? 0 : bf.offset) + vw.off * vw.esz,
+               vw.sN, vw.sP, vw.sK, vw.esz, vw.f32, vw.s.n, vw.s.c, vw.s.h, vw.s.w, vw.cphys, vw.gt, vw.gc0, vw.gcs);
+      j += buf;
+    };
+    view_json("in", s.v_in);
+    view_json("in2", s.v_in2);
+    view_json("out", s.v_out);
     j += "}";
   }
   j += "]}";
@@ -1582,24 +1644,28 @@ void write_plan_json(xenos_plan& p) {
 // ---------------------------------------------------------------------------------------------
 // Runtime
 // ---------------------------------------------------------------------------------------------
-const unsigned char* view_ptr(const xenos_plan& p, int v, const void* d_in, void* d_out) {
+// `ws`: the workspace the intermediate tensors live in (the bound one, or the library's static one)
+struct Mem { const void* d_in; void* d_out; const void* ws; };
+
+const unsigned char* view_ptr(const xenos_plan& p, int v, const Mem& m) {
   const View& vw = p.views[v];
   const Buffer& b = p.bufs[vw.buf];
-  const unsigned char* base = b.ext == 1 ? (const unsigned char*)d_in
-                              : b.ext == 2 ? (const unsigned char*)d_out
-                                           : (const unsigned char*)p.d_workspace + b.offset;
+  const unsigned char* base = b.ext == 1 ? (const unsigned char*)m.d_in
+                              : b.ext == 2 ? (const unsigned char*)m.d_out
+                                           : (const unsigned char*)m.ws + b.offset;
   return base + vw.off * vw.esz;
 }
 
-xenos_status launch_step(xenos_plan& p, const Step& s, const void* d_in, void* d_out, void* stream) {
+xenos_status launch_step(xenos_plan& p, const Step& s, const void* d_in_, void* d_out_, void* stream, const void* ws = nullptr) {
+  const Mem mem{d_in_, d_out_, ws ? ws : p.d_workspace};
   const unsigned char* wb = (const unsigned char*)p.d_weights;
   int rc = 0;
   switch (s.kind) {
     case S_CONV: {
       ConvArgs a = s.conv;
-      a.in = view_ptr(p, s.v_in, d_in, d_out);
-      a.out = (void*)view_ptr(p, s.v_out, d_in, d_out);
-      a.res = s.v_in2 >= 0 ? view_ptr(p, s.v_in2, d_in, d_out) : nullptr;
+      a.in = view_ptr(p, s.v_in, mem);
+      a.out = (void*)view_ptr(p, s.v_out, mem);
+      a.res = s.v_in2 >= 0 ? view_ptr(p, s.v_in2, mem) : nullptr;
       a.w = wb + s.w_off;
       a.scale = (const float*)(wb + s.scale_off);
       a.shift = (const float*)(wb + s.shift_off);
@@ -1613,8 +1679,8 @@ xenos_status launch_step(xenos_plan& p, const Step& s, const void* d_in, void* d
     }
     case S_DW: {
       DwArgs a = s.dw;
-      a.in = view_ptr(p, s.v_in, d_in, d_out);
-      a.out = (void*)view_ptr(p, s.v_out, d_in, d_out);
+      a.in = view_ptr(p, s.v_in, mem);
+      a.out = (void*)view_ptr(p, s.v_out, mem);
       a.w = wb + s.w_off;
       a.scale = (const float*)(wb + s.scale_off);
       a.shift = (const float*)(wb + s.shift_off);
@@ -1623,9 +1689,9 @@ xenos_status launch_step(xenos_plan& p, const Step& s, const void* d_in, void* d
     }
     case S_ELT: {
       EltArgs a = s.elt;
-      a.a = view_ptr(p, s.v_in, d_in, d_out);
-      a.b = s.v_in2 >= 0 ? view_ptr(p, s.v_in2, d_in, d_out) : nullptr;
-      a.out = (void*)view_ptr(p, s.v_out, d_in, d_out);
+      a.a = view_ptr(p, s.v_in, mem);
+      a.b = s.v_in2 >= 0 ? view_ptr(p, s.v_in2, mem) : nullptr;
+      a.out = (void*)view_ptr(p, s.v_out, mem);
       a.scale = s.scale_off >= 0 ? (const float*)(wb + s.scale_off) : nullptr;
       a.shift = s.shift_off >= 0 ? (const float*)(wb + s.shift_off) : nullptr;
       rc = launch_elt(a, p.dt, stream);
@@ -1633,16 +1699,16 @@ xenos_status launch_step(xenos_plan& p, const Step& s, const void* d_in, void* d
     }
     case S_POOL: {
       PoolArgs a = s.pool;
-      a.in = view_ptr(p, s.v_in, d_in, d_out);
-      a.out = (void*)view_ptr(p, s.v_out, d_in, d_out);
+      a.in = view_ptr(p, s.v_in, mem);
+      a.out = (void*)view_ptr(p, s.v_out, mem);
       rc = launch_pool(a, p.dt, stream);
       break;
     }
     case S_SPLITK: {
       SplitKArgs a = s.splitk;
-      a.part = (const float*)view_ptr(p, s.v_in, d_in, d_out);
-      a.res = s.v_in2 >= 0 ? view_ptr(p, s.v_in2, d_in, d_out) : nullptr;
-      a.out = (void*)view_ptr(p, s.v_out, d_in, d_out);
+      a.part = (const float*)view_ptr(p, s.v_in, mem);
+      a.res = s.v_in2 >= 0 ? view_ptr(p, s.v_in2, mem) : nullptr;
+      a.out = (void*)view_ptr(p, s.v_out, mem);
       a.scale = (const float*)(wb + s.scale_off);
       a.shift = (const float*)(wb + s.shift_off);
       rc = launch_splitk_finish(a, p.dt, stream);
@@ -1650,8 +1716,8 @@ xenos_status launch_step(xenos_plan& p, const Step& s, const void* d_in, void* d
     }
     case S_CVT: {
       CvtArgs a = s.cvt;
-      a.in = view_ptr(p, s.v_in, d_in, d_out);
-      a.out = (void*)view_ptr(p, s.v_out, d_in, d_out);
+      a.in = view_ptr(p, s.v_in, mem);
+      a.out = (void*)view_ptr(p, s.v_out, mem);
       rc = launch_cvt(a, p.dt, stream);
       break;
     }
@@ -1854,7 +1920,7 @@ xenos_status xenos_run(xenos_plan* plan, const void* d_input, void* d_output, vo
 
 xenos_status xenos_run_graph(xenos_plan* plan, const void* d_input, void* d_output, void* hip_stream) {
   if (!plan || plan->magic != MAGIC_PLAN || !d_input || !d_output) return fail(XENOS_EINVAL, "xenos_run_graph: bad argument");
-  if (!plan->bound) return fail(XENOS_EINVAL, "xenos_run_graph: plan is not bound (call xenos_plan_bind)");
+  if (!plan->bound || !plan->d_workspace) return fail(XENOS_EINVAL, "xenos_run_graph: plan is not bound to a workspace (call xenos_plan_bind)");
   auto key = std::make_pair(d_input, d_output);
   auto it = plan->graphs.find(key);
   if (it == plan->graphs.end()) {
@@ -1887,9 +1953,10 @@ xenos_status xenos_run_graph(xenos_plan* plan, const void* d_input, void* d_outp
 
 xenos_status xenos_plan_tune(xenos_plan* plan, const void* d_input, void* d_output, void* hip_stream, int reps, int* n_changed) {
   if (!plan || plan->magic != MAGIC_PLAN || !d_input || !d_output || reps < 1) return fail(XENOS_EINVAL, "xenos_plan_tune: bad argument");
-  if (!plan->bound) return fail(XENOS_EINVAL, "xenos_plan_tune: plan is not bound (call xenos_plan_bind)");
+  if (!plan->bound || !plan->d_workspace) return fail(XENOS_EINVAL, "xenos_plan_tune: plan is not bound to a workspace (call xenos_plan_bind)");
   hipStream_t st = (hipStream_t)hip_stream;
-  // one full pass first: every chain then finds its real input in the workspace
+  // one full pass first: every buffer then holds finite values of the real shapes (workspace blocks are reused along the
+  // pass, so a chain is not guaranteed to find its own input there; run times do not depend on the values)
   for (const Step& s : plan->steps) {
     xenos_status rc = launch_step(*plan, s, d_input, d_output, hip_stream);
     if (rc != XENOS_OK) return rc;
@@ -1933,6 +2000,12 @@ xenos_status xenos_plan_tune(xenos_plan* plan, const void* d_input, void* d_outp
       if (launch_step(*plan, s, d_input, d_output, hip_stream) != XENOS_OK) { rc = fail(XENOS_EDEVICE, "xenos_plan_tune: launch failed"); break; }
     }
   }
+  // a full pass with the chosen partitions leaves the output valid
+  if (rc == XENOS_OK)
+    for (const Step& s : plan->steps) {
+      rc = launch_step(*plan, s, d_input, d_output, hip_stream);
+      if (rc != XENOS_OK) break;
+    }
   (void)hipStreamSynchronize(st);
   (void)hipEventDestroy(e0);
   (void)hipEventDestroy(e1);
@@ -1946,7 +2019,7 @@ xenos_status xenos_plan_tune(xenos_plan* plan, const void* d_input, void* d_outp
 
 xenos_status xenos_run_chain(xenos_plan* plan, int chain, const void* d_input, void* d_output, void* hip_stream) {
   if (!plan || plan->magic != MAGIC_PLAN || !d_input || !d_output) return fail(XENOS_EINVAL, "xenos_run_chain: bad argument");
-  if (!plan->bound) return fail(XENOS_EINVAL, "xenos_run_chain: plan is not bound");
+  if (!plan->bound || !plan->d_workspace) return fail(XENOS_EINVAL, "xenos_run_chain: plan is not bound to a workspace");
   if (chain < 0 || chain >= (int)plan->steps.size()) return fail(XENOS_EINVAL, "xenos_run_chain: chain %d out of range", chain);
   return launch_step(*plan, plan->steps[chain], d_input, d_output, hip_stream);
 }

@@ -223,13 +223,21 @@ def graph_from_workload(g, in_dtype=XENOS_F32, in_layout=XENOS_NCHW, out_dtype=X
 
 
 class Session:
-    """Owns the device memory of one bound plan (PyTorch tensors) and runs it on torch's current stream."""
+    """Owns the device memory of one bound plan (PyTorch tensors) and runs it on torch's current stream.
 
-    def __init__(self, g, link=2, split=1, compute=XENOS_F32, tile=0, hw=None, device="cuda:0"):
+    in_dtype / in_layout / out_dtype / out_layout are the caller-side formats of the graph input and output
+    (XENOS_F32 / XENOS_BF16, XENOS_NCHW / XENOS_NHWC).  set_input() and output() always speak fp32 NCHW numpy: the
+    conversion to and from the caller-side format is a torch permute / cast on the device buffers, i.e. what a
+    caller holding such tensors would pass; the library reads and writes them in place.
+    workspace=False binds no workspace: such a session runs through run_static() only."""
+
+    def __init__(self, g, link=2, split=1, compute=XENOS_F32, tile=0, hw=None, device="cuda:0",
+                 in_dtype=XENOS_F32, in_layout=XENOS_NCHW, out_dtype=XENOS_F32, out_layout=XENOS_NCHW, workspace=True):
         import torch
         self.torch = torch
         self.device = torch.device(device)
-        self.graph = graph_from_workload(g)
+        self.in_fmt, self.out_fmt = (in_dtype, in_layout), (out_dtype, out_layout)
+        self.graph = graph_from_workload(g, in_dtype, in_layout, out_dtype, out_layout)
         self.plan = None
         try:
             self.plan = xenos_plan_link_split(self.graph, hw, link, split, compute, tile)
@@ -237,24 +245,45 @@ class Session:
             self.info = q["plan"]
             self.out_desc = q["out_desc"]
             self.weights = torch.empty(q["weight_bytes"] + 256, dtype=torch.uint8, device=self.device)
-            self.workspace = torch.zeros(q["workspace_bytes"] + 256, dtype=torch.uint8, device=self.device)
+            self.workspace = torch.zeros(q["workspace_bytes"] + 256, dtype=torch.uint8, device=self.device) if workspace else None
             od = self.out_desc
-            self.y = torch.zeros((od["n"], od["c"], od["h"], od["w"]), dtype=torch.float32, device=self.device)
-            self.x = torch.zeros(tuple(g.input_shape), dtype=torch.float32, device=self.device)
-            xenos_plan_bind(self.plan, self._al(self.weights), self._al(self.workspace), self.stream())
+            self.y = self._alloc((od["n"], od["c"], od["h"], od["w"]), out_dtype, out_layout)
+            self.x = self._alloc(tuple(g.input_shape), in_dtype, in_layout)
+            xenos_plan_bind(self.plan, self._al(self.weights), self._al(self.workspace) if workspace else 0, self.stream())
         except Exception:
             self.close()
             raise
+
+    def _alloc(self, nchw, dtype, layout):
+        """A zeroed device tensor of logical shape `nchw`, stored in the given dtype and layout."""
+        torch = self.torch
+        n, c, h, w = nchw
+        shape = (n, h, w, c) if layout == XENOS_NHWC else (n, c, h, w)
+        return torch.zeros(shape, dtype=torch.bfloat16 if dtype == XENOS_BF16 else torch.float32, device=self.device)
 
     @staticmethod
     def _al(t) -> int:
         return (t.data_ptr() + 255) // 256 * 256
 
+    def workspace_view(self):
+        """The bound workspace as a uint8 tensor starting at the bound (256-byte aligned) address."""
+        off = self._al(self.workspace) - self.workspace.data_ptr()
+        return self.workspace[off:]
+
     def stream(self) -> int:
         return self.torch.cuda.current_stream(self.device).cuda_stream
 
     def set_input(self, x: np.ndarray):
-        self.x.copy_(self.torch.from_numpy(np.ascontiguousarray(x, dtype=np.float32)))
+        t = self.torch.from_numpy(np.ascontiguousarray(x, dtype=np.float32)).to(self.device)
+        if self.in_fmt[1] == XENOS_NHWC:
+            t = t.permute(0, 2, 3, 1)
+        self.x.copy_(t)                      # (the cast to bf16, where asked for, rounds to nearest even)
+
+    def _y_numpy(self) -> np.ndarray:
+        y = self.y.float()
+        if self.out_fmt[1] == XENOS_NHWC:
+            y = y.permute(0, 3, 1, 2)
+        return y.contiguous().cpu().numpy()
 
     def run(self):
         xenos_run(self.plan, self.x.data_ptr(), self.y.data_ptr(), self.stream())
@@ -269,7 +298,7 @@ class Session:
         self.set_input(x)
         self.run()
         self.torch.cuda.synchronize(self.device)
-        return self.y.cpu().numpy()
+        return self._y_numpy()
 
     def tune(self, reps: int = 5) -> int:
         """xenos_plan_tune on the session's current input; refreshes `info`."""
@@ -280,7 +309,7 @@ class Session:
     def output(self) -> np.ndarray:
         """Synchronises and returns the output buffer of the last run / run_graph."""
         self.torch.cuda.synchronize(self.device)
-        return self.y.cpu().numpy()
+        return self._y_numpy()
 
     def close(self):
         xenos_destroy(self.plan)
