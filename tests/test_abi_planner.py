@@ -120,7 +120,8 @@ def test_every_operator_runs_exactly_once(cfg, batch):
     g = wg.build(cfg, batch, draw=False)
     for link in (0, 1, 2):
         q = plan_json(g, link=link, compute=X.XENOS_BF16)["plan"]
-        seen = [o for c in q["chains"] for o in c["ops"]]
+        # (the summing pass of a reduction split completes the chain of the step before it and names the same operators)
+        seen = [o for c in q["chains"] if c["kind"] != "splitk_finish" for o in c["ops"]]
         # a hoisted pooling operator appears once per concat producer; a copied concat once per input
         assert set(seen) == set(range(len(g.ops))) - ({i for i, o in enumerate(g.ops) if o.kind == "concat"} if link >= 2 else set())
         if link < 2:
