@@ -143,13 +143,27 @@ xenos_status xenos_plan_query(const xenos_plan* plan, size_t* weight_bytes, size
 
 /* Packs the parameters in operand order (K-tile major, (r,s,c) contiguous; Section 4.2.2) into the
  * caller's device buffer d_weights (>= weight_bytes) and records d_workspace (>= workspace_bytes).
- * Both must be 256-byte aligned.  Synchronises hip_stream before returning. */
+ * Both must be 256-byte aligned.  d_workspace may be NULL: the plan then runs through xenos_run_static only.
+ * Synchronises hip_stream before returning. */
 xenos_status xenos_plan_bind(xenos_plan* plan, void* d_weights, void* d_workspace, void* hip_stream);
 
 /* Section 3, the runtime: enqueues the planned kernel sequence on hip_stream.  d_input / d_output
  * are device buffers in the dtype / layout of the graph's input / output descriptors.
  * Asynchronous; allocates nothing; returns XENOS_EDEVICE if a launch fails. */
 xenos_status xenos_run(xenos_plan* plan, const void* d_input, void* d_output, void* hip_stream);
+
+/* For callers that cannot allocate device memory or hand over a workspace (code under HIP-graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc): xenos_run with the intermediate tensors in a workspace that is
+ * part of the library's own device image, XENOS_STATIC_WORKSPACE_BYTES per GPU, held until the process ends.
+ * Same arguments, same result and same asynchrony as xenos_run; the workspace given to xenos_plan_bind is not
+ * touched.  Returns XENOS_EUNSUPPORTED when the plan needs a larger workspace (xenos_plan_query tells), and
+ * XENOS_EDEVICE when the address of the static workspace cannot be obtained.  Calls no allocating routine.  The
+ * first call on a device looks the workspace's address up (not to be made under stream capture).  All calls on one
+ * GPU share the workspace, whatever the plan: calls that overlap in time on one GPU (two streams, two threads) race;
+ * calls that follow each other on one stream do not.  Nothing is cleared between calls: every chain writes what a
+ * later chain of the same pass reads. */
+#define XENOS_STATIC_WORKSPACE_BYTES (32u << 20)
+xenos_status xenos_run_static(xenos_plan* plan, const void* d_input, void* d_output, void* hip_stream);
 
 /* Same result as xenos_run, for latency-bound (batch 1) use: the first call with a given (d_input, d_output)
  * pair captures the kernel sequence into a HIP graph (kernel nodes only; the runtime allocates host-side graph

@@ -11,6 +11,7 @@
 
 #include <algorithm>
 #include <map>
+#include <mutex>
 #include <new>
 #include <string>
 #include <vector>
@@ -1729,6 +1730,42 @@ xenos_status launch_step(xenos_plan& p, const Step& s, const void* d_in_, void* 
 }  // namespace
 
 // ---------------------------------------------------------------------------------------------
+// Workspace of xenos_run_static: a file-scope device array instead of caller memory.  Every GPU the library runs on
+// holds its own copy for the life of the process.  In host code the array's name is only a handle for
+// hipGetSymbolAddress; its device address is looked up once per device and kept.
+// ---------------------------------------------------------------------------------------------
+static __device__ __align__(256) unsigned char scratch[XENOS_STATIC_WORKSPACE_BYTES];
+
+namespace {
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+// device address of `scratch` on the current device (nullptr + message on failure)
+void* static_workspace() {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+    fail(XENOS_EDEVICE, "xenos_run_static: no current device (%s)", hipGetErrorString(e));
+    return nullptr;
+  }
+  std::lock_guard<std::mutex> lk(g_scratch_mu);
+  if (!g_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !ptr) {
+      fail(XENOS_EDEVICE, "xenos_run_static: hipGetSymbolAddress failed: %s", hipGetErrorString(e));
+      return nullptr;
+    }
+    g_scratch_ptr[dev] = ptr;
+  }
+  return g_scratch_ptr[dev];
+}
+
+}  // namespace
+
+// ---------------------------------------------------------------------------------------------
 // C ABI
 // ---------------------------------------------------------------------------------------------
 extern "C" {
@@ -1893,7 +1930,8 @@ xenos_status xenos_plan_query(const xenos_plan* plan, size_t* weight_bytes, size
 }
 
 xenos_status xenos_plan_bind(xenos_plan* plan, void* d_weights, void* d_workspace, void* hip_stream) {
-  if (!plan || plan->magic != MAGIC_PLAN || !d_weights || !d_workspace) return fail(XENOS_EINVAL, "xenos_plan_bind: bad argument");
+  // (d_workspace may be NULL: the plan can then run through xenos_run_static only)
+  if (!plan || plan->magic != MAGIC_PLAN || !d_weights) return fail(XENOS_EINVAL, "xenos_plan_bind: bad argument");
   if (((uintptr_t)d_weights | (uintptr_t)d_workspace) & 255) return fail(XENOS_EINVAL, "xenos_plan_bind: buffers must be 256-byte aligned");
   hipStream_t st = (hipStream_t)hip_stream;
   if (!plan->wimage.empty()) {
@@ -1911,8 +1949,26 @@ xenos_status xenos_plan_bind(xenos_plan* plan, void* d_weights, void* d_workspac
 xenos_status xenos_run(xenos_plan* plan, const void* d_input, void* d_output, void* hip_stream) {
   if (!plan || plan->magic != MAGIC_PLAN || !d_input || !d_output) return fail(XENOS_EINVAL, "xenos_run: bad argument");
   if (!plan->bound) return fail(XENOS_EINVAL, "xenos_run: plan is not bound (call xenos_plan_bind)");
+  if (!plan->d_workspace) return fail(XENOS_EINVAL, "xenos_run: the plan was bound without a workspace (xenos_run_static only)");
   for (const Step& s : plan->steps) {
     xenos_status rc = launch_step(*plan, s, d_input, d_output, hip_stream);
+    if (rc != XENOS_OK) return rc;
+  }
+  return XENOS_OK;
+}
+
+xenos_status xenos_run_static(xenos_plan* plan, const void* d_input, void* d_output, void* hip_stream) {
+  if (!plan || plan->magic != MAGIC_PLAN || !d_input || !d_output) return fail(XENOS_EINVAL, "xenos_run_static: bad argument");
+  if (!plan->bound) return fail(XENOS_EINVAL, "xenos_run_static: plan is not bound (call xenos_plan_bind)");
+  if (plan->workspace_bytes > (size_t)XENOS_STATIC_WORKSPACE_BYTES)
+    return fail(XENOS_EUNSUPPORTED, "xenos_run_static: the plan needs %zu bytes of workspace, the static workspace holds %zu",
+                plan->workspace_bytes, (size_t)XENOS_STATIC_WORKSPACE_BYTES);
+  void* ws = static_workspace();
+  if (!ws) return XENOS_EDEVICE;
+  // No chain reads a workspace byte that an earlier chain of the same pass (or the weight image) has not written, so
+  // nothing is cleared: what the previous call left behind is overwritten before it is read.
+  for (const Step& s : plan->steps) {
+    xenos_status rc = launch_step(*plan, s, d_input, d_output, hip_stream, ws);
     if (rc != XENOS_OK) return rc;
   }
   return XENOS_OK;

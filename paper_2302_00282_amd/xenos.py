@@ -83,13 +83,14 @@ def lib():
         L.xenos_plan_bind.argtypes = [vp, vp, vp, vp]
         L.xenos_run.argtypes = [vp, vp, vp, vp]
         L.xenos_run_graph.argtypes = [vp, vp, vp, vp]
+        L.xenos_run_static.argtypes = [vp, vp, vp, vp]
         L.xenos_run_chain.argtypes = [vp, C.c_int, vp, vp, vp]
         L.xenos_plan_tune.argtypes = [vp, vp, vp, vp, C.c_int, C.POINTER(C.c_int)]
         L.xenos_destroy.argtypes = [vp]
         L.xenos_destroy.restype = None
         L.xenos_last_error.restype = C.c_char_p
         for f in ("xenos_graph_create", "xenos_plan_link_split", "xenos_plan_query", "xenos_plan_bind",
-                  "xenos_run", "xenos_run_graph", "xenos_run_chain", "xenos_plan_tune"):
+                  "xenos_run", "xenos_run_graph", "xenos_run_static", "xenos_run_chain", "xenos_plan_tune"):
             getattr(L, f).restype = C.c_int
         _lib = L
     return _lib
@@ -147,6 +148,13 @@ def xenos_run(plan: int, d_input: int, d_output: int, stream: int = 0):
 
 def xenos_run_graph(plan: int, d_input: int, d_output: int, stream: int = 0):
     _check(lib().xenos_run_graph(plan, d_input, d_output, stream))
+
+
+XENOS_STATIC_WORKSPACE_BYTES = 32 << 20
+
+
+def xenos_run_static(plan: int, d_input: int, d_output: int, stream: int = 0):
+    _check(lib().xenos_run_static(plan, d_input, d_output, stream))
 
 
 def xenos_plan_tune(plan: int, d_input: int, d_output: int, stream: int = 0, reps: int = 5) -> int:
@@ -284,6 +292,9 @@ class Session:
         if self.out_fmt[1] == XENOS_NHWC:
             y = y.permute(0, 3, 1, 2)
         return y.contiguous().cpu().numpy()
+
+    def run_static(self):
+        xenos_run_static(self.plan, self.x.data_ptr(), self.y.data_ptr(), self.stream())
 
     def run(self):
         xenos_run(self.plan, self.x.data_ptr(), self.y.data_ptr(), self.stream())
