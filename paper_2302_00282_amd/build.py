@@ -8,8 +8,8 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libxenos.so")
-SOURCES = ["xenos_kernels.hip", "xenos_lib.cpp"]
-HEADERS = ["kernels.h", os.path.join("..", "..", "include", "xenos.h")]
+SOURCES = ["xenos_kernels.hip", "xenos_linked.hip", "xenos_lib.cpp"]
+HEADERS = ["kernels.h", "device_common.h", os.path.join("..", "..", "include", "xenos.h")]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-x", "hip",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wall", "-Wno-unused-function"]
@@ -26,12 +26,11 @@ def build_library(force: bool = True, verbose: bool = False) -> str:
     """Compile every source with hipcc and link the shared library. Returns its path."""
     if not force and not stale():
         return LIB
-    objs = []
-    for src in SOURCES:
-        obj = os.path.join(CSRC, os.path.splitext(src)[0] + ".o")
-        cmd = ["hipcc", *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
-        _run(cmd, verbose)
-        objs.append(obj)
+    from concurrent.futures import ThreadPoolExecutor
+    objs = [os.path.join(CSRC, os.path.splitext(src)[0] + ".o") for src in SOURCES]
+    cmds = [["hipcc", *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj] for src, obj in zip(SOURCES, objs)]
+    with ThreadPoolExecutor(max_workers=len(cmds)) as ex:      # one hipcc per source, side by side
+        list(ex.map(lambda c: _run(c, verbose), cmds))
     _run(["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs], verbose)
     return LIB
 

@@ -53,6 +53,11 @@ static const int kFcChannels = 128;
 static const int kStemLdsCfg = 8;
 static const int kStemLdsPph = 3, kStemLdsPpw = 8;   // pooling windows per tile when a max-pooling is linked
 static const int kStemLdsTh = 8, kStemLdsTw = 16, kStemLdsInMax = 784;   // (7 * 2 + 7) x (15 * 2 + 7) = 777 positions at most
+// Configuration index of the kernel that links a pointwise (1x1) convolution chain with the depthwise 3x3 chain that consumes
+// it: a TH x TW block of depthwise output pixels x kPwDwChannels channels per workgroup, the pointwise output of the block
+// (+ halo) staged in LDS, at most kPwDwMaxPositions positions
+static const int kPwDwCfg = 9;
+static const int kPwDwChannels = 64, kPwDwMaxPositions = 400;
 static const int kFcWgPerCu = 1;
 static const int kFcDirectSteps = 16;   // reductions of at most this many 64-element steps are not shared out (no summing pass)    // workgroups per compute unit the reduction split of such a chain aims at
 static const int kPairChannels = 64, kPairRed = 48;
@@ -100,6 +105,10 @@ struct ConvArgs {
   int pair, pair_C;
   long long pair_sN, pair_sC, pair_sH;
   int dw_panel;          // > 0: the depthwise result of a whole panel of this many channels is staged in LDS (dwpw_kernel)
+  // linked depthwise CONSUMER (pwdw_kernel): this 1x1 / stride 1 chain's output tile stays in LDS and a depthwise 3x3 chain
+  // (dw_w [9][K], dw_scale / dw_shift [K], dw_stride, dw_pad = 1, dw_relu) runs out of it; H x W is the pointwise map,
+  // OH x OW the depthwise output, th x tw the tile of depthwise output pixels, tiles_y x tiles_x the tile grid per image
+  int pwdw;
   // reduction split across workgroups (ksplit >= 1, M_FLAT only; 0 = none): share z covers steps [z*steps_per_split, ...)
   // and writes raw fp32 sums to part[z][m][k] (row pitch part_ld); a splitk_finish pass completes the chain
   int ksplit, steps_per_split, part_ld;
@@ -175,5 +184,8 @@ size_t conv_lds_bytes(int cfg, int mode);
 bool conv_cfg_has_scalar_loader(int cfg);
 bool conv_cfg_has_dw_prologue(int cfg, int mode);
 size_t dwpw_lds_bytes(int panel_channels, int esz);   // LDS of the depthwise-panel kernel for a panel of that many channels
+// pointwise -> depthwise kernel (xenos_linked.hip)
+int launch_pwdw(const ConvArgs& a, int dtype, void* stream);
+size_t pwdw_lds_bytes(int th, int tw, int stride, int esz);
 
 }  // namespace xenos

@@ -951,7 +951,151 @@ struct Planner {
     return XENOS_OK;
   }
 
+  // ---- the link pass for one convolution: which operators behind it join its chain (Section 4.1, Table 1) ------
+  // conv -> (bias | bn)* -> [add shortcut] -> [relu] -> [max / avg / global pooling]; a depthwise convolution takes no
+  // shortcut and no pooling.  Changes nothing in the plan, so the pattern checks of the deeper links may call it for
+  // nodes that are planned later.
+  struct ChainWalk {
+    Affine af;                     // folded scale / shift of the absorbed bias / bn operators (and the convolution's own bias)
+    bool relu = false, has_res = false;
+    int res_tid = -1, pool_node = -1;
+    int cur = 0, last = 0;         // the chain's output tensor and last node
+    std::vector<int> absorbed;
+  };
+  ChainWalk walk_chain(int i) const {
+    const Node& nd = nodes[i];
+    const GOp& go = g.ops[nd.src];
+    const int link = p.opts.link;
+    const bool dw = nd.kind == XENOS_OP_CONV && desc(nd).groups != 1;
+    ChainWalk w;
+    w.af.scale.assign(desc(nd).out_c, 1.0);
+    w.af.shift.assign(desc(nd).out_c, 0.0);
+    if (!go.bias.empty()) fold_bias(w.af, go.bias);
+    w.cur = i + 1; w.last = i;
+    int stage = 0;
+    while (link >= 1) {
+      const int nx = single_consumer(w.cur);
+      if (nx < 0 || placed.count(w.cur)) break;
+      const Node& nn_ = nodes[nx];
+      const GOp& ng = g.ops[nn_.src];
+      if ((nn_.kind == XENOS_OP_BIAS || nn_.kind == XENOS_OP_BN) && stage == 0) {
+        if (nn_.kind == XENOS_OP_BIAS) fold_bias(w.af, ng.bias); else fold_bn(w.af, ng);
+      } else if (nn_.kind == XENOS_OP_ADD && link >= 2 && !dw && stage <= 1) {
+        const int other = nn_.in[0] == w.cur ? nn_.in[1] : nn_.in[0];
+        if (other == w.cur || !available(other) || other == 0) break;
+        const View& ov = p.views[tview[other]];
+        if (!ov.internal_nhwc() || ov.f32) break;
+        w.has_res = true; w.res_tid = other; stage = 2;
+      } else if (nn_.kind == XENOS_OP_RELU && stage <= 2) {
+        w.relu = true; stage = 3;
+      } else if ((nn_.kind == XENOS_OP_MAXPOOL || nn_.kind == XENOS_OP_AVGPOOL || nn_.kind == XENOS_OP_GLOBAL_AVGPOOL) &&
+                 link >= 2 && !dw && (!w.has_res || nn_.kind == XENOS_OP_GLOBAL_AVGPOOL) && stage <= 3) {
+        w.pool_node = nx; stage = 4;
+      } else {
+        break;
+      }
+      w.absorbed.push_back(nx);
+      w.cur = nx + 1; w.last = nx;
+      if (stage == 4) break;
+    }
+    return w;
+  }
+
+  // depthwise weights [C][k*k] -> [tap][C] in the compute type; returns the byte offset in the weight image
+  long long pack_depthwise(const GOp& go, int C, int taps) {
+    const size_t bytes = (size_t)taps * C * p.esz;
+    const long long off = (long long)wpush(nullptr, bytes);
+    unsigned char* base = p.wimage.data() + off;
+    for (int c = 0; c < C; ++c)
+      for (int t = 0; t < taps; ++t) {
+        const float v = go.weight[(size_t)c * taps + t];
+        if (p.dt == DT_BF16) ((uint16_t*)base)[(size_t)t * C + c] = f2bf_host(v);
+        else ((float*)base)[(size_t)t * C + c] = v;
+      }
+    return off;
+  }
+
+  // ---- link level 3, pointwise -> depthwise (Section 2.2; Table 1, ConvX -> ConvY) -------------------------------
+  // Can the dense convolution node `i` keep its output on chip for the depthwise convolution that consumes it?
+  // conv 1x1 / stride 1 / pad 0 -> (bias | bn)* -> [relu] -> depthwise 3x3 / pad 1 / stride 1 or 2 -> (bias | bn)* -> [relu],
+  // nothing else reading the tensors in between, whole 16-byte channel groups.  Returns the depthwise node or -1.
+  int pwdw_consumer(int i) const {
+    if (p.opts.link < 3 || p.opts.tile != 0 || i < 0 || node_step[i] >= 0) return -1;
+    const Node& nd = nodes[i];
+    if (nd.kind != XENOS_OP_CONV) return -1;
+    const xenos_op_desc& d = desc(nd);
+    const Shape is = tshape[nd.in[0]];
+    if (d.groups != 1 || d.kh != 1 || d.kw != 1 || d.stride_h != 1 || d.pad_h != 0 || nd.in[0] == 0 ||
+        is.c % p.ce != 0 || d.out_c % p.ce != 0) return -1;
+    const ChainWalk w = walk_chain(i);
+    if (w.has_res || w.pool_node >= 0 || w.cur == out_tid || placed.count(w.cur) || fin.count(w.cur)) return -1;
+    const int dn = single_consumer(w.cur);
+    if (dn < 0 || node_step[dn] >= 0 || nodes[dn].kind != XENOS_OP_CONV) return -1;
+    const xenos_op_desc& dd = desc(nodes[dn]);
+    if (dd.groups != d.out_c || dd.out_c != d.out_c || dd.kh != 3 || dd.kw != 3 || dd.pad_h != 1 || (dd.stride_h != 1 && dd.stride_h != 2)) return -1;
+    const ChainWalk w2 = walk_chain(dn);
+    if (fin.count(w2.cur)) return -1;
+    auto pl = placed.find(w2.cur);
+    if (pl != placed.end() && (pl->second.c_stride != 1 || pl->second.c_off % p.ce != 0)) return -1;   // (16-byte stores only)
+    if (w2.cur == out_tid && !ext_is_internal(p.out)) return -1;
+    return dn;
+  }
+  // The pointwise -> depthwise link is taken where the depthwise -> pointwise one (dwpw_kernel, up to 32 channel groups) is
+  // no alternative for that depthwise convolution, or where the pointwise convolution behind it can again hand on to a
+  // depthwise one, so that a depthwise-separable stack becomes a sequence of pointwise -> depthwise chains (the tensors
+  // that reach memory are then the depthwise outputs, the smaller ones of each block).
+  bool pwdw_wanted(int i, int dn) const {
+    const int C = desc(nodes[dn]).out_c;
+    if (C / p.ce > 32) return true;
+    const ChainWalk w2 = walk_chain(dn);
+    const int nx = placed.count(w2.cur) ? -1 : single_consumer(w2.cur);
+    if (nx < 0 || nodes[nx].kind != XENOS_OP_CONV) return true;
+    const xenos_op_desc& nd2 = desc(nodes[nx]);
+    if (nd2.groups != 1 || nd2.kh != 1 || nd2.kw != 1 || nd2.stride_h != 1 || nd2.pad_h != 0) return true;
+    (void)i;
+    return pwdw_consumer(nx) >= 0;
+  }
+
+  // Tile of depthwise output pixels for a pointwise -> depthwise chain: the GEMM runs over the block positions inside
+  // the map in chunks of 64, so the cost of a tile is its chunk count (+ a fixed part); the longest workgroup queue
+  // decides.  Two workgroups share a compute unit.
+  bool choose_pwdw_tile(ConvArgs& c) const {
+    const int s = c.dw_stride, num_cu = std::max(1, p.hw.num_cu);
+    const size_t lds_cap = std::min<size_t>(p.hw.lds_bytes_per_cu, 160 * 1024);
+    double best = 1e300;
+    for (int th = 1; th <= c.OH; ++th)
+      for (int tw = 1; tw <= c.OW; ++tw) {
+        const int PH = (th - 1) * s + 3, PWd = (tw - 1) * s + 3;
+        if (PH * PWd > kPwDwMaxPositions) break;
+        if (pwdw_lds_bytes(th, tw, s, p.esz) > lds_cap) break;
+        const int ty = (c.OH + th - 1) / th, tx = (c.OW + tw - 1) / tw;
+        double total = 0, longest = 0;
+        for (int y = 0; y < ty; ++y) {
+          const int iy0 = y * th * s - 1, hv = std::min(iy0 + PH, c.H) - std::max(iy0, 0);
+          for (int x = 0; x < tx; ++x) {
+            const int ix0 = x * tw * s - 1, wv = std::min(ix0 + PWd, c.W) - std::max(ix0, 0);
+            const double cost = (hv * wv + 63) / 64 + 0.75;
+            total += cost; longest = std::max(longest, cost);
+          }
+        }
+        const double tiles_n = (c.K + kPwDwChannels - 1) / kPwDwChannels;
+        // (the second term stands for the traffic of the whole launch, input block and weight slice per tile: among
+        // tilings that fit one round it prefers the one with the least recomputation)
+        const double all = total * c.N * tiles_n;
+        const double t = p.opts.split ? std::max(all / (2.0 * num_cu), longest) + all / (8.0 * num_cu) : total;
+        if (t < best - 1e-9) { best = t; c.th = th; c.tw = tw; c.tiles_y = ty; c.tiles_x = tx; }
+      }
+    return best < 1e300;
+  }
+
   xenos_status plan_node(int i) {
+    const int k = nodes[i].kind;
+    return k == XENOS_OP_CONV || k == XENOS_OP_FC ? plan_conv(i) : plan_standalone(i);
+  }
+
+  // Plans the chain that convolution / fully connected node `i` starts (and, at link level 3, the convolution it hands
+  // its output to on chip).
+  xenos_status plan_conv(int i) {
     const Node& nd = nodes[i];
     const xenos_op_desc& d = desc(nd);
     const GOp& go = g.ops[nd.src];
@@ -962,45 +1106,19 @@ struct Planner {
     st.ops.push_back(nd.src);
     auto finish = [&](int, int out_tensor, bool is_conv) { st.v_out = out_view_for(out_tensor, is_conv); };
 
-    if (nd.kind == XENOS_OP_CONV || nd.kind == XENOS_OP_FC) {
+    {
       const bool is_fc = nd.kind == XENOS_OP_FC;
       const bool dw = !is_fc && d.groups != 1;
       const int K = d.out_c;
       if (dw && (d.groups != is.c || K != is.c)) return fail(XENOS_EUNSUPPORTED, "%s: only groups == 1 or depthwise (groups == C == out_c)", st.name.c_str());
       if (dw && is.c % p.ce != 0) return fail(XENOS_EUNSUPPORTED, "%s: depthwise channels must be a multiple of %d", st.name.c_str(), p.ce);
-      Affine af;
-      af.scale.assign(K, 1.0);
-      af.shift.assign(K, 0.0);
-      if (!go.bias.empty()) fold_bias(af, go.bias);
-      bool relu = false, has_res = false;
-      int res_tid = -1, pool_node = -1;
-      int cur = i + 1, stage = 0, last = i;
-      std::vector<int> absorbed;
-      while (link >= 1) {
-        const int nx = single_consumer(cur);
-        if (nx < 0 || placed.count(cur)) break;
-        const Node& nn_ = nodes[nx];
-        const GOp& ng = g.ops[nn_.src];
-        if ((nn_.kind == XENOS_OP_BIAS || nn_.kind == XENOS_OP_BN) && stage == 0) {
-          if (nn_.kind == XENOS_OP_BIAS) fold_bias(af, ng.bias); else fold_bn(af, ng);
-        } else if (nn_.kind == XENOS_OP_ADD && link >= 2 && !dw && stage <= 1) {
-          const int other = nn_.in[0] == cur ? nn_.in[1] : nn_.in[0];
-          if (other == cur || !available(other) || other == 0) break;
-          const View& ov = p.views[tview[other]];
-          if (!ov.internal_nhwc() || ov.f32) break;
-          has_res = true; res_tid = other; stage = 2;
-        } else if (nn_.kind == XENOS_OP_RELU && stage <= 2) {
-          relu = true; stage = 3;
-        } else if ((nn_.kind == XENOS_OP_MAXPOOL || nn_.kind == XENOS_OP_AVGPOOL || nn_.kind == XENOS_OP_GLOBAL_AVGPOOL) &&
-                   link >= 2 && !dw && (!has_res || nn_.kind == XENOS_OP_GLOBAL_AVGPOOL) && stage <= 3) {
-          pool_node = nx; stage = 4;
-        } else {
-          break;
-        }
-        absorbed.push_back(nx);
-        cur = nx + 1; last = nx;
-        if (stage == 4) break;
-      }
+      ChainWalk walk = walk_chain(i);
+      Affine& af = walk.af;
+      bool relu = walk.relu, has_res = walk.has_res;
+      int res_tid = walk.res_tid, pool_node = walk.pool_node;
+      int cur = walk.cur, last = walk.last;
+      std::vector<int>& absorbed = walk.absorbed;
+      (void)res_tid;
       // A first layer that can read the graph input in place (stem kernel) does so; that kernel has no pooling
       // epilogue, so a pooling that follows it runs as its own pass over the (NHWC, compute-type) result.  Measured
       // on the 7x7/2 + 3x3/2-pool and 3x3/2 + 3x3/2-pool first layers, the two passes take about a third of the time
@@ -1084,20 +1202,16 @@ struct Planner {
           // Every workgroup of the pointwise chain recomputes the depthwise result of its 64 pixels for all input
           // channels; beyond 32 channel groups per pixel (8 pixels per thread) that serial work costs more than the
           // saved pass (measured on MobileNet, batch 1: pairs up to 256 channels gain 5-11 us each, wider ones lose 6).
+          // (and a pointwise convolution that will hand its own output to the NEXT depthwise convolution on chip keeps this
+          // one out: the stack then runs as pointwise -> depthwise chains, see pwdw_wanted)
+          const int next_dw = pwdw_consumer(pw);
           if (pd.groups == 1 && pd.kh == 1 && pd.kw == 1 && pd.stride_h == 1 && pd.pad_h == 0 && node_step[pw] < 0 && p.opts.tile == 0 &&
-              is.c / p.ce <= 32) {
+              is.c / p.ce <= 32 && !(next_dw >= 0 && pwdw_wanted(pw, next_dw))) {
             const int taps = d.kh * d.kw;
             const size_t bytes = (size_t)taps * is.c * p.esz;
             dwpro = DwPro{};
             dwpro.active = true; dwpro.v_in = vin; dwpro.ops = st.ops;
-            dwpro.w_off = (long long)wpush(nullptr, bytes);
-            unsigned char* base = p.wimage.data() + dwpro.w_off;
-            for (int c = 0; c < is.c; ++c)
-              for (int t = 0; t < taps; ++t) {
-                const float v = go.weight[(size_t)c * taps + t];
-                if (p.dt == DT_BF16) ((uint16_t*)base)[(size_t)t * is.c + c] = f2bf_host(v);
-                else ((float*)base)[(size_t)t * is.c + c] = v;
-              }
+            dwpro.w_off = pack_depthwise(go, is.c, taps);
             push_affine(af, is.c, &dwpro.scale_off, &dwpro.shift_off);
             dwpro.k = d.kh; dwpro.stride = d.stride_h; dwpro.pad = d.pad_h; dwpro.H = is.h; dwpro.W = is.w; dwpro.relu = relu;
             dwpro.flops = 2.0 * is.n * tshape[i + 1].h * tshape[i + 1].w * is.c * taps;
@@ -1122,18 +1236,19 @@ struct Planner {
         // weights [R*S][C]
         const int taps = d.kh * d.kw;
         const size_t bytes = (size_t)taps * is.c * p.esz;
-        st.w_off = (long long)wpush(nullptr, bytes);
-        unsigned char* base = p.wimage.data() + st.w_off;
-        for (int c = 0; c < is.c; ++c)
-          for (int t = 0; t < taps; ++t) {
-            const float v = go.weight[(size_t)c * taps + t];
-            if (p.dt == DT_BF16) ((uint16_t*)base)[(size_t)t * is.c + c] = f2bf_host(v);
-            else ((float*)base)[(size_t)t * is.c + c] = v;
-          }
+        st.w_off = pack_depthwise(go, is.c, taps);
         push_affine(af, is.c, &st.scale_off, &st.shift_off);
         st.flops = 2.0 * a.N * a.OH * a.OW * a.C * taps;
         st.bytes_in = view_bytes(st.v_in); st.bytes_w = (long long)bytes; st.bytes_out = view_bytes(st.v_out);
       } else {
+        if (!dwpro.active && !pairpro.active && !is_fc && !stem) {
+          const int dn = pwdw_consumer(i);
+          if (dn >= 0 && pwdw_wanted(i, dn)) {
+            const View& iv0 = p.views[tview[nd.in[0]]];
+            if (iv0.internal_nhwc() && !iv0.f32 && iv0.esz == p.esz && iv0.off % p.ce == 0 && iv0.sP % p.ce == 0 && iv0.sN % p.ce == 0)
+              return plan_pwdw(i, walk, dn);
+          }
+        }
         st.kind = S_CONV;
         const bool from_dw = dwpro.active;
         const DwPro pro = dwpro;
@@ -1363,8 +1478,71 @@ struct Planner {
       add_step(st);
       return XENOS_OK;
     }
+  }
 
-    // ---- stand-alone operators ---------------------------------------------------------------
+  // ---- pointwise chain -> depthwise chain as ONE step (pwdw_kernel); the checks are pwdw_consumer's ---------------
+  xenos_status plan_pwdw(int i, const ChainWalk& w1, int dn) {
+    const Node& nd = nodes[i];
+    const GOp& go = g.ops[nd.src];
+    const Node& dnode = nodes[dn];
+    const xenos_op_desc& dd = desc(dnode);
+    const Shape is = tshape[nd.in[0]], os = tshape[dn + 1];
+    const int K = desc(nd).out_c;
+    const ChainWalk w2 = walk_chain(dn);
+    Step st;
+    st.kind = S_CONV;
+    st.name = std::string("op") + std::to_string(nd.src);
+    st.ops.push_back(nd.src);
+    for (int a : w1.absorbed) st.ops.push_back(nodes[a].src);
+    st.ops.push_back(dnode.src);
+    for (int a : w2.absorbed) st.ops.push_back(nodes[a].src);
+    st.v_in = tview[nd.in[0]];
+    const View& iv = p.views[st.v_in];
+    ConvArgs& a = st.conv;
+    a.N = is.n; a.C = std::max(is.c, iv.cphys); a.H = is.h; a.W = is.w; a.K = K;   // (padding channels multiply zero weights)
+    a.R = 1; a.S = 1; a.stride = 1; a.pad = 0; a.OH = os.h; a.OW = os.w; a.PH = os.h; a.PW = os.w;
+    a.in_sN = iv.sN; a.in_sH = iv.sP * is.w; a.in_sW = iv.sP;
+    a.relu = w1.relu; a.mode = M_FLAT; a.pool = POOL_NONE;
+    a.pwdw = 1; a.dw_k = 3; a.dw_stride = dd.stride_h; a.dw_pad = 1; a.dw_relu = w2.relu; a.dw_H = is.h; a.dw_W = is.w;
+    a.M_total = a.N * a.OH * a.OW;
+    pack_dense(st, go, is.c, a.C, 1, 1, K);
+    push_affine(w1.af, (K + 127) / 128 * 128, &st.scale_off, &st.shift_off);
+    st.dw_w_off = pack_depthwise(g.ops[dnode.src], K, 9);
+    push_affine(w2.af, (K + 63) / 64 * 64, &st.dw_scale_off, &st.dw_shift_off);
+    st.v_out = out_view_for(w2.cur, true);
+    const View& ov = p.views[st.v_out];
+    a.out_sN = ov.sN; a.out_sP = ov.sP; a.out_sK = ov.sK; a.out_f32 = ov.f32;
+    a.vec_out = ov.sK == 1 && !ov.f32 && ov.esz == p.esz && ov.off % p.ce == 0 && ov.sP % p.ce == 0 && ov.sN % p.ce == 0;
+    if (!a.vec_out) return fail(XENOS_EUNSUPPORTED, "%s: output of the pointwise -> depthwise chain is not aligned", st.name.c_str());
+    if (!choose_pwdw_tile(a)) return fail(XENOS_EUNSUPPORTED, "%s: no tile of the pointwise -> depthwise kernel fits", st.name.c_str());
+    a.tiles_m = a.N * a.tiles_y * a.tiles_x;
+    a.tiles_n = (K + kPwDwChannels - 1) / kPwDwChannels;
+    a.ntiles = a.tiles_m * a.tiles_n;
+    a.xcd_m = 8;
+    a.grid = p.opts.split ? std::max(1, std::min(a.ntiles, 4 * std::max(1, p.hw.num_cu))) : 1;
+    st.cfg = kPwDwCfg;
+    st.lds = pwdw_lds_bytes(a.th, a.tw, a.dw_stride, p.esz);
+    st.flops = 2.0 * is.n * is.h * is.w * (double)K * is.c + 2.0 * os.n * os.h * os.w * (double)K * 9;
+    st.bytes_w += (long long)9 * K * p.esz;
+    st.bytes_in = view_bytes(st.v_in); st.bytes_out = view_bytes(st.v_out);
+    const int sidx = (int)p.steps.size();
+    node_step[i] = sidx; node_step[dn] = sidx;
+    for (int ab : w1.absorbed) node_step[ab] = sidx;
+    for (int ab : w2.absorbed) node_step[ab] = sidx;
+    node_final[w2.last] = 1;
+    add_step(st);
+    return XENOS_OK;
+  }
+
+  // ---- stand-alone operators: whatever the link pass did not absorb into a convolution chain ---------------------
+  xenos_status plan_standalone(int i) {
+    const Node& nd = nodes[i];
+    const xenos_op_desc& d = desc(nd);
+    const GOp& go = g.ops[nd.src];
+    const Shape is = tshape[nd.in[0]];
+    Step st;
+    st.name = std::string("op") + std::to_string(nd.src);
+    st.ops.push_back(nd.src);
     if (nd.kind == XENOS_OP_CONCAT && free_concat[i]) {
       out_view_for(i + 1, false);          // the buffer exists; producers write their slices into it
       node_step[i] = std::max(0, (int)p.steps.size() - 1);
@@ -1613,11 +1791,12 @@ void write_plan_json(xenos_plan& p) {
       const TileCfg pair_tc{kPairRows, kPairChannels, 64, kPairChannels / 2};
       const TileCfg fc_tc{32, kFcChannels, 32, 32};
       const TileCfg stem_lds_tc{kStemLdsTh * kStemLdsTw, c.K, 32, c.K};
-      const TileCfg& tc = s.cfg == kHaloCfg ? halo_tc : s.cfg == kStemCfg ? stem_tc : s.cfg == kStemLdsCfg ? stem_lds_tc : s.cfg == kPairCfg ? pair_tc : s.cfg == kFcCfg ? fc_tc : kTileCfgs[s.cfg];
+      const TileCfg pwdw_tc{64, kPwDwChannels, 32, 32};
+      const TileCfg& tc = s.cfg == kPwDwCfg ? pwdw_tc : s.cfg == kHaloCfg ? halo_tc : s.cfg == kStemCfg ? stem_tc : s.cfg == kStemLdsCfg ? stem_lds_tc : s.cfg == kPairCfg ? pair_tc : s.cfg == kFcCfg ? fc_tc : kTileCfgs[s.cfg];
       snprintf(buf, sizeof buf, ",\"mode\":\"%s\",\"loader\":\"%s\",\"N\":%d,\"C\":%d,\"H\":%d,\"W\":%d,\"K\":%d,\"R\":%d,\"S\":%d,\"stride\":%d,"
                "\"pad\":%d,\"OH\":%d,\"OW\":%d,\"PH\":%d,\"PW\":%d,\"pool\":%d,\"relu\":%d,\"res\":%d,\"bm\":%d,\"bn\":%d,\"tiles_m\":%d,"
                "\"tiles_n\":%d,\"grid\":%d,\"lds\":%zu,\"pph\":%d,\"ppw\":%d,\"patch_h\":%d,\"patch_w\":%d,\"out_c_off\":%lld,\"out_sP\":%lld,\"halo\":%d,\"th\":%d,\"tw\":%d,\"dw_linked\":%d,\"ksplit\":%d,\"candidates\":%d,\"tuned\":%d,\"plin\":%d,\"shuffle_store\":%d",
-               kModeNames[c.mode], s.stem ? "stem" : c.pair ? "pair" : s.fc_stream ? "stream" : s.scalar ? "scalar" : "vector", c.N, c.C, c.H, c.W, c.K, c.R, c.S, c.stride, c.pad, c.OH, c.OW,
+               kModeNames[c.mode], s.stem ? "stem" : c.pair ? "pair" : c.pwdw ? "pwdw" : s.fc_stream ? "stream" : s.scalar ? "scalar" : "vector", c.N, c.C, c.H, c.W, c.K, c.R, c.S, c.stride, c.pad, c.OH, c.OW,
                c.PH, c.PW, c.pool, c.relu, c.has_res, tc.bm, tc.bn, c.tiles_m, c.tiles_n, c.grid, s.lds, c.pph, c.ppw, c.patch_h,
                c.patch_w, p.views[s.v_out].off, c.out_sP, s.cfg == kHaloCfg ? 1 : 0, c.th, c.tw, s.dw_w_off >= 0 ? 1 : 0, c.ksplit > 1 ? c.ksplit : 1, (int)s.cands.size(), s.tuned, s.cfg == kHaloCfg ? c.halo_plin : 0, c.ileave);
       j += buf;

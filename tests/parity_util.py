@@ -234,7 +234,7 @@ def teacher_forced(g, sess, compute, acts=None):
         label = ch["kind"]
         if ch["kind"] == "conv":
             label = "halo" if ch.get("halo") else ch.get("loader", "conv")
-            if ch.get("dw_linked") and label not in ("stem", "pair"):
+            if ch.get("dw_linked") and label not in ("stem", "pair", "pwdw"):
                 label = "dw+" + label
         elif ch["kind"] == "splitk_finish":
             label = pending + ".sum"                  # the summing pass completes the chain of the step before it

@@ -305,3 +305,73 @@ def test_partition_candidates_and_tune_argument_checks():
     finally:
         X.xenos_destroy(P)
         X.xenos_destroy(G)
+
+
+# ------------------------------------------------------------------------------------------ link level 3, one test per pattern
+def _kinds(g, c):
+    return [g.ops[o].kind for o in c["ops"]]
+
+
+def test_pattern_pointwise_to_depthwise_on_chip():
+    # Section 2.2 / Table 1 (ConvX -> ConvY): a depthwise-separable stack becomes pointwise -> depthwise chains, the
+    # tensors that reach memory are the (smaller) depthwise outputs
+    g = wg.build(1, 1, draw=False)
+    for compute in (X.XENOS_BF16, X.XENOS_F32):
+        l2 = plan_json(g, link=2, compute=compute)["plan"]
+        l3 = plan_json(g, link=3, compute=compute)["plan"]
+        pw = [c for c in l3["chains"] if c.get("loader") == "pwdw"]
+        assert len(pw) == 12 and l3["n_chains"] <= l2["n_chains"] - 12
+        for c in pw:
+            assert _kinds(g, c) == ["conv", "bn", "relu", "conv", "bn", "relu"]
+            conv1, conv2 = [o for o in c["ops"] if g.ops[o].kind == "conv"]
+            assert g.ops[conv1].attrs["groups"] == 1 and g.ops[conv2].attrs["groups"] == c["K"]
+            s = g.ops[conv2].attrs["stride"]
+            # tiles of depthwise output pixels cover the output; the staged block of the pointwise output fits the kernel's LDS block
+            assert c["tiles_m"] == c["N"] * -(-c["OH"] // c["th"]) * -(-c["OW"] // c["tw"]) and c["tiles_n"] == -(-c["K"] // 64)
+            assert ((c["th"] - 1) * s + 3) * ((c["tw"] - 1) * s + 3) <= 400 and c["lds"] <= 160 * 1024
+            assert c["out"]["c"] == c["K"] and c["out"]["h"] == c["OH"]
+        # only the first depthwise convolution (its producer is the 3x3 first layer) runs as a chain of its own
+        assert sum(c["kind"] == "dwconv" for c in l3["chains"]) == 1
+        assert l3["hbm_bytes"] < 0.66 * l2["hbm_bytes"]
+    assert all(c.get("loader") != "pwdw" for c in l2["chains"])
+
+
+def test_pattern_depthwise_to_pointwise_on_chip():
+    # a depthwise convolution whose pointwise consumer ends the cascade keeps the older link: its result is the
+    # operand panel of the pointwise GEMM (ShuffleNet units of the first two stages; the third, 352 channels, is too
+    # wide for that kernel and links pointwise -> depthwise instead)
+    g = wg.build(5, 1, draw=False)
+    l3 = plan_json(g, link=3, compute=X.XENOS_BF16)["plan"]
+    dwpw = [c for c in l3["chains"] if c.get("dw_linked") and c.get("loader") == "vector"]
+    pwdw = [c for c in l3["chains"] if c.get("loader") == "pwdw"]
+    assert len(dwpw) >= 12 and len(pwdw) == 4
+    for c in dwpw:
+        k = _kinds(g, c)
+        assert k[0] == "conv" and g.ops[c["ops"][0]].attrs["groups"] > 1 and k.count("conv") == 2
+    for c in pwdw:
+        assert c["K"] == 352 and _kinds(g, c).count("conv") == 2
+
+
+def test_pattern_first_layer_pair_on_chip():
+    g = wg.build(3, 2, draw=False)
+    l3 = plan_json(g, link=3, compute=X.XENOS_BF16)["plan"]
+    c0 = l3["chains"][0]
+    assert c0["loader"] == "pair" and _kinds(g, c0) == ["conv", "relu", "conv", "relu", "maxpool"] and c0["in"]["mem"] == "input"
+    assert plan_json(g, link=3, compute=X.XENOS_F32)["plan"]["chains"][0]["loader"] == "stem"   # the pair kernel is bf16 only
+
+
+def test_plan_metadata_names_the_graph_tensor_of_every_view():
+    # per-chain checks rely on it: every chain's input / output view says which graph tensor (and channel range) it holds
+    for cfg in (1, 2, 4, 5):
+        g = wg.build(cfg, 1, draw=False)
+        shapes = g.shapes()
+        for link in (0, 2, 3):
+            q = plan_json(g, link=link, compute=X.XENOS_BF16)["plan"]
+            for c in q["chains"]:
+                for key in ("in", "in2", "out"):
+                    v = c.get(key)
+                    if v is None or v["tensor"] < 0:
+                        continue
+                    n, ch, h, w = shapes[v["tensor"]]
+                    assert (v["n"], v["h"], v["w"]) == (n, h, w) and v["c0"] + (v["c"] - 1) * v["cs"] < ch, (cfg, link, c["name"], key, v)
+            assert q["chains"][-1]["out"]["tensor"] == g.output and q["chains"][-1]["out"]["mem"] == "output"

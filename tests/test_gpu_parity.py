@@ -11,7 +11,7 @@ from parity_util import (TOL, TOL_CHAIN, TOL_CHAIN_TWO_ROUNDINGS, bf16_rne, cach
                          rounded_graph, teacher_forced)
 
 # kernels that keep a bf16-rounded intermediate tensor on chip (two convolutions in one chain)
-TWO_ROUNDINGS = ("pair", "dw+", "pw+dw", "fire")
+TWO_ROUNDINGS = ("pair", "dw+", "pwdw", "fire")
 
 pytestmark = pytest.mark.gpu
 
@@ -407,6 +407,50 @@ def test_depthwise_pointwise_linked_on_chip(stride, hw, c, k, tail, compute):
         assert np.abs(y3 - y3s).max() <= (4e-6 if compute == 0 else 1e-2) * np.abs(y3s).max()
     else:
         assert np.array_equal(y3, y3s)
+
+
+@pytest.mark.parametrize("compute", [0, 1])
+@pytest.mark.parametrize("stride,h,w,c,k,n,tail", [(1, 13, 13, 16, 24, 3, "pw"), (2, 13, 17, 32, 72, 2, "pw"), (1, 7, 7, 64, 136, 1, "gap"),
+                                                   (2, 30, 22, 24, 64, 2, "conv3"), (1, 28, 28, 8, 8, 1, "out"), (2, 9, 9, 40, 200, 5, "cat"),
+                                                   (1, 5, 40, 16, 320, 1, "pw"), (2, 4, 4, 16, 16, 2, "out")])
+def test_pointwise_depthwise_linked_on_chip(stride, h, w, c, k, n, tail, compute):
+    # link level 3, pointwise -> depthwise (Section 2.2): the 1x1 chain's output tile (+ the halo the 3x3 windows need)
+    # lives in LDS only and the depthwise chain runs out of it.  Odd sizes give clipped blocks at every border, k = 72 /
+    # 136 / 200 ragged channel tiles, stride 2 overlapping blocks; tails: another pointwise chain (which ends the
+    # cascade), a global average, a dense 3x3, the graph output (NHWC: stored in place), a concat slice.
+    b = wg.builder("pwdw", (n, c, h, w), 19, nonzero_bias=True)
+    x = b.cbr(0, c, 3, 1, 1, name="pre")                     # an internal NHWC tensor for the pointwise chain to read
+    t = b.cbr(x, k, 1, name="pw")
+    t = b.cbr(t, k, 3, stride, 1, groups=k, name="dw", relu=(tail != "gap"))
+    fmt = {}
+    if tail == "pw":
+        t = b.cbr(t, 24, 1, name="pw2")
+    elif tail == "gap":
+        t = b.gap(t)
+    elif tail == "conv3":
+        t = b.cbr(t, 16, 3, 1, 1, name="post")
+    elif tail == "cat":
+        u = b.cbr(b.cbr(x, 16, 1, name="side"), 16, 3, stride, 1, groups=16, name="sidedw")
+        t = b.cbr(b.concat([u, t]), 24, 1, name="post")
+    else:
+        fmt = dict(out_layout=1)
+    g = b.finish(t)
+    acts = xo.run_graph(g, keep="all")
+    ref = acts[g.output]
+    for cmp_fmt in ((dict(fmt, out_dtype=1),) if (fmt and compute == 1) else (fmt,)):
+        y3, i3 = check(g, ref, compute=compute, link=3, **cmp_fmt)
+        # (where the depthwise result feeds a pointwise chain that ends the cascade and has at most 256 channels, the older
+        # depthwise -> pointwise link takes the depthwise convolution instead)
+        want = 2 if tail == "cat" else 0 if (tail == "pw" and k <= 256) else 1
+        assert sum(1 for ch in i3["chains"] if ch.get("loader") == "pwdw") == want
+        assert not any(ch["kind"] == "dwconv" for ch in i3["chains"])
+        y3s, _ = run_gpu(g, compute=compute, link=3, split=0, **cmp_fmt)
+        assert np.array_equal(y3, y3s)                        # one workgroup walking every tile: same bits
+        y3m, _ = run_gpu(g, compute=compute, link=3, hw=dict(X_small=True), **cmp_fmt)
+        assert np.array_equal(y3, y3m)                        # 8 compute units: other tiles, persistent workgroups
+    y2, i2 = check(g, ref, compute=compute, link=2)
+    assert i3["n_chains"] < i2["n_chains"]
+    check_chains(g, compute, link=3)
 
 
 @pytest.mark.parametrize("compute", [0, 1])
