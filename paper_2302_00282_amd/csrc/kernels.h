@@ -58,6 +58,10 @@ static const int kStemLdsTh = 8, kStemLdsTw = 16, kStemLdsInMax = 784;   // (7 *
 // (+ halo) staged in LDS, at most kPwDwMaxPositions positions
 static const int kPwDwCfg = 9;
 static const int kPwDwChannels = 64, kPwDwMaxPositions = 400;
+// Configuration index of the kernel that runs a Fire module (squeeze 1x1 -> expand 1x1 || expand 3x3 -> concat [-> max-pooling])
+// as one chain: the squeeze output of a tile (+ halo, at most kFireMaxPositions positions, at most 64 channels) stays in LDS
+static const int kFireCfg = 10;
+static const int kFireMaxPositions = 400;
 static const int kFcWgPerCu = 1;
 static const int kFcDirectSteps = 16;   // reductions of at most this many 64-element steps are not shared out (no summing pass)    // workgroups per compute unit the reduction split of such a chain aims at
 static const int kPairChannels = 64, kPairRed = 48;
@@ -109,6 +113,15 @@ struct ConvArgs {
   // (dw_w [9][K], dw_scale / dw_shift [K], dw_stride, dw_pad = 1, dw_relu) runs out of it; H x W is the pointwise map,
   // OH x OW the depthwise output, th x tw the tile of depthwise output pixels, tiles_y x tiles_x the tile grid per image
   int pwdw;
+  // linked Fire module (fire_kernel): this 1x1 / stride 1 chain is the squeeze (K <= 64 channels); its output tile (+ halo)
+  // stays in LDS and two expand chains read it there: [0] 1x1, [1] 3x3 / pad 1.  fire_w: [E padded to 64][taps][K] in the
+  // compute type; fire_scale / fire_shift: folded epilogue, padded to 64; fire_out: where each part goes (NHWC view of the
+  // compute type: image stride fire_sN, pixel pitch fire_sP), after the linked max-pooling (pool, pk, ps, pp, PH, PW; tiles of
+  // pph x ppw windows) if there is one; th x tw = tile of output pixels otherwise; tiles_n = channel shares
+  int fire;
+  const void* fire_w[2]; const float* fire_scale[2]; const float* fire_shift[2];
+  void* fire_out[2]; long long fire_sN[2], fire_sP[2];
+  int fire_E[2], fire_relu[2];
   // reduction split across workgroups (ksplit >= 1, M_FLAT only; 0 = none): share z covers steps [z*steps_per_split, ...)
   // and writes raw fp32 sums to part[z][m][k] (row pitch part_ld); a splitk_finish pass completes the chain
   int ksplit, steps_per_split, part_ld;
@@ -187,5 +200,8 @@ size_t dwpw_lds_bytes(int panel_channels, int esz);   // LDS of the depthwise-pa
 // pointwise -> depthwise kernel (xenos_linked.hip)
 int launch_pwdw(const ConvArgs& a, int dtype, void* stream);
 size_t pwdw_lds_bytes(int th, int tw, int stride, int esz);
+// Fire-module kernel (xenos_linked.hip); conv_h x conv_w = conv-output pixels of a tile
+int launch_fire(const ConvArgs& a, int dtype, void* stream);
+size_t fire_lds_bytes(int conv_h, int conv_w, int S, int esz, int pooled);
 
 }  // namespace xenos

@@ -2343,6 +2343,10 @@ int launch_conv(const ConvArgs& a, int dtype, int cfg, int scalar_loader, void* 
     return launch_fc(a, dtype, st);
   }
   if (cfg == kStemLdsCfg) return launch_stem_lds(a, dtype, st);
+  if (cfg == kFireCfg || a.fire) {
+    if (cfg != kFireCfg || !a.fire || scalar_loader) return (int)hipErrorInvalidValue;
+    return launch_fire(a, dtype, st);
+  }
   if (cfg == kPwDwCfg || a.pwdw) {
     if (cfg != kPwDwCfg || !a.pwdw || scalar_loader) return (int)hipErrorInvalidValue;
     return launch_pwdw(a, dtype, st);

@@ -114,7 +114,9 @@ struct Step {
   std::vector<Cand> cands;
   int tuned = 0;               // chosen by measurement (xenos_plan_tune)
   int v_in = -1, v_in2 = -1, v_out = -1;
+  int v_out2 = -1;             // second output of a Fire-module chain (the 3x3 expand's part)
   long long w_off = -1, scale_off = -1, shift_off = -1, ktab_off = -1;   // byte offsets into the weight image
+  long long fire_w_off[2] = {-1, -1}, fire_scale_off[2] = {-1, -1}, fire_shift_off[2] = {-1, -1};   // expand chains of a Fire module
   long long dw_w_off = -1, dw_scale_off = -1, dw_shift_off = -1;        // linked depthwise producer, if any
   double flops = 0;
   long long bytes_in = 0, bytes_w = 0, bytes_out = 0, bytes_res = 0;
@@ -906,6 +908,7 @@ struct Planner {
     if (st.v_in >= 0) touch(st.v_in, idx);
     if (st.v_in2 >= 0) touch(st.v_in2, idx);
     if (st.v_out >= 0) touch(st.v_out, idx);
+    if (st.v_out2 >= 0) touch(st.v_out2, idx);
     p.steps.push_back(st);
   }
 
@@ -1088,6 +1091,177 @@ struct Planner {
     return best < 1e300;
   }
 
+  // ---- link level 3, Fire module (Table 1, Conv1x1 -> Conv3x3; Section 4.1 last paragraph) -----------------------
+  // squeeze = conv 1x1 / stride 1 / pad 0 with at most 64 output channels whose chain output is read by exactly two dense
+  // convolutions, one 1x1 / pad 0 and one 3x3 / pad 1 (stride 1), each a plain chain (bias / bn / relu) that may end in
+  // the SAME max-pooling of 2- or 3-wide windows at stride 2 without padding (the pooling the link pass moved in front
+  // of their concat); both outputs take 16-byte stores.
+  struct FireMatch { int e[2] = {-1, -1}; };
+  bool fire_consumers(int i, FireMatch* fm) const {
+    if (p.opts.link < 3 || p.opts.tile != 0 || node_step[i] >= 0) return false;
+    const Node& nd = nodes[i];
+    if (nd.kind != XENOS_OP_CONV || nd.in[0] == 0) return false;
+    const xenos_op_desc& d = desc(nd);
+    const Shape is = tshape[nd.in[0]];
+    const int S = d.out_c;
+    if (d.groups != 1 || d.kh != 1 || d.kw != 1 || d.stride_h != 1 || d.pad_h != 0 || is.c % p.ce != 0 || S > 64 || (S * p.esz) % 32 != 0) return false;
+    const ChainWalk w = walk_chain(i);
+    if (w.has_res || w.pool_node >= 0 || w.cur == out_tid || placed.count(w.cur) || fin.count(w.cur) || consumers[w.cur].size() != 2) return false;
+    int pool_src = -2;
+    for (int c : consumers[w.cur]) {
+      const Node& en = nodes[c];
+      if (en.kind != XENOS_OP_CONV || node_step[c] >= 0 || en.in[0] != w.cur) return false;
+      const xenos_op_desc& ed = desc(en);
+      if (ed.groups != 1 || ed.stride_h != 1 || ed.out_c % p.ce != 0) return false;
+      const int which = ed.kh == 1 && ed.kw == 1 && ed.pad_h == 0 ? 0 : ed.kh == 3 && ed.kw == 3 && ed.pad_h == 1 ? 1 : -1;
+      if (which < 0 || fm->e[which] >= 0) return false;
+      const ChainWalk we = walk_chain(c);
+      if (we.has_res || fin.count(we.cur)) return false;
+      int ps = -1;
+      if (we.pool_node >= 0) {
+        const xenos_op_desc& pd = desc(nodes[we.pool_node]);
+        if (pd.kind != XENOS_OP_MAXPOOL || pd.kh != pd.kw || (pd.kh != 2 && pd.kh != 3) || pd.stride_h != 2 || pd.pad_h != 0) return false;
+        ps = nodes[we.pool_node].src;
+      }
+      if (pool_src != -2 && ps != pool_src) return false;           // both parts pooled by the same operator, or neither
+      pool_src = ps;
+      auto pl = placed.find(we.cur);
+      if (pl != placed.end() && (pl->second.c_stride != 1 || pl->second.c_off % p.ce != 0)) return false;
+      if (we.cur == out_tid && !ext_is_internal(p.out)) return false;
+      fm->e[which] = c;
+    }
+    if (fm->e[0] < 0 || fm->e[1] < 0) return false;
+    const int pk = pool_src >= 0 ? g.ops[pool_src].d.kh : 0;
+    return fire_lds_bytes(pk ? pk : 1, pk ? pk : 1, S, p.esz, pk ? 1 : 0) <= std::min<size_t>(p.hw.lds_bytes_per_cu, 160 * 1024);
+  }
+
+  // Tile (output pixels, or pooling windows) and number of channel shares of a Fire-module chain.  A workgroup's cost:
+  // the squeeze GEMM of its clipped block (chunks of 64 positions x reduction steps) + for every expand tile of its share
+  // the chunks of 64 pixels x taps x k-groups; the longest workgroup queue decides, plus a term for the launch's traffic.
+  bool choose_fire_tile(ConvArgs& c) const {
+    const int num_cu = std::max(1, p.hw.num_cu);
+    const size_t lds_cap = std::min<size_t>(p.hw.lds_bytes_per_cu, 160 * 1024);
+    const bool pool = c.pool != POOL_NONE;
+    const int S = c.K, kgs = S * p.esz / 32, nsteps = c.Kred_pad / (kRowBytes / p.esz);
+    const int nt[2] = {(c.fire_E[0] + 63) / 64, (c.fire_E[1] + 63) / 64};
+    const int YH = pool ? c.PH : c.H, XW = pool ? c.PW : c.W;      // extent of the tile grid (windows or pixels)
+    double best = 1e300;
+    for (int th = 1; th <= YH; ++th)
+      for (int tw = 1; tw <= XW; ++tw) {
+        const int CH = pool ? (th - 1) * c.ps + c.pk : th, CW = pool ? (tw - 1) * c.ps + c.pk : tw;
+        if ((CH + 2) * (CW + 2) > kFireMaxPositions) break;
+        const size_t lds = fire_lds_bytes(CH, CW, S, p.esz, pool ? 1 : 0);
+        if (lds > lds_cap) break;
+        const int occ = 2 * lds <= lds_cap ? 2 : 1;
+        const int ty = (YH + th - 1) / th, tx = (XW + tw - 1) / tw;
+        const double px_chunks = (CH * CW + 63) / 64;
+        double sq_total = 0, sq_longest = 0;
+        for (int y = 0; y < ty; ++y) {
+          const int iy0 = (pool ? y * th * c.ps : y * th) - 1, hv = std::min(iy0 + CH + 2, c.H) - std::max(iy0, 0);
+          for (int x = 0; x < tx; ++x) {
+            const int ix0 = (pool ? x * tw * c.ps : x * tw) - 1, wv = std::min(ix0 + CW + 2, c.W) - std::max(ix0, 0);
+            const double cost = ((hv * wv + 63) / 64) * (double)nsteps * (kRowBytes / 32 + 2);
+            sq_total += cost; sq_longest = std::max(sq_longest, cost);
+          }
+        }
+        for (int shares = 1; shares <= std::max(nt[0], nt[1]); shares *= 2) {
+          // share z takes the expand tiles z, z + shares, ... of each part
+          double ex_total = 0, ex_longest = 0;
+          for (int z = 0; z < shares; ++z) {
+            double e = 0;
+            for (int wch = 0; wch < 2; ++wch) e += ((nt[wch] - z + shares - 1) / shares) * (px_chunks * ((wch ? 9 : 1) * kgs + 3) + 2);
+            ex_total += e; ex_longest = std::max(ex_longest, e);
+          }
+          const double all = ((double)shares * sq_total + (double)ty * tx * ex_total) * c.N;
+          const double longest = sq_longest + ex_longest + 2;
+          const double t = p.opts.split ? std::max(all / ((double)occ * num_cu), longest) + all / (8.0 * num_cu) : all;
+          if (t < best - 1e-9) {
+            best = t;
+            if (pool) { c.pph = th; c.ppw = tw; c.th = CH; c.tw = CW; } else { c.th = th; c.tw = tw; }
+            c.tiles_y = ty; c.tiles_x = tx; c.tiles_n = shares;
+          }
+        }
+      }
+    return best < 1e300;
+  }
+
+  xenos_status plan_fire(int i, const ChainWalk& w, const FireMatch& fm) {
+    const Node& nd = nodes[i];
+    const GOp& go = g.ops[nd.src];
+    const Shape is = tshape[nd.in[0]];
+    const int S = desc(nd).out_c;
+    Step st;
+    st.kind = S_CONV;
+    st.name = std::string("op") + std::to_string(nd.src);
+    st.ops.push_back(nd.src);
+    for (int ab : w.absorbed) st.ops.push_back(nodes[ab].src);
+    st.v_in = tview[nd.in[0]];
+    const View iv = p.views[st.v_in];
+    ConvArgs& a = st.conv;
+    a.N = is.n; a.C = std::max(is.c, iv.cphys); a.H = is.h; a.W = is.w; a.K = S;
+    a.R = 1; a.S = 1; a.stride = 1; a.pad = 0; a.OH = is.h; a.OW = is.w; a.PH = is.h; a.PW = is.w;
+    a.in_sN = iv.sN; a.in_sH = iv.sP * is.w; a.in_sW = iv.sP;
+    a.relu = w.relu; a.mode = M_FLAT; a.pool = POOL_NONE; a.fire = 1;
+    pack_dense(st, go, is.c, a.C, 1, 1, S);
+    push_affine(w.af, (S + 127) / 128 * 128, &st.scale_off, &st.shift_off);
+    const int sidx = (int)p.steps.size();
+    node_step[i] = sidx;
+    for (int ab : w.absorbed) node_step[ab] = sidx;
+    st.flops = 2.0 * is.n * is.h * is.w * (double)S * is.c;
+    for (int which = 0; which < 2; ++which) {
+      const int en = fm.e[which];
+      const GOp& eg = g.ops[nodes[en].src];
+      const int E = desc(nodes[en]).out_c, taps = which ? 9 : 1, Epad = (E + 63) / 64 * 64;
+      const ChainWalk we = walk_chain(en);
+      st.ops.push_back(nodes[en].src);
+      for (int ab : we.absorbed) st.ops.push_back(nodes[ab].src);
+      // weights [E][S][kh][kw] -> [E padded to 64][tap][S] in the compute type
+      const size_t bytes = (size_t)Epad * taps * S * p.esz;
+      st.fire_w_off[which] = (long long)wpush(nullptr, bytes);
+      unsigned char* base = p.wimage.data() + st.fire_w_off[which];
+      memset(base, 0, bytes);
+      for (int k = 0; k < E; ++k)
+        for (int c = 0; c < S; ++c)
+          for (int t = 0; t < taps; ++t) {
+            const float v = eg.weight[((size_t)k * S + c) * taps + t];
+            const size_t o = ((size_t)k * taps + t) * S + c;
+            if (p.dt == DT_BF16) ((uint16_t*)base)[o] = f2bf_host(v); else ((float*)base)[o] = v;
+          }
+      push_affine(we.af, Epad, &st.fire_scale_off[which], &st.fire_shift_off[which]);
+      a.fire_E[which] = E; a.fire_relu[which] = we.relu;
+      if (we.pool_node >= 0) {
+        const xenos_op_desc& pd = desc(nodes[we.pool_node]);
+        const Shape ps = tshape[we.pool_node + 1];
+        a.pool = POOL_MAX; a.pk = pd.kh; a.ps = pd.stride_h; a.pp = 0; a.PH = ps.h; a.PW = ps.w;
+      }
+      const int ov = out_view_for(we.cur, true);
+      if (which == 0) st.v_out = ov; else st.v_out2 = ov;
+      const View& o = p.views[ov];
+      if (o.sK != 1 || o.f32 || o.esz != p.esz || o.off % p.ce != 0 || o.sP % p.ce != 0 || o.sN % p.ce != 0)
+        return fail(XENOS_EUNSUPPORTED, "%s: output of the Fire-module chain is not aligned", st.name.c_str());
+      a.fire_sN[which] = o.sN; a.fire_sP[which] = o.sP;
+      if (which == 0) { a.out_sN = o.sN; a.out_sP = o.sP; a.out_sK = 1; a.vec_out = 1; }
+      node_step[en] = sidx;
+      for (int ab : we.absorbed) node_step[ab] = sidx;
+      node_final[we.last] = 1;
+      const Shape es = tshape[en + 1];
+      st.flops += 2.0 * es.n * es.h * es.w * (double)E * taps * S;
+      st.bytes_w += (long long)E * taps * S * p.esz;
+      st.bytes_out += view_bytes(ov);
+    }
+    if (!choose_fire_tile(a)) return fail(XENOS_EUNSUPPORTED, "%s: no tile of the Fire-module kernel fits", st.name.c_str());
+    a.M_total = a.N * a.H * a.W;
+    a.tiles_m = a.N * a.tiles_y * a.tiles_x;
+    a.ntiles = a.tiles_m * a.tiles_n;
+    a.xcd_m = 8;
+    a.grid = p.opts.split ? std::max(1, std::min(a.ntiles, 4 * std::max(1, p.hw.num_cu))) : 1;
+    st.cfg = kFireCfg;
+    st.lds = fire_lds_bytes(a.th, a.tw, S, p.esz, a.pool != POOL_NONE ? 1 : 0);
+    st.bytes_in = view_bytes(st.v_in);
+    add_step(st);
+    return XENOS_OK;
+  }
+
   xenos_status plan_node(int i) {
     const int k = nodes[i].kind;
     return k == XENOS_OP_CONV || k == XENOS_OP_FC ? plan_conv(i) : plan_standalone(i);
@@ -1242,6 +1416,12 @@ struct Planner {
         st.bytes_in = view_bytes(st.v_in); st.bytes_w = (long long)bytes; st.bytes_out = view_bytes(st.v_out);
       } else {
         if (!dwpro.active && !pairpro.active && !is_fc && !stem) {
+          FireMatch fm;
+          if (fire_consumers(i, &fm)) {
+            const View& iv0 = p.views[tview[nd.in[0]]];
+            if (iv0.internal_nhwc() && !iv0.f32 && iv0.esz == p.esz && iv0.off % p.ce == 0 && iv0.sP % p.ce == 0 && iv0.sN % p.ce == 0)
+              return plan_fire(i, walk, fm);
+          }
           const int dn = pwdw_consumer(i);
           if (dn >= 0 && pwdw_wanted(i, dn)) {
             const View& iv0 = p.views[tview[nd.in[0]]];
@@ -1792,11 +1972,11 @@ void write_plan_json(xenos_plan& p) {
       const TileCfg fc_tc{32, kFcChannels, 32, 32};
       const TileCfg stem_lds_tc{kStemLdsTh * kStemLdsTw, c.K, 32, c.K};
       const TileCfg pwdw_tc{64, kPwDwChannels, 32, 32};
-      const TileCfg& tc = s.cfg == kPwDwCfg ? pwdw_tc : s.cfg == kHaloCfg ? halo_tc : s.cfg == kStemCfg ? stem_tc : s.cfg == kStemLdsCfg ? stem_lds_tc : s.cfg == kPairCfg ? pair_tc : s.cfg == kFcCfg ? fc_tc : kTileCfgs[s.cfg];
+      const TileCfg& tc = s.cfg == kPwDwCfg || s.cfg == kFireCfg ? pwdw_tc : s.cfg == kHaloCfg ? halo_tc : s.cfg == kStemCfg ? stem_tc : s.cfg == kStemLdsCfg ? stem_lds_tc : s.cfg == kPairCfg ? pair_tc : s.cfg == kFcCfg ? fc_tc : kTileCfgs[s.cfg];
       snprintf(buf, sizeof buf, ",\"mode\":\"%s\",\"loader\":\"%s\",\"N\":%d,\"C\":%d,\"H\":%d,\"W\":%d,\"K\":%d,\"R\":%d,\"S\":%d,\"stride\":%d,"
                "\"pad\":%d,\"OH\":%d,\"OW\":%d,\"PH\":%d,\"PW\":%d,\"pool\":%d,\"relu\":%d,\"res\":%d,\"bm\":%d,\"bn\":%d,\"tiles_m\":%d,"
                "\"tiles_n\":%d,\"grid\":%d,\"lds\":%zu,\"pph\":%d,\"ppw\":%d,\"patch_h\":%d,\"patch_w\":%d,\"out_c_off\":%lld,\"out_sP\":%lld,\"halo\":%d,\"th\":%d,\"tw\":%d,\"dw_linked\":%d,\"ksplit\":%d,\"candidates\":%d,\"tuned\":%d,\"plin\":%d,\"shuffle_store\":%d",
-               kModeNames[c.mode], s.stem ? "stem" : c.pair ? "pair" : c.pwdw ? "pwdw" : s.fc_stream ? "stream" : s.scalar ? "scalar" : "vector", c.N, c.C, c.H, c.W, c.K, c.R, c.S, c.stride, c.pad, c.OH, c.OW,
+               kModeNames[c.mode], s.stem ? "stem" : c.pair ? "pair" : c.pwdw ? "pwdw" : c.fire ? "fire" : s.fc_stream ? "stream" : s.scalar ? "scalar" : "vector", c.N, c.C, c.H, c.W, c.K, c.R, c.S, c.stride, c.pad, c.OH, c.OW,
                c.PH, c.PW, c.pool, c.relu, c.has_res, tc.bm, tc.bn, c.tiles_m, c.tiles_n, c.grid, s.lds, c.pph, c.ppw, c.patch_h,
                c.patch_w, p.views[s.v_out].off, c.out_sP, s.cfg == kHaloCfg ? 1 : 0, c.th, c.tw, s.dw_w_off >= 0 ? 1 : 0, c.ksplit > 1 ? c.ksplit : 1, (int)s.cands.size(), s.tuned, s.cfg == kHaloCfg ? c.halo_plin : 0, c.ileave);
       j += buf;
@@ -1816,6 +1996,7 @@ void write_plan_json(xenos_plan& p) {
     view_json("in", s.v_in);
     view_json("in2", s.v_in2);
     view_json("out", s.v_out);
+    view_json("out2", s.v_out2);
     j += "}";
   }
   j += "]}";
@@ -1854,6 +2035,15 @@ xenos_status launch_step(xenos_plan& p, const Step& s, const void* d_in_, void* 
       a.dw_w = s.dw_w_off >= 0 ? (const void*)(wb + s.dw_w_off) : nullptr;
       a.dw_scale = s.dw_scale_off >= 0 ? (const float*)(wb + s.dw_scale_off) : nullptr;
       a.dw_shift = s.dw_shift_off >= 0 ? (const float*)(wb + s.dw_shift_off) : nullptr;
+      if (a.fire) {
+        for (int e = 0; e < 2; ++e) {
+          a.fire_w[e] = wb + s.fire_w_off[e];
+          a.fire_scale[e] = (const float*)(wb + s.fire_scale_off[e]);
+          a.fire_shift[e] = (const float*)(wb + s.fire_shift_off[e]);
+        }
+        a.fire_out[0] = a.out;
+        a.fire_out[1] = (void*)view_ptr(p, s.v_out2, mem);
+      }
       rc = launch_conv(a, p.dt, s.cfg, s.scalar, stream);
       break;
     }

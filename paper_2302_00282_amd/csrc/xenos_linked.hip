@@ -4,9 +4,111 @@
 //  pwdw_kernel   pointwise (1x1) convolution chain -> depthwise 3x3 convolution chain.  The pointwise output of a
 //                spatial tile plus the one-pixel halo the depthwise windows need lives in LDS only, written there by
 //                the GEMM epilogue in the [position][channel] order the depthwise stencil reads.
+//  fire_kernel   squeeze 1x1 -> { expand 1x1 || expand 3x3 } -> concat [-> max-pooling] (a Fire module) as one chain: the
+//                squeeze tile (+ halo) lives in LDS and is the pixel operand of both expand GEMMs.
 #include "device_common.h"
 
 namespace xenos {
+
+// ---------------------------------------------------------------------------------------------
+// 64 pixels x 64 output channels of a 1x1 / stride 1 convolution over all a.C input channels, shared by the kernels below.
+// `pixel(row)` gives the element offset of row's pixel in a.in (channel 0), or -1 for a row without a pixel (it
+// contributes zeros).  4 wavefronts as 2 x 2 of 32 pixels x 32 channels; operands double-buffered through registers and
+// the two LDS stages at s_op (2 * (64 + 64) * LDS_ROW bytes).  The GEMM is computed transposed: on return lane l of
+// wavefront (wave_m, wave_n) holds, for pixel row wave_m*32 + l%32, channels k_row0 + wave_n*32 + 8*g + 4*(l/32) + (0..3)
+// in acc[4*g .. 4*g+3].  Begins with a barrier-free write of stage 0 (the caller guarantees nobody still reads the
+// stages) and ends after a barrier (the stages are free again).
+// ---------------------------------------------------------------------------------------------
+constexpr int PG_BM = 64, PG_BN = 64;
+constexpr int PG_STAGES_BYTES = 2 * (PG_BM + PG_BN) * LDS_ROW;
+
+template <typename T, typename PixelFn>
+__device__ __forceinline__ void pw_gemm_chunk(const ConvArgs& a, int k_row0, unsigned char* s_op, PixelFn pixel, f32x16_t& acc) {
+  using tr = Tr<T>;
+  constexpr int CE = tr::CE, BKE = tr::BKE, ESZ = (int)sizeof(T);
+  constexpr int BM = PG_BM, BN = PG_BN;
+  constexpr int A_IT = BM * CPR / NT, B_IT = BN * CPR / NT;        // 16-byte chunks per thread and step
+  static_assert(A_IT >= 1 && B_IT >= 1, "loader shapes");
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wave_m = wave >> 1, wave_n = wave & 1;
+  const int l31 = lane & 31, lhalf = lane >> 5;
+  const int nsteps = a.Kred_pad / BKE;
+  long long abase[A_IT];
+  bool arow[A_IT];
+  const int ch = tid % CPR;
+#pragma unroll
+  for (int it = 0; it < A_IT; ++it) {
+    const long long off = pixel((tid + it * NT) / CPR);
+    arow[it] = off >= 0;
+    abase[it] = (arow[it] ? off : 0) + ch * CE;
+  }
+  const unsigned char* wrow[B_IT];
+#pragma unroll
+  for (int it = 0; it < B_IT; ++it) {
+    const int idx = tid + it * NT;
+    wrow[it] = (const unsigned char*)a.w + ((long long)(k_row0 + idx / CPR) * a.Kred_pad + (idx % CPR) * CE) * (long long)ESZ;
+  }
+#pragma unroll
+  for (int e = 0; e < 16; ++e) acc[e] = 0.f;
+  u32x4_t ra0[A_IT], rb0[B_IT], ra1[A_IT], rb1[B_IT];
+  auto load = [&](int step, u32x4_t* ra, u32x4_t* rb) {
+    const int ss = step < nsteps ? step : nsteps - 1;              // steps past the end re-read valid memory; never used
+    const int kc = ss * BKE + ch * CE;
+    const u32x4_t z = {0u, 0u, 0u, 0u};
+#pragma unroll
+    for (int it = 0; it < A_IT; ++it) {
+      const bool ok = arow[it] && kc < a.C;                        // channels beyond C are the padding of the reduction
+      const u32x4_t v = *(const u32x4_t*)((const T*)a.in + (ok ? abase[it] + ss * BKE : 0));
+      ra[it] = ok ? v : z;
+    }
+#pragma unroll
+    for (int it = 0; it < B_IT; ++it) rb[it] = *(const u32x4_t*)(wrow[it] + (long long)ss * ROWB);
+  };
+  auto store = [&](int stage, const u32x4_t* ra, const u32x4_t* rb) {
+    unsigned char* sa = s_op + stage * (BM + BN) * LDS_ROW;
+    unsigned char* sb = sa + BM * LDS_ROW;
+#pragma unroll
+    for (int it = 0; it < A_IT; ++it) {
+      const int idx = tid + it * NT;
+      *(u32x4_t*)(sa + (idx / CPR) * LDS_ROW + (idx % CPR) * 16) = ra[it];
+    }
+#pragma unroll
+    for (int it = 0; it < B_IT; ++it) {
+      const int idx = tid + it * NT;
+      *(u32x4_t*)(sb + (idx / CPR) * LDS_ROW + (idx % CPR) * 16) = rb[it];
+    }
+  };
+  auto compute = [&](int stage) {
+    const unsigned char* sa = s_op + stage * (BM + BN) * LDS_ROW + (wave_m * 32 + l31) * LDS_ROW + lhalf * 16;
+    const unsigned char* sb = s_op + stage * (BM + BN) * LDS_ROW + BM * LDS_ROW + (wave_n * 32 + l31) * LDS_ROW + lhalf * 16;
+#pragma unroll
+    for (int kg = 0; kg < KG; ++kg) {
+      const u32x4_t fa = *(const u32x4_t*)(sa + kg * 32), fb = *(const u32x4_t*)(sb + kg * 32);
+      if constexpr (sizeof(T) == 2) {
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, fb), __builtin_bit_cast(bf16x8_t, fa), acc, 0, 0, 0);
+      } else {
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+          acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(fb[e]), __uint_as_float(fa[e]), acc, 0, 0, 0);
+      }
+    }
+  };
+  load(0, ra0, rb0);
+  store(0, ra0, rb0);
+  load(1, ra1, rb1);
+  __syncthreads();                                                 // step 0 (and whatever the caller wrote before) is visible
+  for (int st = 0; st < nsteps; st += 2) {
+    load(st + 2, ra0, rb0);
+    compute(0);
+    store(1, ra1, rb1);
+    __syncthreads();
+    if (st + 1 >= nsteps) break;
+    load(st + 3, ra1, rb1);
+    compute(1);
+    store(0, ra0, rb0);
+    __syncthreads();
+  }
+}
 
 // ---------------------------------------------------------------------------------------------
 // Pointwise -> depthwise on chip.
@@ -35,8 +137,7 @@ __global__ __launch_bounds__(NT) void pwdw_kernel(const ConvArgs a) {
   constexpr int BM = PD_BM, BN = PD_BN;
   constexpr int MP = pwdw_mid_pitch(ESZ);
   constexpr int CG = BN / CE;                                      // 16-byte channel groups of a position
-  constexpr int A_IT = BM * CPR / NT, B_IT = BN * CPR / NT;        // 16-byte chunks per thread and step
-  static_assert(A_IT >= 1 && B_IT >= 1 && NT % CG == 0, "loader shapes");
+  static_assert(NT % CG == 0 && BM == PG_BM && BN == PG_BN, "loader shapes");
   extern __shared__ __align__(16) unsigned char smem[];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wave_m = wave >> 1, wave_n = wave & 1;
@@ -46,7 +147,6 @@ __global__ __launch_bounds__(NT) void pwdw_kernel(const ConvArgs a) {
   const int PH = (a.th - 1) * s + 3, PWd = (a.tw - 1) * s + 3;      // staged block of the pointwise output
   unsigned char* s_mid = smem;
   unsigned char* s_op = smem + PH * PWd * MP;
-  const int nsteps = a.Kred_pad / BKE;
   const int tiles_sp = a.tiles_y * a.tiles_x;
   const int cg = tid % CG;
 
@@ -74,84 +174,13 @@ __global__ __launch_bounds__(NT) void pwdw_kernel(const ConvArgs a) {
 
     for (int mc = 0; mc * BM < npos; ++mc) {
       // ---- pointwise GEMM of 64 block positions x 64 channels over all input channels ----------------
-      long long abase[A_IT];
-      bool arow[A_IT];
-      const int ch = tid % CPR;
-#pragma unroll
-      for (int it = 0; it < A_IT; ++it) {
-        const int m = mc * BM + (tid + it * NT) / CPR;
-        arow[it] = m < npos;
-        const int mm = arow[it] ? m : 0;
-        const int py = mm / wv, px = mm - py * wv;
-        abase[it] = (long long)n * a.in_sN + (long long)(y_lo + py) * a.in_sH + (long long)(x_lo + px) * a.in_sW + ch * CE;
-      }
-      const unsigned char* wrow[B_IT];
-#pragma unroll
-      for (int it = 0; it < B_IT; ++it) {
-        const int idx = tid + it * NT;
-        wrow[it] = (const unsigned char*)a.w + ((long long)(tile_n * BN + idx / CPR) * a.Kred_pad + (idx % CPR) * CE) * (long long)ESZ;
-      }
       f32x16_t acc;
-#pragma unroll
-      for (int e = 0; e < 16; ++e) acc[e] = 0.f;
-      u32x4_t ra0[A_IT], rb0[B_IT], ra1[A_IT], rb1[B_IT];
-      auto load = [&](int step, u32x4_t* ra, u32x4_t* rb) {
-        const int ss = step < nsteps ? step : nsteps - 1;          // steps past the end re-read valid memory; never used
-        const int kc = ss * BKE + ch * CE;
-        const u32x4_t z = {0u, 0u, 0u, 0u};
-#pragma unroll
-        for (int it = 0; it < A_IT; ++it) {
-          const bool ok = arow[it] && kc < a.C;                    // channels beyond C are the padding of the reduction
-          const u32x4_t v = *(const u32x4_t*)((const T*)a.in + (ok ? abase[it] + ss * BKE : 0));
-          ra[it] = ok ? v : z;
-        }
-#pragma unroll
-        for (int it = 0; it < B_IT; ++it) rb[it] = *(const u32x4_t*)(wrow[it] + (long long)ss * ROWB);
-      };
-      auto store = [&](int stage, const u32x4_t* ra, const u32x4_t* rb) {
-        unsigned char* sa = s_op + stage * (BM + BN) * LDS_ROW;
-        unsigned char* sb = sa + BM * LDS_ROW;
-#pragma unroll
-        for (int it = 0; it < A_IT; ++it) {
-          const int idx = tid + it * NT;
-          *(u32x4_t*)(sa + (idx / CPR) * LDS_ROW + (idx % CPR) * 16) = ra[it];
-        }
-#pragma unroll
-        for (int it = 0; it < B_IT; ++it) {
-          const int idx = tid + it * NT;
-          *(u32x4_t*)(sb + (idx / CPR) * LDS_ROW + (idx % CPR) * 16) = rb[it];
-        }
-      };
-      auto compute = [&](int stage) {
-        const unsigned char* sa = s_op + stage * (BM + BN) * LDS_ROW + (wave_m * 32 + l31) * LDS_ROW + lhalf * 16;
-        const unsigned char* sb = s_op + stage * (BM + BN) * LDS_ROW + BM * LDS_ROW + (wave_n * 32 + l31) * LDS_ROW + lhalf * 16;
-#pragma unroll
-        for (int kg = 0; kg < KG; ++kg) {
-          const u32x4_t fa = *(const u32x4_t*)(sa + kg * 32), fb = *(const u32x4_t*)(sb + kg * 32);
-          if constexpr (sizeof(T) == 2) {
-            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, fb), __builtin_bit_cast(bf16x8_t, fa), acc, 0, 0, 0);
-          } else {
-#pragma unroll
-            for (int e = 0; e < 4; ++e)
-              acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(fb[e]), __uint_as_float(fa[e]), acc, 0, 0, 0);
-          }
-        }
-      };
-      load(0, ra0, rb0);
-      store(0, ra0, rb0);
-      load(1, ra1, rb1);
-      __syncthreads();                                             // step 0 (and the zero fill of the block) is visible
-      for (int st = 0; st < nsteps; st += 2) {
-        load(st + 2, ra0, rb0);
-        compute(0);
-        store(1, ra1, rb1);
-        __syncthreads();
-        if (st + 1 >= nsteps) break;
-        load(st + 3, ra1, rb1);
-        compute(1);
-        store(0, ra0, rb0);
-        __syncthreads();
-      }
+      pw_gemm_chunk<T>(a, tile_n * BN, s_op, [&](int row) -> long long {
+        const int m = mc * BM + row;
+        if (m >= npos) return -1;
+        const int py = m / wv, px = m - py * wv;
+        return (long long)n * a.in_sN + (long long)(y_lo + py) * a.in_sH + (long long)(x_lo + px) * a.in_sW;
+      }, acc);
       // ---- the pointwise chain's epilogue, into the LDS block: lane = position wave_m*32 + l31, channels
       // wave_n*32 + 8*g + 4*lhalf + (0..3) ------------------------------------------------------------
       const int m = mc * BM + wave_m * 32 + l31;
@@ -248,6 +277,280 @@ int launch_pwdw(const ConvArgs& a, int dtype, void* stream) {
 
 size_t pwdw_lds_bytes(int th, int tw, int stride, int esz) {
   return (size_t)pwdw_lds(((th - 1) * stride + 3) * ((tw - 1) * stride + 3), esz);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Fire module on chip: squeeze 1x1 -> { expand 1x1  ||  expand 3x3 / pad 1 } -> channel concat [-> max-pooling] as ONE
+// chain (Table 1, Conv1x1 -> Conv3x3; Section 4.1, last paragraph: the consumer's halo is replicated per tile).
+//
+// The squeeze output has few channels (16 .. 64) and two readers; kept in LDS it is written once and never reaches
+// memory.  A workgroup owns a TH x TW tile of output pixels of one image and a share of the expand channels:
+//   phase 1  the squeeze chain (GEMM over all input channels + scale/shift + ReLU) for the (TH+2) x (TW+2) block of
+//            pixels the 3x3 windows cover, in chunks of 64 positions, into an LDS block [position][S channels] in the
+//            storage type; positions outside the map stay zero (the padding of the 3x3 convolution);
+//   phase 2  for each of its 64-channel expand tiles: the tile's weights (all taps) are copied to LDS once, then every
+//            chunk of 64 pixels runs its 1 or 9 taps as MFMAs whose pixel operand is read from the squeeze block at the
+//            tap's offset and whose weight operand from the resident tile: no barrier inside; the epilogue (scale/shift/
+//            ReLU) is per wavefront, staged through a private LDS slice and stored as 16-byte channel groups at the
+//            part's channel offset in the concat buffer (Eq. 1: the halves join without a layout pass).
+// With a linked 3x3 / stride 2 max-pooling (ceil mode; the planner hoists the pooling over the concat) the tile is PTH x
+// PTW pooling windows: the expand results of the (2 PTH + 1) x (2 PTW + 1) pixels they cover are staged per channel tile
+// in LDS and one thread per 16-byte channel group of a window takes the maximum.
+// Workgroups of different channel shares recompute the squeeze block of their tile.
+// ---------------------------------------------------------------------------------------------
+__host__ __device__ constexpr int fire_sq_pitch(int S, int esz) { return S * esz + 16; }
+__host__ __device__ constexpr int fire_w_pitch(int taps, int S, int esz) { return taps * S * esz + 16; }
+__host__ __device__ constexpr int fire_stg_pitch(int esz) { return 32 * esz + 16; }
+__host__ __device__ constexpr int fire_cb_pitch(int esz) { return 64 * esz + 16; }
+// LDS: squeeze block | max(GEMM stages, one 3x3 weight tile) | 4 per-wavefront staging slices | pooled form: conv block of a channel tile
+__host__ __device__ constexpr int fire_lds(int positions, int S, int esz, int pool_positions) {
+  return positions * fire_sq_pitch(S, esz) + cmax(PG_STAGES_BYTES, 64 * fire_w_pitch(9, S, esz)) + 4 * 32 * fire_stg_pitch(esz) +
+         pool_positions * fire_cb_pitch(esz);
+}
+
+template <typename T, bool POOL>
+__global__ __launch_bounds__(NT) void fire_kernel(const ConvArgs a) {
+  using tr = Tr<T>;
+  constexpr int CE = tr::CE, ESZ = (int)sizeof(T);
+  constexpr int STP = fire_stg_pitch(ESZ), CBP = fire_cb_pitch(ESZ);
+  constexpr int G = 32 * ESZ / 16;                                 // 16-byte channel groups of a wavefront's 32 channels
+  extern __shared__ __align__(16) unsigned char smem[];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wave_m = wave >> 1, wave_n = wave & 1;
+  const int l31 = lane & 31, lhalf = lane >> 5;
+
+  const int S = a.K;                                               // squeeze channels
+  const int SQP = fire_sq_pitch(S, ESZ);
+  const int kgs = S * ESZ / 32;                                    // MFMA k-groups per tap
+  // conv-output pixels of a tile: th x tw, or the block the tile's pooling windows cover
+  const int CH = POOL ? (a.pph - 1) * a.ps + a.pk : a.th, CW = POOL ? (a.ppw - 1) * a.ps + a.pk : a.tw;
+  const int PH = CH + 2, PWd = CW + 2;                             // squeeze block
+  unsigned char* s_sq = smem;
+  unsigned char* s_b = smem + PH * PWd * SQP;
+  const int bbytes = 64 * fire_w_pitch(9, S, ESZ);
+  unsigned char* s_stg = s_b + (bbytes > PG_STAGES_BYTES ? bbytes : PG_STAGES_BYTES) + wave * 32 * STP;
+  unsigned char* s_cb = s_b + (bbytes > PG_STAGES_BYTES ? bbytes : PG_STAGES_BYTES) + 4 * 32 * STP;   // POOL: [conv pixel][64 channels]
+  const int tiles_sp = a.tiles_y * a.tiles_x;
+  const int npix = CH * CW;
+
+  for (int t = blockIdx.x; t < a.ntiles; t += gridDim.x) {
+    const int gz = t / a.tiles_m, tm = t - gz * a.tiles_m;          // channel share, spatial tile
+    const int n = tm / tiles_sp, rr = tm - n * tiles_sp, ty = rr / a.tiles_x, tx = rr - ty * a.tiles_x;
+    // first conv-output pixel of the tile
+    const int oy0 = POOL ? ty * a.pph * a.ps - a.pp : ty * a.th, ox0 = POOL ? tx * a.ppw * a.ps - a.pp : tx * a.tw;
+    const int iy0 = oy0 - 1, ix0 = ox0 - 1;                        // map position of block position (0, 0)
+    const int y_lo = iy0 > 0 ? iy0 : 0, y_hi = iy0 + PH < a.H ? iy0 + PH : a.H;
+    const int x_lo = ix0 > 0 ? ix0 : 0, x_hi = ix0 + PWd < a.W ? ix0 + PWd : a.W;
+    const int hv = y_hi - y_lo, wv = x_hi - x_lo, npos = hv * wv;   // the part of the block inside the map (never empty)
+
+    if (hv < PH || wv < PWd) {
+      const u32x4_t z = {0u, 0u, 0u, 0u};
+      for (int i = tid; i < PH * PWd * (SQP / 16); i += NT) *(u32x4_t*)(s_sq + i * 16) = z;
+    }
+    // ---- phase 1: the squeeze chain of the block, into LDS -------------------------------------------------
+    for (int mc = 0; mc * 64 < npos; ++mc) {
+      f32x16_t acc;
+      pw_gemm_chunk<T>(a, 0, s_b, [&](int row) -> long long {
+        const int m = mc * 64 + row;
+        if (m >= npos) return -1;
+        const int py = m / wv, px = m - py * wv;
+        return (long long)n * a.in_sN + (long long)(y_lo + py) * a.in_sH + (long long)(x_lo + px) * a.in_sW;
+      }, acc);
+      const int m = mc * 64 + wave_m * 32 + l31;
+      if (m < npos) {
+        const int py = m / wv, px = m - py * wv;
+        unsigned char* dst = s_sq + ((y_lo + py - iy0) * PWd + (x_lo + px - ix0)) * SQP;
+        const float lo = a.relu ? 0.f : -3.4028235e38f;
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const int c = wave_n * 32 + g * 8 + lhalf * 4;
+          if (c < S) {
+            const f32x4_t sc = *(const f32x4_t*)(a.scale + c), sh = *(const f32x4_t*)(a.shift + c);
+            float y[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) y[e] = fmx(acc[4 * g + e] * sc[e] + sh[e], lo);
+            if constexpr (sizeof(T) == 2) {
+              uint2 o;
+              o.x = f2bf2(y[0], y[1]);
+              o.y = f2bf2(y[2], y[3]);
+              *(uint2*)(dst + c * 2) = o;
+            } else {
+              *(f32x4_t*)(dst + c * 4) = f32x4_t{y[0], y[1], y[2], y[3]};
+            }
+          }
+        }
+      }
+    }
+    __syncthreads();                                               // the block is complete, the GEMM stages are free
+
+    // ---- phase 2: this workgroup's expand tiles -----------------------------------------------------------
+#pragma unroll 1
+    for (int which = 0; which < 2; ++which) {                      // 0: the 1x1 expand, 1: the 3x3 expand
+      const int taps = which ? 9 : 1, E = a.fire_E[which];
+      const int WP = fire_w_pitch(taps, S, ESZ), wrow_b = taps * S * ESZ;   // LDS pitch and bytes of a channel's weights
+      const float lo = a.fire_relu[which] ? 0.f : -3.4028235e38f;
+#pragma unroll 1
+      for (int j = gz; j * 64 < E; j += a.tiles_n) {
+        {   // the tile's weights: 64 channels x taps x S, contiguous in memory (rows beyond E are zero)
+          const unsigned char* src = (const unsigned char*)a.fire_w[which] + (long long)j * 64 * wrow_b;
+          const int cpr = wrow_b / 16;
+          for (int idx = tid; idx < 64 * cpr; idx += NT) {
+            const int row = idx / cpr, c = idx - row * cpr;
+            *(u32x4_t*)(s_b + row * WP + c * 16) = *(const u32x4_t*)(src + (long long)row * wrow_b + c * 16);
+          }
+        }
+        __syncthreads();
+#pragma unroll 1
+        for (int mc = 0; mc * 64 < npix; ++mc) {
+          const int m = mc * 64 + wave_m * 32 + l31;
+          const int mm = m < npix ? m : 0;
+          const int py = mm / CW, px = mm - py * CW;
+          // block position of the pixel's first tap: the 1x1 expand reads the pixel itself, the 3x3 its window
+          const unsigned char* pa = s_sq + ((py + (which ? 0 : 1)) * PWd + px + (which ? 0 : 1)) * SQP + lhalf * 16;
+          const unsigned char* pb = s_b + (wave_n * 32 + l31) * WP + lhalf * 16;
+          f32x16_t acc;
+#pragma unroll
+          for (int e = 0; e < 16; ++e) acc[e] = 0.f;
+#pragma unroll 1
+          for (int tap = 0; tap < taps; ++tap) {
+            const unsigned char* ta = pa + ((tap / 3) * PWd + tap % 3) * SQP;
+            const unsigned char* tb = pb + tap * S * ESZ;
+            for (int kg = 0; kg < kgs; ++kg) {
+              const u32x4_t fa = *(const u32x4_t*)(ta + kg * 32), fb = *(const u32x4_t*)(tb + kg * 32);
+              if constexpr (sizeof(T) == 2) {
+                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, fb), __builtin_bit_cast(bf16x8_t, fa), acc, 0, 0, 0);
+              } else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                  acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(fb[e]), __uint_as_float(fa[e]), acc, 0, 0, 0);
+              }
+            }
+          }
+          // epilogue of the wavefront's 32 pixels x 32 channels: finished values change hands inside the wavefront only
+#pragma unroll
+          for (int g = 0; g < 4; ++g) {
+            const int c = g * 8 + lhalf * 4, kk = j * 64 + wave_n * 32 + c;
+            const f32x4_t sc = *(const f32x4_t*)(a.fire_scale[which] + kk), sh = *(const f32x4_t*)(a.fire_shift[which] + kk);
+            float y[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) y[e] = fmx(acc[4 * g + e] * sc[e] + sh[e], lo);
+            if constexpr (sizeof(T) == 2) {
+              uint2 o;
+              o.x = f2bf2(y[0], y[1]);
+              o.y = f2bf2(y[2], y[3]);
+              *(uint2*)(s_stg + l31 * STP + c * 2) = o;
+            } else {
+              *(u32x4_t*)(s_stg + l31 * STP + c * 4) = u32x4_t{__float_as_uint(y[0]), __float_as_uint(y[1]), __float_as_uint(y[2]), __float_as_uint(y[3])};
+            }
+          }
+#pragma unroll
+          for (int u = 0; u < 32 * G / 64; ++u) {
+            const int idx = lane + u * 64, r = idx / G, cg = idx - r * G;
+            const int mr = mc * 64 + wave_m * 32 + r;
+            const int k0 = j * 64 + wave_n * 32 + cg * CE;
+            u32x4_t v;
+            if constexpr (sizeof(T) == 2) {
+              const uint2 lo8 = *(const uint2*)(s_stg + r * STP + cg * 16), hi8 = *(const uint2*)(s_stg + r * STP + cg * 16 + 8);
+              v = u32x4_t{lo8.x, lo8.y, hi8.x, hi8.y};
+            } else {
+              v = *(const u32x4_t*)(s_stg + r * STP + cg * 16);
+            }
+            if (mr < npix && k0 < E) {
+              const int qy = mr / CW, qx = mr - qy * CW;
+              if constexpr (POOL) {
+                *(u32x4_t*)(s_cb + mr * CBP + (wave_n * 32 + cg * CE) * ESZ) = v;
+              } else {
+                const int oy = oy0 + qy, ox = ox0 + qx;
+                if (oy < a.H && ox < a.W)
+                  *(u32x4_t*)((T*)a.fire_out[which] + (long long)n * a.fire_sN[which] + (long long)(oy * a.W + ox) * a.fire_sP[which] + k0) = v;
+              }
+            }
+          }
+        }
+        if constexpr (POOL) {
+          __syncthreads();                                         // the conv block of this channel tile is complete
+          // one thread = one 16-byte channel group of one pooling window; windows are clipped to the map (never empty)
+          constexpr int CG = 64 / CE;
+          for (int idx = tid; idx < a.pph * a.ppw * CG; idx += NT) {
+            const int q = idx / CG, cg = idx - q * CG, k0 = j * 64 + cg * CE;
+            const int qy = q / a.ppw, qx = q - qy * a.ppw;
+            const int gy = ty * a.pph + qy, gx = tx * a.ppw + qx;
+            if (gy >= a.PH || gx >= a.PW || k0 >= E) continue;
+            float mx[CE];
+#pragma unroll
+            for (int e = 0; e < CE; ++e) mx[e] = -INFINITY;
+            for (int r = 0; r < a.pk; ++r)
+              for (int c = 0; c < a.pk; ++c) {
+                const int cy = qy * a.ps + r, cx = qx * a.ps + c;
+                const int oy = oy0 + cy, ox = ox0 + cx;
+                if (oy < 0 || oy >= a.H || ox < 0 || ox >= a.W) continue;
+                float x[CE];
+                tr::unpack(*(const u32x4_t*)(s_cb + (cy * CW + cx) * CBP + cg * 16), x);
+#pragma unroll
+                for (int e = 0; e < CE; ++e) mx[e] = fmx_raw(mx[e], x[e]);
+              }
+            *(u32x4_t*)((T*)a.fire_out[which] + (long long)n * a.fire_sN[which] + (long long)(gy * a.PW + gx) * a.fire_sP[which] + k0) = tr::pack(mx);
+          }
+        }
+        __syncthreads();                                           // the weight tile (and the conv block) are rewritten
+      }
+    }
+  }
+}
+
+template <typename T, bool POOL>
+static int launch_fire_inst(const ConvArgs& a, int lds, hipStream_t st) {
+  static int raised = 0;
+  if (lds > raised) {
+    hipError_t e = hipFuncSetAttribute((const void*)fire_kernel<T, POOL>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    if (e != hipSuccess) return (int)e;
+    raised = lds;
+  }
+  hipLaunchKernelGGL((fire_kernel<T, POOL>), dim3(a.grid < a.ntiles ? a.grid : a.ntiles), dim3(NT), lds, st, a);
+  return (int)hipGetLastError();
+}
+
+template <typename T>
+static int launch_fire_t(const ConvArgs& a, hipStream_t st) {
+  constexpr int ESZ = (int)sizeof(T), BKE = Tr<T>::BKE, CE = Tr<T>::CE;
+  const bool pool = a.pool != POOL_NONE;
+  // what the kernel assumes, checked again on the host
+  if (a.mode != M_FLAT || a.has_res || a.ksplit >= 1 || a.ileave || a.kchunk || a.pair || a.dw_panel || a.pwdw || a.dw_w ||
+      a.R != 1 || a.S != 1 || a.stride != 1 || a.pad != 0 || a.C % CE != 0 || a.C < CE || a.Kred_pad < (a.C + BKE - 1) / BKE * BKE || a.Kred_pad % BKE != 0 ||
+      a.K < 1 || a.K > 64 || (a.K * ESZ) % 32 != 0 || a.OH != a.H || a.OW != a.W ||
+      !a.fire_w[0] || !a.fire_w[1] || !a.fire_scale[0] || !a.fire_scale[1] || !a.fire_shift[0] || !a.fire_shift[1] || !a.fire_out[0] || !a.fire_out[1] ||
+      a.fire_E[0] < CE || a.fire_E[1] < CE || a.fire_E[0] % CE != 0 || a.fire_E[1] % CE != 0 ||
+      a.fire_sP[0] < a.fire_E[0] || a.fire_sP[1] < a.fire_E[1] || a.fire_sP[0] % CE != 0 || a.fire_sP[1] % CE != 0 ||
+      a.fire_sN[0] % CE != 0 || a.fire_sN[1] % CE != 0 || ((uintptr_t)a.fire_out[0] & 15) || ((uintptr_t)a.fire_out[1] & 15) ||
+      ((uintptr_t)a.fire_w[0] & 15) || ((uintptr_t)a.fire_w[1] & 15) ||
+      a.tiles_n < 1 || a.tiles_m != a.N * a.tiles_y * a.tiles_x || a.ntiles != a.tiles_m * a.tiles_n || a.grid < 1 ||
+      a.in_sN < 0 || a.in_sH < 0 || a.in_sW < a.C)
+    return (int)hipErrorInvalidValue;
+  int ch, cw, pool_pos = 0;
+  if (pool) {
+    // max-pooling with windows of 2 or 3 at stride 2, no padding; every window starts inside the map
+    if (a.pool != POOL_MAX || a.pk < 2 || a.pk > 3 || a.ps != 2 || a.pp != 0 || a.pph < 1 || a.ppw < 1 || a.PH < 1 || a.PW < 1 ||
+        (a.PH - 1) * a.ps >= a.H || (a.PW - 1) * a.ps >= a.W ||
+        a.tiles_y != (a.PH + a.pph - 1) / a.pph || a.tiles_x != (a.PW + a.ppw - 1) / a.ppw)
+      return (int)hipErrorInvalidValue;
+    ch = (a.pph - 1) * a.ps + a.pk; cw = (a.ppw - 1) * a.ps + a.pk;
+    pool_pos = ch * cw;
+  } else {
+    if (a.th < 1 || a.tw < 1 || a.tiles_y != (a.H + a.th - 1) / a.th || a.tiles_x != (a.W + a.tw - 1) / a.tw) return (int)hipErrorInvalidValue;
+    ch = a.th; cw = a.tw;
+  }
+  const int positions = (ch + 2) * (cw + 2);
+  const int lds = fire_lds(positions, a.K, ESZ, pool_pos);
+  if (positions > kFireMaxPositions || lds > 160 * 1024) return (int)hipErrorInvalidValue;
+  return pool ? launch_fire_inst<T, true>(a, lds, st) : launch_fire_inst<T, false>(a, lds, st);
+}
+
+int launch_fire(const ConvArgs& a, int dtype, void* stream) {
+  return dtype == DT_BF16 ? launch_fire_t<bf16_t>(a, (hipStream_t)stream) : launch_fire_t<float>(a, (hipStream_t)stream);
+}
+
+size_t fire_lds_bytes(int conv_h, int conv_w, int S, int esz, int pooled) {
+  return (size_t)fire_lds((conv_h + 2) * (conv_w + 2), S, esz, pooled ? conv_h * conv_w : 0);
 }
 
 }  // namespace xenos

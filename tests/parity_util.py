@@ -164,35 +164,40 @@ def _storage_round(a, v):
 _MOVES = ("concat", "slice", "shuffle")
 
 
-def _chain_reference(g, ch, acts, forced, rnd):
-    """What the oracle computes for chain `ch` from the inputs the chain was given: its operators, in graph order,
-    applied to `forced` (graph tensor id -> the stored, rounded value written to the device) for tensors that come
-    from outside the chain."""
-    v = ch["out"]
-    ops = sorted(ch["ops"])
+def _chain_reference(g, ch, v, acts, forced, rnd):
+    """What the oracle computes for output view `v` of chain `ch` from the inputs the chain was given: the chain's
+    operators, in graph order, applied to `forced` (graph tensor id -> the stored, rounded value written to the device)
+    for tensors that come from outside the chain."""
+    ops = sorted(set(ch["ops"]))
     if not ops or all(g.ops[o].kind in _MOVES for o in ops):
-        # pure data movement (a copied concat part, a strided shuffle copy): the view's tensor, as stored
+        # pure data movement (a copied concat part, a strided shuffle copy, the import pass): the view's tensor, as stored
         return _storage_round(_view_tensor(acts, v), v)
-    vals = {}
+    shapes = g.shapes()
+    vals, parts = {}, {}
     for o in ops:
         op = g.ops[o]
         if op.kind in _MOVES:
             continue
+        t0 = op.inputs[0]
+        if (op.kind in ("maxpool", "avgpool", "gap") and t0 not in vals and t0 >= 1 and g.ops[t0 - 1].kind == "concat"
+                and any(t in vals for t in g.ops[t0 - 1].inputs)):
+            # a pooling that the plan moved in front of the concat it follows: it pools this chain's part(s) of the concat
+            off = 0
+            for t in g.ops[t0 - 1].inputs:
+                if t in vals:
+                    parts[(o + 1, off)] = xo.apply_op(op, [vals[t]])
+                off += shapes[t][1]
+            continue
         # (a tensor the chain reads through another view, e.g. behind a shuffle folded into its weights, holds the same
         # stored values)
-        ins = []
-        for t in op.inputs:
-            if t in vals:
-                ins.append(vals[t])
-            elif vals and t >= 1 and g.ops[t - 1].kind == "concat" and op.kind in ("maxpool", "avgpool", "gap"):
-                # a pooling that the plan moved in front of the concat it follows: it pools this chain's part
-                ins.append(vals[max(vals)])
-            else:
-                ins.append(forced[t] if t in forced else rnd(acts[t]))
+        ins = [vals[t] if t in vals else forced[t] if t in forced else rnd(acts[t]) for t in op.inputs]
         vals[o + 1] = xo.apply_op(op, ins)
-    r = vals[max(vals)]
+    key = (v["tensor"], v["c0"])
+    if key in parts and parts[key].shape[1] == v["c"]:
+        return parts[key]
+    r = vals[v["tensor"]] if v["tensor"] in vals else vals[max(vals)]
     if r.shape[1] == v["c"]:
-        return r                                      # the chain's tensor itself (or its pooled part of a pooled concat)
+        return r                                      # the chain's tensor itself
     pos = ch.get("shuffle_store", 0)
     if pos:
         # the chain stores its channels and those of the other part of its concat, alternating (two-group shuffle)
@@ -241,7 +246,10 @@ def teacher_forced(g, sess, compute, acts=None):
         pending = label
         if v["tensor"] < 0:
             continue                                  # partial sums of a reduction split: finished by the next step
-        ref = _chain_reference(g2, ch, acts, forced, rnd)
+        if ch.get("out2") is not None:                # a chain with two outputs (the two expand parts of a Fire module)
+            v2 = ch["out2"]
+            rows.append((ch["name"] + ".out2", label, rel_err(read_view(sess, v2), _chain_reference(g2, ch, v2, acts, forced, rnd)), 0.0))
+        ref = _chain_reference(g2, ch, v, acts, forced, rnd)
         got = read_view(sess, v)
         rows.append((ch["name"], label, rel_err(got, ref), chain_excess(got, ref) if v["esz"] == 2 else 0.0))
     return rows

@@ -454,6 +454,49 @@ def test_pointwise_depthwise_linked_on_chip(stride, h, w, c, k, n, tail, compute
 
 
 @pytest.mark.parametrize("compute", [0, 1])
+@pytest.mark.parametrize("h,w,c,s,e1,e3,n,pool,tail", [(13, 13, 32, 16, 64, 64, 2, 0, "conv"), (27, 21, 64, 32, 128, 72, 1, 3, "conv"),
+                                                       (9, 30, 24, 48, 40, 200, 3, 0, "conv"), (14, 14, 128, 64, 256, 256, 1, 2, "conv"),
+                                                       (55, 55, 64, 16, 64, 64, 1, 3, "gap"), (5, 5, 16, 16, 8, 8, 2, 0, "out"),
+                                                       (12, 18, 40, 32, 136, 64, 2, 3, "out"), (7, 7, 512, 64, 64, 128, 1, 0, "conv")])
+def test_fire_module_linked_on_chip(h, w, c, s, e1, e3, n, pool, tail, compute):
+    # link level 3, Fire module (Table 1, Conv1x1 -> Conv3x3): squeeze 1x1 -> {expand 1x1 || expand 3x3} -> concat [-> max
+    # pooling] is ONE chain; the squeeze tile (+ halo) lives in LDS.  Odd sizes give clipped blocks, e = 72 / 200 / 136
+    # / 40 ragged channel tiles, s = 16 .. 64 one to four k-groups per tap; pool 3 = 3x3/2 ceil mode, 2 = 2x2/2; tails:
+    # a convolution reading the concat, a global average, the concat as the (NHWC) graph output.
+    b = wg.builder("fire", (n, c, h, w), 37, nonzero_bias=True)
+    x = b.cbr(0, c, 3, 1, 1, name="pre")
+    q = b.cbr(x, s, 1, name="sq", bn=False)
+    t = b.concat([b.cbr(q, e1, 1, name="e1", bn=False), b.cbr(q, e3, 3, 1, 1, name="e3", bn=(pool == 0))])
+    if pool == 3:
+        t = b.maxpool(t, 3, 2, 0, ceil=1)
+    elif pool == 2:
+        t = b.maxpool(t, 2, 2)
+    fmt = {}
+    if tail == "conv":
+        t = b.cbr(t, 24, 1, name="post")
+    elif tail == "gap":
+        t = b.gap(t)
+    else:
+        fmt = dict(out_layout=1, out_dtype=compute)
+    g = b.finish(t)
+    ref = xo.forward(g)
+    y3, i3 = check(g, ref, compute=compute, link=3, **fmt)
+    y2, i2 = check(g, ref, compute=compute, link=2, **fmt)
+    fire = [ch for ch in i3["chains"] if ch.get("loader") == "fire"]
+    fits = compute == 1 or s <= 48                           # (fp32: a 3x3 weight tile of 64 squeeze channels does not fit LDS)
+    assert len(fire) == (1 if fits else 0)
+    if fits:
+        assert i3["n_chains"] == i2["n_chains"] - 2 and (fire[0]["pool"] != 0) == (pool != 0)
+        assert i3["hbm_bytes"] < i2["hbm_bytes"]
+    if not any(ch["kind"] == "splitk_finish" for ch in i3["chains"]):   # (a reduction split sums in another, fixed, order)
+        y3s, _ = run_gpu(g, compute=compute, link=3, split=0, **fmt)
+        assert np.array_equal(y3, y3s)                        # one workgroup walking every tile and channel share: same bits
+        y3m, _ = run_gpu(g, compute=compute, link=3, hw=dict(X_small=True), **fmt)
+        assert np.array_equal(y3, y3m)                        # 8 compute units: other tiles and shares
+    check_chains(g, compute, link=3, **fmt)
+
+
+@pytest.mark.parametrize("compute", [0, 1])
 @pytest.mark.parametrize("kind", ["fc_big", "conv3_deep", "shortcut_deep"])
 def test_reduction_split_across_workgroups(kind, compute):
     # few output tiles and a long reduction: the planner also splits C/R/S across workgroups and sums the shares in
