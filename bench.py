@@ -4,9 +4,13 @@
 One "step" = one forward pass of the whole planned chain sequence over one batch of synthetic input
 that is already resident in HBM.  Prints ONE JSON line.  The headline workload is config 3
 (VGG-16-style, batch 32, bf16 MFMA / fp32 accumulate, linked + split): the largest single-GPU
-configuration and the compute-bound regime in which the MFMA roofline is meaningful.  The same line
-carries the linked / U1 / U0 comparison for that workload and, unless --quick, images/s for the other
-configurations (batch 1 and 32).
+configuration and the compute-bound regime in which the MFMA roofline is meaningful.
+
+Fixed policy, no minimum over variants: the headline (and every `images_per_s` of the other workloads)
+is the path at link level 3, the deepest linking the library has, partitions profiled per chain
+(xenos_plan_tune), enqueued with xenos_run (one launch per chain).  HIP-graph replay of the same plan
+(xenos_run_graph) and the other link levels (2, U1, U0) are reported beside it.  Batch-1 workloads are
+timed over at least 500 passes whatever --steps says (a pass takes 0.1-0.3 ms).
 """
 from __future__ import annotations
 
@@ -38,12 +42,14 @@ WORKLOADS = {
 }
 PEAK = {1: 2500.0, 0: 157.3}          # dense MFMA TFLOP/s: bf16, fp32
 HBM_PEAK = 8000.0                     # GB/s
-LINK_NAMES = {3: "linked_deep", 2: "linked", 1: "U1", 0: "U0"}   # linked_deep: depthwise -> pointwise and conv3x3 -> conv3x3 pairs kept on chip
+LINK_NAMES = {3: "linked_deep", 2: "linked", 1: "U1", 0: "U0"}   # linked_deep: + the chains whose intermediate stays on chip
+HEADLINE_LINK = 3
+MIN_PASSES_BATCH1 = 500
 
 
-def time_steps(sess, torch, steps, warmup, graph=True):
-    """K forward passes; graph=True replays the HIP graph of the chain sequence (xenos_run_graph), which is what a
-    latency-bound caller would use; graph=False enqueues the kernels one by one (xenos_run)."""
+def time_steps(sess, torch, steps, warmup, graph=False):
+    """K forward passes.  graph=False enqueues the kernels one by one (xenos_run); graph=True replays the HIP graph
+    of the same chain sequence (xenos_run_graph)."""
     run = sess.run_graph if graph else sess.run
     for _ in range(warmup):
         run()
@@ -77,29 +83,36 @@ def time_chains(sess, torch, steps):
 TUNE = True     # profiling-driven partition choice (xenos_plan_tune) before timing; --no-tune keeps the cost model's choice
 
 
-def run_workload(name, steps, warmup, links=(2,), chains=False, wg=None, X=None, torch=None, graph=None):
+def chain_label(c):
+    if c["kind"] != "conv":
+        return c["kind"]
+    if c.get("halo"):
+        return "conv3x3_kernel"
+    return {"stem": "stem kernel", "pair": "conv_pair_kernel", "stream": "fc_stream_kernel", "pwdw": "pwdw_kernel", "fire": "fire_kernel",
+            "vector": "dwpw_kernel" if c.get("dw_linked") else "conv_kernel", "scalar": "conv_kernel"}.get(c.get("loader"), "conv_kernel")
+
+
+def run_workload(name, steps, warmup, links=(3,), chains=False, wg=None, X=None, torch=None, graph=None):
     cfg, batch, compute = WORKLOADS[name]
     g = graph if graph is not None else wg.build(cfg, batch)
+    passes = steps if batch > 1 else max(steps, MIN_PASSES_BATCH1)
     out = {"workload": name, "config": cfg, "batch": batch, "dtype": "bf16" if compute else "f32",
-           "gflop": wg.conv_fc_flops(g) / 1e9}
+           "gflop": wg.conv_fc_flops(g) / 1e9, "passes_timed": passes}
     for link in links:
         s = X.Session(g, link=link, split=1, compute=compute)
         s.set_input(g.x)
         retuned = s.tune(reps=5) if TUNE else 0
-        # both ways of enqueueing a pass are product entry points (xenos_run_graph / xenos_run); the step time is the
-        # better of the two, and the line says which
-        ms_graph, wall_g = time_steps(s, torch, steps, warmup, graph=True)
-        ms_eager, wall_e = time_steps(s, torch, steps, warmup, graph=False)
-        ms, wall = (ms_graph, wall_g) if ms_graph <= ms_eager else (ms_eager, wall_e)
-        rec = {"ms_per_step": ms, "wall_ms_per_step": wall, "ms_per_step_eager_launches": ms_eager,
-               "ms_per_step_graph_replay": ms_graph, "launch": "graph_replay" if ms_graph <= ms_eager else "eager",
-               "images_per_s": batch / ms * 1e3, "tuned": bool(TUNE), "chains_retuned": retuned,
+        ms, wall = time_steps(s, torch, passes, warmup, graph=False)
+        ms_graph, _ = time_steps(s, torch, passes, warmup, graph=True)
+        rec = {"ms_per_step": ms, "wall_ms_per_step": wall, "ms_per_step_graph_replay": ms_graph, "launch": "xenos_run (one launch per chain)",
+               "images_per_s": batch / ms * 1e3, "images_per_s_graph_replay": batch / ms_graph * 1e3,
+               "tuned": bool(TUNE), "chains_retuned": retuned,
                "tflops": out["gflop"] / ms, "n_chains": s.info["n_chains"],
                "algorithmic_hbm_mb": s.info["hbm_bytes"] / 1e6,
                "algorithmic_gb_per_s": s.info["hbm_bytes"] / ms / 1e6}
-        if chains and link >= 2:
-            cms = time_chains(s, torch, max(3, steps // 2))
-            rec["chains"] = [dict(i=c["i"], name=c["name"], kind=c["kind"], ms=float(cms[c["i"]]), gflop=c["flops"] / 1e9,
+        if chains:
+            cms = time_chains(s, torch, max(3, min(steps, 20) // 2))
+            rec["chains"] = [dict(i=c["i"], name=c["name"], kind=c["kind"], kernel=chain_label(c), ms=float(cms[c["i"]]), gflop=c["flops"] / 1e9,
                                   mb=(c["bytes_in"] + c["bytes_w"] + c["bytes_out"] + c["bytes_res"]) / 1e6,
                                   mode=c.get("mode"), tile=[c.get("bm"), c.get("bn")] if c["kind"] == "conv" else None,
                                   loader=c.get("loader"), halo=c.get("halo", 0), ksplit=c.get("ksplit", 1))
@@ -111,17 +124,67 @@ def run_workload(name, steps, warmup, links=(2,), chains=False, wg=None, X=None,
     return out, g
 
 
+def layer_table(chains, compute):
+    """Per-chain roofline rows: the bound is the roof the chain's arithmetic intensity puts it under."""
+    ridge = PEAK[compute] * 1e3 / HBM_PEAK          # flop per byte
+    rows = []
+    for c in chains:
+        ai = c["gflop"] * 1e3 / max(c["mb"], 1e-9)
+        bound = "mfma" if (c["kind"] == "conv" and ai >= ridge) else "hbm"
+        tf, gbs = c["gflop"] / c["ms"], c["mb"] / c["ms"]
+        rows.append({"chain": c["name"], "kernel": c["kernel"], "us": round(c["ms"] * 1e3, 2), "gflop": round(c["gflop"], 3), "mb": round(c["mb"], 3),
+                     "tflops": round(tf, 1), "gb_per_s": round(gbs, 1), "bound": bound,
+                     "frac": round(tf / PEAK[compute] if bound == "mfma" else gbs / HBM_PEAK, 4)})
+    return rows
+
+
+def attainable(X, torch):
+    """What this GPU attains on the two roofs, measured here with the library's probe kernels: an MFMA-only loop (bf16
+    32x32x16, no memory instruction in the loop) and a streaming read of 1 GiB of device memory."""
+    nout = 8192 * X.MI355X["num_cu"]
+    out = torch.empty(nout, dtype=torch.uint8, device="cuda:0")
+    src = torch.ones(1 << 28, dtype=torch.float32, device="cuda:0")      # 1 GiB
+    st = torch.cuda.current_stream().cuda_stream
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    res = {}
+    flops = X.xenos_probe_mfma(out.data_ptr(), nout, 2000, st)              # warm-up
+    torch.cuda.synchronize()
+    e0.record()
+    flops = X.xenos_probe_mfma(out.data_ptr(), nout, 20000, st)
+    e1.record()
+    torch.cuda.synchronize()
+    res["mfma_loop_tflops_bf16"] = flops / (e0.elapsed_time(e1) * 1e-3) / 1e12
+    nbytes = src.numel() * 4
+    X.xenos_probe_read(src.data_ptr(), nbytes, out.data_ptr(), nout, st)
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(5):
+        X.xenos_probe_read(src.data_ptr(), nbytes, out.data_ptr(), nout, st)
+    e1.record()
+    torch.cuda.synchronize()
+    res["stream_read_gb_per_s"] = 5 * nbytes / (e0.elapsed_time(e1) * 1e-3) / 1e9
+    del src, out
+    torch.cuda.empty_cache()
+    return res
+
+
 def pmc_traffic(workload):
-    """HBM bytes per launch of the dominant kernel from the committed counter summary (rocprofv3 --pmc FETCH_SIZE /
-    WRITE_SIZE runs of this script), or None when no summary for this workload exists."""
-    path = os.path.join(ROOT, "profiles", "conv3x3_kernel_%s_pmc.txt" % workload)
+    """HBM bytes per launch of the dominant kernel.  rocprofv3 counters cannot be read from inside the timed process,
+    so this is the value of the committed counter summary (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this script
+    on the same workload, link level and partition policy), returned with the file it comes from; None if there is none."""
+    rel = os.path.join("profiles", "conv3x3_kernel_%s_pmc.txt" % workload)
+    val, plan = None, ""
     try:
-        for ln in open(path):
+        for ln in open(os.path.join(ROOT, rel)):
             if ln.startswith("traffic_bytes_per_launch:"):
-                return float(ln.split(":", 1)[1])
+                val = float(ln.split(":", 1)[1])
+            if ln.startswith("plan:"):
+                plan = ln.split(":", 1)[1].strip()
     except OSError:
         pass
-    return None
+    if val is None:
+        return None, "no counter summary committed for this workload"
+    return val, "stored profile value, not measured in this run: %s (%s)" % (rel, plan or "plan not recorded")
 
 
 TABLE4 = [  # (graph, optimisation the row measures, speed-up the paper prints for it on its DSP)
@@ -138,7 +201,7 @@ def table4_rows(steps, warmup, wg, X, torch):
         for label, link, split in (("with", 2, 1), ("without", 1 if opt == "linking" else 2, 1 if opt == "linking" else 0)):
             s = X.Session(g, link=link, split=split, compute=1)
             s.set_input(g.x)
-            ms[label] = min(time_steps(s, torch, steps, warmup, graph=True)[0], time_steps(s, torch, steps, warmup, graph=False)[0])
+            ms[label] = time_steps(s, torch, steps, warmup, graph=False)[0]
             s.close()
         rows.append({"operator": name, "optimisation": opt, "ms_with": round(ms["with"], 5), "ms_without": round(ms["without"], 5),
                      "speedup": round(ms["without"] / ms["with"], 2), "paper_speedup_on_its_dsp": paper})
@@ -162,15 +225,14 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="vgg16_n32_bf16", choices=sorted(WORKLOADS))
-    ap.add_argument("--quick", action="store_true", help="headline workload, linked mode only, no CPU baseline")
-    ap.add_argument("--cpu-images", type=int, default=16)
+    ap.add_argument("--quick", action="store_true", help="headline workload at link levels 3 and 2 only, no CPU baseline, no other workloads")
+    ap.add_argument("--cpu-images", type=int, default=0, help="images of the headline batch the oracle is timed on (0 = all)")
     ap.add_argument("--detail", default="", help="write the full per-chain report (JSON) to this file")
-    ap.add_argument("--link-level", type=int, default=0, choices=(0, 2, 3),
-                    help="time the linked path at this link level only (0: both, the headline is the faster one); for profiling runs")
     ap.add_argument("--no-tune", action="store_true", help="skip xenos_plan_tune: time the cost model's partition choice")
     ap.add_argument("--passes-only", type=int, default=-1, choices=(-1, 0, 1, 2, 3),
-                    help="run the headline workload at this link level (0 = U0, 1 = U1, 2, 3) for --steps eager passes and exit: "
-                         "the process whose HBM traffic rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE counts per link level")
+                    help="run the workload at this link level (0 = U0, 1 = U1, 2, 3): tune (unless --no-tune), synchronise, then --steps "
+                         "eager passes, and exit: the process whose kernels rocprofv3 traces / counts per link level; the JSON line says "
+                         "how many kernel launches the passes are, they are the last ones of the process")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run a plain device copy of 256 MiB three times and exit (reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
@@ -203,42 +265,49 @@ def main():
         g = wg.build(cfg, batch)
         s = X.Session(g, link=args.passes_only, split=1, compute=compute)
         s.set_input(g.x)
+        retuned = s.tune(reps=5) if TUNE else 0
+        torch.cuda.synchronize()
         for _ in range(args.steps):
             s.run()
         torch.cuda.synchronize()
         print(json.dumps({"workload": name, "link": args.passes_only, "passes": args.steps, "n_chains": s.info["n_chains"],
-                          "algorithmic_hbm_mb_per_pass": s.info["hbm_bytes"] / 1e6}))
+                          "kernel_launches_of_the_passes": args.steps * s.info["n_chains"], "tuned": bool(TUNE), "chains_retuned": retuned,
+                          "algorithmic_hbm_mb_per_pass": s.info["hbm_bytes"] / 1e6,
+                          "chains": [dict(name=c["name"], kernel=chain_label(c), gflop=c["flops"] / 1e9,
+                                          mb=(c["bytes_in"] + c["bytes_w"] + c["bytes_out"] + c["bytes_res"]) / 1e6) for c in s.info["chains"]]}))
         s.close()
         return
-    links = ((3, 2) if not args.link_level else (args.link_level,)) + (() if args.quick else (1, 0))
+    links = (3, 2) if args.quick else (3, 2, 1, 0)
     head, g = run_workload(name, args.steps, args.warmup, links, chains=True, wg=wg, X=X, torch=torch)
-    # the headline is the linked + split path at the link level that is faster on this workload (level 3 keeps the first
-    # two 3x3 convolutions of a VGG-style stack in one chain; where no such pair exists the two levels plan the same chains)
-    level = args.link_level or (3 if head["linked_deep"]["ms_per_step"] <= head["linked"]["ms_per_step"] else 2)
-    lk = head[LINK_NAMES[level]]
+    lk = head[LINK_NAMES[HEADLINE_LINK]]
 
     # Roofline of the dominant kernel: conv3x3_kernel (halo-staged 3x3 convolution chains on MFMA), over all its
     # launches in one step.  achieved = algorithmic flops of those chains / their summed launch durations, measured
-    # with HIP events around every launch on the launch stream.  The other conv kernels are reported beside it.
+    # with HIP events around every launch on the launch stream.  The other chains are in `per_layer`.
     conv = [c for c in lk["chains"] if c["kind"] == "conv"]
     dom = [c for c in conv if c.get("halo")] or conv
     dom_ms, dom_gf = sum(c["ms"] for c in dom), sum(c["gflop"] for c in dom)
     conv_ms, conv_gf = sum(c["ms"] for c in conv), sum(c["gflop"] for c in conv)
     step_ms = sum(c["ms"] for c in lk["chains"])
-    roof = {"bound": "mfma", "kernel": "conv3x3_kernel (halo-staged 3x3 conv chains, %d launches per step)" % len(dom),
+    att = attainable(X, torch)
+    traffic, traffic_source = pmc_traffic(name)
+    roof = {"bound": "mfma", "kernel": "%s (%d launches per step)" % (dom[0]["kernel"], len(dom)),
             "achieved": dom_gf / dom_ms, "peak": PEAK[compute], "unit": "TFLOP/s",
-            "frac": dom_gf / dom_ms / PEAK[compute], "traffic": pmc_traffic(name),
+            "frac": dom_gf / dom_ms / PEAK[compute], "traffic": traffic, "traffic_source": traffic_source,
             "avg_launch_ms": dom_ms / len(dom), "flops_per_launch": dom_gf * 1e9 / len(dom),
             "algorithmic_bytes_per_launch": sum(c["mb"] for c in dom) * 1e6 / len(dom),
             "share_of_step": dom_ms / step_ms,
+            "attainable_measured_here": {**{k: round(v, 1) for k, v in att.items()},
+                                         "frac_of_mfma_loop": dom_gf / dom_ms / att["mfma_loop_tflops_bf16"] if compute == 1 else None},
             "all_conv_chains": {"n": len(conv), "achieved": conv_gf / conv_ms, "frac": conv_gf / conv_ms / PEAK[compute],
                                 "share_of_step": conv_ms / step_ms},
             "best_layer": max(({"name": c["name"], "achieved": c["gflop"] / c["ms"], "frac": c["gflop"] / c["ms"] / PEAK[compute]}
-                               for c in dom), key=lambda d: d["achieved"])}
-    memb = [c for c in conv if c["gflop"] / max(c["mb"], 1e-9) * 1e3 < PEAK[compute] * 1e3 / HBM_PEAK]
-    if memb:    # chains whose arithmetic intensity puts them under the HBM roof (first layer, FC layers)
-        roof["memory_bound_chains"] = [{"name": c["name"], "gb_per_s": c["mb"] / c["ms"], "frac_of_hbm": c["mb"] / c["ms"] / HBM_PEAK}
-                                       for c in memb]
+                               for c in dom), key=lambda d: d["achieved"]),
+            "per_layer": layer_table(lk["chains"], compute)}
+    memb = [r for r in roof["per_layer"] if r["bound"] == "hbm"]
+    if memb:    # chains whose arithmetic intensity puts them under the HBM roof (first layer, FC layers, summing passes)
+        roof["memory_bound_chains"] = [{"name": r["chain"], "gb_per_s": r["gb_per_s"], "frac_of_hbm": r["frac"],
+                                        "frac_of_stream_read": round(r["gb_per_s"] / att["stream_read_gb_per_s"], 4)} for r in memb]
 
     line = {
         "metric": "images/sec + % MFMA/HBM roofline, linked vs unlinked, batch 1 and 32",
@@ -247,7 +316,8 @@ def main():
         "dtype": head["dtype"], "data": "synthetic",
         "config": {"workload": f"config {cfg}: {g.name}-style, batch {batch}, {head['dtype']}, linked+split, "
                                f"synthetic seeded weights and input", "batch": batch, "mode": "linked+split",
-                   "link_level": level, "gflop_per_step": head["gflop"], "launch": lk["launch"],
+                   "link_level": HEADLINE_LINK, "gflop_per_step": head["gflop"], "launch": lk["launch"],
+                   "ms_per_step_graph_replay": lk["ms_per_step_graph_replay"],
                    "partition": "profiled per chain (xenos_plan_tune)" if TUNE else "cost model"},
         "tflops": lk["tflops"],
         "roofline": roof,
@@ -257,20 +327,29 @@ def main():
     }
     detail = {"headline": head}
     if not args.quick:
-        line["cpu_baseline"] = cpu_baseline(g, min(args.cpu_images, batch))
+        line["cpu_baseline"] = cpu_baseline(g, batch if args.cpu_images <= 0 else min(args.cpu_images, batch))
         del g
         others = []
         for other in WORKLOADS:
             if other == name:
                 continue
-            olinks = (3, 2, 1, 0) if other.startswith(("mobilenet", "shufflenet")) else (2, 1, 0)   # level 3 only differs where depthwise convs exist
-            r, _ = run_workload(other, args.steps, args.warmup, olinks, chains=True, wg=wg, X=X, torch=torch)
+            r, _ = run_workload(other, args.steps, args.warmup, (3, 2, 1, 0), chains=True, wg=wg, X=X, torch=torch)
             detail[other] = r
-            others.append({"workload": other, "gflop": r["gflop"],
+            d3 = r["linked_deep"]
+            ocomp = WORKLOADS[other][2]
+            rows = layer_table(d3["chains"], ocomp)
+            worst = min(rows, key=lambda x: x["frac"])
+            others.append({"workload": other, "gflop": round(r["gflop"], 3), "passes_timed": r["passes_timed"],
                            **{k: round(r[k]["images_per_s"], 1) for k in ("linked_deep", "linked", "U1", "U0") if k in r},
-                           "linked_tflops": round(r["linked"]["tflops"], 2),
-                           "linked_algorithmic_gb_per_s": round(r["linked"]["algorithmic_gb_per_s"], 1)})
-        line["other_workloads_images_per_s"] = others
+                           "linked_deep_graph_replay": round(d3["images_per_s_graph_replay"], 1),
+                           "ms_per_step": round(d3["ms_per_step"], 4), "n_chains": d3["n_chains"],
+                           "tflops": round(d3["tflops"], 2), "frac_of_mfma_peak": round(d3["tflops"] / PEAK[ocomp], 4),
+                           "algorithmic_hbm_mb": round(d3["algorithmic_hbm_mb"], 2),
+                           "algorithmic_gb_per_s": round(d3["algorithmic_gb_per_s"], 1),
+                           "frac_of_hbm_peak": round(d3["algorithmic_gb_per_s"] / HBM_PEAK, 4),
+                           "unlinked_U0_hbm_mb": round(r["U0"]["algorithmic_hbm_mb"], 2),
+                           "slowest_chain_vs_its_roof": {"chain": worst["chain"], "kernel": worst["kernel"], "bound": worst["bound"], "frac": worst["frac"]}})
+        line["other_workloads"] = others
         line["table4_micro_benchmark"] = table4_rows(max(args.steps, 50), args.warmup, wg, X, torch)
     if args.detail:
         os.makedirs(os.path.dirname(os.path.abspath(args.detail)), exist_ok=True)

@@ -189,6 +189,15 @@ xenos_status xenos_plan_tune(xenos_plan* plan, const void* d_input, void* d_outp
 xenos_status xenos_run_chain(xenos_plan* plan, int chain, const void* d_input, void* d_output,
                              void* hip_stream);
 
+/* Device probes for the measurement report (no part of the inference path): what this GPU attains, to put beside the
+ * published peaks when a kernel's roofline fraction is quoted.  Both enqueue ONE kernel on hip_stream, asynchronously;
+ * the caller times it (events on the same stream).  d_out is scratch of at least 8192 * hw->num_cu bytes.
+ * xenos_probe_mfma: every compute unit runs `iters` rounds of eight independent bf16 MFMA (32x32x16) accumulations with no
+ * memory instruction in the loop; *flops (host, may be NULL) receives the floating-point operations of the launch.
+ * xenos_probe_read: streams `bytes` (a multiple of 16, 16-byte aligned) of device memory through 16-byte loads. */
+xenos_status xenos_probe_mfma(const xenos_hw_info* hw, void* d_out, size_t out_bytes, int iters, void* hip_stream, double* flops);
+xenos_status xenos_probe_read(const xenos_hw_info* hw, const void* d_in, size_t bytes, void* d_out, size_t out_bytes, void* hip_stream);
+
 /* Releases a graph or a plan (either handle type; NULL is ignored).  A plan holds a reference to
  * nothing of the graph after xenos_plan_link_split returns. */
 void xenos_destroy(void* graph_or_plan);

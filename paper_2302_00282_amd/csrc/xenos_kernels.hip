@@ -2702,4 +2702,66 @@ int launch_cvt(const CvtArgs& a, int dtype, void* stream) {
   return (int)hipGetLastError();
 }
 
+// ---------------------------------------------------------------------------------------------
+// Micro-kernels that measure what this device attains, for the denominators of the roofline report:
+// an MFMA-only loop (no memory instruction in the loop) and a streaming read of device memory.
+// ---------------------------------------------------------------------------------------------
+constexpr int PROBE_WG_PER_CU = 2;
+
+__global__ __launch_bounds__(NT) void probe_mfma_kernel(float* out, int iters) {
+  const int lane = threadIdx.x & 63;
+  // operands that differ per lane, finite and small; eight independent accumulators keep the pipe full
+  bf16x8_t fa, fb;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) { fa[e] = (__bf16)(0.001f * (float)((lane + e) & 7)); fb[e] = (__bf16)(0.002f * (float)((lane * 3 + e) & 7)); }
+  f32x16_t acc[8];
+#pragma unroll
+  for (int j = 0; j < 8; ++j)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) acc[j][e] = 0.f;
+  for (int i = 0; i < iters; ++i) {
+#pragma unroll
+    for (int j = 0; j < 8; ++j) acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, fb, acc[j], 0, 0, 0);
+  }
+  float sum = 0.f;
+#pragma unroll
+  for (int j = 0; j < 8; ++j)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) sum += acc[j][e];
+  out[(size_t)blockIdx.x * NT + threadIdx.x] = sum;
+}
+
+__global__ __launch_bounds__(NT) void probe_read_kernel(const u32x4_t* in, size_t n16, uint32_t* out) {
+  uint32_t x = 0;
+  const size_t stride = (size_t)gridDim.x * NT;
+  size_t i = (size_t)blockIdx.x * NT + threadIdx.x;
+  // four loads in flight per thread
+  for (; i + 3 * stride < n16; i += 4 * stride) {
+    const u32x4_t a = in[i], b = in[i + stride], c = in[i + 2 * stride], d = in[i + 3 * stride];
+    x ^= a[0] ^ a[1] ^ a[2] ^ a[3] ^ b[0] ^ b[1] ^ b[2] ^ b[3] ^ c[0] ^ c[1] ^ c[2] ^ c[3] ^ d[0] ^ d[1] ^ d[2] ^ d[3];
+  }
+  for (; i < n16; i += stride) { const u32x4_t a = in[i]; x ^= a[0] ^ a[1] ^ a[2] ^ a[3]; }
+  out[(size_t)blockIdx.x * NT + threadIdx.x] = x;
+}
+
+// MFMA loop on every compute unit: returns the floating-point operations the launch performs through *flops.
+// d_out must hold probe_out_bytes(num_cu) bytes.
+int launch_probe_mfma(void* d_out, int num_cu, int iters, void* stream, double* flops) {
+  if (!d_out || num_cu < 1 || iters < 1) return (int)hipErrorInvalidValue;
+  const int grid = num_cu * PROBE_WG_PER_CU;
+  hipLaunchKernelGGL(probe_mfma_kernel, dim3(grid), dim3(NT), 0, (hipStream_t)stream, (float*)d_out, iters);
+  if (flops) *flops = (double)grid * (NT / 64) * (double)iters * 8.0 * (2.0 * 32 * 32 * 16);
+  return (int)hipGetLastError();
+}
+
+// streaming read of `bytes` (a multiple of 16) from d_in; d_out must hold probe_out_bytes(num_cu) bytes
+int launch_probe_read(const void* d_in, size_t bytes, void* d_out, int num_cu, void* stream) {
+  if (!d_in || !d_out || num_cu < 1 || bytes < 16 || (bytes & 15) || ((uintptr_t)d_in & 15)) return (int)hipErrorInvalidValue;
+  const int grid = num_cu * 8;
+  hipLaunchKernelGGL(probe_read_kernel, dim3(grid), dim3(NT), 0, (hipStream_t)stream, (const u32x4_t*)d_in, bytes / 16, (uint32_t*)d_out);
+  return (int)hipGetLastError();
+}
+
+size_t probe_out_bytes(int num_cu) { return (size_t)num_cu * 8 * NT * 4; }
+
 }  // namespace xenos

@@ -2449,6 +2449,23 @@ xenos_status xenos_run_chain(xenos_plan* plan, int chain, const void* d_input, v
   return launch_step(*plan, plan->steps[chain], d_input, d_output, hip_stream);
 }
 
+xenos_status xenos_probe_mfma(const xenos_hw_info* hw, void* d_out, size_t out_bytes, int iters, void* hip_stream, double* flops) {
+  if (!hw || hw->num_cu <= 0 || !d_out || iters < 1) return fail(XENOS_EINVAL, "xenos_probe_mfma: bad argument");
+  if (out_bytes < probe_out_bytes(hw->num_cu)) return fail(XENOS_EINVAL, "xenos_probe_mfma: d_out must hold %zu bytes", probe_out_bytes(hw->num_cu));
+  const int rc = launch_probe_mfma(d_out, hw->num_cu, iters, hip_stream, flops);
+  if (rc != 0) return fail(XENOS_EDEVICE, "xenos_probe_mfma: launch failed: %s", hipGetErrorString((hipError_t)rc));
+  return XENOS_OK;
+}
+
+xenos_status xenos_probe_read(const xenos_hw_info* hw, const void* d_in, size_t bytes, void* d_out, size_t out_bytes, void* hip_stream) {
+  if (!hw || hw->num_cu <= 0 || !d_in || !d_out || bytes < 16 || (bytes & 15) || ((uintptr_t)d_in & 15))
+    return fail(XENOS_EINVAL, "xenos_probe_read: bad argument (bytes and d_in must be multiples of 16)");
+  if (out_bytes < probe_out_bytes(hw->num_cu)) return fail(XENOS_EINVAL, "xenos_probe_read: d_out must hold %zu bytes", probe_out_bytes(hw->num_cu));
+  const int rc = launch_probe_read(d_in, bytes, d_out, hw->num_cu, hip_stream);
+  if (rc != 0) return fail(XENOS_EDEVICE, "xenos_probe_read: launch failed: %s", hipGetErrorString((hipError_t)rc));
+  return XENOS_OK;
+}
+
 void xenos_destroy(void* h) {
   if (!h) return;
   const uint32_t magic = *(const uint32_t*)h;

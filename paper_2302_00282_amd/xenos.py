@@ -86,11 +86,14 @@ def lib():
         L.xenos_run_static.argtypes = [vp, vp, vp, vp]
         L.xenos_run_chain.argtypes = [vp, C.c_int, vp, vp, vp]
         L.xenos_plan_tune.argtypes = [vp, vp, vp, vp, C.c_int, C.POINTER(C.c_int)]
+        L.xenos_probe_mfma.argtypes = [C.POINTER(HwInfo), vp, C.c_size_t, C.c_int, vp, C.POINTER(C.c_double)]
+        L.xenos_probe_read.argtypes = [C.POINTER(HwInfo), vp, C.c_size_t, vp, C.c_size_t, vp]
         L.xenos_destroy.argtypes = [vp]
         L.xenos_destroy.restype = None
         L.xenos_last_error.restype = C.c_char_p
         for f in ("xenos_graph_create", "xenos_plan_link_split", "xenos_plan_query", "xenos_plan_bind",
-                  "xenos_run", "xenos_run_graph", "xenos_run_static", "xenos_run_chain", "xenos_plan_tune"):
+                  "xenos_run", "xenos_run_graph", "xenos_run_static", "xenos_run_chain", "xenos_plan_tune",
+                  "xenos_probe_mfma", "xenos_probe_read"):
             getattr(L, f).restype = C.c_int
         _lib = L
     return _lib
@@ -166,6 +169,19 @@ def xenos_plan_tune(plan: int, d_input: int, d_output: int, stream: int = 0, rep
 
 def xenos_run_chain(plan: int, chain: int, d_input: int, d_output: int, stream: int = 0):
     _check(lib().xenos_run_chain(plan, chain, d_input, d_output, stream))
+
+
+def xenos_probe_mfma(d_out: int, out_bytes: int, iters: int, stream: int = 0, hw: Optional[dict] = None) -> float:
+    """Enqueues the MFMA-only loop; returns the floating-point operations of the launch."""
+    hwi = HwInfo(**(hw or MI355X))
+    f = C.c_double(0.0)
+    _check(lib().xenos_probe_mfma(C.byref(hwi), d_out, out_bytes, iters, stream, C.byref(f)))
+    return f.value
+
+
+def xenos_probe_read(d_in: int, nbytes: int, d_out: int, out_bytes: int, stream: int = 0, hw: Optional[dict] = None):
+    hwi = HwInfo(**(hw or MI355X))
+    _check(lib().xenos_probe_read(C.byref(hwi), d_in, nbytes, d_out, out_bytes, stream))
 
 
 def xenos_destroy(handle: Optional[int]):
