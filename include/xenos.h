@@ -54,8 +54,11 @@ typedef enum {
   XENOS_OP_CONCAT = 8,          /* x.concat along channels, 2..4 inputs                              */
   XENOS_OP_FC = 9,              /* x.matmul as FullyConnected over the NCHW flattening of its input  */
   XENOS_OP_SLICE = 10,          /* channels [c_begin, c_begin + out_c) of the input (the inverse of x.concat) */
-  XENOS_OP_SHUFFLE = 11         /* channel shuffle of the ShuffleNet models (Section 7.1): with C = groups * m,
+  XENOS_OP_SHUFFLE = 11,        /* channel shuffle of the ShuffleNet models (Section 7.1): with C = groups * m,
                                    output channel i * groups + j is input channel j * m + i                  */
+  XENOS_OP_MATMUL = 12          /* x.matmul (Table 3; the MatmulX -> MatmulY row of Table 1): Y[M][N] = X[M][K] . W[N][K]^T (+ bias[N]).
+                                   The rows are the tensor's first dimension: input M x K x 1 x 1, output M x out_c x 1 x 1,
+                                   i.e. row-major [row][column] in memory under either layout name; any number of rows */
 } xenos_op_kind;
 
 typedef struct {
@@ -70,7 +73,7 @@ typedef struct {
   xenos_op_kind kind;
   int n_inputs;
   int inputs[4];
-  int out_c;                    /* conv, fc, slice                                 */
+  int out_c;                    /* conv, fc, matmul, slice                         */
   int kh, kw;                   /* conv, pool                                      */
   int stride_h, stride_w;       /* conv, pool (must be equal)                      */
   int pad_h, pad_w;             /* conv, pool (must be equal)                      */
@@ -79,7 +82,7 @@ typedef struct {
   int count_include_pad;        /* avgpool                                         */
   int c_begin;                  /* slice: first channel                            */
   float eps;                    /* bn                                              */
-  const float* weight;          /* conv: [out_c][c/groups][kh][kw]; fc: [out_c][c*h*w] */
+  const float* weight;          /* conv: [out_c][c/groups][kh][kw]; fc: [out_c][c*h*w]; matmul: [out_c][c] */
   const float* bias;            /* conv, fc (optional); bias op (required): [c]    */
   const float* gamma;           /* bn: [c] each                                    */
   const float* beta;

@@ -175,6 +175,20 @@ def fc(x, w, bias=None) -> np.ndarray:
     return y.reshape(n, o, 1, 1)
 
 
+def matmul(x, w, bias=None) -> np.ndarray:
+    """x.matmul (Table 3): Y[M][N] = X[M][K] . W[N][K]^T (+ bias[N]) on an M x K x 1 x 1 tensor, whose first dimension
+    are the rows: the fully connected definition on a 1x1 map, written out as such."""
+    x, w = _f64(x), _f64(w)
+    assert x.ndim == 4 and x.shape[2:] == (1, 1), x.shape
+    m, k = x.shape[0], x.shape[1]
+    n, k2 = w.shape
+    assert k == k2
+    b = None if bias is None else _f64(bias)
+    y = np.empty((m, n), np.float64)
+    lib().xo_fc(_p(np.ascontiguousarray(x.reshape(m, k))), m, k, _p(w), _p(b), n, _p(y))
+    return y.reshape(m, n, 1, 1)
+
+
 def apply_op(op, ins: List[np.ndarray]) -> np.ndarray:
     """One operator of the graph, by its plain definition."""
     a, p = op.attrs, op.params
@@ -199,6 +213,8 @@ def apply_op(op, ins: List[np.ndarray]) -> np.ndarray:
         return concat(ins)
     if op.kind == "fc":
         return fc(ins[0], p["weight"], p.get("bias"))
+    if op.kind == "matmul":
+        return matmul(ins[0], p["weight"], p.get("bias"))
     if op.kind == "slice":
         return channel_slice(ins[0], a["c_begin"], a["out_c"])
     if op.kind == "shuffle":

@@ -1264,7 +1264,7 @@ struct Planner {
 
   xenos_status plan_node(int i) {
     const int k = nodes[i].kind;
-    return k == XENOS_OP_CONV || k == XENOS_OP_FC ? plan_conv(i) : plan_standalone(i);
+    return k == XENOS_OP_CONV || k == XENOS_OP_FC || k == XENOS_OP_MATMUL ? plan_conv(i) : plan_standalone(i);
   }
 
   // Plans the chain that convolution / fully connected node `i` starts (and, at link level 3, the convolution it hands
@@ -1281,7 +1281,8 @@ struct Planner {
     auto finish = [&](int, int out_tensor, bool is_conv) { st.v_out = out_view_for(out_tensor, is_conv); };
 
     {
-      const bool is_fc = nd.kind == XENOS_OP_FC;
+      // (a matmul is a fully connected operator over a 1x1 map: its rows are the images)
+      const bool is_fc = nd.kind == XENOS_OP_FC || nd.kind == XENOS_OP_MATMUL;
       const bool dw = !is_fc && d.groups != 1;
       const int K = d.out_c;
       if (dw && (d.groups != is.c || K != is.c)) return fail(XENOS_EUNSUPPORTED, "%s: only groups == 1 or depthwise (groups == C == out_c)", st.name.c_str());
@@ -2192,6 +2193,13 @@ xenos_status xenos_graph_create(const xenos_tensor_desc* input, const xenos_op_d
           if (d.out_c <= 0) { rc = fail(XENOS_EINVAL, "op %d: bad fc attributes", i); break; }
           os = Shape{s.n, d.out_c, 1, 1};
           need(d.weight, (size_t)d.out_c * s.c * s.h * s.w, o.weight, "weight", true);
+          need(d.bias, d.out_c, o.bias, "bias", false);
+          break;
+        case XENOS_OP_MATMUL:
+          if (d.out_c <= 0) { rc = fail(XENOS_EINVAL, "op %d: bad matmul attributes", i); break; }
+          if (s.h != 1 || s.w != 1) { rc = fail(XENOS_ESHAPE, "op %d: matmul takes an M x K x 1 x 1 tensor (rows x columns), got %dx%dx%dx%d", i, s.n, s.c, s.h, s.w); break; }
+          os = Shape{s.n, d.out_c, 1, 1};
+          need(d.weight, (size_t)d.out_c * s.c, o.weight, "weight", true);
           need(d.bias, d.out_c, o.bias, "bias", false);
           break;
         case XENOS_OP_BIAS: need(d.bias, s.c, o.bias, "bias", true); break;

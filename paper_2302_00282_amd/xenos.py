@@ -21,12 +21,12 @@ XENOS_OK, XENOS_EINVAL, XENOS_ESHAPE, XENOS_EUNSUPPORTED, XENOS_ENOMEM, XENOS_ED
 XENOS_F32, XENOS_BF16 = 0, 1
 XENOS_NCHW, XENOS_NHWC = 0, 1
 (XENOS_OP_CONV, XENOS_OP_BIAS, XENOS_OP_BN, XENOS_OP_RELU, XENOS_OP_MAXPOOL, XENOS_OP_AVGPOOL,
- XENOS_OP_GLOBAL_AVGPOOL, XENOS_OP_ADD, XENOS_OP_CONCAT, XENOS_OP_FC, XENOS_OP_SLICE, XENOS_OP_SHUFFLE) = range(12)
+ XENOS_OP_GLOBAL_AVGPOOL, XENOS_OP_ADD, XENOS_OP_CONCAT, XENOS_OP_FC, XENOS_OP_SLICE, XENOS_OP_SHUFFLE, XENOS_OP_MATMUL) = range(13)
 
 _KIND = {"conv": XENOS_OP_CONV, "bias": XENOS_OP_BIAS, "bn": XENOS_OP_BN, "relu": XENOS_OP_RELU,
          "maxpool": XENOS_OP_MAXPOOL, "avgpool": XENOS_OP_AVGPOOL, "gap": XENOS_OP_GLOBAL_AVGPOOL,
          "add": XENOS_OP_ADD, "concat": XENOS_OP_CONCAT, "fc": XENOS_OP_FC, "slice": XENOS_OP_SLICE,
-         "shuffle": XENOS_OP_SHUFFLE}
+         "shuffle": XENOS_OP_SHUFFLE, "matmul": XENOS_OP_MATMUL}
 
 _FP = C.POINTER(C.c_float)
 
@@ -221,7 +221,7 @@ def op_descs(g, keep: List[np.ndarray]) -> List[OpDesc]:
             d.pad_h = d.pad_w = a["pad"]
             d.ceil_mode = a.get("ceil", 0)
             d.count_include_pad = a.get("count_include_pad", 0)
-        elif op.kind == "fc":
+        elif op.kind in ("fc", "matmul"):
             d.out_c = a["out_c"]
         elif op.kind == "slice":
             d.out_c, d.c_begin = a["out_c"], a["c_begin"]

@@ -79,7 +79,7 @@ def cached_forward(g, tag):
 
 # ---------------------------------------------------------------------------------------------- bf16 diagnostic oracle
 def rounded_graph(g):
-    """The same graph with its input and its conv / fc weights pre-rounded to bf16 (RNE), still fp32 arrays: the
+    """The same graph with its input and its conv / fc / matmul weights pre-rounded to bf16 (RNE), still fp32 arrays: the
     oracle then computes, in fp64, what the bf16 path would compute with exact arithmetic and exact intermediates,
     which separates kernel error from the quantisation of the operands.  Biases and BN parameters stay fp32 (the
     library folds them in fp64 and applies them to the fp32 accumulator)."""
@@ -88,7 +88,7 @@ def rounded_graph(g):
     g2.ops = []
     for op in g.ops:
         o = copy.copy(op)
-        if op.kind in ("conv", "fc"):
+        if op.kind in ("conv", "fc", "matmul"):
             o.params = dict(op.params)
             o.params["weight"] = bf16_rne(op.params["weight"])
         g2.ops.append(o)

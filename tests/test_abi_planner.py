@@ -375,3 +375,28 @@ def test_plan_metadata_names_the_graph_tensor_of_every_view():
                     n, ch, h, w = shapes[v["tensor"]]
                     assert (v["n"], v["h"], v["w"]) == (n, h, w) and v["c0"] + (v["c"] - 1) * v["cs"] < ch, (cfg, link, c["name"], key, v)
             assert q["chains"][-1]["out"]["tensor"] == g.output and q["chains"][-1]["out"]["mem"] == "output"
+
+
+def test_pattern_matmul_to_matmul_layout_link():
+    # Table 1, MatmulX -> MatmulY: the first matmul's chain (+ ReLU) writes the row-major [row][column] tensor the
+    # second one reads as its operand, with no pass in between; bias, ReLU and the shortcut add are operators of the
+    # matmul chains, not passes of their own
+    g = wg.matmul_chain(rows=128, widths=(512, 2048, 512), draw=False)
+    for compute in (X.XENOS_BF16, X.XENOS_F32):
+        q = plan_json(g, link=2, compute=compute)["plan"]
+        mm = [c for c in q["chains"] if c["kind"] == "conv"]
+        assert len(mm) == 2 and _kinds(g, mm[0]) == ["matmul", "relu"] and _kinds(g, mm[1]) == ["matmul", "add"]
+        assert mm[0]["N"] == 128 and mm[0]["K"] == 2048 and mm[1]["C"] == 2048 and mm[1]["K"] == 512
+        o, i = mm[0]["out"], mm[1]["in"]
+        assert o["mem"] == i["mem"] == "workspace" and o["byte_off"] == i["byte_off"] and (o["sN"], o["sP"], o["sK"]) == (2048, 2048, 1) == (i["sN"], i["sP"], i["sK"])
+        between = [c for c in q["chains"] if mm[0]["i"] < c["i"] < mm[1]["i"]]
+        assert between == []
+        u0 = plan_json(g, link=0, compute=compute)["plan"]
+        assert u0["n_chains"] > q["n_chains"] and u0["hbm_bytes"] > q["hbm_bytes"]
+    # shape errors of the operator
+    keep = []
+    bad = wg.matmul_chain(rows=4, widths=(8, 8), residual=False, draw=False)
+    ops = X.op_descs(bad, keep)
+    with pytest.raises(X.XenosError) as e:
+        X.xenos_graph_create(X.TensorDesc(4, 2, 2, 2, X.XENOS_F32, X.XENOS_NCHW), ops, 1)     # not a rows x columns tensor
+    assert e.value.status == X.XENOS_ESHAPE

@@ -497,6 +497,31 @@ def test_fire_module_linked_on_chip(h, w, c, s, e1, e3, n, pool, tail, compute):
 
 
 @pytest.mark.parametrize("compute", [0, 1])
+@pytest.mark.parametrize("rows,widths,residual", [(128, (512, 2048, 512), True), (1, (64, 256, 64), True), (33, (96, 200, 72), False),
+                                                  (384, (128, 128, 128, 40), False), (7, (1024, 64, 1024), True), (200, (24, 136), False)])
+def test_matmul_chains(rows, widths, residual, compute):
+    # Table 1, MatmulX -> MatmulY: x.matmul with any number of rows (1 .. 384 here; up to 32 rows the bf16 path streams the
+    # weights, above that the rows are GEMM tiles), chains of two and three matmuls with ReLU between them and a
+    # shortcut around; the intermediate is written once in the row-major order its consumer reads.  The first shape is
+    # the feed-forward block of a small BERT (128 tokens, 512 -> 2048 -> 512).
+    g = wg.matmul_chain(rows=rows, widths=widths, seed=83, residual=residual)
+    acts = xo.run_graph(g, keep="all")
+    ref, scale = acts[g.output], last_chain_scale(g, acts)
+    for link in (3, 2, 1, 0):
+        y, info = check(g, ref, scale, compute=compute, link=link)
+    y2, i2 = run_gpu(g, compute=compute, link=2)
+    y2b, _ = run_gpu(g, compute=compute, link=2)
+    assert np.array_equal(y2, y2b)                            # reduction splits are summed in a fixed order
+    nmm = len(widths) - 1
+    assert sum(1 for ch in i2["chains"] if ch["kind"] == "conv") == nmm
+    check_chains(g, compute, link=2)
+    # NHWC and NCHW name the same memory for a rows x columns tensor: bf16 rows in, bf16 rows out, read and written in place
+    if compute == 1 and widths[0] % 8 == 0 and widths[-1] % 8 == 0:
+        yb, ib = check(g, ref, scale, compute=1, link=2, in_dtype=1, in_layout=1, out_dtype=1, out_layout=0)
+        assert not any(ch["kind"] == "cvt" for ch in ib["chains"])
+
+
+@pytest.mark.parametrize("compute", [0, 1])
 @pytest.mark.parametrize("kind", ["fc_big", "conv3_deep", "shortcut_deep"])
 def test_reduction_split_across_workgroups(kind, compute):
     # few output tiles and a long reduction: the planner also splits C/R/S across workgroups and sums the shares in

@@ -427,3 +427,40 @@ def test_graph_runner_against_library_and_batch_independence(builder, kw):
 def test_oracle_is_deterministic():
     g = wg.single_chain(batch=2)
     assert np.array_equal(xo.forward(g), xo.forward(g))
+
+
+# ------------------------------------------------------------------------------------------ x.matmul (Table 3; Table 1 MatmulX -> MatmulY)
+def test_matmul_against_numpy_and_row_structure():
+    r = np.random.default_rng(77)
+    m, k, n = 9, 13, 7
+    x, w, b = r.standard_normal((m, k, 1, 1)), r.standard_normal((n, k)), r.standard_normal(n)
+    y = xo.matmul(x, w, b)
+    assert y.shape == (m, n, 1, 1)
+    want = np.matmul(x.reshape(m, k), w.T) + b                         # library routine, float64
+    np.testing.assert_allclose(y.reshape(m, n), want, rtol=0, atol=1e-12)
+    # a transposed operand fails this: W is [out][in], rows of X are independent
+    np.testing.assert_allclose(xo.matmul(x[3:4], w, b), y[3:4], rtol=0, atol=0)
+    eye = np.eye(k)
+    np.testing.assert_array_equal(xo.matmul(x, eye), x)                # identity weights
+    onehot = np.zeros((k, k, 1, 1)); onehot[np.arange(k), np.arange(k)] = 1.0
+    np.testing.assert_array_equal(xo.matmul(onehot, w).reshape(k, n), w.T)   # one-hot row i selects column i of W^T = W[:, i]
+    # the same operator as a fully connected layer on a 1x1 map and as a 1x1 convolution
+    np.testing.assert_allclose(y, xo.fc(x, w, b), rtol=0, atol=0)
+    np.testing.assert_allclose(y, xo.conv2d(x, w.reshape(n, k, 1, 1), b), rtol=0, atol=1e-12)
+
+
+def test_matmul_chain_graph_against_library():
+    # MatmulX -> MatmulY with ReLU between and a shortcut around (the feed-forward block of a small transformer)
+    g = wg.matmul_chain(rows=11, widths=(24, 40, 24), seed=5)
+    y = xo.forward(g)
+    t = torch.from_numpy(g.x.astype(np.float64)).reshape(11, 24)
+    p = g.ops[0].params
+    x0 = torch.relu((t - torch.from_numpy(p["mean"].astype(np.float64))) / torch.sqrt(torch.from_numpy(p["var"].astype(np.float64)) + float(np.float32(1e-5)))
+                    * torch.from_numpy(p["gamma"].astype(np.float64)) + torch.from_numpy(p["beta"].astype(np.float64)))
+    mm = [op for op in g.ops if op.kind == "matmul"]
+    h = torch.relu(x0 @ torch.from_numpy(mm[0].params["weight"].astype(np.float64)).T + torch.from_numpy(mm[0].params["bias"].astype(np.float64)))
+    out = h @ torch.from_numpy(mm[1].params["weight"].astype(np.float64)).T + torch.from_numpy(mm[1].params["bias"].astype(np.float64)) + x0
+    np.testing.assert_allclose(y.reshape(11, 24), out.numpy(), rtol=0, atol=1e-12)
+    # without the shortcut: widths that differ, three matmuls
+    g3 = wg.matmul_chain(rows=5, widths=(16, 8, 32, 12), seed=6, residual=False)
+    assert [op.kind for op in g3.ops] == ["matmul", "relu", "matmul", "relu", "matmul"] and xo.forward(g3).shape == (5, 12, 1, 1)

@@ -39,7 +39,7 @@ def seed_for(config: int, batch: int) -> int:
 
 @dataclass
 class Op:
-    kind: str                      # conv bias bn relu maxpool avgpool gap add concat fc slice shuffle
+    kind: str                      # conv bias bn relu maxpool avgpool gap add concat fc slice shuffle matmul
     inputs: List[int]
     attrs: Dict[str, float] = field(default_factory=dict)
     params: Dict[str, np.ndarray] = field(default_factory=dict)
@@ -92,6 +92,9 @@ def _infer(op: Op, ins):
         assert all(i[0] == n and i[2:] == (h, w) for i in ins)
         return (n, sum(i[1] for i in ins), h, w)
     if op.kind == "fc":
+        return (n, a["out_c"], 1, 1)
+    if op.kind == "matmul":
+        assert (h, w) == (1, 1), (ins, op.name)
         return (n, a["out_c"], 1, 1)
     if op.kind == "slice":
         assert 0 <= a["c_begin"] and a["out_c"] >= 1 and a["c_begin"] + a["out_c"] <= c, (ins, a)
@@ -188,6 +191,16 @@ class _Builder:
         if want_bias:
             p["bias"] = self._normal((out_c,), 0.1)
         return self._push(Op("fc", [x], dict(out_c=out_c), p, name))
+
+    def matmul(self, x, out_c, name="", bias=None):
+        """Y[M][out_c] = X[M][K] . W[out_c][K]^T (+ bias) on an M x K x 1 x 1 tensor (rows x columns)."""
+        m, k, h, w = self._shapes[x]
+        assert (h, w) == (1, 1)
+        p = {"weight": self._normal((out_c, k), math.sqrt(2.0 / k))}
+        want_bias = self.nonzero_bias if bias is None else bias
+        if want_bias:
+            p["bias"] = self._normal((out_c,), 0.1)
+        return self._push(Op("matmul", [x], dict(out_c=out_c), p, name))
 
     def cbr(self, x, out_c, k, stride=1, pad=0, groups=1, name="", bn=True, relu=True):
         t = self.conv(x, out_c, k, stride, pad, groups, name)
@@ -353,6 +366,24 @@ def table4(name: str, batch=1, seed=None, nonzero_bias=False, draw=True) -> Grap
             t = b.maxpool(t, 2, 2, name="pool")
         elif tail == "gap":
             t = b.gap(t, name="gap")
+    return b.finish(t)
+
+
+def matmul_chain(rows=128, widths=(512, 2048, 512), seed=None, residual=True, nonzero_bias=True, draw=True) -> Graph:
+    """MatmulX -> MatmulY chains (Table 1, last row; the transformer / LSTM workloads of Section 7.1 are made of them): the
+    feed-forward block of a small BERT is rows x 512 -> 2048 -> 512 with a ReLU in between and a shortcut around it.
+    widths = (K, N1, N2, ...): one matmul per step, ReLU between them.  With residual (and equal first and last width) a
+    BN + ReLU pre-activation comes first and is added to the last result, as the block's shortcut."""
+    b = _Builder("matmul_chain", (rows, widths[0], 1, 1), seed_for(20, rows) if seed is None else seed, nonzero_bias, draw)
+    shortcut = residual and widths[-1] == widths[0]
+    x0 = b.relu(b.bn(0, "pre.bn"), "pre.relu") if shortcut else 0
+    t = x0
+    for i, n_out in enumerate(widths[1:], 1):
+        t = b.matmul(t, n_out, name=f"mm{i}")
+        if i < len(widths) - 1:
+            t = b.relu(t, f"mm{i}.relu")
+    if shortcut:
+        t = b.add(t, x0, "shortcut")
     return b.finish(t)
 
 
