@@ -70,7 +70,7 @@ static const int kPairInMax = 256;   // positions of the staged block of the gra
 static const int kHaloRows = 256, kHaloCols = 128, kHaloPatchMax = 360;
 static const long long kL2BytesPerXcd = 4ll << 20;   // gfx950: one 4 MB L2 per XCD
 // the staged patch has one of two fixed row pitches (pixels): tiles up to 16 or up to 32 pixels wide
-static const int kHaloPitchNarrow = 18, kHaloPitchWide = 34;
+static const int kHaloPitchTiny = 10, kHaloPitchNarrow = 18, kHaloPitchWide = 34;
 
 struct ConvArgs {
   const void* in;        // activations: NHWC in the compute type (vector loader), or any strided fp32/T tensor (scalar loader)

@@ -573,7 +573,12 @@ __device__ __forceinline__ float quad_add(float v) {
 // tap are then 32 consecutive LDS rows per half-wavefront, the one pattern `ds_read_b128` serves at 238 B/clk/CU
 // (measured; any other row pattern runs at 127 B/clk/CU).  Measured on VGG-16 layers it is within +-3 % of the plain form
 // (the junk rows cost what the faster reads gain) and 6 % faster on 14x14 maps; the tuner picks it where it wins.
-template <typename T, int MODE, int PWID, int BN>
+// PART (pixel-major chains only): the reduction is split across workgroups as well (Section 4.2.2: a C split needs an
+// additional reduction).  A work item is (pixel tile, channel tile, share z): share z covers the channel chunks
+// [z * a.steps_per_split, (z + 1) * a.steps_per_split) and writes raw fp32 sums to a.part[z][pixel][channel]; the summing
+// pass adds the shares in index order and runs the rest of the chain.  For maps so small that pixel x channel tiles
+// leave most compute units idle (7x7 and 14x14 at batch 32).
+template <typename T, int MODE, int PWID, int BN, bool PART = false>
 __global__ __launch_bounds__(V2_NT) void conv3x3_kernel(const ConvArgs a) {
   using tr = Tr<T>;
   constexpr int CE = tr::CE, BKE = tr::BKE, ESZ = (int)sizeof(T);
@@ -612,7 +617,9 @@ __global__ __launch_bounds__(V2_NT) void conv3x3_kernel(const ConvArgs a) {
   static_assert(!PLIN || MODE == M_FLAT, "the patch-linear form exists for the pixel-major enumeration");
   const int PW_ = PLIN ? a.tw + 2 : PWID;                          // patch row pitch in pixels (a.tw + 2 <= PW_)
   const int PP = (a.th + 2) * PW_ + (PLIN ? 2 : 0), Hp = a.H + 2;  // (the last tap of the last junk rows reads 2 positions further)
-  const int nchunks = a.C / BKE;
+  const int KS = PART ? a.ksplit : 1;                              // shares of the reduction
+  const int nchunks = PART ? a.steps_per_split : a.C / BKE;        // channel chunks of one work item
+  static_assert(!PART || MODE == M_FLAT, "the reduction split exists for pixel-major chains");
 
   // ---- this workgroup's tiles ---------------------------------------------------------------------
   // Workgroups are dealt round-robin to the XCDs; each XCD owns a contiguous, balanced range of pixel tiles and
@@ -627,14 +634,15 @@ __global__ __launch_bounds__(V2_NT) void conv3x3_kernel(const ConvArgs a) {
   const int wgs = full ? (G - xcd + NUM_XCD - 1) / NUM_XCD : 1;    // workgroups of this XCD
   const int m0 = full ? xcd * a.tiles_m / NUM_XCD : xcd * a.tiles_m / nx;
   const int mlen = (full ? (xcd + 1) * a.tiles_m / NUM_XCD : (xcd + 1) * a.tiles_m / nx) - m0;
-  const int ntl = mlen * a.tiles_n;                                // tiles of this XCD
+  const int TNX = a.tiles_n * KS;                                  // channel tiles x reduction shares: one index
+  const int ntl = mlen * TNX;                                      // work items of this XCD
   // Order of an XCD's tiles: groups of `mg` pixel tiles, each group once per output-channel tile before the next group.
   // With a group as large as the XCD's range this is one sweep per channel tile (one weight slice live in the L2 at a
   // time); a group that the XCD's workgroups cover in one or two rounds reads its input patches while they are still
   // in the L2 instead of once per channel tile.
   const int mg = a.halo_mgroup < mlen ? a.halo_mgroup : mlen;
   auto tile_of = [&](int l, int& tile_m, int& tile_n) __attribute__((always_inline)) {
-    const int per = mg * a.tiles_n, grp = l / per, r = l - grp * per;
+    const int per = mg * TNX, grp = l / per, r = l - grp * per;
     const int left = mlen - grp * mg, glen = left < mg ? left : mg;   // the last group of the range may be short
     tile_n = r / glen;
     tile_m = m0 + grp * mg + (r - tile_n * glen);
@@ -643,13 +651,15 @@ __global__ __launch_bounds__(V2_NT) void conv3x3_kernel(const ConvArgs a) {
   if (li >= ntl) return;                                           // uniform per workgroup
   // A tile of the workgroup's sequence, decoded once (three uniform divisions) and kept for everything that needs it:
   // loads, weights, epilogue tables, epilogue
-  struct Tile { int tile_n, q0, x0, n0, r0; };
+  struct Tile { int tile_n, q0, x0, n0, r0, z; };
   auto decode = [&](int l) __attribute__((always_inline)) -> Tile {
     int tile_m, tile_n;
     tile_of(l, tile_m, tile_n);
+    const int z = PART ? tile_n % KS : 0;                          // (tile_of hands back the combined index)
+    if (PART) tile_n /= KS;
     const int tyi = tile_m / a.tiles_x;
     const int q0 = tyi * a.th, n0 = q0 / Hp;
-    return Tile{tile_n, q0, (tile_m - tyi * a.tiles_x) * a.tw, n0, q0 - n0 * Hp};
+    return Tile{tile_n, q0, (tile_m - tyi * a.tiles_x) * a.tw, n0, q0 - n0 * Hp, z};
   };
   // image and row of stacked row t.q0 + y: compares as long as a tile spans at most four images
   const bool few = a.th + 2 <= 3 * Hp;
@@ -683,12 +693,12 @@ __global__ __launch_bounds__(V2_NT) void conv3x3_kernel(const ConvArgs a) {
       const int k = few ? (rel >= Hp ? 1 : 0) + (rel >= 2 * Hp ? 1 : 0) + (rel >= 3 * Hp ? 1 : 0) : rel / Hp;
       const int n = n0 + k, ih = rel - k * Hp - 1, iw = x0 - 1 + pc;
       const bool ok = pp < PP && n < a.N && (unsigned)ih < (unsigned)a.H && (unsigned)iw < (unsigned)a.W;
-      aoff[it] = ok ? n * sN + ih * sH + iw * sW + c8 * CE : c8 * CE;
+      aoff[it] = (ok ? n * sN + ih * sH + iw * sW + c8 * CE : c8 * CE) + (PART ? t.z * nchunks * BKE : 0);
       aok |= (ok ? 1u : 0u) << it;
     }
   };
   auto weight_addr = [&](const Tile& t) __attribute__((always_inline)) -> int {
-    return ((t.tile_n * BN + tid / CPR) * a.Kred_pad + (tid % CPR) * CE) * ESZ;
+    return ((t.tile_n * BN + tid / CPR) * a.Kred_pad + (tid % CPR) * CE) * ESZ + (PART ? t.z * nchunks * 9 * ROWB : 0);
   };
 
   // ---- which pixel of the tile a GEMM row is ---------------------------------------------------------------
@@ -698,7 +708,9 @@ __global__ __launch_bounds__(V2_NT) void conv3x3_kernel(const ConvArgs a) {
   // vertically adjacent 2x2 windows for the zig-zag one (a window covers 4 consecutive residues).  Rows left over
   // when TH is not a multiple of 8 follow in plain order.  Any enumeration is legal: every pixel carries its own
   // output address.
-  static_assert(PLIN || PWID % 16 == 2, "the conflict-free enumeration assumes patch pitch = 2 mod 16");
+  // (pitch = 2 mod 8: rows ty = 0 .. 7 then start at 8 different even residues mod 16, with pitch 18 and 34 in order,
+  // with pitch 10 permuted; a 2x2 window of the zig-zag enumeration covers 4 residues and 4 stacked windows all 16)
+  static_assert(PLIN || PWID % 8 == 2, "the conflict-free enumeration assumes patch pitch = 2 mod 8");
   auto flat_px = [&](int m, int& ty, int& tx) __attribute__((always_inline)) {
     if (PLIN) { ty = m / PW_; tx = m - ty * PW_; return; }
     const int nbx = a.tw >> 1, rows8 = (a.tw & 1) ? 0 : (a.th >> 3) * 8, full = rows8 * a.tw;
@@ -1075,7 +1087,23 @@ __global__ __launch_bounds__(V2_NT) void conv3x3_kernel(const ConvArgs a) {
         }
     };
     using std::true_type; using std::false_type;
-    if (MODE == M_FLAT) {
+    if constexpr (PART) {
+      // raw fp32 sums of this share: lane = pixel lp of block i, 4 consecutive channels per group; the row table holds
+      // pixel * part_ld (the host sets the output strides to the partial buffer's)
+      float* pz = a.part + (long long)tcur.z * a.M_total * a.part_ld;
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        const long long ob = s_rowoff[wave_m * 64 + i * 32 + lp];
+        if (ob < 0) continue;
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+          for (int g = 0; g < 4; ++g) {
+            const int k0 = tile_n * BN + wave_n * WN + j * 32 + g * 8 + lhalf * 4;
+            *(f32x4_t*)(pz + ob + k0) = f32x4_t{acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]};
+          }
+      }
+    } else if (MODE == M_FLAT) {
       if (a.has_res) finish_store(true_type{}, false_type{});
       else finish_store(false_type{}, false_type{});
     } else {
@@ -1116,21 +1144,22 @@ __global__ __launch_bounds__(V2_NT) void conv3x3_kernel(const ConvArgs a) {
   }
 }
 
-template <typename T, int MODE, int PWID, int BN>
+template <typename T, int MODE, int PWID, int BN, bool PART = false>
 static int launch_conv3x3_pw(const ConvArgs& a, hipStream_t st) {
   static bool raised = false;
   if (!raised) {
-    hipError_t e = hipFuncSetAttribute((const void*)conv3x3_kernel<T, MODE, PWID, BN>, hipFuncAttributeMaxDynamicSharedMemorySize, v2_lds_total(BN));
+    hipError_t e = hipFuncSetAttribute((const void*)conv3x3_kernel<T, MODE, PWID, BN, PART>, hipFuncAttributeMaxDynamicSharedMemorySize, v2_lds_total(BN));
     if (e != hipSuccess) return (int)e;
     raised = true;
   }
-  hipLaunchKernelGGL((conv3x3_kernel<T, MODE, PWID, BN>), dim3(a.grid), dim3(V2_NT), v2_lds_total(BN), st, a);
+  hipLaunchKernelGGL((conv3x3_kernel<T, MODE, PWID, BN, PART>), dim3(a.grid), dim3(V2_NT), v2_lds_total(BN), st, a);
   return (int)hipGetLastError();
 }
 
 template <typename T, int MODE, int BN>
 static int launch_conv3x3_inst(const ConvArgs& a, hipStream_t st) {
   if (a.halo_plin) {
+    if (a.ksplit >= 1) return (int)hipErrorInvalidValue;
     if constexpr (MODE == M_FLAT) {
       const int pw = a.tw + 2;
       if (a.th * pw > V2_BM || (a.th + 2) * pw + 2 > V2_PPMAX) return (int)hipErrorInvalidValue;
@@ -1139,6 +1168,15 @@ static int launch_conv3x3_inst(const ConvArgs& a, hipStream_t st) {
       return (int)hipErrorInvalidValue;
     }
   }
+  if (a.ksplit >= 1) {   // reduction split across workgroups: pixel-major chains in the plain form
+    if constexpr (MODE == M_FLAT) {
+      if (a.tw + 2 <= kHaloPitchTiny && (a.th + 2) * kHaloPitchTiny <= V2_PPMAX) return launch_conv3x3_pw<T, MODE, kHaloPitchTiny, BN, true>(a, st);
+      if (a.tw + 2 <= kHaloPitchNarrow && (a.th + 2) * kHaloPitchNarrow <= V2_PPMAX) return launch_conv3x3_pw<T, MODE, kHaloPitchNarrow, BN, true>(a, st);
+      if (a.tw + 2 <= kHaloPitchWide && (a.th + 2) * kHaloPitchWide <= V2_PPMAX) return launch_conv3x3_pw<T, MODE, kHaloPitchWide, BN, true>(a, st);
+    }
+    return (int)hipErrorInvalidValue;
+  }
+  if (a.tw + 2 <= kHaloPitchTiny && (a.th + 2) * kHaloPitchTiny <= V2_PPMAX) return launch_conv3x3_pw<T, MODE, kHaloPitchTiny, BN>(a, st);
   if (a.tw + 2 <= kHaloPitchNarrow && (a.th + 2) * kHaloPitchNarrow <= V2_PPMAX) return launch_conv3x3_pw<T, MODE, kHaloPitchNarrow, BN>(a, st);
   if (a.tw + 2 <= kHaloPitchWide && (a.th + 2) * kHaloPitchWide <= V2_PPMAX) return launch_conv3x3_pw<T, MODE, kHaloPitchWide, BN>(a, st);
   return (int)hipErrorInvalidValue;
@@ -1149,10 +1187,19 @@ static int launch_conv3x3_t(const ConvArgs& a, hipStream_t st) {
   // the host checks the preconditions again: a wrong shape here would index outside the patch buffers
   if (a.R != 3 || a.S != 3 || a.stride != 1 || a.pad != 1 || !a.kchunk || a.C % Tr<T>::BKE != 0 || a.C < Tr<T>::BKE || a.th < 1 || a.tw < 1 ||
       a.th * a.tw > V2_BM || a.tiles_m != a.tiles_y * a.tiles_x || (a.halo_bn != 64 && a.halo_bn != 128) ||
-      a.tiles_n != (a.K + a.halo_bn - 1) / a.halo_bn || a.ksplit >= 1 || a.dw_w || !a.vec_out || (a.has_res && !a.vec_res) ||
+      a.tiles_n != (a.K + a.halo_bn - 1) / a.halo_bn || a.dw_w || (a.ksplit < 1 && (!a.vec_out || (a.has_res && !a.vec_res))) ||
       (long long)a.N * a.in_sN >= (1ll << 31) || a.in_sN < 0 || a.in_sH < 0 || a.in_sW < 0 ||
       (a.mode == M_ZIGZAG && (((a.th | a.tw | a.H | a.W) & 1) || a.has_res)))
     return (int)hipErrorInvalidValue;
+  if (a.ksplit >= 1) {
+    // reduction split: whole shares of channel chunks, raw fp32 sums to part[share][pixel][part_ld]; the kernel takes the
+    // pixel's offset in the partial buffer from the output strides
+    const int nch = a.C / Tr<T>::BKE;
+    if (a.mode != M_FLAT || a.has_res || a.halo_plin || !a.part || ((uintptr_t)a.part & 15) || a.steps_per_split < 1 || a.steps_per_split * a.ksplit != nch ||
+        a.part_ld != a.tiles_n * a.halo_bn || a.out_sP != a.part_ld || a.out_sN != (long long)a.OH * a.OW * a.part_ld || a.M_total != a.N * a.OH * a.OW ||
+        a.OH != a.H || a.OW != a.W)
+      return (int)hipErrorInvalidValue;
+  }
   if (a.mode == M_FLAT) return a.halo_bn == 128 ? launch_conv3x3_inst<T, M_FLAT, 128>(a, st) : launch_conv3x3_inst<T, M_FLAT, 64>(a, st);
   if (a.mode == M_ZIGZAG) return a.halo_bn == 128 ? launch_conv3x3_inst<T, M_ZIGZAG, 128>(a, st) : launch_conv3x3_inst<T, M_ZIGZAG, 64>(a, st);
   return (int)hipErrorInvalidValue;
@@ -2324,7 +2371,7 @@ int launch_conv(const ConvArgs& a, int dtype, int cfg, int scalar_loader, void* 
   hipStream_t st = (hipStream_t)stream;
   if (a.grid < 1 || a.tiles_m < 1 || a.tiles_n < 1) return (int)hipErrorInvalidValue;
   if (cfg < kHaloCfg && a.xcd_m != 1 && a.xcd_m != 2 && a.xcd_m != 4 && a.xcd_m != 8) return (int)hipErrorInvalidValue;
-  if (a.ksplit >= 1 && (a.mode != M_FLAT || !a.part || a.steps_per_split < 1 || (a.dw_w && a.dw_panel <= 0) || cfg == kHaloCfg)) return (int)hipErrorInvalidValue;
+  if (a.ksplit >= 1 && (a.mode != M_FLAT || !a.part || a.steps_per_split < 1 || (a.dw_w && a.dw_panel <= 0))) return (int)hipErrorInvalidValue;
   if (a.ileave) {
     // the interleaving store exists in the pixel-major epilogues of the general kernel and of the depthwise-panel kernel;
     // it moves whole 16-byte groups

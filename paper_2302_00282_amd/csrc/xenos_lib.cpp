@@ -522,7 +522,7 @@ struct Planner {
     if (cfg == kHaloCfg) {
       // persistent workgroups, one per compute unit, an equal number on every XCD
       c.xcd_m = 8;
-      const int per_xcd = std::max(1, std::min(std::max(1, p.hw.num_cu) / 8, (c.tiles_m + 7) / 8 * c.tiles_n));
+      const int per_xcd = std::max(1, std::min(std::max(1, p.hw.num_cu) / 8, (c.tiles_m + 7) / 8 * c.tiles_n * ks));
       c.grid = 8 * per_xcd;
       // Order of an XCD's tiles.  One sweep of its pixel tiles per output-channel tile keeps a single weight slice
       // live in the XCD's L2 (4 MB), and re-reads the input once per channel tile when the XCD's share of the input
@@ -544,6 +544,79 @@ struct Planner {
       c.grid = (int)(best * 8);
     }
     if (!p.opts.split) c.grid = 1;
+  }
+
+  // What the halo-staged 3x3 kernel needs of a chain's input side (its output side depends on who stores the result)
+  bool halo_input_ok(const Step& st) const {
+    const ConvArgs& c = st.conv;
+    return !c.ileave && !c.dw_w && !c.pair && c.R == 3 && c.S == 3 && c.stride == 1 && c.pad == 1 && !st.scalar && c.C % (kRowBytes / p.esz) == 0 &&
+           (long long)c.N * c.in_sN < (1ll << 31) && conv_lds_bytes(kHaloCfg, M_FLAT) <= p.hw.lds_bytes_per_cu;
+  }
+  // Tile of the plain form of the halo kernel for a pixel-major (step 1) or zig-zag (step 2) chain: the TH x TW block of
+  // at most kHaloRows pixels that wastes the fewest GEMM rows over the images stacked with their padding rows
+  bool choose_halo_tile(const ConvArgs& c, int step, ConvArgs& t) const {
+    const long long rows = (long long)c.N * (c.H + 2);
+    double best_fill = 0;
+    for (int tw = step; tw <= std::min(c.W + step - 1, kHaloRows); tw += step) {
+      if (tw + 2 > kHaloPitchWide) break;
+      // (the staged patch has one of three row pitches: a narrow tile of a small map is more rows high within the same patch)
+      const int pitch = tw + 2 <= kHaloPitchTiny ? kHaloPitchTiny : tw + 2 <= kHaloPitchNarrow ? kHaloPitchNarrow : kHaloPitchWide;
+      int th = kHaloRows / tw / step * step;
+      while (th >= step && (th + 2) * pitch > kHaloPatchMax) th -= step;
+      if (th < step) continue;
+      const long long ty = (rows + th - 1) / th, tx = (c.W + tw - 1) / tw;
+      const double fill = (double)c.N * c.H * c.W / ((double)ty * tx * kHaloRows);
+      if (fill > best_fill + 1e-9) { best_fill = fill; t.th = th; t.tw = tw; t.tiles_y = (int)ty; t.tiles_x = (int)tx; }
+    }
+    return best_fill > 0;
+  }
+
+  // Reduction split inside the halo kernel (Section 4.2.2: a split over C needs an extra reduction).  For maps so small
+  // that the pixel x channel tiles of a 3x3 layer leave most units idle (7x7 x 512 at batch 32: 32 tiles of 128
+  // channels), each tile's channel chunks are shared out over `ks` workgroups and a summing pass finishes the chain.
+  // The choice is a time model in microseconds on the measured rates of the kernel: a 256 x 128 tile does one chunk of
+  // 9 taps x 128 bytes of channels in 7.4 us (bf16; 4.6 us with 64 channels), a tile costs about 3 us around its chunks,
+  // the summing pass one launch and the partial sums written and read back.  Returns ks (0 = do not split).
+  struct HaloSplit { int ks = 0, bn = 0; ConvArgs tile{}; };
+  HaloSplit choose_halo_split(const Step& st) const {
+    HaloSplit r;
+    const ConvArgs& c = st.conv;
+    const int num_cu = std::max(1, p.hw.num_cu);
+    if (!p.opts.split || p.opts.tile != 0 || !halo_input_ok(st) || c.OH != c.H || c.OW != c.W) return r;
+    const int bke = kRowBytes / p.esz, nch = c.C / bke;
+    if (nch < 2) return r;
+    ConvArgs t = c;
+    if (!choose_halo_tile(c, 1, t)) return r;
+    t.tiles_m = t.tiles_y * t.tiles_x;
+    t.halo_plin = 0;
+    // (measured on ResNet-18: with fewer pixel tiles, batch 1 to 8 on 7x7 and 14x14 maps, the small gather tiles with
+    // their own reduction split are faster than shares of 256-row tiles that are mostly dummy rows)
+    if (t.tiles_m < 8) return r;
+    const double chunk_flops = 2.0 * kHaloRows * 9 * bke;                      // per output channel of the tile
+    const double rate[2] = {p.dt == DT_BF16 ? 5.1e6 : 0.45e6, p.dt == DT_BF16 ? 4.1e6 : 0.40e6};   // flop / us / unit
+    static const int bns[2] = {128, 64};
+    const double kTileUs = 3.0, kLaunchUs = 3.0, kPartBytesPerUs = 4.0e6;
+    double best = 1e300, unsplit = 1e300;
+    for (int v = 0; v < 2; ++v) {
+      const int tn = (c.K + bns[v] - 1) / bns[v];
+      const long long tiles = (long long)t.tiles_m * tn;
+      const double chunk_us = chunk_flops * bns[v] / rate[v];
+      for (int ks = 1; ks <= nch; ++ks) {
+        if (nch % ks) continue;
+        const long long rounds = (tiles * ks + num_cu - 1) / num_cu;
+        double us = rounds * (kTileUs + nch / ks * chunk_us);
+        if (ks == 1) { unsplit = std::min(unsplit, us); continue; }
+        us += kLaunchUs + 2.0 * ks * c.N * c.OH * c.OW * (double)(tn * bns[v]) * 4 / kPartBytesPerUs;
+        if (us < best) { best = us; r.ks = ks; r.bn = bns[v]; }
+      }
+    }
+    // (the unsplit forms are also what the tuner picks among: give them the benefit of the doubt)
+    if (r.ks < 2 || best > 0.8 * unsplit) { r.ks = 0; return r; }
+    t.halo_bn = r.bn;
+    t.tiles_n = (c.K + r.bn - 1) / r.bn;
+    t.ntiles = t.tiles_m * t.tiles_n;
+    r.tile = t;
+    return r;
   }
 
   xenos_status split_conv(Step& st) {
@@ -597,9 +670,9 @@ struct Planner {
     // halo-staged 3x3 kernel: a TH x TW block of output pixels (256 GEMM rows) x 128 channels per workgroup,
     // tiles laid over the images stacked with their padding rows
     // (the halo kernel stores 16-byte channel groups only: outputs and shortcuts that cannot take them use conv_kernel)
-    const bool halo_ok = !st.gap_finish && !c.ileave && c.vec_out && (!c.has_res || c.vec_res) && !c.dw_w && c.R == 3 && c.S == 3 && c.stride == 1 && c.pad == 1 && !st.scalar && c.kchunk &&
+    const bool halo_ok = !st.gap_finish && halo_input_ok(st) && c.kchunk && c.vec_out && (!c.has_res || c.vec_res) &&
                          (c.mode == M_FLAT || (c.mode == M_ZIGZAG && c.H % 2 == 0 && c.W % 2 == 0)) &&
-                         (long long)c.N * c.in_sN < (1ll << 31) && conv_lds_bytes(kHaloCfg, c.mode) <= p.hw.lds_bytes_per_cu;
+                         conv_lds_bytes(kHaloCfg, c.mode) <= p.hw.lds_bytes_per_cu;
     // a forced configuration binds the chains it applies to; the others get the planner's choice
     const int force_tile = p.opts.tile >= 1 && p.opts.tile <= kNumTileCfgs ? p.opts.tile
                            : (p.opts.tile == kHaloCfg + 1 || (p.opts.tile >= 7 && p.opts.tile <= 10)) && halo_ok ? kHaloCfg + 1 : 0;
@@ -640,18 +713,8 @@ struct Planner {
     if (halo_ok && (force_tile == 0 || force_tile == kHaloCfg + 1)) {
       const int step = c.mode == M_ZIGZAG ? 2 : 1;
       const long long rows = (long long)c.N * (c.H + 2);
-      double best_fill = 0;
       ConvArgs t0 = c;
-      for (int tw = step; tw <= std::min(c.W + step - 1, kHaloRows); tw += step) {
-        if (tw + 2 > kHaloPitchWide) break;
-        const int pitch = tw + 2 <= kHaloPitchNarrow ? kHaloPitchNarrow : kHaloPitchWide;
-        int th = kHaloRows / tw / step * step;
-        while (th >= step && (th + 2) * pitch > kHaloPatchMax) th -= step;
-        if (th < step) continue;
-        const long long ty = (rows + th - 1) / th, tx = (c.W + tw - 1) / tw;
-        const double fill = (double)c.N * c.H * c.W / ((double)ty * tx * kHaloRows);
-        if (fill > best_fill + 1e-9) { best_fill = fill; t0.th = th; t0.tw = tw; t0.tiles_y = (int)ty; t0.tiles_x = (int)tx; }
-      }
+      const double best_fill = choose_halo_tile(c, step, t0) ? 1.0 : 0.0;
       // patch-linear form (pixel-major chains): GEMM row = patch position with pitch TW + 2, two junk rows per patch row;
       // its A fragments are read at the full LDS rate
       ConvArgs tl = c;
@@ -1534,6 +1597,14 @@ struct Planner {
           st.gap_finish = 1;
           a.mode = M_FLAT; a.pool = POOL_NONE;
         }
+        // a 3x3 layer on a small map: reduction shared out inside the halo kernel (a linked global average then moves
+        // to the summing pass as above)
+        HaloSplit hsplit;
+        if (!from_dw && !from_pair && !is_fc && !st.stem && !a.ileave && (a.mode == M_FLAT || a.mode == M_GAP)) hsplit = choose_halo_split(st);
+        if (hsplit.ks >= 2 && a.mode == M_GAP) {
+          st.gap_finish = 1;
+          a.mode = M_FLAT; a.pool = POOL_NONE;
+        }
         a.M_total = a.mode == M_FLAT ? a.N * a.OH * a.OW : a.mode == M_ZIGZAG ? a.N * a.PH * a.PW * 4 : a.OH * a.OW;
         // A fully connected chain over at most 32 images streams its weights once: the kernel made for that keeps many
         // loads in flight per unit and shares the reduction out over workgroups (the summing pass finishes the chain)
@@ -1592,6 +1663,50 @@ struct Planner {
         // Parameter split beyond K (Section 4.2.2: C, R, S splits need an extra reduction): when the outC x H/W
         // partition leaves most compute units idle and the reduction is long, split it across workgroups too.
         // Shares are summed in index order by a second pass, so the result does not depend on timing.
+        // the convolution step hands a.ksplit shares of raw sums [share][pixel][a.part_ld] to a summing pass, which
+        // applies the chain's epilogue (scale, shift, shortcut, ReLU, global average) and stores the chain's output
+        auto emit_with_summing_pass = [&]() -> xenos_status {
+          const int ks = a.ksplit;
+          View pv;
+          pv.esz = 4; pv.f32 = 1; pv.s = Shape{1, 1, 1, 1};
+          const long long pbytes = (long long)ks * a.M_total * a.part_ld * 4;
+          pv.buf = new_buffer(pbytes, 0);
+          p.views.push_back(pv);
+          const int v_part = (int)p.views.size() - 1;
+          Step fin;
+          fin.kind = S_SPLITK; fin.name = st.name + ".sum";
+          fin.ops = st.ops;                                      // the summing pass completes the same chain
+          fin.v_in = v_part; fin.v_in2 = st.v_in2; fin.v_out = st.v_out;
+          fin.scale_off = st.scale_off; fin.shift_off = st.shift_off;
+          SplitKArgs& f = fin.splitk;
+          f.ksplit = ks; f.part_ld = a.part_ld; f.M = a.M_total; f.K = K; f.OHW = a.OH * a.OW;
+          f.res_sN = a.res_sN; f.res_sP = a.res_sP;
+          f.out_sN = a.out_sN; f.out_sP = a.out_sP; f.out_sK = a.out_sK; f.relu = a.relu; f.out_f32 = a.out_f32;
+          f.gap = st.gap_finish;
+          fin.bytes_in = pbytes; fin.bytes_res = st.bytes_res; fin.bytes_out = st.bytes_out;
+          st.v_out = v_part; st.v_in2 = -1; a.has_res = 0;
+          // (the halo kernel finds a pixel's row of the partial sums through the output strides)
+          if (st.cfg == kHaloCfg) { a.out_sN = (long long)a.OH * a.OW * a.part_ld; a.out_sP = a.part_ld; a.out_sK = 1; }
+          st.bytes_out = pbytes; st.bytes_res = 0;
+          const int sidx = (int)p.steps.size();
+          node_step[i] = sidx + 1;
+          for (int ab : absorbed) node_step[ab] = sidx + 1;
+          node_final[last] = 1;
+          add_step(st);
+          add_step(fin);
+          return XENOS_OK;
+        };
+        if (hsplit.ks >= 2) {
+          const ConvArgs& t = hsplit.tile;
+          a.th = t.th; a.tw = t.tw; a.tiles_y = t.tiles_y; a.tiles_x = t.tiles_x; a.tiles_m = t.tiles_m;
+          a.halo_plin = 0; a.halo_bn = t.halo_bn; a.tiles_n = t.tiles_n; a.ntiles = t.ntiles;
+          st.cfg = kHaloCfg; st.lds = conv_lds_bytes(kHaloCfg, M_FLAT);
+          st.cands.clear();                                        // the plan's structure depends on this split
+          a.ksplit = hsplit.ks; a.steps_per_split = a.C / (kRowBytes / p.esz) / hsplit.ks;
+          a.part_ld = a.tiles_n * a.halo_bn;
+          set_grid(a, kHaloCfg);
+          return emit_with_summing_pass();
+        }
         const int nsteps = a.Kred_pad / (kRowBytes / p.esz);
         if (st.fc_stream || (p.opts.split && !a.ileave && st.cfg < kHaloCfg && a.mode == M_FLAT && (!from_dw || (st.gap_finish && a.dw_panel > 0)) &&
             (st.gap_finish || (a.ntiles * 2 <= p.hw.num_cu && nsteps >= 32)))) {
@@ -1623,32 +1738,7 @@ struct Planner {
               a.part_ld = a.tiles_n * kTileCfgs[st.cfg].bn;
               set_grid(a, st.cfg);
             }
-            View pv;
-            pv.esz = 4; pv.f32 = 1; pv.s = Shape{1, 1, 1, 1};
-            const long long pbytes = (long long)ks * a.M_total * a.part_ld * 4;
-            pv.buf = new_buffer(pbytes, 0);
-            p.views.push_back(pv);
-            const int v_part = (int)p.views.size() - 1;
-            Step fin;
-            fin.kind = S_SPLITK; fin.name = st.name + ".sum";
-            fin.ops = st.ops;                                      // the summing pass completes the same chain
-            fin.v_in = v_part; fin.v_in2 = st.v_in2; fin.v_out = st.v_out;
-            fin.scale_off = st.scale_off; fin.shift_off = st.shift_off;
-            SplitKArgs& f = fin.splitk;
-            f.ksplit = ks; f.part_ld = a.part_ld; f.M = a.M_total; f.K = K; f.OHW = a.OH * a.OW;
-            f.res_sN = a.res_sN; f.res_sP = a.res_sP;
-            f.out_sN = a.out_sN; f.out_sP = a.out_sP; f.out_sK = a.out_sK; f.relu = a.relu; f.out_f32 = a.out_f32;
-            f.gap = st.gap_finish;
-            fin.bytes_in = pbytes; fin.bytes_res = st.bytes_res; fin.bytes_out = st.bytes_out;
-            st.v_out = v_part; st.v_in2 = -1; a.has_res = 0;
-            st.bytes_out = pbytes; st.bytes_res = 0;
-            const int sidx = (int)p.steps.size();
-            node_step[i] = sidx + 1;
-            for (int ab : absorbed) node_step[ab] = sidx + 1;
-            node_final[last] = 1;
-            add_step(st);
-            add_step(fin);
-            return XENOS_OK;
+            return emit_with_summing_pass();
           }
         }
       }

@@ -142,12 +142,22 @@ def test_linking_patterns_of_the_workloads():
     r32 = plan_json(g2, link=2, compute=X.XENOS_F32)["plan"]
     assert r32["chains"][0]["loader"] == "stem" and r32["chains"][1]["kind"] == "pool"
     assert all(c["kind"] in ("conv", "splitk_finish") for c in r32["chains"][2:])
-    # last block + global average (CBRA): at batch 1 through the summing pass of a reduction split, at batch 32 in the
-    # convolution's own epilogue; either way the average is an operator of that chain, not a pass of its own
+    # last block + global average (CBRA): through the summing pass of a reduction split (batch 1: the gather kernel's
+    # split, batch 32: channel chunks shared out inside the halo-staged kernel); without the operator split the average
+    # runs in the convolution's own epilogue.  Either way it is an operator of that chain, not a pass of its own
     assert any(g2.ops[o].kind == "gap" for o in convs[-2]["ops"]) and convs[-2]["mode"] == "flat"
     assert res["chains"][convs[-2]["i"] + 1]["kind"] == "splitk_finish"
     res32 = plan_json(wg.build(2, 32, draw=False), link=2, compute=X.XENOS_BF16)["plan"]
-    assert [c for c in res32["chains"] if c["kind"] == "conv"][-2]["mode"] == "gap"
+    last32 = [c for c in res32["chains"] if c["kind"] == "conv"][-2]
+    assert last32["mode"] == "flat" and last32["halo"] == 1 and last32["ksplit"] > 1 and any(g2.ops[o].kind == "gap" for o in last32["ops"])
+    assert res32["chains"][last32["i"] + 1]["kind"] == "splitk_finish"
+    # the 7x7 x 512 layers at batch 32: 9 pixel tiles x 4 channel tiles would occupy 36 of 256 units; their channel
+    # chunks are shared out so that at least half the units work
+    shared = [c for c in res32["chains"] if c["kind"] == "conv" and c["halo"] == 1 and c["ksplit"] > 1]
+    assert len(shared) == 3 and all(c["H"] == 7 and 2 * c["tiles_m"] * c["tiles_n"] * c["ksplit"] >= 256 for c in shared)
+    u32 = plan_json(wg.build(2, 32, draw=False), link=2, split=0, compute=X.XENOS_BF16)["plan"]
+    assert [c for c in u32["chains"] if c["kind"] == "conv"][-2]["mode"] == "gap"
+    assert not any(c["kind"] == "splitk_finish" for c in u32["chains"])
     sq = plan_json(wg.build(4, 1, draw=False), link=2, compute=X.XENOS_BF16)["plan"]
     # bf16: the 3x3/2 first layer stages its input block in LDS and its 3x3/2 ceil-mode pool is linked into it; fp32: the
     # gather form of the first-layer kernel, then the pool as the only stand-alone pass

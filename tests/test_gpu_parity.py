@@ -544,6 +544,36 @@ def test_reduction_split_across_workgroups(kind, compute):
     assert np.array_equal(y, y2)                       # fixed summation order: run-to-run identical
 
 
+@pytest.mark.parametrize("compute", [0, 1])
+@pytest.mark.parametrize("kind,n,c,hw,k", [("conv3", 32, 256, 7, 256), ("conv3", 29, 512, 7, 136), ("shortcut", 32, 256, 7, 256),
+                                           ("gap", 30, 256, 7, 256), ("shortcut", 9, 512, 14, 512), ("gap", 32, 512, 7, 512),
+                                           ("conv3", 40, 384, 5, 72)])
+def test_reduction_split_inside_the_halo_kernel(kind, n, c, hw, k, compute):
+    # 3x3 layers on small maps with many channels (the last stages of ResNet at batch 32): pixel x channel tiles alone
+    # leave most units idle, so every tile's channel chunks are shared out over workgroups of the halo-staged kernel and
+    # the summing pass finishes the chain (Section 4.2.2: a split over C needs an additional reduction).  k = 136 / 72
+    # leave a ragged channel tile; tiles straddle several images and the last one overhangs; 7- and 5-wide maps take the
+    # patch pitch of 10 pixels, the 14-wide one that of 18.
+    b = wg.builder("halosplit_" + kind, (n, 24, hw, hw), 71, nonzero_bias=True)
+    x = b.cbr(0, c, 1, 1, 0, name="in")                # the split chains read NHWC tensors of the compute type
+    if kind == "conv3":
+        t = b.cbr(b.cbr(x, k, 3, 1, 1, name="c"), 24, 1, 1, 0, name="head")
+    else:
+        u = b.cbr(x, k, 3, 1, 1, name="c1")
+        v = b.cbr(u, k, 3, 1, 1, name="c2", relu=False)
+        t = b.relu(b.add(v, u))
+        t = b.fc(b.gap(t), 10, "fc") if kind == "gap" else b.cbr(t, 24, 1, 1, 0, name="head")
+    g = b.finish(t)
+    y, info = check(g, compute=compute)
+    shared = [ch for ch in info["chains"] if ch.get("halo") and ch.get("ksplit", 1) > 1]
+    assert len(shared) == (1 if kind == "conv3" else 2), [(ch["name"], ch.get("halo"), ch.get("ksplit")) for ch in info["chains"]]
+    assert sum(1 for ch in info["chains"] if ch["kind"] == "splitk_finish") == len(shared)
+    y2, _ = run_gpu(g, compute=compute)
+    assert np.array_equal(y, y2)                       # shares are summed in index order: run-to-run identical
+    check(g, compute=compute, hw=dict(X_small=True))   # a machine of 8 units: other share counts, long walks per workgroup
+    check_chains(g, compute, link=3)
+
+
 @pytest.mark.parametrize("net", ["mobilenet", "squeezenet", "resnet"])
 def test_graph_replay_matches_eager_every_time(net):
     # replayed several times with eager work and synchronisations in between; every replay must equal the eager result.
