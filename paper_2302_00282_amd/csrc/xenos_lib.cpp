@@ -559,8 +559,10 @@ struct Planner {
     double best_fill = 0;
     for (int tw = step; tw <= std::min(c.W + step - 1, kHaloRows); tw += step) {
       if (tw + 2 > kHaloPitchWide) break;
-      // (the staged patch has one of three row pitches: a narrow tile of a small map is more rows high within the same patch)
-      const int pitch = tw + 2 <= kHaloPitchTiny ? kHaloPitchTiny : tw + 2 <= kHaloPitchNarrow ? kHaloPitchNarrow : kHaloPitchWide;
+      // (the staged patch has one of three row pitches; the smallest is for maps up to 8 wide, whose tiles are then more rows
+      // high within the same patch: 34 x 7 pixels of a 7x7 map instead of 18 x 7.  Wider maps measured the same with 32 x 8
+      // tiles at that pitch as with 16 x 16 tiles, and keep the squarer tile, which re-reads less halo)
+      const int pitch = (c.W <= 8 && tw + 2 <= kHaloPitchTiny) ? kHaloPitchTiny : tw + 2 <= kHaloPitchNarrow ? kHaloPitchNarrow : kHaloPitchWide;
       int th = kHaloRows / tw / step * step;
       while (th >= step && (th + 2) * pitch > kHaloPatchMax) th -= step;
       if (th < step) continue;

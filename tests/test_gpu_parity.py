@@ -266,14 +266,19 @@ def test_first_layer_reads_the_graph_input_in_place(k, ksz, stride, pad, hw, c, 
         # a padded channel count is not worth a pooling pass of its own: the general kernel keeps the pool linked
         assert info["chains"][0]["loader"] != "stem"
         return
-    assert info["chains"][0]["loader"] == "stem" and info["n_chains"] == (3 if pool and not linked_pool else 2)
+    # (the summing pass of a reduction split belongs to the chain before it)
+    n_chains = sum(1 for ch in info["chains"] if ch["kind"] != "splitk_finish")
+    assert info["chains"][0]["loader"] == "stem" and n_chains == (3 if pool and not linked_pool else 2)
     assert info["chains"][0]["K"] == (32 if k <= 32 else 64)
     assert not pool or linked_pool or info["chains"][1]["kind"] == "pool"
     assert not linked_pool or info["chains"][0]["pool"] != 0
     y0, i0 = check(g, ref, compute=compute, link=1)          # un-linked: the general kernel (after an import pass if the input is large)
     assert all(c.get("loader") != "stem" for c in i0["chains"])
     ys, _ = run_gpu(g, compute=compute, link=2, split=0)
-    assert np.array_equal(y, ys)                              # one workgroup walking all blocks: same bits
+    if n_chains == info["n_chains"]:                          # (shares of a reduction split are summed in another order)
+        assert np.array_equal(y, ys)                          # one workgroup walking all blocks: same bits
+    else:
+        assert rel_err(y, ys.astype(np.float64)) <= TOL[compute]
 
 
 @pytest.mark.parametrize("compute", [0, 1])
