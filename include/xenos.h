@@ -104,10 +104,12 @@ typedef struct {
 /* link:  0 = operator by operator (the paper's Vanilla dataflow: every operator is one pass)
  *        1 = fused CBR only; pooling / add / concat stay separate passes (the "HO baseline")
  *        2 = operator linking on (Section 4.1): CBR + pool, shortcut add, concat-by-offset
- *        3 = 2 plus the chains whose intermediate tensor stays on chip: depthwise -> pointwise (Section 2.2 example) and,
- *            on the bf16 path, a first-layer 3x3 convolution -> 3x3 convolution pair (Table 1, ConvX -> ConvY)
+ *        3 = 2 plus the chains whose intermediate tensor stays on chip (Table 1, ConvX -> ConvY): depthwise -> pointwise
+ *            and pointwise -> depthwise (Section 2.2 example), a 1x1 squeeze convolution -> its 1x1 and 3x3 expand
+ *            convolutions -> concat (-> max-pool), and, on the bf16 path, a first-layer 3x3 -> 3x3 convolution pair
  * split: 0 = every chain runs on ONE compute unit (no operator split; for tests)
- *        1 = DSP-aware operator split (Section 4.2): output channels first, then H/W
+ *        1 = DSP-aware operator split (Section 4.2): output channels first, then H/W, then (layers whose output tiles
+ *            leave most units idle) the reduction, whose shares a summing pass adds in index order
  * compute: element type of activations and weights in HBM; accumulation is always fp32.
  * tile: 0 = planner's choice; 1..4 force a tile shape of the general conv kernel; 5 the halo-staged 3x3 kernel
  *       (7 / 8: with 128- / 64-channel tiles; 9 / 10: the same in its patch-linear form where one exists) and 6 the
