@@ -2109,8 +2109,10 @@ static int launch_conv_mode(const ConvArgs& a, hipStream_t st) {
 __host__ __device__ constexpr int dwpw_panel_pitch(int cp, int esz) { return cp * esz + 16; }   // odd number of 16-byte slots
 __host__ __device__ constexpr int dwpw_lds(int cp, int esz) { return 64 * dwpw_panel_pitch(cp, esz) + 2 * 64 * LDS_ROW; }
 
+// (three wavefronts per SIMD: 143 registers instead of 167 + 16, a third workgroup per unit overlaps the two phases of
+// the others; measured 2 % on a network of such chains at batch 32, four wavefronts spill and lose)
 template <typename T>
-__global__ __launch_bounds__(NT) void dwpw_kernel(const ConvArgs a) {
+__global__ __launch_bounds__(NT, 3) void dwpw_kernel(const ConvArgs a) {
   using tr = Tr<T>;
   constexpr int CE = tr::CE, BKE = tr::BKE, ESZ = (int)sizeof(T);
   constexpr int BM = 64, BN = 64;
