@@ -1714,8 +1714,8 @@ struct Planner {
         }
         const int nsteps = a.Kred_pad / (kRowBytes / p.esz);
         if (st.fc_stream || (p.opts.split && !a.ileave && st.cfg < kHaloCfg && a.mode == M_FLAT && (!from_dw || (st.gap_finish && a.dw_panel > 0)) &&
-            (st.gap_finish || (a.ntiles * 2 <= p.hw.num_cu && nsteps >= 32)))) {
-          int ks = std::min({(2 * p.hw.num_cu + a.ntiles - 1) / a.ntiles, nsteps / 8, 32});
+            (st.gap_finish || (a.ntiles * 2 <= p.hw.num_cu && nsteps >= 16)))) {
+          int ks = std::min({(2 * p.hw.num_cu + a.ntiles - 1) / a.ntiles, nsteps / 2, 32});
           if (st.gap_finish) ks = std::max(ks, 1);
           if (from_dw) ks = 1;                                     // the depthwise-panel kernel hands over one share
           const int fc_tiles = (K + kFcChannels - 1) / kFcChannels;

@@ -342,7 +342,8 @@ def test_pattern_pointwise_to_depthwise_on_chip():
             assert c["out"]["c"] == c["K"] and c["out"]["h"] == c["OH"]
         # only the first depthwise convolution (its producer is the 3x3 first layer) runs as a chain of its own
         assert sum(c["kind"] == "dwconv" for c in l3["chains"]) == 1
-        assert l3["hbm_bytes"] < 0.66 * l2["hbm_bytes"]
+        # (the byte counts include the partial sums of the reduction splits of the tail, the same at both levels)
+        assert l3["hbm_bytes"] < 0.70 * l2["hbm_bytes"]
     assert all(c.get("loader") != "pwdw" for c in l2["chains"])
 
 
@@ -397,10 +398,12 @@ def test_pattern_matmul_to_matmul_layout_link():
         mm = [c for c in q["chains"] if c["kind"] == "conv"]
         assert len(mm) == 2 and _kinds(g, mm[0]) == ["matmul", "relu"] and _kinds(g, mm[1]) == ["matmul", "add"]
         assert mm[0]["N"] == 128 and mm[0]["K"] == 2048 and mm[1]["C"] == 2048 and mm[1]["K"] == 512
-        o, i = mm[0]["out"], mm[1]["in"]
-        assert o["mem"] == i["mem"] == "workspace" and o["byte_off"] == i["byte_off"] and (o["sN"], o["sP"], o["sK"]) == (2048, 2048, 1) == (i["sN"], i["sP"], i["sK"])
+        # (where the first matmul shares its reduction out over workgroups, its summing pass is the launch that finishes the
+        # chain and writes the tensor)
         between = [c for c in q["chains"] if mm[0]["i"] < c["i"] < mm[1]["i"]]
-        assert between == []
+        assert [c["kind"] for c in between] in ([], ["splitk_finish"]) and all(c["ops"] == mm[0]["ops"] for c in between)
+        o, i = (between[0] if between else mm[0])["out"], mm[1]["in"]
+        assert o["mem"] == i["mem"] == "workspace" and o["byte_off"] == i["byte_off"] and (o["sN"], o["sP"], o["sK"]) == (2048, 2048, 1) == (i["sN"], i["sP"], i["sK"])
         u0 = plan_json(g, link=0, compute=compute)["plan"]
         assert u0["n_chains"] > q["n_chains"] and u0["hbm_bytes"] > q["hbm_bytes"]
     # shape errors of the operator

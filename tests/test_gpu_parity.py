@@ -450,9 +450,13 @@ def test_pointwise_depthwise_linked_on_chip(stride, h, w, c, k, n, tail, compute
         assert sum(1 for ch in i3["chains"] if ch.get("loader") == "pwdw") == want
         assert not any(ch["kind"] == "dwconv" for ch in i3["chains"])
         y3s, _ = run_gpu(g, compute=compute, link=3, split=0, **cmp_fmt)
-        assert np.array_equal(y3, y3s)                        # one workgroup walking every tile: same bits
         y3m, _ = run_gpu(g, compute=compute, link=3, hw=dict(X_small=True), **cmp_fmt)
-        assert np.array_equal(y3, y3m)                        # 8 compute units: other tiles, persistent workgroups
+        if any(ch.get("ksplit", 1) > 1 for ch in i3["chains"]):
+            # (a chain after the pair shares its reduction out over workgroups: another, fixed, summation order)
+            assert rel_err(y3, y3s.astype(np.float64)) <= TOL[compute] and rel_err(y3, y3m.astype(np.float64)) <= TOL[compute]
+        else:
+            assert np.array_equal(y3, y3s)                    # one workgroup walking every tile: same bits
+            assert np.array_equal(y3, y3m)                    # 8 compute units: other tiles, persistent workgroups
     y2, i2 = check(g, ref, compute=compute, link=2)
     assert i3["n_chains"] < i2["n_chains"]
     check_chains(g, compute, link=3)
@@ -572,7 +576,8 @@ def test_reduction_split_inside_the_halo_kernel(kind, n, c, hw, k, compute):
     y, info = check(g, compute=compute)
     shared = [ch for ch in info["chains"] if ch.get("halo") and ch.get("ksplit", 1) > 1]
     assert len(shared) == (1 if kind == "conv3" else 2), [(ch["name"], ch.get("halo"), ch.get("ksplit")) for ch in info["chains"]]
-    assert sum(1 for ch in info["chains"] if ch["kind"] == "splitk_finish") == len(shared)
+    # (one summing pass per shared chain; another chain of the graph may split its reduction on the gather kernel)
+    assert all(info["chains"][ch["i"] + 1]["kind"] == "splitk_finish" for ch in shared)
     y2, _ = run_gpu(g, compute=compute)
     assert np.array_equal(y, y2)                       # shares are summed in index order: run-to-run identical
     check(g, compute=compute, hw=dict(X_small=True))   # a machine of 8 units: other share counts, long walks per workgroup
@@ -677,8 +682,11 @@ def test_channel_slice_and_shuffle(kind, compute):
         y, info = check(g, ref, compute=compute, link=link)
         assert info["linked_shuffles"] == (linked if link >= 2 else 0)
     y1, _ = run_gpu(g, compute=compute, link=2, split=0)
-    y2, _ = run_gpu(g, compute=compute, link=2)
-    assert np.array_equal(y1, y2)
+    y2, i2 = run_gpu(g, compute=compute, link=2)
+    if any(ch.get("ksplit", 1) > 1 for ch in i2["chains"]):     # (shares of a reduction split: another, fixed, summation order)
+        assert rel_err(y1, y2.astype(np.float64)) <= TOL[compute]
+    else:
+        assert np.array_equal(y1, y2)
     _, info = run_gpu(g, compute=compute, link=2)
     n_copy = sum(1 for ch in info["chains"] if ch["kind"] == "elt")
     n_fin = sum(1 for ch in info["chains"] if ch.get("shuffle_store"))
@@ -906,7 +914,7 @@ def test_random_shapes_of_the_chip_resident_kernels(case):
     y, info = check(g, ref, compute=1, link=3)
     assert want in [ch.get("loader") for ch in info["chains"]]
     ys, _ = run_gpu(g, compute=1, link=3, split=0)           # one workgroup walking every tile
-    if want == "stream":
+    if want == "stream" or any(ch.get("ksplit", 1) > 1 for ch in info["chains"]):
         assert rel_err(ys, ref) <= TOL[1]                    # (a different reduction split: compared with the oracle)
     else:
         assert np.array_equal(y, ys)
