@@ -1203,9 +1203,12 @@ struct Planner {
     return fire_lds_bytes(pk ? pk : 1, pk ? pk : 1, S, p.esz, pk ? 1 : 0) <= std::min<size_t>(p.hw.lds_bytes_per_cu, 160 * 1024);
   }
 
-  // Tile (output pixels, or pooling windows) and number of channel shares of a Fire-module chain.  A workgroup's cost:
-  // the squeeze GEMM of its clipped block (chunks of 64 positions x reduction steps) + for every expand tile of its share
-  // the chunks of 64 pixels x taps x k-groups; the longest workgroup queue decides, plus a term for the launch's traffic.
+  // Tile (output pixels, or pooling windows) and number of channel shares of a Fire-module chain.  A workgroup's time in
+  // microseconds, from timestamps taken inside the kernel at its phase boundaries (bf16, batch 1): 1.4 to start, the
+  // squeeze GEMM of its clipped block 1.0 + 0.35 per chunk of 64 positions and reduction step, and for every expand
+  // tile of its share the weight copy (0.7 + 0.15 per 4 KB), the GEMM (0.5 + 0.028 per tap and k-group, per chunk of 64
+  // pixels) and 0.9 for epilogue and stores (+ 1.5 with a linked pooling): at batch 1 these fixed latencies, not the
+  // MFMA work, are the time of a module.  The longest workgroup decides, or the sum of all over the units' slots.
   bool choose_fire_tile(ConvArgs& c) const {
     const int num_cu = std::max(1, p.hw.num_cu);
     const size_t lds_cap = std::min<size_t>(p.hw.lds_bytes_per_cu, 160 * 1024);
@@ -1228,20 +1231,26 @@ struct Planner {
           const int iy0 = (pool ? y * th * c.ps : y * th) - 1, hv = std::min(iy0 + CH + 2, c.H) - std::max(iy0, 0);
           for (int x = 0; x < tx; ++x) {
             const int ix0 = (pool ? x * tw * c.ps : x * tw) - 1, wv = std::min(ix0 + CW + 2, c.W) - std::max(ix0, 0);
-            const double cost = ((hv * wv + 63) / 64) * (double)nsteps * (kRowBytes / 32 + 2);
+            const double cost = 1.0 + ((hv * wv + 63) / 64) * (double)nsteps * (p.dt == DT_BF16 ? 0.35 : 0.5);
             sq_total += cost; sq_longest = std::max(sq_longest, cost);
           }
         }
-        for (int shares = 1; shares <= std::max(nt[0], nt[1]); shares *= 2) {
+        for (int shares = 1; shares <= std::max(nt[0], nt[1]); ++shares) {
           // share z takes the expand tiles z, z + shares, ... of each part
           double ex_total = 0, ex_longest = 0;
           for (int z = 0; z < shares; ++z) {
             double e = 0;
-            for (int wch = 0; wch < 2; ++wch) e += ((nt[wch] - z + shares - 1) / shares) * (px_chunks * ((wch ? 9 : 1) * kgs + 3) + 2);
+            for (int wch = 0; wch < 2; ++wch) {
+              const int taps = wch ? 9 : 1;
+              const double copy = 0.7 + 0.15 * (64.0 * taps * S * p.esz / 4096.0);
+              const double gemm = px_chunks * (0.5 + (p.dt == DT_BF16 ? 0.028 : 0.11) * taps * kgs);
+              e += ((nt[wch] - z + shares - 1) / shares) * (copy + gemm + 0.9 + (pool ? 1.5 : 0.0));
+            }
             ex_total += e; ex_longest = std::max(ex_longest, e);
           }
-          const double all = ((double)shares * sq_total + (double)ty * tx * ex_total) * c.N;
-          const double longest = sq_longest + ex_longest + 2;
+          const double wgs = (double)shares * ty * tx * c.N;
+          const double all = ((double)shares * sq_total + (double)ty * tx * ex_total) * c.N + 1.4 * wgs;
+          const double longest = 1.4 + sq_longest + ex_longest;
           const double t = p.opts.split ? std::max(all / ((double)occ * num_cu), longest) + all / (8.0 * num_cu) : all;
           if (t < best - 1e-9) {
             best = t;
