@@ -11,74 +11,88 @@
 namespace xenos {
 
 // ---------------------------------------------------------------------------------------------
-// 64 pixels x 64 output channels of a 1x1 / stride 1 convolution over all a.C input channels, shared by the kernels below.
-// `pixel(row)` gives the element offset of row's pixel in a.in (channel 0), or -1 for a row without a pixel (it
-// contributes zeros).  4 wavefronts as 2 x 2 of 32 pixels x 32 channels; operands double-buffered through registers and
-// the two LDS stages at s_op (2 * (64 + 64) * LDS_ROW bytes).  The GEMM is computed transposed: on return lane l of
+// The 1x1 / stride 1 convolution over all a.C input channels that both kernels below start with, in chunks of 64 pixels x
+// 64 output channels.  4 wavefronts as 2 x 2 of 32 pixels x 32 channels; the GEMM is computed transposed, so a lane of
 // wavefront (wave_m, wave_n) holds, for pixel row wave_m*32 + l%32, channels k_row0 + wave_n*32 + 8*g + 4*(l/32) + (0..3)
-// in acc[4*g .. 4*g+3].  Begins with a barrier-free write of stage 0 (the caller guarantees nobody still reads the
-// stages) and ends after a barrier (the stages are free again).
+// in acc[4*g .. 4*g+3].  Two LDS stages at s_op (2 * (64 + 64) * LDS_ROW bytes).
 // ---------------------------------------------------------------------------------------------
 constexpr int PG_BM = 64, PG_BN = 64;
 constexpr int PG_STAGES_BYTES = 2 * (PG_BM + PG_BN) * LDS_ROW;
 
-template <typename T, typename PixelFn>
-__device__ __forceinline__ void pw_gemm_chunk(const ConvArgs& a, int k_row0, unsigned char* s_op, PixelFn pixel, f32x16_t& acc) {
+// The GEMMs of ALL chunks of a phase as one sequence of steps (chunk 0 step 0, step 1, ..., chunk 1 step 0, ...): the
+// operands of step g + PG_DEPTH are requested from memory when step g is staged, so the memory latency (about 1 us at
+// batch 32; timestamps inside the kernels showed it exposed once per chunk, 1.4 us per chunk of a 64-channel layer of
+// which 0.3 are work) passes behind the steps before it, across chunk boundaries too.  A ring of PG_DEPTH register sets
+// holds the requests in flight, two LDS stages hold the step being multiplied and the next one, one barrier per step.
+// pixel(chunk, row) gives the element offset of a row's input pixel (-1 = no pixel); epilogue(chunk, acc) receives
+// the finished accumulators of a chunk (lane = row wave_m * 32 + l31, channels wave_n * 32 + 8 g + 4 lhalf + 0..3).
+// Ends without a barrier: the caller's next barrier frees the stages.
+constexpr int PG_DEPTH = 4;
+
+template <typename T, typename PixelFn, typename EpiFn>
+__device__ __forceinline__ void pw_gemm_phase(const ConvArgs& a, int k_row0, unsigned char* s_op, int nchunks, PixelFn pixel, EpiFn epilogue) {
   using tr = Tr<T>;
   constexpr int CE = tr::CE, BKE = tr::BKE, ESZ = (int)sizeof(T);
-  constexpr int BM = PG_BM, BN = PG_BN;
+  constexpr int BM = PG_BM, BN = PG_BN, D = PG_DEPTH;
   constexpr int A_IT = BM * CPR / NT, B_IT = BN * CPR / NT;        // 16-byte chunks per thread and step
-  static_assert(A_IT >= 1 && B_IT >= 1, "loader shapes");
+  static_assert(A_IT >= 1 && B_IT >= 1 && A_IT <= 8 && D % 2 == 0, "loader shapes");
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wave_m = wave >> 1, wave_n = wave & 1;
   const int l31 = lane & 31, lhalf = lane >> 5;
-  const int nsteps = a.Kred_pad / BKE;
-  long long abase[A_IT];
-  bool arow[A_IT];
+  const int nsteps = a.Kred_pad / BKE, G = nchunks * nsteps;
   const int ch = tid % CPR;
-#pragma unroll
-  for (int it = 0; it < A_IT; ++it) {
-    const long long off = pixel((tid + it * NT) / CPR);
-    arow[it] = off >= 0;
-    abase[it] = (arow[it] ? off : 0) + ch * CE;
-  }
   const unsigned char* wrow[B_IT];
 #pragma unroll
   for (int it = 0; it < B_IT; ++it) {
     const int idx = tid + it * NT;
     wrow[it] = (const unsigned char*)a.w + ((long long)(k_row0 + idx / CPR) * a.Kred_pad + (idx % CPR) * CE) * (long long)ESZ;
   }
+  // the chunk and step the next request belongs to, and this thread's input rows of that chunk
+  int ld_chunk = -1, ld_step = nsteps - 1;
+  long long abase[A_IT];
+  unsigned arow = 0;
+  u32x4_t ra[D][A_IT], rb[D][B_IT];
+  unsigned okm[D];                                                 // which of a set's input chunks are real (the others are zero)
+  auto request = [&](int q, int d) __attribute__((always_inline)) {
+    if (q >= G) return;                                            // (uniform)
+    if (++ld_step == nsteps) {
+      ld_step = 0;
+      ++ld_chunk;
+      arow = 0;
 #pragma unroll
-  for (int e = 0; e < 16; ++e) acc[e] = 0.f;
-  u32x4_t ra0[A_IT], rb0[B_IT], ra1[A_IT], rb1[B_IT];
-  auto load = [&](int step, u32x4_t* ra, u32x4_t* rb) {
-    const int ss = step < nsteps ? step : nsteps - 1;              // steps past the end re-read valid memory; never used
-    const int kc = ss * BKE + ch * CE;
+      for (int it = 0; it < A_IT; ++it) {
+        const long long off = pixel(ld_chunk, (tid + it * NT) / CPR);
+        arow |= (off >= 0 ? 1u : 0u) << it;
+        abase[it] = (off >= 0 ? off : 0) + ch * CE;
+      }
+    }
+    const int kc = ld_step * BKE + ch * CE;
+    okm[d] = kc < a.C ? arow : 0u;                                 // channels beyond C are the padding of the reduction
+#pragma unroll
+    for (int it = 0; it < A_IT; ++it)
+      ra[d][it] = *(const u32x4_t*)((const T*)a.in + (((okm[d] >> it) & 1u) ? abase[it] + ld_step * BKE : 0));
+#pragma unroll
+    for (int it = 0; it < B_IT; ++it) rb[d][it] = *(const u32x4_t*)(wrow[it] + (long long)ld_step * ROWB);
+  };
+  auto store = [&](int stage, int d) __attribute__((always_inline)) {
+    unsigned char* sa = s_op + stage * (BM + BN) * LDS_ROW;
+    unsigned char* sb = sa + BM * LDS_ROW;
     const u32x4_t z = {0u, 0u, 0u, 0u};
 #pragma unroll
     for (int it = 0; it < A_IT; ++it) {
-      const bool ok = arow[it] && kc < a.C;                        // channels beyond C are the padding of the reduction
-      const u32x4_t v = *(const u32x4_t*)((const T*)a.in + (ok ? abase[it] + ss * BKE : 0));
-      ra[it] = ok ? v : z;
-    }
-#pragma unroll
-    for (int it = 0; it < B_IT; ++it) rb[it] = *(const u32x4_t*)(wrow[it] + (long long)ss * ROWB);
-  };
-  auto store = [&](int stage, const u32x4_t* ra, const u32x4_t* rb) {
-    unsigned char* sa = s_op + stage * (BM + BN) * LDS_ROW;
-    unsigned char* sb = sa + BM * LDS_ROW;
-#pragma unroll
-    for (int it = 0; it < A_IT; ++it) {
       const int idx = tid + it * NT;
-      *(u32x4_t*)(sa + (idx / CPR) * LDS_ROW + (idx % CPR) * 16) = ra[it];
+      *(u32x4_t*)(sa + (idx / CPR) * LDS_ROW + (idx % CPR) * 16) = ((okm[d] >> it) & 1u) ? ra[d][it] : z;
     }
 #pragma unroll
     for (int it = 0; it < B_IT; ++it) {
       const int idx = tid + it * NT;
-      *(u32x4_t*)(sb + (idx / CPR) * LDS_ROW + (idx % CPR) * 16) = rb[it];
+      *(u32x4_t*)(sb + (idx / CPR) * LDS_ROW + (idx % CPR) * 16) = rb[d][it];
     }
   };
-  auto compute = [&](int stage) {
+  f32x16_t acc;
+#pragma unroll
+  for (int e = 0; e < 16; ++e) acc[e] = 0.f;
+  auto compute = [&](int stage) __attribute__((always_inline)) {
     const unsigned char* sa = s_op + stage * (BM + BN) * LDS_ROW + (wave_m * 32 + l31) * LDS_ROW + lhalf * 16;
     const unsigned char* sb = s_op + stage * (BM + BN) * LDS_ROW + BM * LDS_ROW + (wave_n * 32 + l31) * LDS_ROW + lhalf * 16;
 #pragma unroll
@@ -93,20 +107,28 @@ __device__ __forceinline__ void pw_gemm_chunk(const ConvArgs& a, int k_row0, uns
       }
     }
   };
-  load(0, ra0, rb0);
-  store(0, ra0, rb0);
-  load(1, ra1, rb1);
-  __syncthreads();                                                 // step 0 (and whatever the caller wrote before) is visible
-  for (int st = 0; st < nsteps; st += 2) {
-    load(st + 2, ra0, rb0);
-    compute(0);
-    store(1, ra1, rb1);
-    __syncthreads();
-    if (st + 1 >= nsteps) break;
-    load(st + 3, ra1, rb1);
-    compute(1);
-    store(0, ra0, rb0);
-    __syncthreads();
+#pragma unroll
+  for (int d = 0; d < D; ++d) request(d, d);
+  int c_chunk = 0, c_step = 0;
+  for (int g0 = 0; g0 < G; g0 += D) {
+#pragma unroll
+    for (int d = 0; d < D; ++d) {
+      const int g = g0 + d;
+      if (g < G) {                                                 // (uniform)
+        // stage d % 2 was last read by step g - 2, which every wavefront finished before the barrier of step g - 1
+        store(d & 1, d);
+        request(g + D, d);
+        __syncthreads();                                           // step g (and whatever the caller wrote before the phase) is visible
+        compute(d & 1);
+        if (++c_step == nsteps) {
+          epilogue(c_chunk, acc);
+#pragma unroll
+          for (int e = 0; e < 16; ++e) acc[e] = 0.f;
+          c_step = 0;
+          ++c_chunk;
+        }
+      }
+    }
   }
 }
 
@@ -172,17 +194,22 @@ __global__ __launch_bounds__(NT) void pwdw_kernel(const ConvArgs a) {
       for (int i = tid; i < PH * PWd * (MP / 16); i += NT) *(u32x4_t*)(s_mid + i * 16) = z;
     }
 
-    for (int mc = 0; mc * BM < npos; ++mc) {
-      // ---- pointwise GEMM of 64 block positions x 64 channels over all input channels ----------------
-      f32x16_t acc;
-      pw_gemm_chunk<T>(a, tile_n * BN, s_op, [&](int row) -> long long {
-        const int m = mc * BM + row;
-        if (m >= npos) return -1;
-        const int py = m / wv, px = m - py * wv;
-        return (long long)n * a.in_sN + (long long)(y_lo + py) * a.in_sH + (long long)(x_lo + px) * a.in_sW;
-      }, acc);
-      // ---- the pointwise chain's epilogue, into the LDS block: lane = position wave_m*32 + l31, channels
-      // wave_n*32 + 8*g + 4*lhalf + (0..3) ------------------------------------------------------------
+    // scale and shift of this lane's channels: the same for every chunk, requested once
+    f32x4_t psc[4], psh[4];
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      const int kk = tile_n * BN + wave_n * 32 + g * 8 + lhalf * 4;
+      psc[g] = *(const f32x4_t*)(a.scale + kk);
+      psh[g] = *(const f32x4_t*)(a.shift + kk);
+    }
+    // ---- pointwise GEMM of the block, 64 positions x 64 channels per chunk over all input channels, and the pointwise
+    // chain's epilogue into the LDS block: lane = position wave_m*32 + l31, channels wave_n*32 + 8*g + 4*lhalf + (0..3)
+    pw_gemm_phase<T>(a, tile_n * BN, s_op, (npos + BM - 1) / BM, [&](int mc, int row) -> long long {
+      const int m = mc * BM + row;
+      if (m >= npos) return -1;
+      const int py = m / wv, px = m - py * wv;
+      return (long long)n * a.in_sN + (long long)(y_lo + py) * a.in_sH + (long long)(x_lo + px) * a.in_sW;
+    }, [&](int mc, const f32x16_t& acc) {
       const int m = mc * BM + wave_m * 32 + l31;
       if (m < npos) {
         const int py = m / wv, px = m - py * wv;
@@ -190,8 +217,8 @@ __global__ __launch_bounds__(NT) void pwdw_kernel(const ConvArgs a) {
         const float lo = a.relu ? 0.f : -3.4028235e38f;
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
-          const int c = wave_n * 32 + g * 8 + lhalf * 4, kk = tile_n * BN + c;
-          const f32x4_t sc = *(const f32x4_t*)(a.scale + kk), sh = *(const f32x4_t*)(a.shift + kk);
+          const int c = wave_n * 32 + g * 8 + lhalf * 4;
+          const f32x4_t sc = psc[g], sh = psh[g];
           float y[4];
 #pragma unroll
           for (int e = 0; e < 4; ++e) y[e] = fmx(acc[4 * g + e] * sc[e] + sh[e], lo);
@@ -205,7 +232,7 @@ __global__ __launch_bounds__(NT) void pwdw_kernel(const ConvArgs a) {
           }
         }
       }
-    }
+    });
     __syncthreads();                                               // the block is complete
 
     // ---- depthwise chain out of the block: one thread = one 16-byte channel group of one output pixel --------
@@ -348,14 +375,20 @@ __global__ __launch_bounds__(NT) void fire_kernel(const ConvArgs a) {
       for (int i = tid; i < PH * PWd * (SQP / 16); i += NT) *(u32x4_t*)(s_sq + i * 16) = z;
     }
     // ---- phase 1: the squeeze chain of the block, into LDS -------------------------------------------------
-    for (int mc = 0; mc * 64 < npos; ++mc) {
-      f32x16_t acc;
-      pw_gemm_chunk<T>(a, 0, s_b, [&](int row) -> long long {
-        const int m = mc * 64 + row;
-        if (m >= npos) return -1;
-        const int py = m / wv, px = m - py * wv;
-        return (long long)n * a.in_sN + (long long)(y_lo + py) * a.in_sH + (long long)(x_lo + px) * a.in_sW;
-      }, acc);
+    // (scale and shift of this lane's channels are the same for every chunk: requested once)
+    f32x4_t qsc[4], qsh[4];
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      const int c = wave_n * 32 + g * 8 + lhalf * 4;
+      qsc[g] = *(const f32x4_t*)(a.scale + (c < S ? c : 0));
+      qsh[g] = *(const f32x4_t*)(a.shift + (c < S ? c : 0));
+    }
+    pw_gemm_phase<T>(a, 0, s_b, (npos + 63) / 64, [&](int mc, int row) -> long long {
+      const int m = mc * 64 + row;
+      if (m >= npos) return -1;
+      const int py = m / wv, px = m - py * wv;
+      return (long long)n * a.in_sN + (long long)(y_lo + py) * a.in_sH + (long long)(x_lo + px) * a.in_sW;
+    }, [&](int mc, const f32x16_t& acc) {
       const int m = mc * 64 + wave_m * 32 + l31;
       if (m < npos) {
         const int py = m / wv, px = m - py * wv;
@@ -365,7 +398,7 @@ __global__ __launch_bounds__(NT) void fire_kernel(const ConvArgs a) {
         for (int g = 0; g < 4; ++g) {
           const int c = wave_n * 32 + g * 8 + lhalf * 4;
           if (c < S) {
-            const f32x4_t sc = *(const f32x4_t*)(a.scale + c), sh = *(const f32x4_t*)(a.shift + c);
+            const f32x4_t sc = qsc[g], sh = qsh[g];
             float y[4];
 #pragma unroll
             for (int e = 0; e < 4; ++e) y[e] = fmx(acc[4 * g + e] * sc[e] + sh[e], lo);
@@ -380,7 +413,7 @@ __global__ __launch_bounds__(NT) void fire_kernel(const ConvArgs a) {
           }
         }
       }
-    }
+    });
     __syncthreads();                                               // the block is complete, the GEMM stages are free
 
     // ---- phase 2: this workgroup's expand tiles -----------------------------------------------------------
