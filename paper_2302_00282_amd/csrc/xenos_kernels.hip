@@ -2003,13 +2003,28 @@ __global__ __launch_bounds__(SL_NT, 2) void stem_lds_kernel(const ConvArgs a) {
         float m[8];
 #pragma unroll
         for (int e = 0; e < 8; ++e) m[e] = -INFINITY;
-        for (int i = 0; i < a.pk; ++i)
-          for (int j = 0; j < a.pk; ++j) {
+        if (a.pk == 3) {
+          // (all nine reads of the window before the first maximum: one LDS latency, not nine)
+          u32x4_t wv9[9];
+#pragma unroll
+          for (int t9 = 0; t9 < 9; ++t9)
+            wv9[t9] = *(const u32x4_t*)(s_stage + ((wy * a.ps + t9 / 3) * CW + wx * a.ps + t9 % 3) * SPITCH + ch * 16);
+#pragma unroll
+          for (int t9 = 0; t9 < 9; ++t9) {
             float v[8];
-            Tr<bf16_t>::unpack(*(const u32x4_t*)(s_stage + ((wy * a.ps + i) * CW + wx * a.ps + j) * SPITCH + ch * 16), v);
+            Tr<bf16_t>::unpack(wv9[t9], v);
 #pragma unroll
             for (int e = 0; e < 8; ++e) m[e] = fmx_raw(m[e], v[e]);
           }
+        } else {
+          for (int i = 0; i < a.pk; ++i)
+            for (int j = 0; j < a.pk; ++j) {
+              float v[8];
+              Tr<bf16_t>::unpack(*(const u32x4_t*)(s_stage + ((wy * a.ps + i) * CW + wx * a.ps + j) * SPITCH + ch * 16), v);
+#pragma unroll
+              for (int e = 0; e < 8; ++e) m[e] = fmx_raw(m[e], v[e]);
+            }
+        }
         *(u32x4_t*)((unsigned char*)a.out + ((long long)n * a.out_sN + (long long)(py * a.PW + px) * a.out_sP) * 2 + ch * 16) = Tr<bf16_t>::pack(m);
       }
     } else {

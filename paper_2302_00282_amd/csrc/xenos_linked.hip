@@ -512,16 +512,36 @@ __global__ __launch_bounds__(NT) void fire_kernel(const ConvArgs a) {
             float mx[CE];
 #pragma unroll
             for (int e = 0; e < CE; ++e) mx[e] = -INFINITY;
-            for (int r = 0; r < a.pk; ++r)
-              for (int c = 0; c < a.pk; ++c) {
-                const int cy = qy * a.ps + r, cx = qx * a.ps + c;
-                const int oy = oy0 + cy, ox = ox0 + cx;
-                if (oy < 0 || oy >= a.H || ox < 0 || ox >= a.W) continue;
+            if (a.pk == 3) {
+              // all nine reads of the window are issued before the first maximum (elements outside the map read the
+              // window's first element, which is inside, once more): as a loop over rows and columns the stage paid one
+              // LDS latency per element, 3 of the 21 us of a pooled module's workgroup at batch 32
+              u32x4_t wv9[9];
+#pragma unroll
+              for (int t9 = 0; t9 < 9; ++t9) {
+                const int cy = qy * a.ps + t9 / 3, cx = qx * a.ps + t9 % 3;
+                const bool in = oy0 + cy < a.H && ox0 + cx < a.W;   // (no padding: windows start inside the map)
+                wv9[t9] = *(const u32x4_t*)(s_cb + (in ? cy * CW + cx : qy * a.ps * CW + qx * a.ps) * CBP + cg * 16);
+              }
+#pragma unroll
+              for (int t9 = 0; t9 < 9; ++t9) {
                 float x[CE];
-                tr::unpack(*(const u32x4_t*)(s_cb + (cy * CW + cx) * CBP + cg * 16), x);
+                tr::unpack(wv9[t9], x);
 #pragma unroll
                 for (int e = 0; e < CE; ++e) mx[e] = fmx_raw(mx[e], x[e]);
               }
+            } else {
+              for (int r = 0; r < a.pk; ++r)
+                for (int c = 0; c < a.pk; ++c) {
+                  const int cy = qy * a.ps + r, cx = qx * a.ps + c;
+                  const int oy = oy0 + cy, ox = ox0 + cx;
+                  if (oy < 0 || oy >= a.H || ox < 0 || ox >= a.W) continue;
+                  float x[CE];
+                  tr::unpack(*(const u32x4_t*)(s_cb + (cy * CW + cx) * CBP + cg * 16), x);
+#pragma unroll
+                  for (int e = 0; e < CE; ++e) mx[e] = fmx_raw(mx[e], x[e]);
+                }
+            }
             *(u32x4_t*)((T*)a.fire_out[which] + (long long)n * a.fire_sN[which] + (long long)(gy * a.PW + gx) * a.fire_sP[which] + k0) = tr::pack(mx);
           }
         }
