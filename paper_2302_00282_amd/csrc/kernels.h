@@ -78,6 +78,7 @@ struct ConvArgs {
   const float* scale;    // folded per-channel scale [Kout_pad] (1 where no BN)
   const float* shift;    // folded per-channel shift [Kout_pad]
   const void* res;       // residual (NHWC view, compute type) or nullptr
+  const void* zeros;     // 256 bytes of zeros in device memory: what a masked 16-byte load reads (dwpw_kernel)
   void* out;
   const int32_t* ktab;   // scalar loader only: per reduction index {offset, (r<<16)|s}
   int N, C, H, W;

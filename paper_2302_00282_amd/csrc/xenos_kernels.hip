@@ -2170,28 +2170,34 @@ __global__ __launch_bounds__(NT, 3) void dwpw_kernel(const ConvArgs a) {
 #pragma unroll
         for (int e = 0; e < CE; ++e) d[e] = 0.f;
         if (a.dw_k == 3) {
-          // all tap loads of the pixel are issued before any is used (masked taps read a valid dummy address): one
-          // memory latency per pixel, not one per tap.  (Unrolling over several pixels and keeping the tap weights
-          // in registers was measured slower: the register pressure costs more than the extra loads in flight gain.)
+          // all tap loads of the pixel are issued before any is used: one memory latency per pixel, not one per tap.
+          // (Unrolling over several pixels and keeping the tap weights in registers was measured slower: the register
+          // pressure costs more than the extra loads in flight gain.)  The phase is bound by its vector instructions
+          // (460 per item, counted in the compiler's output, of which 72 multiplied masked taps by zero and 90 computed
+          // nine 64-bit addresses from scratch): a masked tap reads a block of zeros instead, and a tap's address is the
+          // window's first address plus a constant of the launch.
           u32x4_t xr[9], wr[9];
-          unsigned msk = 0;
+          const long long p00 = base + ((long long)ih0 * a.dw_W + iw0) * a.dw_sP + cc;   // (dereferenced only with an in-range tap)
+          const long long rowst = (long long)a.dw_W * a.dw_sP;
+          bool rok[3], cok[3];
+#pragma unroll
+          for (int j = 0; j < 3; ++j) {
+            rok[j] = valid && (unsigned)(ih0 + j) < (unsigned)a.dw_H;
+            cok[j] = (unsigned)(iw0 + j) < (unsigned)a.dw_W;
+          }
 #pragma unroll
           for (int t9 = 0; t9 < 9; ++t9) {
-            const int ih = ih0 + t9 / 3, iw = iw0 + t9 % 3;
-            const bool ok = valid && (unsigned)ih < (unsigned)a.dw_H && (unsigned)iw < (unsigned)a.dw_W;
-            const long long off = ok ? base + ((long long)ih * a.dw_W + iw) * a.dw_sP + cc : cc;
-            xr[t9] = *(const u32x4_t*)((const T*)a.in + off);
+            const T* px = (const T*)a.in + p00 + (t9 / 3) * rowst + (t9 % 3) * a.dw_sP;
+            xr[t9] = *(const u32x4_t*)((rok[t9 / 3] && cok[t9 % 3]) ? px : (const T*)a.zeros);
             wr[t9] = *(const u32x4_t*)((const T*)a.dw_w + (long long)t9 * a.C + cc);
-            msk |= (ok ? 1u : 0u) << t9;
           }
 #pragma unroll
           for (int t9 = 0; t9 < 9; ++t9) {
             float x[CE], w[CE];
             tr::unpack(xr[t9], x);
             tr::unpack(wr[t9], w);
-            const float keep = ((msk >> t9) & 1u) ? 1.f : 0.f;
 #pragma unroll
-            for (int e = 0; e < CE; ++e) d[e] = fmaf(x[e] * keep, w[e], d[e]);
+            for (int e = 0; e < CE; ++e) d[e] = fmaf(x[e], w[e], d[e]);
           }
         } else {
           for (int t9 = 0; t9 < a.dw_k * a.dw_k; ++t9) {
@@ -2335,7 +2341,7 @@ static int launch_dwpw_t(const ConvArgs& a, hipStream_t st) {
   if (a.mode != M_FLAT || a.has_res || a.pool != POOL_NONE || (!a.vec_out && !raw) || (a.ksplit >= 1 && !raw) || a.kchunk || a.R != 1 || a.S != 1 || a.stride != 1 || a.pad != 0 ||
       a.C % CE != 0 || a.K % CE != 0 || a.dw_panel < BKE || a.dw_panel % BKE != 0 || lds > 160 * 1024 || a.dw_k < 1 ||
       a.tiles_m != (a.M_total + 63) / 64 || a.tiles_n != (a.K + 63) / 64 || a.ntiles != a.tiles_m * a.tiles_n || a.grid < 1 ||
-      a.Kred_pad < (a.C + BKE - 1) / BKE * BKE || !a.dw_w || !a.dw_scale || !a.dw_shift)
+      a.Kred_pad < (a.C + BKE - 1) / BKE * BKE || !a.dw_w || !a.dw_scale || !a.dw_shift || !a.zeros || ((uintptr_t)a.zeros & 15))
     return (int)hipErrorInvalidValue;
   static int raised = 0;
   if (lds > raised) {

@@ -140,6 +140,7 @@ struct xenos_plan {
   xenos_tensor_desc in{}, out{};
   int dt = DT_F32, esz = 4, ce = 4;
   int n_linked_shuffles = 0;   // channel shuffles realised as the store order of their concat (no pass of their own)
+  size_t zero_off = 0;         // 256 zero bytes at the start of the weight image
   std::vector<Buffer> bufs;
   std::vector<View> views;
   std::vector<Step> steps;
@@ -830,6 +831,7 @@ struct Planner {
     p.dt = p.opts.compute == XENOS_BF16 ? DT_BF16 : DT_F32;
     p.esz = p.dt == DT_BF16 ? 2 : 4;
     p.ce = 16 / p.esz;
+    p.zero_off = wpush(nullptr, 256);      // (new bytes of the image are zero)
     build_nodes();
     const int nn = (int)nodes.size();
     tview.assign(nn + 1, -1);
@@ -2132,6 +2134,7 @@ xenos_status launch_step(xenos_plan& p, const Step& s, const void* d_in_, void* 
       a.in = view_ptr(p, s.v_in, mem);
       a.out = (void*)view_ptr(p, s.v_out, mem);
       a.res = s.v_in2 >= 0 ? view_ptr(p, s.v_in2, mem) : nullptr;
+      a.zeros = wb + p.zero_off;
       a.w = wb + s.w_off;
       a.scale = (const float*)(wb + s.scale_off);
       a.shift = (const float*)(wb + s.shift_off);
