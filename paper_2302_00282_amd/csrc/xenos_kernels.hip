@@ -2732,6 +2732,34 @@ __global__ __launch_bounds__(NT) void pool_vec_kernel(const PoolArgs a) {
 #pragma unroll
     for (int e = 0; e < CE; ++e) { mx[e] = -INFINITY; sum[e] = 0.f; }
     int cnt = 0, cntp = 0;
+    // windows of 2x2 and 3x3: every element of the window is requested before the first is used (elements outside the map
+    // read the image's first pixel and are skipped); as a loop over rows and columns the pass paid one memory latency per
+    // element of the window
+    auto window = [&](auto kc) __attribute__((always_inline)) {
+      constexpr int K = decltype(kc)::value;
+      u32x4_t wv[K * K];
+      unsigned in = 0;
+#pragma unroll
+      for (int t = 0; t < K * K; ++t) {
+        const int ih = oh * a.s - a.p + t / K, iw = ow * a.s - a.p + t % K;
+        if (ih < a.H + a.p && iw < a.W + a.p) ++cntp;
+        const bool ok = ih >= 0 && ih < a.H && iw >= 0 && iw < a.W;
+        in |= (ok ? 1u : 0u) << t;
+        wv[t] = *(const u32x4_t*)(ib + (ok ? ((long long)ih * a.W + iw) * a.in_sP : 0));
+      }
+#pragma unroll
+      for (int t = 0; t < K * K; ++t) {
+        if (!((in >> t) & 1u)) continue;
+        float v[CE];
+        tr::unpack(wv[t], v);
+#pragma unroll
+        for (int e = 0; e < CE; ++e) { mx[e] = fmx_raw(mx[e], v[e]); sum[e] += v[e]; }
+        ++cnt;
+      }
+    };
+    if (a.k == 3) window(std::integral_constant<int, 3>{});
+    else if (a.k == 2) window(std::integral_constant<int, 2>{});
+    else
     for (int i = 0; i < a.k; ++i)
       for (int j = 0; j < a.k; ++j) {
         const int ih = oh * a.s - a.p + i, iw = ow * a.s - a.p + j;
