@@ -197,10 +197,13 @@ xenos_status xenos_run_chain(xenos_plan* plan, int chain, const void* d_input, v
 /* Device probes for the measurement report (no part of the inference path): what this GPU attains, to put beside the
  * published peaks when a kernel's roofline fraction is quoted.  Both enqueue ONE kernel on hip_stream, asynchronously;
  * the caller times it (events on the same stream).  d_out is scratch of at least 8192 * hw->num_cu bytes.
- * xenos_probe_mfma: every compute unit runs `iters` rounds of eight independent bf16 MFMA (32x32x16) accumulations with no
- * memory instruction in the loop; *flops (host, may be NULL) receives the floating-point operations of the launch.
+ * xenos_probe_mfma: every compute unit runs `iters` rounds (rounded up to a multiple of four) of eight independent bf16
+ * MFMA (32x32x16) accumulations with no memory instruction in the loop; *flops (host, may be NULL) receives the
+ * floating-point operations of the launch.  `data` chooses the operand values, on which the sustained clock depends:
+ * 0 = a few small values per lane, 1 = pseudo-random dense operands, 2 = pseudo-random with half of the pixel operand
+ * zero (activations behind a ReLU); any other value is XENOS_EINVAL.
  * xenos_probe_read: streams `bytes` (a multiple of 16, 16-byte aligned) of device memory through 16-byte loads. */
-xenos_status xenos_probe_mfma(const xenos_hw_info* hw, void* d_out, size_t out_bytes, int iters, void* hip_stream, double* flops);
+xenos_status xenos_probe_mfma(const xenos_hw_info* hw, void* d_out, size_t out_bytes, int iters, int data, void* hip_stream, double* flops);
 xenos_status xenos_probe_read(const xenos_hw_info* hw, const void* d_in, size_t bytes, void* d_out, size_t out_bytes, void* hip_stream);
 
 /* Releases a graph or a plan (either handle type; NULL is ignored).  A plan holds a reference to

@@ -199,7 +199,7 @@ bool conv_cfg_has_scalar_loader(int cfg);
 bool conv_cfg_has_dw_prologue(int cfg, int mode);
 size_t dwpw_lds_bytes(int panel_channels, int esz);   // LDS of the depthwise-panel kernel for a panel of that many channels
 // device probes for the roofline denominators (xenos_kernels.hip)
-int launch_probe_mfma(void* d_out, int num_cu, int iters, void* stream, double* flops);
+int launch_probe_mfma(void* d_out, int num_cu, int iters, int data, void* stream, double* flops);
 int launch_probe_read(const void* d_in, size_t bytes, void* d_out, int num_cu, void* stream);
 size_t probe_out_bytes(int num_cu);
 // pointwise -> depthwise kernel (xenos_linked.hip)

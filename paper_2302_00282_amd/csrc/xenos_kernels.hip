@@ -2832,20 +2832,42 @@ int launch_cvt(const CvtArgs& a, int dtype, void* stream) {
 // ---------------------------------------------------------------------------------------------
 constexpr int PROBE_WG_PER_CU = 2;
 
-__global__ __launch_bounds__(NT) void probe_mfma_kernel(float* out, int iters) {
+// `data` selects the operand values, which decide the rate: the chip lowers its clock with the switching activity of the
+// MFMA inputs.  0 = a handful of small values per lane (little toggling), 1 = pseudo-random dense operands (random sign,
+// mantissa and a 2-bit exponent spread, the weight operand 16 times smaller), 2 = the same with every second pixel-operand
+// element zero, as activations behind a ReLU are.  Four fragments per operand rotate through eight accumulators.
+__global__ __launch_bounds__(NT) void probe_mfma_kernel(float* out, int iters, int data) {
   const int lane = threadIdx.x & 63;
-  // operands that differ per lane, finite and small; eight independent accumulators keep the pipe full
-  bf16x8_t fa, fb;
+  bf16x8_t fa[4], fb[4];
 #pragma unroll
-  for (int e = 0; e < 8; ++e) { fa[e] = (__bf16)(0.001f * (float)((lane + e) & 7)); fb[e] = (__bf16)(0.002f * (float)((lane * 3 + e) & 7)); }
+  for (int s = 0; s < 4; ++s)
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      if (data == 0) {
+        fa[s][e] = (__bf16)(0.001f * (float)((lane + e + s) & 7));
+        fb[s][e] = (__bf16)(0.002f * (float)((lane * 3 + e + s) & 7));
+      } else {
+        uint32_t h = (uint32_t)lane * 2654435761u ^ (uint32_t)(s * 8 + e + 1) * 0x9E3779B9u;
+        h ^= h >> 16; h *= 0x7feb352du; h ^= h >> 15; h *= 0x846ca68bu; h ^= h >> 16;
+        const uint32_t sign = h & 1u, mant = (h >> 1) & 0x7fu, ex = 124u + ((h >> 8) & 3u);
+        const bool zero = data == 2 && ((h >> 12) & 1u);
+        const uint16_t va = zero ? (uint16_t)0 : (uint16_t)((sign << 15) | (ex << 7) | mant);
+        const uint32_t g = h * 0x2c1b3c6du + 0x297a2d39u;
+        const uint16_t vb = (uint16_t)(((g & 1u) << 15) | ((120u + ((g >> 8) & 3u)) << 7) | ((g >> 1) & 0x7fu));
+        fa[s][e] = __builtin_bit_cast(__bf16, va);
+        fb[s][e] = __builtin_bit_cast(__bf16, vb);
+      }
+    }
   f32x16_t acc[8];
 #pragma unroll
   for (int j = 0; j < 8; ++j)
 #pragma unroll
     for (int e = 0; e < 16; ++e) acc[j][e] = 0.f;
-  for (int i = 0; i < iters; ++i) {
+  for (int i = 0; i < iters; i += 4) {
 #pragma unroll
-    for (int j = 0; j < 8; ++j) acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, fb, acc[j], 0, 0, 0);
+    for (int k = 0; k < 4; ++k)
+#pragma unroll
+      for (int j = 0; j < 8; ++j) acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[(j + k) & 3], fa[((j >> 2) + k) & 3], acc[j], 0, 0, 0);
   }
   float sum = 0.f;
 #pragma unroll
@@ -2870,10 +2892,11 @@ __global__ __launch_bounds__(NT) void probe_read_kernel(const u32x4_t* in, size_
 
 // MFMA loop on every compute unit: returns the floating-point operations the launch performs through *flops.
 // d_out must hold probe_out_bytes(num_cu) bytes.
-int launch_probe_mfma(void* d_out, int num_cu, int iters, void* stream, double* flops) {
-  if (!d_out || num_cu < 1 || iters < 1) return (int)hipErrorInvalidValue;
+int launch_probe_mfma(void* d_out, int num_cu, int iters, int data, void* stream, double* flops) {
+  if (!d_out || num_cu < 1 || iters < 1 || data < 0 || data > 2) return (int)hipErrorInvalidValue;
+  iters = (iters + 3) / 4 * 4;                                     // (the loop runs four rounds per turn)
   const int grid = num_cu * PROBE_WG_PER_CU;
-  hipLaunchKernelGGL(probe_mfma_kernel, dim3(grid), dim3(NT), 0, (hipStream_t)stream, (float*)d_out, iters);
+  hipLaunchKernelGGL(probe_mfma_kernel, dim3(grid), dim3(NT), 0, (hipStream_t)stream, (float*)d_out, iters, data);
   if (flops) *flops = (double)grid * (NT / 64) * (double)iters * 8.0 * (2.0 * 32 * 32 * 16);
   return (int)hipGetLastError();
 }

@@ -2564,10 +2564,10 @@ xenos_status xenos_run_chain(xenos_plan* plan, int chain, const void* d_input, v
   return launch_step(*plan, plan->steps[chain], d_input, d_output, hip_stream);
 }
 
-xenos_status xenos_probe_mfma(const xenos_hw_info* hw, void* d_out, size_t out_bytes, int iters, void* hip_stream, double* flops) {
-  if (!hw || hw->num_cu <= 0 || !d_out || iters < 1) return fail(XENOS_EINVAL, "xenos_probe_mfma: bad argument");
+xenos_status xenos_probe_mfma(const xenos_hw_info* hw, void* d_out, size_t out_bytes, int iters, int data, void* hip_stream, double* flops) {
+  if (!hw || hw->num_cu <= 0 || !d_out || iters < 1 || data < 0 || data > 2) return fail(XENOS_EINVAL, "xenos_probe_mfma: bad argument");
   if (out_bytes < probe_out_bytes(hw->num_cu)) return fail(XENOS_EINVAL, "xenos_probe_mfma: d_out must hold %zu bytes", probe_out_bytes(hw->num_cu));
-  const int rc = launch_probe_mfma(d_out, hw->num_cu, iters, hip_stream, flops);
+  const int rc = launch_probe_mfma(d_out, hw->num_cu, iters, data, hip_stream, flops);
   if (rc != 0) return fail(XENOS_EDEVICE, "xenos_probe_mfma: launch failed: %s", hipGetErrorString((hipError_t)rc));
   return XENOS_OK;
 }

@@ -86,7 +86,7 @@ def lib():
         L.xenos_run_static.argtypes = [vp, vp, vp, vp]
         L.xenos_run_chain.argtypes = [vp, C.c_int, vp, vp, vp]
         L.xenos_plan_tune.argtypes = [vp, vp, vp, vp, C.c_int, C.POINTER(C.c_int)]
-        L.xenos_probe_mfma.argtypes = [C.POINTER(HwInfo), vp, C.c_size_t, C.c_int, vp, C.POINTER(C.c_double)]
+        L.xenos_probe_mfma.argtypes = [C.POINTER(HwInfo), vp, C.c_size_t, C.c_int, C.c_int, vp, C.POINTER(C.c_double)]
         L.xenos_probe_read.argtypes = [C.POINTER(HwInfo), vp, C.c_size_t, vp, C.c_size_t, vp]
         L.xenos_destroy.argtypes = [vp]
         L.xenos_destroy.restype = None
@@ -171,11 +171,12 @@ def xenos_run_chain(plan: int, chain: int, d_input: int, d_output: int, stream: 
     _check(lib().xenos_run_chain(plan, chain, d_input, d_output, stream))
 
 
-def xenos_probe_mfma(d_out: int, out_bytes: int, iters: int, stream: int = 0, hw: Optional[dict] = None) -> float:
-    """Enqueues the MFMA-only loop; returns the floating-point operations of the launch."""
+def xenos_probe_mfma(d_out: int, out_bytes: int, iters: int, stream: int = 0, hw: Optional[dict] = None, data: int = 0) -> float:
+    """Enqueues the MFMA-only loop (data: 0 small structured operands, 1 random dense, 2 random with half of the pixel
+    operand zero); returns the floating-point operations of the launch."""
     hwi = HwInfo(**(hw or MI355X))
     f = C.c_double(0.0)
-    _check(lib().xenos_probe_mfma(C.byref(hwi), d_out, out_bytes, iters, stream, C.byref(f)))
+    _check(lib().xenos_probe_mfma(C.byref(hwi), d_out, out_bytes, iters, data, stream, C.byref(f)))
     return f.value
 
 
