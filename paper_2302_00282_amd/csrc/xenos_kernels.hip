@@ -1585,12 +1585,18 @@ constexpr int FC_NW = 4, FC_NT = 64 * FC_NW, FC_BN = 32 * FC_NW, FC_DEPTH = 4;
 __global__ __launch_bounds__(FC_NT, 2) void fc_stream_kernel(const ConvArgs a) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l31 = lane & 31, lhalf = lane >> 5;
-  const int tile_n = blockIdx.x % a.tiles_n, z = blockIdx.x / a.tiles_n;
+  // Reduction shared out across workgroups (a.ksplit >= 1: a workgroup owns 128 channels, a wavefront 32 of them, and share z
+  // of the steps; raw sums go to the summing pass), or, for a short reduction (a.ksplit < 1), across the four wavefronts of
+  // a workgroup that owns 32 channels: every wavefront then has all its steps in flight at once (one memory round trip
+  // instead of one per FC_DEPTH steps), the four partial sums meet in LDS and the chain's epilogue runs here.
+  const bool direct = a.ksplit < 1;
+  const int tile_n = direct ? 0 : blockIdx.x % a.tiles_n, z = direct ? wave : blockIdx.x / a.tiles_n;
   const int nsteps_all = a.Kred_pad / 64;
-  const int s0 = z * a.steps_per_split;
-  const int ns = nsteps_all - s0 < a.steps_per_split ? nsteps_all - s0 : a.steps_per_split;
-  if (ns <= 0) return;
-  const int k0 = tile_n * FC_BN + wave * 32;                       // first output channel of this wavefront
+  const int sps = direct ? (nsteps_all + FC_NW - 1) / FC_NW : a.steps_per_split;
+  const int s0 = z * sps;
+  const int ns = nsteps_all - s0 < sps ? nsteps_all - s0 : sps;
+  if (ns <= 0 && !direct) return;                                  // (uniform per workgroup)
+  const int k0 = direct ? (int)blockIdx.x * 32 : tile_n * FC_BN + wave * 32;   // first output channel of this wavefront
   // weights: [32-channel block][step][k-group][lane][8 elements], the order in which this wavefront loads them
   const unsigned char* wp = (const unsigned char*)a.w + ((((long long)(k0 / 32) * nsteps_all + s0) * 4 * 64 + lane) * 16);
   // activations: row m of the flattened input (reduction index = position in the NHWC tensor of an image)
@@ -1609,8 +1615,10 @@ __global__ __launch_bounds__(FC_NT, 2) void fc_stream_kernel(const ConvArgs a) {
   f32x16_t acc;
 #pragma unroll
   for (int e = 0; e < 16; ++e) acc[e] = 0.f;
+  if (ns > 0) {                                                    // (a wavefront of the direct form may have no step)
 #pragma unroll
-  for (int d = 0; d < FC_DEPTH; ++d) fetch(d, d);
+    for (int d = 0; d < FC_DEPTH; ++d) fetch(d, d);
+  }
   for (int s = 0; s < ns; s += FC_DEPTH) {
 #pragma unroll
     for (int d = 0; d < FC_DEPTH; ++d) {
@@ -1623,14 +1631,23 @@ __global__ __launch_bounds__(FC_NT, 2) void fc_stream_kernel(const ConvArgs a) {
     }
   }
   // accumulator rows = channels, columns = images: this lane holds 4 groups of 4 consecutive channels of image l31
-  if (a.ksplit < 1) {
-    // short reduction, not shared out: the chain's epilogue runs here and no summing pass follows
+  if (direct) {
+    // the four wavefronts' sums of the same 32 channels x 32 images, added in wavefront order; wavefront w finishes
+    // accumulator elements 4w .. 4w + 3 of every lane
+    __shared__ float s_red[FC_NW][16][64];
+#pragma unroll
+    for (int e = 0; e < 16; ++e) s_red[wave][e][lane] = acc[e];
+    __syncthreads();
     if (l31 < a.M_total) {
 #pragma unroll
-      for (int e = 0; e < 16; ++e) {
+      for (int q = 0; q < 4; ++q) {
+        const int e = wave * 4 + q;
+        float sum = s_red[0][e][lane];
+#pragma unroll
+        for (int w = 1; w < FC_NW; ++w) sum += s_red[w][e][lane];
         const int k = k0 + (e >> 2) * 8 + lhalf * 4 + (e & 3);
         if (k < a.K) {
-          float v = acc[e] * a.scale[k] + a.shift[k];
+          float v = sum * a.scale[k] + a.shift[k];
           if (a.relu) v = fmx(v, 0.f);
           const long long o = (long long)l31 * a.out_sN + (long long)k * a.out_sK;
           if (a.out_f32) ((float*)a.out)[o] = v; else ((uint16_t*)a.out)[o] = f2bf(v);
@@ -1655,7 +1672,7 @@ static int launch_fc(const ConvArgs& a, int dtype, hipStream_t st) {
       a.steps_per_split < 1 || a.tiles_n != (a.K + FC_BN - 1) / FC_BN ||
       (a.ksplit >= 1 && ((long long)a.ksplit * a.steps_per_split < a.Kred_pad / 64 || !a.part || a.part_ld < a.tiles_n * FC_BN || a.part_ld % 4 != 0 ||
                          ((uintptr_t)a.part & 15) != 0 || a.grid != a.tiles_n * a.ksplit)) ||
-      (a.ksplit < 1 && (a.steps_per_split < a.Kred_pad / 64 || a.grid != a.tiles_n || a.has_res || !a.out || !a.scale || !a.shift)))
+      (a.ksplit < 1 && (a.steps_per_split < a.Kred_pad / 64 || a.grid != (a.K + 31) / 32 || a.has_res || !a.out || !a.scale || !a.shift)))
     return (int)hipErrorInvalidValue;
   hipLaunchKernelGGL(fc_stream_kernel, dim3(a.grid), dim3(FC_NT), 0, st, a);
   return (int)hipGetLastError();

@@ -1738,7 +1738,8 @@ struct Planner {
             st.cands.clear();
             st.cfg = kFcCfg; st.lds = 0;
             a.ksplit = 0; a.steps_per_split = nsteps;
-            a.tiles_m = 1; a.tiles_n = fc_tiles; a.ntiles = fc_tiles; a.xcd_m = 1; a.grid = fc_tiles;
+            // (a workgroup per 32 channels, the steps dealt to its four wavefronts)
+            a.tiles_m = 1; a.tiles_n = fc_tiles; a.ntiles = fc_tiles; a.xcd_m = 1; a.grid = (K + 31) / 32;
           } else
           if (st.fc_stream || ks >= 4 || st.gap_finish) {
             const int spk = (nsteps + ks - 1) / ks;

@@ -331,11 +331,13 @@ def test_first_two_3x3_convolutions_linked_on_chip(h, w, n, c, pool, bn):
     assert all(ch.get("loader") != "pair" for ch in i3["chains"])
 
 
-@pytest.mark.parametrize("n,c,hw,k1,k2", [(32, 64, 7, 200, 72), (5, 512, 1, 1024, 40), (1, 512, 2, 136, 24), (17, 8, 8, 1088, 1000)])
+@pytest.mark.parametrize("n,c,hw,k1,k2", [(32, 64, 7, 200, 72), (5, 512, 1, 1024, 40), (1, 512, 2, 136, 24), (17, 8, 8, 1088, 1000), (3, 64, 3, 640, 24)])
 def test_fully_connected_streaming_kernel(n, c, hw, k1, k2):
     # FC chains over at most 32 images (bf16): the weight-streaming kernel (128 channels per workgroup, the reduction shared
     # out over workgroups) writes fp32 shares, the summing pass applies bias / ReLU.  Two FC layers in a row: the second
     # reads the first one's N x 1 x 1 x K output; channel counts that are not multiples of 128 leave ragged channel tiles.
+    # Reductions of at most 16 steps of 64 take the direct form (a workgroup per 32 channels, the steps dealt to its four
+    # wavefronts, no summing pass): 8 and 16 steps, and 9 and 10 steps, which leave the last wavefront none or one.
     b = wg.builder("fcs", (n, c, hw, hw), 29, nonzero_bias=True)
     t = b.cbr(0, c, 3, 1, 1, name="c0")
     t = b.relu(b.fc(t, k1, "fc1"))
