@@ -1159,10 +1159,11 @@ struct Planner {
   }
 
   // ---- link level 3, Fire module (Table 1, Conv1x1 -> Conv3x3; Section 4.1 last paragraph) -----------------------
-  // squeeze = conv 1x1 / stride 1 / pad 0 with at most 64 output channels whose chain output is read by exactly two dense
-  // convolutions, one 1x1 / pad 0 and one 3x3 / pad 1 (stride 1), each a plain chain (bias / bn / relu) that may end in
-  // the SAME max-pooling of 2- or 3-wide windows at stride 2 without padding (the pooling the link pass moved in front
-  // of their concat); both outputs take 16-byte stores.
+  // squeeze = conv 1x1 / stride 1 / pad 0 with at most 64 output channels whose chain output is read by dense convolutions
+  // only: one 1x1 / pad 0 and one 3x3 / pad 1 (stride 1) (a Fire module), or one of the two alone (a plain ConvX -> ConvY
+  // pair); each a plain chain (bias / bn / relu) that may end in a max-pooling of 2- or 3-wide windows at stride 2 without
+  // padding (of a module: the SAME pooling, the one the link pass moved in front of their concat); the outputs take
+  // 16-byte stores.
   struct FireMatch { int e[2] = {-1, -1}; };
   bool fire_consumers(int i, FireMatch* fm) const {
     if (p.opts.link < 3 || p.opts.tile != 0 || node_step[i] >= 0) return false;
@@ -1176,7 +1177,7 @@ struct Planner {
     // recomputed at the fp32 MFMA rate; measured on the SqueezeNet graph at batch 32, 0.67 against 0.74 ms)
     if (p.dt == DT_F32 && (long long)is.n * is.h * is.w > 4096) return false;
     const ChainWalk w = walk_chain(i);
-    if (w.has_res || w.pool_node >= 0 || w.cur == out_tid || placed.count(w.cur) || fin.count(w.cur) || consumers[w.cur].size() != 2) return false;
+    if (w.has_res || w.pool_node >= 0 || w.cur == out_tid || placed.count(w.cur) || fin.count(w.cur) || (consumers[w.cur].size() != 2 && consumers[w.cur].size() != 1)) return false;
     int pool_src = -2;
     for (int c : consumers[w.cur]) {
       const Node& en = nodes[c];
@@ -1200,7 +1201,7 @@ struct Planner {
       if (we.cur == out_tid && !ext_is_internal(p.out)) return false;
       fm->e[which] = c;
     }
-    if (fm->e[0] < 0 || fm->e[1] < 0) return false;
+    if (fm->e[0] < 0 && fm->e[1] < 0) return false;
     const int pk = pool_src >= 0 ? g.ops[pool_src].d.kh : 0;
     return fire_lds_bytes(pk ? pk : 1, pk ? pk : 1, S, p.esz, pk ? 1 : 0) <= std::min<size_t>(p.hw.lds_bytes_per_cu, 160 * 1024);
   }
@@ -1289,6 +1290,7 @@ struct Planner {
     st.flops = 2.0 * is.n * is.h * is.w * (double)S * is.c;
     for (int which = 0; which < 2; ++which) {
       const int en = fm.e[which];
+      if (en < 0) { a.fire_E[which] = 0; a.fire_relu[which] = 0; continue; }   // (a pair: the module's other part does not exist)
       const GOp& eg = g.ops[nodes[en].src];
       const int E = desc(nodes[en]).out_c, taps = which ? 9 : 1, Epad = (E + 63) / 64 * 64;
       const ChainWalk we = walk_chain(en);
@@ -1314,12 +1316,13 @@ struct Planner {
         a.pool = POOL_MAX; a.pk = pd.kh; a.ps = pd.stride_h; a.pp = 0; a.PH = ps.h; a.PW = ps.w;
       }
       const int ov = out_view_for(we.cur, true);
-      if (which == 0) st.v_out = ov; else st.v_out2 = ov;
+      if (which == 0 || fm.e[0] < 0) st.v_out = ov;
+      if (which == 1) st.v_out2 = ov;
       const View& o = p.views[ov];
       if (o.sK != 1 || o.f32 || o.esz != p.esz || o.off % p.ce != 0 || o.sP % p.ce != 0 || o.sN % p.ce != 0)
         return fail(XENOS_EUNSUPPORTED, "%s: output of the Fire-module chain is not aligned", st.name.c_str());
       a.fire_sN[which] = o.sN; a.fire_sP[which] = o.sP;
-      if (which == 0) { a.out_sN = o.sN; a.out_sP = o.sP; a.out_sK = 1; a.vec_out = 1; }
+      if (which == 0 || fm.e[0] < 0) { a.out_sN = o.sN; a.out_sP = o.sP; a.out_sK = 1; a.vec_out = 1; }
       node_step[en] = sidx;
       for (int ab : we.absorbed) node_step[ab] = sidx;
       node_final[we.last] = 1;
@@ -2146,12 +2149,13 @@ xenos_status launch_step(xenos_plan& p, const Step& s, const void* d_in_, void* 
       a.dw_shift = s.dw_shift_off >= 0 ? (const float*)(wb + s.dw_shift_off) : nullptr;
       if (a.fire) {
         for (int e = 0; e < 2; ++e) {
-          a.fire_w[e] = wb + s.fire_w_off[e];
-          a.fire_scale[e] = (const float*)(wb + s.fire_scale_off[e]);
-          a.fire_shift[e] = (const float*)(wb + s.fire_shift_off[e]);
+          const bool has = a.fire_E[e] > 0;
+          a.fire_w[e] = has ? wb + s.fire_w_off[e] : nullptr;
+          a.fire_scale[e] = has ? (const float*)(wb + s.fire_scale_off[e]) : nullptr;
+          a.fire_shift[e] = has ? (const float*)(wb + s.fire_shift_off[e]) : nullptr;
         }
-        a.fire_out[0] = a.out;
-        a.fire_out[1] = (void*)view_ptr(p, s.v_out2, mem);
+        a.fire_out[0] = a.fire_E[0] > 0 ? a.out : nullptr;
+        a.fire_out[1] = a.fire_E[1] > 0 ? (void*)view_ptr(p, s.v_out2, mem) : nullptr;
       }
       rc = launch_conv(a, p.dt, s.cfg, s.scalar, stream);
       break;

@@ -583,14 +583,16 @@ static int launch_fire_t(const ConvArgs& a, hipStream_t st) {
   if (a.mode != M_FLAT || a.has_res || a.ksplit >= 1 || a.ileave || a.kchunk || a.pair || a.dw_panel || a.pwdw || a.dw_w ||
       a.R != 1 || a.S != 1 || a.stride != 1 || a.pad != 0 || a.C % CE != 0 || a.C < CE || a.Kred_pad < (a.C + BKE - 1) / BKE * BKE || a.Kred_pad % BKE != 0 ||
       a.K < 1 || a.K > 64 || (a.K * ESZ) % 32 != 0 || a.OH != a.H || a.OW != a.W ||
-      !a.fire_w[0] || !a.fire_w[1] || !a.fire_scale[0] || !a.fire_scale[1] || !a.fire_shift[0] || !a.fire_shift[1] || !a.fire_out[0] || !a.fire_out[1] ||
-      a.fire_E[0] < CE || a.fire_E[1] < CE || a.fire_E[0] % CE != 0 || a.fire_E[1] % CE != 0 ||
-      a.fire_sP[0] < a.fire_E[0] || a.fire_sP[1] < a.fire_E[1] || a.fire_sP[0] % CE != 0 || a.fire_sP[1] % CE != 0 ||
-      a.fire_sN[0] % CE != 0 || a.fire_sN[1] % CE != 0 || ((uintptr_t)a.fire_out[0] & 15) || ((uintptr_t)a.fire_out[1] & 15) ||
-      ((uintptr_t)a.fire_w[0] & 15) || ((uintptr_t)a.fire_w[1] & 15) ||
+      (a.fire_E[0] < 1 && a.fire_E[1] < 1) ||
       a.tiles_n < 1 || a.tiles_m != a.N * a.tiles_y * a.tiles_x || a.ntiles != a.tiles_m * a.tiles_n || a.grid < 1 ||
       a.in_sN < 0 || a.in_sH < 0 || a.in_sW < a.C)
     return (int)hipErrorInvalidValue;
+  for (int e = 0; e < 2; ++e) {   // a part with no channels does not exist (a ConvX -> ConvY pair instead of a module)
+    if (a.fire_E[e] == 0) continue;
+    if (!a.fire_w[e] || !a.fire_scale[e] || !a.fire_shift[e] || !a.fire_out[e] || a.fire_E[e] < CE || a.fire_E[e] % CE != 0 ||
+        a.fire_sP[e] < a.fire_E[e] || a.fire_sP[e] % CE != 0 || a.fire_sN[e] % CE != 0 || ((uintptr_t)a.fire_out[e] & 15) || ((uintptr_t)a.fire_w[e] & 15))
+      return (int)hipErrorInvalidValue;
+  }
   int ch, cw, pool_pos = 0;
   if (pool) {
     // max-pooling with windows of 2 or 3 at stride 2, no padding; every window starts inside the map

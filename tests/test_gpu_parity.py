@@ -508,6 +508,49 @@ def test_fire_module_linked_on_chip(h, w, c, s, e1, e3, n, pool, tail, compute):
 
 
 @pytest.mark.parametrize("compute", [0, 1])
+@pytest.mark.parametrize("h,w,c,s,k2,n,second,pool,tail", [(13, 13, 32, 16, 64, 2, 3, 0, "conv"), (27, 21, 64, 32, 72, 1, 3, 3, "conv"),
+                                                           (9, 30, 24, 48, 200, 3, 1, 0, "conv"), (14, 14, 128, 64, 256, 1, 3, 2, "out"),
+                                                           (12, 18, 40, 32, 136, 2, 1, 2, "conv"), (7, 7, 512, 64, 128, 1, 3, 0, "gap")])
+def test_conv1x1_to_conv_pair_linked_on_chip(h, w, c, s, k2, n, second, pool, tail, compute):
+    # link level 3, Table 1 ConvX -> ConvY with a single consumer: conv 1x1 (at most 64 channels) -> conv 3x3 / pad 1 or conv
+    # 1x1 [-> max-pooling] is ONE chain on the Fire-module kernel with one of its two parts absent; the intermediate tensor
+    # (+ halo for the 3x3) lives in LDS.
+    b = wg.builder("pair1x1", (n, c, h, w), 53, nonzero_bias=True)
+    x = b.cbr(0, c, 3, 1, 1, name="pre")
+    q = b.cbr(x, s, 1, name="first", bn=False)
+    t = b.cbr(q, k2, second, 1, second // 2, name="second", bn=(pool == 0))
+    if pool == 3:
+        t = b.maxpool(t, 3, 2, 0, ceil=1)
+    elif pool == 2:
+        t = b.maxpool(t, 2, 2)
+    fmt = {}
+    if tail == "conv":
+        t = b.cbr(t, 24, 1, name="post")
+    elif tail == "gap":
+        t = b.gap(t)
+    else:
+        fmt = dict(out_layout=1, out_dtype=compute)
+    g = b.finish(t)
+    ref = xo.forward(g)
+    y3, i3 = check(g, ref, compute=compute, link=3, **fmt)
+    y2, i2 = check(g, ref, compute=compute, link=2, **fmt)
+    fire = [ch for ch in i3["chains"] if ch.get("loader") == "fire"]
+    # (fp32: a 3x3 weight tile of 64 channels does not fit LDS; a global average is part of the second chain, which the
+    # kernel does not finish: such a pair stays two chains)
+    fits = (compute == 1 or s <= 48) and tail != "gap"
+    assert len(fire) == (1 if fits else 0)
+    if fits:
+        assert i3["n_chains"] == i2["n_chains"] - 1 and (fire[0]["pool"] != 0) == (pool != 0)
+        assert i3["hbm_bytes"] < i2["hbm_bytes"]
+    if not any(ch["kind"] == "splitk_finish" for ch in i3["chains"]):
+        y3s, _ = run_gpu(g, compute=compute, link=3, split=0, **fmt)
+        assert np.array_equal(y3, y3s)
+        y3m, _ = run_gpu(g, compute=compute, link=3, hw=dict(X_small=True), **fmt)
+        assert np.array_equal(y3, y3m)
+    check_chains(g, compute, link=3, **fmt)
+
+
+@pytest.mark.parametrize("compute", [0, 1])
 @pytest.mark.parametrize("rows,widths,residual", [(128, (512, 2048, 512), True), (1, (64, 256, 64), True), (33, (96, 200, 72), False),
                                                   (384, (128, 128, 128, 40), False), (7, (1024, 64, 1024), True), (200, (24, 136), False)])
 def test_matmul_chains(rows, widths, residual, compute):
