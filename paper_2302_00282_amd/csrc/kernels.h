@@ -207,6 +207,6 @@ int launch_pwdw(const ConvArgs& a, int dtype, void* stream);
 size_t pwdw_lds_bytes(int th, int tw, int stride, int esz);
 // Fire-module kernel (xenos_linked.hip); conv_h x conv_w = conv-output pixels of a tile
 int launch_fire(const ConvArgs& a, int dtype, void* stream);
-size_t fire_lds_bytes(int conv_h, int conv_w, int S, int esz, int pooled);
+size_t fire_lds_bytes(int conv_h, int conv_w, int S, int esz, int pooled, int ring = 1);   // ring: halo of the block (1 with a 3x3 part)
 
 }  // namespace xenos

@@ -1159,7 +1159,8 @@ struct Planner {
   }
 
   // ---- link level 3, Fire module (Table 1, Conv1x1 -> Conv3x3; Section 4.1 last paragraph) -----------------------
-  // squeeze = conv 1x1 / stride 1 / pad 0 with at most 64 output channels whose chain output is read by dense convolutions
+  // squeeze = conv 1x1 / stride 1 / pad 0 (or, over whole reduction steps of input channels, 3x3 / stride 1 / pad 1: Table 1,
+  // Conv3x3 -> Conv1x1 and Conv3x3 -> Conv3x3) with at most 64 output channels whose chain output is read by dense convolutions
   // only: one 1x1 / pad 0 and one 3x3 / pad 1 (stride 1) (a Fire module), or one of the two alone (a plain ConvX -> ConvY
   // pair); each a plain chain (bias / bn / relu) that may end in a max-pooling of 2- or 3-wide windows at stride 2 without
   // padding (of a module: the SAME pooling, the one the link pass moved in front of their concat); the outputs take
@@ -1172,7 +1173,11 @@ struct Planner {
     const xenos_op_desc& d = desc(nd);
     const Shape is = tshape[nd.in[0]];
     const int S = d.out_c;
-    if (d.groups != 1 || d.kh != 1 || d.kw != 1 || d.stride_h != 1 || d.pad_h != 0 || is.c % p.ce != 0 || S > 64 || (S * p.esz) % 32 != 0) return false;
+    const bool first3 = d.kh == 3 && d.kw == 3 && d.pad_h == 1 && d.pad_w == 1;
+    if (d.groups != 1 || d.stride_h != 1 || d.stride_w != 1 || is.c % p.ce != 0 || S > 64 || (S * p.esz) % 32 != 0) return false;
+    if (!first3 && (d.kh != 1 || d.kw != 1 || d.pad_h != 0 || d.pad_w != 0)) return false;
+    // (a 3x3 first convolution reads the taps of a chunk of input channels in consecutive steps: whole chunks only)
+    if (first3 && (std::max(is.c, p.views[tview[nd.in[0]]].cphys) % (kRowBytes / p.esz) != 0 || is.h > 0xffff || is.w > 0xffff)) return false;
     // (fp32 at large batch: the module as three chains on the big GEMM tiles is faster than one chain whose squeeze halo is
     // recomputed at the fp32 MFMA rate; measured on the SqueezeNet graph at batch 32, 0.67 against 0.74 ms)
     if (p.dt == DT_F32 && (long long)is.n * is.h * is.w > 4096) return false;
@@ -1203,7 +1208,7 @@ struct Planner {
     }
     if (fm->e[0] < 0 && fm->e[1] < 0) return false;
     const int pk = pool_src >= 0 ? g.ops[pool_src].d.kh : 0;
-    return fire_lds_bytes(pk ? pk : 1, pk ? pk : 1, S, p.esz, pk ? 1 : 0) <= std::min<size_t>(p.hw.lds_bytes_per_cu, 160 * 1024);
+    return fire_lds_bytes(pk ? pk : 1, pk ? pk : 1, S, p.esz, pk ? 1 : 0, fm->e[1] >= 0 ? 1 : 0) <= std::min<size_t>(p.hw.lds_bytes_per_cu, 160 * 1024);
   }
 
   // Tile (output pixels, or pooling windows) and number of channel shares of a Fire-module chain.  A workgroup's time in
@@ -1218,22 +1223,23 @@ struct Planner {
     const bool pool = c.pool != POOL_NONE;
     const int S = c.K, kgs = S * p.esz / 32, nsteps = c.Kred_pad / (kRowBytes / p.esz);
     const int nt[2] = {(c.fire_E[0] + 63) / 64, (c.fire_E[1] + 63) / 64};
+    const int ring = c.fire_E[1] > 0 ? 1 : 0;                      // halo of the first convolution's block
     const int YH = pool ? c.PH : c.H, XW = pool ? c.PW : c.W;      // extent of the tile grid (windows or pixels)
     double best = 1e300;
     for (int th = 1; th <= YH; ++th)
       for (int tw = 1; tw <= XW; ++tw) {
         const int CH = pool ? (th - 1) * c.ps + c.pk : th, CW = pool ? (tw - 1) * c.ps + c.pk : tw;
-        if ((CH + 2) * (CW + 2) > kFireMaxPositions) break;
-        const size_t lds = fire_lds_bytes(CH, CW, S, p.esz, pool ? 1 : 0);
+        if ((CH + 2 * ring) * (CW + 2 * ring) > kFireMaxPositions) break;
+        const size_t lds = fire_lds_bytes(CH, CW, S, p.esz, pool ? 1 : 0, ring);
         if (lds > lds_cap) break;
         const int occ = 2 * lds <= lds_cap ? 2 : 1;
         const int ty = (YH + th - 1) / th, tx = (XW + tw - 1) / tw;
         const double px_chunks = (CH * CW + 63) / 64;
         double sq_total = 0, sq_longest = 0;
         for (int y = 0; y < ty; ++y) {
-          const int iy0 = (pool ? y * th * c.ps : y * th) - 1, hv = std::min(iy0 + CH + 2, c.H) - std::max(iy0, 0);
+          const int iy0 = (pool ? y * th * c.ps : y * th) - ring, hv = std::min(iy0 + CH + 2 * ring, c.H) - std::max(iy0, 0);
           for (int x = 0; x < tx; ++x) {
-            const int ix0 = (pool ? x * tw * c.ps : x * tw) - 1, wv = std::min(ix0 + CW + 2, c.W) - std::max(ix0, 0);
+            const int ix0 = (pool ? x * tw * c.ps : x * tw) - ring, wv = std::min(ix0 + CW + 2 * ring, c.W) - std::max(ix0, 0);
             const double cost = 1.0 + ((hv * wv + 63) / 64) * (double)nsteps * (p.dt == DT_BF16 ? 0.35 : 0.5);
             sq_total += cost; sq_longest = std::max(sq_longest, cost);
           }
@@ -1279,15 +1285,17 @@ struct Planner {
     const View iv = p.views[st.v_in];
     ConvArgs& a = st.conv;
     a.N = is.n; a.C = std::max(is.c, iv.cphys); a.H = is.h; a.W = is.w; a.K = S;
-    a.R = 1; a.S = 1; a.stride = 1; a.pad = 0; a.OH = is.h; a.OW = is.w; a.PH = is.h; a.PW = is.w;
+    const int R1 = desc(nd).kh;                                    // 1, or 3 (pad 1)
+    a.R = R1; a.S = R1; a.stride = 1; a.pad = R1 / 2; a.OH = is.h; a.OW = is.w; a.PH = is.h; a.PW = is.w;
     a.in_sN = iv.sN; a.in_sH = iv.sP * is.w; a.in_sW = iv.sP;
     a.relu = w.relu; a.mode = M_FLAT; a.pool = POOL_NONE; a.fire = 1;
-    pack_dense(st, go, is.c, a.C, 1, 1, S);
+    pack_dense(st, go, is.c, a.C, R1, R1, S);
+    if (R1 == 3 && !a.kchunk) return fail(XENOS_EUNSUPPORTED, "%s: 3x3 weights of a linked pair are not packed by channel chunk", st.name.c_str());
     push_affine(w.af, (S + 127) / 128 * 128, &st.scale_off, &st.shift_off);
     const int sidx = (int)p.steps.size();
     node_step[i] = sidx;
     for (int ab : w.absorbed) node_step[ab] = sidx;
-    st.flops = 2.0 * is.n * is.h * is.w * (double)S * is.c;
+    st.flops = 2.0 * is.n * is.h * is.w * (double)S * is.c * R1 * R1;
     for (int which = 0; which < 2; ++which) {
       const int en = fm.e[which];
       if (en < 0) { a.fire_E[which] = 0; a.fire_relu[which] = 0; continue; }   // (a pair: the module's other part does not exist)
@@ -1338,7 +1346,7 @@ struct Planner {
     a.xcd_m = 8;
     a.grid = p.opts.split ? std::max(1, std::min(a.ntiles, 4 * std::max(1, p.hw.num_cu))) : 1;
     st.cfg = kFireCfg;
-    st.lds = fire_lds_bytes(a.th, a.tw, S, p.esz, a.pool != POOL_NONE ? 1 : 0);
+    st.lds = fire_lds_bytes(a.th, a.tw, S, p.esz, a.pool != POOL_NONE ? 1 : 0, a.fire_E[1] > 0 ? 1 : 0);
     st.bytes_in = view_bytes(st.v_in);
     add_step(st);
     return XENOS_OK;

@@ -27,10 +27,17 @@ constexpr int PG_STAGES_BYTES = 2 * (PG_BM + PG_BN) * LDS_ROW;
 // pixel(chunk, row) gives the element offset of a row's input pixel (-1 = no pixel); epilogue(chunk, acc) receives
 // the finished accumulators of a chunk (lane = row wave_m * 32 + l31, channels wave_n * 32 + 8 g + 4 lhalf + 0..3).
 // Ends without a barrier: the caller's next barrier frees the stages.
+// TAPS = 9: the convolution is 3x3 / stride 1 / pad 1 instead of 1x1, its weights packed with all taps of a chunk of BKE
+// channels in consecutive steps (a.C a multiple of BKE): step s is tap s % 9 of chunk s / 9, the input element of a row
+// is its pixel's neighbour at that tap, zero outside the map; coord(chunk, row) gives the pixel's (y << 16) | x.
 constexpr int PG_DEPTH = 4;
 
-template <typename T, typename PixelFn, typename EpiFn>
-__device__ __forceinline__ void pw_gemm_phase(const ConvArgs& a, int k_row0, unsigned char* s_op, int nchunks, PixelFn pixel, EpiFn epilogue) {
+struct NoCoord { __device__ __forceinline__ int operator()(int, int) const { return 0; } };
+
+template <typename T, int TAPS = 1, typename PixelFn, typename EpiFn, typename CoordFn = NoCoord>
+__device__ __forceinline__ void pw_gemm_phase(const ConvArgs& a, int k_row0, unsigned char* s_op, int nchunks, PixelFn pixel, EpiFn epilogue,
+                                              CoordFn coord = CoordFn()) {
+  static_assert(TAPS == 1 || TAPS == 9, "1x1 or 3x3 / pad 1");
   using tr = Tr<T>;
   constexpr int CE = tr::CE, BKE = tr::BKE, ESZ = (int)sizeof(T);
   constexpr int BM = PG_BM, BN = PG_BN, D = PG_DEPTH;
@@ -50,6 +57,7 @@ __device__ __forceinline__ void pw_gemm_phase(const ConvArgs& a, int k_row0, uns
   // the chunk and step the next request belongs to, and this thread's input rows of that chunk
   int ld_chunk = -1, ld_step = nsteps - 1;
   long long abase[A_IT];
+  int ayx[TAPS == 9 ? A_IT : 1];                                   // TAPS = 9: (y << 16) | x of this thread's rows
   unsigned arow = 0;
   u32x4_t ra[D][A_IT], rb[D][B_IT];
   unsigned okm[D];                                                 // which of a set's input chunks are real (the others are zero)
@@ -64,13 +72,29 @@ __device__ __forceinline__ void pw_gemm_phase(const ConvArgs& a, int k_row0, uns
         const long long off = pixel(ld_chunk, (tid + it * NT) / CPR);
         arow |= (off >= 0 ? 1u : 0u) << it;
         abase[it] = (off >= 0 ? off : 0) + ch * CE;
+        if constexpr (TAPS == 9) ayx[it] = coord(ld_chunk, (tid + it * NT) / CPR);
       }
     }
-    const int kc = ld_step * BKE + ch * CE;
-    okm[d] = kc < a.C ? arow : 0u;                                 // channels beyond C are the padding of the reduction
+    if constexpr (TAPS == 9) {
+      const int cch = ld_step / 9, tap = ld_step - cch * 9, dy = tap / 3 - 1, dx = tap - (tap / 3) * 3 - 1;
+      const long long toff = (long long)dy * a.in_sH + (long long)dx * a.in_sW + (long long)cch * BKE;
+      unsigned ok = 0;
 #pragma unroll
-    for (int it = 0; it < A_IT; ++it)
-      ra[d][it] = *(const u32x4_t*)((const T*)a.in + (((okm[d] >> it) & 1u) ? abase[it] + ld_step * BKE : 0));
+      for (int it = 0; it < A_IT; ++it) {
+        const int y = (ayx[it] >> 16) + dy, x = (ayx[it] & 0xffff) + dx;
+        ok |= (((arow >> it) & 1u) && (unsigned)y < (unsigned)a.H && (unsigned)x < (unsigned)a.W ? 1u : 0u) << it;
+      }
+      okm[d] = ok;
+#pragma unroll
+      for (int it = 0; it < A_IT; ++it)
+        ra[d][it] = *(const u32x4_t*)((const T*)a.in + (((ok >> it) & 1u) ? abase[it] + toff : 0));
+    } else {
+      const int kc = ld_step * BKE + ch * CE;
+      okm[d] = kc < a.C ? arow : 0u;                               // channels beyond C are the padding of the reduction
+#pragma unroll
+      for (int it = 0; it < A_IT; ++it)
+        ra[d][it] = *(const u32x4_t*)((const T*)a.in + (((okm[d] >> it) & 1u) ? abase[it] + ld_step * BKE : 0));
+    }
 #pragma unroll
     for (int it = 0; it < B_IT; ++it) rb[d][it] = *(const u32x4_t*)(wrow[it] + (long long)ld_step * ROWB);
   };
@@ -335,7 +359,7 @@ __host__ __device__ constexpr int fire_lds(int positions, int S, int esz, int po
          pool_positions * fire_cb_pitch(esz);
 }
 
-template <typename T, bool POOL>
+template <typename T, bool POOL, int TAPS1>
 __global__ __launch_bounds__(NT) void fire_kernel(const ConvArgs a) {
   using tr = Tr<T>;
   constexpr int CE = tr::CE, ESZ = (int)sizeof(T);
@@ -351,7 +375,9 @@ __global__ __launch_bounds__(NT) void fire_kernel(const ConvArgs a) {
   const int kgs = S * ESZ / 32;                                    // MFMA k-groups per tap
   // conv-output pixels of a tile: th x tw, or the block the tile's pooling windows cover
   const int CH = POOL ? (a.pph - 1) * a.ps + a.pk : a.th, CW = POOL ? (a.ppw - 1) * a.ps + a.pk : a.tw;
-  const int PH = CH + 2, PWd = CW + 2;                             // squeeze block
+  // the block of the first convolution's output a tile reads: its pixels, and one ring of halo when a 3x3 part exists
+  const int ring = a.fire_E[1] > 0 ? 1 : 0;
+  const int PH = CH + 2 * ring, PWd = CW + 2 * ring;
   unsigned char* s_sq = smem;
   unsigned char* s_b = smem + PH * PWd * SQP;
   const int bbytes = 64 * fire_w_pitch(9, S, ESZ);
@@ -365,7 +391,7 @@ __global__ __launch_bounds__(NT) void fire_kernel(const ConvArgs a) {
     const int n = tm / tiles_sp, rr = tm - n * tiles_sp, ty = rr / a.tiles_x, tx = rr - ty * a.tiles_x;
     // first conv-output pixel of the tile
     const int oy0 = POOL ? ty * a.pph * a.ps - a.pp : ty * a.th, ox0 = POOL ? tx * a.ppw * a.ps - a.pp : tx * a.tw;
-    const int iy0 = oy0 - 1, ix0 = ox0 - 1;                        // map position of block position (0, 0)
+    const int iy0 = oy0 - ring, ix0 = ox0 - ring;                  // map position of block position (0, 0)
     const int y_lo = iy0 > 0 ? iy0 : 0, y_hi = iy0 + PH < a.H ? iy0 + PH : a.H;
     const int x_lo = ix0 > 0 ? ix0 : 0, x_hi = ix0 + PWd < a.W ? ix0 + PWd : a.W;
     const int hv = y_hi - y_lo, wv = x_hi - x_lo, npos = hv * wv;   // the part of the block inside the map (never empty)
@@ -383,7 +409,7 @@ __global__ __launch_bounds__(NT) void fire_kernel(const ConvArgs a) {
       qsc[g] = *(const f32x4_t*)(a.scale + (c < S ? c : 0));
       qsh[g] = *(const f32x4_t*)(a.shift + (c < S ? c : 0));
     }
-    pw_gemm_phase<T>(a, 0, s_b, (npos + 63) / 64, [&](int mc, int row) -> long long {
+    pw_gemm_phase<T, TAPS1>(a, 0, s_b, (npos + 63) / 64, [&](int mc, int row) -> long long {
       const int m = mc * 64 + row;
       if (m >= npos) return -1;
       const int py = m / wv, px = m - py * wv;
@@ -413,6 +439,10 @@ __global__ __launch_bounds__(NT) void fire_kernel(const ConvArgs a) {
           }
         }
       }
+    }, [&](int mc, int row) -> int {
+      const int m = mc * 64 + row, mm = m < npos ? m : 0;
+      const int py = mm / wv, px = mm - py * wv;
+      return ((y_lo + py) << 16) | (x_lo + px);
     });
     __syncthreads();                                               // the block is complete, the GEMM stages are free
 
@@ -451,7 +481,7 @@ __global__ __launch_bounds__(NT) void fire_kernel(const ConvArgs a) {
           const int mm = m < npix ? m : 0;
           const int py = mm / CW, px = mm - py * CW;
           // block position of the pixel's first tap: the 1x1 expand reads the pixel itself, the 3x3 its window
-          const unsigned char* pa = s_sq + ((py + (which ? 0 : 1)) * PWd + px + (which ? 0 : 1)) * SQP + lhalf * 16;
+          const unsigned char* pa = s_sq + ((py + (which ? 0 : ring)) * PWd + px + (which ? 0 : ring)) * SQP + lhalf * 16;
           const unsigned char* pb = s_b + (wave_n * 32 + l31) * WP + lhalf * 16;
           f32x16_t acc;
 #pragma unroll
@@ -563,15 +593,15 @@ __global__ __launch_bounds__(NT) void fire_kernel(const ConvArgs a) {
   }
 }
 
-template <typename T, bool POOL>
+template <typename T, bool POOL, int TAPS1>
 static int launch_fire_inst(const ConvArgs& a, int lds, hipStream_t st) {
   static int raised = 0;
   if (lds > raised) {
-    hipError_t e = hipFuncSetAttribute((const void*)fire_kernel<T, POOL>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    hipError_t e = hipFuncSetAttribute((const void*)fire_kernel<T, POOL, TAPS1>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
     if (e != hipSuccess) return (int)e;
     raised = lds;
   }
-  hipLaunchKernelGGL((fire_kernel<T, POOL>), dim3(a.grid < a.ntiles ? a.grid : a.ntiles), dim3(NT), lds, st, a);
+  hipLaunchKernelGGL((fire_kernel<T, POOL, TAPS1>), dim3(a.grid < a.ntiles ? a.grid : a.ntiles), dim3(NT), lds, st, a);
   return (int)hipGetLastError();
 }
 
@@ -580,8 +610,12 @@ static int launch_fire_t(const ConvArgs& a, hipStream_t st) {
   constexpr int ESZ = (int)sizeof(T), BKE = Tr<T>::BKE, CE = Tr<T>::CE;
   const bool pool = a.pool != POOL_NONE;
   // what the kernel assumes, checked again on the host
-  if (a.mode != M_FLAT || a.has_res || a.ksplit >= 1 || a.ileave || a.kchunk || a.pair || a.dw_panel || a.pwdw || a.dw_w ||
-      a.R != 1 || a.S != 1 || a.stride != 1 || a.pad != 0 || a.C % CE != 0 || a.C < CE || a.Kred_pad < (a.C + BKE - 1) / BKE * BKE || a.Kred_pad % BKE != 0 ||
+  // the first convolution: 1x1 / pad 0, or 3x3 / pad 1 with the taps of a channel chunk packed in consecutive steps
+  const bool first3 = a.R == 3;
+  if (a.mode != M_FLAT || a.has_res || a.ksplit >= 1 || a.ileave || a.pair || a.dw_panel || a.pwdw || a.dw_w || a.stride != 1 || a.R != a.S ||
+      (first3 ? (a.pad != 1 || !a.kchunk || a.C % BKE != 0 || a.Kred_pad != 9 * a.C || a.H > 0xffff || a.W > 0xffff)
+              : (a.R != 1 || a.pad != 0 || a.kchunk || a.Kred_pad < (a.C + BKE - 1) / BKE * BKE)) ||
+      a.C % CE != 0 || a.C < CE || a.Kred_pad % BKE != 0 ||
       a.K < 1 || a.K > 64 || (a.K * ESZ) % 32 != 0 || a.OH != a.H || a.OW != a.W ||
       (a.fire_E[0] < 1 && a.fire_E[1] < 1) ||
       a.tiles_n < 1 || a.tiles_m != a.N * a.tiles_y * a.tiles_x || a.ntiles != a.tiles_m * a.tiles_n || a.grid < 1 ||
@@ -606,18 +640,20 @@ static int launch_fire_t(const ConvArgs& a, hipStream_t st) {
     if (a.th < 1 || a.tw < 1 || a.tiles_y != (a.H + a.th - 1) / a.th || a.tiles_x != (a.W + a.tw - 1) / a.tw) return (int)hipErrorInvalidValue;
     ch = a.th; cw = a.tw;
   }
-  const int positions = (ch + 2) * (cw + 2);
+  const int ring = a.fire_E[1] > 0 ? 1 : 0;
+  const int positions = (ch + 2 * ring) * (cw + 2 * ring);
   const int lds = fire_lds(positions, a.K, ESZ, pool_pos);
   if (positions > kFireMaxPositions || lds > 160 * 1024) return (int)hipErrorInvalidValue;
-  return pool ? launch_fire_inst<T, true>(a, lds, st) : launch_fire_inst<T, false>(a, lds, st);
+  if (first3) return pool ? launch_fire_inst<T, true, 9>(a, lds, st) : launch_fire_inst<T, false, 9>(a, lds, st);
+  return pool ? launch_fire_inst<T, true, 1>(a, lds, st) : launch_fire_inst<T, false, 1>(a, lds, st);
 }
 
 int launch_fire(const ConvArgs& a, int dtype, void* stream) {
   return dtype == DT_BF16 ? launch_fire_t<bf16_t>(a, (hipStream_t)stream) : launch_fire_t<float>(a, (hipStream_t)stream);
 }
 
-size_t fire_lds_bytes(int conv_h, int conv_w, int S, int esz, int pooled) {
-  return (size_t)fire_lds((conv_h + 2) * (conv_w + 2), S, esz, pooled ? conv_h * conv_w : 0);
+size_t fire_lds_bytes(int conv_h, int conv_w, int S, int esz, int pooled, int ring) {
+  return (size_t)fire_lds((conv_h + 2 * ring) * (conv_w + 2 * ring), S, esz, pooled ? conv_h * conv_w : 0);
 }
 
 }  // namespace xenos

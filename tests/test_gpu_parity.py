@@ -551,6 +551,49 @@ def test_conv1x1_to_conv_pair_linked_on_chip(h, w, c, s, k2, n, second, pool, ta
 
 
 @pytest.mark.parametrize("compute", [0, 1])
+@pytest.mark.parametrize("h,w,c,s,k2,n,second,pool,tail", [(13, 13, 128, 16, 80, 2, 1, 0, "conv"), (27, 21, 128, 32, 72, 1, 3, 3, "conv"),
+                                                           (9, 30, 128, 48, 200, 3, 1, 0, "conv"), (14, 14, 128, 64, 256, 1, 3, 2, "out"),
+                                                           (12, 18, 192, 32, 136, 2, 1, 2, "conv"), (7, 7, 192, 64, 128, 1, 3, 0, "conv"),
+                                                           (40, 33, 128, 64, 64, 1, 1, 0, "out")])
+def test_conv3x3_to_conv_pair_linked_on_chip(h, w, c, s, k2, n, second, pool, tail, compute):
+    # link level 3, Table 1 Conv3x3 -> Conv1x1 and Conv3x3 -> Conv3x3 (halo recomputed per tile): a 3x3 / pad 1 convolution
+    # with at most 64 output channels over whole reduction steps of input channels (64 bf16 / 32 fp32) -> conv 1x1 or conv
+    # 3x3 / pad 1 [-> max-pooling] is ONE chain; the intermediate tensor lives in LDS (with one ring of halo for a 3x3
+    # consumer, none for a 1x1).  Clipped blocks at the borders, ragged channel tiles, one to four k-groups per tap.
+    # (the chains before and behind the pair have more than 64 output channels, so that they do not pair up themselves)
+    b = wg.builder("pair3x3", (n, c, h, w), 59, nonzero_bias=True)
+    x = b.cbr(0, c, 1, name="pre")
+    q = b.cbr(x, s, 3, 1, 1, name="first")
+    t = b.cbr(q, k2, second, 1, second // 2, name="second", bn=(pool == 0))
+    if pool == 3:
+        t = b.maxpool(t, 3, 2, 0, ceil=1)
+    elif pool == 2:
+        t = b.maxpool(t, 2, 2)
+    fmt = {}
+    if tail == "conv":
+        t = b.cbr(t, 24, 1, name="post")
+    else:
+        fmt = dict(out_layout=1, out_dtype=compute)
+    g = b.finish(t)
+    ref = xo.forward(g)
+    y3, i3 = check(g, ref, compute=compute, link=3, **fmt)
+    y2, i2 = check(g, ref, compute=compute, link=2, **fmt)
+    fire = [ch for ch in i3["chains"] if ch.get("loader") == "fire"]
+    fits = compute == 1 or s <= 48                         # (fp32: the kernel's LDS map reserves a 3x3 weight tile, which 64 channels do not fit)
+    assert len(fire) == (1 if fits else 0), [(ch["name"], ch.get("loader")) for ch in i3["chains"]]
+    if fits:
+        # (one chain fewer, two where the 3x3 convolution alone would share its reduction out and need a summing pass)
+        assert fire[0]["R"] == 3 and i3["n_chains"] <= i2["n_chains"] - 1 and (fire[0]["pool"] != 0) == (pool != 0)
+        assert i3["hbm_bytes"] < i2["hbm_bytes"]
+    if not any(ch["kind"] == "splitk_finish" for ch in i3["chains"]):
+        y3s, _ = run_gpu(g, compute=compute, link=3, split=0, **fmt)
+        assert np.array_equal(y3, y3s)
+        y3m, _ = run_gpu(g, compute=compute, link=3, hw=dict(X_small=True), **fmt)
+        assert np.array_equal(y3, y3m)
+    check_chains(g, compute, link=3, **fmt)
+
+
+@pytest.mark.parametrize("compute", [0, 1])
 @pytest.mark.parametrize("rows,widths,residual", [(128, (512, 2048, 512), True), (1, (64, 256, 64), True), (33, (96, 200, 72), False),
                                                   (384, (128, 128, 128, 40), False), (7, (1024, 64, 1024), True), (200, (24, 136), False)])
 def test_matmul_chains(rows, widths, residual, compute):
