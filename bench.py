@@ -6,11 +6,17 @@ that is already resident in HBM.  Prints ONE JSON line.  The headline workload i
 (VGG-16-style, batch 32, bf16 MFMA / fp32 accumulate, linked + split): the largest single-GPU
 configuration and the compute-bound regime in which the MFMA roofline is meaningful.
 
-Fixed policy, no minimum over variants: the headline (and every `images_per_s` of the other workloads)
-is the path at link level 3, the deepest linking the library has, partitions profiled per chain
-(xenos_plan_tune), enqueued with xenos_run (one launch per chain).  HIP-graph replay of the same plan
-(xenos_run_graph) and the other link levels (2, U1, U0) are reported beside it.  Batch-1 workloads are
-timed over at least 500 passes whatever --steps says (a pass takes 0.1-0.3 ms).
+Fixed policy, no minimum over variants: the headline is the path at link level 3, the deepest linking the library has, partitions profiled per chain
+(xenos_plan_tune), one launch per chain, with TWO passes in flight: step k is enqueued on stream k % 2 with
+the workspace and output of that stream (xenos_run on the bound workspace, xenos_run_with on the second
+one), so consecutive steps, which work on independent batches, overlap: the kernels of one fill the
+compute units that the last round of tiles of the other leaves idle, and the gap behind a dependent launch
+is covered.  `value` is images/s of K such steps between two device synchronisations.  The same K steps
+one after the other on one stream (the latency of a pass), HIP-graph replay of the same plan
+(xenos_run_graph) and the other link levels (2, U1, U0) are reported beside it.  The roofline of the
+dominant kernel is measured on launches that have the chip to themselves (one pass at a time, HIP events
+around every launch).  The other workloads report images/s of one pass at a time at every link level, and of two
+passes in flight beside it.  Batch-1 workloads are timed over at least 1000 passes whatever --steps says.
 """
 from __future__ import annotations
 
@@ -44,6 +50,7 @@ PEAK = {1: 2500.0, 0: 157.3}          # dense MFMA TFLOP/s: bf16, fp32
 HBM_PEAK = 8000.0                     # GB/s
 LINK_NAMES = {3: "linked_deep", 2: "linked", 1: "U1", 0: "U0"}   # linked_deep: + the chains whose intermediate stays on chip
 HEADLINE_LINK = 3
+IN_FLIGHT = 2                         # passes of the headline policy that are in flight at a time (one stream each)
 MIN_PASSES_BATCH1 = 1000
 
 
@@ -59,6 +66,37 @@ def time_steps(sess, torch, steps, warmup, graph=False):
     e0.record()
     for _ in range(steps):
         run()
+    e1.record()
+    torch.cuda.synchronize()
+    wall = (time.perf_counter() - t0) * 1e3 / steps
+    return e0.elapsed_time(e1) / steps, wall
+
+
+def time_in_flight(sess, lanes, torch, steps, warmup):
+    """K forward passes with 1 + len(lanes) of them in flight: pass k goes to stream j = k % (1 + len(lanes)) with the
+    input, workspace and output of that stream (the session's own for j = 0, a lane's otherwise), so a pass follows
+    the pass before it on its stream and overlaps the passes of the other streams.  Returns (ms per pass between an event
+    every stream waits for and one that waits for every stream, wall-clock ms per pass between two synchronisations)."""
+    runs = [sess.run] + [l.run for l in lanes]
+    streams = [torch.cuda.Stream() for _ in runs]
+
+    def go(n):
+        for k in range(n):
+            j = k % len(runs)
+            with torch.cuda.stream(streams[j]):
+                runs[j]()
+
+    go(warmup)
+    torch.cuda.synchronize()
+    cur = torch.cuda.current_stream()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    for st in streams:
+        st.wait_event(e0)
+    go(steps)
+    for st in streams:
+        cur.wait_stream(st)
     e1.record()
     torch.cuda.synchronize()
     wall = (time.perf_counter() - t0) * 1e3 / steps
@@ -119,7 +157,14 @@ def run_workload(name, steps, warmup, links=(3,), chains=False, wg=None, X=None,
         ms, wall = time_steps(s, torch, passes, warmup, graph=False)
         ms_graph, _ = time_steps(s, torch, passes, warmup, graph=True)
         each = time_each_step(s, torch, passes)
-        rec = {"ms_per_step": ms, "wall_ms_per_step": wall, "ms_per_step_graph_replay": ms_graph, "launch": "xenos_run (one launch per chain)",
+        lanes = [s.lane() for _ in range(IN_FLIGHT - 1)]
+        for l in lanes:
+            l.x.copy_(s.x)
+        ms_fl, wall_fl = time_in_flight(s, lanes, torch, passes, warmup)
+        del lanes
+        rec = {"ms_per_step_in_flight": ms_fl, "wall_ms_per_step_in_flight": wall_fl, "passes_in_flight": IN_FLIGHT,
+               "images_per_s_in_flight": batch / ms_fl * 1e3,
+               "ms_per_step": ms, "wall_ms_per_step": wall, "ms_per_step_graph_replay": ms_graph, "launch": "xenos_run (one launch per chain)",
                "ms_per_step_median": float(np.median(each)), "ms_per_step_min": float(each.min()), "ms_per_step_p90": float(np.percentile(each, 90)),
                "images_per_s": batch / ms * 1e3, "images_per_s_graph_replay": batch / ms_graph * 1e3,
                "tuned": bool(TUNE), "chains_retuned": retuned,
@@ -262,6 +307,8 @@ def main():
                     help="run the workload at this link level (0 = U0, 1 = U1, 2, 3): tune (unless --no-tune), synchronise, then --steps "
                          "eager passes, and exit: the process whose kernels rocprofv3 traces / counts per link level; the JSON line says "
                          "how many kernel launches the passes are, they are the last ones of the process")
+    ap.add_argument("--in-flight", type=int, default=1, choices=(1, 2),
+                    help="with --passes-only: passes in flight at a time (2 = the headline's step policy, on two streams)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run a plain device copy of 256 MiB three times and exit (reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
@@ -296,10 +343,19 @@ def main():
         s.set_input(g.x)
         retuned = s.tune(reps=5) if TUNE else 0
         torch.cuda.synchronize()
-        for _ in range(args.steps):
-            s.run()
+        if args.in_flight == 1:
+            for _ in range(args.steps):
+                s.run()
+        else:
+            lane = s.lane()
+            lane.x.copy_(s.x)
+            streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+            torch.cuda.synchronize()
+            for k in range(args.steps):
+                with torch.cuda.stream(streams[k % 2]):
+                    (s.run if k % 2 == 0 else lane.run)()
         torch.cuda.synchronize()
-        print(json.dumps({"workload": name, "link": args.passes_only, "passes": args.steps, "n_chains": s.info["n_chains"],
+        print(json.dumps({"workload": name, "link": args.passes_only, "passes": args.steps, "passes_in_flight": args.in_flight, "n_chains": s.info["n_chains"],
                           "kernel_launches_of_the_passes": args.steps * s.info["n_chains"], "tuned": bool(TUNE), "chains_retuned": retuned,
                           "algorithmic_hbm_mb_per_pass": s.info["hbm_bytes"] / 1e6,
                           "chains": [dict(name=c["name"], kernel=chain_label(c), gflop=c["flops"] / 1e9,
@@ -345,18 +401,28 @@ def main():
 
     line = {
         "metric": "images/sec + % MFMA/HBM roofline, linked vs unlinked, batch 1 and 32",
-        "value": lk["images_per_s"], "unit": "images/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": lk["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "value": lk["images_per_s_in_flight"], "unit": "images/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": lk["ms_per_step_in_flight"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": head["dtype"], "data": "synthetic",
         "config": {"workload": f"config {cfg}: {g.name}-style, batch {batch}, {head['dtype']}, linked+split, "
                                f"synthetic seeded weights and input", "batch": batch, "mode": "linked+split",
                    "link_level": HEADLINE_LINK, "gflop_per_step": head["gflop"], "launch": lk["launch"],
+                   "passes_in_flight": IN_FLIGHT,
+                   "step_policy": "step k runs on stream k % 2 with that stream's workspace and output (xenos_run / xenos_run_with on one "
+                                  "plan): two independent batches are in flight, every step is a whole pass over its own batch",
+                   "wall_ms_per_step": lk["wall_ms_per_step_in_flight"],
+                   "one_pass_at_a_time": {"ms_per_step": lk["ms_per_step"], "images_per_s": lk["images_per_s"],
+                                          "note": "the same steps one after the other on one stream: the latency of a pass, and the "
+                                                  "condition under which the roofline of the dominant kernel is measured (a launch "
+                                                  "has the chip to itself; the sum of these launch durations is therefore longer than "
+                                                  "ms_per_step of the overlapped steps)"},
                    "ms_per_step_graph_replay": lk["ms_per_step_graph_replay"],
                    "ms_per_step_median": lk["ms_per_step_median"], "ms_per_step_min": lk["ms_per_step_min"], "ms_per_step_p90": lk["ms_per_step_p90"],
                    "partition": "profiled per chain (xenos_plan_tune)" if TUNE else "cost model"},
-        "tflops": lk["tflops"],
+        "tflops": head["gflop"] / lk["ms_per_step_in_flight"],
         "roofline": roof,
-        "linked_vs_unlinked": {k: {"images_per_s": head[k]["images_per_s"], "ms_per_step": head[k]["ms_per_step"],
+        "linked_vs_unlinked": {k: {"images_per_s": head[k]["images_per_s_in_flight"], "ms_per_step": head[k]["ms_per_step_in_flight"],
+                                   "images_per_s_one_pass_at_a_time": head[k]["images_per_s"], "ms_per_step_one_pass_at_a_time": head[k]["ms_per_step"],
                                    "n_chains": head[k]["n_chains"], "algorithmic_hbm_mb": head[k]["algorithmic_hbm_mb"]}
                                for k in ("linked_deep", "linked", "U1", "U0") if k in head},
     }
@@ -377,6 +443,8 @@ def main():
             others.append({"workload": other, "gflop": round(r["gflop"], 3), "passes_timed": r["passes_timed"],
                            **{k: round(r[k]["images_per_s"], 1) for k in ("linked_deep", "linked", "U1", "U0") if k in r},
                            "linked_deep_graph_replay": round(d3["images_per_s_graph_replay"], 1),
+                           "linked_deep_two_passes_in_flight": round(d3["images_per_s_in_flight"], 1),
+                           "ms_per_step_two_passes_in_flight": round(d3["ms_per_step_in_flight"], 4),
                            "ms_per_step": round(d3["ms_per_step"], 4), "ms_per_step_median": round(d3["ms_per_step_median"], 4), "n_chains": d3["n_chains"],
                            "tflops": round(d3["tflops"], 2), "frac_of_mfma_peak": round(d3["tflops"] / PEAK[ocomp], 4),
                            "algorithmic_hbm_mb": round(d3["algorithmic_hbm_mb"], 2),

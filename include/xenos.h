@@ -157,6 +157,15 @@ xenos_status xenos_plan_bind(xenos_plan* plan, void* d_weights, void* d_workspac
  * Asynchronous; allocates nothing; returns XENOS_EDEVICE if a launch fails. */
 xenos_status xenos_run(xenos_plan* plan, const void* d_input, void* d_output, void* hip_stream);
 
+/* xenos_run with the intermediate tensors in d_workspace (256-byte aligned, at least workspace_bytes of
+ * xenos_plan_query) instead of the workspace given to xenos_plan_bind, which is not touched.  A pass reads the plan and
+ * the packed weights and writes only its workspace and its output, so several passes of ONE plan may be in flight at a
+ * time, each on its own stream with its own workspace and output: kernels of one pass then fill the compute units that
+ * the last round of tiles of another leaves idle (Section 4.2.1: no unit idle), and the gap behind a dependent launch of
+ * one stream is covered by the other.  Passes that share a workspace or an output must follow each other on one
+ * stream.  Same result as xenos_run, bit for bit; asynchronous; allocates nothing. */
+xenos_status xenos_run_with(xenos_plan* plan, const void* d_input, void* d_output, void* d_workspace, void* hip_stream);
+
 /* For callers that cannot allocate device memory or hand over a workspace (code under HIP-graph capture, tight
  * serving loops, harnesses that forbid hipMalloc): xenos_run with the intermediate tensors in a workspace that is
  * part of the library's own device image, XENOS_STATIC_WORKSPACE_BYTES per GPU, held until the process ends.

@@ -2454,6 +2454,19 @@ xenos_status xenos_run(xenos_plan* plan, const void* d_input, void* d_output, vo
   return XENOS_OK;
 }
 
+xenos_status xenos_run_with(xenos_plan* plan, const void* d_input, void* d_output, void* d_workspace, void* hip_stream) {
+  if (!plan || plan->magic != MAGIC_PLAN || !d_input || !d_output || !d_workspace) return fail(XENOS_EINVAL, "xenos_run_with: bad argument");
+  if (!plan->bound) return fail(XENOS_EINVAL, "xenos_run_with: plan is not bound (call xenos_plan_bind)");
+  if ((uintptr_t)d_workspace & 255) return fail(XENOS_EINVAL, "xenos_run_with: the workspace must be 256-byte aligned");
+  // The pass reads the plan (host) and the weight image (device) and writes only d_workspace and d_output, so passes
+  // with different workspaces and outputs do not touch each other's memory.
+  for (const Step& s : plan->steps) {
+    xenos_status rc = launch_step(*plan, s, d_input, d_output, hip_stream, d_workspace);
+    if (rc != XENOS_OK) return rc;
+  }
+  return XENOS_OK;
+}
+
 xenos_status xenos_run_static(xenos_plan* plan, const void* d_input, void* d_output, void* hip_stream) {
   if (!plan || plan->magic != MAGIC_PLAN || !d_input || !d_output) return fail(XENOS_EINVAL, "xenos_run_static: bad argument");
   if (!plan->bound) return fail(XENOS_EINVAL, "xenos_run_static: plan is not bound (call xenos_plan_bind)");

@@ -84,6 +84,7 @@ def lib():
         L.xenos_run.argtypes = [vp, vp, vp, vp]
         L.xenos_run_graph.argtypes = [vp, vp, vp, vp]
         L.xenos_run_static.argtypes = [vp, vp, vp, vp]
+        L.xenos_run_with.argtypes = [vp, vp, vp, vp, vp]
         L.xenos_run_chain.argtypes = [vp, C.c_int, vp, vp, vp]
         L.xenos_plan_tune.argtypes = [vp, vp, vp, vp, C.c_int, C.POINTER(C.c_int)]
         L.xenos_probe_mfma.argtypes = [C.POINTER(HwInfo), vp, C.c_size_t, C.c_int, C.c_int, vp, C.POINTER(C.c_double)]
@@ -92,7 +93,7 @@ def lib():
         L.xenos_destroy.restype = None
         L.xenos_last_error.restype = C.c_char_p
         for f in ("xenos_graph_create", "xenos_plan_link_split", "xenos_plan_query", "xenos_plan_bind",
-                  "xenos_run", "xenos_run_graph", "xenos_run_static", "xenos_run_chain", "xenos_plan_tune",
+                  "xenos_run", "xenos_run_graph", "xenos_run_static", "xenos_run_with", "xenos_run_chain", "xenos_plan_tune",
                   "xenos_probe_mfma", "xenos_probe_read"):
             getattr(L, f).restype = C.c_int
         _lib = L
@@ -158,6 +159,10 @@ XENOS_STATIC_WORKSPACE_BYTES = 32 << 20
 
 def xenos_run_static(plan: int, d_input: int, d_output: int, stream: int = 0):
     _check(lib().xenos_run_static(plan, d_input, d_output, stream))
+
+
+def xenos_run_with(plan: int, d_input: int, d_output: int, d_workspace: int, stream: int = 0):
+    _check(lib().xenos_run_with(plan, d_input, d_output, d_workspace, stream))
 
 
 def xenos_plan_tune(plan: int, d_input: int, d_output: int, stream: int = 0, reps: int = 5) -> int:
@@ -319,6 +324,10 @@ class Session:
     def run_graph(self):
         xenos_run_graph(self.plan, self.x.data_ptr(), self.y.data_ptr(), self.stream())
 
+    def lane(self) -> "Lane":
+        """Device buffers for one more pass of this session's plan in flight (xenos_run_with)."""
+        return Lane(self)
+
     def run_chain(self, i: int):
         xenos_run_chain(self.plan, i, self.x.data_ptr(), self.y.data_ptr(), self.stream())
 
@@ -343,6 +352,38 @@ class Session:
         xenos_destroy(self.plan)
         xenos_destroy(self.graph)
         self.plan = self.graph = None
+
+
+class Lane:
+    """An input, an output and a workspace of their own for passes of a Session's plan that run beside the session's
+    passes (xenos_run_with): the weights are the session's.  Launches go to torch's current stream; passes of one lane
+    must follow each other on one stream, passes of different lanes may overlap."""
+
+    def __init__(self, sess: Session):
+        torch = sess.torch
+        self.sess = sess
+        self.x = torch.zeros_like(sess.x)
+        self.y = torch.zeros_like(sess.y)
+        self.workspace = torch.zeros(sess.info["workspace_bytes"] + 256, dtype=torch.uint8, device=sess.device)
+
+    def set_input(self, x: np.ndarray):
+        s = self.sess
+        t = s.torch.from_numpy(np.ascontiguousarray(x, dtype=np.float32)).to(s.device)
+        if s.in_fmt[1] == XENOS_NHWC:
+            t = t.permute(0, 2, 3, 1)
+        self.x.copy_(t)
+
+    def run(self):
+        s = self.sess
+        xenos_run_with(s.plan, self.x.data_ptr(), self.y.data_ptr(), s._al(self.workspace), s.stream())
+
+    def output(self) -> np.ndarray:
+        s = self.sess
+        s.torch.cuda.synchronize(s.device)
+        y = self.y.float()
+        if s.out_fmt[1] == XENOS_NHWC:
+            y = y.permute(0, 3, 1, 2)
+        return y.contiguous().cpu().numpy()
 
     def __del__(self):
         try:

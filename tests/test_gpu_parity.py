@@ -701,6 +701,45 @@ def test_graph_replay_matches_eager_every_time(net):
         s.close()
 
 
+@pytest.mark.parametrize("compute", [0, 1])
+@pytest.mark.parametrize("net", ["mobilenet", "squeezenet", "resnet", "vgg", "shufflenet"])
+def test_passes_in_flight_on_two_streams(net, compute):
+    # xenos_run_with: passes of one plan, each with its own workspace and output, overlapping on two streams (and beside
+    # the session's own xenos_run on a third).  Every pass must give, bit for bit, what a pass alone gives for its input
+    # (reduction splits, chip-resident chains and the summing passes all keep their partial results in the workspace),
+    # and that result is checked against the oracle.
+    import torch
+    X = _xenos()
+    builder, kw = {"mobilenet": SMALL[0], "resnet": SMALL[1], "vgg": SMALL[2], "squeezenet": SMALL[3], "shufflenet": SMALL[4]}[net]
+    g = builder(batch=3, seed=33, nonzero_bias=True, **kw)
+    xs = [g.x, np.ascontiguousarray(g.x[::-1]), np.ascontiguousarray(-0.5 * g.x)]
+    s = X.Session(g, link=3, compute=compute)
+    try:
+        alone = [s.forward(x).copy() for x in xs]
+        for x, y in zip(xs, alone):
+            assert rel_err(y, xo.forward(g, x)) <= TOL[compute]
+        lanes = [s.lane(), s.lane()]
+        streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+        for rep in range(3):
+            order = [(rep + j) % 3 for j in range(3)]           # which input each of the three concurrent passes takes
+            s.set_input(xs[order[0]])
+            lanes[0].set_input(xs[order[1]])
+            lanes[1].set_input(xs[order[2]])
+            s.y.zero_(); lanes[0].y.zero_(); lanes[1].y.zero_()
+            torch.cuda.synchronize()
+            for _ in range(2):                                   # two rounds back to back: a lane's passes follow each other on its stream
+                for lane, st in zip(lanes, streams):
+                    with torch.cuda.stream(st):
+                        lane.run()
+                s.run()
+            torch.cuda.synchronize()
+            assert np.array_equal(s.output(), alone[order[0]]), rep
+            assert np.array_equal(lanes[0].output(), alone[order[1]]), rep
+            assert np.array_equal(lanes[1].output(), alone[order[2]]), rep
+    finally:
+        s.close()
+
+
 # ------------------------------------------------------------------------------------------ channel slice / shuffle
 def shuffle_graph(kind, n=2, c=32, hw=13, seed=5):
     mid_groups = 0
