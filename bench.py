@@ -72,13 +72,18 @@ def time_steps(sess, torch, steps, warmup, graph=False):
     return e0.elapsed_time(e1) / steps, wall
 
 
+_STREAMS = []
+
+
 def time_in_flight(sess, lanes, torch, steps, warmup):
     """K forward passes with 1 + len(lanes) of them in flight: pass k goes to stream j = k % (1 + len(lanes)) with the
     input, workspace and output of that stream (the session's own for j = 0, a lane's otherwise), so a pass follows
     the pass before it on its stream and overlaps the passes of the other streams.  Returns (ms per pass between an event
     every stream waits for and one that waits for every stream, wall-clock ms per pass between two synchronisations)."""
     runs = [sess.run] + [l.run for l in lanes]
-    streams = [torch.cuda.Stream() for _ in runs]
+    while len(_STREAMS) < len(runs):      # created once per process, one after the other, and reused by every measurement
+        _STREAMS.append(torch.cuda.Stream())
+    streams = _STREAMS[:len(runs)]
 
     def go(n):
         for k in range(n):
