@@ -75,6 +75,48 @@ def time_steps(sess, torch, steps, warmup, graph=False):
 _STREAMS = []
 
 
+def pick_streams(X, torch, n=IN_FLIGHT, tries=8):
+    """The streams the steps in flight run on, created once per process.  HIP serves a process's streams from a few
+    hardware queues (four by default) and two streams that share a queue run their kernels one after the other, so each
+    new stream is checked against the ones already chosen with a probe that has nothing to do with the workload: a small
+    MFMA-only kernel on eight compute units, once on each of the two streams at a time; a stream on whose queue the pair
+    takes as long as two such kernels in a row is dropped and the next one is tried.  Returns a note for the JSON line."""
+    if len(_STREAMS) >= n:
+        return "kept"
+    hw = dict(X.MI355X)
+    hw["num_cu"] = 8
+    nout = 8192 * hw["num_cu"]
+    outs = [torch.empty(nout, dtype=torch.uint8, device="cuda:0") for _ in range(2)]
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    cur = torch.cuda.current_stream()
+
+    def pair_ms(sa, sb):
+        # one probe kernel on each stream (both behind e0), or two in a row on sa when sb is None
+        torch.cuda.synchronize()
+        e0.record()
+        for j, st in enumerate((sa, sb if sb is not None else sa)):
+            st.wait_event(e0)
+            X.xenos_probe_mfma(outs[j].data_ptr(), nout, 4000, st.cuda_stream, hw=hw)
+            cur.wait_stream(st)
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1)
+
+    _STREAMS.append(torch.cuda.Stream())
+    pair_ms(_STREAMS[0], None)                                          # warm-up
+    serial = pair_ms(_STREAMS[0], None)
+    dropped = 0
+    while len(_STREAMS) < n and dropped < tries:
+        cand = torch.cuda.Stream()
+        if all(min(pair_ms(st, cand), pair_ms(st, cand)) < 0.75 * serial for st in _STREAMS):
+            _STREAMS.append(cand)
+        else:
+            dropped += 1
+    while len(_STREAMS) < n:                                           # (no independent queue found: the steps then simply run in turn)
+        _STREAMS.append(torch.cuda.Stream())
+    return "%d streams on separate hardware queues (probe pairs overlap), %d candidate streams dropped" % (n, dropped)
+
+
 def time_in_flight(sess, lanes, torch, steps, warmup):
     """K forward passes with 1 + len(lanes) of them in flight: pass k goes to stream j = k % (1 + len(lanes)) with the
     input, workspace and output of that stream (the session's own for j = 0, a lane's otherwise), so a pass follows
@@ -342,6 +384,7 @@ def main():
 
     name = args.workload
     cfg, batch, compute = WORKLOADS[name]
+    stream_note = pick_streams(X, torch)
     if args.passes_only >= 0:
         g = wg.build(cfg, batch)
         s = X.Session(g, link=args.passes_only, split=1, compute=compute)
@@ -354,7 +397,7 @@ def main():
         else:
             lane = s.lane()
             lane.x.copy_(s.x)
-            streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+            streams = _STREAMS[:2]
             torch.cuda.synchronize()
             for k in range(args.steps):
                 with torch.cuda.stream(streams[k % 2]):
@@ -412,7 +455,7 @@ def main():
         "config": {"workload": f"config {cfg}: {g.name}-style, batch {batch}, {head['dtype']}, linked+split, "
                                f"synthetic seeded weights and input", "batch": batch, "mode": "linked+split",
                    "link_level": HEADLINE_LINK, "gflop_per_step": head["gflop"], "launch": lk["launch"],
-                   "passes_in_flight": IN_FLIGHT,
+                   "passes_in_flight": IN_FLIGHT, "streams": stream_note,
                    "step_policy": "step k runs on stream k % 2 with that stream's workspace and output (xenos_run / xenos_run_with on one "
                                   "plan): two independent batches are in flight, every step is a whole pass over its own batch",
                    "wall_ms_per_step": lk["wall_ms_per_step_in_flight"],
