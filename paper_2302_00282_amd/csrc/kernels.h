@@ -53,6 +53,9 @@ static const int kFcChannels = 128;
 static const int kStemLdsCfg = 8;
 static const int kStemLdsPph = 3, kStemLdsPpw = 8;   // pooling windows per tile when a max-pooling is linked
 static const int kStemLdsTh = 8, kStemLdsTw = 16, kStemLdsInMax = 784;   // (7 * 2 + 7) x (15 * 2 + 7) = 777 positions at most
+// (per kernel size class the kernel is instantiated for, by taps: up to 3x3 at stride 2 a block is at most 17 x 33 or 15 x 35
+// positions, up to 5x5 19 x 35)
+static inline int stem_lds_in_positions(int taps) { return taps <= 12 ? 576 : taps <= 28 ? 672 : kStemLdsInMax; }
 // Configuration index of the kernel that links a pointwise (1x1) convolution chain with the depthwise 3x3 chain that consumes
 // it: a TH x TW block of depthwise output pixels x kPwDwChannels channels per workgroup, the pointwise output of the block
 // (+ halo) staged in LDS, at most kPwDwMaxPositions positions

@@ -1880,8 +1880,17 @@ constexpr int SL_TH = kStemLdsTh, SL_TW = kStemLdsTw;             // output pixe
 constexpr int SL_INMAX = kStemLdsInMax;                            // positions of the staged input block
 static_assert(SL_TH * SL_TW == 32 * SL_NW && SL_TW == 16, "one wavefront = two tile rows of 16 pixels");
 
+// positions of the staged input block by kernel size class (NSTEP MFMA steps of four taps): up to 3x3 at stride 2 a block is
+// at most 17 x 33 or 15 x 35 positions, up to 5x5 19 x 35; the host checks the launch against these
+constexpr int sl_inpos(int nstep) { return nstep <= 3 ? 576 : nstep <= 7 ? 672 : SL_INMAX; }
+static_assert(sl_inpos(3) == 576 && sl_inpos(7) == 672, "the same limits as stem_lds_in_positions(), which the host checks");
+
+// (the small kernels keep three or six weight fragments per lane, so four or three workgroups share a compute unit instead of
+// two: a tile is a chain of short dependent phases, and what hides their latencies is other tiles in flight.  Measured at
+// batch 32 on the 3x3 / 2 first layers with a linked pooling: 64 channels 33.7 -> 30.3 us with three workgroups (30.8 with four,
+// which spills), 24 channels padded to 32: 28.3 -> 23.5 us with four)
 template <int KB, int NSTEP, bool POOL>
-__global__ __launch_bounds__(SL_NT, 2) void stem_lds_kernel(const ConvArgs a) {
+__global__ __launch_bounds__(SL_NT, NSTEP <= 3 ? (KB == 1 ? 4 : 3) : 2) void stem_lds_kernel(const ConvArgs a) {
   constexpr int K = KB * 32;
   constexpr int SPITCH = K * 2 + 16;                               // staging row pitch (odd number of 16-byte slots)
   constexpr int CPP = K * 2 / 16, PPI = 64 / CPP;                  // 16-byte chunks per output pixel, pixels per store instruction
@@ -1921,7 +1930,7 @@ __global__ __launch_bounds__(SL_NT, 2) void stem_lds_kernel(const ConvArgs a) {
 
   // ---- the input block of a tile: element e = (channel, block row, block column), consecutive threads along W; what does
   // not depend on the tile (position in the block, offset from the block's first element) is worked out once ----------
-  constexpr int NI = (SL_INMAX * 4 + SL_NT - 1) / SL_NT;
+  constexpr int NI = (sl_inpos(NSTEP) * 4 + SL_NT - 1) / SL_NT;
   int xe[NI], xg[NI];
 #pragma unroll
   for (int it = 0; it < NI; ++it) {
@@ -1962,6 +1971,9 @@ __global__ __launch_bounds__(SL_NT, 2) void stem_lds_kernel(const ConvArgs a) {
       }
     }
   };
+
+  // pooling stage: the window and 16-byte channel group this thread finishes in the first round
+  const int pl_wi = tid / CPP, pl_ch = tid - pl_wi * CPP, pl_wy = POOL ? pl_wi / a.ppw : 0, pl_wx = POOL ? pl_wi - pl_wy * a.ppw : 0;
 
   int tile = blockIdx.x;
   if (tile < a.tiles_m) load_block(tile);
@@ -2014,7 +2026,9 @@ __global__ __launch_bounds__(SL_NT, 2) void stem_lds_kernel(const ConvArgs a) {
       __syncthreads();
       const int tr = tile - n * tiles_img, tyi = tr / a.tiles_x, txi = tr - tyi * a.tiles_x;
       for (int idx = tid; idx < a.pph * a.ppw * CPP; idx += SL_NT) {
-        const int wi = idx / CPP, ch = idx - wi * CPP, wy = wi / a.ppw, wx = wi - wy * a.ppw;
+        // (the first round's window and channel group are the same for every tile: worked out once, before the tile loop)
+        int wi = pl_wi, ch = pl_ch, wy = pl_wy, wx = pl_wx;
+        if (idx != tid) { wi = idx / CPP; ch = idx - wi * CPP; wy = wi / a.ppw; wx = wi - wy * a.ppw; }
         const int py = tyi * a.pph + wy, px = txi * a.ppw + wx;
         if (py >= a.PH || px >= a.PW) continue;
         float m[8];
@@ -2076,7 +2090,7 @@ static int launch_stem_lds(const ConvArgs& a, int dtype, hipStream_t st) {
   const int CH = pool ? (a.pph - 1) * a.ps + a.pk : SL_TH, CW = pool ? (a.ppw - 1) * a.ps + a.pk : SL_TW;
   const int IH = (CH - 1) * a.stride + a.R, IW = (CW - 1) * a.stride + a.S;
   if (dtype != DT_BF16 || a.pair_C < 1 || a.pair_C > 4 || a.C != a.pair_C || a.R != a.S || a.R < 1 || a.R > 7 || (a.stride != 1 && a.stride != 2) ||
-      a.pad < 0 || a.pad > a.R || IH * IW > SL_INMAX || IH >= 4096 || IW >= 4096 || !a.dw_w || a.has_res || a.ksplit >= 1 ||
+      a.pad < 0 || a.pad > a.R || IH * IW > stem_lds_in_positions(a.R * a.S) || IH >= 4096 || IW >= 4096 || !a.dw_w || a.has_res || a.ksplit >= 1 ||
       a.out_sK != 1 || a.out_f32 || (a.out_sP * 2) % 16 != 0 || (a.out_sN * 2) % 16 != 0 || ((uintptr_t)a.out & 15) || ((uintptr_t)a.dw_w & 15) ||
       a.pair_sN < 0 || a.pair_sC < 0 || a.pair_sH < 0 || (long long)4 * a.pair_sC + (long long)(a.H + 64) * a.pair_sH >= (1ll << 31) ||
       a.OH != (a.H + 2 * a.pad - a.R) / a.stride + 1 || a.OW != (a.W + 2 * a.pad - a.S) / a.stride + 1)

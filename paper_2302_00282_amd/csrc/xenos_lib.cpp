@@ -1404,14 +1404,15 @@ struct Planner {
         // recomputed per tile.
         const View& gv = p.views[tview[0]];
         stem_lds = p.dt == DT_BF16 && p.opts.tile == 0 && is.c <= 4 && d.kh == d.kw && d.kh >= 3 && d.kh <= 7 && d.stride_h == d.stride_w &&
-                   (d.stride_h == 1 || d.stride_h == 2) && d.pad_h == d.pad_w && d.pad_h <= d.kh && gv.f32 && gv.sP == 1;
+                   (d.stride_h == 1 || d.stride_h == 2) && d.pad_h == d.pad_w && d.pad_h <= d.kh && gv.f32 && gv.sP == 1 &&
+                   ((kStemLdsTh - 1) * d.stride_h + d.kh) * ((kStemLdsTw - 1) * d.stride_h + d.kw) <= stem_lds_in_positions(d.kh * d.kw);
         bool keep_pool = false;
         if (stem_lds && pool_node >= 0 && !placed.count(cur) && cur != out_tid) {
           const xenos_op_desc& pd = desc(nodes[pool_node]);
           const int chh = (kStemLdsPph - 1) * 2 + pd.kh, cww = (kStemLdsPpw - 1) * 2 + pd.kw;
           keep_pool = pd.kind == XENOS_OP_MAXPOOL && pd.kh == pd.kw && (pd.kh == 2 || pd.kh == 3) && pd.stride_h == 2 && pd.stride_w == 2 &&
                       pd.pad_h == pd.pad_w && pd.pad_h >= 0 && pd.pad_h <= 1 && chh * cww <= kStemLdsTh * kStemLdsTw &&
-                      ((chh - 1) * d.stride_h + d.kh) * ((cww - 1) * d.stride_h + d.kw) <= kStemLdsInMax;
+                      ((chh - 1) * d.stride_h + d.kh) * ((cww - 1) * d.stride_h + d.kw) <= stem_lds_in_positions(d.kh * d.kw);
         }
         // (a 3x3 layer takes the LDS-staged form only for its linked pooling: one launch for two, the same time at batch 32;
         // without pooling the gather form is faster)
