@@ -431,6 +431,8 @@ def main():
             "event_gap_ms_per_launch": lk["event_gap_ms_per_launch"],
             "launch_duration_method": "HIP events around every launch of an instrumented pass, minus the gap the events add per launch "
                                       "= (instrumented pass - plain pass) / launches, both measured in this run",
+            "condition": "launch durations of passes that run one at a time: a launch has the chip to itself (the steps behind `value` "
+                         "overlap two passes, so a launch there shares the chip and its duration says nothing about the kernel)",
             "flops_per_launch": dom_gf * 1e9 / len(dom),
             "algorithmic_bytes_per_launch": sum(c["mb"] for c in dom) * 1e6 / len(dom),
             "share_of_step": dom_ms / step_ms,
