@@ -15,7 +15,8 @@ is covered.  `value` is images/s of K such steps between two device synchronisat
 one after the other on one stream (the latency of a pass), HIP-graph replay of the same plan
 (xenos_run_graph) and the other link levels (2, U1, U0) are reported beside it.  The roofline of the
 dominant kernel is measured on launches that have the chip to themselves (one pass at a time, HIP events
-around every launch).  The other workloads report images/s of one pass at a time at every link level, and of two
+around every launch); its HBM traffic is counted by rocprofv3 child processes started before this process touches
+the GPU (measure_traffic).  The other workloads report images/s of one pass at a time at every link level, and of two
 passes in flight beside it.  Batch-1 workloads are timed over at least 1000 passes whatever --steps says.
 """
 from __future__ import annotations
@@ -289,6 +290,73 @@ def attainable(X, torch):
     return res
 
 
+def measure_traffic(workload, link):
+    """HBM bytes per launch of the dominant kernel, measured for this run: four child processes under rocprofv3 (one
+    counter each: FETCH_SIZE and WRITE_SIZE, in KiB per dispatch, for a plain 256 MiB device copy and for four passes of the
+    workload planned and tuned as the timed one is), the workload's counters scaled by what the same counters read for the
+    copy.  Called before this process touches the GPU.  Returns (bytes per launch or None, a note saying what was done)."""
+    import csv
+    import glob
+    import shutil
+    import subprocess
+    import tempfile
+    if shutil.which("rocprofv3") is None:
+        return None, "rocprofv3 not found"
+    tmp = tempfile.mkdtemp(prefix="xenos_traffic_", dir="/tmp")
+    env = dict(os.environ, TMPDIR="/tmp")
+
+    def run(tag, counter, prog_args):
+        d = os.path.join(tmp, tag)
+        cmd = ["rocprofv3", "--pmc", counter, "--output-format", "csv", "-d", d, "--", sys.executable, os.path.join(ROOT, "bench.py")] + prog_args
+        r = subprocess.run(cmd, cwd=ROOT, env=env, capture_output=True, text=True, timeout=240)
+        if r.returncode != 0:
+            raise RuntimeError("%s: rc %d: %s" % (tag, r.returncode, (r.stderr or r.stdout)[-300:]))
+        files = glob.glob(os.path.join(d, "**", "*counter_collection.csv"), recursive=True)
+        if not files:
+            raise RuntimeError("%s: no counter file" % tag)
+        by = {}
+        for row in csv.DictReader(open(max(files, key=os.path.getmtime))):
+            if row["Counter_Name"] != counter:
+                continue
+            e = by.setdefault(int(row["Dispatch_Id"]), [row["Kernel_Name"], 0.0])
+            e[1] += float(row["Counter_Value"])
+        info = None
+        for ln in r.stdout.splitlines():
+            if ln.startswith("{"):
+                info = json.loads(ln)
+        return [by[k] for k in sorted(by)], info
+
+    try:
+        scale = {}
+        for counter in ("FETCH_SIZE", "WRITE_SIZE"):
+            rows, info = run("cal_" + counter, counter, ["--calibrate-copy"])
+            cp = [v for k, v in rows if "copy" in k.lower()]
+            if not cp or info is None:
+                raise RuntimeError("calibration copy not found in the trace")
+            scale[counter] = (info["copy_bytes_read"] / 1024.0) / (sum(cp) / len(cp))
+        per = {}
+        n_dom = 0
+        passes = 4
+        for counter in ("FETCH_SIZE", "WRITE_SIZE"):
+            rows, info = run("w_" + counter, counter, ["--workload", workload, "--passes-only", str(link), "--steps", str(passes)] + ([] if TUNE else ["--no-tune"]))
+            n = info["kernel_launches_of_the_passes"]
+            last = rows[-n:]
+            nc = info["n_chains"]
+            dom = [i for i, c in enumerate(info["chains"]) if c["kernel"] == "conv3x3_kernel"] or list(range(nc))
+            n_dom = len(dom)
+            per[counter] = sum(last[p * nc + i][1] for p in range(passes) for i in dom) / passes * 1024.0 * scale[counter]
+        total = (per["FETCH_SIZE"] + per["WRITE_SIZE"]) / n_dom
+        note = ("measured for this run: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (one counter per child process) over %d passes of the same "
+                "workload, link level and partition policy, scaled by the same counters' reading of a 256 MiB device copy (x %.3f / x %.3f); "
+                "fetched %.1f MB + written %.1f MB per launch" % (passes, scale["FETCH_SIZE"], scale["WRITE_SIZE"],
+                                                                    per["FETCH_SIZE"] / n_dom / 1e6, per["WRITE_SIZE"] / n_dom / 1e6))
+        return total, note
+    except Exception as e:      # the profiler is not part of the product: without it the stored summary is quoted instead
+        return None, "counter run failed (%s)" % str(e)[:200]
+    finally:
+        shutil.rmtree(tmp, ignore_errors=True)
+
+
 def pmc_traffic(workload):
     """HBM bytes per launch of the dominant kernel.  rocprofv3 counters cannot be read from inside the timed process,
     so this is the value of the committed counter summary (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this script
@@ -356,6 +424,7 @@ def main():
                          "how many kernel launches the passes are, they are the last ones of the process")
     ap.add_argument("--in-flight", type=int, default=1, choices=(1, 2),
                     help="with --passes-only: passes in flight at a time (2 = the headline's step policy, on two streams)")
+    ap.add_argument("--no-traffic", action="store_true", help="do not run the rocprofv3 counter passes that measure roofline.traffic (quote the stored summary)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run a plain device copy of 256 MiB three times and exit (reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
@@ -364,6 +433,12 @@ def main():
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no collectives, no sharding); --gpus must be 1", file=sys.stderr)
         sys.exit(2)
+
+    # HBM traffic of the dominant kernel for the roofline: counted by child processes under rocprofv3 while this process has
+    # not touched the GPU yet
+    live_traffic = (None, "")
+    if not (args.quick or args.no_traffic or args.calibrate_copy or args.passes_only >= 0):
+        live_traffic = measure_traffic(args.workload, HEADLINE_LINK)
 
     import torch
     from paper_2302_00282_amd import xenos as X
@@ -423,7 +498,10 @@ def main():
     conv_ms, conv_gf = sum(c["ms"] for c in conv), sum(c["gflop"] for c in conv)
     step_ms = sum(c["ms"] for c in lk["chains"])
     att = attainable(X, torch)
-    traffic, traffic_source = pmc_traffic(name)
+    traffic, traffic_source = live_traffic
+    if traffic is None:
+        stored, stored_source = pmc_traffic(name)
+        traffic, traffic_source = stored, (traffic_source + "; " if traffic_source else "") + stored_source
     roof = {"bound": "mfma", "kernel": "%s (%d launches per step)" % (dom[0]["kernel"], len(dom)),
             "achieved": dom_gf / dom_ms, "peak": PEAK[compute], "unit": "TFLOP/s",
             "frac": dom_gf / dom_ms / PEAK[compute], "traffic": traffic, "traffic_source": traffic_source,
