@@ -308,7 +308,16 @@ def measure_traffic(workload, link):
     def run(tag, counter, prog_args):
         d = os.path.join(tmp, tag)
         cmd = ["rocprofv3", "--pmc", counter, "--output-format", "csv", "-d", d, "--", sys.executable, os.path.join(ROOT, "bench.py")] + prog_args
-        r = subprocess.run(cmd, cwd=ROOT, env=env, capture_output=True, text=True, timeout=240)
+        # (a child that does not finish is ended with its whole process group: the profiler starts the program as its child)
+        pr = subprocess.Popen(cmd, cwd=ROOT, env=env, stdout=subprocess.PIPE, stderr=subprocess.PIPE, text=True, start_new_session=True)
+        try:
+            out, err = pr.communicate(timeout=90)
+        except subprocess.TimeoutExpired:
+            import signal
+            os.killpg(pr.pid, signal.SIGKILL)
+            pr.communicate()
+            raise RuntimeError("%s: no result within 90 s" % tag)
+        r = argparse.Namespace(returncode=pr.returncode, stdout=out, stderr=err)
         if r.returncode != 0:
             raise RuntimeError("%s: rc %d: %s" % (tag, r.returncode, (r.stderr or r.stdout)[-300:]))
         files = glob.glob(os.path.join(d, "**", "*counter_collection.csv"), recursive=True)
