@@ -317,6 +317,27 @@ def test_partition_candidates_and_tune_argument_checks():
         X.xenos_destroy(G)
 
 
+def test_run_entry_points_reject_bad_arguments_before_any_launch():
+    # xenos_run / xenos_run_with / xenos_run_static / xenos_run_graph / xenos_run_chain on a plan that is not bound, and
+    # null pointers: XENOS_EINVAL with a message, nothing touches the device (there is none here)
+    G = X.graph_from_workload(wg.build(0, 1))
+    P = X.xenos_plan_link_split(G)
+    try:
+        for call in (lambda: X.xenos_run(P, 256, 256), lambda: X.xenos_run_with(P, 256, 256, 256), lambda: X.xenos_run_static(P, 256, 256),
+                     lambda: X.xenos_run_graph(P, 256, 256), lambda: X.xenos_run_chain(P, 0, 256, 256)):
+            with pytest.raises(X.XenosError) as e:
+                call()
+            assert e.value.status == X.XENOS_EINVAL and "bound" in str(e.value)
+        for call in (lambda: X.xenos_run_with(P, 0, 256, 256), lambda: X.xenos_run_with(P, 256, 0, 256), lambda: X.xenos_run_with(P, 256, 256, 0),
+                     lambda: X.xenos_run(P, 0, 256)):
+            with pytest.raises(X.XenosError) as e:
+                call()
+            assert e.value.status == X.XENOS_EINVAL
+    finally:
+        X.xenos_destroy(P)
+        X.xenos_destroy(G)
+
+
 # ------------------------------------------------------------------------------------------ link level 3, one test per pattern
 def _kinds(g, c):
     return [g.ops[o].kind for o in c["ops"]]
